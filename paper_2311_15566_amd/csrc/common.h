@@ -1,0 +1,105 @@
+// Shared declarations of the spotshard HIP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string>
+#include <vector>
+#include <map>
+
+#include "../../include/spotshard.h"
+
+namespace ss {
+
+// ---------------------------------------------------------------------------
+// error plumbing
+// ---------------------------------------------------------------------------
+void set_error(const char *fmt, ...);
+#define SS_FAIL(code, ...)        \
+  do {                            \
+    ::ss::set_error(__VA_ARGS__); \
+    return (code);                \
+  } while (0)
+#define SS_HIP(call)                                                                   \
+  do {                                                                                 \
+    hipError_t e_ = (call);                                                            \
+    if (e_ != hipSuccess) SS_FAIL(SS_EHIP, "%s: %s", #call, hipGetErrorString(e_));    \
+  } while (0)
+#define SS_TRY(call)                  \
+  do {                                \
+    ss_status s_ = (call);            \
+    if (s_ != SS_OK) return s_;       \
+  } while (0)
+
+// ---------------------------------------------------------------------------
+// element types
+// ---------------------------------------------------------------------------
+typedef uint16_t bf16_t;  // bfloat16 bit pattern
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__host__ __device__ inline float bf16_to_f32(bf16_t b) {
+  union { uint32_t u; float f; } c;
+  c.u = ((uint32_t)b) << 16;
+  return c.f;
+}
+// round-to-nearest-even; inputs are finite
+__host__ __device__ inline bf16_t f32_to_bf16(float f) {
+  union { uint32_t u; float f; } c;
+  c.f = f;
+  uint32_t u = c.u;
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static constexpr int kPerLane = 4;   // elements in a lane's 16-byte piece
+  static constexpr int kFragK = 16;    // k extent of one 1 KiB operand fragment
+  __host__ __device__ static float to_f32(float v) { return v; }
+  __host__ __device__ static float from_f32(float v) { return v; }
+};
+template <> struct Elem<bf16_t> {
+  static constexpr int kPerLane = 8;
+  static constexpr int kFragK = 32;
+  __host__ __device__ static float to_f32(bf16_t v) { return bf16_to_f32(v); }
+  __host__ __device__ static bf16_t from_f32(float v) { return f32_to_bf16(v); }
+};
+
+// Matrix-core operand order.  A [rows x K] operand (weights: rows = output features;
+// activations: rows = batch rows / tokens) is stored as 1 KiB fragments
+// [row_tile = rows/16][k_block = K/FragK][lane 0..63][PerLane], where lane = (kq*16 + r)
+// holds row r of the tile and the k's  k_block*FragK + kq*PerLane + (0..PerLane-1).
+// Both operands of a product use the same order, so a wave loads one fragment as one
+// fully coalesced 1 KiB access and the k permutation cancels in the dot product.
+template <typename T>
+__host__ __device__ inline size_t frag_offset(int row, int k, int k_blocks) {
+  constexpr int PL = Elem<T>::kPerLane, FK = Elem<T>::kFragK;
+  size_t frag = (size_t)(row >> 4) * k_blocks + (k / FK);
+  int kk = k % FK;
+  int lane = (kk / PL) * 16 + (row & 15);
+  return frag * (64 * PL) + lane * PL + (kk % PL);
+}
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+inline size_t align_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
+
+// ---------------------------------------------------------------------------
+// device-side view of one layer and of the shard
+// ---------------------------------------------------------------------------
+struct LayerDev {
+  const float *ln1_g, *ln1_b, *ln2_g, *ln2_b;
+  const void *wqkv;  // fragments, rows = [q heads | k heads | v heads] x Dh, K = d
+  const float *bqkv;
+  const void *wo;    // rows = d, K = Hs*Dh
+  const float *bo;
+  const void *w1;    // rows = Fs (SwiGLU: gate/up fragment rows interleaved per 16-row tile, 2*Fs), K = d
+  const float *b1;
+  const void *w2;    // rows = d, K = Fs
+  const float *b2;
+};
+
+struct Shard;  // defined in shard.h
+
+}  // namespace ss

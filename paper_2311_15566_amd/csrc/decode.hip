@@ -1,0 +1,414 @@
+// The decode step and the initial phase: row kernels (embedding, norms) and the launch
+// sequence over a group of co-resident shards, with HIP-graph replay of the decode step.
+#include <algorithm>
+
+#include "kernels.h"
+#include "shard.h"
+
+namespace ss {
+
+// ---------------------------------------------------------------------------
+// row kernels
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float block_sum(float v, float *scratch) {
+  // sum over a 256-thread block; every thread gets the result
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) v += __shfl_xor(v, off);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return scratch[0] + scratch[1] + scratch[2] + scratch[3];
+}
+
+__device__ __forceinline__ void row_stats(const float *row, int d, int rms, float eps, float *scratch, float *mean_out,
+                                          float *rstd_out) {
+  float s = 0.f;
+  for (int k = threadIdx.x; k < d; k += 256) s += row[k];
+  const float mean = rms ? 0.f : block_sum(s, scratch) / (float)d;
+  float q = 0.f;
+  for (int k = threadIdx.x; k < d; k += 256) {
+    const float c = row[k] - mean;
+    q += c * c;
+  }
+  const float var = block_sum(q, scratch) / (float)d;
+  *mean_out = mean;
+  *rstd_out = rsqrtf(var + eps);
+}
+
+// x[r] = wte[token] (+ wpe[position]); decode: position = committed length, also the first
+// norm's statistics.  grid = rows.
+template <typename T>
+__global__ void __launch_bounds__(256) embed_rows(const int32_t *tokens, const T *wte, const T *wpe, const int32_t *lens,
+                                                  int S, float *x, float *stats, int d, int V, int rms, float eps) {
+  __shared__ float scratch[4];
+  const int r = blockIdx.x;
+  int tok = tokens[r];
+  tok = min(max(tok, 0), V - 1);
+  const int pos = lens ? lens[r] : (r % S);
+  float *xr = x + (size_t)r * d;
+  for (int k = threadIdx.x; k < d; k += 256) {
+    float v = Elem<T>::to_f32(wte[(size_t)tok * d + k]);
+    if (wpe) v += Elem<T>::to_f32(wpe[(size_t)pos * d + k]);
+    xr[k] = v;
+  }
+  if (stats) {
+    __syncthreads();
+    float mean, rstd;
+    row_stats(xr, d, rms, eps, scratch, &mean, &rstd);
+    if (threadIdx.x == 0) stats[r * 2] = mean, stats[r * 2 + 1] = rstd;
+  }
+}
+
+// a = Norm(x) for every token row, written in operand order.  grid = rows.
+template <typename T>
+__global__ void __launch_bounds__(256) norm_rows(const float *x, const float *gamma, const float *beta, void *a_out,
+                                                 int d, int k_blocks, int rms, float eps) {
+  __shared__ float scratch[4];
+  const int r = blockIdx.x;
+  const float *xr = x + (size_t)r * d;
+  float mean, rstd;
+  row_stats(xr, d, rms, eps, scratch, &mean, &rstd);
+  T *a = (T *)a_out;
+  for (int k = threadIdx.x; k < d; k += 256) {
+    float y = (xr[k] - mean) * rstd * gamma[k];
+    if (beta) y += beta[k];
+    a[frag_offset<T>(r, k, k_blocks)] = Elem<T>::from_f32(y);
+  }
+}
+
+// last prompt position of every sequence -> the decode step's residual rows, with statistics
+__global__ void __launch_bounds__(256) gather_last(const float *x, int S, float *xd, float *stats, int d, int rms,
+                                                   float eps) {
+  __shared__ float scratch[4];
+  const int b = blockIdx.x;
+  const float *src = x + ((size_t)b * S + S - 1) * d;
+  float *dst = xd + (size_t)b * d;
+  for (int k = threadIdx.x; k < d; k += 256) dst[k] = src[k];
+  __syncthreads();
+  float mean, rstd;
+  row_stats(dst, d, rms, eps, scratch, &mean, &rstd);
+  if (threadIdx.x == 0) stats[b * 2] = mean, stats[b * 2 + 1] = rstd;
+}
+
+// ---------------------------------------------------------------------------
+// group checks
+// ---------------------------------------------------------------------------
+static ss_status check_group(Shard *const *group, int n_group, int B) {
+  if (!group || n_group < 1 || n_group > 8) SS_FAIL(SS_EINVAL, "group must hold 1..8 shards");
+  for (int i = 0; i < n_group; ++i)
+    if (!group[i]) SS_FAIL(SS_EINVAL, "group[%d] is NULL", i);
+  const Shard *g0 = group[0];
+  if (B < 1 || B > g0->L.Bmax) SS_FAIL(SS_EINVAL, "batch %d outside [1,%d]", B, g0->L.Bmax);
+  for (int i = 1; i < n_group; ++i) {
+    const Shard *s = group[i];
+    if (s->s.layer_lo != g0->s.layer_lo || s->s.layer_hi != g0->s.layer_hi)
+      SS_FAIL(SS_EINVAL, "shards of a group must hold the same layers");
+    if (s->m.d_model != g0->m.d_model || s->m.head_dim != g0->m.head_dim || s->m.dtype != g0->m.dtype ||
+        s->m.act != g0->m.act || s->m.pos != g0->m.pos || s->m.norm != g0->m.norm)
+      SS_FAIL(SS_EINVAL, "shards of a group must come from the same model");
+    if (B > s->L.Bmax) SS_FAIL(SS_EINVAL, "batch %d exceeds group[%d]'s max_batch %d", B, i, s->L.Bmax);
+    for (int j = 0; j < i; ++j) {
+      const Shard *o = group[j];
+      if (s == o) SS_FAIL(SS_EINVAL, "a shard appears twice in the group");
+      if (s->s.head_lo < o->s.head_hi && o->s.head_lo < s->s.head_hi) SS_FAIL(SS_EINVAL, "head slices of the group overlap");
+      if (s->s.ffn_lo < o->s.ffn_hi && o->s.ffn_lo < s->s.ffn_hi) SS_FAIL(SS_EINVAL, "FFN slices of the group overlap");
+    }
+  }
+  return SS_OK;
+}
+
+static void attn_plan(const Layout &L, int B, int *rows_per_block, int *splits) {
+  // enough blocks to fill 256 CUs a few times over, at least 64 rows per block; the partial
+  // buffer holds ceil(Smax/64) splits
+  const int pairs = std::max(1, B * L.Hs);
+  const int want = std::max(1, std::min(ceil_div(1024, pairs), L.attn_splits));
+  const int rpb = (int)align_up((size_t)ceil_div(L.Smax, want), 64);
+  *rows_per_block = rpb;
+  *splits = ceil_div(L.Smax, rpb);
+}
+
+// ---------------------------------------------------------------------------
+// LM head + argmax + commit (shared by decode and the end of the initial phase)
+// ---------------------------------------------------------------------------
+static ss_status lm_head(Shard *const *group, int n_group, int B, float *xd, float *stats, float *logits,
+                         int32_t *next_tokens, int commit_inc, hipStream_t st) {
+  Shard *g0 = group[0];
+  const Layout &L = g0->L;
+  SkinnyArgs a = {};
+  a.w = g0->lm_head.ptr, a.tasks = g0->lm_head.row_tiles, a.k_blocks = g0->lm_head.k_blocks, a.B = B, a.N = L.V;
+  plan_skinny(&a, L.esz, L.splitk_bytes, 1);
+  a.x = xd, a.stats = stats, a.gamma = g0->lnf_g, a.beta = g0->lnf_b;
+  a.splitk = (float *)(g0->ws + L.ws_splitk), a.counters = (int *)(g0->ws + L.ws_counters);
+  a.out_f32 = logits, a.ld_out = L.V;
+  a.am_val = (float *)(g0->ws + L.ws_argmax);
+  a.am_idx = (int *)(a.am_val + (size_t)ceil_div(a.tasks, 4) * 32);
+  a.next_tokens = next_tokens;
+  for (int i = 0; i < n_group; ++i) a.lens[i] = group[i]->d_len;
+  a.n_lens = n_group, a.commit_inc = commit_inc;
+  return launch_skinny(g0->m.dtype, PRO_NORM, EPI_LOGITS, a, st);
+}
+
+// ---------------------------------------------------------------------------
+// one decode step, kernel by kernel
+// ---------------------------------------------------------------------------
+static ss_status enqueue_decode(Shard *const *group, int n_group, const int32_t *tokens_in, int B, float *logits,
+                                int32_t *next_tokens, hipStream_t st, int stop_after_layer) {
+  Shard *g0 = group[0];
+  const Layout &L0 = g0->L;
+  const ss_model_desc &m = g0->m;
+  const int dt = m.dtype, d = L0.d;
+  const int FK = dt == SS_DTYPE_BF16 ? 32 : 16;
+  const int rms = m.norm == SS_NORM_RMSNORM;
+  float *xd = (float *)(g0->ws + L0.ws_y);
+  float *stats = (float *)(g0->ws + L0.ws_stats);
+  float *stat_part = stats + 64;
+  if (dt == SS_DTYPE_BF16)
+    hipLaunchKernelGGL(embed_rows<bf16_t>, dim3(B), dim3(256), 0, st, tokens_in, (const bf16_t *)g0->wte,
+                       (const bf16_t *)g0->wpe, g0->d_len, 0, xd, stats, d, L0.V, rms, m.norm_eps);
+  else
+    hipLaunchKernelGGL(embed_rows<float>, dim3(B), dim3(256), 0, st, tokens_in, (const float *)g0->wte,
+                       (const float *)g0->wpe, g0->d_len, 0, xd, stats, d, L0.V, rms, m.norm_eps);
+  SS_HIP(hipGetLastError());
+
+  for (int l = 0; l < L0.Ls; ++l) {
+    const LayerDev &D0 = g0->layers[l];
+    for (int i = 0; i < n_group; ++i) {  // QKV projection of the new token
+      Shard *s = group[i];
+      const Layout &L = s->L;
+      SkinnyArgs a = {};
+      a.w = s->wqkv[l].ptr, a.tasks = s->wqkv[l].row_tiles, a.k_blocks = s->wqkv[l].k_blocks, a.B = B, a.N = L.qkv_n;
+      plan_skinny(&a, L.esz, L.splitk_bytes, 1);
+      a.x = xd, a.stats = stats, a.gamma = D0.ln1_g, a.beta = D0.ln1_b;
+      a.splitk = (float *)(s->ws + L.ws_splitk), a.counters = (int *)(s->ws + L.ws_counters);
+      a.bias = s->layers[l].bqkv, a.out_f32 = (float *)(s->ws + L.ws_qkv), a.ld_out = L.qkv_n;
+      SS_TRY(launch_skinny(dt, PRO_NORM, EPI_F32, a, st));
+    }
+    for (int i = 0; i < n_group; ++i) {  // attention over the committed rows + append
+      Shard *s = group[i];
+      const Layout &L = s->L;
+      DecodeAttnArgs a = {};
+      a.qkv = (const float *)(s->ws + L.ws_qkv);
+      a.k_cache = s->kv_ptr(l, 0), a.v_cache = s->kv_ptr(l, 1);
+      a.row_stride = s->kv_row_stride(), a.head_stride = s->kv_head_stride();
+      a.lens = s->d_len, a.rope = m.pos == SS_POS_ROPE ? s->rope : nullptr;
+      a.part = (float *)(s->ws + L.ws_attn_part);
+      a.counters = (int *)(s->ws + L.ws_counters) + (L.n_counters - L.Bmax * L.Hs);
+      a.o_out = s->ws + L.ws_o;
+      a.B = B, a.Hs = L.Hs, a.Dh = L.Dh, a.Smax = L.Smax;
+      attn_plan(L, B, &a.rows_per_block, &a.splits);
+      SS_TRY(launch_decode_attn(dt, a, st));
+    }
+    for (int i = 0; i < n_group; ++i) {  // output projection, sum over the group, residual
+      Shard *s = group[i];
+      const Layout &L = s->L;
+      SkinnyArgs a = {};
+      a.w = s->wo[l].ptr, a.tasks = s->wo[l].row_tiles, a.k_blocks = s->wo[l].k_blocks, a.B = B, a.N = d;
+      plan_skinny(&a, L.esz, L.splitk_bytes, 1);
+      a.act = s->ws + L.ws_o;
+      a.splitk = (float *)(s->ws + L.ws_splitk), a.counters = (int *)(s->ws + L.ws_counters);
+      a.bias = i == 0 ? D0.bo : nullptr;
+      a.x_resid = xd, a.stat_part = stat_part, a.stats_out = stats, a.rms = rms, a.eps = m.norm_eps;
+      SS_TRY(launch_skinny(dt, PRO_ACT, EPI_RESID, a, st));
+    }
+    for (int i = 0; i < n_group; ++i) {  // first FFN matrix + activation
+      Shard *s = group[i];
+      const Layout &L = s->L;
+      const bool glu = m.act == SS_ACT_SWIGLU;
+      SkinnyArgs a = {};
+      a.w = s->w1[l].ptr, a.tasks = L.Fs / 16, a.k_blocks = s->w1[l].k_blocks, a.B = B, a.N = L.Fs;
+      plan_skinny(&a, L.esz, L.splitk_bytes, glu ? 2 : 1);
+      a.x = xd, a.stats = stats, a.gamma = D0.ln2_g, a.beta = D0.ln2_b;
+      a.splitk = (float *)(s->ws + L.ws_splitk), a.counters = (int *)(s->ws + L.ws_counters);
+      a.bias = s->layers[l].b1, a.act_out = s->ws + L.ws_u, a.out_k_blocks = L.Fs / FK, a.act_kind = m.act;
+      SS_TRY(launch_skinny(dt, PRO_NORM, glu ? EPI_SWIGLU : EPI_ACT, a, st));
+    }
+    for (int i = 0; i < n_group; ++i) {  // second FFN matrix, sum over the group, residual
+      Shard *s = group[i];
+      const Layout &L = s->L;
+      SkinnyArgs a = {};
+      a.w = s->w2[l].ptr, a.tasks = s->w2[l].row_tiles, a.k_blocks = s->w2[l].k_blocks, a.B = B, a.N = d;
+      plan_skinny(&a, L.esz, L.splitk_bytes, 1);
+      a.act = s->ws + L.ws_u;
+      a.splitk = (float *)(s->ws + L.ws_splitk), a.counters = (int *)(s->ws + L.ws_counters);
+      a.bias = i == 0 ? D0.b2 : nullptr;
+      a.x_resid = xd, a.stat_part = stat_part, a.stats_out = stats, a.rms = rms, a.eps = m.norm_eps;
+      SS_TRY(launch_skinny(dt, PRO_ACT, EPI_RESID, a, st));
+    }
+    if (l == stop_after_layer) SS_FAIL(SS_EINTR, "decode step interrupted after layer %d; nothing committed", l);
+  }
+  return lm_head(group, n_group, B, xd, stats, logits, next_tokens, 1, st);
+}
+
+void destroy_graphs(Shard *sh) {
+  for (auto &kv : sh->graphs) (void)hipGraphExecDestroy(kv.second);
+  sh->graphs.clear();
+}
+
+ss_status run_decode_step(Shard *const *group, int n_group, const int32_t *tokens_in, int B, float *logits,
+                          int32_t *next_tokens, hipStream_t st, int stop_after_layer) {
+  Shard *g0 = group[0];
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  SS_HIP(hipStreamIsCapturing(st, &cs));
+  const bool graph = g0->use_graph && stop_after_layer < 0 && cs == hipStreamCaptureStatusNone;
+  if (!graph) return enqueue_decode(group, n_group, tokens_in, B, logits, next_tokens, st, stop_after_layer);
+  GraphKey key;
+  key.B = B;
+  key.ptrs = {tokens_in, logits, next_tokens, (const void *)st};
+  for (int i = 0; i < n_group; ++i) key.ptrs.push_back(group[i]);
+  auto it = g0->graphs.find(key);
+  if (it == g0->graphs.end()) {
+    hipGraph_t gr = nullptr;
+    SS_HIP(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
+    ss_status rc = enqueue_decode(group, n_group, tokens_in, B, logits, next_tokens, st, -1);
+    hipError_t e = hipStreamEndCapture(st, &gr);
+    if (rc != SS_OK) {
+      if (gr) (void)hipGraphDestroy(gr);
+      return rc;
+    }
+    if (e != hipSuccess) SS_FAIL(SS_EHIP, "hipStreamEndCapture: %s", hipGetErrorString(e));
+    hipGraphExec_t ex = nullptr;
+    e = hipGraphInstantiate(&ex, gr, nullptr, nullptr, 0);
+    (void)hipGraphDestroy(gr);
+    if (e != hipSuccess) SS_FAIL(SS_EHIP, "hipGraphInstantiate: %s", hipGetErrorString(e));
+    if (g0->graphs.size() >= 16) destroy_graphs(g0);
+    it = g0->graphs.emplace(key, ex).first;
+  }
+  SS_HIP(hipGraphLaunch(it->second, st));
+  return SS_OK;
+}
+
+// ---------------------------------------------------------------------------
+// the initial phase
+// ---------------------------------------------------------------------------
+ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, int B, int S, float *logits,
+                      int32_t *next_tokens, hipStream_t st) {
+  Shard *g0 = group[0];
+  const Layout &L0 = g0->L;
+  const ss_model_desc &m = g0->m;
+  const int dt = m.dtype, d = L0.d;
+  const int FK = dt == SS_DTYPE_BF16 ? 32 : 16;
+  const int rms = m.norm == SS_NORM_RMSNORM;
+  const int T_live = B * S, T = (int)align_up((size_t)T_live, 128);
+  for (int i = 0; i < n_group; ++i)
+    if (T > group[i]->L.Tmax) SS_FAIL(SS_EINVAL, "%d prompt tokens exceed group[%d]'s workspace (%d)", T_live, i, group[i]->L.Tmax);
+  float *x = (float *)(g0->ws + L0.ws_x);
+  void *abuf = g0->ws + L0.ws_a;
+  if (dt == SS_DTYPE_BF16)
+    hipLaunchKernelGGL(embed_rows<bf16_t>, dim3(T_live), dim3(256), 0, st, tokens, (const bf16_t *)g0->wte,
+                       (const bf16_t *)g0->wpe, (const int32_t *)nullptr, S, x, (float *)nullptr, d, L0.V, rms, m.norm_eps);
+  else
+    hipLaunchKernelGGL(embed_rows<float>, dim3(T_live), dim3(256), 0, st, tokens, (const float *)g0->wte,
+                       (const float *)g0->wpe, (const int32_t *)nullptr, S, x, (float *)nullptr, d, L0.V, rms, m.norm_eps);
+  SS_HIP(hipGetLastError());
+  auto norm = [&](const float *g, const float *b) -> ss_status {
+    if (dt == SS_DTYPE_BF16)
+      hipLaunchKernelGGL(norm_rows<bf16_t>, dim3(T_live), dim3(256), 0, st, x, g, b, abuf, d, d / FK, rms, m.norm_eps);
+    else
+      hipLaunchKernelGGL(norm_rows<float>, dim3(T_live), dim3(256), 0, st, x, g, b, abuf, d, d / FK, rms, m.norm_eps);
+    SS_HIP(hipGetLastError());
+    return SS_OK;
+  };
+  for (int l = 0; l < L0.Ls; ++l) {
+    const LayerDev &D0 = g0->layers[l];
+    SS_TRY(norm(D0.ln1_g, D0.ln1_b));
+    for (int i = 0; i < n_group; ++i) {
+      Shard *s = group[i];
+      const Layout &L = s->L;
+      TileGemmArgs a = {};
+      a.w = s->wqkv[l].ptr, a.row_tiles = s->wqkv[l].row_tiles, a.k_blocks = s->wqkv[l].k_blocks;
+      a.act = abuf, a.T = T, a.T_live = T_live, a.N = L.qkv_n, a.bias = s->layers[l].bqkv;
+      a.out_f32 = (float *)(s->ws + L.ws_qkv), a.ld_out = L.qkv_n;
+      SS_TRY(launch_tile_gemm(dt, EPI_F32, a, st));
+      PrefillAttnArgs p = {};
+      p.qkv = (float *)(s->ws + L.ws_qkv);
+      p.k_cache = s->kv_ptr(l, 0), p.v_cache = s->kv_ptr(l, 1);
+      p.row_stride = s->kv_row_stride(), p.head_stride = s->kv_head_stride();
+      p.rope = m.pos == SS_POS_ROPE ? s->rope : nullptr;
+      p.o_out = s->ws + L.ws_o;
+      p.B = B, p.S = S, p.Hs = L.Hs, p.Dh = L.Dh, p.Smax = L.Smax;
+      SS_TRY(launch_prefill_kv_write(dt, p, st));
+      SS_TRY(launch_prefill_attn(dt, p, st));
+    }
+    for (int i = 0; i < n_group; ++i) {
+      Shard *s = group[i];
+      const Layout &L = s->L;
+      TileGemmArgs a = {};
+      a.w = s->wo[l].ptr, a.row_tiles = s->wo[l].row_tiles, a.k_blocks = s->wo[l].k_blocks;
+      a.act = s->ws + L.ws_o, a.T = T, a.T_live = T_live, a.N = d, a.bias = i == 0 ? D0.bo : nullptr;
+      a.x_resid = x;
+      SS_TRY(launch_tile_gemm(dt, EPI_RESID, a, st));
+    }
+    SS_TRY(norm(D0.ln2_g, D0.ln2_b));
+    for (int i = 0; i < n_group; ++i) {
+      Shard *s = group[i];
+      const Layout &L = s->L;
+      const bool glu = m.act == SS_ACT_SWIGLU;
+      TileGemmArgs a = {};
+      a.w = s->w1[l].ptr, a.row_tiles = s->w1[l].row_tiles, a.k_blocks = s->w1[l].k_blocks;
+      a.act = abuf, a.T = T, a.T_live = T_live, a.N = L.Fs, a.bias = s->layers[l].b1;
+      a.act_out = s->ws + L.ws_u, a.out_k_blocks = L.Fs / FK, a.act_kind = m.act;
+      SS_TRY(launch_tile_gemm(dt, glu ? EPI_SWIGLU : EPI_ACT, a, st));
+    }
+    for (int i = 0; i < n_group; ++i) {
+      Shard *s = group[i];
+      const Layout &L = s->L;
+      TileGemmArgs a = {};
+      a.w = s->w2[l].ptr, a.row_tiles = s->w2[l].row_tiles, a.k_blocks = s->w2[l].k_blocks;
+      a.act = s->ws + L.ws_u, a.T = T, a.T_live = T_live, a.N = d, a.bias = i == 0 ? D0.b2 : nullptr;
+      a.x_resid = x;
+      SS_TRY(launch_tile_gemm(dt, EPI_RESID, a, st));
+    }
+  }
+  float *xd = (float *)(g0->ws + L0.ws_y);
+  float *stats = (float *)(g0->ws + L0.ws_stats);
+  hipLaunchKernelGGL(gather_last, dim3(B), dim3(256), 0, st, x, S, xd, stats, d, rms, m.norm_eps);
+  SS_HIP(hipGetLastError());
+  return lm_head(group, n_group, B, xd, stats, logits, next_tokens, S, st);
+}
+
+}  // namespace ss
+
+using namespace ss;
+
+extern "C" {
+
+ss_status ss_prefill(ss_shard *const *group_, int32_t n_group, const int32_t *tokens, int32_t B, int32_t S_in,
+                     float *logits, int32_t *next_tokens, void *hip_stream) {
+  Shard *const *group = (Shard *const *)group_;
+  if (!tokens) SS_FAIL(SS_EINVAL, "tokens is NULL");
+  SS_TRY(check_group(group, n_group, B));
+  if (S_in < 1) SS_FAIL(SS_EINVAL, "S_in must be positive");
+  for (int i = 0; i < n_group; ++i) {
+    if (S_in > group[i]->L.Smax) SS_FAIL(SS_EINVAL, "S_in %d exceeds group[%d]'s max_seq %d", S_in, i, group[i]->L.Smax);
+    for (int b = 0; b < B; ++b)
+      if (group[i]->h_len[b] != 0) SS_FAIL(SS_ESTATE, "row %d of group[%d] already holds %d tokens", b, i, group[i]->h_len[b]);
+  }
+  SS_TRY(run_prefill(group, n_group, tokens, B, S_in, logits, next_tokens, (hipStream_t)hip_stream));
+  for (int i = 0; i < n_group; ++i)
+    for (int b = 0; b < B; ++b) group[i]->h_len[b] = S_in;
+  return SS_OK;
+}
+
+ss_status ss_decode_step(ss_shard *const *group_, int32_t n_group, const int32_t *tokens_in, int32_t B, float *logits,
+                         int32_t *next_tokens, void *hip_stream) {
+  Shard *const *group = (Shard *const *)group_;
+  if (!tokens_in) SS_FAIL(SS_EINVAL, "tokens_in is NULL");
+  SS_TRY(check_group(group, n_group, B));
+  for (int b = 0; b < B; ++b) {
+    const int n = group[0]->h_len[b];
+    for (int i = 0; i < n_group; ++i) {
+      if (group[i]->h_len[b] != n)
+        SS_FAIL(SS_ESTATE, "row %d: group[%d] committed %d tokens, group[0] %d", b, i, group[i]->h_len[b], n);
+      if (n + 1 > group[i]->L.Smax) SS_FAIL(SS_ESTATE, "row %d: cache of group[%d] is full (%d rows)", b, i, n);
+    }
+  }
+  int stop = -1;
+  for (int i = 0; i < n_group; ++i) stop = std::max(stop, group[i]->interrupt_after);
+  ss_status rc = run_decode_step(group, n_group, tokens_in, B, logits, next_tokens, (hipStream_t)hip_stream, stop);
+  if (rc != SS_OK) return rc;  // SS_EINTR: nothing committed
+  for (int i = 0; i < n_group; ++i)
+    for (int b = 0; b < B; ++b) group[i]->h_len[b] += 1;
+  return SS_OK;
+}
+
+}  // extern "C"

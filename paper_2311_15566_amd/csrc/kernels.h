@@ -1,0 +1,103 @@
+// Launchers of the hot-path kernels.  Every launcher checks on the host that the operand
+// shapes fit what its kernel assumes before it launches.
+#pragma once
+#include "common.h"
+
+namespace ss {
+
+enum Prologue { PRO_ACT = 0, PRO_NORM = 1 };
+enum Epilogue { EPI_F32 = 0, EPI_RESID = 1, EPI_ACT = 2, EPI_SWIGLU = 3, EPI_LOGITS = 4 };
+
+// Skinny GEMM of the decode step: out[b, n] = sum_k act[b, k] * W[n, k], b < B <= 32.
+// HBM-bound weight streaming: each wave streams whole 1 KiB weight fragments, activations are
+// staged once per block in LDS, split-K partials are reduced by the last block to arrive
+// (fixed order, so results do not depend on scheduling).
+struct SkinnyArgs {
+  // weights
+  const void *w;
+  int tasks;      // wave tasks: 16-row tiles (SwiGLU: gate/up tile pairs)
+  int k_blocks;   // fragments along K
+  int split;      // blocks along K
+  int kb_per_split;
+  int lds_chunk;  // fragments staged in LDS at a time
+  int B;          // live batch rows
+  int nb;         // 16-row batch tiles (1 or 2)
+  int N;          // logical output features (for masking)
+  // prologue
+  const void *act;      // PRO_ACT: fragments [nb][k_blocks]
+  const float *x;       // PRO_NORM: [B][K] float32, row-major
+  const float *stats;   // PRO_NORM: [32][2] = (mean, 1/std)
+  const float *gamma, *beta;
+  // split-K scratch
+  float *splitk;
+  int *counters;        // [groups] + 1
+  // epilogues
+  const float *bias;
+  float *out_f32;       // EPI_F32 / EPI_LOGITS: [B][ld_out]
+  int ld_out;
+  float *x_resid;       // EPI_RESID: residual stream [B][N], updated in place
+  float *stat_part;     // EPI_RESID: [groups][32][2]
+  float *stats_out;     // EPI_RESID: [32][2]
+  int rms;              // EPI_RESID: statistics for RMSNorm (no mean)
+  float eps;
+  void *act_out;        // EPI_ACT / EPI_SWIGLU: fragments [nb][out_k_blocks]
+  int out_k_blocks;
+  int act_kind;
+  float *am_val;        // EPI_LOGITS: [groups][32]
+  int *am_idx;
+  int32_t *next_tokens;
+  int32_t *lens[8];     // EPI_LOGITS: committed lengths to advance (all shards of the group)
+  int n_lens;
+  int commit_inc;
+};
+ss_status launch_skinny(int dtype, int pro, int epi, const SkinnyArgs &a, hipStream_t st);
+// fills split / kb_per_split / lds_chunk / nb from the shape
+void plan_skinny(SkinnyArgs *a, int esz, size_t splitk_bytes, int tasks_rows16);
+
+// Prefill GEMM: out[t, n] = sum_k act[t, k] * W[n, k] over T tokens (multiple of 128), MFMA-bound.
+struct TileGemmArgs {
+  const void *w;      // weight fragments
+  int row_tiles;      // 16-row weight tiles (SwiGLU: 2 per 16 outputs, interleaved)
+  int k_blocks;
+  const void *act;    // activation fragments [T/16][k_blocks]
+  int T;              // tokens (padded to 128)
+  int T_live;         // tokens that exist
+  int N;
+  const float *bias;
+  float *out_f32;     // EPI_F32: [T][ld_out]
+  int ld_out;
+  float *x_resid;     // EPI_RESID: [T][N]
+  void *act_out;      // EPI_ACT / EPI_SWIGLU
+  int out_k_blocks;
+  int act_kind;
+};
+ss_status launch_tile_gemm(int dtype, int epi, const TileGemmArgs &a, hipStream_t st);
+
+// Decode attention over the committed cache (plus the new token), sequence-split.
+struct DecodeAttnArgs {
+  const float *qkv;     // [B][3*Hs*Dh] float32: q | k | v of the new token, biases applied
+  char *k_cache, *v_cache;   // this layer's planes: [Bmax][Hs][Smax][Dh]
+  size_t row_stride, head_stride;  // bytes
+  const int32_t *lens;  // committed lengths (device)
+  const float2 *rope;   // [Smax][Dh/2] or NULL
+  float *part;          // [B*Hs][splits][Dh+4]
+  int *counters;        // [B*Hs]
+  void *o_out;          // fragments [nb][Hs*Dh / FragK]
+  int B, Hs, Dh, Smax;
+  int rows_per_block, splits;
+};
+ss_status launch_decode_attn(int dtype, const DecodeAttnArgs &a, hipStream_t st);
+
+// Prefill: rotate q, k; write K/V rows [0, S) of every sequence; then causal attention.
+struct PrefillAttnArgs {
+  float *qkv;           // [T][3*Hs*Dh] float32 (q rotated in place)
+  char *k_cache, *v_cache;
+  size_t row_stride, head_stride;
+  const float2 *rope;
+  void *o_out;          // fragments [T/16][Hs*Dh / FragK]
+  int B, S, Hs, Dh, Smax;
+};
+ss_status launch_prefill_kv_write(int dtype, const PrefillAttnArgs &a, hipStream_t st);
+ss_status launch_prefill_attn(int dtype, const PrefillAttnArgs &a, hipStream_t st);
+
+}  // namespace ss

@@ -1,0 +1,86 @@
+// Host object of one shard and the carve-up of its device memory.
+#pragma once
+#include "common.h"
+
+namespace ss {
+
+// One weight matrix in matrix-core operand order (see frag_offset).
+struct FragMat {
+  void *ptr = nullptr;
+  int rows = 0;        // logical output features (SwiGLU w1: 2*Fs, gate/up tiles interleaved)
+  int K = 0;           // logical reduction length
+  int row_tiles = 0;   // ceil(rows/16)
+  int k_blocks = 0;    // ceil(K/FragK)
+};
+
+struct Layout {
+  // sizes
+  int Ls, Hs, Fs, d, Dh, V, max_pos, Bmax, Smax;
+  int esz;             // bytes per element of the model dtype
+  int Bpad;            // max_batch rounded up to 16
+  int Tmax;            // prefill tokens the workspace holds (Bmax*Smax rounded up to 16)
+  int qkv_n;           // 3*Hs*Dh
+  int w1_rows;         // Fs or 2*Fs
+  int attn_splits;     // sequence splits of decode attention at Smax
+  // offsets into device_mem
+  size_t off_wte, off_wpe, off_lm, off_lnf_g, off_lnf_b, off_rope;
+  std::vector<size_t> off_layer;       // start of each layer's block
+  size_t layer_bytes;
+  size_t lo_ln1_g, lo_ln1_b, lo_ln2_g, lo_ln2_b, lo_wqkv, lo_bqkv, lo_wo, lo_bo, lo_w1, lo_b1, lo_w2, lo_b2;
+  size_t off_kv, kv_bytes, off_len;
+  size_t off_ws, ws_bytes;             // workspace, doubles as upload staging
+  // workspace sub-offsets (relative to off_ws)
+  size_t ws_x, ws_a, ws_qkv, ws_o, ws_u, ws_splitk, splitk_bytes, ws_stats, ws_counters, ws_attn_part,
+      ws_argmax, ws_y;
+  int n_counters;
+  size_t total;
+};
+
+bool compute_layout(const ss_model_desc &m, const ss_slice &s, int max_batch, int max_seq, Layout *L);
+
+struct GraphKey {
+  std::vector<const void *> ptrs;
+  int B;
+  bool operator<(const GraphKey &o) const { return B != o.B ? B < o.B : ptrs < o.ptrs; }
+};
+
+struct Shard {
+  ss_model_desc m;
+  ss_slice s;
+  Layout L;
+  char *base = nullptr;  // device_mem
+  // model context
+  void *wte = nullptr, *wpe = nullptr;
+  FragMat lm_head;
+  float *lnf_g = nullptr, *lnf_b = nullptr;
+  float2 *rope = nullptr;  // [Smax][Dh/2] (cos, sin)
+  std::vector<LayerDev> layers;
+  std::vector<FragMat> wqkv, wo, w1, w2;
+  // cache context
+  char *kv = nullptr;      // [Ls][2][Bmax][Hs][Smax][Dh]
+  int32_t *d_len = nullptr;
+  std::vector<int32_t> h_len;  // host mirror of the committed lengths
+  // workspace
+  char *ws = nullptr;
+  int interrupt_after = -1;
+  bool use_graph = true;
+  std::map<GraphKey, hipGraphExec_t> graphs;
+
+  size_t kv_head_stride() const { return (size_t)L.Smax * L.Dh * L.esz; }  // bytes between heads
+  size_t kv_row_stride() const { return kv_head_stride() * L.Hs; }          // between batch rows
+  size_t kv_plane_stride() const { return kv_row_stride() * L.Bmax; }       // between K and V
+  size_t kv_layer_stride() const { return kv_plane_stride() * 2; }
+  char *kv_ptr(int layer, int c) const { return kv + layer * kv_layer_stride() + c * kv_plane_stride(); }
+};
+
+// shard.hip
+ss_status validate_desc(const ss_model_desc &m, const ss_slice &s, int max_batch, int max_seq);
+
+// decode.hip
+ss_status run_decode_step(Shard *const *group, int n_group, const int32_t *tokens_in, int B, float *logits,
+                          int32_t *next_tokens, hipStream_t st, int stop_after_layer);
+ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, int B, int S_in, float *logits,
+                      int32_t *next_tokens, hipStream_t st);
+void destroy_graphs(Shard *sh);
+
+}  // namespace ss

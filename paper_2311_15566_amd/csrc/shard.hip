@@ -1,0 +1,589 @@
+// Shard object: device-memory carve-up, model-context upload into matrix-core operand
+// order, cache-context export/import and the KV head re-partition kernel.
+#include "shard.h"
+
+#include <math.h>
+#include <stdarg.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+
+namespace ss {
+
+// ---------------------------------------------------------------------------
+// errors
+// ---------------------------------------------------------------------------
+static thread_local char g_err[512] = "";
+void set_error(const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+// ---------------------------------------------------------------------------
+// validation + layout
+// ---------------------------------------------------------------------------
+ss_status validate_desc(const ss_model_desc &m, const ss_slice &s, int max_batch, int max_seq) {
+  if (m.n_layers <= 0 || m.d_model <= 0 || m.n_heads <= 0 || m.ffn <= 0 || m.vocab <= 0)
+    SS_FAIL(SS_EINVAL, "model descriptor has a non-positive dimension");
+  if (m.head_dim != 64 && m.head_dim != 128) SS_FAIL(SS_EINVAL, "head_dim must be 64 or 128 (got %d)", m.head_dim);
+  if (m.d_model % 64) SS_FAIL(SS_EINVAL, "d_model must be a multiple of 64 (got %d)", m.d_model);
+  if (m.dtype != SS_DTYPE_F32 && m.dtype != SS_DTYPE_BF16) SS_FAIL(SS_EINVAL, "unknown dtype %d", m.dtype);
+  if (m.norm != SS_NORM_LAYERNORM && m.norm != SS_NORM_RMSNORM) SS_FAIL(SS_EINVAL, "unknown norm %d", m.norm);
+  if (m.act < SS_ACT_GELU_TANH || m.act > SS_ACT_SWIGLU) SS_FAIL(SS_EINVAL, "unknown activation %d", m.act);
+  if (m.pos != SS_POS_LEARNED && m.pos != SS_POS_ROPE) SS_FAIL(SS_EINVAL, "unknown position scheme %d", m.pos);
+  if (!(0 <= s.layer_lo && s.layer_lo < s.layer_hi && s.layer_hi <= m.n_layers))
+    SS_FAIL(SS_EINVAL, "layer interval [%d,%d) not inside [0,%d)", s.layer_lo, s.layer_hi, m.n_layers);
+  if (!(0 <= s.head_lo && s.head_lo < s.head_hi && s.head_hi <= m.n_heads))
+    SS_FAIL(SS_EINVAL, "head interval [%d,%d) not inside [0,%d)", s.head_lo, s.head_hi, m.n_heads);
+  if (!(0 <= s.ffn_lo && s.ffn_lo < s.ffn_hi && s.ffn_hi <= m.ffn))
+    SS_FAIL(SS_EINVAL, "FFN interval [%d,%d) not inside [0,%d)", s.ffn_lo, s.ffn_hi, m.ffn);
+  if ((s.ffn_hi - s.ffn_lo) % 64) SS_FAIL(SS_EINVAL, "FFN slice width must be a multiple of 64");
+  if (max_batch < 1 || max_batch > 32) SS_FAIL(SS_EINVAL, "max_batch must be in [1,32] (got %d)", max_batch);
+  if (max_seq < 1 || max_seq > 65536) SS_FAIL(SS_EINVAL, "max_seq must be in [1,65536] (got %d)", max_seq);
+  if (m.pos == SS_POS_LEARNED && m.max_pos < max_seq)
+    SS_FAIL(SS_EINVAL, "learned position table (%d rows) shorter than max_seq %d", m.max_pos, max_seq);
+  return SS_OK;
+}
+
+static size_t frag_bytes(int rows, int K, int esz) {
+  int fk = esz == 2 ? 32 : 16;
+  return (size_t)ceil_div(rows, 16) * ceil_div(K, fk) * 1024;
+}
+
+bool compute_layout(const ss_model_desc &m, const ss_slice &s, int max_batch, int max_seq, Layout *L) {
+  L->Ls = s.layer_hi - s.layer_lo;
+  L->Hs = s.head_hi - s.head_lo;
+  L->Fs = s.ffn_hi - s.ffn_lo;
+  L->d = m.d_model;
+  L->Dh = m.head_dim;
+  L->V = m.vocab;
+  L->max_pos = m.pos == SS_POS_LEARNED ? m.max_pos : 0;
+  L->Bmax = max_batch;
+  L->Smax = max_seq;
+  L->esz = m.dtype == SS_DTYPE_BF16 ? 2 : 4;
+  L->Bpad = (int)align_up(max_batch, 16);
+  L->Tmax = (int)align_up((size_t)max_batch * max_seq, 128);
+  L->qkv_n = 3 * L->Hs * L->Dh;
+  L->w1_rows = m.act == SS_ACT_SWIGLU ? 2 * L->Fs : L->Fs;
+  L->attn_splits = ceil_div(max_seq, 64);
+  const int esz = L->esz, d = L->d, HD = L->Hs * L->Dh;
+  size_t o = 0;
+  auto take = [&](size_t bytes) {
+    size_t at = o;
+    o = align_up(o + bytes, 256);
+    return at;
+  };
+  L->off_wte = take((size_t)L->V * d * esz);
+  L->off_wpe = take((size_t)L->max_pos * d * esz);
+  L->off_lm = take(frag_bytes(L->V, d, esz));
+  L->off_lnf_g = take((size_t)d * 4);
+  L->off_lnf_b = take((size_t)d * 4);
+  L->off_rope = take((size_t)max_seq * (L->Dh / 2) * sizeof(float2));
+  // one layer's block
+  size_t lo = 0;
+  auto ltake = [&](size_t bytes) {
+    size_t at = lo;
+    lo = align_up(lo + bytes, 256);
+    return at;
+  };
+  L->lo_ln1_g = ltake((size_t)d * 4);
+  L->lo_ln1_b = ltake((size_t)d * 4);
+  L->lo_ln2_g = ltake((size_t)d * 4);
+  L->lo_ln2_b = ltake((size_t)d * 4);
+  L->lo_wqkv = ltake(frag_bytes(L->qkv_n, d, esz));
+  L->lo_bqkv = ltake((size_t)L->qkv_n * 4);
+  L->lo_wo = ltake(frag_bytes(d, HD, esz));
+  L->lo_bo = ltake((size_t)d * 4);
+  L->lo_w1 = ltake(frag_bytes(L->w1_rows, d, esz));
+  L->lo_b1 = ltake((size_t)L->w1_rows * 4);
+  L->lo_w2 = ltake(frag_bytes(d, L->Fs, esz));
+  L->lo_b2 = ltake((size_t)d * 4);
+  L->layer_bytes = lo;
+  L->off_layer.clear();
+  for (int l = 0; l < L->Ls; ++l) L->off_layer.push_back(take(L->layer_bytes));
+  L->kv_bytes = (size_t)L->Ls * 2 * max_batch * L->Hs * max_seq * L->Dh * esz;
+  L->off_kv = take(L->kv_bytes);
+  L->off_len = take((size_t)32 * 4);
+  // workspace
+  size_t w = 0;
+  auto wtake = [&](size_t bytes) {
+    size_t at = w;
+    w = align_up(w + bytes, 256);
+    return at;
+  };
+  const int T = L->Tmax;
+  const int nmax = std::max(std::max(L->qkv_n, L->w1_rows), std::max(d, (int)align_up(L->V, 64)));
+  L->ws_x = wtake((size_t)T * d * 4);
+  L->ws_a = wtake((size_t)T * d * esz);
+  L->ws_qkv = wtake((size_t)T * L->qkv_n * 4);
+  L->ws_o = wtake((size_t)T * HD * esz);
+  L->ws_u = wtake((size_t)T * L->Fs * esz);
+  L->ws_y = wtake((size_t)L->Bpad * d * 4);  // residual stream of the decode step
+  L->splitk_bytes = std::min<size_t>((size_t)64 << 20, (size_t)16 * L->Bpad * nmax * 4);
+  L->ws_splitk = wtake(L->splitk_bytes);
+  L->ws_stats = wtake((size_t)64 * 4 + (size_t)ceil_div(d, 64) * 32 * 2 * 4);
+  L->n_counters = 8 + ceil_div(nmax, 64) + max_batch * L->Hs;
+  L->ws_counters = wtake((size_t)L->n_counters * 4);
+  L->ws_attn_part = wtake((size_t)max_batch * L->Hs * L->attn_splits * (L->Dh + 4) * 4);
+  L->ws_argmax = wtake((size_t)ceil_div(nmax, 64) * 32 * 8);
+  // upload staging shares the workspace: it must hold the largest raw tensor slice
+  size_t stage = std::max((size_t)L->V * d, (size_t)d * std::max(std::max(HD, L->Fs), 1)) * esz;
+  L->ws_bytes = std::max(w, align_up(stage, 256));
+  L->off_ws = take(L->ws_bytes);
+  L->total = o;
+  return true;
+}
+
+// ---------------------------------------------------------------------------
+// kernels used at creation
+// ---------------------------------------------------------------------------
+// src: raw slice; element (n, k) at src[n*sn + k*sk].  dst: fragments; logical row tile t of
+// the slice lands at tile t*tile_mul + tile_add (SwiGLU gate/up interleave).  Rows >= N and
+// k >= K are zero-filled.
+template <typename T>
+__global__ void __launch_bounds__(256) shuffle_to_frags(const T *__restrict__ src, T *__restrict__ dst, int N, int K,
+                                                        size_t sn, size_t sk, int k_blocks, int tile_mul,
+                                                        int tile_add, int row_tiles) {
+  constexpr int PL = Elem<T>::kPerLane, FK = Elem<T>::kFragK;
+  size_t total = (size_t)row_tiles * k_blocks * 64;  // one thread per 16-byte lane piece
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    int lane = (int)(i & 63);
+    size_t frag = i >> 6;
+    int kb = (int)(frag % k_blocks);
+    int t = (int)(frag / k_blocks);
+    int n = t * 16 + (lane & 15);
+    int k0 = kb * FK + (lane >> 4) * PL;
+    T v[PL];
+#pragma unroll
+    for (int j = 0; j < PL; ++j) {
+      int k = k0 + j;
+      v[j] = (n < N && k < K) ? src[(size_t)n * sn + (size_t)k * sk] : (T)0;
+    }
+    T *o = dst + ((size_t)(t * tile_mul + tile_add) * k_blocks + kb) * (64 * PL) + lane * PL;
+#pragma unroll
+    for (int j = 0; j < PL; ++j) o[j] = v[j];
+  }
+}
+
+__global__ void fill_i32(int32_t *p, int n, int32_t v) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// ---------------------------------------------------------------------------
+// KV head re-partition: a pure move.  Segment = (layer, K|V, mapped row, head): n rows of
+// Dh elements, contiguous in both layouts.  One block copies one chunk of one segment with
+// 16-byte accesses; lengths come from the host mirror, so the grid has no idle blocks.
+// ---------------------------------------------------------------------------
+struct RepackArgs {
+  const char *src;
+  char *dst;
+  size_t s_layer, s_plane, s_row, s_head;  // source strides in bytes
+  size_t d_layer, d_plane, d_row, d_head;  // destination strides in bytes
+  int n_layers, n_heads;                   // intersection extents
+  int row_bytes;                           // Dh * esz
+  int n_map;                               // mapped destination rows
+  int chunks_per_seg;                      // grid.x = segments * chunks_per_seg
+  int chunk_vec;                           // 16-byte vectors per chunk
+  int32_t map_dst[32], map_src[32], map_len[32];
+  int32_t *dst_len;                        // device lengths of dst
+};
+
+// the destination's lengths are set after the rows have landed (stream order)
+__global__ void kv_repack_commit(RepackArgs a) {
+  if (threadIdx.x < a.n_map) a.dst_len[a.map_dst[threadIdx.x]] = a.map_len[threadIdx.x];
+}
+
+__global__ void __launch_bounds__(256) kv_repack_kernel(RepackArgs a) {
+  int chunk = blockIdx.x % a.chunks_per_seg;
+  int seg = blockIdx.x / a.chunks_per_seg;
+  int h = seg % a.n_heads;
+  seg /= a.n_heads;
+  int r = seg % a.n_map;
+  seg /= a.n_map;
+  int c = seg & 1;
+  int l = seg >> 1;
+  size_t nvec = ((size_t)a.map_len[r] * a.row_bytes) >> 4;
+  size_t v0 = (size_t)chunk * a.chunk_vec;
+  if (v0 >= nvec) return;
+  size_t v1 = v0 + a.chunk_vec < nvec ? v0 + a.chunk_vec : nvec;
+  const u32x4 *s = (const u32x4 *)(a.src + l * a.s_layer + c * a.s_plane + a.map_src[r] * a.s_row + h * a.s_head);
+  u32x4 *d = (u32x4 *)(a.dst + l * a.d_layer + c * a.d_plane + a.map_dst[r] * a.d_row + h * a.d_head);
+  size_t i = v0 + threadIdx.x;
+  // four independent 16-byte loads in flight per lane, then the stores
+  for (; i + 768 < v1; i += 1024) {
+    u32x4 x0 = __builtin_nontemporal_load(s + i);
+    u32x4 x1 = __builtin_nontemporal_load(s + i + 256);
+    u32x4 x2 = __builtin_nontemporal_load(s + i + 512);
+    u32x4 x3 = __builtin_nontemporal_load(s + i + 768);
+    __builtin_nontemporal_store(x0, d + i);
+    __builtin_nontemporal_store(x1, d + i + 256);
+    __builtin_nontemporal_store(x2, d + i + 512);
+    __builtin_nontemporal_store(x3, d + i + 768);
+  }
+  for (; i < v1; i += 256) __builtin_nontemporal_store(__builtin_nontemporal_load(s + i), d + i);
+}
+
+}  // namespace ss
+
+using namespace ss;
+
+// ---------------------------------------------------------------------------
+// C ABI
+// ---------------------------------------------------------------------------
+extern "C" {
+
+const char *ss_last_error(void) { return g_err; }
+const char *ss_version(void) { return "spotshard 0.1 (gfx950)"; }
+
+size_t ss_shard_device_bytes(const ss_model_desc *desc, const ss_slice *slice, int32_t max_batch, int32_t max_seq) {
+  if (!desc || !slice) return 0;
+  if (validate_desc(*desc, *slice, max_batch, max_seq) != SS_OK) return 0;
+  Layout L;
+  compute_layout(*desc, *slice, max_batch, max_seq, &L);
+  return L.total;
+}
+
+}  // extern "C"
+
+namespace ss {
+
+template <typename T>
+static ss_status upload_matrix(Shard *sh, hipStream_t st, const void *host, size_t host_ld, size_t row0, size_t col0,
+                               size_t rows, size_t cols, bool rows_are_out, void *dst, int k_blocks, int row_tiles,
+                               int tile_mul, int tile_add) {
+  // host: row-major [*, host_ld]; take rows [row0,row0+rows) x cols [col0,col0+cols) into staging (dense)
+  if (!host) SS_FAIL(SS_EINVAL, "a required weight pointer is NULL");
+  T *stage = (T *)sh->ws;
+  const T *h = (const T *)host + row0 * host_ld + col0;
+  if (cols == host_ld)
+    SS_HIP(hipMemcpyAsync(stage, h, rows * cols * sizeof(T), hipMemcpyHostToDevice, st));
+  else
+    SS_HIP(hipMemcpy2DAsync(stage, cols * sizeof(T), h, host_ld * sizeof(T), cols * sizeof(T), rows,
+                            hipMemcpyHostToDevice, st));
+  int N, K;
+  size_t sn, sk;
+  if (rows_are_out) {  // staging is [N][K]
+    N = (int)rows, K = (int)cols, sn = cols, sk = 1;
+  } else {             // staging is [K][N]
+    N = (int)cols, K = (int)rows, sn = 1, sk = cols;
+  }
+  size_t total = (size_t)row_tiles * k_blocks * 64;
+  int blocks = (int)std::min<size_t>((total + 255) / 256, 65535);
+  hipLaunchKernelGGL(shuffle_to_frags<T>, dim3(blocks), dim3(256), 0, st, stage, (T *)dst, N, K, sn, sk, k_blocks,
+                     tile_mul, tile_add, row_tiles);
+  SS_HIP(hipGetLastError());
+  return SS_OK;
+}
+
+static ss_status upload_vec(hipStream_t st, const void *host, size_t off, size_t n, float *dst, bool required) {
+  if (!host) {
+    if (required) SS_FAIL(SS_EINVAL, "a required vector pointer is NULL");
+    return SS_OK;
+  }
+  SS_HIP(hipMemcpyAsync(dst, (const float *)host + off, n * 4, hipMemcpyHostToDevice, st));
+  return SS_OK;
+}
+
+template <typename T>
+static ss_status upload_all(Shard *sh, const ss_weights *P, hipStream_t st) {
+  const Layout &L = sh->L;
+  const ss_model_desc &m = sh->m;
+  const int d = L.d, Dh = L.Dh, HD = L.Hs * Dh;
+  const int FK = Elem<T>::kFragK;
+  const int Hp = P->slice.head_hi - P->slice.head_lo, Fp = P->slice.ffn_hi - P->slice.ffn_lo;
+  const size_t c0 = (size_t)(sh->s.head_lo - P->slice.head_lo) * Dh;  // column offset of our heads in the parent
+  const size_t f0 = (size_t)(sh->s.ffn_lo - P->slice.ffn_lo);
+  const bool bias = m.has_bias, ln = m.norm == SS_NORM_LAYERNORM;
+  if (!P->wte || !P->lm_head || !P->lnf_g) SS_FAIL(SS_EINVAL, "wte / lm_head / lnf_g must not be NULL");
+  SS_HIP(hipMemcpyAsync(sh->wte, P->wte, (size_t)L.V * d * sizeof(T), hipMemcpyHostToDevice, st));
+  if (m.pos == SS_POS_LEARNED) {
+    if (!P->wpe) SS_FAIL(SS_EINVAL, "wpe is NULL for a learned-position model");
+    SS_HIP(hipMemcpyAsync(sh->wpe, P->wpe, (size_t)L.max_pos * d * sizeof(T), hipMemcpyHostToDevice, st));
+  }
+  sh->lm_head = FragMat{sh->base + L.off_lm, L.V, d, ceil_div(L.V, 16), d / FK};
+  SS_TRY(upload_matrix<T>(sh, st, P->lm_head, d, 0, 0, L.V, d, true, sh->lm_head.ptr, d / FK, ceil_div(L.V, 16), 1, 0));
+  SS_TRY(upload_vec(st, P->lnf_g, 0, d, sh->lnf_g, true));
+  SS_TRY(upload_vec(st, P->lnf_b, 0, d, sh->lnf_b, ln));
+  for (int l = 0; l < L.Ls; ++l) {
+    const ss_layer_weights &W = P->layers[sh->s.layer_lo - P->slice.layer_lo + l];
+    char *lb = sh->base + L.off_layer[l];
+    LayerDev &D = sh->layers[l];
+    float *ln1_g = (float *)(lb + L.lo_ln1_g), *ln1_b = (float *)(lb + L.lo_ln1_b);
+    float *ln2_g = (float *)(lb + L.lo_ln2_g), *ln2_b = (float *)(lb + L.lo_ln2_b);
+    float *bqkv = (float *)(lb + L.lo_bqkv), *bo = (float *)(lb + L.lo_bo), *b1 = (float *)(lb + L.lo_b1),
+          *b2 = (float *)(lb + L.lo_b2);
+    SS_TRY(upload_vec(st, W.ln1_g, 0, d, ln1_g, true));
+    SS_TRY(upload_vec(st, W.ln1_b, 0, d, ln1_b, ln));
+    SS_TRY(upload_vec(st, W.ln2_g, 0, d, ln2_g, true));
+    SS_TRY(upload_vec(st, W.ln2_b, 0, d, ln2_b, ln));
+    sh->wqkv[l] = FragMat{lb + L.lo_wqkv, L.qkv_n, d, L.qkv_n / 16, d / FK};
+    const void *qkvw[3] = {W.wq, W.wk, W.wv};
+    const void *qkvb[3] = {W.bq, W.bk, W.bv};
+    for (int p = 0; p < 3; ++p) {
+      SS_TRY(upload_matrix<T>(sh, st, qkvw[p], (size_t)Hp * Dh, 0, c0, d, HD, false, sh->wqkv[l].ptr, d / FK,
+                              HD / 16, 1, p * (HD / 16)));
+      SS_TRY(upload_vec(st, qkvb[p], c0, HD, bqkv + p * HD, bias));
+    }
+    sh->wo[l] = FragMat{lb + L.lo_wo, d, HD, d / 16, HD / FK};
+    SS_TRY(upload_matrix<T>(sh, st, W.wo, d, c0, 0, HD, d, false, sh->wo[l].ptr, HD / FK, d / 16, 1, 0));
+    SS_TRY(upload_vec(st, W.bo, 0, d, bo, bias));
+    sh->w1[l] = FragMat{lb + L.lo_w1, L.w1_rows, d, L.w1_rows / 16, d / FK};
+    if (m.act == SS_ACT_SWIGLU) {
+      SS_TRY(upload_matrix<T>(sh, st, W.wg, Fp, 0, f0, d, L.Fs, false, sh->w1[l].ptr, d / FK, L.Fs / 16, 2, 0));
+      SS_TRY(upload_matrix<T>(sh, st, W.wu, Fp, 0, f0, d, L.Fs, false, sh->w1[l].ptr, d / FK, L.Fs / 16, 2, 1));
+    } else {
+      SS_TRY(upload_matrix<T>(sh, st, W.w1, Fp, 0, f0, d, L.Fs, false, sh->w1[l].ptr, d / FK, L.Fs / 16, 1, 0));
+      SS_TRY(upload_vec(st, W.b1, f0, L.Fs, b1, bias));
+    }
+    sh->w2[l] = FragMat{lb + L.lo_w2, d, L.Fs, d / 16, L.Fs / FK};
+    SS_TRY(upload_matrix<T>(sh, st, W.w2, d, f0, 0, L.Fs, d, false, sh->w2[l].ptr, L.Fs / FK, d / 16, 1, 0));
+    SS_TRY(upload_vec(st, W.b2, 0, d, b2, bias));
+    D.ln1_g = ln1_g, D.ln1_b = ln ? ln1_b : nullptr, D.ln2_g = ln2_g, D.ln2_b = ln ? ln2_b : nullptr;
+    D.wqkv = sh->wqkv[l].ptr, D.bqkv = bias ? bqkv : nullptr;
+    D.wo = sh->wo[l].ptr, D.bo = bias ? bo : nullptr;
+    D.w1 = sh->w1[l].ptr, D.b1 = (bias && m.act != SS_ACT_SWIGLU) ? b1 : nullptr;
+    D.w2 = sh->w2[l].ptr, D.b2 = bias ? b2 : nullptr;
+  }
+  return SS_OK;
+}
+
+}  // namespace ss
+
+extern "C" {
+
+ss_status ss_shard_create(const ss_model_desc *desc, const ss_slice *slice, const ss_weights *parent,
+                          int32_t max_batch, int32_t max_seq, void *device_mem, size_t device_bytes,
+                          void *hip_stream, ss_shard **out) {
+  if (!desc || !slice || !parent || !device_mem || !out) SS_FAIL(SS_EINVAL, "NULL argument");
+  *out = nullptr;
+  SS_TRY(validate_desc(*desc, *slice, max_batch, max_seq));
+  const ss_slice &ps = parent->slice;
+  if (!(ps.layer_lo <= slice->layer_lo && slice->layer_hi <= ps.layer_hi && ps.head_lo <= slice->head_lo &&
+        slice->head_hi <= ps.head_hi && ps.ffn_lo <= slice->ffn_lo && slice->ffn_hi <= ps.ffn_hi))
+    SS_FAIL(SS_EINVAL, "slice is not inside the parent's slice");
+  if (!parent->layers) SS_FAIL(SS_EINVAL, "parent->layers is NULL");
+  if (((uintptr_t)device_mem) & 255) SS_FAIL(SS_EINVAL, "device_mem must be 256-byte aligned");
+  Shard *sh = new (std::nothrow) Shard();
+  if (!sh) SS_FAIL(SS_ENOMEM, "host allocation failed");
+  sh->m = *desc;
+  sh->s = *slice;
+  compute_layout(*desc, *slice, max_batch, max_seq, &sh->L);
+  const Layout &L = sh->L;
+  if (device_bytes < L.total) {
+    delete sh;
+    SS_FAIL(SS_ENOMEM, "device_mem holds %zu bytes, the shard needs %zu", device_bytes, L.total);
+  }
+  hipStream_t st = (hipStream_t)hip_stream;
+  sh->base = (char *)device_mem;
+  sh->wte = sh->base + L.off_wte;
+  sh->wpe = L.max_pos ? sh->base + L.off_wpe : nullptr;
+  sh->lnf_g = (float *)(sh->base + L.off_lnf_g);
+  sh->lnf_b = desc->norm == SS_NORM_LAYERNORM ? (float *)(sh->base + L.off_lnf_b) : nullptr;
+  sh->rope = (float2 *)(sh->base + L.off_rope);
+  sh->kv = sh->base + L.off_kv;
+  sh->d_len = (int32_t *)(sh->base + L.off_len);
+  sh->ws = sh->base + L.off_ws;
+  sh->h_len.assign(max_batch, 0);
+  sh->layers.resize(L.Ls);
+  sh->wqkv.resize(L.Ls), sh->wo.resize(L.Ls), sh->w1.resize(L.Ls), sh->w2.resize(L.Ls);
+  ss_status rc = desc->dtype == SS_DTYPE_BF16 ? upload_all<bf16_t>(sh, parent, st) : upload_all<float>(sh, parent, st);
+  if (rc == SS_OK && desc->pos == SS_POS_ROPE) {
+    // angles in double on the host, table in float32
+    std::vector<float2> tab((size_t)max_seq * (L.Dh / 2));
+    for (int p = 0; p < max_seq; ++p)
+      for (int i = 0; i < L.Dh / 2; ++i) {
+        double ang = (double)p * pow((double)desc->rope_theta, -2.0 * i / L.Dh);
+        tab[(size_t)p * (L.Dh / 2) + i] = make_float2((float)cos(ang), (float)sin(ang));
+      }
+    hipError_t e = hipMemcpyAsync(sh->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) {
+      set_error("rope table upload: %s", hipGetErrorString(e));
+      rc = SS_EHIP;
+    }
+  }
+  if (rc == SS_OK) {
+    hipLaunchKernelGGL(fill_i32, dim3(1), dim3(32), 0, st, sh->d_len, 32, 0);
+    int nc = L.n_counters;
+    hipLaunchKernelGGL(fill_i32, dim3(ceil_div(nc, 256)), dim3(256), 0, st, (int32_t *)(sh->ws + L.ws_counters), nc, 0);
+    hipError_t e = hipStreamSynchronize(st);
+    if (e != hipSuccess) {
+      set_error("shard creation: %s", hipGetErrorString(e));
+      rc = SS_EHIP;
+    }
+  }
+  if (rc != SS_OK) {
+    delete sh;
+    return rc;
+  }
+  *out = (ss_shard *)sh;
+  return SS_OK;
+}
+
+ss_status ss_shard_destroy(ss_shard *shard) {
+  if (!shard) return SS_OK;
+  Shard *sh = (Shard *)shard;
+  destroy_graphs(sh);
+  delete sh;
+  return SS_OK;
+}
+
+ss_status ss_shard_reset(ss_shard *shard, void *hip_stream) {
+  if (!shard) SS_FAIL(SS_EINVAL, "NULL shard");
+  Shard *sh = (Shard *)shard;
+  hipLaunchKernelGGL(fill_i32, dim3(1), dim3(32), 0, (hipStream_t)hip_stream, sh->d_len, 32, 0);
+  SS_HIP(hipGetLastError());
+  std::fill(sh->h_len.begin(), sh->h_len.end(), 0);
+  return SS_OK;
+}
+
+ss_status ss_committed_len(const ss_shard *shard, int32_t *out_host, void *hip_stream) {
+  if (!shard || !out_host) SS_FAIL(SS_EINVAL, "NULL argument");
+  const Shard *sh = (const Shard *)shard;
+  SS_HIP(hipMemcpyAsync(out_host, sh->d_len, sh->L.Bmax * 4, hipMemcpyDeviceToHost, (hipStream_t)hip_stream));
+  SS_HIP(hipStreamSynchronize((hipStream_t)hip_stream));
+  return SS_OK;
+}
+
+ss_status ss_shard_geometry(const ss_shard *shard, int32_t out[6]) {
+  if (!shard || !out) SS_FAIL(SS_EINVAL, "NULL argument");
+  const Shard *sh = (const Shard *)shard;
+  out[0] = sh->L.Ls, out[1] = sh->L.Hs, out[2] = sh->L.Fs, out[3] = sh->L.Bmax, out[4] = sh->L.Smax, out[5] = sh->L.esz;
+  return SS_OK;
+}
+
+ss_status ss_debug_interrupt_after_layer(ss_shard *shard, int32_t layer) {
+  if (!shard) SS_FAIL(SS_EINVAL, "NULL shard");
+  Shard *sh = (Shard *)shard;
+  if (layer < -1 || layer >= sh->L.Ls) SS_FAIL(SS_EINVAL, "layer %d outside the shard's %d layers", layer, sh->L.Ls);
+  sh->interrupt_after = layer;
+  return SS_OK;
+}
+
+ss_status ss_set_graph_launch(ss_shard *shard, int32_t enabled) {
+  if (!shard) SS_FAIL(SS_EINVAL, "NULL shard");
+  ((Shard *)shard)->use_graph = enabled != 0;
+  return SS_OK;
+}
+
+// ---------------------------------------------------------------------------
+// re-partition
+// ---------------------------------------------------------------------------
+ss_status ss_kv_repack(ss_shard *dst_, const ss_shard *src_, const int32_t *batch_map, int32_t first_source,
+                       uint64_t *bytes_moved, void *hip_stream) {
+  if (!dst_ || !src_ || !batch_map) SS_FAIL(SS_EINVAL, "NULL argument");
+  Shard *dst = (Shard *)dst_;
+  const Shard *src = (const Shard *)src_;
+  if (dst == src) SS_FAIL(SS_EINVAL, "source and destination are the same shard");
+  if (dst->L.esz != src->L.esz || dst->L.Dh != src->L.Dh)
+    SS_FAIL(SS_EINVAL, "source and destination differ in cache dtype or head_dim");
+  RepackArgs a;
+  memset(&a, 0, sizeof(a));
+  bool used[32] = {false};
+  int max_len = 0;
+  uint64_t rows_total = 0;
+  for (int bd = 0; bd < dst->L.Bmax; ++bd) {
+    int bs = batch_map[bd];
+    if (bs < 0) continue;
+    if (bs >= src->L.Bmax) SS_FAIL(SS_EINVAL, "batch_map[%d] = %d outside the source's %d rows", bd, bs, src->L.Bmax);
+    if (used[bs]) SS_FAIL(SS_EINVAL, "source row %d mapped twice", bs);
+    used[bs] = true;
+    int n = src->h_len[bs];
+    if (n > dst->L.Smax) SS_FAIL(SS_ESTATE, "source row %d holds %d rows, destination capacity is %d", bs, n, dst->L.Smax);
+    if (!first_source && dst->h_len[bd] != n)
+      SS_FAIL(SS_ESTATE, "destination row %d already holds %d rows, this source has %d", bd, dst->h_len[bd], n);
+    a.map_dst[a.n_map] = bd, a.map_src[a.n_map] = bs, a.map_len[a.n_map] = n;
+    a.n_map++;
+    max_len = std::max(max_len, n);
+    rows_total += (uint64_t)n;
+  }
+  const int l_lo = std::max(dst->s.layer_lo, src->s.layer_lo), l_hi = std::min(dst->s.layer_hi, src->s.layer_hi);
+  const int h_lo = std::max(dst->s.head_lo, src->s.head_lo), h_hi = std::min(dst->s.head_hi, src->s.head_hi);
+  a.n_layers = std::max(0, l_hi - l_lo);
+  a.n_heads = std::max(0, h_hi - h_lo);
+  a.row_bytes = dst->L.Dh * dst->L.esz;
+  if (bytes_moved) *bytes_moved = (uint64_t)a.n_layers * 2 * a.n_heads * rows_total * a.row_bytes;
+  for (int i = 0; i < a.n_map; ++i) dst->h_len[a.map_dst[i]] = a.map_len[i];
+  if (a.n_map == 0) return SS_OK;
+  a.dst_len = dst->d_len;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (a.n_layers == 0 || a.n_heads == 0 || max_len == 0) {  // nothing to move: only the lengths change
+    hipLaunchKernelGGL(kv_repack_commit, dim3(1), dim3(32), 0, st, a);
+    SS_HIP(hipGetLastError());
+    return SS_OK;
+  }
+  a.src = src->kv_ptr(l_lo - src->s.layer_lo, 0) + (size_t)(h_lo - src->s.head_lo) * src->kv_head_stride();
+  a.dst = dst->kv_ptr(l_lo - dst->s.layer_lo, 0) + (size_t)(h_lo - dst->s.head_lo) * dst->kv_head_stride();
+  a.s_layer = src->kv_layer_stride(), a.s_plane = src->kv_plane_stride(), a.s_row = src->kv_row_stride(),
+  a.s_head = src->kv_head_stride();
+  a.d_layer = dst->kv_layer_stride(), a.d_plane = dst->kv_plane_stride(), a.d_row = dst->kv_row_stride(),
+  a.d_head = dst->kv_head_stride();
+  const size_t seg_vec = ((size_t)max_len * a.row_bytes) >> 4;
+  a.chunk_vec = 4096;  // 64 KiB per block
+  a.chunks_per_seg = (int)((seg_vec + a.chunk_vec - 1) / a.chunk_vec);
+  size_t blocks = (size_t)a.n_layers * 2 * a.n_map * a.n_heads * a.chunks_per_seg;
+  if (blocks > 0x7fffffffULL) SS_FAIL(SS_EINVAL, "re-partition too large for one launch");
+  hipLaunchKernelGGL(kv_repack_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a);
+  hipLaunchKernelGGL(kv_repack_commit, dim3(1), dim3(32), 0, st, a);
+  SS_HIP(hipGetLastError());
+  return SS_OK;
+}
+
+// ---------------------------------------------------------------------------
+// export / import in the exchange order [layer][K|V][b][head][j < n[b]][Dh]
+// ---------------------------------------------------------------------------
+size_t ss_kv_export_bytes(const ss_shard *shard) {
+  if (!shard) return 0;
+  const Shard *sh = (const Shard *)shard;
+  size_t rows = 0;
+  for (int b = 0; b < sh->L.Bmax; ++b) rows += sh->h_len[b];
+  return (size_t)sh->L.Ls * 2 * sh->L.Hs * rows * sh->L.Dh * sh->L.esz;
+}
+
+static ss_status kv_transfer(const Shard *sh, char *host, size_t bytes, const int32_t *lens, bool to_host,
+                             hipStream_t st) {
+  size_t rows = 0;
+  for (int b = 0; b < sh->L.Bmax; ++b) rows += lens[b];
+  size_t need = (size_t)sh->L.Ls * 2 * sh->L.Hs * rows * sh->L.Dh * sh->L.esz;
+  if (bytes != need) SS_FAIL(SS_EINVAL, "buffer holds %zu bytes, the committed rows take %zu", bytes, need);
+  const size_t rb = (size_t)sh->L.Dh * sh->L.esz;
+  size_t off = 0;
+  for (int l = 0; l < sh->L.Ls; ++l)
+    for (int c = 0; c < 2; ++c)
+      for (int b = 0; b < sh->L.Bmax; ++b) {
+        size_t w = (size_t)lens[b] * rb;  // bytes per head for this row
+        if (!w) continue;
+        char *dev = sh->kv_ptr(l, c) + b * sh->kv_row_stride();
+        if (to_host)
+          SS_HIP(hipMemcpy2DAsync(host + off, w, dev, sh->kv_head_stride(), w, sh->L.Hs, hipMemcpyDeviceToHost, st));
+        else
+          SS_HIP(hipMemcpy2DAsync(dev, sh->kv_head_stride(), host + off, w, w, sh->L.Hs, hipMemcpyHostToDevice, st));
+        off += w * sh->L.Hs;
+      }
+  SS_HIP(hipStreamSynchronize(st));
+  return SS_OK;
+}
+
+ss_status ss_kv_export(const ss_shard *shard, void *host_dst, size_t bytes, void *hip_stream) {
+  if (!shard || (!host_dst && bytes)) SS_FAIL(SS_EINVAL, "NULL argument");
+  const Shard *sh = (const Shard *)shard;
+  return kv_transfer(sh, (char *)host_dst, bytes, sh->h_len.data(), true, (hipStream_t)hip_stream);
+}
+
+ss_status ss_kv_import(ss_shard *shard, const void *host_src, const int32_t *lens, size_t bytes, void *hip_stream) {
+  if (!shard || !lens || (!host_src && bytes)) SS_FAIL(SS_EINVAL, "NULL argument");
+  Shard *sh = (Shard *)shard;
+  for (int b = 0; b < sh->L.Bmax; ++b)
+    if (lens[b] < 0 || lens[b] > sh->L.Smax) SS_FAIL(SS_EINVAL, "lens[%d] = %d outside [0,%d]", b, lens[b], sh->L.Smax);
+  SS_TRY(kv_transfer(sh, (char *)host_src, bytes, lens, false, (hipStream_t)hip_stream));
+  SS_HIP(hipMemcpyAsync(sh->d_len, lens, sh->L.Bmax * 4, hipMemcpyHostToDevice, (hipStream_t)hip_stream));
+  SS_HIP(hipStreamSynchronize((hipStream_t)hip_stream));
+  for (int b = 0; b < sh->L.Bmax; ++b) sh->h_len[b] = lens[b];
+  return SS_OK;
+}
+
+}  // extern "C"

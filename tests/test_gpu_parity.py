@@ -1,0 +1,369 @@
+"""GPU parity: the HIP library against the CPU oracle on the same seeded inputs, through the C ABI.
+
+Bars: KV re-partition and token ids bit-exact; float32 model logits within 1e-4; bf16 model
+logits within max-abs 5e-2 and relative-L2 1e-2 of the oracle (which computes in float64 on the
+same bf16-rounded weights), compared teacher-forced; ids must agree wherever the oracle's
+top-1/top-2 margin exceeds 0.1 (twice the max-abs tolerance).
+"""
+import numpy as np
+import pytest
+
+from oracle import decoder as D
+from synth import make_tokens, make_weights, scaled_workload, sub_slice_of, tp_slice, workload
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, REL_L2, MARGIN = 5e-2, 1e-2, 0.1
+
+
+@pytest.fixture(scope="module")
+def ss():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2311_15566_amd as lib
+    return lib
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def canonical_to_array(flat, L, B, H, S, Dh, lens):
+    """exchange order [layer][K|V][b][head][j<n][Dh] -> dense [L,2,B,H,S,Dh] (zeros beyond n)."""
+    out = np.zeros((L, 2, B, H, S, Dh), dtype=flat.dtype)
+    off = 0
+    for l in range(L):
+        for c in range(2):
+            for b in range(B):
+                n = int(lens[b])
+                blk = flat[off:off + H * n * Dh].reshape(H, n, Dh)
+                out[l, c, b, :, :n] = blk
+                off += H * n * Dh
+    assert off == flat.size
+    return out
+
+
+def array_to_canonical(arr, lens):
+    L, _, B, H, S, Dh = arr.shape
+    parts = []
+    for l in range(L):
+        for c in range(2):
+            for b in range(B):
+                parts.append(arr[l, c, b, :, :int(lens[b])].reshape(-1))
+    return np.concatenate(parts)
+
+
+def check_logits(got, ref, bf16, what=""):
+    ref = np.asarray(ref, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    err = np.abs(got - ref).max()
+    rel = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30)
+    if bf16:
+        assert err < MAX_ABS and rel < REL_L2, f"{what}: max-abs {err:.3e} rel-L2 {rel:.3e}"
+    else:
+        assert err < 1e-4 and rel < 1e-5, f"{what}: max-abs {err:.3e} rel-L2 {rel:.3e}"
+    return err, rel
+
+
+def check_ids(got_ids, ref_logits, what=""):
+    ref_ids = D.greedy(ref_logits)
+    srt = np.sort(ref_logits, axis=-1)
+    margin = srt[:, -1] - srt[:, -2]
+    for b in range(len(ref_ids)):
+        if margin[b] > MARGIN:
+            assert got_ids[b] == ref_ids[b], f"{what}: row {b} id {got_ids[b]} != {ref_ids[b]} (margin {margin[b]:.3f})"
+        else:  # inside the margin either of the near-tied ids is right
+            assert ref_logits[b, got_ids[b]] >= srt[b, -1] - MARGIN
+
+
+# ----------------------------------------------------------------------------
+# config 1: tiny GPT, float32, free-running, ids identical
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("graph", [False, True])
+def test_tiny_gpt_free_running(ss, graph):
+    import torch
+    w = workload("tiny_gpt")
+    W = make_weights(w.desc, w.slice, w.seed)
+    toks = make_tokens(w.seed, w.batch, w.s_in, w.desc["vocab"])
+    ora = D.OracleShard(w.desc, w.slice, W, w.batch, w.s_max)
+    sh = ss.Shard(w.desc, w.slice, W, w.batch, w.s_max)
+    sh.set_graph_launch(graph)
+    logits = torch.empty(w.batch, w.desc["vocab"], dtype=torch.float32, device="cuda")
+    nxt = torch.empty(w.batch, dtype=torch.int32, device="cuda")
+    ref = D.prefill([ora], toks)
+    ss.prefill([sh], dev(toks), logits, nxt)
+    check_logits(logits.cpu().numpy(), ref, False, "prefill")
+    assert np.array_equal(nxt.cpu().numpy(), D.greedy(ref))
+    for step in range(w.steps):
+        ref = D.decode_step([ora], D.greedy(ref))
+        ss.decode_step([sh], nxt, logits, nxt)          # free-running: feeds its own token
+        check_logits(logits.cpu().numpy(), ref, False, f"step {step}")
+        assert np.array_equal(nxt.cpu().numpy(), D.greedy(ref)), f"step {step}"
+    assert list(ss.committed_len(sh)) == [w.s_in + w.steps]
+    # cache contents agree with the oracle's
+    flat = ss.kv_export(sh)
+    assert np.abs(flat - D.kv_canonical(ora)).max() < 1e-5
+    # one more step would overflow the cache: refused on the host, nothing changes
+    with pytest.raises(ss.SpotShardError) as e:
+        ss.decode_step([sh], nxt, logits, nxt)
+    assert e.value.status == 3
+    assert list(ss.committed_len(sh)) == [w.s_in + w.steps]
+    sh.destroy()
+
+
+# ----------------------------------------------------------------------------
+# scaled versions of the three model families, float32 and bf16, several tiles + ragged tails
+# ----------------------------------------------------------------------------
+def scaled(name, dtype, **kw):
+    base = dict(d_model=320, n_heads=6, head_dim=64, ffn=768, vocab=1000, layers=3, M=2, m=1,
+                batch=5, s_in=70, steps=6, dtype=dtype)
+    base.update(kw)
+    return scaled_workload(name, **base)
+
+
+CASES = [
+    ("tiny_gpt", "f32", {}),
+    ("tiny_gpt", "bf16", {}),
+    ("llama30b_m2", "f32", {}),
+    ("llama30b_m2", "bf16", dict(head_dim=128, n_heads=4, d_model=512, batch=17, s_in=150, vocab=1511)),
+    ("opt66b_m8", "bf16", dict(batch=32, s_in=33, d_model=448, ffn=1152, head_dim=128, n_heads=2)),
+    ("gpt20b_m4", "bf16", dict(batch=8, s_in=300, head_dim=128, n_heads=4, steps=4)),
+]
+
+
+@pytest.mark.parametrize("name,dtype,kw", CASES)
+def test_scaled_family_teacher_forced(ss, name, dtype, kw):
+    import torch
+    w = scaled(name, dtype, **kw)
+    bf16 = dtype == "bf16"
+    W = make_weights(w.desc, tp_slice(w.desc, 0, w.desc["n_layers"], 0, 1), w.seed)   # parent = full model
+    toks = make_tokens(w.seed, w.batch, w.s_in, w.desc["vocab"])
+    ora = D.OracleShard(w.desc, w.slice, W, w.batch, w.s_max)
+    sh = ss.Shard(w.desc, w.slice, W, w.batch, w.s_max)
+    V = w.desc["vocab"]
+    logits = torch.empty(w.batch, V, dtype=torch.float32, device="cuda")
+    nxt = torch.empty(w.batch, dtype=torch.int32, device="cuda")
+    ref = D.prefill_matrix([ora], toks)
+    ss.prefill([sh], dev(toks), logits, nxt)
+    check_logits(logits.cpu().numpy(), ref, bf16, "prefill")
+    check_ids(nxt.cpu().numpy(), ref, "prefill")
+    for step in range(w.steps):
+        tok = D.greedy(ref)                              # teacher forcing: the oracle's token
+        ref = D.decode_step([ora], tok)
+        ss.decode_step([sh], dev(tok), logits, nxt)
+        check_logits(logits.cpu().numpy(), ref, bf16, f"step {step}")
+        check_ids(nxt.cpu().numpy(), ref, f"step {step}")
+    assert list(ss.committed_len(sh)) == [w.s_in + w.steps] * w.batch
+    # the cache the GPU built equals the oracle's up to the cache precision
+    got = ss.kv_export(sh)
+    want = D.kv_canonical(ora)
+    if bf16:
+        from synth import bf16_bits_to_f32
+        got = bf16_bits_to_f32(got)
+        assert np.abs(got - want).max() < 2e-2
+    else:
+        assert np.abs(got - want).max() < 1e-4
+    sh.destroy()
+
+
+def test_decode_is_deterministic_and_graph_equals_eager(ss):
+    import torch
+    w = scaled("llama30b_m2", "bf16", batch=9, s_in=40, steps=5)
+    W = make_weights(w.desc, w.slice, w.seed)
+    toks = make_tokens(w.seed, w.batch, w.s_in, w.desc["vocab"])
+    outs = []
+    for graph in (False, True, True):
+        sh = ss.Shard(w.desc, w.slice, W, w.batch, w.s_max)
+        sh.set_graph_launch(graph)
+        logits = torch.empty(w.batch, w.desc["vocab"], dtype=torch.float32, device="cuda")
+        nxt = torch.empty(w.batch, dtype=torch.int32, device="cuda")
+        ss.prefill([sh], dev(toks), logits, nxt)
+        run = [logits.cpu().numpy().copy()]
+        for _ in range(w.steps):
+            ss.decode_step([sh], nxt, logits, nxt)
+            torch.cuda.synchronize()
+            run.append(logits.cpu().numpy().copy())
+        run.append(ss.kv_export(sh))
+        outs.append(run)
+        sh.destroy()
+    for a, b in zip(outs[0], outs[1]):
+        assert np.array_equal(a, b)
+    for a, b in zip(outs[1], outs[2]):
+        assert np.array_equal(a, b)
+
+
+def test_ragged_lengths_and_row_independence(ss):
+    """Rows at different positions in one batch (imported cache), each row matches the oracle."""
+    import torch
+    w = scaled("llama30b_m2", "f32", batch=4, s_in=9, steps=0, s_max=24)
+    W = make_weights(w.desc, w.slice, w.seed)
+    lens = [9, 3, 0, 14]
+    ora = D.OracleShard(w.desc, w.slice, W, 4, 24)
+    toks = make_tokens(w.seed, 4, 14, w.desc["vocab"])
+    for b, n in enumerate(lens):
+        for t in range(n):
+            D.decode_step([ora], toks[:, t], rows=[b])
+    assert list(ora.n) == lens
+    sh = ss.Shard(w.desc, w.slice, W, 4, 24)
+    ss.kv_import(sh, D.kv_canonical(ora).astype(np.float32), lens)
+    assert list(ss.committed_len(sh)) == lens
+    logits = torch.empty(4, w.desc["vocab"], dtype=torch.float32, device="cuda")
+    nxt = torch.empty(4, dtype=torch.int32, device="cuda")
+    step_tok = toks[:, 13].copy()
+    ref = D.decode_step([ora], step_tok)
+    ss.decode_step([sh], dev(step_tok), logits, nxt)
+    check_logits(logits.cpu().numpy(), ref, False, "ragged")
+    assert np.array_equal(nxt.cpu().numpy(), D.greedy(ref))
+    assert list(ss.committed_len(sh)) == [n + 1 for n in lens]
+    sh.destroy()
+
+
+# ----------------------------------------------------------------------------
+# KV re-partition: bit-exact against the index formula
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_repack_split_merge_bit_exact(ss, dtype):
+    w = scaled("llama30b_m2", dtype, n_heads=8, head_dim=128, d_model=256, ffn=256, layers=2, M=2, m=1,
+               batch=5, s_in=300, steps=0, s_max=300)
+    W = make_weights(w.desc, w.slice, w.seed)
+    half = w.slice                                          # heads [4,8)
+    src = ss.Shard(w.desc, half, W, 5, 300)
+    g = src.geometry()
+    L, H, Dh = g["layers"], g["heads"], w.desc["head_dim"]
+    rng = np.random.default_rng(11)
+    lens = [300, 1, 0, 257, 64]
+    np_dt = np.uint16 if dtype == "bf16" else np.float32
+    src_arr = rng.integers(0, 60000, size=(L, 2, 5, H, 300, Dh)).astype(np_dt)
+    for b, n in enumerate(lens):
+        src_arr[:, :, b, :, n:] = 0
+    ss.kv_import(src, array_to_canonical(src_arr, lens), lens)
+    assert np.array_equal(ss.kv_export(src), array_to_canonical(src_arr, lens))   # import/export round trip
+    # split into two quarter shards with other batch size / capacity, dropping row 1, permuting rows
+    bmap = [3, -1, 0, 4]
+    dsts = []
+    for p in range(2):
+        q = sub_slice_of(half, p, 2)
+        dshard = ss.Shard(w.desc, q, W, 4, 320)
+        moved = ss.kv_repack(dshard, src, bmap)
+        exp = np.zeros((L, 2, 4, H // 2, 320, Dh), dtype=np_dt)
+        moved_ref = D.kv_repack_arrays(exp, q, src_arr, half, lens, bmap)
+        assert moved == moved_ref * np.dtype(np_dt).itemsize
+        dlens = list(ss.committed_len(dshard))
+        assert dlens == [257, 0, 300, 64]
+        got = canonical_to_array(ss.kv_export(dshard), L, 4, H // 2, 320, Dh, dlens)
+        assert np.array_equal(got, exp)
+        dsts.append((dshard, q, exp, dlens))
+    # merge back into a fresh half shard: M' -> M is the identity on the kept rows
+    back = ss.Shard(w.desc, half, W, 5, 300)
+    for i, (dshard, q, exp, dlens) in enumerate(dsts):
+        ss.kv_repack(back, dshard, [2, -1, -1, 0, 3], first_source=(i == 0))
+    blens = list(ss.committed_len(back))
+    assert blens == [300, 0, 0, 257, 64]
+    got = canonical_to_array(ss.kv_export(back), L, 5, H, 300, Dh, blens)
+    want = src_arr.copy()
+    want[:, :, 1] = 0
+    assert np.array_equal(got, want)
+    # a source that disagrees with what the destination holds is refused
+    other = ss.Shard(w.desc, sub_slice_of(half, 1, 2), W, 4, 320)
+    ss.kv_import(other, np.zeros(0, dtype=np_dt), [0, 0, 0, 0])
+    with pytest.raises(ss.SpotShardError) as e:
+        ss.kv_repack(back, other, [0, -1, -1, -1, -1], first_source=False)
+    assert e.value.status == 3
+    for s in [src, back, other] + [d[0] for d in dsts]:
+        s.destroy()
+
+
+def test_resume_on_repartitioned_shards_matches_uninterrupted(ss):
+    """Decode k steps on an M=2 shard, re-partition its cache into two M'=4 shards, resume j
+    steps on the pair: logits match the uninterrupted run and the oracle."""
+    import torch
+    w = scaled("llama30b_m2", "bf16", n_heads=8, head_dim=128, d_model=512, ffn=1024, layers=3, M=2, m=0,
+               batch=6, s_in=90, steps=8, s_max=110)
+    W = make_weights(w.desc, w.slice, w.seed)
+    toks = make_tokens(w.seed, w.batch, w.s_in, w.desc["vocab"])
+    V = w.desc["vocab"]
+    ora = D.OracleShard(w.desc, w.slice, W, w.batch, w.s_max)
+    ref = D.prefill_matrix([ora], toks)
+    refs, feed = [], []
+    for _ in range(w.steps):
+        tok = D.greedy(ref)
+        feed.append(tok)
+        ref = D.decode_step([ora], tok)
+        refs.append(ref)
+    # uninterrupted GPU run (teacher-forced with the oracle's tokens)
+    full = ss.Shard(w.desc, w.slice, W, w.batch, w.s_max)
+    logits = torch.empty(w.batch, V, dtype=torch.float32, device="cuda")
+    ss.prefill([full], dev(toks), logits, None)
+    unint = []
+    for i in range(w.steps):
+        ss.decode_step([full], dev(feed[i]), logits, None)
+        unint.append(logits.cpu().numpy().copy())
+    # interrupted run: 4 steps, re-partition, 4 more on the pair
+    run = ss.Shard(w.desc, w.slice, W, w.batch, w.s_max)
+    ss.prefill([run], dev(toks), logits, None)
+    for i in range(4):
+        ss.decode_step([run], dev(feed[i]), logits, None)
+        assert np.array_equal(logits.cpu().numpy(), unint[i])
+    pair = [ss.Shard(w.desc, sub_slice_of(w.slice, p, 2), W, w.batch, w.s_max) for p in range(2)]
+    keep = list(range(w.batch))
+    for p in pair:
+        ss.kv_repack(p, run, keep)
+    for i in range(4, w.steps):
+        ss.decode_step(pair, dev(feed[i]), logits, None)
+        got = logits.cpu().numpy()
+        check_logits(got, refs[i], True, f"resumed step {i} vs oracle")
+        assert np.abs(got - unint[i]).max() < 2e-2, f"resumed step {i} vs uninterrupted"
+    for s in [full, run] + pair:
+        s.destroy()
+
+
+def test_interrupted_step_commits_nothing_and_retry_is_identical(ss):
+    import torch
+    w = scaled("tiny_gpt", "bf16", batch=3, s_in=20, steps=2)
+    W = make_weights(w.desc, w.slice, w.seed)
+    toks = make_tokens(w.seed, w.batch, w.s_in, w.desc["vocab"])
+    V = w.desc["vocab"]
+    a, b = (ss.Shard(w.desc, w.slice, W, w.batch, w.s_max) for _ in range(2))
+    la, lb = (torch.empty(w.batch, V, dtype=torch.float32, device="cuda") for _ in range(2))
+    na, nb = (torch.empty(w.batch, dtype=torch.int32, device="cuda") for _ in range(2))
+    ss.prefill([a], dev(toks), la, na)
+    ss.prefill([b], dev(toks), lb, nb)
+    before = ss.kv_export(b)
+    b.interrupt_after_layer(1)
+    with pytest.raises(ss.SpotShardError) as e:
+        ss.decode_step([b], nb, lb, None)
+    assert e.value.status == 5
+    assert list(ss.committed_len(b)) == [w.s_in] * w.batch
+    assert np.array_equal(ss.kv_export(b), before)        # committed rows untouched
+    b.interrupt_after_layer(-1)
+    ss.decode_step([b], nb, lb, nb)                        # retry
+    ss.decode_step([a], na, la, na)
+    assert np.array_equal(la.cpu().numpy(), lb.cpu().numpy())
+    assert np.array_equal(ss.kv_export(a), ss.kv_export(b))
+    a.destroy()
+    b.destroy()
+
+
+def test_argument_errors(ss):
+    import torch
+    w = workload("tiny_gpt")
+    W = make_weights(w.desc, w.slice, w.seed)
+    sh = ss.Shard(w.desc, w.slice, W, 1, 32)
+    t = dev(make_tokens(1, 1, 8, 1024))
+    ss.prefill([sh], t, None, None)
+    with pytest.raises(ss.SpotShardError) as e:            # row not empty
+        ss.prefill([sh], t, None, None)
+    assert e.value.status == 3
+    sh.reset()
+    assert list(ss.committed_len(sh)) == [0]
+    ss.prefill([sh], t, None, None)
+    with pytest.raises(ss.SpotShardError) as e:            # same shard twice in a group
+        ss.decode_step([sh, sh], t[:, 0].contiguous(), None, None)
+    assert e.value.status == 1
+    with pytest.raises(ss.SpotShardError):                 # slice outside the parent
+        ss.Shard(w.desc, dict(w.slice, head_hi=5), W, 1, 32)
+    with pytest.raises(ss.SpotShardError) as e:            # repack onto itself
+        ss.kv_repack(sh, sh, [0])
+    assert e.value.status == 1
+    sh.destroy()
