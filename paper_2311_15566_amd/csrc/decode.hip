@@ -247,9 +247,10 @@ void destroy_graphs(Shard *sh) {
 ss_status run_decode_step(Shard *const *group, int n_group, const int32_t *tokens_in, int B, float *logits,
                           int32_t *next_tokens, hipStream_t st, int stop_after_layer) {
   Shard *g0 = group[0];
+  // the NULL stream cannot be captured, and a stream the caller is capturing is left to the caller
   hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-  SS_HIP(hipStreamIsCapturing(st, &cs));
-  const bool graph = g0->use_graph && stop_after_layer < 0 && cs == hipStreamCaptureStatusNone;
+  if (st) SS_HIP(hipStreamIsCapturing(st, &cs));
+  const bool graph = g0->use_graph && stop_after_layer < 0 && st != nullptr && cs == hipStreamCaptureStatusNone;
   if (!graph) return enqueue_decode(group, n_group, tokens_in, B, logits, next_tokens, st, stop_after_layer);
   GraphKey key;
   key.B = B;

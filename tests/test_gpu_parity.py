@@ -80,8 +80,18 @@ def check_ids(got_ids, ref_logits, what=""):
 # ----------------------------------------------------------------------------
 # config 1: tiny GPT, float32, free-running, ids identical
 # ----------------------------------------------------------------------------
+@pytest.fixture
+def side_stream():
+    """Work runs on a non-default stream (the NULL stream cannot be graph-captured)."""
+    import torch
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        yield s
+    torch.cuda.synchronize()
+
+
 @pytest.mark.parametrize("graph", [False, True])
-def test_tiny_gpt_free_running(ss, graph):
+def test_tiny_gpt_free_running(ss, graph, side_stream):
     import torch
     w = workload("tiny_gpt")
     W = make_weights(w.desc, w.slice, w.seed)
@@ -133,7 +143,7 @@ CASES = [
 
 
 @pytest.mark.parametrize("name,dtype,kw", CASES)
-def test_scaled_family_teacher_forced(ss, name, dtype, kw):
+def test_scaled_family_teacher_forced(ss, name, dtype, kw, side_stream):
     import torch
     w = scaled(name, dtype, **kw)
     bf16 = dtype == "bf16"
@@ -167,7 +177,7 @@ def test_scaled_family_teacher_forced(ss, name, dtype, kw):
     sh.destroy()
 
 
-def test_decode_is_deterministic_and_graph_equals_eager(ss):
+def test_decode_is_deterministic_and_graph_equals_eager(ss, side_stream):
     import torch
     w = scaled("llama30b_m2", "bf16", batch=9, s_in=40, steps=5)
     W = make_weights(w.desc, w.slice, w.seed)
@@ -274,7 +284,7 @@ def test_repack_split_merge_bit_exact(ss, dtype):
         s.destroy()
 
 
-def test_resume_on_repartitioned_shards_matches_uninterrupted(ss):
+def test_resume_on_repartitioned_shards_matches_uninterrupted(ss, side_stream):
     """Decode k steps on an M=2 shard, re-partition its cache into two M'=4 shards, resume j
     steps on the pair: logits match the uninterrupted run and the oracle."""
     import torch
@@ -318,7 +328,7 @@ def test_resume_on_repartitioned_shards_matches_uninterrupted(ss):
         s.destroy()
 
 
-def test_interrupted_step_commits_nothing_and_retry_is_identical(ss):
+def test_interrupted_step_commits_nothing_and_retry_is_identical(ss, side_stream):
     import torch
     w = scaled("tiny_gpt", "bf16", batch=3, s_in=20, steps=2)
     W = make_weights(w.desc, w.slice, w.seed)
