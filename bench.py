@@ -1,0 +1,242 @@
+#!/usr/bin/env python3
+"""Benchmark of the decode hot path on one MI355X.
+
+A step is one incremental decoding iteration of the whole batch through the shard (embedding,
+every layer's QKV / attention + KV append / out-projection / FFN, LM head, greedy argmax,
+token-level commit).  The timed region is exactly --steps iterations after a fresh initial
+phase, replayed as a HIP graph, with every input already resident in HBM.  The initial phase
+and the KV re-partition are measured in the same run and reported beside it.
+
+Prints ONE JSON line (see the design doc for the byte counts behind `roofline`).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def shard_dims(w):
+    d = w.desc
+    s = w.slice
+    return dict(Ls=s["layer_hi"] - s["layer_lo"], Hs=s["head_hi"] - s["head_lo"], Fs=s["ffn_hi"] - s["ffn_lo"],
+                d=d["d_model"], Dh=d["head_dim"], V=d["vocab"], esz=2 if d["dtype"] == "bf16" else 4,
+                c1=2 if d["act"] == "swiglu" else 1)
+
+
+def algorithmic_bytes(w, n_list):
+    """Bytes the method must move per decode step: every shard weight once (the batch shares
+    it), the committed K/V rows plus the new one once, and the new row written."""
+    g = shard_dims(w)
+    HD = g["Hs"] * g["Dh"]
+    per_layer = dict(qkv_gemm=g["d"] * 3 * HD * g["esz"], out_proj=HD * g["d"] * g["esz"],
+                     ffn_up_gemm=g["c1"] * g["d"] * g["Fs"] * g["esz"], ffn_down=g["Fs"] * g["d"] * g["esz"])
+    lm = g["V"] * g["d"] * g["esz"]
+    kv_row = g["Ls"] * 2 * w.batch * HD * g["esz"]          # all layers, K and V, all batch rows, one position
+    weights = g["Ls"] * sum(per_layer.values()) + lm
+    steps = [weights + kv_row * (n + 1) + kv_row for n in n_list]
+    classes = dict(qkv_gemm=g["Ls"] * per_layer["qkv_gemm"], ffn_up_gemm=g["Ls"] * per_layer["ffn_up_gemm"],
+                   resid_gemm=g["Ls"] * (per_layer["out_proj"] + per_layer["ffn_down"]), lm_head=lm)
+    attn = [kv_row * (n + 1) + kv_row for n in n_list]
+    return steps, classes, attn, weights
+
+
+def prefill_flops(w):
+    g = shard_dims(w)
+    HD = g["Hs"] * g["Dh"]
+    T = w.batch * w.s_in
+    per_tok = 2 * g["Ls"] * (g["d"] * 3 * HD + HD * g["d"] + (g["c1"] + 1) * g["d"] * g["Fs"])
+    attn = g["Ls"] * w.batch * g["Hs"] * 4 * g["Dh"] * (w.s_in * (w.s_in + 1) // 2)
+    return T * per_tok + attn + 2 * w.batch * g["V"] * g["d"]
+
+
+def cpu_baseline(w, W, n_ctx, steps=32):
+    """The oracle as it stands, timed on this machine's host cores: full batch, `steps` decode
+    iterations at context n_ctx (cache rows filled with noise; timing does not depend on values)."""
+    from oracle import decoder as D
+    t0 = time.perf_counter()
+    ora = D.OracleShard(w.desc, w.slice, W, w.batch, n_ctx + steps + 2, real=np.float32)
+    rng = np.random.default_rng(1)
+    ora.kv[:, :, :, :, :n_ctx] = rng.standard_normal(size=ora.kv[:, :, :, :, :n_ctx].shape, dtype=np.float32) * 0.5
+    ora.n[:] = n_ctx
+    toks = rng.integers(0, w.desc["vocab"], size=w.batch)
+    setup = time.perf_counter() - t0
+    D.decode_step([ora], toks)                                # untimed first touch
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        toks = D.greedy(D.decode_step([ora], toks))
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    return dict(value=w.batch * steps / dt, unit="tokens/s", cores=int(threads), kind="oracle",
+                sample=f"full batch of {w.batch}, {steps} decode steps at context {n_ctx} (of {w.s_in}..{w.s_in + w.steps}), "
+                       f"float32 numpy oracle, {dt:.1f} s timed (+{setup:.0f} s set-up)")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=128)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="gpt20b_m4", choices=["gpt20b_m4", "llama30b_m2", "opt66b_m8", "tiny_gpt"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the kernel-class, prefill and repack legs")
+    ap.add_argument("--eager", action="store_true", help="launch kernel by kernel instead of replaying a graph")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs one tensor-parallel shard on ONE GPU; collectives and sharding "
+                 "across GPUs are not part of it (run with --gpus 1)")
+
+    import torch
+    import paper_2311_15566_amd as ss
+    from synth import make_tokens, make_weights, sub_slice_of, workload
+
+    assert torch.cuda.is_available(), "bench.py needs an MI355X"
+    torch.cuda.set_device(0)
+    w = workload(args.workload)
+    K, Wm = args.steps, args.warmup
+    if K > w.s_max - w.s_in:
+        sys.exit(f"--steps {K} exceeds the workload's {w.s_max - w.s_in} decode steps")
+    t0 = time.perf_counter()
+    W = make_weights(w.desc, w.slice, w.seed)
+    toks = make_tokens(w.seed, w.batch, w.s_in, w.desc["vocab"])
+    log(f"[bench] {w.name}: weights drawn in {time.perf_counter() - t0:.1f} s")
+
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        t0 = time.perf_counter()
+        sh = ss.Shard(w.desc, w.slice, W, w.batch, w.s_max)
+        log(f"[bench] shard created ({sh.mem.numel() / 1e9:.2f} GB on device) in {time.perf_counter() - t0:.1f} s")
+        sh.set_graph_launch(not args.eager)
+        V = w.desc["vocab"]
+        d_toks = torch.from_numpy(toks).cuda()
+        logits = torch.empty(w.batch, V, dtype=torch.float32, device="cuda")
+        nxt = torch.empty(w.batch, dtype=torch.int32, device="cuda")
+
+        def fresh():
+            sh.reset()
+            ss.prefill([sh], d_toks, logits, nxt)
+
+        # warm-up: initial phase + Wm decode steps, then start over
+        fresh()
+        for _ in range(Wm):
+            ss.decode_step([sh], nxt, logits, nxt)
+        torch.cuda.synchronize()
+        sh.reset()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        ss.prefill([sh], d_toks, logits, nxt)
+        e1.record()
+        torch.cuda.synchronize()
+        prefill_ms = e0.elapsed_time(e1)
+
+        # ---- the timed region: exactly K decode steps ----
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(K):
+            ss.decode_step([sh], nxt, logits, nxt)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        final_ids = nxt.cpu().numpy().copy()
+        assert list(ss.committed_len(sh)) == [w.s_in + K] * w.batch
+
+        n_list = [w.s_in + i for i in range(K)]
+        step_bytes, class_bytes, attn_bytes, weight_bytes = algorithmic_bytes(w, n_list)
+        out = dict(metric="decode tokens/s per TP shard on 1 GPU", value=w.batch * K / dt, unit="tokens/s", n_gpus=1,
+                   steps=K, warmup=Wm, ms_per_step=dt / K * 1e3, higher_is_better=True, scaling="weak",
+                   vs_baseline=None, dtype=w.desc["dtype"], data="synthetic",
+                   config=dict(workload=f"{w.name}: {shard_dims(w)['Ls']} layers, d={w.desc['d_model']}, "
+                                        f"{shard_dims(w)['Hs']} heads x {w.desc['head_dim']}, FFN {shard_dims(w)['Fs']}, "
+                                        f"vocab {V}, batch {w.batch}, prompt {w.s_in}, {K} decode steps",
+                               batch=w.batch, prompt=w.s_in, launch="eager" if args.eager else "hip-graph"))
+        whole = sum(step_bytes) / dt / 1e9
+        out["step_hbm"] = dict(bytes_per_step=sum(step_bytes) / K, achieved=whole, peak=HBM_PEAK_GBPS, unit="GB/s",
+                               frac=whole / HBM_PEAK_GBPS)
+
+        if not args.no_extras:
+            # ---- kernel classes: the same K steps again, kernel by kernel with HIP events ----
+            fresh()
+            torch.cuda.synchronize()
+            sh.kernel_timing(True)
+            for _ in range(K):
+                ss.decode_step([sh], nxt, logits, nxt)
+            tm = sh.kernel_timing_read()
+            sh.kernel_timing(False)
+            assert np.array_equal(nxt.cpu().numpy(), final_ids), "eager and graph runs disagree"
+            classes = {}
+            for name, (ms, cnt) in tm.items():
+                if cnt == 0:
+                    continue
+                if name in class_bytes:
+                    b = class_bytes[name] * K
+                elif name == "decode_attn":
+                    b = sum(attn_bytes)
+                else:
+                    b = 0
+                classes[name] = dict(launches=int(cnt), avg_us=ms / cnt * 1e3, GBps=(b / (ms * 1e-3) / 1e9) if b else None)
+            out["classes"] = classes
+            dom = "resid_gemm"                                   # out-projection + second FFN matrix: most bytes per step
+            ms, cnt = tm[dom]
+            ach = class_bytes[dom] * K / (ms * 1e-3) / 1e9
+            out["roofline"] = dict(bound="hbm", kernel="skinny_gemm<PRO_ACT,EPI_RESID> (out-projection and FFN-down)",
+                                   achieved=ach, peak=HBM_PEAK_GBPS, unit="GB/s", frac=ach / HBM_PEAK_GBPS, traffic=None,
+                                   bytes_per_launch=class_bytes[dom] * K / cnt, avg_launch_us=ms / cnt * 1e3,
+                                   launches=int(cnt))
+            fl = prefill_flops(w)
+            peak = MFMA_PEAK_TFLOPS[w.desc["dtype"]]
+            out["prefill"] = dict(ms=prefill_ms, tokens=w.batch * w.s_in, TFLOPs=fl / (prefill_ms * 1e-3) / 1e12,
+                                  peak=peak, frac=fl / (prefill_ms * 1e-3) / 1e12 / peak)
+
+            # ---- KV re-partition of this shard's cache into two half-width shards ----
+            g = shard_dims(w)
+            if g["Hs"] % 2 == 0 and g["Fs"] % 128 == 0:
+                parts = [ss.Shard(w.desc, sub_slice_of(w.slice, p, 2), W, w.batch, w.s_max) for p in range(2)]
+                keep = list(range(w.batch))
+                for p in parts:
+                    ss.kv_repack(p, sh, keep)                     # untimed first touch
+                torch.cuda.synchronize()
+                reps = 5
+                e0.record()
+                moved = 0
+                for _ in range(reps):
+                    for p in parts:
+                        moved += ss.kv_repack(p, sh, keep)
+                e1.record()
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1)
+                traffic = 2 * moved / (ms * 1e-3) / 1e9
+                out["repack"] = dict(payload_bytes=moved // reps, ms=ms / reps, traffic_GBps=traffic,
+                                     frac=traffic / HBM_PEAK_GBPS, rows=w.s_in + K,
+                                     note="traffic = bytes read + bytes written; payload = half")
+                for p in parts:
+                    p.destroy()
+        else:
+            out["roofline"] = dict(bound="hbm", kernel="whole decode step", achieved=whole, peak=HBM_PEAK_GBPS,
+                                   unit="GB/s", frac=whole / HBM_PEAK_GBPS, traffic=None)
+        sh.destroy()
+        del sh
+        torch.cuda.empty_cache()
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, W, w.s_in + K // 2)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

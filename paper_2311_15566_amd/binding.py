@@ -71,6 +71,8 @@ def _load():
     L.ss_debug_interrupt_after_layer.argtypes = [vp, i32]
     L.ss_set_graph_launch.argtypes = [vp, i32]
     L.ss_shard_geometry.argtypes = [vp, C.POINTER(i32)]
+    L.ss_kernel_timing.argtypes = [vp, i32]
+    L.ss_kernel_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), vp]
     return L
 
 
@@ -164,6 +166,15 @@ class Shard:
 
     def set_graph_launch(self, enabled: bool):
         _check(lib.ss_set_graph_launch(self.handle, int(enabled)))
+
+    def kernel_timing(self, enabled: bool):
+        _check(lib.ss_kernel_timing(self.handle, int(enabled)))
+
+    def kernel_timing_read(self, stream=None):
+        ms, cnt = (C.c_double * 8)(), (C.c_int64 * 8)()
+        _check(lib.ss_kernel_timing_read(self.handle, ms, cnt, _stream(stream)))
+        names = ("embed", "qkv_gemm", "decode_attn", "resid_gemm", "ffn_up_gemm", "lm_head")
+        return {n: (ms[i], cnt[i]) for i, n in enumerate(names)}
 
     def geometry(self):
         out = (C.c_int32 * 6)()

@@ -157,28 +157,18 @@ __global__ void __launch_bounds__(256) decode_attn(DecodeAttnArgs a) {
   if (live_splits > 1) {
     if (tid < DH) {
       float *p = part + (size_t)sp * (DH + 4);
-      p[tid] = A;
-      if (tid == 0) p[DH] = M, p[DH + 1] = Lsum;
+      st_dev(p + tid, A);
+      if (tid == 0) st_dev(p + DH, M), st_dev(p + DH + 1, Lsum);
     }
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-      int old = atomicAdd(&a.counters[bh], 1);
-      int last = old == live_splits - 1;
-      if (last) a.counters[bh] = 0;
-      s_flag = last;
-    }
-    __syncthreads();
-    if (!s_flag) return;
-    __threadfence();
+    if (!arrive_last(&a.counters[bh], live_splits, &s_flag)) return;
     if (tid < DH) {
       M = -1e30f, Lsum = 0.f, A = 0.f;
-      for (int s2 = 0; s2 < live_splits; ++s2) M = fmaxf(M, part[(size_t)s2 * (DH + 4) + DH]);
+      for (int s2 = 0; s2 < live_splits; ++s2) M = fmaxf(M, ld_dev(part + (size_t)s2 * (DH + 4) + DH));
       for (int s2 = 0; s2 < live_splits; ++s2) {
         const float *p = part + (size_t)s2 * (DH + 4);
-        const float f = __expf(p[DH] - M);
-        Lsum += p[DH + 1] * f;
-        A += p[tid] * f;
+        const float f = __expf(ld_dev(p + DH) - M);
+        Lsum += ld_dev(p + DH + 1) * f;
+        A += ld_dev(p + tid) * f;
       }
     }
   }

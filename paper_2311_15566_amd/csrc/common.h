@@ -82,6 +82,41 @@ __host__ __device__ inline size_t frag_offset(int row, int k, int k_blocks) {
   return frag * (64 * PL) + lane * PL + (kk % PL);
 }
 
+// ---------------------------------------------------------------------------
+// Cross-block hand-off inside one kernel without whole-cache write-backs.  Each XCD has its
+// own L2, so data one block leaves for another goes through device-scope (write-through /
+// read-around) accesses; the writer waits for its stores to complete, the block then bumps a
+// device-scope counter, and whoever sees the final count reads with device-scope loads.
+// ---------------------------------------------------------------------------
+#ifdef __HIPCC__
+__device__ __forceinline__ void st_dev(float *p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_dev(int *p, int v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_dev(const float *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int ld_dev(const int *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Called by every thread of the block after its st_dev stores.  Returns true in every thread
+// of the one block that arrives last of `expected`; that block also re-arms the counter.
+__device__ __forceinline__ bool arrive_last(int *counter, int expected, int *s_flag) {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int last = old == expected - 1;
+    if (last) st_dev(counter, 0);
+    *s_flag = last;
+  }
+  __syncthreads();
+  return *s_flag != 0;
+}
+#endif
+
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
 

@@ -149,6 +149,36 @@ static ss_status lm_head(Shard *const *group, int n_group, int B, float *xd, flo
 }
 
 // ---------------------------------------------------------------------------
+// optional event bracket around one launch (measurement aid)
+// ---------------------------------------------------------------------------
+struct Bracket {
+  Shard *sh;
+  hipStream_t st;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  int cls;
+  static hipEvent_t get(Shard *sh) {
+    if (!sh->free_events.empty()) {
+      hipEvent_t e = sh->free_events.back();
+      sh->free_events.pop_back();
+      return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
+  Bracket(Shard *s, int c, hipStream_t stream) : sh(s), st(stream), cls(c) {
+    if (!sh->timing) return;
+    e0 = get(sh), e1 = get(sh);
+    if (e0) (void)hipEventRecord(e0, st);
+  }
+  ~Bracket() {
+    if (!sh->timing || !e0 || !e1) return;
+    (void)hipEventRecord(e1, st);
+    sh->timed.push_back({cls, e0, e1});
+  }
+};
+
+// ---------------------------------------------------------------------------
 // one decode step, kernel by kernel
 // ---------------------------------------------------------------------------
 static ss_status enqueue_decode(Shard *const *group, int n_group, const int32_t *tokens_in, int B, float *logits,
@@ -162,13 +192,16 @@ static ss_status enqueue_decode(Shard *const *group, int n_group, const int32_t 
   float *xd = (float *)(g0->ws + L0.ws_y);
   float *stats = (float *)(g0->ws + L0.ws_stats);
   float *stat_part = stats + 64;
-  if (dt == SS_DTYPE_BF16)
-    hipLaunchKernelGGL(embed_rows<bf16_t>, dim3(B), dim3(256), 0, st, tokens_in, (const bf16_t *)g0->wte,
-                       (const bf16_t *)g0->wpe, g0->d_len, 0, xd, stats, d, L0.V, rms, m.norm_eps);
-  else
-    hipLaunchKernelGGL(embed_rows<float>, dim3(B), dim3(256), 0, st, tokens_in, (const float *)g0->wte,
-                       (const float *)g0->wpe, g0->d_len, 0, xd, stats, d, L0.V, rms, m.norm_eps);
-  SS_HIP(hipGetLastError());
+  {
+    Bracket br(g0, 0, st);
+    if (dt == SS_DTYPE_BF16)
+      hipLaunchKernelGGL(embed_rows<bf16_t>, dim3(B), dim3(256), 0, st, tokens_in, (const bf16_t *)g0->wte,
+                         (const bf16_t *)g0->wpe, g0->d_len, 0, xd, stats, d, L0.V, rms, m.norm_eps);
+    else
+      hipLaunchKernelGGL(embed_rows<float>, dim3(B), dim3(256), 0, st, tokens_in, (const float *)g0->wte,
+                         (const float *)g0->wpe, g0->d_len, 0, xd, stats, d, L0.V, rms, m.norm_eps);
+    SS_HIP(hipGetLastError());
+  }
 
   for (int l = 0; l < L0.Ls; ++l) {
     const LayerDev &D0 = g0->layers[l];
@@ -181,6 +214,7 @@ static ss_status enqueue_decode(Shard *const *group, int n_group, const int32_t 
       a.x = xd, a.stats = stats, a.gamma = D0.ln1_g, a.beta = D0.ln1_b;
       a.splitk = (float *)(s->ws + L.ws_splitk), a.counters = (int *)(s->ws + L.ws_counters);
       a.bias = s->layers[l].bqkv, a.out_f32 = (float *)(s->ws + L.ws_qkv), a.ld_out = L.qkv_n;
+      Bracket br(g0, 1, st);
       SS_TRY(launch_skinny(dt, PRO_NORM, EPI_F32, a, st));
     }
     for (int i = 0; i < n_group; ++i) {  // attention over the committed rows + append
@@ -196,6 +230,7 @@ static ss_status enqueue_decode(Shard *const *group, int n_group, const int32_t 
       a.o_out = s->ws + L.ws_o;
       a.B = B, a.Hs = L.Hs, a.Dh = L.Dh, a.Smax = L.Smax;
       attn_plan(L, B, &a.rows_per_block, &a.splits);
+      Bracket br(g0, 2, st);
       SS_TRY(launch_decode_attn(dt, a, st));
     }
     for (int i = 0; i < n_group; ++i) {  // output projection, sum over the group, residual
@@ -208,6 +243,7 @@ static ss_status enqueue_decode(Shard *const *group, int n_group, const int32_t 
       a.splitk = (float *)(s->ws + L.ws_splitk), a.counters = (int *)(s->ws + L.ws_counters);
       a.bias = i == 0 ? D0.bo : nullptr;
       a.x_resid = xd, a.stat_part = stat_part, a.stats_out = stats, a.rms = rms, a.eps = m.norm_eps;
+      Bracket br(g0, 3, st);
       SS_TRY(launch_skinny(dt, PRO_ACT, EPI_RESID, a, st));
     }
     for (int i = 0; i < n_group; ++i) {  // first FFN matrix + activation
@@ -220,6 +256,7 @@ static ss_status enqueue_decode(Shard *const *group, int n_group, const int32_t 
       a.x = xd, a.stats = stats, a.gamma = D0.ln2_g, a.beta = D0.ln2_b;
       a.splitk = (float *)(s->ws + L.ws_splitk), a.counters = (int *)(s->ws + L.ws_counters);
       a.bias = s->layers[l].b1, a.act_out = s->ws + L.ws_u, a.out_k_blocks = L.Fs / FK, a.act_kind = m.act;
+      Bracket br(g0, 4, st);
       SS_TRY(launch_skinny(dt, PRO_NORM, glu ? EPI_SWIGLU : EPI_ACT, a, st));
     }
     for (int i = 0; i < n_group; ++i) {  // second FFN matrix, sum over the group, residual
@@ -232,16 +269,22 @@ static ss_status enqueue_decode(Shard *const *group, int n_group, const int32_t 
       a.splitk = (float *)(s->ws + L.ws_splitk), a.counters = (int *)(s->ws + L.ws_counters);
       a.bias = i == 0 ? D0.b2 : nullptr;
       a.x_resid = xd, a.stat_part = stat_part, a.stats_out = stats, a.rms = rms, a.eps = m.norm_eps;
+      Bracket br(g0, 3, st);
       SS_TRY(launch_skinny(dt, PRO_ACT, EPI_RESID, a, st));
     }
     if (l == stop_after_layer) SS_FAIL(SS_EINTR, "decode step interrupted after layer %d; nothing committed", l);
   }
+  Bracket br(g0, 5, st);
   return lm_head(group, n_group, B, xd, stats, logits, next_tokens, 1, st);
 }
 
 void destroy_graphs(Shard *sh) {
   for (auto &kv : sh->graphs) (void)hipGraphExecDestroy(kv.second);
   sh->graphs.clear();
+  for (auto &t : sh->timed) (void)hipEventDestroy(t.e0), (void)hipEventDestroy(t.e1);
+  sh->timed.clear();
+  for (auto e : sh->free_events) (void)hipEventDestroy(e);
+  sh->free_events.clear();
 }
 
 ss_status run_decode_step(Shard *const *group, int n_group, const int32_t *tokens_in, int B, float *logits,
@@ -250,7 +293,8 @@ ss_status run_decode_step(Shard *const *group, int n_group, const int32_t *token
   // the NULL stream cannot be captured, and a stream the caller is capturing is left to the caller
   hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
   if (st) SS_HIP(hipStreamIsCapturing(st, &cs));
-  const bool graph = g0->use_graph && stop_after_layer < 0 && st != nullptr && cs == hipStreamCaptureStatusNone;
+  const bool graph = g0->use_graph && !g0->timing && stop_after_layer < 0 && st != nullptr &&
+                     cs == hipStreamCaptureStatusNone;
   if (!graph) return enqueue_decode(group, n_group, tokens_in, B, logits, next_tokens, st, stop_after_layer);
   GraphKey key;
   key.B = B;
@@ -387,6 +431,27 @@ ss_status ss_prefill(ss_shard *const *group_, int32_t n_group, const int32_t *to
   SS_TRY(run_prefill(group, n_group, tokens, B, S_in, logits, next_tokens, (hipStream_t)hip_stream));
   for (int i = 0; i < n_group; ++i)
     for (int b = 0; b < B; ++b) group[i]->h_len[b] = S_in;
+  return SS_OK;
+}
+
+ss_status ss_kernel_timing(ss_shard *shard, int32_t enabled) {
+  if (!shard) SS_FAIL(SS_EINVAL, "NULL shard");
+  ((Shard *)shard)->timing = enabled != 0;
+  return SS_OK;
+}
+
+ss_status ss_kernel_timing_read(ss_shard *shard, double ms[8], int64_t count[8], void *hip_stream) {
+  if (!shard || !ms || !count) SS_FAIL(SS_EINVAL, "NULL argument");
+  Shard *sh = (Shard *)shard;
+  SS_HIP(hipStreamSynchronize((hipStream_t)hip_stream));
+  for (int i = 0; i < 8; ++i) ms[i] = 0.0, count[i] = 0;
+  for (auto &t : sh->timed) {
+    float f = 0.f;
+    if (hipEventElapsedTime(&f, t.e0, t.e1) == hipSuccess && t.cls >= 0 && t.cls < 8) ms[t.cls] += f, count[t.cls] += 1;
+    sh->free_events.push_back(t.e0);
+    sh->free_events.push_back(t.e1);
+  }
+  sh->timed.clear();
   return SS_OK;
 }
 

@@ -4,6 +4,7 @@
 
 #include <limits.h>
 #include <math.h>
+#include <stdlib.h>
 
 #include <algorithm>
 
@@ -46,12 +47,16 @@ __device__ __forceinline__ void store4_frag(void *base, int row, int k, int k_bl
 }
 
 // ---------------------------------------------------------------------------
-// skinny GEMM
+// skinny GEMM.  grid = (groups of 4 wave tasks, K splits); block = 4 waves.
+// A wave owns one 16-row weight tile (SwiGLU: a gate/up tile pair) over the block's K range
+// and streams it in register batches of U fragments, two batches in flight (the first is
+// requested before the block stages its activations).  The activations of the K range are
+// staged once per block in LDS, normalised on the way in for the norm prologue.
 // ---------------------------------------------------------------------------
 template <typename T, int NB, int NW, int PRO, int EPI>
 __global__ void __launch_bounds__(256) skinny_gemm(SkinnyArgs a) {
   constexpr int PL = Elem<T>::kPerLane, FK = Elem<T>::kFragK;
-  constexpr int U = 4;
+  constexpr int U = NW == 1 ? 8 : 4;
   extern __shared__ __align__(16) char smem[];  // [NB][lds_chunk] fragments of the activations
   __shared__ float red_f[4][32][2];
   __shared__ int red_i[4][32];
@@ -62,7 +67,7 @@ __global__ void __launch_bounds__(256) skinny_gemm(SkinnyArgs a) {
   const int task = group * 4 + wave;
   const bool live = task < a.tasks;
   const int kb0 = sp * a.kb_per_split;
-  const int kb1 = min(kb0 + a.kb_per_split, a.k_blocks);
+  const int nk = min(a.kb_per_split, a.k_blocks - kb0);  // fragments along K for this block
   const int K = a.k_blocks * FK;
 
   f32x4 acc[NB][NW];
@@ -71,68 +76,70 @@ __global__ void __launch_bounds__(256) skinny_gemm(SkinnyArgs a) {
 #pragma unroll
     for (int j = 0; j < NW; ++j) acc[t][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  const u32x4 *wbase = (const u32x4 *)a.w + (size_t)task * NW * a.k_blocks * 64 + lane;
+  const u32x4 *wbase = (const u32x4 *)a.w + ((size_t)task * NW * a.k_blocks + kb0) * 64 + lane;
+  auto load_batch = [&](u32x4(&buf)[NW][U], int kb) {
+#pragma unroll
+    for (int j = 0; j < NW; ++j)
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        buf[j][u] = (live && kb + u < nk) ? __builtin_nontemporal_load(wbase + ((size_t)j * a.k_blocks + kb + u) * 64)
+                                          : u32x4{0u, 0u, 0u, 0u};
+  };
+  auto compute = [&](u32x4(&buf)[NW][U], int kb, int nkb) {  // kb relative to the staged chunk
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (kb + u < nkb) {
+#pragma unroll
+        for (int t = 0; t < NB; ++t) {
+          const u32x4 af = lds[(t * a.lds_chunk + kb + u) * 64 + lane];
+#pragma unroll
+          for (int j = 0; j < NW; ++j) acc[t][j] = Mma<T>::mma(buf[j][u], af, acc[t][j]);
+        }
+      }
+  };
 
-  for (int c0 = kb0; c0 < kb1; c0 += a.lds_chunk) {
-    const int nkb = min(a.lds_chunk, kb1 - c0);
-    __syncthreads();
+  u32x4 cur[NW][U], nxt[NW][U];
+  load_batch(cur, 0);
+
+  for (int c0 = 0; c0 < nk; c0 += a.lds_chunk) {  // lds_chunk is a multiple of 2U when it is < nk
+    const int nkb = min(a.lds_chunk, nk - c0);
+    if (c0) __syncthreads();
     if (PRO == PRO_ACT) {
       const u32x4 *src = (const u32x4 *)a.act;
       const int per = nkb * 64;
       for (int i = tid; i < NB * per; i += 256) {
-        int t = i / per, r = i - t * per;
-        lds[t * a.lds_chunk * 64 + r] = src[((size_t)t * a.k_blocks + c0) * 64 + r];
+        const int t = i / per, r = i - t * per;
+        lds[t * a.lds_chunk * 64 + r] = src[((size_t)t * a.k_blocks + kb0 + c0) * 64 + r];
       }
     } else {
       const int ppr = nkb * 4;  // 16-byte pieces per row in this chunk
-      for (int i = tid; i < NB * 16 * ppr; i += 256) {
-        int row = i / ppr, p = i - row * ppr;
-        if (row < a.B) {
-          const int k0 = c0 * FK + p * PL;
-          const float mean = a.stats[row * 2], rstd = a.stats[row * 2 + 1];
-          const float *xr = a.x + (size_t)row * K + k0;
-          T v[PL];
+      for (int i = tid; i < a.B * ppr; i += 256) {
+        const int row = i / ppr, p = i - row * ppr;
+        const int k0 = (kb0 + c0) * FK + p * PL;
+        const float mean = a.stats[row * 2], rstd = a.stats[row * 2 + 1];
+        const f32x4 *xp = (const f32x4 *)(a.x + (size_t)row * K + k0);
+        const f32x4 *gp = (const f32x4 *)(a.gamma + k0);
+        const f32x4 *bp = (const f32x4 *)(a.beta + k0);
+        T v[PL];
 #pragma unroll
-          for (int e = 0; e < PL; ++e) {
-            float y = (xr[e] - mean) * rstd * a.gamma[k0 + e];
-            if (a.beta) y += a.beta[k0 + e];
-            v[e] = Elem<T>::from_f32(y);
-          }
-          const int kbl = p >> 2, kq = p & 3;
-          T *dst = (T *)(lds + ((row >> 4) * a.lds_chunk + kbl) * 64 + kq * 16 + (row & 15));
+        for (int q = 0; q < PL / 4; ++q) {
+          const f32x4 xv = xp[q], gv = gp[q];
+          f32x4 y = (xv - mean) * rstd * gv;
+          if (a.beta) y += bp[q];
 #pragma unroll
-          for (int e = 0; e < PL; ++e) dst[e] = v[e];
+          for (int e = 0; e < 4; ++e) v[q * 4 + e] = Elem<T>::from_f32(y[e]);
         }
+        u32x4 packed;
+        __builtin_memcpy(&packed, v, 16);
+        lds[((row >> 4) * a.lds_chunk + (p >> 2)) * 64 + (p & 3) * 16 + (row & 15)] = packed;
       }
     }
     __syncthreads();
-    if (live) {
-      const u32x4 *wp = wbase + (size_t)c0 * 64;
-      int kb = 0;
-      for (; kb + U <= nkb; kb += U) {
-        u32x4 wf[NW][U];
-#pragma unroll
-        for (int j = 0; j < NW; ++j)
-#pragma unroll
-          for (int u = 0; u < U; ++u)
-            wf[j][u] = __builtin_nontemporal_load(wp + ((size_t)j * a.k_blocks + kb + u) * 64);
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-          for (int t = 0; t < NB; ++t) {
-            u32x4 af = lds[(t * a.lds_chunk + kb + u) * 64 + lane];
-#pragma unroll
-            for (int j = 0; j < NW; ++j) acc[t][j] = Mma<T>::mma(wf[j][u], af, acc[t][j]);
-          }
-      }
-      for (; kb < nkb; ++kb) {
-#pragma unroll
-        for (int j = 0; j < NW; ++j) {
-          u32x4 wf = __builtin_nontemporal_load(wp + ((size_t)j * a.k_blocks + kb) * 64);
-#pragma unroll
-          for (int t = 0; t < NB; ++t) acc[t][j] = Mma<T>::mma(wf, lds[(t * a.lds_chunk + kb) * 64 + lane], acc[t][j]);
-        }
-      }
+    for (int kb = 0; kb < nkb; kb += 2 * U) {
+      load_batch(nxt, c0 + kb + U);
+      compute(cur, kb, nkb);
+      load_batch(cur, c0 + kb + 2 * U);
+      compute(nxt, kb + U, nkb);
     }
   }
 
@@ -145,32 +152,43 @@ __global__ void __launch_bounds__(256) skinny_gemm(SkinnyArgs a) {
     if (live) {
 #pragma unroll
       for (int t = 0; t < NB; ++t)
+        if (t * 16 + bl < a.B) {
 #pragma unroll
-        for (int j = 0; j < NW; ++j)
-          *(f32x4 *)(a.splitk + ((size_t)sp * NB * 16 + t * 16 + bl) * npad + (size_t)(task * NW + j) * 16 + q4) =
-              acc[t][j];
+          for (int j = 0; j < NW; ++j) {
+            float *p = a.splitk + ((size_t)sp * NB * 16 + t * 16 + bl) * npad + (size_t)(task * NW + j) * 16 + q4;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) st_dev(p + i, acc[t][j][i]);
+          }
+        }
     }
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-      int old = atomicAdd(&a.counters[group], 1);
-      int last = old == a.split - 1;
-      if (last) a.counters[group] = 0;  // ready for the next launch
-      s_flag = last;
-    }
-    __syncthreads();
-    if (!s_flag) return;
-    __threadfence();
+    if (!arrive_last(&a.counters[group], a.split, &s_flag)) return;
     if (live) {
 #pragma unroll
       for (int t = 0; t < NB; ++t)
+        if (t * 16 + bl < a.B) {
 #pragma unroll
-        for (int j = 0; j < NW; ++j) {
-          f32x4 sum = f32x4{0.f, 0.f, 0.f, 0.f};
-          for (int s2 = 0; s2 < a.split; ++s2)
-            sum += *(const f32x4 *)(a.splitk + ((size_t)s2 * NB * 16 + t * 16 + bl) * npad +
-                                    (size_t)(task * NW + j) * 16 + q4);
-          acc[t][j] = sum;
+          for (int j = 0; j < NW; ++j) {
+            // partials are summed in split order; loads are issued four splits at a time
+            f32x4 sum = f32x4{0.f, 0.f, 0.f, 0.f};
+            const float *p0 = a.splitk + ((size_t)t * 16 + bl) * npad + (size_t)(task * NW + j) * 16 + q4;
+            const size_t sstride = (size_t)NB * 16 * npad;
+            int s2 = 0;
+            for (; s2 + 4 <= a.split; s2 += 4) {
+              float v[4][4];
+#pragma unroll
+              for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[r][i] = ld_dev(p0 + (size_t)(s2 + r) * sstride + i);
+#pragma unroll
+              for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) sum[i] += v[r][i];
+            }
+            for (; s2 < a.split; ++s2)
+#pragma unroll
+              for (int i = 0; i < 4; ++i) sum[i] += ld_dev(p0 + (size_t)s2 * sstride + i);
+            acc[t][j] = sum;
+          }
         }
     }
   }
@@ -243,37 +261,41 @@ __global__ void __launch_bounds__(256) skinny_gemm(SkinnyArgs a) {
       float p1 = 0.f, p2 = 0.f;
 #pragma unroll
       for (int w = 0; w < 4; ++w) p1 += red_f[w][tid][0], p2 += red_f[w][tid][1];
-      a.stat_part[((size_t)group * 32 + tid) * 2 + 0] = p1;
-      a.stat_part[((size_t)group * 32 + tid) * 2 + 1] = p2;
+      st_dev(&a.stat_part[((size_t)group * 32 + tid) * 2 + 0], p1);
+      st_dev(&a.stat_part[((size_t)group * 32 + tid) * 2 + 1], p2);
     }
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-      int old = atomicAdd(&a.counters[gridDim.x], 1);
-      int last = old == (int)gridDim.x - 1;
-      if (last) a.counters[gridDim.x] = 0;
-      s_flag = last;
-    }
-    __syncthreads();
-    if (!s_flag) return;
-    __threadfence();
-    if (tid < a.B) {
+    if (!arrive_last(&a.counters[gridDim.x], (int)gridDim.x, &s_flag)) return;
+    {
+      // thread (slice = tid / 32, b = tid % 32) sums groups slice, slice + 8, ... in order; the 8
+      // slices are then added in order, so the result does not depend on scheduling
+      const int b = tid & 31, slice = tid >> 5;
       float t1 = 0.f, t2 = 0.f;
-      for (int g = 0; g < (int)gridDim.x; ++g) {
-        t1 += a.stat_part[((size_t)g * 32 + tid) * 2 + 0];
-        t2 += a.stat_part[((size_t)g * 32 + tid) * 2 + 1];
+      if (b < a.B) {
+#pragma unroll 4
+        for (int g = slice; g < (int)gridDim.x; g += 8) {
+          t1 += ld_dev(&a.stat_part[((size_t)g * 32 + b) * 2 + 0]);
+          t2 += ld_dev(&a.stat_part[((size_t)g * 32 + b) * 2 + 1]);
+        }
       }
-      const float inv = 1.0f / (float)a.N;
-      float mean = t1 * inv, ms = t2 * inv;
-      float rstd;
-      if (a.rms) {
-        rstd = rsqrtf(ms + a.eps);
-        mean = 0.f;
-      } else {
-        rstd = rsqrtf(fmaxf(ms - mean * mean, 0.f) + a.eps);
+      __shared__ float fin[8][32][2];
+      fin[slice][b][0] = t1, fin[slice][b][1] = t2;
+      __syncthreads();
+      if (tid < a.B) {
+        float u1 = 0.f, u2 = 0.f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) u1 += fin[q][tid][0], u2 += fin[q][tid][1];
+        const float inv = 1.0f / (float)a.N;
+        float mean = u1 * inv, ms = u2 * inv;
+        float rstd;
+        if (a.rms) {
+          rstd = rsqrtf(ms + a.eps);
+          mean = 0.f;
+        } else {
+          rstd = rsqrtf(fmaxf(ms - mean * mean, 0.f) + a.eps);
+        }
+        a.stats_out[tid * 2 + 0] = mean;
+        a.stats_out[tid * 2 + 1] = rstd;
       }
-      a.stats_out[tid * 2 + 0] = mean;
-      a.stats_out[tid * 2 + 1] = rstd;
     }
     return;
   }
@@ -312,47 +334,63 @@ __global__ void __launch_bounds__(256) skinny_gemm(SkinnyArgs a) {
         int oi = red_i[w][tid];
         if (ov > bv || (ov == bv && oi < bi)) bv = ov, bi = oi;
       }
-      a.am_val[(size_t)group * 32 + tid] = bv;
-      a.am_idx[(size_t)group * 32 + tid] = bi;
+      st_dev(&a.am_val[(size_t)group * 32 + tid], bv);
+      st_dev(&a.am_idx[(size_t)group * 32 + tid], bi);
     }
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-      int old = atomicAdd(&a.counters[gridDim.x], 1);
-      int last = old == (int)gridDim.x - 1;
-      if (last) a.counters[gridDim.x] = 0;
-      s_flag = last;
-    }
-    __syncthreads();
-    if (!s_flag) return;
-    __threadfence();
-    if (tid < a.B) {
+    if (!arrive_last(&a.counters[gridDim.x], (int)gridDim.x, &s_flag)) return;
+    {
+      // thread (slice = tid / 32, b = tid % 32) scans groups slice, slice + 8, ...; ties go to the
+      // lowest index whatever the order, so the merge over slices is order-independent
+      const int b = tid & 31, slice = tid >> 5;
       float bv = -INFINITY;
       int bi = INT_MAX;
-      for (int g = 0; g < (int)gridDim.x; ++g) {
-        float ov = a.am_val[(size_t)g * 32 + tid];
-        int oi = a.am_idx[(size_t)g * 32 + tid];
-        if (ov > bv || (ov == bv && oi < bi)) bv = ov, bi = oi;
+      if (b < a.B) {
+#pragma unroll 4
+        for (int g = slice; g < (int)gridDim.x; g += 8) {
+          const float ov = ld_dev(&a.am_val[(size_t)g * 32 + b]);
+          const int oi = ld_dev(&a.am_idx[(size_t)g * 32 + b]);
+          if (ov > bv || (ov == bv && oi < bi)) bv = ov, bi = oi;
+        }
       }
-      if (a.next_tokens) a.next_tokens[tid] = bi;
-      // token-level commit: the last action of the step
-      for (int q = 0; q < a.n_lens; ++q) a.lens[q][tid] += a.commit_inc;
+      __shared__ float fin_v[8][32];
+      __shared__ int fin_i[8][32];
+      fin_v[slice][b] = bv, fin_i[slice][b] = bi;
+      __syncthreads();
+      if (tid < a.B) {
+        bv = fin_v[0][tid], bi = fin_i[0][tid];
+#pragma unroll
+        for (int q = 1; q < 8; ++q) {
+          const float ov = fin_v[q][tid];
+          const int oi = fin_i[q][tid];
+          if (ov > bv || (ov == bv && oi < bi)) bv = ov, bi = oi;
+        }
+        if (a.next_tokens) a.next_tokens[tid] = bi;
+        // token-level commit: the last action of the step
+        for (int q = 0; q < a.n_lens; ++q) a.lens[q][tid] += a.commit_inc;
+      }
     }
     return;
   }
+}
+
+static int env_int(const char *name, int dflt) {
+  const char *v = getenv(name);
+  return v && *v ? atoi(v) : dflt;
 }
 
 void plan_skinny(SkinnyArgs *a, int esz, size_t splitk_bytes, int nw) {
   (void)esz;
   a->nb = a->B <= 16 ? 1 : 2;
   const int groups = ceil_div(a->tasks, 4);
-  const int max_chunk = 32 / a->nb;  // 32 KiB of LDS per block
-  int split = std::max(1, std::min(1024 / std::max(groups, 1), a->k_blocks / 4));
+  static const int target_blocks = env_int("SS_SKINNY_BLOCKS", 512);  // about 2 blocks per compute unit
+  static const int lds_kb = env_int("SS_SKINNY_LDS_KB", 32);
+  const int max_chunk = std::max(16, lds_kb / a->nb / 16 * 16);        // fragments staged at a time, multiple of 16
+  int split = std::max(1, std::min(target_blocks / std::max(groups, 1), a->k_blocks / 4));
   const size_t per_split = (size_t)a->nb * 16 * a->tasks * nw * 16 * 4;
   while (split > 1 && per_split * split > splitk_bytes) --split;
   a->kb_per_split = ceil_div(a->k_blocks, split);
   a->split = ceil_div(a->k_blocks, a->kb_per_split);
-  a->lds_chunk = std::min(a->kb_per_split, max_chunk);
+  a->lds_chunk = a->kb_per_split <= max_chunk ? a->kb_per_split : max_chunk;
 }
 
 template <typename T, int NB>
@@ -372,7 +410,8 @@ ss_status launch_skinny(int dtype, int pro, int epi, const SkinnyArgs &a, hipStr
   if (!ok_combo) SS_FAIL(SS_EINVAL, "skinny GEMM: unsupported prologue/epilogue pair %d/%d", pro, epi);
   if (a.B < 1 || a.B > 32 || a.nb != (a.B <= 16 ? 1 : 2)) SS_FAIL(SS_EINVAL, "skinny GEMM: batch %d / tiles %d", a.B, a.nb);
   if (a.tasks < 1 || a.k_blocks < 1 || a.split < 1 || a.kb_per_split < 1 || a.lds_chunk < 1 ||
-      (size_t)a.split * a.kb_per_split < (size_t)a.k_blocks || a.lds_chunk * a.nb > 64)
+      (size_t)a.split * a.kb_per_split < (size_t)a.k_blocks || a.lds_chunk * a.nb > 64 ||
+      (a.lds_chunk < a.kb_per_split && a.lds_chunk % 16))
     SS_FAIL(SS_EINVAL, "skinny GEMM: inconsistent plan");
   const int groups = ceil_div(a.tasks, 4);
   dim3 grid(groups, a.split);

@@ -65,6 +65,11 @@ struct Shard {
   int interrupt_after = -1;
   bool use_graph = true;
   std::map<GraphKey, hipGraphExec_t> graphs;
+  // per-kernel-class event timing (measurement aid)
+  bool timing = false;
+  struct TimedLaunch { int cls; hipEvent_t e0, e1; };
+  std::vector<TimedLaunch> timed;
+  std::vector<hipEvent_t> free_events;
 
   size_t kv_head_stride() const { return (size_t)L.Smax * L.Dh * L.esz; }  // bytes between heads
   size_t kv_row_stride() const { return kv_head_stride() * L.Hs; }          // between batch rows
