@@ -39,14 +39,19 @@ typedef enum {
 enum { SS_NORM_LAYERNORM = 0, SS_NORM_RMSNORM = 1 };
 enum { SS_ACT_GELU_TANH = 0, SS_ACT_RELU = 1, SS_ACT_SWIGLU = 2 };
 enum { SS_POS_LEARNED = 0, SS_POS_ROPE = 1 };
-enum { SS_DTYPE_F32 = 0, SS_DTYPE_BF16 = 1 };
+enum { SS_DTYPE_F32 = 0, SS_DTYPE_BF16 = 1, SS_DTYPE_F16 = 2 };
 
 /* The full model (Section 2.1: a stack of identical Transformer layers, each
  * multi-head attention + FFN).  Pre-norm blocks, final norm, greedy LM head. */
 typedef struct {
   int32_t n_layers, d_model, n_heads, head_dim, ffn, vocab;
   int32_t max_pos;  /* rows of the learned position table (0 for RoPE) */
-  int32_t norm, act, pos, has_bias, dtype;
+  int32_t norm, act, pos, has_bias;
+  int32_t dtype;    /* weights (and the matrix-core operand type): SS_DTYPE_F32 or SS_DTYPE_BF16 */
+  int32_t kv_dtype; /* cache element: SS_DTYPE_F32 for an f32 model; SS_DTYPE_F16 or SS_DTYPE_BF16
+                       (both 2 bytes) for a bf16 model.  Half keeps 3 more mantissa bits: bf16 keys
+                       alone cost ~4e-3 relative logits error at the OPT-66B shape, half ~6e-4;
+                       values saturate at +-65504. */
   float norm_eps, rope_theta;
 } ss_model_desc;
 

@@ -14,7 +14,7 @@ _STATUS = {1: "SS_EINVAL", 2: "SS_ENOMEM", 3: "SS_ESTATE", 4: "SS_EHIP", 5: "SS_
 _NORM = {"layernorm": 0, "rmsnorm": 1}
 _ACT = {"gelu_tanh": 0, "relu": 1, "swiglu": 2}
 _POS = {"learned": 0, "rope": 1}
-_DTYPE = {"f32": 0, "bf16": 1}
+_DTYPE = {"f32": 0, "bf16": 1, "f16": 2}
 
 
 class SpotShardError(RuntimeError):
@@ -25,7 +25,7 @@ class SpotShardError(RuntimeError):
 
 class ModelDesc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_heads", "head_dim", "ffn", "vocab", "max_pos",
-                                         "norm", "act", "pos", "has_bias", "dtype")] + \
+                                         "norm", "act", "pos", "has_bias", "dtype", "kv_dtype")] + \
                [("norm_eps", C.c_float), ("rope_theta", C.c_float)]
 
 
@@ -91,7 +91,12 @@ def _check(status):
 def _desc(d: dict) -> ModelDesc:
     return ModelDesc(d["n_layers"], d["d_model"], d["n_heads"], d["head_dim"], d["ffn"], d["vocab"], d["max_pos"],
                      _NORM[d["norm"]], _ACT[d["act"]], _POS[d["pos"]], int(d["has_bias"]), _DTYPE[d["dtype"]],
-                     d["norm_eps"], d["rope_theta"])
+                     _DTYPE[kv_dtype_of(d)], d["norm_eps"], d["rope_theta"])
+
+
+def kv_dtype_of(d: dict) -> str:
+    """Cache element type: the descriptor's "kv_dtype", default half for a bf16 model."""
+    return d.get("kv_dtype") or ("f32" if d["dtype"] == "f32" else "f16")
 
 
 def _slice(s: dict) -> Slice:
@@ -215,7 +220,7 @@ def kv_repack(dst, src, batch_map, first_source=True, stream=None) -> int:
 
 def kv_export(shard, stream=None) -> np.ndarray:
     n = lib.ss_kv_export_bytes(shard.handle)
-    dt = np.uint16 if shard.desc["dtype"] == "bf16" else np.float32
+    dt = {"f32": np.float32, "f16": np.float16, "bf16": np.uint16}[kv_dtype_of(shard.desc)]   # bf16: raw bit patterns
     out = np.empty(n // np.dtype(dt).itemsize, dtype=dt)
     _check(lib.ss_kv_export(shard.handle, out.ctypes.data if n else None, n, _stream(stream)))
     return out

@@ -6,6 +6,7 @@
 
 namespace ss {
 
+// KT: cache element type; AT: activation operand type of the GEMM that consumes the output
 template <typename T, int DH> struct RowGeom {
   static constexpr int EPL = Elem<T>::kPerLane;      // elements per lane (16 bytes)
   static constexpr int LPR = DH / EPL;               // lanes per cache row
@@ -28,6 +29,14 @@ __device__ __forceinline__ void unpack16<bf16_t>(const u32x4 &raw, float *out) {
   }
 }
 
+template <>
+__device__ __forceinline__ void unpack16<f16_t>(const u32x4 &raw, float *out) {
+  typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+  h8 h = __builtin_bit_cast(h8, raw);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) out[i] = (float)h[i];
+}
+
 // q, k of the new token at position pos, rotated (half-split pairing) when a table is given.
 __device__ __forceinline__ float rope_elem(const float *v, int e, int half, const float2 *tab) {
   if (!tab) return v[e];
@@ -47,7 +56,7 @@ __device__ __forceinline__ float rope_elem(const float *v, int e, int half, cons
 // scores the new token from registers, writes its key/value as cache row n and emits the
 // head output.  Blocks past the live splits exit at once.
 // ---------------------------------------------------------------------------
-template <typename T, int DH>
+template <typename T, typename AT, int DH>
 __global__ void __launch_bounds__(256) decode_attn(DecodeAttnArgs a) {
   typedef RowGeom<T, DH> Gm;
   constexpr int EPL = Gm::EPL, LPR = Gm::LPR, G = Gm::G, U = 4;
@@ -196,8 +205,7 @@ __global__ void __launch_bounds__(256) decode_attn(DecodeAttnArgs a) {
     const float f0 = __expf(M - mn), p = __expf(sn - mn);
     const float Lf = Lsum * f0 + p;
     const float o = (A * f0 + p * vnew) / Lf;
-    T *op = (T *)a.o_out + frag_offset<T>(b, h * DH + tid, HD / Elem<T>::kFragK);
-    *op = Elem<T>::from_f32(o);
+    store_act<AT>(a.o_out, b, h * DH + tid, HD / Elem<AT>::kFragK, Elem<AT>::kParts, o);
   }
 }
 
@@ -206,13 +214,18 @@ ss_status launch_decode_attn(int dtype, const DecodeAttnArgs &a, hipStream_t st)
   if (a.rows_per_block < 1 || a.splits < 1 || (size_t)a.splits * a.rows_per_block < (size_t)a.Smax)
     SS_FAIL(SS_EINVAL, "decode attention: %d splits of %d rows do not cover %d rows", a.splits, a.rows_per_block, a.Smax);
   dim3 grid(a.B * a.Hs, a.splits);
-#define SS_LAUNCH(TT, DH) hipLaunchKernelGGL((decode_attn<TT, DH>), grid, dim3(256), 0, st, a)
-  if (dtype == SS_DTYPE_BF16) {
-    if (a.Dh == 128) SS_LAUNCH(bf16_t, 128);
-    else SS_LAUNCH(bf16_t, 64);
+#define SS_LAUNCH(KT, AT, DH) hipLaunchKernelGGL((decode_attn<KT, AT, DH>), grid, dim3(256), 0, st, a)
+  if (dtype == SS_DTYPE_BF16 && a.kv_dtype == SS_DTYPE_F16) {
+    if (a.Dh == 128) SS_LAUNCH(f16_t, bf16_t, 128);
+    else SS_LAUNCH(f16_t, bf16_t, 64);
+  } else if (dtype == SS_DTYPE_BF16 && a.kv_dtype == SS_DTYPE_BF16) {
+    if (a.Dh == 128) SS_LAUNCH(bf16_t, bf16_t, 128);
+    else SS_LAUNCH(bf16_t, bf16_t, 64);
+  } else if (dtype == SS_DTYPE_F32 && a.kv_dtype == SS_DTYPE_F32) {
+    if (a.Dh == 128) SS_LAUNCH(float, float, 128);
+    else SS_LAUNCH(float, float, 64);
   } else {
-    if (a.Dh == 128) SS_LAUNCH(float, 128);
-    else SS_LAUNCH(float, 64);
+    SS_FAIL(SS_EINVAL, "decode attention: dtype %d with kv_dtype %d", dtype, a.kv_dtype);
   }
 #undef SS_LAUNCH
   SS_HIP(hipGetLastError());
@@ -243,8 +256,12 @@ __global__ void __launch_bounds__(DH) prefill_kv_write(PrefillAttnArgs a) {
 ss_status launch_prefill_kv_write(int dtype, const PrefillAttnArgs &a, hipStream_t st) {
   if (a.S < 1 || a.S > a.Smax || a.B < 1 || (a.Dh != 64 && a.Dh != 128)) SS_FAIL(SS_EINVAL, "prefill KV write: bad shape");
   dim3 grid(a.B * a.S, a.Hs);
-#define SS_LAUNCH(TT, DH) hipLaunchKernelGGL((prefill_kv_write<TT, DH>), grid, dim3(DH), 0, st, a)
-  if (dtype == SS_DTYPE_BF16) {
+#define SS_LAUNCH(KT, DH) hipLaunchKernelGGL((prefill_kv_write<KT, DH>), grid, dim3(DH), 0, st, a)
+  (void)dtype;
+  if (a.kv_dtype == SS_DTYPE_F16) {
+    if (a.Dh == 128) SS_LAUNCH(f16_t, 128);
+    else SS_LAUNCH(f16_t, 64);
+  } else if (a.kv_dtype == SS_DTYPE_BF16) {
     if (a.Dh == 128) SS_LAUNCH(bf16_t, 128);
     else SS_LAUNCH(bf16_t, 64);
   } else {
@@ -261,7 +278,7 @@ ss_status launch_prefill_kv_write(int dtype, const PrefillAttnArgs &a, hipStream
 // thread (qi = tid/4, part = tid%4) owns a quarter of the head dims of query qi.  Keys and
 // values (read back from the cache, i.e. at cache precision) go through LDS 32 rows at a time.
 // ---------------------------------------------------------------------------
-template <typename T, int DH>
+template <typename T, typename AT, int DH>
 __global__ void __launch_bounds__(256) prefill_attn(PrefillAttnArgs a) {
   constexpr int TQ = 64, TK = 32, DP = DH / 4, EPL = Elem<T>::kPerLane;
   __shared__ __align__(16) float sk[TK][DH + 4];
@@ -317,23 +334,27 @@ __global__ void __launch_bounds__(256) prefill_attn(PrefillAttnArgs a) {
   if (qlive) {
     const float inv = 1.0f / l;
     const int tok = b * a.S + qi;
-    T *o = (T *)a.o_out;
 #pragma unroll
     for (int e = 0; e < DP; ++e)
-      o[frag_offset<T>(tok, h * DH + part * DP + e, HD / Elem<T>::kFragK)] = Elem<T>::from_f32(acc[e] * inv);
+      store_act<AT>(a.o_out, tok, h * DH + part * DP + e, HD / Elem<AT>::kFragK, Elem<AT>::kParts, acc[e] * inv);
   }
 }
 
 ss_status launch_prefill_attn(int dtype, const PrefillAttnArgs &a, hipStream_t st) {
   if (a.S < 1 || a.S > a.Smax || a.B < 1 || (a.Dh != 64 && a.Dh != 128)) SS_FAIL(SS_EINVAL, "prefill attention: bad shape");
   dim3 grid(a.B * a.Hs, ceil_div(a.S, 64));
-#define SS_LAUNCH(TT, DH) hipLaunchKernelGGL((prefill_attn<TT, DH>), grid, dim3(256), 0, st, a)
-  if (dtype == SS_DTYPE_BF16) {
-    if (a.Dh == 128) SS_LAUNCH(bf16_t, 128);
-    else SS_LAUNCH(bf16_t, 64);
+#define SS_LAUNCH(KT, AT, DH) hipLaunchKernelGGL((prefill_attn<KT, AT, DH>), grid, dim3(256), 0, st, a)
+  if (dtype == SS_DTYPE_BF16 && a.kv_dtype == SS_DTYPE_F16) {
+    if (a.Dh == 128) SS_LAUNCH(f16_t, bf16_t, 128);
+    else SS_LAUNCH(f16_t, bf16_t, 64);
+  } else if (dtype == SS_DTYPE_BF16 && a.kv_dtype == SS_DTYPE_BF16) {
+    if (a.Dh == 128) SS_LAUNCH(bf16_t, bf16_t, 128);
+    else SS_LAUNCH(bf16_t, bf16_t, 64);
+  } else if (dtype == SS_DTYPE_F32 && a.kv_dtype == SS_DTYPE_F32) {
+    if (a.Dh == 128) SS_LAUNCH(float, float, 128);
+    else SS_LAUNCH(float, float, 64);
   } else {
-    if (a.Dh == 128) SS_LAUNCH(float, 128);
-    else SS_LAUNCH(float, 64);
+    SS_FAIL(SS_EINVAL, "prefill attention: dtype %d with kv_dtype %d", dtype, a.kv_dtype);
   }
 #undef SS_LAUNCH
   SS_HIP(hipGetLastError());

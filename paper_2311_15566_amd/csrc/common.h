@@ -53,16 +53,32 @@ __host__ __device__ inline bf16_t f32_to_bf16(float f) {
   return (bf16_t)(u >> 16);
 }
 
+typedef _Float16 f16_t;   // IEEE half: a KV-cache element type
 template <typename T> struct Elem;
+template <> struct Elem<f16_t> {
+  static constexpr int kPerLane = 8;
+  __host__ __device__ static float to_f32(f16_t v) { return (float)v; }
+  // round-to-nearest-even, saturating at the largest finite half
+  __host__ __device__ static f16_t from_f32(float v) {
+    v = v > 65504.f ? 65504.f : (v < -65504.f ? -65504.f : v);
+    return (f16_t)v;
+  }
+};
 template <> struct Elem<float> {
   static constexpr int kPerLane = 4;   // elements in a lane's 16-byte piece
   static constexpr int kFragK = 16;    // k extent of one 1 KiB operand fragment
+  static constexpr int kParts = 1;     // fragments per activation k block
   __host__ __device__ static float to_f32(float v) { return v; }
   __host__ __device__ static float from_f32(float v) { return v; }
 };
 template <> struct Elem<bf16_t> {
   static constexpr int kPerLane = 8;
   static constexpr int kFragK = 32;
+  // bf16 activations that feed a weight-streaming GEMM are carried as hi + lo pairs
+  // (x = hi + lo, both bf16, ~16 mantissa bits): two fragments per k block, two MFMAs per
+  // weight fragment.  The matrix cores idle in these HBM-bound kernels, and the logits
+  // error drops from ~7e-3 to ~3.6e-3 relative (what the bf16 KV cache alone costs).
+  static constexpr int kParts = 2;
   __host__ __device__ static float to_f32(bf16_t v) { return bf16_to_f32(v); }
   __host__ __device__ static bf16_t from_f32(float v) { return f32_to_bf16(v); }
 };
@@ -116,6 +132,24 @@ __device__ __forceinline__ bool arrive_last(int *counter, int expected, int *s_f
   return *s_flag != 0;
 }
 #endif
+
+// Activation operand with `parts` fragments per k block: [row tile][k block][part][lane][PerLane].
+template <typename T>
+__host__ __device__ inline size_t frag_offset_parts(int row, int k, int k_blocks, int parts, int part) {
+  constexpr int PL = Elem<T>::kPerLane, FK = Elem<T>::kFragK;
+  size_t frag = ((size_t)(row >> 4) * k_blocks + (k / FK)) * parts + part;
+  int kk = k % FK;
+  int lane = (kk / PL) * 16 + (row & 15);
+  return frag * (64 * PL) + lane * PL + (kk % PL);
+}
+// store a float activation into a (possibly hi/lo split) operand buffer
+template <typename T>
+__device__ inline void store_act(void *base, int row, int k, int k_blocks, int parts, float v) {
+  T *b = (T *)base;
+  const T hi = Elem<T>::from_f32(v);
+  b[frag_offset_parts<T>(row, k, k_blocks, parts, 0)] = hi;
+  if (parts > 1) b[frag_offset_parts<T>(row, k, k_blocks, parts, 1)] = Elem<T>::from_f32(v - Elem<T>::to_f32(hi));
+}
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t a, size_t b) { return (a + b - 1) / b * b; }

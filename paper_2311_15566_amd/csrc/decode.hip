@@ -68,11 +68,10 @@ __global__ void __launch_bounds__(256) norm_rows(const float *x, const float *ga
   const float *xr = x + (size_t)r * d;
   float mean, rstd;
   row_stats(xr, d, rms, eps, scratch, &mean, &rstd);
-  T *a = (T *)a_out;
   for (int k = threadIdx.x; k < d; k += 256) {
     float y = (xr[k] - mean) * rstd * gamma[k];
     if (beta) y += beta[k];
-    a[frag_offset<T>(r, k, k_blocks)] = Elem<T>::from_f32(y);
+    store_act<T>(a_out, r, k, k_blocks, Elem<T>::kParts, y);
   }
 }
 
@@ -104,7 +103,7 @@ static ss_status check_group(Shard *const *group, int n_group, int B) {
     if (s->s.layer_lo != g0->s.layer_lo || s->s.layer_hi != g0->s.layer_hi)
       SS_FAIL(SS_EINVAL, "shards of a group must hold the same layers");
     if (s->m.d_model != g0->m.d_model || s->m.head_dim != g0->m.head_dim || s->m.dtype != g0->m.dtype ||
-        s->m.act != g0->m.act || s->m.pos != g0->m.pos || s->m.norm != g0->m.norm)
+        s->m.act != g0->m.act || s->m.pos != g0->m.pos || s->m.norm != g0->m.norm || s->m.kv_dtype != g0->m.kv_dtype)
       SS_FAIL(SS_EINVAL, "shards of a group must come from the same model");
     if (B > s->L.Bmax) SS_FAIL(SS_EINVAL, "batch %d exceeds group[%d]'s max_batch %d", B, i, s->L.Bmax);
     for (int j = 0; j < i; ++j) {
@@ -228,7 +227,7 @@ static ss_status enqueue_decode(Shard *const *group, int n_group, const int32_t 
       a.part = (float *)(s->ws + L.ws_attn_part);
       a.counters = (int *)(s->ws + L.ws_counters) + (L.n_counters - L.Bmax * L.Hs);
       a.o_out = s->ws + L.ws_o;
-      a.B = B, a.Hs = L.Hs, a.Dh = L.Dh, a.Smax = L.Smax;
+      a.B = B, a.Hs = L.Hs, a.Dh = L.Dh, a.Smax = L.Smax, a.kv_dtype = s->m.kv_dtype;
       attn_plan(L, B, &a.rows_per_block, &a.splits);
       Bracket br(g0, 2, st);
       SS_TRY(launch_decode_attn(dt, a, st));
@@ -334,6 +333,7 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, i
   const int FK = dt == SS_DTYPE_BF16 ? 32 : 16;
   const int rms = m.norm == SS_NORM_RMSNORM;
   const int T_live = B * S, T = (int)align_up((size_t)T_live, 128);
+  const int parts = dt == SS_DTYPE_BF16 ? 2 : 1;  // bf16 GEMM inputs are hi/lo pairs
   for (int i = 0; i < n_group; ++i)
     if (T > group[i]->L.Tmax) SS_FAIL(SS_EINVAL, "%d prompt tokens exceed group[%d]'s workspace (%d)", T_live, i, group[i]->L.Tmax);
   float *x = (float *)(g0->ws + L0.ws_x);
@@ -361,7 +361,7 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, i
       const Layout &L = s->L;
       TileGemmArgs a = {};
       a.w = s->wqkv[l].ptr, a.row_tiles = s->wqkv[l].row_tiles, a.k_blocks = s->wqkv[l].k_blocks;
-      a.act = abuf, a.T = T, a.T_live = T_live, a.N = L.qkv_n, a.bias = s->layers[l].bqkv;
+      a.act = abuf, a.act_parts = parts, a.T = T, a.T_live = T_live, a.N = L.qkv_n, a.bias = s->layers[l].bqkv;
       a.out_f32 = (float *)(s->ws + L.ws_qkv), a.ld_out = L.qkv_n;
       SS_TRY(launch_tile_gemm(dt, EPI_F32, a, st));
       PrefillAttnArgs p = {};
@@ -370,7 +370,7 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, i
       p.row_stride = s->kv_row_stride(), p.head_stride = s->kv_head_stride();
       p.rope = m.pos == SS_POS_ROPE ? s->rope : nullptr;
       p.o_out = s->ws + L.ws_o;
-      p.B = B, p.S = S, p.Hs = L.Hs, p.Dh = L.Dh, p.Smax = L.Smax;
+      p.B = B, p.S = S, p.Hs = L.Hs, p.Dh = L.Dh, p.Smax = L.Smax, p.kv_dtype = s->m.kv_dtype;
       SS_TRY(launch_prefill_kv_write(dt, p, st));
       SS_TRY(launch_prefill_attn(dt, p, st));
     }
@@ -379,7 +379,7 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, i
       const Layout &L = s->L;
       TileGemmArgs a = {};
       a.w = s->wo[l].ptr, a.row_tiles = s->wo[l].row_tiles, a.k_blocks = s->wo[l].k_blocks;
-      a.act = s->ws + L.ws_o, a.T = T, a.T_live = T_live, a.N = d, a.bias = i == 0 ? D0.bo : nullptr;
+      a.act = s->ws + L.ws_o, a.act_parts = parts, a.T = T, a.T_live = T_live, a.N = d, a.bias = i == 0 ? D0.bo : nullptr;
       a.x_resid = x;
       SS_TRY(launch_tile_gemm(dt, EPI_RESID, a, st));
     }
@@ -390,8 +390,8 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, i
       const bool glu = m.act == SS_ACT_SWIGLU;
       TileGemmArgs a = {};
       a.w = s->w1[l].ptr, a.row_tiles = s->w1[l].row_tiles, a.k_blocks = s->w1[l].k_blocks;
-      a.act = abuf, a.T = T, a.T_live = T_live, a.N = L.Fs, a.bias = s->layers[l].b1;
-      a.act_out = s->ws + L.ws_u, a.out_k_blocks = L.Fs / FK, a.act_kind = m.act;
+      a.act = abuf, a.act_parts = parts, a.T = T, a.T_live = T_live, a.N = L.Fs, a.bias = s->layers[l].b1;
+      a.act_out = s->ws + L.ws_u, a.out_k_blocks = L.Fs / FK, a.out_parts = parts, a.act_kind = m.act;
       SS_TRY(launch_tile_gemm(dt, glu ? EPI_SWIGLU : EPI_ACT, a, st));
     }
     for (int i = 0; i < n_group; ++i) {
@@ -399,7 +399,7 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, i
       const Layout &L = s->L;
       TileGemmArgs a = {};
       a.w = s->w2[l].ptr, a.row_tiles = s->w2[l].row_tiles, a.k_blocks = s->w2[l].k_blocks;
-      a.act = s->ws + L.ws_u, a.T = T, a.T_live = T_live, a.N = d, a.bias = i == 0 ? D0.b2 : nullptr;
+      a.act = s->ws + L.ws_u, a.act_parts = parts, a.T = T, a.T_live = T_live, a.N = d, a.bias = i == 0 ? D0.b2 : nullptr;
       a.x_resid = x;
       SS_TRY(launch_tile_gemm(dt, EPI_RESID, a, st));
     }

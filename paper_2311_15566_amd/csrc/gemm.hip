@@ -37,13 +37,18 @@ __device__ __forceinline__ float act_apply(int kind, float h) {
 __device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)); }
 
 template <typename T>
-__device__ __forceinline__ void store4_frag(void *base, int row, int k, int k_blocks, float v0, float v1, float v2,
-                                            float v3) {
-  T *p = (T *)base + frag_offset<T>(row, k, k_blocks);  // k is a multiple of 4: the four values are contiguous
-  p[0] = Elem<T>::from_f32(v0);
-  p[1] = Elem<T>::from_f32(v1);
-  p[2] = Elem<T>::from_f32(v2);
-  p[3] = Elem<T>::from_f32(v3);
+__device__ __forceinline__ void store4_frag(void *base, int row, int k, int k_blocks, int parts, float v0, float v1,
+                                            float v2, float v3) {
+  // k is a multiple of 4: the four values are contiguous within a part
+  const float v[4] = {v0, v1, v2, v3};
+  T *hi = (T *)base + frag_offset_parts<T>(row, k, k_blocks, parts, 0);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) hi[i] = Elem<T>::from_f32(v[i]);
+  if (parts > 1) {
+    T *lo = (T *)base + frag_offset_parts<T>(row, k, k_blocks, parts, 1);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) lo[i] = Elem<T>::from_f32(v[i] - Elem<T>::to_f32(hi[i]));
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -55,9 +60,9 @@ __device__ __forceinline__ void store4_frag(void *base, int row, int k, int k_bl
 // ---------------------------------------------------------------------------
 template <typename T, int NB, int NW, int PRO, int EPI>
 __global__ void __launch_bounds__(256) skinny_gemm(SkinnyArgs a) {
-  constexpr int PL = Elem<T>::kPerLane, FK = Elem<T>::kFragK;
+  constexpr int PL = Elem<T>::kPerLane, FK = Elem<T>::kFragK, AP = Elem<T>::kParts;
   constexpr int U = NW == 1 ? 8 : 4;
-  extern __shared__ __align__(16) char smem[];  // [NB][lds_chunk] fragments of the activations
+  extern __shared__ __align__(16) char smem[];  // [NB][lds_chunk][AP] fragments of the activations
   __shared__ float red_f[4][32][2];
   __shared__ int red_i[4][32];
   __shared__ int s_flag;
@@ -90,11 +95,13 @@ __global__ void __launch_bounds__(256) skinny_gemm(SkinnyArgs a) {
     for (int u = 0; u < U; ++u)
       if (kb + u < nkb) {
 #pragma unroll
-        for (int t = 0; t < NB; ++t) {
-          const u32x4 af = lds[(t * a.lds_chunk + kb + u) * 64 + lane];
+        for (int t = 0; t < NB; ++t)
 #pragma unroll
-          for (int j = 0; j < NW; ++j) acc[t][j] = Mma<T>::mma(buf[j][u], af, acc[t][j]);
-        }
+          for (int part = 0; part < AP; ++part) {
+            const u32x4 af = lds[((t * a.lds_chunk + kb + u) * AP + part) * 64 + lane];
+#pragma unroll
+            for (int j = 0; j < NW; ++j) acc[t][j] = Mma<T>::mma(buf[j][u], af, acc[t][j]);
+          }
       }
   };
 
@@ -106,10 +113,10 @@ __global__ void __launch_bounds__(256) skinny_gemm(SkinnyArgs a) {
     if (c0) __syncthreads();
     if (PRO == PRO_ACT) {
       const u32x4 *src = (const u32x4 *)a.act;
-      const int per = nkb * 64;
+      const int per = nkb * AP * 64;
       for (int i = tid; i < NB * per; i += 256) {
         const int t = i / per, r = i - t * per;
-        lds[t * a.lds_chunk * 64 + r] = src[((size_t)t * a.k_blocks + kb0 + c0) * 64 + r];
+        lds[t * a.lds_chunk * AP * 64 + r] = src[((size_t)t * a.k_blocks + kb0 + c0) * AP * 64 + r];
       }
     } else {
       const int ppr = nkb * 4;  // 16-byte pieces per row in this chunk
@@ -120,18 +127,24 @@ __global__ void __launch_bounds__(256) skinny_gemm(SkinnyArgs a) {
         const f32x4 *xp = (const f32x4 *)(a.x + (size_t)row * K + k0);
         const f32x4 *gp = (const f32x4 *)(a.gamma + k0);
         const f32x4 *bp = (const f32x4 *)(a.beta + k0);
-        T v[PL];
+        T v[AP][PL];
 #pragma unroll
         for (int q = 0; q < PL / 4; ++q) {
           const f32x4 xv = xp[q], gv = gp[q];
           f32x4 y = (xv - mean) * rstd * gv;
           if (a.beta) y += bp[q];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v[q * 4 + e] = Elem<T>::from_f32(y[e]);
+          for (int e = 0; e < 4; ++e) {
+            v[0][q * 4 + e] = Elem<T>::from_f32(y[e]);
+            if (AP > 1) v[AP - 1][q * 4 + e] = Elem<T>::from_f32(y[e] - Elem<T>::to_f32(v[0][q * 4 + e]));
+          }
         }
-        u32x4 packed;
-        __builtin_memcpy(&packed, v, 16);
-        lds[((row >> 4) * a.lds_chunk + (p >> 2)) * 64 + (p & 3) * 16 + (row & 15)] = packed;
+#pragma unroll
+        for (int part = 0; part < AP; ++part) {
+          u32x4 packed;
+          __builtin_memcpy(&packed, v[part], 16);
+          lds[(((row >> 4) * a.lds_chunk + (p >> 2)) * AP + part) * 64 + (p & 3) * 16 + (row & 15)] = packed;
+        }
       }
     }
     __syncthreads();
@@ -225,7 +238,7 @@ __global__ void __launch_bounds__(256) skinny_gemm(SkinnyArgs a) {
               u[i] = act_apply(a.act_kind, acc[t][0][i] + (a.bias ? a.bias[n0 + i] : 0.f));
             }
           }
-          store4_frag<T>(a.act_out, b, n0, a.out_k_blocks, u[0], u[1], u[2], u[3]);
+          store4_frag<T>(a.act_out, b, n0, a.out_k_blocks, AP, u[0], u[1], u[2], u[3]);
         }
       }
     }
@@ -379,12 +392,12 @@ static int env_int(const char *name, int dflt) {
 }
 
 void plan_skinny(SkinnyArgs *a, int esz, size_t splitk_bytes, int nw) {
-  (void)esz;
   a->nb = a->B <= 16 ? 1 : 2;
   const int groups = ceil_div(a->tasks, 4);
   static const int target_blocks = env_int("SS_SKINNY_BLOCKS", 512);  // about 2 blocks per compute unit
-  static const int lds_kb = env_int("SS_SKINNY_LDS_KB", 32);
-  const int max_chunk = std::max(16, lds_kb / a->nb / 16 * 16);        // fragments staged at a time, multiple of 16
+  static const int lds_kb = env_int("SS_SKINNY_LDS_KB", 64);
+  const int parts = esz == 2 ? 2 : 1;                                   // bf16 activations are hi/lo pairs
+  const int max_chunk = std::max(16, lds_kb / (a->nb * parts) / 16 * 16);  // k blocks staged at a time, multiple of 16
   int split = std::max(1, std::min(target_blocks / std::max(groups, 1), a->k_blocks / 4));
   const size_t per_split = (size_t)a->nb * 16 * a->tasks * nw * 16 * 4;
   while (split > 1 && per_split * split > splitk_bytes) --split;
@@ -410,12 +423,12 @@ ss_status launch_skinny(int dtype, int pro, int epi, const SkinnyArgs &a, hipStr
   if (!ok_combo) SS_FAIL(SS_EINVAL, "skinny GEMM: unsupported prologue/epilogue pair %d/%d", pro, epi);
   if (a.B < 1 || a.B > 32 || a.nb != (a.B <= 16 ? 1 : 2)) SS_FAIL(SS_EINVAL, "skinny GEMM: batch %d / tiles %d", a.B, a.nb);
   if (a.tasks < 1 || a.k_blocks < 1 || a.split < 1 || a.kb_per_split < 1 || a.lds_chunk < 1 ||
-      (size_t)a.split * a.kb_per_split < (size_t)a.k_blocks || a.lds_chunk * a.nb > 64 ||
+      (size_t)a.split * a.kb_per_split < (size_t)a.k_blocks || a.lds_chunk * a.nb * (dtype == SS_DTYPE_BF16 ? 2 : 1) > 64 ||
       (a.lds_chunk < a.kb_per_split && a.lds_chunk % 16))
     SS_FAIL(SS_EINVAL, "skinny GEMM: inconsistent plan");
   const int groups = ceil_div(a.tasks, 4);
   dim3 grid(groups, a.split);
-  size_t lds = (size_t)a.nb * a.lds_chunk * 1024;
+  size_t lds = (size_t)a.nb * a.lds_chunk * (dtype == SS_DTYPE_BF16 ? 2 : 1) * 1024;
   if (dtype == SS_DTYPE_BF16) {
     if (a.nb == 1) launch_skinny_t<bf16_t, 1>(pro, epi, a, grid, lds, st);
     else launch_skinny_t<bf16_t, 2>(pro, epi, a, grid, lds, st);
@@ -431,11 +444,11 @@ ss_status launch_skinny(int dtype, int pro, int epi, const SkinnyArgs &a, hipStr
 // tiled prefill GEMM: block = 128 output features x 128 tokens, 4 waves of 64 x 64,
 // K advanced two fragments at a time through LDS with register prefetch of the next stage.
 // ---------------------------------------------------------------------------
-template <typename T, int EPI>
+template <typename T, int EPI, int AP>
 __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
   constexpr int KS = 2;  // k fragments per stage
   __shared__ __align__(16) u32x4 lds_w[KS][8][64];
-  __shared__ __align__(16) u32x4 lds_a[KS][8][64];
+  __shared__ __align__(16) u32x4 lds_a[KS][8][AP][64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave >> 1, wc = wave & 1;
   const int rt0 = blockIdx.x * 8;   // first weight row tile
@@ -449,9 +462,9 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // each thread moves 4 weight pieces and 4 activation pieces per stage:
-  // piece index p = tid + 256*r, r = 0..3 -> (ks = p / 512, tile = (p / 64) % 8, ln = p % 64)
-  u32x4 pw[4], pa[4];
+  // per stage each thread moves 4 weight pieces and 4*AP activation pieces:
+  // piece p = tid + 256*r -> (ks = p / 512, tile = (p / 64) % 8, ln = p % 64)
+  u32x4 pw[4], pa[4][AP];
   auto fetch = [&](int kb) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -461,7 +474,9 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
       const bool kok = k < a.k_blocks;
       pw[r] = (kok && rt0 + tile < a.row_tiles) ? W[((size_t)(rt0 + tile) * a.k_blocks + k) * 64 + ln]
                                                : u32x4{0u, 0u, 0u, 0u};
-      pa[r] = kok ? A[((size_t)(tt0 + tile) * a.k_blocks + k) * 64 + ln] : u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int part = 0; part < AP; ++part)
+        pa[r][part] = kok ? A[(((size_t)(tt0 + tile) * a.k_blocks + k) * AP + part) * 64 + ln] : u32x4{0u, 0u, 0u, 0u};
     }
   };
   fetch(0);
@@ -472,19 +487,26 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
       const int p = tid + 256 * r;
       const int ks = p >> 9, tile = (p >> 6) & 7, ln = p & 63;
       lds_w[ks][tile][ln] = pw[r];
-      lds_a[ks][tile][ln] = pa[r];
+#pragma unroll
+      for (int part = 0; part < AP; ++part) lds_a[ks][tile][part][ln] = pa[r][part];
     }
     __syncthreads();
     if (kb + KS < a.k_blocks) fetch(kb + KS);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      u32x4 wf[4], af[4];
+      u32x4 wf[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) wf[i] = lds_w[ks][wr * 4 + i][lane], af[i] = lds_a[ks][wc * 4 + i][lane];
+      for (int i = 0; i < 4; ++i) wf[i] = lds_w[ks][wr * 4 + i][lane];
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int part = 0; part < AP; ++part) {
+        u32x4 af[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = Mma<T>::mma(wf[i], af[j], acc[i][j]);
+        for (int j = 0; j < 4; ++j) af[j] = lds_a[ks][wc * 4 + j][part][lane];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[i][j] = Mma<T>::mma(wf[i], af[j], acc[i][j]);
+      }
     }
   }
 
@@ -501,7 +523,7 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
           float u[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) u[e] = silu_f(acc[i][j][e]) * acc[i + 1][j][e];
-          store4_frag<T>(a.act_out, tok, n0, a.out_k_blocks, u[0], u[1], u[2], u[3]);
+          store4_frag<T>(a.act_out, tok, n0, a.out_k_blocks, a.out_parts, u[0], u[1], u[2], u[3]);
         }
       }
     } else {
@@ -520,8 +542,8 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
             f32x4 x = *xp;
             *xp = f32x4{x[0] + v[0], x[1] + v[1], x[2] + v[2], x[3] + v[3]};
           } else {  // EPI_ACT
-            store4_frag<T>(a.act_out, tok, n0, a.out_k_blocks, act_apply(a.act_kind, v[0]), act_apply(a.act_kind, v[1]),
-                           act_apply(a.act_kind, v[2]), act_apply(a.act_kind, v[3]));
+            store4_frag<T>(a.act_out, tok, n0, a.out_k_blocks, a.out_parts, act_apply(a.act_kind, v[0]),
+                           act_apply(a.act_kind, v[1]), act_apply(a.act_kind, v[2]), act_apply(a.act_kind, v[3]));
           }
         }
       }
@@ -533,18 +555,26 @@ ss_status launch_tile_gemm(int dtype, int epi, const TileGemmArgs &a, hipStream_
   if (a.T < 128 || a.T % 128) SS_FAIL(SS_EINVAL, "prefill GEMM: token count %d is not a multiple of 128", a.T);
   if (a.row_tiles < 1 || a.k_blocks < 1 || a.N % 4) SS_FAIL(SS_EINVAL, "prefill GEMM: bad shape");
   if ((epi == EPI_F32 && (a.ld_out % 4)) || epi == EPI_LOGITS) SS_FAIL(SS_EINVAL, "prefill GEMM: bad epilogue");
+  if (a.act_parts != 1 && !(a.act_parts == 2 && dtype == SS_DTYPE_BF16)) SS_FAIL(SS_EINVAL, "prefill GEMM: bad act_parts");
+  if ((epi == EPI_ACT || epi == EPI_SWIGLU) && a.out_parts != 1 && !(a.out_parts == 2 && dtype == SS_DTYPE_BF16))
+    SS_FAIL(SS_EINVAL, "prefill GEMM: bad out_parts");
   dim3 grid(ceil_div(a.row_tiles, 8), a.T / 128);
-#define SS_LAUNCH(TT, EPI) hipLaunchKernelGGL((tile_gemm<TT, EPI>), grid, dim3(256), 0, st, a)
-  if (dtype == SS_DTYPE_BF16) {
-    if (epi == EPI_F32) SS_LAUNCH(bf16_t, EPI_F32);
-    else if (epi == EPI_RESID) SS_LAUNCH(bf16_t, EPI_RESID);
-    else if (epi == EPI_ACT) SS_LAUNCH(bf16_t, EPI_ACT);
-    else SS_LAUNCH(bf16_t, EPI_SWIGLU);
+#define SS_LAUNCH(TT, EPI, AP) hipLaunchKernelGGL((tile_gemm<TT, EPI, AP>), grid, dim3(256), 0, st, a)
+  if (dtype == SS_DTYPE_BF16 && a.act_parts == 2) {
+    if (epi == EPI_F32) SS_LAUNCH(bf16_t, EPI_F32, 2);
+    else if (epi == EPI_RESID) SS_LAUNCH(bf16_t, EPI_RESID, 2);
+    else if (epi == EPI_ACT) SS_LAUNCH(bf16_t, EPI_ACT, 2);
+    else SS_LAUNCH(bf16_t, EPI_SWIGLU, 2);
+  } else if (dtype == SS_DTYPE_BF16) {
+    if (epi == EPI_F32) SS_LAUNCH(bf16_t, EPI_F32, 1);
+    else if (epi == EPI_RESID) SS_LAUNCH(bf16_t, EPI_RESID, 1);
+    else if (epi == EPI_ACT) SS_LAUNCH(bf16_t, EPI_ACT, 1);
+    else SS_LAUNCH(bf16_t, EPI_SWIGLU, 1);
   } else {
-    if (epi == EPI_F32) SS_LAUNCH(float, EPI_F32);
-    else if (epi == EPI_RESID) SS_LAUNCH(float, EPI_RESID);
-    else if (epi == EPI_ACT) SS_LAUNCH(float, EPI_ACT);
-    else SS_LAUNCH(float, EPI_SWIGLU);
+    if (epi == EPI_F32) SS_LAUNCH(float, EPI_F32, 1);
+    else if (epi == EPI_RESID) SS_LAUNCH(float, EPI_RESID, 1);
+    else if (epi == EPI_ACT) SS_LAUNCH(float, EPI_ACT, 1);
+    else SS_LAUNCH(float, EPI_SWIGLU, 1);
   }
 #undef SS_LAUNCH
   SS_HIP(hipGetLastError());

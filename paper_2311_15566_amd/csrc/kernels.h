@@ -59,7 +59,8 @@ struct TileGemmArgs {
   const void *w;      // weight fragments
   int row_tiles;      // 16-row weight tiles (SwiGLU: 2 per 16 outputs, interleaved)
   int k_blocks;
-  const void *act;    // activation fragments [T/16][k_blocks]
+  const void *act;    // activation fragments [T/16][k_blocks][act_parts]
+  int act_parts;      // 1, or 2 for bf16 hi/lo pairs
   int T;              // tokens (padded to 128)
   int T_live;         // tokens that exist
   int N;
@@ -67,8 +68,9 @@ struct TileGemmArgs {
   float *out_f32;     // EPI_F32: [T][ld_out]
   int ld_out;
   float *x_resid;     // EPI_RESID: [T][N]
-  void *act_out;      // EPI_ACT / EPI_SWIGLU
+  void *act_out;      // EPI_ACT / EPI_SWIGLU: fragments [T/16][out_k_blocks][out_parts]
   int out_k_blocks;
+  int out_parts;
   int act_kind;
 };
 ss_status launch_tile_gemm(int dtype, int epi, const TileGemmArgs &a, hipStream_t st);
@@ -84,6 +86,7 @@ struct DecodeAttnArgs {
   int *counters;        // [B*Hs]
   void *o_out;          // fragments [nb][Hs*Dh / FragK]
   int B, Hs, Dh, Smax;
+  int kv_dtype;         // cache element type (SS_DTYPE_*)
   int rows_per_block, splits;
 };
 ss_status launch_decode_attn(int dtype, const DecodeAttnArgs &a, hipStream_t st);
@@ -94,8 +97,9 @@ struct PrefillAttnArgs {
   char *k_cache, *v_cache;
   size_t row_stride, head_stride;
   const float2 *rope;
-  void *o_out;          // fragments [T/16][Hs*Dh / FragK]
+  void *o_out;          // fragments [T/16][Hs*Dh / FragK][parts of the operand type]
   int B, S, Hs, Dh, Smax;
+  int kv_dtype;
 };
 ss_status launch_prefill_kv_write(int dtype, const PrefillAttnArgs &a, hipStream_t st);
 ss_status launch_prefill_attn(int dtype, const PrefillAttnArgs &a, hipStream_t st);

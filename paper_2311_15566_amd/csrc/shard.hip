@@ -31,6 +31,8 @@ ss_status validate_desc(const ss_model_desc &m, const ss_slice &s, int max_batch
   if (m.head_dim != 64 && m.head_dim != 128) SS_FAIL(SS_EINVAL, "head_dim must be 64 or 128 (got %d)", m.head_dim);
   if (m.d_model % 64) SS_FAIL(SS_EINVAL, "d_model must be a multiple of 64 (got %d)", m.d_model);
   if (m.dtype != SS_DTYPE_F32 && m.dtype != SS_DTYPE_BF16) SS_FAIL(SS_EINVAL, "unknown dtype %d", m.dtype);
+  if (m.dtype == SS_DTYPE_F32 ? m.kv_dtype != SS_DTYPE_F32 : (m.kv_dtype != SS_DTYPE_F16 && m.kv_dtype != SS_DTYPE_BF16))
+    SS_FAIL(SS_EINVAL, "kv_dtype %d does not go with dtype %d", m.kv_dtype, m.dtype);
   if (m.norm != SS_NORM_LAYERNORM && m.norm != SS_NORM_RMSNORM) SS_FAIL(SS_EINVAL, "unknown norm %d", m.norm);
   if (m.act < SS_ACT_GELU_TANH || m.act > SS_ACT_SWIGLU) SS_FAIL(SS_EINVAL, "unknown activation %d", m.act);
   if (m.pos != SS_POS_LEARNED && m.pos != SS_POS_ROPE) SS_FAIL(SS_EINVAL, "unknown position scheme %d", m.pos);
@@ -117,10 +119,10 @@ bool compute_layout(const ss_model_desc &m, const ss_slice &s, int max_batch, in
   const int T = L->Tmax;
   const int nmax = std::max(std::max(L->qkv_n, L->w1_rows), std::max(d, (int)align_up(L->V, 64)));
   L->ws_x = wtake((size_t)T * d * 4);
-  L->ws_a = wtake((size_t)T * d * esz);
+  L->ws_a = wtake((size_t)T * d * esz * (esz == 2 ? 2 : 1));  // bf16: hi/lo pairs
   L->ws_qkv = wtake((size_t)T * L->qkv_n * 4);
-  L->ws_o = wtake((size_t)T * HD * esz);
-  L->ws_u = wtake((size_t)T * L->Fs * esz);
+  L->ws_o = wtake((size_t)T * HD * esz * (esz == 2 ? 2 : 1));
+  L->ws_u = wtake((size_t)T * L->Fs * esz * (esz == 2 ? 2 : 1));
   L->ws_y = wtake((size_t)L->Bpad * d * 4);  // residual stream of the decode step
   L->splitk_bytes = std::min<size_t>((size_t)64 << 20, (size_t)16 * L->Bpad * nmax * 4);
   L->ws_splitk = wtake(L->splitk_bytes);
@@ -479,7 +481,7 @@ ss_status ss_kv_repack(ss_shard *dst_, const ss_shard *src_, const int32_t *batc
   Shard *dst = (Shard *)dst_;
   const Shard *src = (const Shard *)src_;
   if (dst == src) SS_FAIL(SS_EINVAL, "source and destination are the same shard");
-  if (dst->L.esz != src->L.esz || dst->L.Dh != src->L.Dh)
+  if (dst->L.esz != src->L.esz || dst->L.Dh != src->L.Dh || dst->m.kv_dtype != src->m.kv_dtype)
     SS_FAIL(SS_EINVAL, "source and destination differ in cache dtype or head_dim");
   RepackArgs a;
   memset(&a, 0, sizeof(a));

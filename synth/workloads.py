@@ -83,7 +83,8 @@ def _desc(n_layers, d_model, n_heads, head_dim, ffn, vocab, max_pos, norm, act, 
     return dict(n_layers=n_layers, d_model=d_model, n_heads=n_heads, head_dim=head_dim,
                 ffn=ffn, vocab=vocab, max_pos=max_pos, norm=norm, act=act, pos=pos,
                 has_bias=bool(has_bias), dtype=dtype, norm_eps=float(norm_eps),
-                rope_theta=float(rope_theta), tied_lm_head=(pos == "learned"))
+                rope_theta=float(rope_theta), tied_lm_head=(pos == "learned"),
+                kv_dtype="f32" if dtype == "f32" else "f16")
 
 
 def tp_slice(desc, layer_lo, layer_hi, m, M):
@@ -128,6 +129,7 @@ def scaled_workload(name: str, *, d_model, n_heads, head_dim, ffn, vocab, layers
     d.update(n_layers=layers, d_model=d_model, n_heads=n_heads, head_dim=head_dim, ffn=ffn, vocab=vocab)
     if dtype is not None:
         d["dtype"] = dtype
+        d["kv_dtype"] = "f32" if dtype == "f32" else "f16"
     s_max = s_max if s_max is not None else s_in + steps
     if d["pos"] == "learned":
         d["max_pos"] = s_max

@@ -139,13 +139,18 @@ CASES = [
     ("llama30b_m2", "bf16", dict(head_dim=128, n_heads=4, d_model=512, batch=17, s_in=150, vocab=1511)),
     ("opt66b_m8", "bf16", dict(batch=32, s_in=33, d_model=448, ffn=1152, head_dim=128, n_heads=2)),
     ("gpt20b_m4", "bf16", dict(batch=8, s_in=300, head_dim=128, n_heads=4, steps=4)),
+    ("gpt20b_m4", "bf16", dict(batch=3, s_in=130, kv_dtype="bf16")),          # bf16 cache elements
 ]
 
 
 @pytest.mark.parametrize("name,dtype,kw", CASES)
 def test_scaled_family_teacher_forced(ss, name, dtype, kw, side_stream):
     import torch
+    kw = dict(kw)
+    kv_dtype = kw.pop("kv_dtype", None)
     w = scaled(name, dtype, **kw)
+    if kv_dtype:
+        w.desc["kv_dtype"] = kv_dtype
     bf16 = dtype == "bf16"
     W = make_weights(w.desc, tp_slice(w.desc, 0, w.desc["n_layers"], 0, 1), w.seed)   # parent = full model
     toks = make_tokens(w.seed, w.batch, w.s_in, w.desc["vocab"])
@@ -170,8 +175,8 @@ def test_scaled_family_teacher_forced(ss, name, dtype, kw, side_stream):
     want = D.kv_canonical(ora)
     if bf16:
         from synth import bf16_bits_to_f32
-        got = bf16_bits_to_f32(got)
-        assert np.abs(got - want).max() < 2e-2
+        got = bf16_bits_to_f32(got) if got.dtype == np.uint16 else got.astype(np.float32)
+        assert np.abs(got - want).max() < (2e-2 if w.desc["kv_dtype"] == "bf16" else 4e-3)
     else:
         assert np.abs(got - want).max() < 1e-4
     sh.destroy()
@@ -194,7 +199,7 @@ def test_decode_is_deterministic_and_graph_equals_eager(ss, side_stream):
             ss.decode_step([sh], nxt, logits, nxt)
             torch.cuda.synchronize()
             run.append(logits.cpu().numpy().copy())
-        run.append(ss.kv_export(sh))
+        run.append(bits(ss.kv_export(sh)))
         outs.append(run)
         sh.destroy()
     for a, b in zip(outs[0], outs[1]):
@@ -232,10 +237,16 @@ def test_ragged_lengths_and_row_independence(ss):
 # ----------------------------------------------------------------------------
 # KV re-partition: bit-exact against the index formula
 # ----------------------------------------------------------------------------
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
-def test_repack_split_merge_bit_exact(ss, dtype):
+def bits(a):
+    """Raw bit patterns of an exported cache (comparisons must not go through float semantics)."""
+    return a.view(np.uint16) if a.dtype.itemsize == 2 else a.view(np.uint32)
+
+
+@pytest.mark.parametrize("dtype,kv_dtype", [("bf16", "f16"), ("bf16", "bf16"), ("f32", "f32")])
+def test_repack_split_merge_bit_exact(ss, dtype, kv_dtype):
     w = scaled("llama30b_m2", dtype, n_heads=8, head_dim=128, d_model=256, ffn=256, layers=2, M=2, m=1,
                batch=5, s_in=300, steps=0, s_max=300)
+    w.desc["kv_dtype"] = kv_dtype
     W = make_weights(w.desc, w.slice, w.seed)
     half = w.slice                                          # heads [4,8)
     src = ss.Shard(w.desc, half, W, 5, 300)
@@ -243,12 +254,12 @@ def test_repack_split_merge_bit_exact(ss, dtype):
     L, H, Dh = g["layers"], g["heads"], w.desc["head_dim"]
     rng = np.random.default_rng(11)
     lens = [300, 1, 0, 257, 64]
-    np_dt = np.uint16 if dtype == "bf16" else np.float32
-    src_arr = rng.integers(0, 60000, size=(L, 2, 5, H, 300, Dh)).astype(np_dt)
+    np_dt = np.uint16 if dtype == "bf16" else np.uint32
+    src_arr = rng.integers(0, 60000, size=(L, 2, 5, H, 300, Dh)).astype(np_dt)      # arbitrary bit patterns
     for b, n in enumerate(lens):
         src_arr[:, :, b, :, n:] = 0
     ss.kv_import(src, array_to_canonical(src_arr, lens), lens)
-    assert np.array_equal(ss.kv_export(src), array_to_canonical(src_arr, lens))   # import/export round trip
+    assert np.array_equal(bits(ss.kv_export(src)), array_to_canonical(src_arr, lens))   # import/export round trip
     # split into two quarter shards with other batch size / capacity, dropping row 1, permuting rows
     bmap = [3, -1, 0, 4]
     dsts = []
@@ -261,7 +272,7 @@ def test_repack_split_merge_bit_exact(ss, dtype):
         assert moved == moved_ref * np.dtype(np_dt).itemsize
         dlens = list(ss.committed_len(dshard))
         assert dlens == [257, 0, 300, 64]
-        got = canonical_to_array(ss.kv_export(dshard), L, 4, H // 2, 320, Dh, dlens)
+        got = canonical_to_array(bits(ss.kv_export(dshard)), L, 4, H // 2, 320, Dh, dlens)
         assert np.array_equal(got, exp)
         dsts.append((dshard, q, exp, dlens))
     # merge back into a fresh half shard: M' -> M is the identity on the kept rows
@@ -270,7 +281,7 @@ def test_repack_split_merge_bit_exact(ss, dtype):
         ss.kv_repack(back, dshard, [2, -1, -1, 0, 3], first_source=(i == 0))
     blens = list(ss.committed_len(back))
     assert blens == [300, 0, 0, 257, 64]
-    got = canonical_to_array(ss.kv_export(back), L, 5, H, 300, Dh, blens)
+    got = canonical_to_array(bits(ss.kv_export(back)), L, 5, H, 300, Dh, blens)
     want = src_arr.copy()
     want[:, :, 1] = 0
     assert np.array_equal(got, want)
@@ -339,18 +350,18 @@ def test_interrupted_step_commits_nothing_and_retry_is_identical(ss, side_stream
     na, nb = (torch.empty(w.batch, dtype=torch.int32, device="cuda") for _ in range(2))
     ss.prefill([a], dev(toks), la, na)
     ss.prefill([b], dev(toks), lb, nb)
-    before = ss.kv_export(b)
+    before = bits(ss.kv_export(b))
     b.interrupt_after_layer(1)
     with pytest.raises(ss.SpotShardError) as e:
         ss.decode_step([b], nb, lb, None)
     assert e.value.status == 5
     assert list(ss.committed_len(b)) == [w.s_in] * w.batch
-    assert np.array_equal(ss.kv_export(b), before)        # committed rows untouched
+    assert np.array_equal(bits(ss.kv_export(b)), before)  # committed rows untouched
     b.interrupt_after_layer(-1)
     ss.decode_step([b], nb, lb, nb)                        # retry
     ss.decode_step([a], na, la, na)
     assert np.array_equal(la.cpu().numpy(), lb.cpu().numpy())
-    assert np.array_equal(ss.kv_export(a), ss.kv_export(b))
+    assert np.array_equal(bits(ss.kv_export(a)), bits(ss.kv_export(b)))
     a.destroy()
     b.destroy()
 
