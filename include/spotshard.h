@@ -169,8 +169,14 @@ ss_status ss_kv_import(ss_shard *shard, const void *host_src, const int32_t *len
  * shard) and return SS_EINTR without committing.  -1 switches it off. */
 ss_status ss_debug_interrupt_after_layer(ss_shard *shard, int32_t layer);
 
-/* 1 (default): ss_decode_step replays a captured HIP graph of the step; 0: launches
- * the kernels one by one. */
+/* How ss_decode_step is launched.  Persistent (default 1): the whole step is ONE kernel
+ * whose blocks stay resident and meet at device-wide barriers between the step's phases
+ * (bf16 models with head_dim 128, one shard in the group, batch <= 32; other cases fall
+ * back).  Otherwise, graph (default 1): replay of a captured HIP graph of the step's
+ * kernels; 0: the kernels one by one.  All three give bit-identical results.  If a
+ * barrier of the persistent kernel does not complete within its spin limit the step
+ * commits nothing and the next ss_committed_len returns SS_EHIP. */
+ss_status ss_set_persistent(ss_shard *shard, int32_t enabled);
 ss_status ss_set_graph_launch(ss_shard *shard, int32_t enabled);
 
 /* Measurement aid: per-kernel-class timing of decode steps.  While enabled on group[0],

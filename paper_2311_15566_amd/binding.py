@@ -70,6 +70,7 @@ def _load():
     L.ss_kv_import.argtypes = [vp, vp, C.POINTER(i32), sz, vp]
     L.ss_debug_interrupt_after_layer.argtypes = [vp, i32]
     L.ss_set_graph_launch.argtypes = [vp, i32]
+    L.ss_set_persistent.argtypes = [vp, i32]
     L.ss_shard_geometry.argtypes = [vp, C.POINTER(i32)]
     L.ss_kernel_timing.argtypes = [vp, i32]
     L.ss_kernel_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), vp]
@@ -168,6 +169,9 @@ class Shard:
 
     def interrupt_after_layer(self, layer: int):
         _check(lib.ss_debug_interrupt_after_layer(self.handle, layer))
+
+    def set_persistent(self, enabled: bool):
+        _check(lib.ss_set_persistent(self.handle, int(enabled)))
 
     def set_graph_launch(self, enabled: bool):
         _check(lib.ss_set_graph_launch(self.handle, int(enabled)))

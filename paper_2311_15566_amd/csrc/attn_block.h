@@ -1,0 +1,240 @@
+// One block's share of decode attention, as a device function: the stand-alone kernel and the
+// persistent decode-step kernel both call it.
+#pragma once
+#include <math.h>
+
+#include "kernels.h"
+
+namespace ss {
+
+// KT: cache element type; AT: activation operand type of the GEMM that consumes the output
+template <typename T, int DH> struct RowGeom {
+  static constexpr int EPL = Elem<T>::kPerLane;      // elements per lane (16 bytes)
+  static constexpr int LPR = DH / EPL;               // lanes per cache row
+  static constexpr int G = 64 / LPR;                 // rows per wave-wide load
+};
+
+template <typename T>
+__device__ __forceinline__ void unpack16(const u32x4 &raw, float *out);
+template <>
+__device__ __forceinline__ void unpack16<float>(const u32x4 &raw, float *out) {
+  f32x4 f = __builtin_bit_cast(f32x4, raw);
+  out[0] = f[0], out[1] = f[1], out[2] = f[2], out[3] = f[3];
+}
+template <>
+__device__ __forceinline__ void unpack16<bf16_t>(const u32x4 &raw, float *out) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    out[2 * i] = __uint_as_float(raw[i] << 16);
+    out[2 * i + 1] = __uint_as_float(raw[i] & 0xffff0000u);
+  }
+}
+
+template <>
+__device__ __forceinline__ void unpack16<f16_t>(const u32x4 &raw, float *out) {
+  typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+  h8 h = __builtin_bit_cast(h8, raw);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) out[i] = (float)h[i];
+}
+
+// q, k of the new token at position pos, rotated (half-split pairing) when a table is given.
+__device__ __forceinline__ float rope_elem(const float *v, int e, int half, const float2 *tab) {
+  if (!tab) return v[e];
+  if (e < half) {
+    float2 cs = tab[e];
+    return v[e] * cs.x - v[e + half] * cs.y;
+  }
+  float2 cs = tab[e - half];
+  return v[e - half] * cs.y + v[e] * cs.x;
+}
+
+// ---------------------------------------------------------------------------
+// decode attention.  grid = (B*Hs, splits); block = 4 waves.
+// Block (bh, s) covers committed rows [s*rpb, min((s+1)*rpb, n)); a lane group of LPR lanes
+// owns one row at a time and keeps its own running (max, sum, acc); groups, waves and then
+// splits are merged with the usual rescaling.  The last block to arrive for (b, h) also
+// scores the new token from registers, writes its key/value as cache row n and emits the
+// head output.  Blocks past the live splits exit at once.
+// ---------------------------------------------------------------------------
+struct AttnShared {
+  float sq[128];
+  float sm_m[4], sm_l[4];
+  float sm_acc[4][128];
+  float sm_red[4];
+  int flag;
+};
+
+template <typename T, typename AT, int DH>
+__device__ __forceinline__ void decode_attn_block(const DecodeAttnArgs &a, const int bh, const int sp, AttnShared &sh) {
+  typedef RowGeom<T, DH> Gm;
+  constexpr int EPL = Gm::EPL, LPR = Gm::LPR, G = Gm::G, U = 4;
+  auto &sq = sh.sq;
+  auto &sm_m = sh.sm_m;
+  auto &sm_l = sh.sm_l;
+  auto &sm_acc = sh.sm_acc;
+  auto &sm_red = sh.sm_red;
+  int &s_flag = sh.flag;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = bh / a.Hs, h = bh - b * a.Hs;
+  const int n = a.lens[b];
+  const int live_splits = max(1, (n + a.rows_per_block - 1) / a.rows_per_block);
+  if (sp >= live_splits) return;
+  const int HD = a.Hs * DH;
+  const float scale = rsqrtf((float)DH);
+  const float2 *tab = a.rope ? a.rope + (size_t)n * (DH / 2) : nullptr;
+  const float *qraw = a.qkv + (size_t)b * 3 * HD + h * DH;
+  __syncthreads();  // the previous user of the shared scratch is done
+  if (tid < DH) sq[tid] = rope_elem(qraw, tid, DH / 2, tab);
+  __syncthreads();
+
+  const int c = lane % LPR, g = lane / LPR;
+  float qf[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) qf[e] = sq[c * EPL + e];
+
+  const int r0 = sp * a.rows_per_block;
+  const int r1 = min(r0 + a.rows_per_block, n);
+  const char *kbase = a.k_cache + b * a.row_stride + h * a.head_stride;
+  const char *vbase = a.v_cache + b * a.row_stride + h * a.head_stride;
+  constexpr int ROWB = DH * (int)sizeof(T);
+
+  float m = -1e30f, l = 0.f, acc[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+
+  for (int base = r0 + wave * (U * G); base < r1; base += 4 * U * G) {
+    u32x4 kr[U], vr[U];
+    int row[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      row[u] = base + u * G + g;
+      const int rr = min(row[u], r1 - 1);  // clamp: masked below, stays inside committed rows
+      kr[u] = __builtin_nontemporal_load((const u32x4 *)(kbase + (size_t)rr * ROWB) + c);
+      vr[u] = __builtin_nontemporal_load((const u32x4 *)(vbase + (size_t)rr * ROWB) + c);
+    }
+    float s[U];
+    float mb = -1e30f;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float kf[EPL];
+      unpack16<T>(kr[u], kf);
+      float d = 0.f;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) d += qf[e] * kf[e];
+#pragma unroll
+      for (int off = 1; off < LPR; off <<= 1) d += __shfl_xor(d, off);
+      s[u] = row[u] < r1 ? d * scale : -INFINITY;
+      mb = fmaxf(mb, s[u]);
+    }
+    const float mn = fmaxf(m, mb);
+    const float alpha = __expf(m - mn);
+    l *= alpha;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] *= alpha;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const float p = __expf(s[u] - mn);
+      l += p;
+      float vf[EPL];
+      unpack16<T>(vr[u], vf);
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[e] += p * vf[e];
+    }
+    m = mn;
+  }
+  // merge the G lane groups of the wave
+#pragma unroll
+  for (int off = LPR; off < 64; off <<= 1) {
+    const float mo = __shfl_xor(m, off), lo = __shfl_xor(l, off);
+    const float mn = fmaxf(m, mo);
+    const float f0 = __expf(m - mn), f1 = __expf(mo - mn);
+    l = l * f0 + lo * f1;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] = acc[e] * f0 + __shfl_xor(acc[e], off) * f1;
+    m = mn;
+  }
+  if (lane < LPR) {
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) sm_acc[wave][lane * EPL + e] = acc[e];
+    if (lane == 0) sm_m[wave] = m, sm_l[wave] = l;
+  }
+  __syncthreads();
+  // merge the 4 waves; thread e owns output dim e
+  float M = -1e30f, Lsum = 0.f, A = 0.f;
+  if (tid < DH) {
+#pragma unroll
+    for (int w = 0; w < 4; ++w) M = fmaxf(M, sm_m[w]);
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float f = __expf(sm_m[w] - M);
+      Lsum += sm_l[w] * f;
+      A += sm_acc[w][tid] * f;
+    }
+  }
+  float *part = a.part + ((size_t)bh * a.splits) * (DH + 4);
+  if (live_splits > 1) {
+    if (tid < DH) {
+      float *p = part + (size_t)sp * (DH + 4);
+      st_dev(p + tid, A);
+      if (tid == 0) st_dev(p + DH, M), st_dev(p + DH + 1, Lsum);
+    }
+    if (!arrive_last(&a.counters[bh], live_splits, &s_flag)) return;
+    if (tid < DH) {
+      M = -1e30f, Lsum = 0.f, A = 0.f;
+      for (int s2 = 0; s2 < live_splits; ++s2) M = fmaxf(M, ld_dev(part + (size_t)s2 * (DH + 4) + DH));
+      for (int s2 = 0; s2 < live_splits; ++s2) {
+        const float *p = part + (size_t)s2 * (DH + 4);
+        const float f = __expf(ld_dev(p + DH) - M);
+        Lsum += ld_dev(p + DH + 1) * f;
+        A += ld_dev(p + tid) * f;
+      }
+    }
+  }
+  // the new token: append as row n (not committed until the step's last kernel), attend to itself
+  float vnew = 0.f, prod = 0.f;
+  if (tid < DH) {
+    const float kn = rope_elem(qraw + HD, tid, DH / 2, tab);
+    const T kt = Elem<T>::from_f32(kn);
+    const T vt = Elem<T>::from_f32(qraw[2 * HD + tid]);
+    ((T *)(a.k_cache + b * a.row_stride + h * a.head_stride + (size_t)n * ROWB))[tid] = kt;
+    ((T *)(a.v_cache + b * a.row_stride + h * a.head_stride + (size_t)n * ROWB))[tid] = vt;
+    vnew = Elem<T>::to_f32(vt);
+    prod = sq[tid] * Elem<T>::to_f32(kt);
+  }
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) prod += __shfl_xor(prod, off);
+  if (lane == 0) sm_red[wave] = prod;
+  __syncthreads();
+  if (tid < DH) {
+    float sn = 0.f;
+#pragma unroll
+    for (int w = 0; w < (DH + 63) / 64; ++w) sn += sm_red[w];
+    sn *= scale;
+    const float mn = fmaxf(M, sn);
+    const float f0 = __expf(M - mn), p = __expf(sn - mn);
+    const float Lf = Lsum * f0 + p;
+    const float o = (A * f0 + p * vnew) / Lf;
+    // neighbouring dims pair up so that the operand buffer is written in whole words
+    constexpr int AP = Elem<AT>::kParts;
+    const float o_next = __shfl_xor(o, 1);
+    if (sizeof(AT) == 4) {
+      float *p = (float *)a.o_out + frag_offset_parts<AT>(b, h * DH + tid, HD / Elem<AT>::kFragK, AP, 0);
+      st_dev(p, o);
+    } else if ((tid & 1) == 0) {
+      const int k = h * DH + tid;
+      const AT h0 = Elem<AT>::from_f32(o), h1 = Elem<AT>::from_f32(o_next);
+#pragma unroll
+      for (int part = 0; part < AP; ++part) {
+        AT w[2];
+        w[0] = part == 0 ? h0 : Elem<AT>::from_f32(o - Elem<AT>::to_f32(h0));
+        w[1] = part == 0 ? h1 : Elem<AT>::from_f32(o_next - Elem<AT>::to_f32(h1));
+        uint32_t word;
+        __builtin_memcpy(&word, w, 4);
+        st_dev((uint32_t *)((AT *)a.o_out + frag_offset_parts<AT>(b, k, HD / Elem<AT>::kFragK, AP, part)), word);
+      }
+    }
+  }
+}
+
+}  // namespace ss

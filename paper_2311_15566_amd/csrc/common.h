@@ -111,12 +111,21 @@ __device__ __forceinline__ void st_dev(float *p, float v) {
 __device__ __forceinline__ void st_dev(int *p, int v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ void st_dev(uint32_t *p, uint32_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 __device__ __forceinline__ float ld_dev(const float *p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ int ld_dev(const int *p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// Single-assignment rule: a buffer that one block writes and another block of the SAME launch
+// reads with ordinary (L2-cached) loads is written with st_dev and is written only once per
+// launch, at an address no block has read earlier in that launch; then no L2 can hold a stale
+// copy of it.  Buffers that are rewritten within a launch (partials, counters) are read with
+// ld_dev.
+
 // Called by every thread of the block after its st_dev stores.  Returns true in every thread
 // of the one block that arrives last of `expected`; that block also re-arms the counter.
 __device__ __forceinline__ bool arrive_last(int *counter, int expected, int *s_flag) {

@@ -3,6 +3,7 @@
 #include <algorithm>
 
 #include "kernels.h"
+#include "rows.h"
 #include "shard.h"
 
 namespace ss {
@@ -10,53 +11,10 @@ namespace ss {
 // ---------------------------------------------------------------------------
 // row kernels
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ float block_sum(float v, float *scratch) {
-  // sum over a 256-thread block; every thread gets the result
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) v += __shfl_xor(v, off);
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
-  __syncthreads();
-  return scratch[0] + scratch[1] + scratch[2] + scratch[3];
-}
-
-__device__ __forceinline__ void row_stats(const float *row, int d, int rms, float eps, float *scratch, float *mean_out,
-                                          float *rstd_out) {
-  float s = 0.f;
-  for (int k = threadIdx.x; k < d; k += 256) s += row[k];
-  const float mean = rms ? 0.f : block_sum(s, scratch) / (float)d;
-  float q = 0.f;
-  for (int k = threadIdx.x; k < d; k += 256) {
-    const float c = row[k] - mean;
-    q += c * c;
-  }
-  const float var = block_sum(q, scratch) / (float)d;
-  *mean_out = mean;
-  *rstd_out = rsqrtf(var + eps);
-}
-
-// x[r] = wte[token] (+ wpe[position]); decode: position = committed length, also the first
-// norm's statistics.  grid = rows.
 template <typename T>
-__global__ void __launch_bounds__(256) embed_rows(const int32_t *tokens, const T *wte, const T *wpe, const int32_t *lens,
-                                                  int S, float *x, float *stats, int d, int V, int rms, float eps) {
+__global__ void __launch_bounds__(256) embed_rows(EmbedArgs a) {
   __shared__ float scratch[4];
-  const int r = blockIdx.x;
-  int tok = tokens[r];
-  tok = min(max(tok, 0), V - 1);
-  const int pos = lens ? lens[r] : (r % S);
-  float *xr = x + (size_t)r * d;
-  for (int k = threadIdx.x; k < d; k += 256) {
-    float v = Elem<T>::to_f32(wte[(size_t)tok * d + k]);
-    if (wpe) v += Elem<T>::to_f32(wpe[(size_t)pos * d + k]);
-    xr[k] = v;
-  }
-  if (stats) {
-    __syncthreads();
-    float mean, rstd;
-    row_stats(xr, d, rms, eps, scratch, &mean, &rstd);
-    if (threadIdx.x == 0) stats[r * 2] = mean, stats[r * 2 + 1] = rstd;
-  }
+  embed_row_block<T, true>(a, blockIdx.x, scratch);
 }
 
 // a = Norm(x) for every token row, written in operand order.  grid = rows.
@@ -127,16 +85,21 @@ static void attn_plan(const Layout &L, int B, int *rows_per_block, int *splits) 
 }
 
 // ---------------------------------------------------------------------------
-// LM head + argmax + commit (shared by decode and the end of the initial phase)
+// the decode step as a list of phases
 // ---------------------------------------------------------------------------
-static ss_status lm_head(Shard *const *group, int n_group, int B, float *xd, float *stats, float *logits,
-                         int32_t *next_tokens, int commit_inc, hipStream_t st) {
+static float *xv(const Shard *g0, int v) { return (float *)(g0->ws + g0->L.ws_xv + (size_t)v * g0->L.xv_stride); }
+static float *statv(const Shard *g0, int v) { return (float *)(g0->ws + g0->L.ws_statv) + (size_t)v * 64; }
+
+static Phase lm_head_phase(Shard *const *group, int n_group, int B, const float *x, const float *stats, float *logits,
+                           int32_t *next_tokens, int commit_inc, int target_blocks) {
   Shard *g0 = group[0];
   const Layout &L = g0->L;
-  SkinnyArgs a = {};
+  Phase ph = {};
+  ph.kind = PH_LM_HEAD;
+  SkinnyArgs &a = ph.g;
   a.w = g0->lm_head.ptr, a.tasks = g0->lm_head.row_tiles, a.k_blocks = g0->lm_head.k_blocks, a.B = B, a.N = L.V;
-  plan_skinny(&a, L.esz, L.splitk_bytes, 1);
-  a.x = xd, a.stats = stats, a.gamma = g0->lnf_g, a.beta = g0->lnf_b;
+  plan_skinny(&a, L.esz, L.splitk_bytes, 1, target_blocks);
+  a.x = x, a.stats = stats, a.gamma = g0->lnf_g, a.beta = g0->lnf_b;
   a.splitk = (float *)(g0->ws + L.ws_splitk), a.counters = (int *)(g0->ws + L.ws_counters);
   a.out_f32 = logits, a.ld_out = L.V;
   a.am_val = (float *)(g0->ws + L.ws_argmax);
@@ -144,7 +107,109 @@ static ss_status lm_head(Shard *const *group, int n_group, int B, float *xd, flo
   a.next_tokens = next_tokens;
   for (int i = 0; i < n_group; ++i) a.lens[i] = group[i]->d_len;
   a.n_lens = n_group, a.commit_inc = commit_inc;
-  return launch_skinny(g0->m.dtype, PRO_NORM, EPI_LOGITS, a, st);
+  ph.gx = ceil_div(a.tasks, 4), ph.gy = a.split;
+  return ph;
+}
+
+// Phases of one decode step, in order.  Buffers follow the single-assignment rule: residual
+// stream version v (0 = embedding, 2l+1 = after layer l's attention, 2l+2 = after its FFN), one
+// q|k|v, attention-output and FFN-activation buffer per layer.
+static void build_decode_plan(Shard *const *group, int n_group, const int32_t *tokens_in, int B, float *logits,
+                              int32_t *next_tokens, int stop_after_layer, int target_blocks, std::vector<Phase> *plan) {
+  Shard *g0 = group[0];
+  const Layout &L0 = g0->L;
+  const ss_model_desc &m = g0->m;
+  const int dt = m.dtype, d = L0.d;
+  const int FK = dt == SS_DTYPE_BF16 ? 32 : 16;
+  const int rms = m.norm == SS_NORM_RMSNORM;
+  float *stat_part = (float *)(g0->ws + L0.ws_stat_part);
+  plan->clear();
+  {
+    Phase ph = {};
+    ph.kind = PH_EMBED, ph.gx = B, ph.gy = 1;
+    ph.e = EmbedArgs{tokens_in, g0->wte, g0->wpe, g0->d_len, 0, xv(g0, 0), statv(g0, 0), d, L0.V, rms, m.norm_eps};
+    plan->push_back(ph);
+  }
+  // sum over the group at a reduce slot: shard i adds its partial to what the previous shards left
+  auto resid = [&](int l, int i, const FragMat &w, const void *act, const float *bias, int v_in, int v_out) {
+    Shard *s = group[i];
+    const Layout &L = s->L;
+    Phase ph = {};
+    ph.kind = PH_RESID, ph.shard = i;
+    SkinnyArgs &a = ph.g;
+    a.w = w.ptr, a.tasks = w.row_tiles, a.k_blocks = w.k_blocks, a.B = B, a.N = d;
+    plan_skinny(&a, L.esz, L.splitk_bytes, 1, target_blocks);
+    a.act = act;
+    a.splitk = (float *)(s->ws + L.ws_splitk), a.counters = (int *)(s->ws + L.ws_counters);
+    a.bias = i == 0 ? bias : nullptr;
+    const int pp0 = 2 * L0.Ls + 1;
+    a.x_in = xv(g0, i == 0 ? v_in : pp0 + ((i - 1) & 1));
+    a.x_resid = xv(g0, i == n_group - 1 ? v_out : pp0 + (i & 1));
+    a.stat_part = stat_part, a.stats_out = statv(g0, v_out), a.rms = rms, a.eps = m.norm_eps;
+    ph.gx = ceil_div(a.tasks, 4), ph.gy = a.split;
+    (void)l;
+    plan->push_back(ph);
+  };
+  for (int l = 0; l < L0.Ls; ++l) {
+    const LayerDev &D0 = g0->layers[l];
+    for (int i = 0; i < n_group; ++i) {  // QKV projection of the new token
+      Shard *s = group[i];
+      const Layout &L = s->L;
+      Phase ph = {};
+      ph.kind = PH_QKV, ph.shard = i;
+      SkinnyArgs &a = ph.g;
+      a.w = s->wqkv[l].ptr, a.tasks = s->wqkv[l].row_tiles, a.k_blocks = s->wqkv[l].k_blocks, a.B = B, a.N = L.qkv_n;
+      plan_skinny(&a, L.esz, L.splitk_bytes, 1, target_blocks);
+      a.x = xv(g0, 2 * l), a.stats = statv(g0, 2 * l), a.gamma = D0.ln1_g, a.beta = D0.ln1_b;
+      a.splitk = (float *)(s->ws + L.ws_splitk), a.counters = (int *)(s->ws + L.ws_counters);
+      a.bias = s->layers[l].bqkv, a.out_f32 = (float *)(s->ws + L.ws_qkv_l + l * L.qkv_l_stride), a.ld_out = L.qkv_n;
+      ph.gx = ceil_div(a.tasks, 4), ph.gy = a.split;
+      plan->push_back(ph);
+    }
+    for (int i = 0; i < n_group; ++i) {  // attention over the committed rows + append
+      Shard *s = group[i];
+      const Layout &L = s->L;
+      Phase ph = {};
+      ph.kind = PH_ATTN, ph.shard = i;
+      DecodeAttnArgs &a = ph.at;
+      a.qkv = (const float *)(s->ws + L.ws_qkv_l + l * L.qkv_l_stride);
+      a.k_cache = s->kv_ptr(l, 0), a.v_cache = s->kv_ptr(l, 1);
+      a.row_stride = s->kv_row_stride(), a.head_stride = s->kv_head_stride();
+      a.lens = s->d_len, a.rope = m.pos == SS_POS_ROPE ? s->rope : nullptr;
+      a.part = (float *)(s->ws + L.ws_attn_part);
+      a.counters = (int *)(s->ws + L.ws_counters) + (L.n_counters - L.Bmax * L.Hs);
+      a.o_out = s->ws + L.ws_o_l + l * L.o_l_stride;
+      a.B = B, a.Hs = L.Hs, a.Dh = L.Dh, a.Smax = L.Smax, a.kv_dtype = s->m.kv_dtype;
+      attn_plan(L, B, &a.rows_per_block, &a.splits);
+      ph.gx = B * L.Hs, ph.gy = a.splits;
+      plan->push_back(ph);
+    }
+    for (int i = 0; i < n_group; ++i)  // output projection, sum over the group, residual
+      resid(l, i, group[i]->wo[l], group[i]->ws + group[i]->L.ws_o_l + l * group[i]->L.o_l_stride, D0.bo, 2 * l,
+            2 * l + 1);
+    for (int i = 0; i < n_group; ++i) {  // first FFN matrix + activation
+      Shard *s = group[i];
+      const Layout &L = s->L;
+      const bool glu = m.act == SS_ACT_SWIGLU;
+      Phase ph = {};
+      ph.kind = PH_FFN_UP, ph.shard = i;
+      SkinnyArgs &a = ph.g;
+      a.w = s->w1[l].ptr, a.tasks = L.Fs / 16, a.k_blocks = s->w1[l].k_blocks, a.B = B, a.N = L.Fs;
+      plan_skinny(&a, L.esz, L.splitk_bytes, glu ? 2 : 1, target_blocks);
+      a.x = xv(g0, 2 * l + 1), a.stats = statv(g0, 2 * l + 1), a.gamma = D0.ln2_g, a.beta = D0.ln2_b;
+      a.splitk = (float *)(s->ws + L.ws_splitk), a.counters = (int *)(s->ws + L.ws_counters);
+      a.bias = s->layers[l].b1, a.act_out = s->ws + L.ws_u_l + l * L.u_l_stride, a.out_k_blocks = L.Fs / FK;
+      a.act_kind = m.act;
+      ph.gx = ceil_div(a.tasks, 4), ph.gy = a.split;
+      plan->push_back(ph);
+    }
+    for (int i = 0; i < n_group; ++i)  // second FFN matrix, sum over the group, residual
+      resid(l, i, group[i]->w2[l], group[i]->ws + group[i]->L.ws_u_l + l * group[i]->L.u_l_stride, D0.b2, 2 * l + 1,
+            2 * l + 2);
+    if (l == stop_after_layer) return;
+  }
+  plan->push_back(lm_head_phase(group, n_group, B, xv(g0, 2 * L0.Ls), statv(g0, 2 * L0.Ls), logits, next_tokens, 1,
+                                target_blocks));
 }
 
 // ---------------------------------------------------------------------------
@@ -177,104 +242,33 @@ struct Bracket {
   }
 };
 
-// ---------------------------------------------------------------------------
-// one decode step, kernel by kernel
-// ---------------------------------------------------------------------------
+// one phase as a kernel of its own
+static ss_status launch_phase(Shard *g0, const Phase &ph, hipStream_t st) {
+  const int dt = g0->m.dtype;
+  Bracket br(g0, ph.kind, st);
+  switch (ph.kind) {
+    case PH_EMBED:
+      if (dt == SS_DTYPE_BF16) hipLaunchKernelGGL(embed_rows<bf16_t>, dim3(ph.gx), dim3(256), 0, st, ph.e);
+      else hipLaunchKernelGGL(embed_rows<float>, dim3(ph.gx), dim3(256), 0, st, ph.e);
+      SS_HIP(hipGetLastError());
+      return SS_OK;
+    case PH_QKV: return launch_skinny(dt, PRO_NORM, EPI_F32, ph.g, st);
+    case PH_ATTN: return launch_decode_attn(dt, ph.at, st);
+    case PH_RESID: return launch_skinny(dt, PRO_ACT, EPI_RESID, ph.g, st);
+    case PH_FFN_UP: return launch_skinny(dt, PRO_NORM, g0->m.act == SS_ACT_SWIGLU ? EPI_SWIGLU : EPI_ACT, ph.g, st);
+    case PH_LM_HEAD: return launch_skinny(dt, PRO_NORM, EPI_LOGITS, ph.g, st);
+  }
+  SS_FAIL(SS_EINVAL, "unknown phase kind %d", ph.kind);
+}
+
 static ss_status enqueue_decode(Shard *const *group, int n_group, const int32_t *tokens_in, int B, float *logits,
                                 int32_t *next_tokens, hipStream_t st, int stop_after_layer) {
-  Shard *g0 = group[0];
-  const Layout &L0 = g0->L;
-  const ss_model_desc &m = g0->m;
-  const int dt = m.dtype, d = L0.d;
-  const int FK = dt == SS_DTYPE_BF16 ? 32 : 16;
-  const int rms = m.norm == SS_NORM_RMSNORM;
-  float *xd = (float *)(g0->ws + L0.ws_y);
-  float *stats = (float *)(g0->ws + L0.ws_stats);
-  float *stat_part = stats + 64;
-  {
-    Bracket br(g0, 0, st);
-    if (dt == SS_DTYPE_BF16)
-      hipLaunchKernelGGL(embed_rows<bf16_t>, dim3(B), dim3(256), 0, st, tokens_in, (const bf16_t *)g0->wte,
-                         (const bf16_t *)g0->wpe, g0->d_len, 0, xd, stats, d, L0.V, rms, m.norm_eps);
-    else
-      hipLaunchKernelGGL(embed_rows<float>, dim3(B), dim3(256), 0, st, tokens_in, (const float *)g0->wte,
-                         (const float *)g0->wpe, g0->d_len, 0, xd, stats, d, L0.V, rms, m.norm_eps);
-    SS_HIP(hipGetLastError());
-  }
-
-  for (int l = 0; l < L0.Ls; ++l) {
-    const LayerDev &D0 = g0->layers[l];
-    for (int i = 0; i < n_group; ++i) {  // QKV projection of the new token
-      Shard *s = group[i];
-      const Layout &L = s->L;
-      SkinnyArgs a = {};
-      a.w = s->wqkv[l].ptr, a.tasks = s->wqkv[l].row_tiles, a.k_blocks = s->wqkv[l].k_blocks, a.B = B, a.N = L.qkv_n;
-      plan_skinny(&a, L.esz, L.splitk_bytes, 1);
-      a.x = xd, a.stats = stats, a.gamma = D0.ln1_g, a.beta = D0.ln1_b;
-      a.splitk = (float *)(s->ws + L.ws_splitk), a.counters = (int *)(s->ws + L.ws_counters);
-      a.bias = s->layers[l].bqkv, a.out_f32 = (float *)(s->ws + L.ws_qkv), a.ld_out = L.qkv_n;
-      Bracket br(g0, 1, st);
-      SS_TRY(launch_skinny(dt, PRO_NORM, EPI_F32, a, st));
-    }
-    for (int i = 0; i < n_group; ++i) {  // attention over the committed rows + append
-      Shard *s = group[i];
-      const Layout &L = s->L;
-      DecodeAttnArgs a = {};
-      a.qkv = (const float *)(s->ws + L.ws_qkv);
-      a.k_cache = s->kv_ptr(l, 0), a.v_cache = s->kv_ptr(l, 1);
-      a.row_stride = s->kv_row_stride(), a.head_stride = s->kv_head_stride();
-      a.lens = s->d_len, a.rope = m.pos == SS_POS_ROPE ? s->rope : nullptr;
-      a.part = (float *)(s->ws + L.ws_attn_part);
-      a.counters = (int *)(s->ws + L.ws_counters) + (L.n_counters - L.Bmax * L.Hs);
-      a.o_out = s->ws + L.ws_o;
-      a.B = B, a.Hs = L.Hs, a.Dh = L.Dh, a.Smax = L.Smax, a.kv_dtype = s->m.kv_dtype;
-      attn_plan(L, B, &a.rows_per_block, &a.splits);
-      Bracket br(g0, 2, st);
-      SS_TRY(launch_decode_attn(dt, a, st));
-    }
-    for (int i = 0; i < n_group; ++i) {  // output projection, sum over the group, residual
-      Shard *s = group[i];
-      const Layout &L = s->L;
-      SkinnyArgs a = {};
-      a.w = s->wo[l].ptr, a.tasks = s->wo[l].row_tiles, a.k_blocks = s->wo[l].k_blocks, a.B = B, a.N = d;
-      plan_skinny(&a, L.esz, L.splitk_bytes, 1);
-      a.act = s->ws + L.ws_o;
-      a.splitk = (float *)(s->ws + L.ws_splitk), a.counters = (int *)(s->ws + L.ws_counters);
-      a.bias = i == 0 ? D0.bo : nullptr;
-      a.x_resid = xd, a.stat_part = stat_part, a.stats_out = stats, a.rms = rms, a.eps = m.norm_eps;
-      Bracket br(g0, 3, st);
-      SS_TRY(launch_skinny(dt, PRO_ACT, EPI_RESID, a, st));
-    }
-    for (int i = 0; i < n_group; ++i) {  // first FFN matrix + activation
-      Shard *s = group[i];
-      const Layout &L = s->L;
-      const bool glu = m.act == SS_ACT_SWIGLU;
-      SkinnyArgs a = {};
-      a.w = s->w1[l].ptr, a.tasks = L.Fs / 16, a.k_blocks = s->w1[l].k_blocks, a.B = B, a.N = L.Fs;
-      plan_skinny(&a, L.esz, L.splitk_bytes, glu ? 2 : 1);
-      a.x = xd, a.stats = stats, a.gamma = D0.ln2_g, a.beta = D0.ln2_b;
-      a.splitk = (float *)(s->ws + L.ws_splitk), a.counters = (int *)(s->ws + L.ws_counters);
-      a.bias = s->layers[l].b1, a.act_out = s->ws + L.ws_u, a.out_k_blocks = L.Fs / FK, a.act_kind = m.act;
-      Bracket br(g0, 4, st);
-      SS_TRY(launch_skinny(dt, PRO_NORM, glu ? EPI_SWIGLU : EPI_ACT, a, st));
-    }
-    for (int i = 0; i < n_group; ++i) {  // second FFN matrix, sum over the group, residual
-      Shard *s = group[i];
-      const Layout &L = s->L;
-      SkinnyArgs a = {};
-      a.w = s->w2[l].ptr, a.tasks = s->w2[l].row_tiles, a.k_blocks = s->w2[l].k_blocks, a.B = B, a.N = d;
-      plan_skinny(&a, L.esz, L.splitk_bytes, 1);
-      a.act = s->ws + L.ws_u;
-      a.splitk = (float *)(s->ws + L.ws_splitk), a.counters = (int *)(s->ws + L.ws_counters);
-      a.bias = i == 0 ? D0.b2 : nullptr;
-      a.x_resid = xd, a.stat_part = stat_part, a.stats_out = stats, a.rms = rms, a.eps = m.norm_eps;
-      Bracket br(g0, 3, st);
-      SS_TRY(launch_skinny(dt, PRO_ACT, EPI_RESID, a, st));
-    }
-    if (l == stop_after_layer) SS_FAIL(SS_EINTR, "decode step interrupted after layer %d; nothing committed", l);
-  }
-  Bracket br(g0, 5, st);
-  return lm_head(group, n_group, B, xd, stats, logits, next_tokens, 1, st);
+  std::vector<Phase> plan;
+  build_decode_plan(group, n_group, tokens_in, B, logits, next_tokens, stop_after_layer, 0, &plan);
+  for (const Phase &ph : plan) SS_TRY(launch_phase(group[0], ph, st));
+  if (stop_after_layer >= 0)
+    SS_FAIL(SS_EINTR, "decode step interrupted after layer %d; nothing committed", stop_after_layer);
+  return SS_OK;
 }
 
 void destroy_graphs(Shard *sh) {
@@ -289,16 +283,22 @@ void destroy_graphs(Shard *sh) {
 ss_status run_decode_step(Shard *const *group, int n_group, const int32_t *tokens_in, int B, float *logits,
                           int32_t *next_tokens, hipStream_t st, int stop_after_layer) {
   Shard *g0 = group[0];
-  // the NULL stream cannot be captured, and a stream the caller is capturing is left to the caller
-  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-  if (st) SS_HIP(hipStreamIsCapturing(st, &cs));
-  const bool graph = g0->use_graph && !g0->timing && stop_after_layer < 0 && st != nullptr &&
-                     cs == hipStreamCaptureStatusNone;
-  if (!graph) return enqueue_decode(group, n_group, tokens_in, B, logits, next_tokens, st, stop_after_layer);
   GraphKey key;
   key.B = B;
   key.ptrs = {tokens_in, logits, next_tokens, (const void *)st};
   for (int i = 0; i < n_group; ++i) key.ptrs.push_back(group[i]);
+  const bool plain = !g0->timing && stop_after_layer < 0;
+  if (plain && g0->use_persistent && n_group == 1 && persistent_supported(g0, B)) {
+    std::vector<Phase> plan;
+    if (!(g0->phases_valid && !(g0->phases_key < key) && !(key < g0->phases_key)))
+      build_decode_plan(group, n_group, tokens_in, B, logits, next_tokens, -1, 512, &plan);
+    return launch_persistent_step(g0, plan, key, st);
+  }
+  // the NULL stream cannot be captured, and a stream the caller is capturing is left to the caller
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  if (st) SS_HIP(hipStreamIsCapturing(st, &cs));
+  const bool graph = g0->use_graph && plain && st != nullptr && cs == hipStreamCaptureStatusNone;
+  if (!graph) return enqueue_decode(group, n_group, tokens_in, B, logits, next_tokens, st, stop_after_layer);
   auto it = g0->graphs.find(key);
   if (it == g0->graphs.end()) {
     hipGraph_t gr = nullptr;
@@ -338,13 +338,12 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, i
     if (T > group[i]->L.Tmax) SS_FAIL(SS_EINVAL, "%d prompt tokens exceed group[%d]'s workspace (%d)", T_live, i, group[i]->L.Tmax);
   float *x = (float *)(g0->ws + L0.ws_x);
   void *abuf = g0->ws + L0.ws_a;
-  if (dt == SS_DTYPE_BF16)
-    hipLaunchKernelGGL(embed_rows<bf16_t>, dim3(T_live), dim3(256), 0, st, tokens, (const bf16_t *)g0->wte,
-                       (const bf16_t *)g0->wpe, (const int32_t *)nullptr, S, x, (float *)nullptr, d, L0.V, rms, m.norm_eps);
-  else
-    hipLaunchKernelGGL(embed_rows<float>, dim3(T_live), dim3(256), 0, st, tokens, (const float *)g0->wte,
-                       (const float *)g0->wpe, (const int32_t *)nullptr, S, x, (float *)nullptr, d, L0.V, rms, m.norm_eps);
-  SS_HIP(hipGetLastError());
+  {
+    EmbedArgs e{tokens, g0->wte, g0->wpe, nullptr, S, x, nullptr, d, L0.V, rms, m.norm_eps};
+    if (dt == SS_DTYPE_BF16) hipLaunchKernelGGL(embed_rows<bf16_t>, dim3(T_live), dim3(256), 0, st, e);
+    else hipLaunchKernelGGL(embed_rows<float>, dim3(T_live), dim3(256), 0, st, e);
+    SS_HIP(hipGetLastError());
+  }
   auto norm = [&](const float *g, const float *b) -> ss_status {
     if (dt == SS_DTYPE_BF16)
       hipLaunchKernelGGL(norm_rows<bf16_t>, dim3(T_live), dim3(256), 0, st, x, g, b, abuf, d, d / FK, rms, m.norm_eps);
@@ -404,11 +403,12 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, i
       SS_TRY(launch_tile_gemm(dt, EPI_RESID, a, st));
     }
   }
-  float *xd = (float *)(g0->ws + L0.ws_y);
-  float *stats = (float *)(g0->ws + L0.ws_stats);
+  float *xd = xv(g0, 2 * L0.Ls);
+  float *stats = statv(g0, 2 * L0.Ls);
   hipLaunchKernelGGL(gather_last, dim3(B), dim3(256), 0, st, x, S, xd, stats, d, rms, m.norm_eps);
   SS_HIP(hipGetLastError());
-  return lm_head(group, n_group, B, xd, stats, logits, next_tokens, S, st);
+  const Phase ph = lm_head_phase(group, n_group, B, xd, stats, logits, next_tokens, S, 0);
+  return launch_skinny(dt, PRO_NORM, EPI_LOGITS, ph.g, st);
 }
 
 }  // namespace ss

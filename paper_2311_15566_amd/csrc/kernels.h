@@ -35,7 +35,9 @@ struct SkinnyArgs {
   const float *bias;
   float *out_f32;       // EPI_F32 / EPI_LOGITS: [B][ld_out]
   int ld_out;
-  float *x_resid;       // EPI_RESID: residual stream [B][N], updated in place
+  const float *x_in;    // EPI_RESID: residual stream before this GEMM, [B][N]
+  float *x_resid;       // EPI_RESID: residual stream after it (may equal x_in only when no other block of the
+                        // same launch reads it)
   float *stat_part;     // EPI_RESID: [groups][32][2]
   float *stats_out;     // EPI_RESID: [32][2]
   int rms;              // EPI_RESID: statistics for RMSNorm (no mean)
@@ -51,8 +53,10 @@ struct SkinnyArgs {
   int commit_inc;
 };
 ss_status launch_skinny(int dtype, int pro, int epi, const SkinnyArgs &a, hipStream_t st);
+ss_status check_skinny(int dtype, const SkinnyArgs &a);  // the shape checks launch_skinny makes
 // fills split / kb_per_split / lds_chunk / nb from the shape
-void plan_skinny(SkinnyArgs *a, int esz, size_t splitk_bytes, int tasks_rows16);
+// (target_blocks = 0: the default of the kernel-by-kernel path)
+void plan_skinny(SkinnyArgs *a, int esz, size_t splitk_bytes, int weight_tiles_per_wave, int target_blocks);
 
 // Prefill GEMM: out[t, n] = sum_k act[t, k] * W[n, k] over T tokens (multiple of 128), MFMA-bound.
 struct TileGemmArgs {
@@ -90,6 +94,30 @@ struct DecodeAttnArgs {
   int rows_per_block, splits;
 };
 ss_status launch_decode_attn(int dtype, const DecodeAttnArgs &a, hipStream_t st);
+ss_status check_decode_attn(const DecodeAttnArgs &a);
+
+// One phase of the decode step: a kernel of the kernel-by-kernel path, or one stretch between
+// two device-wide barriers of the persistent kernel.
+enum PhaseKind { PH_EMBED = 0, PH_QKV = 1, PH_ATTN = 2, PH_RESID = 3, PH_FFN_UP = 4, PH_LM_HEAD = 5 };
+struct EmbedArgs {
+  const int32_t *tokens;  // [rows]
+  const void *wte, *wpe;  // [V][d], [max_pos][d] or NULL
+  const int32_t *lens;    // decode: position = committed length; NULL: position = row % S
+  int S;
+  float *x;               // [rows][d]
+  float *stats;           // [rows][2] (mean, 1/std) of the first norm, or NULL
+  int d, V, rms;
+  float eps;
+};
+
+struct Phase {
+  int kind;      // PhaseKind; also the timing class
+  int gx, gy;    // blocks: (rows, 1), (groups, splits) or (batch*heads, splits)
+  int shard;     // index of the shard in the group that owns the phase's scratch
+  EmbedArgs e;
+  SkinnyArgs g;
+  DecodeAttnArgs at;
+};
 
 // Prefill: rotate q, k; write K/V rows [0, S) of every sequence; then causal attention.
 struct PrefillAttnArgs {

@@ -1,0 +1,56 @@
+// Matrix-core product and small device helpers shared by the GEMM kernels.
+#pragma once
+#include "common.h"
+
+namespace ss {
+
+// one 16 x 16 x FragK product per call: D[n][b] += sum_k W[n][k] * A[b][k]
+// lane l returns D[(l>>4)*4 + i][l & 15], i = 0..3
+template <typename T> struct Mma;
+template <> struct Mma<bf16_t> {
+  static __device__ __forceinline__ f32x4 mma(u32x4 w, u32x4 a, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, a), c, 0,
+                                                   0, 0);
+  }
+};
+template <> struct Mma<float> {
+  static __device__ __forceinline__ f32x4 mma(u32x4 w, u32x4 a, f32x4 c) {
+    f32x4 wf = __builtin_bit_cast(f32x4, w), af = __builtin_bit_cast(f32x4, a);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) c = __builtin_amdgcn_mfma_f32_16x16x4f32(wf[j], af[j], c, 0, 0, 0);
+    return c;
+  }
+};
+
+__device__ __forceinline__ float act_apply(int kind, float h) {
+  if (kind == SS_ACT_GELU_TANH) return 0.5f * h * (1.0f + tanhf(0.7978845608028654f * (h + 0.044715f * h * h * h)));
+  return fmaxf(h, 0.0f);  // SS_ACT_RELU
+}
+__device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)); }
+
+// Four consecutive activations (k a multiple of 4) into an operand buffer with `parts`
+// fragments per k block, as whole 32-bit words.  DEV: device-scope (write-through) stores, for
+// buffers another block of the same launch reads.
+template <typename T, bool DEV>
+__device__ __forceinline__ void store4_frag(void *base, int row, int k, int k_blocks, int parts, const float (&v)[4]) {
+  T hi[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) hi[i] = Elem<T>::from_f32(v[i]);
+#pragma unroll
+  for (int part = 0; part < 2; ++part) {
+    if (part >= parts) break;
+    T w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = part == 0 ? hi[i] : Elem<T>::from_f32(v[i] - Elem<T>::to_f32(hi[i]));
+    uint32_t words[sizeof(T)];  // 4 elements = sizeof(T) words
+    __builtin_memcpy(words, w, 4 * sizeof(T));
+    uint32_t *p = (uint32_t *)((T *)base + frag_offset_parts<T>(row, k, k_blocks, parts, part));
+#pragma unroll
+    for (int i = 0; i < (int)sizeof(T); ++i) {
+      if (DEV) st_dev(p + i, words[i]);
+      else p[i] = words[i];
+    }
+  }
+}
+
+}  // namespace ss

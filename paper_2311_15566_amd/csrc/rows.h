@@ -1,0 +1,108 @@
+// Row-wise device helpers: block reductions, the embedding of one row, norm statistics.
+#pragma once
+#include "kernels.h"
+
+namespace ss {
+
+// sum over a 256-thread block; every thread gets the result.  scratch: 4 floats of LDS.
+__device__ __forceinline__ float block_sum(float v, float *scratch) {
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) v += __shfl_xor(v, off);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return scratch[0] + scratch[1] + scratch[2] + scratch[3];
+}
+
+__device__ __forceinline__ void row_stats(const float *row, int d, int rms, float eps, float *scratch, float *mean_out,
+                                          float *rstd_out) {
+  float s = 0.f;
+  for (int k = threadIdx.x; k < d; k += 256) s += row[k];
+  const float mean = rms ? 0.f : block_sum(s, scratch) / (float)d;
+  float q = 0.f;
+  for (int k = threadIdx.x; k < d; k += 256) {
+    const float c = row[k] - mean;
+    q += c * c;
+  }
+  const float var = block_sum(q, scratch) / (float)d;
+  *mean_out = mean;
+  *rstd_out = rsqrtf(var + eps);
+}
+
+template <typename T>
+__device__ __forceinline__ void widen16(const u32x4 &raw, float *out);
+template <>
+__device__ __forceinline__ void widen16<float>(const u32x4 &raw, float *out) {
+  f32x4 f = __builtin_bit_cast(f32x4, raw);
+  out[0] = f[0], out[1] = f[1], out[2] = f[2], out[3] = f[3];
+}
+template <>
+__device__ __forceinline__ void widen16<bf16_t>(const u32x4 &raw, float *out) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    out[2 * i] = __uint_as_float(raw[i] << 16);
+    out[2 * i + 1] = __uint_as_float(raw[i] & 0xffff0000u);
+  }
+}
+
+// x[r] = wte[token] (+ wpe[position]) with 16-byte loads, the row held in registers for the
+// two-pass statistics.  d <= 16384.  DEV: device-scope stores (see the single-assignment rule).
+template <typename T, bool DEV>
+__device__ __forceinline__ void embed_row_block(const EmbedArgs &a, const int r, float *scratch) {
+  constexpr int PL = Elem<T>::kPerLane, MAXV = 64 / PL;
+  int tok = a.tokens[r];
+  tok = min(max(tok, 0), a.V - 1);
+  const int pos = a.lens ? a.lens[r] : (r % a.S);
+  const int nvec = a.d / PL;
+  const u32x4 *te = (const u32x4 *)((const T *)a.wte + (size_t)tok * a.d);
+  const u32x4 *pe = a.wpe ? (const u32x4 *)((const T *)a.wpe + (size_t)pos * a.d) : nullptr;
+  float vals[MAXV][PL];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < MAXV; ++i) {
+    const int v = threadIdx.x + i * 256;
+    if (v < nvec) {
+      widen16<T>(te[v], vals[i]);
+      if (pe) {
+        float p[PL];
+        widen16<T>(pe[v], p);
+#pragma unroll
+        for (int e = 0; e < PL; ++e) vals[i][e] += p[e];
+      }
+      float *xo = a.x + (size_t)r * a.d + (size_t)v * PL;
+#pragma unroll
+      for (int e = 0; e < PL; ++e) {
+        s += vals[i][e];
+        if (DEV) st_dev(xo + e, vals[i][e]);
+        else xo[e] = vals[i][e];
+      }
+    }
+  }
+  if (a.stats) {
+    const float mean = a.rms ? 0.f : block_sum(s, scratch) / (float)a.d;
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i) {
+      const int v = threadIdx.x + i * 256;
+      if (v < nvec) {
+#pragma unroll
+        for (int e = 0; e < PL; ++e) {
+          const float c = vals[i][e] - mean;
+          q += c * c;
+        }
+      }
+    }
+    const float var = block_sum(q, scratch) / (float)a.d;
+    if (threadIdx.x == 0) {
+      if (DEV) {
+        st_dev(&a.stats[r * 2], mean);
+        st_dev(&a.stats[r * 2 + 1], rsqrtf(var + a.eps));
+      } else {
+        a.stats[r * 2] = mean;
+        a.stats[r * 2 + 1] = rsqrtf(var + a.eps);
+      }
+    }
+  }
+}
+
+}  // namespace ss

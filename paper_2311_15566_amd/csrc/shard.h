@@ -1,6 +1,6 @@
 // Host object of one shard and the carve-up of its device memory.
 #pragma once
-#include "common.h"
+#include "kernels.h"
 
 namespace ss {
 
@@ -30,9 +30,18 @@ struct Layout {
   size_t off_kv, kv_bytes, off_len;
   size_t off_ws, ws_bytes;             // workspace, doubles as upload staging
   // workspace sub-offsets (relative to off_ws)
-  size_t ws_x, ws_a, ws_qkv, ws_o, ws_u, ws_splitk, splitk_bytes, ws_stats, ws_counters, ws_attn_part,
-      ws_argmax, ws_y;
+  size_t ws_x, ws_a, ws_qkv, ws_o, ws_u, ws_splitk, splitk_bytes, ws_stat_part, ws_counters, ws_attn_part,
+      ws_argmax;
   int n_counters;
+  // decode step: every buffer one block writes and another block of the same launch reads is
+  // written once per step (single-assignment rule), so each producer has its own
+  size_t ws_xv, xv_stride;        // residual stream versions: [2*Ls + 3][32][d] f32 (last two: group ping-pong)
+  size_t ws_statv;                // norm statistics per version: [2*Ls + 3][32][2]
+  size_t ws_qkv_l, qkv_l_stride;  // per layer: [32][qkv_n] f32
+  size_t ws_o_l, o_l_stride;      // per layer: attention output operand
+  size_t ws_u_l, u_l_stride;      // per layer: FFN activation operand
+  size_t ws_phases, phases_bytes; // the persistent kernel's phase table
+  size_t ws_bar;                  // grid-barrier state (int32 x 1024)
   size_t total;
 };
 
@@ -64,6 +73,10 @@ struct Shard {
   char *ws = nullptr;
   int interrupt_after = -1;
   bool use_graph = true;
+  bool use_persistent = true;
+  GraphKey phases_key;   // what the phase table on the device was built for
+  bool phases_valid = false;
+  std::vector<Phase> host_plan;
   std::map<GraphKey, hipGraphExec_t> graphs;
   // per-kernel-class event timing (measurement aid)
   bool timing = false;
@@ -87,5 +100,10 @@ ss_status run_decode_step(Shard *const *group, int n_group, const int32_t *token
 ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, int B, int S_in, float *logits,
                       int32_t *next_tokens, hipStream_t st);
 void destroy_graphs(Shard *sh);
+
+// step.hip: the whole decode step as one persistent kernel (bf16, head_dim 128, one shard)
+bool persistent_supported(const Shard *sh, int B);
+ss_status launch_persistent_step(Shard *sh, const std::vector<Phase> &plan, const GraphKey &key, hipStream_t st);
+ss_status persistent_check_abort(const Shard *sh, hipStream_t st);
 
 }  // namespace ss

@@ -29,7 +29,8 @@ ss_status validate_desc(const ss_model_desc &m, const ss_slice &s, int max_batch
   if (m.n_layers <= 0 || m.d_model <= 0 || m.n_heads <= 0 || m.ffn <= 0 || m.vocab <= 0)
     SS_FAIL(SS_EINVAL, "model descriptor has a non-positive dimension");
   if (m.head_dim != 64 && m.head_dim != 128) SS_FAIL(SS_EINVAL, "head_dim must be 64 or 128 (got %d)", m.head_dim);
-  if (m.d_model % 64) SS_FAIL(SS_EINVAL, "d_model must be a multiple of 64 (got %d)", m.d_model);
+  if (m.d_model % 64 || m.d_model > 16384)
+    SS_FAIL(SS_EINVAL, "d_model must be a multiple of 64, at most 16384 (got %d)", m.d_model);
   if (m.dtype != SS_DTYPE_F32 && m.dtype != SS_DTYPE_BF16) SS_FAIL(SS_EINVAL, "unknown dtype %d", m.dtype);
   if (m.dtype == SS_DTYPE_F32 ? m.kv_dtype != SS_DTYPE_F32 : (m.kv_dtype != SS_DTYPE_F16 && m.kv_dtype != SS_DTYPE_BF16))
     SS_FAIL(SS_EINVAL, "kv_dtype %d does not go with dtype %d", m.kv_dtype, m.dtype);
@@ -123,10 +124,24 @@ bool compute_layout(const ss_model_desc &m, const ss_slice &s, int max_batch, in
   L->ws_qkv = wtake((size_t)T * L->qkv_n * 4);
   L->ws_o = wtake((size_t)T * HD * esz * (esz == 2 ? 2 : 1));
   L->ws_u = wtake((size_t)T * L->Fs * esz * (esz == 2 ? 2 : 1));
-  L->ws_y = wtake((size_t)L->Bpad * d * 4);  // residual stream of the decode step
+  {
+    const int fk = esz == 2 ? 32 : 16, parts = esz == 2 ? 2 : 1;
+    L->xv_stride = align_up((size_t)32 * d * 4, 256);
+    L->ws_xv = wtake(L->xv_stride * (2 * L->Ls + 3));
+    L->ws_statv = wtake((size_t)(2 * L->Ls + 3) * 64 * 4);
+    L->qkv_l_stride = align_up((size_t)32 * L->qkv_n * 4, 256);
+    L->ws_qkv_l = wtake(L->qkv_l_stride * L->Ls);
+    L->o_l_stride = (size_t)2 * (HD / fk) * parts * 1024;
+    L->ws_o_l = wtake(L->o_l_stride * L->Ls);
+    L->u_l_stride = (size_t)2 * (L->Fs / fk) * parts * 1024;
+    L->ws_u_l = wtake(L->u_l_stride * L->Ls);
+    L->phases_bytes = (size_t)(5 * L->Ls + 2) * 1024;
+    L->ws_phases = wtake(L->phases_bytes);
+    L->ws_bar = wtake((size_t)1024 * 4);
+  }
   L->splitk_bytes = std::min<size_t>((size_t)64 << 20, (size_t)16 * L->Bpad * nmax * 4);
   L->ws_splitk = wtake(L->splitk_bytes);
-  L->ws_stats = wtake((size_t)64 * 4 + (size_t)ceil_div(d, 64) * 32 * 2 * 4);
+  L->ws_stat_part = wtake((size_t)ceil_div(d, 64) * 32 * 2 * 4);
   L->n_counters = 8 + ceil_div(nmax, 64) + max_batch * L->Hs;
   L->ws_counters = wtake((size_t)L->n_counters * 4);
   L->ws_attn_part = wtake((size_t)max_batch * L->Hs * L->attn_splits * (L->Dh + 4) * 4);
@@ -412,6 +427,7 @@ ss_status ss_shard_create(const ss_model_desc *desc, const ss_slice *slice, cons
     hipLaunchKernelGGL(fill_i32, dim3(1), dim3(32), 0, st, sh->d_len, 32, 0);
     int nc = L.n_counters;
     hipLaunchKernelGGL(fill_i32, dim3(ceil_div(nc, 256)), dim3(256), 0, st, (int32_t *)(sh->ws + L.ws_counters), nc, 0);
+    hipLaunchKernelGGL(fill_i32, dim3(4), dim3(256), 0, st, (int32_t *)(sh->ws + L.ws_bar), 1024, 0);
     hipError_t e = hipStreamSynchronize(st);
     if (e != hipSuccess) {
       set_error("shard creation: %s", hipGetErrorString(e));
@@ -448,6 +464,7 @@ ss_status ss_committed_len(const ss_shard *shard, int32_t *out_host, void *hip_s
   const Shard *sh = (const Shard *)shard;
   SS_HIP(hipMemcpyAsync(out_host, sh->d_len, sh->L.Bmax * 4, hipMemcpyDeviceToHost, (hipStream_t)hip_stream));
   SS_HIP(hipStreamSynchronize((hipStream_t)hip_stream));
+  SS_TRY(persistent_check_abort(sh, (hipStream_t)hip_stream));
   return SS_OK;
 }
 
@@ -463,6 +480,12 @@ ss_status ss_debug_interrupt_after_layer(ss_shard *shard, int32_t layer) {
   Shard *sh = (Shard *)shard;
   if (layer < -1 || layer >= sh->L.Ls) SS_FAIL(SS_EINVAL, "layer %d outside the shard's %d layers", layer, sh->L.Ls);
   sh->interrupt_after = layer;
+  return SS_OK;
+}
+
+ss_status ss_set_persistent(ss_shard *shard, int32_t enabled) {
+  if (!shard) SS_FAIL(SS_EINVAL, "NULL shard");
+  ((Shard *)shard)->use_persistent = enabled != 0;
   return SS_OK;
 }
 

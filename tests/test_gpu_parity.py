@@ -54,6 +54,11 @@ def array_to_canonical(arr, lens):
     return np.concatenate(parts)
 
 
+def bits(a):
+    """Raw bit patterns of an exported cache (comparisons must not go through float semantics)."""
+    return a.view(np.uint16) if a.dtype.itemsize == 2 else a.view(np.uint32)
+
+
 def check_logits(got, ref, bf16, what=""):
     ref = np.asarray(ref, dtype=np.float64)
     got = np.asarray(got, dtype=np.float64)
@@ -182,14 +187,26 @@ def test_scaled_family_teacher_forced(ss, name, dtype, kw, side_stream):
     sh.destroy()
 
 
-def test_decode_is_deterministic_and_graph_equals_eager(ss, side_stream):
+@pytest.mark.parametrize("name,kw", [
+    ("llama30b_m2", dict(batch=9, s_in=40, steps=5)),                                        # head_dim 64: no persistent kernel
+    ("llama30b_m2", dict(batch=9, s_in=140, steps=6, head_dim=128, n_heads=4, d_model=512)),
+    ("opt66b_m8", dict(batch=32, s_in=33, steps=4, d_model=448, ffn=1152, head_dim=128, n_heads=2)),
+    ("gpt20b_m4", dict(batch=5, s_in=70, steps=4, head_dim=128, n_heads=4, kv_dtype="bf16")),
+])
+def test_launch_modes_are_bit_identical(ss, side_stream, name, kw):
+    """Persistent kernel, graph replay and kernel-by-kernel launches give the same bits, run after run."""
     import torch
-    w = scaled("llama30b_m2", "bf16", batch=9, s_in=40, steps=5)
+    kw = dict(kw)
+    kv_dtype = kw.pop("kv_dtype", None)
+    w = scaled(name, "bf16", **kw)
+    if kv_dtype:
+        w.desc["kv_dtype"] = kv_dtype
     W = make_weights(w.desc, w.slice, w.seed)
     toks = make_tokens(w.seed, w.batch, w.s_in, w.desc["vocab"])
     outs = []
-    for graph in (False, True, True):
+    for persistent, graph in ((False, False), (False, True), (True, True), (True, True)):
         sh = ss.Shard(w.desc, w.slice, W, w.batch, w.s_max)
+        sh.set_persistent(persistent)
         sh.set_graph_launch(graph)
         logits = torch.empty(w.batch, w.desc["vocab"], dtype=torch.float32, device="cuda")
         nxt = torch.empty(w.batch, dtype=torch.int32, device="cuda")
@@ -199,13 +216,13 @@ def test_decode_is_deterministic_and_graph_equals_eager(ss, side_stream):
             ss.decode_step([sh], nxt, logits, nxt)
             torch.cuda.synchronize()
             run.append(logits.cpu().numpy().copy())
+        assert list(ss.committed_len(sh)) == [w.s_in + w.steps] * w.batch
         run.append(bits(ss.kv_export(sh)))
         outs.append(run)
         sh.destroy()
-    for a, b in zip(outs[0], outs[1]):
-        assert np.array_equal(a, b)
-    for a, b in zip(outs[1], outs[2]):
-        assert np.array_equal(a, b)
+    for other in outs[1:]:
+        for a, b in zip(outs[0], other):
+            assert np.array_equal(a, b)
 
 
 def test_ragged_lengths_and_row_independence(ss):
@@ -237,11 +254,6 @@ def test_ragged_lengths_and_row_independence(ss):
 # ----------------------------------------------------------------------------
 # KV re-partition: bit-exact against the index formula
 # ----------------------------------------------------------------------------
-def bits(a):
-    """Raw bit patterns of an exported cache (comparisons must not go through float semantics)."""
-    return a.view(np.uint16) if a.dtype.itemsize == 2 else a.view(np.uint32)
-
-
 @pytest.mark.parametrize("dtype,kv_dtype", [("bf16", "f16"), ("bf16", "bf16"), ("f32", "f32")])
 def test_repack_split_merge_bit_exact(ss, dtype, kv_dtype):
     w = scaled("llama30b_m2", dtype, n_heads=8, head_dim=128, d_model=256, ffn=256, layers=2, M=2, m=1,
