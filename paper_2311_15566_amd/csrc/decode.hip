@@ -1,5 +1,7 @@
 // The decode step and the initial phase: row kernels (embedding, norms) and the launch
 // sequence over a group of co-resident shards, with HIP-graph replay of the decode step.
+#include <stdlib.h>
+
 #include <algorithm>
 
 #include "kernels.h"
@@ -74,12 +76,13 @@ static ss_status check_group(Shard *const *group, int n_group, int B) {
   return SS_OK;
 }
 
-static void attn_plan(const Layout &L, int B, int *rows_per_block, int *splits) {
+static void attn_plan(const Layout &L, int B, int max_rows, int *rows_per_block, int *splits) {
   // enough blocks to fill 256 CUs a few times over, at least 64 rows per block; the partial
   // buffer holds ceil(Smax/64) splits
   const int pairs = std::max(1, B * L.Hs);
   const int want = std::max(1, std::min(ceil_div(1024, pairs), L.attn_splits));
-  const int rpb = (int)align_up((size_t)ceil_div(L.Smax, want), 64);
+  int rpb = (int)align_up((size_t)ceil_div(L.Smax, want), 64);
+  if (max_rows > 0 && rpb > max_rows) rpb = max_rows;
   *rows_per_block = rpb;
   *splits = ceil_div(L.Smax, rpb);
 }
@@ -103,11 +106,11 @@ static Phase lm_head_phase(Shard *const *group, int n_group, int B, const float 
   a.splitk = (float *)(g0->ws + L.ws_splitk), a.counters = (int *)(g0->ws + L.ws_counters);
   a.out_f32 = logits, a.ld_out = L.V;
   a.am_val = (float *)(g0->ws + L.ws_argmax);
-  a.am_idx = (int *)(a.am_val + (size_t)ceil_div(a.tasks, 4) * 32);
+  a.am_idx = (int *)(a.am_val + (size_t)ceil_div(a.tasks, 3) * 32);
   a.next_tokens = next_tokens;
   for (int i = 0; i < n_group; ++i) a.lens[i] = group[i]->d_len;
   a.n_lens = n_group, a.commit_inc = commit_inc;
-  ph.gx = ceil_div(a.tasks, 4), ph.gy = a.split;
+  ph.gx = ceil_div(a.tasks, target_blocks < 0 ? 3 : 4), ph.gy = a.split;
   return ph;
 }
 
@@ -146,7 +149,7 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
     a.x_in = xv(g0, i == 0 ? v_in : pp0 + ((i - 1) & 1));
     a.x_resid = xv(g0, i == n_group - 1 ? v_out : pp0 + (i & 1));
     a.stat_part = stat_part, a.stats_out = statv(g0, v_out), a.rms = rms, a.eps = m.norm_eps;
-    ph.gx = ceil_div(a.tasks, 4), ph.gy = a.split;
+    ph.gx = ceil_div(a.tasks, target_blocks < 0 ? 3 : 4), ph.gy = a.split;
     (void)l;
     plan->push_back(ph);
   };
@@ -163,7 +166,7 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
       a.x = xv(g0, 2 * l), a.stats = statv(g0, 2 * l), a.gamma = D0.ln1_g, a.beta = D0.ln1_b;
       a.splitk = (float *)(s->ws + L.ws_splitk), a.counters = (int *)(s->ws + L.ws_counters);
       a.bias = s->layers[l].bqkv, a.out_f32 = (float *)(s->ws + L.ws_qkv_l + l * L.qkv_l_stride), a.ld_out = L.qkv_n;
-      ph.gx = ceil_div(a.tasks, 4), ph.gy = a.split;
+      ph.gx = ceil_div(a.tasks, target_blocks < 0 ? 3 : 4), ph.gy = a.split;
       plan->push_back(ph);
     }
     for (int i = 0; i < n_group; ++i) {  // attention over the committed rows + append
@@ -180,7 +183,7 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
       a.counters = (int *)(s->ws + L.ws_counters) + (L.n_counters - L.Bmax * L.Hs);
       a.o_out = s->ws + L.ws_o_l + l * L.o_l_stride;
       a.B = B, a.Hs = L.Hs, a.Dh = L.Dh, a.Smax = L.Smax, a.kv_dtype = s->m.kv_dtype;
-      attn_plan(L, B, &a.rows_per_block, &a.splits);
+      attn_plan(L, B, target_blocks < 0 ? 192 : 0, &a.rows_per_block, &a.splits);
       ph.gx = B * L.Hs, ph.gy = a.splits;
       plan->push_back(ph);
     }
@@ -200,7 +203,7 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
       a.splitk = (float *)(s->ws + L.ws_splitk), a.counters = (int *)(s->ws + L.ws_counters);
       a.bias = s->layers[l].b1, a.act_out = s->ws + L.ws_u_l + l * L.u_l_stride, a.out_k_blocks = L.Fs / FK;
       a.act_kind = m.act;
-      ph.gx = ceil_div(a.tasks, 4), ph.gy = a.split;
+      ph.gx = ceil_div(a.tasks, target_blocks < 0 ? 3 : 4), ph.gy = a.split;
       plan->push_back(ph);
     }
     for (int i = 0; i < n_group; ++i)  // second FFN matrix, sum over the group, residual
@@ -288,11 +291,22 @@ ss_status run_decode_step(Shard *const *group, int n_group, const int32_t *token
   key.ptrs = {tokens_in, logits, next_tokens, (const void *)st};
   for (int i = 0; i < n_group; ++i) key.ptrs.push_back(group[i]);
   const bool plain = !g0->timing && stop_after_layer < 0;
-  if (plain && g0->use_persistent && n_group == 1 && persistent_supported(g0, B)) {
+  static const int persistent_version = [] {
+    const char *v = getenv("SS_PERSISTENT");
+    return v && *v ? atoi(v) : 2;
+  }();
+  if (plain && g0->use_persistent && n_group == 1 && persistent_version > 0) {
+    const bool cached = g0->phases_valid && !(g0->phases_key < key) && !(key < g0->phases_key);
     std::vector<Phase> plan;
-    if (!(g0->phases_valid && !(g0->phases_key < key) && !(key < g0->phases_key)))
-      build_decode_plan(group, n_group, tokens_in, B, logits, next_tokens, -1, 512, &plan);
-    return launch_persistent_step(g0, plan, key, st);
+    const int blocks2 = persistent_version >= 2 ? persistent2_blocks(g0, B) : 0;
+    if (blocks2 > 0) {
+      if (!cached) build_decode_plan(group, n_group, tokens_in, B, logits, next_tokens, -1, -blocks2, &plan);
+      return launch_persistent2_step(g0, plan, key, st);
+    }
+    if (persistent_supported(g0, B)) {
+      if (!cached) build_decode_plan(group, n_group, tokens_in, B, logits, next_tokens, -1, 512, &plan);
+      return launch_persistent_step(g0, plan, key, st);
+    }
   }
   // the NULL stream cannot be captured, and a stream the caller is capturing is left to the caller
   hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;

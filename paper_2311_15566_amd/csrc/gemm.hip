@@ -29,14 +29,39 @@ static int env_int(const char *name, int dflt) {
 
 void plan_skinny(SkinnyArgs *a, int esz, size_t splitk_bytes, int nw, int target) {
   a->nb = a->B <= 16 ? 1 : 2;
+  const int parts = esz == 2 ? 2 : 1;                                   // bf16 activations are hi/lo pairs
+  const size_t per_split = (size_t)a->nb * 16 * a->tasks * nw * 16 * 4;
+  if (target < 0) {
+    // persistent kernel: 3 compute waves per block, a wave holds at most 32 fragments in
+    // registers, the block's activations must fit 64 KiB of LDS.  Choose the number of K
+    // splits that minimises (rounds over the resident blocks) x (fragments per round + a
+    // per-item overhead).
+    const int nblocks = -target;
+    const int groups = ceil_div(a->tasks, 3);
+    const int max_kb = std::max(1, std::min(32 / nw, (a->nb == 1 ? 64 : 56) / (a->nb * parts)));
+    int best_s = 0;
+    long best_cost = 0;
+    for (int s = ceil_div(a->k_blocks, max_kb); s <= a->k_blocks; ++s) {
+      if (s > 1 && per_split * s > splitk_bytes) break;
+      const int kb = ceil_div(a->k_blocks, s);
+      if (ceil_div(a->k_blocks, kb) != s) continue;  // same split count as a smaller s
+      const long rounds = ceil_div(groups * s, nblocks);
+      const long cost = rounds * (kb * nw + 8);
+      if (!best_s || cost < best_cost) best_s = s, best_cost = cost;
+      if (kb <= 4) break;
+    }
+    if (!best_s) best_s = ceil_div(a->k_blocks, max_kb);
+    a->kb_per_split = ceil_div(a->k_blocks, best_s);
+    a->split = ceil_div(a->k_blocks, a->kb_per_split);
+    a->lds_chunk = a->kb_per_split;
+    return;
+  }
   const int groups = ceil_div(a->tasks, 4);
   static const int dflt_blocks = env_int("SS_SKINNY_BLOCKS", 512);  // 2 blocks per compute unit
   const int target_blocks = target > 0 ? target : dflt_blocks;
   static const int lds_kb = env_int("SS_SKINNY_LDS_KB", 64);
-  const int parts = esz == 2 ? 2 : 1;                                   // bf16 activations are hi/lo pairs
   const int max_chunk = std::max(16, lds_kb / (a->nb * parts) / 16 * 16);  // k blocks staged at a time, multiple of 16
   int split = std::max(1, std::min(target_blocks / std::max(groups, 1), a->k_blocks / 4));
-  const size_t per_split = (size_t)a->nb * 16 * a->tasks * nw * 16 * 4;
   while (split > 1 && per_split * split > splitk_bytes) --split;
   a->kb_per_split = ceil_div(a->k_blocks, split);
   a->split = ceil_div(a->k_blocks, a->kb_per_split);

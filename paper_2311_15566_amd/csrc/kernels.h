@@ -55,7 +55,8 @@ struct SkinnyArgs {
 ss_status launch_skinny(int dtype, int pro, int epi, const SkinnyArgs &a, hipStream_t st);
 ss_status check_skinny(int dtype, const SkinnyArgs &a);  // the shape checks launch_skinny makes
 // fills split / kb_per_split / lds_chunk / nb from the shape
-// (target_blocks = 0: the default of the kernel-by-kernel path)
+// (target_blocks = 0: the default of the kernel-by-kernel path; < 0: plan for the persistent kernel
+// with -target_blocks resident blocks)
 void plan_skinny(SkinnyArgs *a, int esz, size_t splitk_bytes, int weight_tiles_per_wave, int target_blocks);
 
 // Prefill GEMM: out[t, n] = sum_k act[t, k] * W[n, k] over T tokens (multiple of 128), MFMA-bound.

@@ -103,6 +103,9 @@ void destroy_graphs(Shard *sh);
 
 // step.hip: the whole decode step as one persistent kernel (bf16, head_dim 128, one shard)
 bool persistent_supported(const Shard *sh, int B);
+// step2.hip: the wave-specialised persistent kernel; resident blocks, or 0 if unsupported
+int persistent2_blocks(const Shard *sh, int B);
+ss_status launch_persistent2_step(Shard *sh, const std::vector<Phase> &plan, const GraphKey &key, hipStream_t st);
 ss_status launch_persistent_step(Shard *sh, const std::vector<Phase> &plan, const GraphKey &key, hipStream_t st);
 ss_status persistent_check_abort(const Shard *sh, hipStream_t st);
 

@@ -141,11 +141,11 @@ bool compute_layout(const ss_model_desc &m, const ss_slice &s, int max_batch, in
   }
   L->splitk_bytes = std::min<size_t>((size_t)64 << 20, (size_t)16 * L->Bpad * nmax * 4);
   L->ws_splitk = wtake(L->splitk_bytes);
-  L->ws_stat_part = wtake((size_t)ceil_div(d, 64) * 32 * 2 * 4);
-  L->n_counters = 8 + ceil_div(nmax, 64) + max_batch * L->Hs;
+  L->ws_stat_part = wtake((size_t)(ceil_div(d, 48) + 8) * 32 * 2 * 4);
+  L->n_counters = 16 + ceil_div(nmax, 48) + max_batch * L->Hs;
   L->ws_counters = wtake((size_t)L->n_counters * 4);
   L->ws_attn_part = wtake((size_t)max_batch * L->Hs * L->attn_splits * (L->Dh + 4) * 4);
-  L->ws_argmax = wtake((size_t)ceil_div(nmax, 64) * 32 * 8);
+  L->ws_argmax = wtake((size_t)(ceil_div(nmax, 48) + 8) * 32 * 8);
   // upload staging shares the workspace: it must hold the largest raw tensor slice
   size_t stage = std::max((size_t)L->V * d, (size_t)d * std::max(std::max(HD, L->Fs), 1)) * esz;
   L->ws_bytes = std::max(w, align_up(stage, 256));
