@@ -292,8 +292,10 @@ ss_status run_decode_step(Shard *const *group, int n_group, const int32_t *token
   for (int i = 0; i < n_group; ++i) key.ptrs.push_back(group[i]);
   const bool plain = !g0->timing && stop_after_layer < 0;
   static const int persistent_version = [] {
+    // 0: graph / kernel-by-kernel (default); 1: persistent kernel; 2: wave-specialised persistent
+    // kernel (switched off: a full-size run of it ended in a GPU fault whose cause is not yet known)
     const char *v = getenv("SS_PERSISTENT");
-    return v && *v ? atoi(v) : 2;
+    return v && *v ? atoi(v) : 0;
   }();
   if (plain && g0->use_persistent && n_group == 1 && persistent_version > 0) {
     const bool cached = g0->phases_valid && !(g0->phases_key < key) && !(key < g0->phases_key);
