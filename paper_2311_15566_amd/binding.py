@@ -170,8 +170,9 @@ class Shard:
     def interrupt_after_layer(self, layer: int):
         _check(lib.ss_debug_interrupt_after_layer(self.handle, layer))
 
-    def set_persistent(self, enabled: bool):
-        _check(lib.ss_set_persistent(self.handle, int(enabled)))
+    def set_persistent(self, mode: int):
+        """0 off, 1 block-body persistent kernel, 2 wave-specialised persistent kernel, -1 process default."""
+        _check(lib.ss_set_persistent(self.handle, int(mode)))
 
     def set_graph_launch(self, enabled: bool):
         _check(lib.ss_set_graph_launch(self.handle, int(enabled)))

@@ -1,6 +1,7 @@
 // The decode step and the initial phase: row kernels (embedding, norms) and the launch
 // sequence over a group of co-resident shards, with HIP-graph replay of the decode step.
 #include <stdlib.h>
+#include <string.h>
 
 #include <algorithm>
 
@@ -291,13 +292,14 @@ ss_status run_decode_step(Shard *const *group, int n_group, const int32_t *token
   key.ptrs = {tokens_in, logits, next_tokens, (const void *)st};
   for (int i = 0; i < n_group; ++i) key.ptrs.push_back(group[i]);
   const bool plain = !g0->timing && stop_after_layer < 0;
-  static const int persistent_version = [] {
+  static const int persistent_default = [] {
     // 0: graph / kernel-by-kernel (default); 1: persistent kernel; 2: wave-specialised persistent
     // kernel (switched off: a full-size run of it ended in a GPU fault whose cause is not yet known)
     const char *v = getenv("SS_PERSISTENT");
     return v && *v ? atoi(v) : 0;
   }();
-  if (plain && g0->use_persistent && n_group == 1 && persistent_version > 0) {
+  const int persistent_version = g0->persistent_mode >= 0 ? g0->persistent_mode : persistent_default;
+  if (plain && n_group == 1 && persistent_version > 0) {
     const bool cached = g0->phases_valid && !(g0->phases_key < key) && !(key < g0->phases_key);
     std::vector<Phase> plan;
     const int blocks2 = persistent_version >= 2 ? persistent2_blocks(g0, B) : 0;
@@ -448,6 +450,51 @@ ss_status ss_prefill(ss_shard *const *group_, int32_t n_group, const int32_t *to
   for (int i = 0; i < n_group; ++i)
     for (int b = 0; b < B; ++b) group[i]->h_len[b] = S_in;
   return SS_OK;
+}
+
+// Host-only check aid: the phase table of one decode step for a shard of the given shape whose
+// device memory starts at address `fake_base` (nothing is allocated or launched).  Writes up to
+// max_phases Phase records to out_phases, the layout's total bytes to out_total, returns the
+// number of phases (negative on error).  mode: 0 kernel-by-kernel plan, > 0 resident blocks of
+// the persistent kernel (1: block bodies, 2: wave-specialised).
+int32_t ss_debug_plan(const ss_model_desc *desc, const ss_slice *slice, int32_t max_batch, int32_t max_seq, int32_t B,
+                      int32_t mode, int32_t blocks, uint64_t fake_base, void *out_phases, int32_t max_phases,
+                      uint64_t *out_total, uint64_t *out_sizeof_phase) {
+  if (!desc || !slice || validate_desc(*desc, *slice, max_batch, max_seq) != SS_OK) return -1;
+  Shard sh;
+  sh.m = *desc, sh.s = *slice;
+  compute_layout(*desc, *slice, max_batch, max_seq, &sh.L);
+  const Layout &L = sh.L;
+  sh.base = (char *)fake_base;
+  sh.wte = sh.base + L.off_wte, sh.wpe = L.max_pos ? sh.base + L.off_wpe : nullptr;
+  sh.lnf_g = (float *)(sh.base + L.off_lnf_g), sh.lnf_b = (float *)(sh.base + L.off_lnf_b);
+  sh.rope = (float2 *)(sh.base + L.off_rope), sh.kv = sh.base + L.off_kv, sh.d_len = (int32_t *)(sh.base + L.off_len);
+  sh.ws = sh.base + L.off_ws;
+  const int FK = desc->dtype == SS_DTYPE_BF16 ? 32 : 16, d = L.d, HD = L.Hs * L.Dh;
+  sh.lm_head = FragMat{sh.base + L.off_lm, L.V, d, ceil_div(L.V, 16), d / FK};
+  sh.layers.resize(L.Ls), sh.wqkv.resize(L.Ls), sh.wo.resize(L.Ls), sh.w1.resize(L.Ls), sh.w2.resize(L.Ls);
+  for (int l = 0; l < L.Ls; ++l) {
+    char *lb = sh.base + L.off_layer[l];
+    sh.wqkv[l] = FragMat{lb + L.lo_wqkv, L.qkv_n, d, L.qkv_n / 16, d / FK};
+    sh.wo[l] = FragMat{lb + L.lo_wo, d, HD, d / 16, HD / FK};
+    sh.w1[l] = FragMat{lb + L.lo_w1, L.w1_rows, d, L.w1_rows / 16, d / FK};
+    sh.w2[l] = FragMat{lb + L.lo_w2, d, L.Fs, d / 16, L.Fs / FK};
+    LayerDev &D = sh.layers[l];
+    D.ln1_g = (float *)(lb + L.lo_ln1_g), D.ln1_b = (float *)(lb + L.lo_ln1_b);
+    D.ln2_g = (float *)(lb + L.lo_ln2_g), D.ln2_b = (float *)(lb + L.lo_ln2_b);
+    D.bqkv = (float *)(lb + L.lo_bqkv), D.bo = (float *)(lb + L.lo_bo), D.b1 = (float *)(lb + L.lo_b1),
+    D.b2 = (float *)(lb + L.lo_b2);
+  }
+  Shard *group[1] = {&sh};
+  std::vector<Phase> plan;
+  build_decode_plan(group, 1, (const int32_t *)8, B, (float *)16, (int32_t *)24, -1, mode == 0 ? 0 : (mode == 1 ? blocks : -blocks),
+                    &plan);
+  if (out_total) *out_total = L.total;
+  if (out_sizeof_phase) *out_sizeof_phase = sizeof(Phase);
+  const int n = (int)plan.size();
+  if (out_phases)
+    for (int i = 0; i < n && i < max_phases; ++i) memcpy((char *)out_phases + (size_t)i * sizeof(Phase), &plan[i], sizeof(Phase));
+  return n;
 }
 
 ss_status ss_kernel_timing(ss_shard *shard, int32_t enabled) {

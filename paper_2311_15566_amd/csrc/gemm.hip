@@ -32,28 +32,30 @@ void plan_skinny(SkinnyArgs *a, int esz, size_t splitk_bytes, int nw, int target
   const int parts = esz == 2 ? 2 : 1;                                   // bf16 activations are hi/lo pairs
   const size_t per_split = (size_t)a->nb * 16 * a->tasks * nw * 16 * 4;
   if (target < 0) {
-    // persistent kernel: 3 compute waves per block, a wave holds at most 32 fragments in
-    // registers, the block's activations must fit 64 KiB of LDS.  Choose the number of K
-    // splits that minimises (rounds over the resident blocks) x (fragments per round + a
-    // per-item overhead).
+    // persistent kernel: 3 compute waves per block; a wave holds at most 32 fragments in
+    // registers and the block's staged activations must fit its LDS, so a block walks its K
+    // range in chunks of at most max_kb k blocks (accumulating in registers) and K may also be
+    // split across blocks (partials through memory, last arriver reduces).  Cost in units of one
+    // fragment per wave: rounds over the resident blocks x (chunks x (fragments + staging) +
+    // hand-off), the hand-off dearer when partials go through memory.
     const int nblocks = -target;
     const int groups = ceil_div(a->tasks, 3);
     const int max_kb = std::max(1, std::min(32 / nw, (a->nb == 1 ? 64 : 56) / (a->nb * parts)));
-    int best_s = 0;
-    long best_cost = 0;
-    for (int s = ceil_div(a->k_blocks, max_kb); s <= a->k_blocks; ++s) {
+    int best_s = 1, best_chunk = std::min(max_kb, a->k_blocks);
+    long best_cost = -1;
+    for (int s = 1; s <= std::max(1, a->k_blocks / 4); ++s) {
       if (s > 1 && per_split * s > splitk_bytes) break;
-      const int kb = ceil_div(a->k_blocks, s);
-      if (ceil_div(a->k_blocks, kb) != s) continue;  // same split count as a smaller s
+      const int kbps = ceil_div(a->k_blocks, s);
+      if (ceil_div(a->k_blocks, kbps) != s) continue;  // same split count as a smaller s
+      const int chunks = ceil_div(kbps, max_kb);
+      const int lc = ceil_div(kbps, chunks);
       const long rounds = ceil_div(groups * s, nblocks);
-      const long cost = rounds * (kb * nw + 8);
-      if (!best_s || cost < best_cost) best_s = s, best_cost = cost;
-      if (kb <= 4) break;
+      const long cost = rounds * ((long)chunks * (lc * nw + 6) + (s > 1 ? 8 + a->B / 8 : 3));
+      if (best_cost < 0 || cost < best_cost) best_s = s, best_chunk = lc, best_cost = cost;
     }
-    if (!best_s) best_s = ceil_div(a->k_blocks, max_kb);
     a->kb_per_split = ceil_div(a->k_blocks, best_s);
     a->split = ceil_div(a->k_blocks, a->kb_per_split);
-    a->lds_chunk = a->kb_per_split;
+    a->lds_chunk = best_chunk;
     return;
   }
   const int groups = ceil_div(a->tasks, 4);
@@ -83,7 +85,7 @@ ss_status check_skinny(int dtype, const SkinnyArgs &a) {
   if (a.B < 1 || a.B > 32 || a.nb != (a.B <= 16 ? 1 : 2)) SS_FAIL(SS_EINVAL, "skinny GEMM: batch %d / tiles %d", a.B, a.nb);
   if (a.tasks < 1 || a.k_blocks < 1 || a.split < 1 || a.kb_per_split < 1 || a.lds_chunk < 1 ||
       (size_t)a.split * a.kb_per_split < (size_t)a.k_blocks || a.lds_chunk * a.nb * (dtype == SS_DTYPE_BF16 ? 2 : 1) > 64 ||
-      (a.lds_chunk < a.kb_per_split && a.lds_chunk % 16))
+      a.lds_chunk > a.kb_per_split)
     SS_FAIL(SS_EINVAL, "skinny GEMM: inconsistent plan");
   return SS_OK;
 }
@@ -93,6 +95,7 @@ ss_status launch_skinny(int dtype, int pro, int epi, const SkinnyArgs &a, hipStr
                         (pro == PRO_ACT && epi == EPI_RESID);
   if (!ok_combo) SS_FAIL(SS_EINVAL, "skinny GEMM: unsupported prologue/epilogue pair %d/%d", pro, epi);
   SS_TRY(check_skinny(dtype, a));
+  if (a.lds_chunk < a.kb_per_split && a.lds_chunk % 16) SS_FAIL(SS_EINVAL, "skinny GEMM: chunk of %d k blocks", a.lds_chunk);
   const int groups = ceil_div(a.tasks, 4);
   dim3 grid(groups, a.split);
   size_t lds = (size_t)a.nb * a.lds_chunk * (dtype == SS_DTYPE_BF16 ? 2 : 1) * 1024;

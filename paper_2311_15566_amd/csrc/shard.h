@@ -73,7 +73,7 @@ struct Shard {
   char *ws = nullptr;
   int interrupt_after = -1;
   bool use_graph = true;
-  bool use_persistent = true;
+  int persistent_mode = -1;  // -1: the process default; 0 off; 1 block-body kernel; 2 wave-specialised kernel
   GraphKey phases_key;   // what the phase table on the device was built for
   bool phases_valid = false;
   std::vector<Phase> host_plan;

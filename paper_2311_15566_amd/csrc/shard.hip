@@ -137,7 +137,7 @@ bool compute_layout(const ss_model_desc &m, const ss_slice &s, int max_batch, in
     L->ws_u_l = wtake(L->u_l_stride * L->Ls);
     L->phases_bytes = (size_t)(5 * L->Ls + 2) * 1024;
     L->ws_phases = wtake(L->phases_bytes);
-    L->ws_bar = wtake((size_t)1024 * 4);
+    L->ws_bar = wtake((size_t)2048 * 4);  // [0,1024) barrier state, [1024,1536) per-block progress, [1536,..) abort record
   }
   L->splitk_bytes = std::min<size_t>((size_t)64 << 20, (size_t)16 * L->Bpad * nmax * 4);
   L->ws_splitk = wtake(L->splitk_bytes);
@@ -427,7 +427,7 @@ ss_status ss_shard_create(const ss_model_desc *desc, const ss_slice *slice, cons
     hipLaunchKernelGGL(fill_i32, dim3(1), dim3(32), 0, st, sh->d_len, 32, 0);
     int nc = L.n_counters;
     hipLaunchKernelGGL(fill_i32, dim3(ceil_div(nc, 256)), dim3(256), 0, st, (int32_t *)(sh->ws + L.ws_counters), nc, 0);
-    hipLaunchKernelGGL(fill_i32, dim3(4), dim3(256), 0, st, (int32_t *)(sh->ws + L.ws_bar), 1024, 0);
+    hipLaunchKernelGGL(fill_i32, dim3(8), dim3(256), 0, st, (int32_t *)(sh->ws + L.ws_bar), 2048, 0);
     hipError_t e = hipStreamSynchronize(st);
     if (e != hipSuccess) {
       set_error("shard creation: %s", hipGetErrorString(e));
@@ -485,7 +485,8 @@ ss_status ss_debug_interrupt_after_layer(ss_shard *shard, int32_t layer) {
 
 ss_status ss_set_persistent(ss_shard *shard, int32_t enabled) {
   if (!shard) SS_FAIL(SS_EINVAL, "NULL shard");
-  ((Shard *)shard)->use_persistent = enabled != 0;
+  if (enabled < -1 || enabled > 2) SS_FAIL(SS_EINVAL, "persistent mode %d", enabled);
+  ((Shard *)shard)->persistent_mode = enabled;
   return SS_OK;
 }
 

@@ -142,7 +142,10 @@ ss_status launch_persistent_step(Shard *sh, const std::vector<Phase> &plan, cons
     if (plan.size() * sizeof(Phase) > L.phases_bytes) SS_FAIL(SS_EINVAL, "phase table does not fit its buffer");
     for (const Phase &ph : plan) {
       if (ph.kind == PH_ATTN) SS_TRY(check_decode_attn(ph.at));
-      else if (ph.kind != PH_EMBED) SS_TRY(check_skinny(sh->m.dtype, ph.g));
+      else if (ph.kind != PH_EMBED) {
+        SS_TRY(check_skinny(sh->m.dtype, ph.g));
+        if (ph.g.lds_chunk < ph.g.kb_per_split && ph.g.lds_chunk % 16) SS_FAIL(SS_EINVAL, "skinny GEMM: chunk of %d k blocks", ph.g.lds_chunk);
+      }
       if (ph.gx < 1 || ph.gy < 1) SS_FAIL(SS_EINVAL, "empty phase");
     }
     sh->host_plan = plan;  // stays alive while the copy is in flight
@@ -162,7 +165,7 @@ ss_status launch_persistent_step(Shard *sh, const std::vector<Phase> &plan, cons
   A.n_phases = (int)sh->host_plan.size();
   A.bar.leaf = bar, A.bar.root = bar + 512, A.bar.epoch = bar + 544, A.bar.abort_flag = (int *)(bar + 576);
   A.bar.per_leaf = 64, A.bar.n_leaf = ceil_div(grid, 64);
-  A.bar.spin_limit = 1 << 22;
+  A.bar.spin_limit = 1 << 16;  // ~0.1 s: the kernel must exit long before anything takes the queue for hung
   hipLaunchKernelGGL(k, dim3(grid), dim3(256), kLdsBytes, st, A);
   SS_HIP(hipGetLastError());
   return SS_OK;
@@ -170,14 +173,32 @@ ss_status launch_persistent_step(Shard *sh, const std::vector<Phase> &plan, cons
 
 ss_status persistent_check_abort(const Shard *sh, hipStream_t st) {
   int flag = 0;
-  int *dev = (int *)(sh->ws + sh->L.ws_bar) + 576;
-  SS_HIP(hipMemcpyAsync(&flag, dev, 4, hipMemcpyDeviceToHost, st));
+  int *bar = (int *)(sh->ws + sh->L.ws_bar);
+  SS_HIP(hipMemcpyAsync(&flag, bar + 576, 4, hipMemcpyDeviceToHost, st));
   SS_HIP(hipStreamSynchronize(st));
   if (flag) {
-    flag = 0;
-    SS_HIP(hipMemcpyAsync(dev, &flag, 4, hipMemcpyHostToDevice, st));
+    // who gave up first, and how far every block's control wave had come
+    std::vector<int> prog(512 + 3, 0);
+    SS_HIP(hipMemcpyAsync(prog.data(), bar + 1024, 512 * 4, hipMemcpyDeviceToHost, st));
+    SS_HIP(hipMemcpyAsync(prog.data() + 512, bar + 1536, 3 * 4, hipMemcpyDeviceToHost, st));
+    unsigned epoch = 0;
+    SS_HIP(hipMemcpyAsync(&epoch, bar + 544, 4, hipMemcpyDeviceToHost, st));
     SS_HIP(hipStreamSynchronize(st));
-    SS_FAIL(SS_EHIP, "a device-wide barrier of the persistent decode step timed out; that step committed nothing");
+    int lo = prog[0], hi = prog[0], n_lo = 0, first_lo = -1;
+    for (int i = 0; i < 512; ++i) lo = std::min(lo, prog[i]), hi = std::max(hi, prog[i]);
+    for (int i = 0; i < 512; ++i)
+      if (prog[i] == lo) {
+        if (first_lo < 0) first_lo = i;
+        ++n_lo;
+      }
+    flag = 0;
+    SS_HIP(hipMemcpyAsync(bar + 576, &flag, 4, hipMemcpyHostToDevice, st));
+    SS_HIP(hipStreamSynchronize(st));
+    SS_FAIL(SS_EHIP,
+            "a device-wide barrier of the persistent decode step timed out (block %d at barrier %d after %d polls; "
+            "epoch of the launch %u; arrivals per block between %d and %d, %d blocks at the minimum, first of them %d); "
+            "that step committed nothing",
+            prog[512], prog[513], prog[514], epoch, lo, hi, n_lo, first_lo);
   }
   return SS_OK;
 }

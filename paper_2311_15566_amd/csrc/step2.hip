@@ -31,6 +31,8 @@ constexpr int UB = 16;    // fragments per register buffer
 struct BarState2 {
   unsigned *leaf, *root, *epoch;
   int *abort_flag;
+  int *progress;   // [blocks]: barriers this block's control wave has arrived at (this launch)
+  int *abort_rec;  // first block to give up: block, barrier, polls
   int n_leaf, per_leaf;
   int spin_limit;
 };
@@ -59,6 +61,7 @@ __device__ __forceinline__ bool grid_barrier_wave(const BarState2 &b, const int 
   if ((threadIdx.x & 63) == 0) {
     const int leaf = blockIdx.x / b.per_leaf;
     const unsigned members = (unsigned)min(b.per_leaf, nblocks - leaf * b.per_leaf);
+    st_dev(&b.progress[blockIdx.x], (int)e);
     const unsigned old = __hip_atomic_fetch_add(&b.leaf[leaf * 32], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (old + 1u == members * e) __hip_atomic_fetch_add(b.root, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const unsigned target = (unsigned)b.n_leaf * e;
@@ -66,7 +69,11 @@ __device__ __forceinline__ bool grid_barrier_wave(const BarState2 &b, const int 
     while ((int)(__hip_atomic_load(b.root, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
       __builtin_amdgcn_s_sleep(1);
       if (++it > b.spin_limit || ld_dev(b.abort_flag)) {
-        st_dev(b.abort_flag, 1);
+        if (__hip_atomic_exchange(b.abort_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) {
+          st_dev(&b.abort_rec[0], (int)blockIdx.x);
+          st_dev(&b.abort_rec[1], (int)e);
+          st_dev(&b.abort_rec[2], it);
+        }
         good = 0;
         break;
       }
@@ -93,17 +100,28 @@ __device__ __forceinline__ bool arrive_last_wave(int *counter, int expected) {
 struct Item {
   int p;   // phase index, or n_phases when there is none
   int vb;  // virtual block within the phase
+  int c;   // GEMM: chunk of the block's K range (a block walks its chunks in order, accumulating)
 };
 
+// chunks of virtual block vb of a GEMM phase
+__device__ __forceinline__ int item_chunks(const Phase &P, int vb) {
+  if (P.kind == PH_ATTN || P.kind == PH_EMBED) return 1;
+  const int by = vb / P.gx;
+  const int nks = min(P.g.kb_per_split, P.g.k_blocks - by * P.g.kb_per_split);
+  return (nks + P.g.lds_chunk - 1) / P.g.lds_chunk;
+}
+
 __device__ __forceinline__ Item next_item(const StepArgs2 &A, Item it, const int nblocks) {
-  // the block's items: for each phase in order, vb = blockIdx.x, blockIdx.x + nblocks, ...
+  // the block's items: for each phase in order, vb = blockIdx.x, blockIdx.x + nblocks, ...; for
+  // each vb its chunks in order
+  if (it.p < A.n_phases && it.vb >= 0 && it.c + 1 < item_chunks(A.phases[it.p], it.vb)) return Item{it.p, it.vb, it.c + 1};
   int p = it.p, vb = it.vb + nblocks;
   while (p < A.n_phases) {
-    if (A.phases[p].kind != PH_EMBED && vb < A.phases[p].gx * A.phases[p].gy) return Item{p, vb};
+    if (A.phases[p].kind != PH_EMBED && vb < A.phases[p].gx * A.phases[p].gy) return Item{p, vb, 0};
     ++p;
     vb = blockIdx.x;
   }
-  return Item{A.n_phases, 0};
+  return Item{A.n_phases, 0, 0};
 }
 
 // What one compute wave streams for an item: nf fragments; fragment f lives at base + f_off(f).
@@ -146,8 +164,9 @@ __device__ __forceinline__ Stream make_stream(const StepArgs2 &A, const Item it,
   const SkinnyArgs &a = P.g;
   const int task = bx * CW + wave;
   if (task >= a.tasks) return s;
-  const int kb0 = by * a.kb_per_split;
-  const int nk = min(a.kb_per_split, a.k_blocks - kb0);
+  const int nks = min(a.kb_per_split, a.k_blocks - by * a.kb_per_split);
+  const int kb0 = by * a.kb_per_split + it.c * a.lds_chunk;
+  const int nk = min(a.lds_chunk, nks - it.c * a.lds_chunk);
   s.nw = (GLU && P.kind == PH_FFN_UP) ? 2 : 1;
   s.k_blocks = a.k_blocks;
   s.nf = nk * s.nw;
@@ -199,7 +218,7 @@ __global__ void __launch_bounds__(256, 2) decode_step_persistent2(StepArgs2 A) {
   if (tid == 0) sh.abort = 0;
 
   // ---- phase 0: the embedding, by the control waves of the first B blocks ----
-  Item it = next_item(A, Item{0, (int)blockIdx.x - nblocks}, nblocks);  // first non-embedding item
+  Item it = next_item(A, Item{0, (int)blockIdx.x - nblocks, 0}, nblocks);  // first non-embedding item
   Stream st = make_stream<GLU>(A, it, wave, lane);
   u32x4 bufA[UB], bufB[UB];
   if (!control) {
@@ -258,6 +277,7 @@ __global__ void __launch_bounds__(256, 2) decode_step_persistent2(StepArgs2 A) {
   }
 
   int cur_phase = 0;  // the phase whose leading barrier the control wave has passed
+  f32x4 acc[NB][2];   // GEMM accumulators of a compute wave, carried over the chunks of an item
   while (it.p < A.n_phases) {
     const Phase &P = A.phases[it.p];
     const int kind = P.kind;
@@ -464,8 +484,10 @@ __global__ void __launch_bounds__(256, 2) decode_step_persistent2(StepArgs2 A) {
     // skinny GEMM item: tasks bx*3 .. bx*3+2, K range by
     // =======================================================================
     const SkinnyArgs &a = P.g;
-    const int kb0 = by * a.kb_per_split;
-    const int nk = min(a.kb_per_split, a.k_blocks - kb0);
+    const int nks = min(a.kb_per_split, a.k_blocks - by * a.kb_per_split);
+    const int kb0 = by * a.kb_per_split + it.c * a.lds_chunk;
+    const int nk = min(a.lds_chunk, nks - it.c * a.lds_chunk);
+    const bool first_chunk = it.c == 0, last_chunk = (it.c + 1) * a.lds_chunk >= nks;
     const int K = a.k_blocks * FK;
     const bool glu = GLU && kind == PH_FFN_UP;
     // ---- stage the activations of the K range (all four waves) ----
@@ -507,9 +529,10 @@ __global__ void __launch_bounds__(256, 2) decode_step_persistent2(StepArgs2 A) {
     }
     __syncthreads();  // B1
     if (!control) {
-      f32x4 acc[NB][2];
+      if (first_chunk) {
 #pragma unroll
-      for (int t = 0; t < NB; ++t) acc[t][0] = acc[t][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int t = 0; t < NB; ++t) acc[t][0] = acc[t][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+      }
       auto consume = [&](u32x4(&buf)[UB], int f0) {
 #pragma unroll
         for (int u = 0; u < UB; ++u) {
@@ -533,16 +556,19 @@ __global__ void __launch_bounds__(256, 2) decode_step_persistent2(StepArgs2 A) {
       load_buf(bufA, nst, 0);
       consume(bufB, UB);
       load_buf(bufB, nst, UB);
+      if (last_chunk) {
 #pragma unroll
-      for (int t = 0; t < NB; ++t) {
-        sh.hand[wave][t][0][lane] = acc[t][0];
-        if (GLU) sh.hand[wave][t][NWMAX - 1][lane] = acc[t][1];
+        for (int t = 0; t < NB; ++t) {
+          sh.hand[wave][t][0][lane] = acc[t][0];
+          if (GLU) sh.hand[wave][t][NWMAX - 1][lane] = acc[t][1];
+        }
       }
       st = nst;
       it = nit;
     }
     __syncthreads();  // B2
-    if (control) {
+    if (control && !last_chunk) it = next_item(A, it, nblocks);
+    if (control && last_chunk) {
       const int ngroups = P.gx;
       const int q4 = (lane >> 4) * 4, bl = lane & 15;
       const int NWr = glu ? 2 : 1;
@@ -787,6 +813,10 @@ static int persistent_grid2(StepKernel2 k, int B) {
       hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, (const void *)k, 256, lds_bytes2(B)) == hipSuccess && occ >= 2 &&
       cus > 0)
     grid = std::min(2 * cus, 512);  // the barrier tree is sized for 512 blocks
+  if (grid > 0) {
+    const char *v = getenv("SS_PERSISTENT_BLOCKS");  // fewer resident blocks (testing aid)
+    if (v && atoi(v) > 0) grid = std::min(grid, atoi(v));
+  }
   cache[k] = grid;
   return grid;
 }
@@ -809,8 +839,10 @@ ss_status launch_persistent2_step(Shard *sh, const std::vector<Phase> &plan, con
       } else if (ph.kind != PH_EMBED) {
         SS_TRY(check_skinny(sh->m.dtype, ph.g));
         const int nw = (ph.kind == PH_FFN_UP && sh->m.act == SS_ACT_SWIGLU) ? 2 : 1;
-        if (ph.g.kb_per_split * nw > 2 * UB || ph.g.lds_chunk != ph.g.kb_per_split)
-          SS_FAIL(SS_EINVAL, "persistent step: %d fragments per wave exceed the register buffers", ph.g.kb_per_split * nw);
+        if (ph.g.lds_chunk * nw > 2 * UB)
+          SS_FAIL(SS_EINVAL, "persistent step: %d fragments per wave and chunk exceed the register buffers", ph.g.lds_chunk * nw);
+        if ((size_t)ph.g.nb * ph.g.lds_chunk * 2 * 1024 > (size_t)lds_bytes2(key.B))
+          SS_FAIL(SS_EINVAL, "persistent step: a chunk of %d k blocks does not fit the LDS", ph.g.lds_chunk);
         if (ph.gx != ceil_div(ph.g.tasks, CW) || ph.gy != ph.g.split) SS_FAIL(SS_EINVAL, "persistent step: bad grid");
       }
     }
@@ -830,8 +862,11 @@ ss_status launch_persistent2_step(Shard *sh, const std::vector<Phase> &plan, con
   A.phases = (const Phase *)(sh->ws + L.ws_phases);
   A.n_phases = (int)sh->host_plan.size();
   A.bar.leaf = bar, A.bar.root = bar + 512, A.bar.epoch = bar + 544, A.bar.abort_flag = (int *)(bar + 576);
+  A.bar.progress = (int *)(bar + 1024), A.bar.abort_rec = (int *)(bar + 1536);
   A.bar.per_leaf = 64, A.bar.n_leaf = ceil_div(grid, 64);
-  A.bar.spin_limit = 1 << 22;
+  // a poll takes about a microsecond: a barrier that has not completed after ~0.1 s never will,
+  // and the kernel must be gone long before anything takes the queue for hung
+  A.bar.spin_limit = 1 << 16;
   hipLaunchKernelGGL(k, dim3(grid), dim3(256), lds_bytes2(key.B), stream, A);
   SS_HIP(hipGetLastError());
   return SS_OK;

@@ -207,7 +207,7 @@ def test_launch_modes_agree(ss, side_stream, name, kw):
     toks = make_tokens(w.seed, w.batch, w.s_in, w.desc["vocab"])
     forced = make_tokens(w.seed + 1, w.batch, w.steps, w.desc["vocab"])
     outs = []
-    for persistent, graph in ((False, False), (False, True), (True, True), (True, True)):
+    for persistent, graph in ((0, False), (0, True), (1, True), (1, True)):
         sh = ss.Shard(w.desc, w.slice, W, w.batch, w.s_max)
         sh.set_persistent(persistent)
         sh.set_graph_launch(graph)
