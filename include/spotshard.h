@@ -198,6 +198,11 @@ int32_t ss_debug_plan(const ss_model_desc *desc, const ss_slice *slice, int32_t 
                       int32_t B, int32_t mode, int32_t blocks, uint64_t fake_base, void *out_phases,
                       int32_t max_phases, uint64_t *out_total, uint64_t *out_sizeof_phase);
 
+/* Measurement aid: with SS_TRACE set in the environment the wave-specialised persistent kernel
+ * records block 0's 100 MHz wall clock at kernel start (out[0]), after each of its barriers
+ * (out[1..n_phases-1]) and at its end (out[n_phases]); out[63] is scratch.  Copies n words. */
+ss_status ss_debug_read_trace(const ss_shard *shard, uint64_t *out, int32_t n, void *hip_stream);
+
 /* Geometry of the shard, for callers that size buffers: out[0..5] = layers, heads,
  * ffn columns, max_batch, max_seq, bytes per cache element. */
 ss_status ss_shard_geometry(const ss_shard *shard, int32_t out[6]);

@@ -41,7 +41,8 @@ struct Layout {
   size_t ws_o_l, o_l_stride;      // per layer: attention output operand
   size_t ws_u_l, u_l_stride;      // per layer: FFN activation operand
   size_t ws_phases, phases_bytes; // the persistent kernel's phase table
-  size_t ws_bar;                  // grid-barrier state (int32 x 1024)
+  size_t ws_bar;                  // grid-barrier state (int32 x 2048)
+  size_t ws_trace;                // per-phase clock trace of the persistent kernel (measurement aid)
   size_t total;
 };
 

@@ -137,6 +137,7 @@ bool compute_layout(const ss_model_desc &m, const ss_slice &s, int max_batch, in
     L->ws_u_l = wtake(L->u_l_stride * L->Ls);
     L->phases_bytes = (size_t)(5 * L->Ls + 2) * 1024;
     L->ws_phases = wtake(L->phases_bytes);
+    L->ws_trace = wtake((size_t)(5 * L->Ls + 66) * 8);
     L->ws_bar = wtake((size_t)2048 * 4);  // [0,1024) barrier state, [1024,1536) per-block progress, [1536,..) abort record
   }
   L->splitk_bytes = std::min<size_t>((size_t)64 << 20, (size_t)16 * L->Bpad * nmax * 4);
@@ -480,6 +481,15 @@ ss_status ss_debug_interrupt_after_layer(ss_shard *shard, int32_t layer) {
   Shard *sh = (Shard *)shard;
   if (layer < -1 || layer >= sh->L.Ls) SS_FAIL(SS_EINVAL, "layer %d outside the shard's %d layers", layer, sh->L.Ls);
   sh->interrupt_after = layer;
+  return SS_OK;
+}
+
+ss_status ss_debug_read_trace(const ss_shard *shard, uint64_t *out, int32_t n, void *hip_stream) {
+  if (!shard || !out || n < 1) SS_FAIL(SS_EINVAL, "bad argument");
+  const Shard *sh = (const Shard *)shard;
+  if (n > 5 * sh->L.Ls + 66) n = 5 * sh->L.Ls + 66;
+  SS_HIP(hipMemcpyAsync(out, sh->ws + sh->L.ws_trace, (size_t)n * 8, hipMemcpyDeviceToHost, (hipStream_t)hip_stream));
+  SS_HIP(hipStreamSynchronize((hipStream_t)hip_stream));
   return SS_OK;
 }
 

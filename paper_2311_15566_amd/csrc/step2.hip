@@ -33,8 +33,10 @@ struct BarState2 {
   int *abort_flag;
   int *progress;   // [blocks]: barriers this block's control wave has arrived at (this launch)
   int *abort_rec;  // first block to give up: block, barrier, polls
+  unsigned long long *trace;  // block 0's control wave: wall clock at kernel start and after each barrier
   int n_leaf, per_leaf;
   int spin_limit;
+  unsigned trace_base;  // epoch at the start of the launch (host mirror)
 };
 struct StepArgs2 {
   const Phase *phases;
@@ -79,6 +81,7 @@ __device__ __forceinline__ bool grid_barrier_wave(const BarState2 &b, const int 
       }
     }
   }
+  if (blockIdx.x == 0 && (threadIdx.x & 63) == 0 && b.trace) b.trace[e - (unsigned)b.trace[63]] = wall_clock64();
   return __shfl(good, 0) != 0;
 }
 
@@ -216,6 +219,7 @@ __global__ void __launch_bounds__(256, 2) decode_step_persistent2(StepArgs2 A) {
   const int nblocks = gridDim.x;
   const unsigned base_epoch = *A.bar.epoch;
   if (tid == 0) sh.abort = 0;
+  if (blockIdx.x == 0 && tid == 0 && A.bar.trace) A.bar.trace[0] = wall_clock64(), A.bar.trace[63] = base_epoch;
 
   // ---- phase 0: the embedding, by the control waves of the first B blocks ----
   Item it = next_item(A, Item{0, (int)blockIdx.x - nblocks, 0}, nblocks);  // first non-embedding item
@@ -779,7 +783,10 @@ __global__ void __launch_bounds__(256, 2) decode_step_persistent2(StepArgs2 A) {
       ok = grid_barrier_wave(A.bar, nblocks, base_epoch + (unsigned)cur_phase + 1u);
       ++cur_phase;
     }
-    if (blockIdx.x == 0 && lane == 0 && ok) *A.bar.epoch = base_epoch + (unsigned)(A.n_phases - 1);
+    if (blockIdx.x == 0 && lane == 0 && ok) {
+      *A.bar.epoch = base_epoch + (unsigned)(A.n_phases - 1);
+      if (A.bar.trace) A.bar.trace[A.n_phases] = wall_clock64();
+    }
   }
 }
 
@@ -863,6 +870,8 @@ ss_status launch_persistent2_step(Shard *sh, const std::vector<Phase> &plan, con
   A.n_phases = (int)sh->host_plan.size();
   A.bar.leaf = bar, A.bar.root = bar + 512, A.bar.epoch = bar + 544, A.bar.abort_flag = (int *)(bar + 576);
   A.bar.progress = (int *)(bar + 1024), A.bar.abort_rec = (int *)(bar + 1536);
+  A.bar.trace = getenv("SS_TRACE") ? (unsigned long long *)(sh->ws + L.ws_trace) : nullptr;
+  A.bar.trace_base = 0;
   A.bar.per_leaf = 64, A.bar.n_leaf = ceil_div(grid, 64);
   // a poll takes about a microsecond: a barrier that has not completed after ~0.1 s never will,
   // and the kernel must be gone long before anything takes the queue for hung
