@@ -169,17 +169,8 @@ ss_status ss_kv_import(ss_shard *shard, const void *host_src, const int32_t *len
  * shard) and return SS_EINTR without committing.  -1 switches it off. */
 ss_status ss_debug_interrupt_after_layer(ss_shard *shard, int32_t layer);
 
-/* How ss_decode_step is launched.  Graph (default 1): replay of a captured HIP graph of the
- * step's kernels; 0: the kernels one by one; both give the same bits.  Persistent mode (bf16
- * models with head_dim 128, one shard in the group; other cases fall back): the whole step as
- * ONE kernel whose blocks stay resident and meet at device-wide barriers between the step's
- * phases; 1 = the kernels' block bodies run by resident blocks, 2 = wave-specialised (compute
- * waves stream weights and cache rows across the barriers, a control wave owns stores and
- * hand-offs; sums are ordered differently, results agree to float32 rounding), 0 = off,
- * -1 = the process default (environment SS_PERSISTENT, else off).  If a barrier does not
- * complete within its spin limit (~0.1 s) the step commits nothing and the next
- * ss_committed_len returns SS_EHIP with a description. */
-ss_status ss_set_persistent(ss_shard *shard, int32_t enabled);
+/* How ss_decode_step is launched.  1 (default): replay of a captured HIP graph of the step's
+ * kernels; 0: the kernels one by one.  Both give the same bits. */
 ss_status ss_set_graph_launch(ss_shard *shard, int32_t enabled);
 
 /* Measurement aid: per-kernel-class timing of decode steps.  While enabled on group[0],
@@ -195,13 +186,8 @@ ss_status ss_kernel_timing_read(ss_shard *shard, double ms[8], int64_t count[8],
  * for a shard of this shape placed at device address fake_base.  See the implementation for
  * the record layout; used by the CPU tests that bound-check every buffer a phase addresses. */
 int32_t ss_debug_plan(const ss_model_desc *desc, const ss_slice *slice, int32_t max_batch, int32_t max_seq,
-                      int32_t B, int32_t mode, int32_t blocks, uint64_t fake_base, void *out_phases,
-                      int32_t max_phases, uint64_t *out_total, uint64_t *out_sizeof_phase);
-
-/* Measurement aid: with SS_TRACE set in the environment the wave-specialised persistent kernel
- * records block 0's 100 MHz wall clock at kernel start (out[0]), after each of its barriers
- * (out[1..n_phases-1]) and at its end (out[n_phases]); out[63] is scratch.  Copies n words. */
-ss_status ss_debug_read_trace(const ss_shard *shard, uint64_t *out, int32_t n, void *hip_stream);
+                      int32_t B, uint64_t fake_base, void *out_phases, int32_t max_phases, uint64_t *out_total,
+                      uint64_t *out_sizeof_phase);
 
 /* Geometry of the shard, for callers that size buffers: out[0..5] = layers, heads,
  * ffn columns, max_batch, max_seq, bytes per cache element. */

@@ -70,10 +70,8 @@ def _load():
     L.ss_kv_import.argtypes = [vp, vp, C.POINTER(i32), sz, vp]
     L.ss_debug_interrupt_after_layer.argtypes = [vp, i32]
     L.ss_set_graph_launch.argtypes = [vp, i32]
-    L.ss_set_persistent.argtypes = [vp, i32]
     L.ss_shard_geometry.argtypes = [vp, C.POINTER(i32)]
     L.ss_kernel_timing.argtypes = [vp, i32]
-    L.ss_debug_read_trace.argtypes = [vp, C.POINTER(C.c_uint64), i32, vp]
     L.ss_kernel_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), vp]
     return L
 
@@ -171,10 +169,6 @@ class Shard:
     def interrupt_after_layer(self, layer: int):
         _check(lib.ss_debug_interrupt_after_layer(self.handle, layer))
 
-    def set_persistent(self, mode: int):
-        """0 off, 1 block-body persistent kernel, 2 wave-specialised persistent kernel, -1 process default."""
-        _check(lib.ss_set_persistent(self.handle, int(mode)))
-
     def set_graph_launch(self, enabled: bool):
         _check(lib.ss_set_graph_launch(self.handle, int(enabled)))
 
@@ -186,11 +180,6 @@ class Shard:
         _check(lib.ss_kernel_timing_read(self.handle, ms, cnt, _stream(stream)))
         names = ("embed", "qkv_gemm", "decode_attn", "resid_gemm", "ffn_up_gemm", "lm_head")
         return {n: (ms[i], cnt[i]) for i, n in enumerate(names)}
-
-    def read_trace(self, n, stream=None):
-        out = (C.c_uint64 * n)()
-        _check(lib.ss_debug_read_trace(self.handle, out, n, _stream(stream)))
-        return list(out)
 
     def geometry(self):
         out = (C.c_int32 * 6)()

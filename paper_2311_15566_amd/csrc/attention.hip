@@ -7,14 +7,15 @@
 
 namespace ss {
 
-template <typename T, typename AT, int DH>
-__global__ void __launch_bounds__(256) decode_attn(DecodeAttnArgs a) {
-  __shared__ AttnShared sh;
-  decode_attn_block<T, AT, DH>(a, blockIdx.x, blockIdx.y, sh);
+template <typename T, typename AT, int DH, int NWV>
+__global__ void __launch_bounds__(NWV * 64) decode_attn(DecodeAttnArgs a) {
+  __shared__ AttnShared<NWV> sh;
+  decode_attn_block<T, AT, DH, NWV>(a, blockIdx.x, blockIdx.y, sh);
 }
 
 ss_status check_decode_attn(const DecodeAttnArgs &a) {
   if (a.B < 1 || a.B > 32 || a.Hs < 1 || (a.Dh != 64 && a.Dh != 128)) SS_FAIL(SS_EINVAL, "decode attention: bad shape");
+  if (a.waves != 4 && a.waves != 16) SS_FAIL(SS_EINVAL, "decode attention: %d waves per block", a.waves);
   if (a.rows_per_block < 1 || a.splits < 1 || (size_t)a.splits * a.rows_per_block < (size_t)a.Smax)
     SS_FAIL(SS_EINVAL, "decode attention: %d splits of %d rows do not cover %d rows", a.splits, a.rows_per_block, a.Smax);
   return SS_OK;
@@ -23,7 +24,11 @@ ss_status check_decode_attn(const DecodeAttnArgs &a) {
 ss_status launch_decode_attn(int dtype, const DecodeAttnArgs &a, hipStream_t st) {
   SS_TRY(check_decode_attn(a));
   dim3 grid(a.B * a.Hs, a.splits);
-#define SS_LAUNCH(KT, AT, DH) hipLaunchKernelGGL((decode_attn<KT, AT, DH>), grid, dim3(256), 0, st, a)
+#define SS_LAUNCH(KT, AT, DH)                                                                        \
+  do {                                                                                               \
+    if (a.waves == 16) hipLaunchKernelGGL((decode_attn<KT, AT, DH, 16>), grid, dim3(1024), 0, st, a); \
+    else hipLaunchKernelGGL((decode_attn<KT, AT, DH, 4>), grid, dim3(256), 0, st, a);                \
+  } while (0)
   if (dtype == SS_DTYPE_BF16 && a.kv_dtype == SS_DTYPE_F16) {
     if (a.Dh == 128) SS_LAUNCH(f16_t, bf16_t, 128);
     else SS_LAUNCH(f16_t, bf16_t, 64);

@@ -1,5 +1,4 @@
-// One block's share of decode attention, as a device function: the stand-alone kernel and the
-// persistent decode-step kernel both call it.
+// One block's share of decode attention, as a device function.
 #pragma once
 #include <math.h>
 
@@ -50,23 +49,25 @@ __device__ __forceinline__ float rope_elem(const float *v, int e, int half, cons
 }
 
 // ---------------------------------------------------------------------------
-// decode attention.  grid = (B*Hs, splits); block = 4 waves.
+// decode attention.  grid = (B*Hs, splits); block = NWV waves.
 // Block (bh, s) covers committed rows [s*rpb, min((s+1)*rpb, n)); a lane group of LPR lanes
 // owns one row at a time and keeps its own running (max, sum, acc); groups, waves and then
 // splits are merged with the usual rescaling.  The last block to arrive for (b, h) also
 // scores the new token from registers, writes its key/value as cache row n and emits the
 // head output.  Blocks past the live splits exit at once.
 // ---------------------------------------------------------------------------
+template <int NWV>
 struct AttnShared {
   float sq[128];
-  float sm_m[4], sm_l[4];
-  float sm_acc[4][128];
+  float sm_m[NWV], sm_l[NWV];
+  float sm_acc[NWV][128];
   float sm_red[4];
   int flag;
 };
 
-template <typename T, typename AT, int DH>
-__device__ __forceinline__ void decode_attn_block(const DecodeAttnArgs &a, const int bh, const int sp, AttnShared &sh) {
+template <typename T, typename AT, int DH, int NWV>
+__device__ __forceinline__ void decode_attn_block(const DecodeAttnArgs &a, const int bh, const int sp,
+                                                  AttnShared<NWV> &sh) {
   typedef RowGeom<T, DH> Gm;
   constexpr int EPL = Gm::EPL, LPR = Gm::LPR, G = Gm::G, U = 4;
   auto &sq = sh.sq;
@@ -103,7 +104,7 @@ __device__ __forceinline__ void decode_attn_block(const DecodeAttnArgs &a, const
 #pragma unroll
   for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
 
-  for (int base = r0 + wave * (U * G); base < r1; base += 4 * U * G) {
+  for (int base = r0 + wave * (U * G); base < r1; base += NWV * U * G) {
     u32x4 kr[U], vr[U];
     int row[U];
 #pragma unroll
@@ -160,13 +161,13 @@ __device__ __forceinline__ void decode_attn_block(const DecodeAttnArgs &a, const
     if (lane == 0) sm_m[wave] = m, sm_l[wave] = l;
   }
   __syncthreads();
-  // merge the 4 waves; thread e owns output dim e
+  // merge the waves; thread e owns output dim e
   float M = -1e30f, Lsum = 0.f, A = 0.f;
   if (tid < DH) {
 #pragma unroll
-    for (int w = 0; w < 4; ++w) M = fmaxf(M, sm_m[w]);
+    for (int w = 0; w < NWV; ++w) M = fmaxf(M, sm_m[w]);
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
+    for (int w = 0; w < NWV; ++w) {
       const float f = __expf(sm_m[w] - M);
       Lsum += sm_l[w] * f;
       A += sm_acc[w][tid] * f;
@@ -204,7 +205,7 @@ __device__ __forceinline__ void decode_attn_block(const DecodeAttnArgs &a, const
   }
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) prod += __shfl_xor(prod, off);
-  if (lane == 0) sm_red[wave] = prod;
+  if (lane == 0 && wave < 4) sm_red[wave] = prod;
   __syncthreads();
   if (tid < DH) {
     float sn = 0.f;

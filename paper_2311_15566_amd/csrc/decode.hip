@@ -17,7 +17,7 @@ namespace ss {
 template <typename T>
 __global__ void __launch_bounds__(256) embed_rows(EmbedArgs a) {
   __shared__ float scratch[4];
-  embed_row_block<T, true>(a, blockIdx.x, scratch);
+  embed_row_block<T>(a, blockIdx.x, scratch);
 }
 
 // a = Norm(x) for every token row, written in operand order.  grid = rows.
@@ -36,18 +36,25 @@ __global__ void __launch_bounds__(256) norm_rows(const float *x, const float *ga
   }
 }
 
-// last prompt position of every sequence -> the decode step's residual rows, with statistics
-__global__ void __launch_bounds__(256) gather_last(const float *x, int S, float *xd, float *stats, int d, int rms,
-                                                   float eps) {
+// last prompt position of every sequence -> the decode step's residual rows, with the final
+// norm's operand (x * gamma) and the rows' (sum, sum of squares)
+template <typename T>
+__global__ void __launch_bounds__(256) gather_last(const float *x, int S, float *xd, const float *gamma, void *act_out,
+                                                   float *stat_out, int d) {
   __shared__ float scratch[4];
   const int b = blockIdx.x;
   const float *src = x + ((size_t)b * S + S - 1) * d;
   float *dst = xd + (size_t)b * d;
-  for (int k = threadIdx.x; k < d; k += 256) dst[k] = src[k];
-  __syncthreads();
-  float mean, rstd;
-  row_stats(dst, d, rms, eps, scratch, &mean, &rstd);
-  if (threadIdx.x == 0) stats[b * 2] = mean, stats[b * 2 + 1] = rstd;
+  float s1 = 0.f, s2 = 0.f;
+  for (int k = threadIdx.x; k < d; k += 256) {
+    const float v = src[k];
+    dst[k] = v;
+    s1 += v, s2 += v * v;
+    store_act<T>(act_out, b, k, d / Elem<T>::kFragK, Elem<T>::kParts, v * gamma[k]);
+  }
+  s1 = block_sum(s1, scratch);
+  s2 = block_sum(s2, scratch);
+  if (threadIdx.x == 0) stat_out[b * 2] = s1, stat_out[b * 2 + 1] = s2;
 }
 
 // ---------------------------------------------------------------------------
@@ -77,81 +84,93 @@ static ss_status check_group(Shard *const *group, int n_group, int B) {
   return SS_OK;
 }
 
-static void attn_plan(const Layout &L, int B, int max_rows, int *rows_per_block, int *splits) {
-  // enough blocks to fill 256 CUs a few times over, at least 64 rows per block; the partial
-  // buffer holds ceil(Smax/64) splits
+static void attn_plan(const Layout &L, int B, int *rows_per_block, int *splits, int *waves) {
   const int pairs = std::max(1, B * L.Hs);
+  if (pairs >= 64) {
+    // enough (row, head) pairs to occupy the chip: one block of 16 waves per pair, merged in
+    // LDS, nothing of the softmax goes through memory
+    *rows_per_block = (int)align_up((size_t)L.Smax, 64), *splits = 1, *waves = 16;
+    return;
+  }
+  // few pairs: split the sequence over blocks of 4 waves (at least 64 rows each; the partial
+  // buffer holds ceil(Smax/64) splits), the last block to arrive for a pair merges
   const int want = std::max(1, std::min(ceil_div(1024, pairs), L.attn_splits));
-  int rpb = (int)align_up((size_t)ceil_div(L.Smax, want), 64);
-  if (max_rows > 0 && rpb > max_rows) rpb = max_rows;
+  const int rpb = (int)align_up((size_t)ceil_div(L.Smax, want), 64);
   *rows_per_block = rpb;
   *splits = ceil_div(L.Smax, rpb);
+  *waves = 4;
 }
 
 // ---------------------------------------------------------------------------
 // the decode step as a list of phases
 // ---------------------------------------------------------------------------
-static float *xv(const Shard *g0, int v) { return (float *)(g0->ws + g0->L.ws_xv + (size_t)v * g0->L.xv_stride); }
-static float *statv(const Shard *g0, int v) { return (float *)(g0->ws + g0->L.ws_statv) + (size_t)v * 64; }
+static int pick_ks(int k_blocks) { return k_blocks >= 16 ? 8 : 4; }  // waves per block
 
-static Phase lm_head_phase(Shard *const *group, int n_group, int B, const float *x, const float *stats, float *logits,
-                           int32_t *next_tokens, int commit_inc, int target_blocks) {
+// the final norm and the LM head over the rows in the decode buffers, greedy choice, commit
+static Phase lm_head_phase(Shard *const *group, int n_group, int B, int stat_groups, float *logits, int32_t *next_tokens,
+                           int commit_inc) {
   Shard *g0 = group[0];
   const Layout &L = g0->L;
   Phase ph = {};
   ph.kind = PH_LM_HEAD;
-  SkinnyArgs &a = ph.g;
-  a.w = g0->lm_head.ptr, a.tasks = g0->lm_head.row_tiles, a.k_blocks = g0->lm_head.k_blocks, a.B = B, a.N = L.V;
-  plan_skinny(&a, L.esz, L.splitk_bytes, 1, target_blocks);
-  a.x = x, a.stats = stats, a.gamma = g0->lnf_g, a.beta = g0->lnf_b;
-  a.splitk = (float *)(g0->ws + L.ws_splitk), a.counters = (int *)(g0->ws + L.ws_counters);
+  StreamGemmArgs &a = ph.g;
+  a.w = g0->lm_head.ptr, a.row_tiles = g0->lm_head.row_tiles, a.k_blocks = g0->lm_head.k_blocks, a.B = B, a.N = L.V;
+  a.ks = pick_ks(a.k_blocks);
+  a.act = g0->ws + L.ws_ad;
+  a.stat_in = (const float *)(g0->ws + L.ws_statd), a.stat_groups = stat_groups, a.norm_dim = L.d;
+  a.rms = g0->m.norm == SS_NORM_RMSNORM, a.eps = g0->m.norm_eps;
+  a.wg = g0->wg_lm, a.cb = g0->cb_lm;
   a.out_f32 = logits, a.ld_out = L.V;
   a.am_val = (float *)(g0->ws + L.ws_argmax);
-  a.am_idx = (int *)(a.am_val + (size_t)ceil_div(a.tasks, 3) * 32);
+  a.am_idx = (int *)(a.am_val + (size_t)ceil_div(a.row_tiles, 2) * 32);
+  a.counter = (int *)(g0->ws + L.ws_counters);
   a.next_tokens = next_tokens;
   for (int i = 0; i < n_group; ++i) a.lens[i] = group[i]->d_len;
   a.n_lens = n_group, a.commit_inc = commit_inc;
-  ph.gx = ceil_div(a.tasks, target_blocks < 0 ? 3 : 4), ph.gy = a.split;
+  ph.gx = stream_gemm_blocks(EPI_LOGITS, a), ph.gy = 1;
   return ph;
 }
 
-// Phases of one decode step, in order.  Buffers follow the single-assignment rule: residual
-// stream version v (0 = embedding, 2l+1 = after layer l's attention, 2l+2 = after its FFN), one
-// q|k|v, attention-output and FFN-activation buffer per layer.
+// Phases of one decode step, in order.  The residual stream x, the operand of the next normalised
+// GEMM (x * gamma) and the rows' partial sums live in group[0]'s workspace; q|k|v, the attention
+// output and the FFN activation in each shard's own.
 static void build_decode_plan(Shard *const *group, int n_group, const int32_t *tokens_in, int B, float *logits,
-                              int32_t *next_tokens, int stop_after_layer, int target_blocks, std::vector<Phase> *plan) {
+                              int32_t *next_tokens, int stop_after_layer, std::vector<Phase> *plan) {
   Shard *g0 = group[0];
   const Layout &L0 = g0->L;
   const ss_model_desc &m = g0->m;
   const int dt = m.dtype, d = L0.d;
   const int FK = dt == SS_DTYPE_BF16 ? 32 : 16;
   const int rms = m.norm == SS_NORM_RMSNORM;
-  float *stat_part = (float *)(g0->ws + L0.ws_stat_part);
+  float *x = (float *)(g0->ws + L0.ws_xd);
+  void *ad = g0->ws + L0.ws_ad;
+  float *statd = (float *)(g0->ws + L0.ws_statd);
+  const float *first_gamma = g0->layers[0].ln1_g;
   plan->clear();
   {
     Phase ph = {};
     ph.kind = PH_EMBED, ph.gx = B, ph.gy = 1;
-    ph.e = EmbedArgs{tokens_in, g0->wte, g0->wpe, g0->d_len, 0, xv(g0, 0), statv(g0, 0), d, L0.V, rms, m.norm_eps};
+    ph.e = EmbedArgs{tokens_in, g0->wte, g0->wpe, g0->d_len, 0, x, d, L0.V, first_gamma, ad, statd};
     plan->push_back(ph);
   }
-  // sum over the group at a reduce slot: shard i adds its partial to what the previous shards left
-  auto resid = [&](int l, int i, const FragMat &w, const void *act, const float *bias, int v_in, int v_out) {
-    Shard *s = group[i];
-    const Layout &L = s->L;
+  int stat_groups = 1;  // partial-sum groups behind the rows in statd
+  // a GEMM whose input is Norm(x): operand x * gamma from the producer of x, statistics deferred
+  auto normed = [&](StreamGemmArgs &a, const float *wg, const float *cb) {
+    a.act = ad, a.stat_in = statd, a.stat_groups = stat_groups, a.norm_dim = d, a.rms = rms, a.eps = m.norm_eps;
+    a.wg = wg, a.cb = cb;
+  };
+  // sum over the group at a reduce slot: shard i adds its partial to what the previous shards
+  // left; the last one also emits the next operand (x * next_gamma) and the partial sums
+  auto resid = [&](int i, const FragMat &w, const void *act, const float *bias, const float *next_gamma) {
     Phase ph = {};
     ph.kind = PH_RESID, ph.shard = i;
-    SkinnyArgs &a = ph.g;
-    a.w = w.ptr, a.tasks = w.row_tiles, a.k_blocks = w.k_blocks, a.B = B, a.N = d;
-    plan_skinny(&a, L.esz, L.splitk_bytes, 1, target_blocks);
+    StreamGemmArgs &a = ph.g;
+    a.w = w.ptr, a.row_tiles = w.row_tiles, a.k_blocks = w.k_blocks, a.ks = pick_ks(a.k_blocks), a.B = B, a.N = d;
     a.act = act;
-    a.splitk = (float *)(s->ws + L.ws_splitk), a.counters = (int *)(s->ws + L.ws_counters);
-    a.bias = i == 0 ? bias : nullptr;
-    const int pp0 = 2 * L0.Ls + 1;
-    a.x_in = xv(g0, i == 0 ? v_in : pp0 + ((i - 1) & 1));
-    a.x_resid = xv(g0, i == n_group - 1 ? v_out : pp0 + (i & 1));
-    a.stat_part = stat_part, a.stats_out = statv(g0, v_out), a.rms = rms, a.eps = m.norm_eps;
-    ph.gx = ceil_div(a.tasks, target_blocks < 0 ? 3 : 4), ph.gy = a.split;
-    (void)l;
+    a.cb = i == 0 ? bias : nullptr;
+    a.x_in = x, a.x_out = x;
+    if (i == n_group - 1) a.act_out = ad, a.out_k_blocks = d / FK, a.g_out = next_gamma, a.stat_out = statd;
+    ph.gx = stream_gemm_blocks(EPI_RESID, a), ph.gy = 1;
     plan->push_back(ph);
   };
   for (int l = 0; l < L0.Ls; ++l) {
@@ -161,13 +180,12 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
       const Layout &L = s->L;
       Phase ph = {};
       ph.kind = PH_QKV, ph.shard = i;
-      SkinnyArgs &a = ph.g;
-      a.w = s->wqkv[l].ptr, a.tasks = s->wqkv[l].row_tiles, a.k_blocks = s->wqkv[l].k_blocks, a.B = B, a.N = L.qkv_n;
-      plan_skinny(&a, L.esz, L.splitk_bytes, 1, target_blocks);
-      a.x = xv(g0, 2 * l), a.stats = statv(g0, 2 * l), a.gamma = D0.ln1_g, a.beta = D0.ln1_b;
-      a.splitk = (float *)(s->ws + L.ws_splitk), a.counters = (int *)(s->ws + L.ws_counters);
-      a.bias = s->layers[l].bqkv, a.out_f32 = (float *)(s->ws + L.ws_qkv_l + l * L.qkv_l_stride), a.ld_out = L.qkv_n;
-      ph.gx = ceil_div(a.tasks, target_blocks < 0 ? 3 : 4), ph.gy = a.split;
+      StreamGemmArgs &a = ph.g;
+      a.w = s->wqkv[l].ptr, a.row_tiles = s->wqkv[l].row_tiles, a.k_blocks = s->wqkv[l].k_blocks, a.B = B, a.N = L.qkv_n;
+      a.ks = pick_ks(a.k_blocks);
+      normed(a, s->wg_qkv[l], s->cb_qkv[l]);
+      a.out_f32 = (float *)(s->ws + L.ws_qkvd), a.ld_out = L.qkv_n;
+      ph.gx = stream_gemm_blocks(EPI_F32, a), ph.gy = 1;
       plan->push_back(ph);
     }
     for (int i = 0; i < n_group; ++i) {  // attention over the committed rows + append
@@ -176,44 +194,40 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
       Phase ph = {};
       ph.kind = PH_ATTN, ph.shard = i;
       DecodeAttnArgs &a = ph.at;
-      a.qkv = (const float *)(s->ws + L.ws_qkv_l + l * L.qkv_l_stride);
+      a.qkv = (const float *)(s->ws + L.ws_qkvd);
       a.k_cache = s->kv_ptr(l, 0), a.v_cache = s->kv_ptr(l, 1);
       a.row_stride = s->kv_row_stride(), a.head_stride = s->kv_head_stride();
       a.lens = s->d_len, a.rope = m.pos == SS_POS_ROPE ? s->rope : nullptr;
       a.part = (float *)(s->ws + L.ws_attn_part);
-      a.counters = (int *)(s->ws + L.ws_counters) + (L.n_counters - L.Bmax * L.Hs);
-      a.o_out = s->ws + L.ws_o_l + l * L.o_l_stride;
+      a.counters = (int *)(s->ws + L.ws_counters) + 16;
+      a.o_out = s->ws + L.ws_od;
       a.B = B, a.Hs = L.Hs, a.Dh = L.Dh, a.Smax = L.Smax, a.kv_dtype = s->m.kv_dtype;
-      attn_plan(L, B, target_blocks < 0 ? 192 : 0, &a.rows_per_block, &a.splits);
+      attn_plan(L, B, &a.rows_per_block, &a.splits, &a.waves);
       ph.gx = B * L.Hs, ph.gy = a.splits;
       plan->push_back(ph);
     }
+    stat_groups = d / 16;  // from here on the partial sums come from the residual GEMMs' weight tiles
     for (int i = 0; i < n_group; ++i)  // output projection, sum over the group, residual
-      resid(l, i, group[i]->wo[l], group[i]->ws + group[i]->L.ws_o_l + l * group[i]->L.o_l_stride, D0.bo, 2 * l,
-            2 * l + 1);
+      resid(i, group[i]->wo[l], group[i]->ws + group[i]->L.ws_od, D0.bo, D0.ln2_g);
     for (int i = 0; i < n_group; ++i) {  // first FFN matrix + activation
       Shard *s = group[i];
       const Layout &L = s->L;
-      const bool glu = m.act == SS_ACT_SWIGLU;
       Phase ph = {};
       ph.kind = PH_FFN_UP, ph.shard = i;
-      SkinnyArgs &a = ph.g;
-      a.w = s->w1[l].ptr, a.tasks = L.Fs / 16, a.k_blocks = s->w1[l].k_blocks, a.B = B, a.N = L.Fs;
-      plan_skinny(&a, L.esz, L.splitk_bytes, glu ? 2 : 1, target_blocks);
-      a.x = xv(g0, 2 * l + 1), a.stats = statv(g0, 2 * l + 1), a.gamma = D0.ln2_g, a.beta = D0.ln2_b;
-      a.splitk = (float *)(s->ws + L.ws_splitk), a.counters = (int *)(s->ws + L.ws_counters);
-      a.bias = s->layers[l].b1, a.act_out = s->ws + L.ws_u_l + l * L.u_l_stride, a.out_k_blocks = L.Fs / FK;
-      a.act_kind = m.act;
-      ph.gx = ceil_div(a.tasks, target_blocks < 0 ? 3 : 4), ph.gy = a.split;
+      StreamGemmArgs &a = ph.g;
+      a.w = s->w1[l].ptr, a.row_tiles = s->w1[l].row_tiles, a.k_blocks = s->w1[l].k_blocks, a.B = B, a.N = L.Fs;
+      a.ks = pick_ks(a.k_blocks);
+      normed(a, s->wg_1[l], s->cb_1[l]);
+      a.act_out = s->ws + L.ws_ud, a.out_k_blocks = L.Fs / FK, a.act_kind = m.act;
+      ph.gx = stream_gemm_blocks(m.act == SS_ACT_SWIGLU ? EPI_SWIGLU : EPI_ACT, a), ph.gy = 1;
       plan->push_back(ph);
     }
+    const float *next_gamma = l + 1 < L0.Ls ? g0->layers[l + 1].ln1_g : g0->lnf_g;
     for (int i = 0; i < n_group; ++i)  // second FFN matrix, sum over the group, residual
-      resid(l, i, group[i]->w2[l], group[i]->ws + group[i]->L.ws_u_l + l * group[i]->L.u_l_stride, D0.b2, 2 * l + 1,
-            2 * l + 2);
+      resid(i, group[i]->w2[l], group[i]->ws + group[i]->L.ws_ud, D0.b2, next_gamma);
     if (l == stop_after_layer) return;
   }
-  plan->push_back(lm_head_phase(group, n_group, B, xv(g0, 2 * L0.Ls), statv(g0, 2 * L0.Ls), logits, next_tokens, 1,
-                                target_blocks));
+  plan->push_back(lm_head_phase(group, n_group, B, stat_groups, logits, next_tokens, 1));
 }
 
 // ---------------------------------------------------------------------------
@@ -256,11 +270,11 @@ static ss_status launch_phase(Shard *g0, const Phase &ph, hipStream_t st) {
       else hipLaunchKernelGGL(embed_rows<float>, dim3(ph.gx), dim3(256), 0, st, ph.e);
       SS_HIP(hipGetLastError());
       return SS_OK;
-    case PH_QKV: return launch_skinny(dt, PRO_NORM, EPI_F32, ph.g, st);
+    case PH_QKV: return launch_stream_gemm(dt, EPI_F32, ph.g, st);
     case PH_ATTN: return launch_decode_attn(dt, ph.at, st);
-    case PH_RESID: return launch_skinny(dt, PRO_ACT, EPI_RESID, ph.g, st);
-    case PH_FFN_UP: return launch_skinny(dt, PRO_NORM, g0->m.act == SS_ACT_SWIGLU ? EPI_SWIGLU : EPI_ACT, ph.g, st);
-    case PH_LM_HEAD: return launch_skinny(dt, PRO_NORM, EPI_LOGITS, ph.g, st);
+    case PH_RESID: return launch_stream_gemm(dt, EPI_RESID, ph.g, st);
+    case PH_FFN_UP: return launch_stream_gemm(dt, g0->m.act == SS_ACT_SWIGLU ? EPI_SWIGLU : EPI_ACT, ph.g, st);
+    case PH_LM_HEAD: return launch_stream_gemm(dt, EPI_LOGITS, ph.g, st);
   }
   SS_FAIL(SS_EINVAL, "unknown phase kind %d", ph.kind);
 }
@@ -268,7 +282,7 @@ static ss_status launch_phase(Shard *g0, const Phase &ph, hipStream_t st) {
 static ss_status enqueue_decode(Shard *const *group, int n_group, const int32_t *tokens_in, int B, float *logits,
                                 int32_t *next_tokens, hipStream_t st, int stop_after_layer) {
   std::vector<Phase> plan;
-  build_decode_plan(group, n_group, tokens_in, B, logits, next_tokens, stop_after_layer, 0, &plan);
+  build_decode_plan(group, n_group, tokens_in, B, logits, next_tokens, stop_after_layer, &plan);
   for (const Phase &ph : plan) SS_TRY(launch_phase(group[0], ph, st));
   if (stop_after_layer >= 0)
     SS_FAIL(SS_EINTR, "decode step interrupted after layer %d; nothing committed", stop_after_layer);
@@ -292,26 +306,6 @@ ss_status run_decode_step(Shard *const *group, int n_group, const int32_t *token
   key.ptrs = {tokens_in, logits, next_tokens, (const void *)st};
   for (int i = 0; i < n_group; ++i) key.ptrs.push_back(group[i]);
   const bool plain = !g0->timing && stop_after_layer < 0;
-  static const int persistent_default = [] {
-    // 0: graph / kernel-by-kernel (default); 1: persistent kernel; 2: wave-specialised persistent
-    // kernel (switched off: a full-size run of it ended in a GPU fault whose cause is not yet known)
-    const char *v = getenv("SS_PERSISTENT");
-    return v && *v ? atoi(v) : 0;
-  }();
-  const int persistent_version = g0->persistent_mode >= 0 ? g0->persistent_mode : persistent_default;
-  if (plain && n_group == 1 && persistent_version > 0) {
-    const bool cached = g0->phases_valid && !(g0->phases_key < key) && !(key < g0->phases_key);
-    std::vector<Phase> plan;
-    const int blocks2 = persistent_version >= 2 ? persistent2_blocks(g0, B) : 0;
-    if (blocks2 > 0) {
-      if (!cached) build_decode_plan(group, n_group, tokens_in, B, logits, next_tokens, -1, -blocks2, &plan);
-      return launch_persistent2_step(g0, plan, key, st);
-    }
-    if (persistent_supported(g0, B)) {
-      if (!cached) build_decode_plan(group, n_group, tokens_in, B, logits, next_tokens, -1, 512, &plan);
-      return launch_persistent_step(g0, plan, key, st);
-    }
-  }
   // the NULL stream cannot be captured, and a stream the caller is capturing is left to the caller
   hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
   if (st) SS_HIP(hipStreamIsCapturing(st, &cs));
@@ -357,7 +351,7 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, i
   float *x = (float *)(g0->ws + L0.ws_x);
   void *abuf = g0->ws + L0.ws_a;
   {
-    EmbedArgs e{tokens, g0->wte, g0->wpe, nullptr, S, x, nullptr, d, L0.V, rms, m.norm_eps};
+    EmbedArgs e{tokens, g0->wte, g0->wpe, nullptr, S, x, d, L0.V, nullptr, nullptr, nullptr};
     if (dt == SS_DTYPE_BF16) hipLaunchKernelGGL(embed_rows<bf16_t>, dim3(T_live), dim3(256), 0, st, e);
     else hipLaunchKernelGGL(embed_rows<float>, dim3(T_live), dim3(256), 0, st, e);
     SS_HIP(hipGetLastError());
@@ -421,12 +415,14 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, i
       SS_TRY(launch_tile_gemm(dt, EPI_RESID, a, st));
     }
   }
-  float *xd = xv(g0, 2 * L0.Ls);
-  float *stats = statv(g0, 2 * L0.Ls);
-  hipLaunchKernelGGL(gather_last, dim3(B), dim3(256), 0, st, x, S, xd, stats, d, rms, m.norm_eps);
+  float *xd = (float *)(g0->ws + L0.ws_xd);
+  void *ad = g0->ws + L0.ws_ad;
+  float *statd = (float *)(g0->ws + L0.ws_statd);
+  if (dt == SS_DTYPE_BF16) hipLaunchKernelGGL(gather_last<bf16_t>, dim3(B), dim3(256), 0, st, x, S, xd, g0->lnf_g, ad, statd, d);
+  else hipLaunchKernelGGL(gather_last<float>, dim3(B), dim3(256), 0, st, x, S, xd, g0->lnf_g, ad, statd, d);
   SS_HIP(hipGetLastError());
-  const Phase ph = lm_head_phase(group, n_group, B, xd, stats, logits, next_tokens, S, 0);
-  return launch_skinny(dt, PRO_NORM, EPI_LOGITS, ph.g, st);
+  const Phase ph = lm_head_phase(group, n_group, B, 1, logits, next_tokens, S);
+  return launch_stream_gemm(dt, EPI_LOGITS, ph.g, st);
 }
 
 }  // namespace ss
@@ -455,40 +451,20 @@ ss_status ss_prefill(ss_shard *const *group_, int32_t n_group, const int32_t *to
 // Host-only check aid: the phase table of one decode step for a shard of the given shape whose
 // device memory starts at address `fake_base` (nothing is allocated or launched).  Writes up to
 // max_phases Phase records to out_phases, the layout's total bytes to out_total, returns the
-// number of phases (negative on error).  mode: 0 kernel-by-kernel plan, > 0 resident blocks of
-// the persistent kernel (1: block bodies, 2: wave-specialised).
+// number of phases (negative on error).
 int32_t ss_debug_plan(const ss_model_desc *desc, const ss_slice *slice, int32_t max_batch, int32_t max_seq, int32_t B,
-                      int32_t mode, int32_t blocks, uint64_t fake_base, void *out_phases, int32_t max_phases,
-                      uint64_t *out_total, uint64_t *out_sizeof_phase) {
+                      uint64_t fake_base, void *out_phases, int32_t max_phases, uint64_t *out_total,
+                      uint64_t *out_sizeof_phase) {
   if (!desc || !slice || validate_desc(*desc, *slice, max_batch, max_seq) != SS_OK) return -1;
   Shard sh;
   sh.m = *desc, sh.s = *slice;
   compute_layout(*desc, *slice, max_batch, max_seq, &sh.L);
   const Layout &L = sh.L;
   sh.base = (char *)fake_base;
-  sh.wte = sh.base + L.off_wte, sh.wpe = L.max_pos ? sh.base + L.off_wpe : nullptr;
-  sh.lnf_g = (float *)(sh.base + L.off_lnf_g), sh.lnf_b = (float *)(sh.base + L.off_lnf_b);
-  sh.rope = (float2 *)(sh.base + L.off_rope), sh.kv = sh.base + L.off_kv, sh.d_len = (int32_t *)(sh.base + L.off_len);
-  sh.ws = sh.base + L.off_ws;
-  const int FK = desc->dtype == SS_DTYPE_BF16 ? 32 : 16, d = L.d, HD = L.Hs * L.Dh;
-  sh.lm_head = FragMat{sh.base + L.off_lm, L.V, d, ceil_div(L.V, 16), d / FK};
-  sh.layers.resize(L.Ls), sh.wqkv.resize(L.Ls), sh.wo.resize(L.Ls), sh.w1.resize(L.Ls), sh.w2.resize(L.Ls);
-  for (int l = 0; l < L.Ls; ++l) {
-    char *lb = sh.base + L.off_layer[l];
-    sh.wqkv[l] = FragMat{lb + L.lo_wqkv, L.qkv_n, d, L.qkv_n / 16, d / FK};
-    sh.wo[l] = FragMat{lb + L.lo_wo, d, HD, d / 16, HD / FK};
-    sh.w1[l] = FragMat{lb + L.lo_w1, L.w1_rows, d, L.w1_rows / 16, d / FK};
-    sh.w2[l] = FragMat{lb + L.lo_w2, d, L.Fs, d / 16, L.Fs / FK};
-    LayerDev &D = sh.layers[l];
-    D.ln1_g = (float *)(lb + L.lo_ln1_g), D.ln1_b = (float *)(lb + L.lo_ln1_b);
-    D.ln2_g = (float *)(lb + L.lo_ln2_g), D.ln2_b = (float *)(lb + L.lo_ln2_b);
-    D.bqkv = (float *)(lb + L.lo_bqkv), D.bo = (float *)(lb + L.lo_bo), D.b1 = (float *)(lb + L.lo_b1),
-    D.b2 = (float *)(lb + L.lo_b2);
-  }
+  bind_pointers(&sh);
   Shard *group[1] = {&sh};
   std::vector<Phase> plan;
-  build_decode_plan(group, 1, (const int32_t *)8, B, (float *)16, (int32_t *)24, -1, mode == 0 ? 0 : (mode == 1 ? blocks : -blocks),
-                    &plan);
+  build_decode_plan(group, 1, (const int32_t *)8, B, (float *)16, (int32_t *)24, -1, &plan);
   if (out_total) *out_total = L.total;
   if (out_sizeof_phase) *out_sizeof_phase = sizeof(Phase);
   const int n = (int)plan.size();

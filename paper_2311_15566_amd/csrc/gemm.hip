@@ -1,8 +1,6 @@
-// GEMM kernels on the matrix cores: the skinny (decode) weight-streaming GEMM with fused
-// prologues/epilogues, and the tiled prefill GEMM.
+// The tiled GEMM of the initial phase (matrix-core bound).
 #include "kernels.h"
 #include "mma.h"
-#include "skinny_block.h"
 
 #include <limits.h>
 #include <math.h>
@@ -11,104 +9,6 @@
 #include <algorithm>
 
 namespace ss {
-
-// ---------------------------------------------------------------------------
-// skinny GEMM as a kernel of its own: grid = (groups of 4 wave tasks, K splits)
-// ---------------------------------------------------------------------------
-template <typename T, int NB, int NW, int PRO, int EPI>
-__global__ void __launch_bounds__(256) skinny_gemm(SkinnyArgs a) {
-  extern __shared__ __align__(16) char smem[];
-  __shared__ SkinnyShared sh;
-  skinny_block<T, NB, NW, PRO, EPI>(a, blockIdx.x, blockIdx.y, gridDim.x, (u32x4 *)smem, sh);
-}
-
-static int env_int(const char *name, int dflt) {
-  const char *v = getenv(name);
-  return v && *v ? atoi(v) : dflt;
-}
-
-void plan_skinny(SkinnyArgs *a, int esz, size_t splitk_bytes, int nw, int target) {
-  a->nb = a->B <= 16 ? 1 : 2;
-  const int parts = esz == 2 ? 2 : 1;                                   // bf16 activations are hi/lo pairs
-  const size_t per_split = (size_t)a->nb * 16 * a->tasks * nw * 16 * 4;
-  if (target < 0) {
-    // persistent kernel: 3 compute waves per block; a wave holds at most 32 fragments in
-    // registers and the block's staged activations must fit its LDS, so a block walks its K
-    // range in chunks of at most max_kb k blocks (accumulating in registers) and K may also be
-    // split across blocks (partials through memory, last arriver reduces).  Cost in units of one
-    // fragment per wave: rounds over the resident blocks x (chunks x (fragments + staging) +
-    // hand-off), the hand-off dearer when partials go through memory.
-    const int nblocks = -target;
-    const int groups = ceil_div(a->tasks, 3);
-    const int max_kb = std::max(1, std::min(32 / nw, (a->nb == 1 ? 64 : 56) / (a->nb * parts)));
-    int best_s = 1, best_chunk = std::min(max_kb, a->k_blocks);
-    long best_cost = -1;
-    for (int s = 1; s <= std::max(1, a->k_blocks / 4); ++s) {
-      if (s > 1 && per_split * s > splitk_bytes) break;
-      const int kbps = ceil_div(a->k_blocks, s);
-      if (ceil_div(a->k_blocks, kbps) != s) continue;  // same split count as a smaller s
-      const int chunks = ceil_div(kbps, max_kb);
-      const int lc = ceil_div(kbps, chunks);
-      const long rounds = ceil_div(groups * s, nblocks);
-      const long cost = rounds * ((long)chunks * (lc * nw + 6) + (s > 1 ? 8 + a->B / 8 : 3));
-      if (best_cost < 0 || cost < best_cost) best_s = s, best_chunk = lc, best_cost = cost;
-    }
-    a->kb_per_split = ceil_div(a->k_blocks, best_s);
-    a->split = ceil_div(a->k_blocks, a->kb_per_split);
-    a->lds_chunk = best_chunk;
-    return;
-  }
-  const int groups = ceil_div(a->tasks, 4);
-  static const int dflt_blocks = env_int("SS_SKINNY_BLOCKS", 512);  // 2 blocks per compute unit
-  const int target_blocks = target > 0 ? target : dflt_blocks;
-  static const int lds_kb = env_int("SS_SKINNY_LDS_KB", 64);
-  const int max_chunk = std::max(16, lds_kb / (a->nb * parts) / 16 * 16);  // k blocks staged at a time, multiple of 16
-  int split = std::max(1, std::min(target_blocks / std::max(groups, 1), a->k_blocks / 4));
-  while (split > 1 && per_split * split > splitk_bytes) --split;
-  a->kb_per_split = ceil_div(a->k_blocks, split);
-  a->split = ceil_div(a->k_blocks, a->kb_per_split);
-  a->lds_chunk = a->kb_per_split <= max_chunk ? a->kb_per_split : max_chunk;
-}
-
-template <typename T, int NB>
-static void launch_skinny_t(int pro, int epi, const SkinnyArgs &a, dim3 grid, size_t lds, hipStream_t st) {
-#define SS_LAUNCH(NW, PRO, EPI) hipLaunchKernelGGL((skinny_gemm<T, NB, NW, PRO, EPI>), grid, dim3(256), lds, st, a)
-  if (pro == PRO_NORM && epi == EPI_F32) SS_LAUNCH(1, PRO_NORM, EPI_F32);
-  else if (pro == PRO_NORM && epi == EPI_LOGITS) SS_LAUNCH(1, PRO_NORM, EPI_LOGITS);
-  else if (pro == PRO_NORM && epi == EPI_ACT) SS_LAUNCH(1, PRO_NORM, EPI_ACT);
-  else if (pro == PRO_NORM && epi == EPI_SWIGLU) SS_LAUNCH(2, PRO_NORM, EPI_SWIGLU);
-  else if (pro == PRO_ACT && epi == EPI_RESID) SS_LAUNCH(1, PRO_ACT, EPI_RESID);
-#undef SS_LAUNCH
-}
-
-ss_status check_skinny(int dtype, const SkinnyArgs &a) {
-  if (a.B < 1 || a.B > 32 || a.nb != (a.B <= 16 ? 1 : 2)) SS_FAIL(SS_EINVAL, "skinny GEMM: batch %d / tiles %d", a.B, a.nb);
-  if (a.tasks < 1 || a.k_blocks < 1 || a.split < 1 || a.kb_per_split < 1 || a.lds_chunk < 1 ||
-      (size_t)a.split * a.kb_per_split < (size_t)a.k_blocks || a.lds_chunk * a.nb * (dtype == SS_DTYPE_BF16 ? 2 : 1) > 64 ||
-      a.lds_chunk > a.kb_per_split)
-    SS_FAIL(SS_EINVAL, "skinny GEMM: inconsistent plan");
-  return SS_OK;
-}
-
-ss_status launch_skinny(int dtype, int pro, int epi, const SkinnyArgs &a, hipStream_t st) {
-  const bool ok_combo = (pro == PRO_NORM && (epi == EPI_F32 || epi == EPI_LOGITS || epi == EPI_ACT || epi == EPI_SWIGLU)) ||
-                        (pro == PRO_ACT && epi == EPI_RESID);
-  if (!ok_combo) SS_FAIL(SS_EINVAL, "skinny GEMM: unsupported prologue/epilogue pair %d/%d", pro, epi);
-  SS_TRY(check_skinny(dtype, a));
-  if (a.lds_chunk < a.kb_per_split && a.lds_chunk % 16) SS_FAIL(SS_EINVAL, "skinny GEMM: chunk of %d k blocks", a.lds_chunk);
-  const int groups = ceil_div(a.tasks, 4);
-  dim3 grid(groups, a.split);
-  size_t lds = (size_t)a.nb * a.lds_chunk * (dtype == SS_DTYPE_BF16 ? 2 : 1) * 1024;
-  if (dtype == SS_DTYPE_BF16) {
-    if (a.nb == 1) launch_skinny_t<bf16_t, 1>(pro, epi, a, grid, lds, st);
-    else launch_skinny_t<bf16_t, 2>(pro, epi, a, grid, lds, st);
-  } else {
-    if (a.nb == 1) launch_skinny_t<float, 1>(pro, epi, a, grid, lds, st);
-    else launch_skinny_t<float, 2>(pro, epi, a, grid, lds, st);
-  }
-  SS_HIP(hipGetLastError());
-  return SS_OK;
-}
 
 // ---------------------------------------------------------------------------
 // tiled prefill GEMM: block = 128 output features x 128 tokens, 4 waves of 64 x 64,

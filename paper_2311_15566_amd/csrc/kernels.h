@@ -5,59 +5,59 @@
 
 namespace ss {
 
-enum Prologue { PRO_ACT = 0, PRO_NORM = 1 };
 enum Epilogue { EPI_F32 = 0, EPI_RESID = 1, EPI_ACT = 2, EPI_SWIGLU = 3, EPI_LOGITS = 4 };
 
-// Skinny GEMM of the decode step: out[b, n] = sum_k act[b, k] * W[n, k], b < B <= 32.
-// HBM-bound weight streaming: each wave streams whole 1 KiB weight fragments, activations are
-// staged once per block in LDS, split-K partials are reduced by the last block to arrive
-// (fixed order, so results do not depend on scheduling).
-struct SkinnyArgs {
-  // weights
-  const void *w;
-  int tasks;      // wave tasks: 16-row tiles (SwiGLU: gate/up tile pairs)
-  int k_blocks;   // fragments along K
-  int split;      // blocks along K
-  int kb_per_split;
-  int lds_chunk;  // fragments staged in LDS at a time
-  int B;          // live batch rows
-  int nb;         // 16-row batch tiles (1 or 2)
-  int N;          // logical output features (for masking)
-  // prologue
-  const void *act;      // PRO_ACT: fragments [nb][k_blocks]
-  const float *x;       // PRO_NORM: [B][K] float32, row-major
-  const float *stats;   // PRO_NORM: [32][2] = (mean, 1/std)
-  const float *gamma, *beta;
-  // split-K scratch
-  float *splitk;
-  int *counters;        // [groups] + 1
+// Weight-streaming GEMM of the decode step: out[b, n] = sum_k act[b, k] * W[n, k], b < B <= 32.
+// HBM-bound.  One block owns a pair of 16-row weight tiles (SwiGLU: a gate/up pair) over the
+// whole of K; its waves split K between them, each streaming 1 KiB weight fragments and the
+// matching activation fragments (from L2) straight into registers, and add their sums up
+// through LDS, so nothing of the product goes through memory and no block waits for another.
+//
+// Deferred normalisation: where the GEMM input is Norm(x) = (x - mean) * rstd * gamma + beta, the
+// operand holds x * gamma (written by the producer of x before the row statistics exist) and the
+// epilogue applies  rstd * (acc - mean * wg[n]) + cb[n]  with wg[n] = sum_k W[n,k] gamma[k] and
+// cb[n] = sum_k W[n,k] beta[k] + bias[n], both folded when the weights are uploaded.  mean and
+// rstd come from the producer's per-tile partial sums (sum x, sum x^2), added in tile order.
+struct StreamGemmArgs {
+  const void *w;        // weight fragments [row_tiles][k_blocks]
+  int row_tiles;        // 16-row tiles (SwiGLU: gate/up tiles interleaved, 2 per 16 outputs)
+  int k_blocks;
+  int ks;               // waves per block = slices of K (4 or 8)
+  int B;                // live batch rows
+  int N;                // logical output features (for masking)
+  const void *act;      // operand fragments [B tiles][k_blocks][parts]
+  // deferred normalisation (stat_groups > 0)
+  const float *stat_in; // [stat_groups][32][2] partial (sum, sum of squares) of the rows of x
+  int stat_groups;
+  int norm_dim;         // length of a row of x
+  int rms;
+  float eps;
+  const float *wg;      // [row_tiles * 16] or NULL (RMSNorm)
+  const float *cb;      // [row_tiles * 16] folded beta and bias, or the plain bias, or NULL
   // epilogues
-  const float *bias;
   float *out_f32;       // EPI_F32 / EPI_LOGITS: [B][ld_out]
   int ld_out;
   const float *x_in;    // EPI_RESID: residual stream before this GEMM, [B][N]
-  float *x_resid;       // EPI_RESID: residual stream after it (may equal x_in only when no other block of the
-                        // same launch reads it)
-  float *stat_part;     // EPI_RESID: [groups][32][2]
-  float *stats_out;     // EPI_RESID: [32][2]
-  int rms;              // EPI_RESID: statistics for RMSNorm (no mean)
-  float eps;
-  void *act_out;        // EPI_ACT / EPI_SWIGLU: fragments [nb][out_k_blocks]
+  float *x_out;         // EPI_RESID: after it (may equal x_in)
+  void *act_out;        // EPI_ACT / EPI_SWIGLU: activation fragments; EPI_RESID: x_out * g_out (or NULL)
   int out_k_blocks;
+  const float *g_out;   // EPI_RESID: gamma of the norm that follows
+  float *stat_out;      // EPI_RESID: [row_tiles][32][2] partial sums of x_out (with act_out)
   int act_kind;
-  float *am_val;        // EPI_LOGITS: [groups][32]
+  float *am_val;        // EPI_LOGITS: [blocks][32]
   int *am_idx;
+  int *counter;         // EPI_LOGITS: arrival counter of the grid
   int32_t *next_tokens;
   int32_t *lens[8];     // EPI_LOGITS: committed lengths to advance (all shards of the group)
   int n_lens;
   int commit_inc;
 };
-ss_status launch_skinny(int dtype, int pro, int epi, const SkinnyArgs &a, hipStream_t st);
-ss_status check_skinny(int dtype, const SkinnyArgs &a);  // the shape checks launch_skinny makes
-// fills split / kb_per_split / lds_chunk / nb from the shape
-// (target_blocks = 0: the default of the kernel-by-kernel path; < 0: plan for the persistent kernel
-// with -target_blocks resident blocks)
-void plan_skinny(SkinnyArgs *a, int esz, size_t splitk_bytes, int weight_tiles_per_wave, int target_blocks);
+ss_status launch_stream_gemm(int dtype, int epi, const StreamGemmArgs &a, hipStream_t st);
+ss_status check_stream_gemm(int dtype, int epi, const StreamGemmArgs &a);  // the shape checks the launcher makes
+int stream_gemm_blocks(int epi, const StreamGemmArgs &a);
+// wg / cb of a weight matrix in fragment order (gamma NULL: wg is not written)
+ss_status launch_fold_norm(int dtype, const void *w, int row_tiles, int k_blocks, const float *gamma, const float *beta,
+                           const float *bias, float *wg, float *cb, hipStream_t st);
 
 // Prefill GEMM: out[t, n] = sum_k act[t, k] * W[n, k] over T tokens (multiple of 128), MFMA-bound.
 struct TileGemmArgs {
@@ -93,12 +93,12 @@ struct DecodeAttnArgs {
   int B, Hs, Dh, Smax;
   int kv_dtype;         // cache element type (SS_DTYPE_*)
   int rows_per_block, splits;
+  int waves;            // per block: 4, or 16 when one block takes a whole (row, head)
 };
 ss_status launch_decode_attn(int dtype, const DecodeAttnArgs &a, hipStream_t st);
 ss_status check_decode_attn(const DecodeAttnArgs &a);
 
-// One phase of the decode step: a kernel of the kernel-by-kernel path, or one stretch between
-// two device-wide barriers of the persistent kernel.
+// One phase of the decode step = one kernel launch.
 enum PhaseKind { PH_EMBED = 0, PH_QKV = 1, PH_ATTN = 2, PH_RESID = 3, PH_FFN_UP = 4, PH_LM_HEAD = 5 };
 struct EmbedArgs {
   const int32_t *tokens;  // [rows]
@@ -106,17 +106,19 @@ struct EmbedArgs {
   const int32_t *lens;    // decode: position = committed length; NULL: position = row % S
   int S;
   float *x;               // [rows][d]
-  float *stats;           // [rows][2] (mean, 1/std) of the first norm, or NULL
-  int d, V, rms;
-  float eps;
+  int d, V;
+  // decode step only (NULL in the initial phase): operand of the first GEMM and its row sums
+  const float *gamma;     // gamma of the first norm
+  void *act_out;          // x * gamma as operand fragments [rows / 16][d / FragK][parts]
+  float *stat_out;        // [32][2] (sum x, sum x^2) per row
 };
 
 struct Phase {
   int kind;      // PhaseKind; also the timing class
-  int gx, gy;    // blocks: (rows, 1), (groups, splits) or (batch*heads, splits)
+  int gx, gy;    // blocks: (rows, 1), (tile pairs, 1) or (batch*heads, splits)
   int shard;     // index of the shard in the group that owns the phase's scratch
   EmbedArgs e;
-  SkinnyArgs g;
+  StreamGemmArgs g;
   DecodeAttnArgs at;
 };
 

@@ -45,63 +45,48 @@ __device__ __forceinline__ void widen16<bf16_t>(const u32x4 &raw, float *out) {
   }
 }
 
-// x[r] = wte[token] (+ wpe[position]) with 16-byte loads, the row held in registers for the
-// two-pass statistics.  d <= 16384.  DEV: device-scope stores (see the single-assignment rule).
-template <typename T, bool DEV>
+// x[r] = wte[token] (+ wpe[position]) with 16-byte loads, the row held in registers.  With
+// a.act_out set (decode step) also the first GEMM's operand x * gamma and the row's (sum, sum of
+// squares).  d <= 16384.
+template <typename T>
 __device__ __forceinline__ void embed_row_block(const EmbedArgs &a, const int r, float *scratch) {
-  constexpr int PL = Elem<T>::kPerLane, MAXV = 64 / PL;
+  constexpr int PL = Elem<T>::kPerLane, FK = Elem<T>::kFragK, MAXV = 64 / PL;
   int tok = a.tokens[r];
   tok = min(max(tok, 0), a.V - 1);
   const int pos = a.lens ? a.lens[r] : (r % a.S);
   const int nvec = a.d / PL;
   const u32x4 *te = (const u32x4 *)((const T *)a.wte + (size_t)tok * a.d);
   const u32x4 *pe = a.wpe ? (const u32x4 *)((const T *)a.wpe + (size_t)pos * a.d) : nullptr;
-  float vals[MAXV][PL];
-  float s = 0.f;
+  float s1 = 0.f, s2 = 0.f;
 #pragma unroll
   for (int i = 0; i < MAXV; ++i) {
     const int v = threadIdx.x + i * 256;
     if (v < nvec) {
-      widen16<T>(te[v], vals[i]);
+      float vals[PL];
+      widen16<T>(te[v], vals);
       if (pe) {
         float p[PL];
         widen16<T>(pe[v], p);
 #pragma unroll
-        for (int e = 0; e < PL; ++e) vals[i][e] += p[e];
+        for (int e = 0; e < PL; ++e) vals[e] += p[e];
       }
       float *xo = a.x + (size_t)r * a.d + (size_t)v * PL;
 #pragma unroll
       for (int e = 0; e < PL; ++e) {
-        s += vals[i][e];
-        if (DEV) st_dev(xo + e, vals[i][e]);
-        else xo[e] = vals[i][e];
+        s1 += vals[e], s2 += vals[e] * vals[e];
+        xo[e] = vals[e];
+      }
+      if (a.act_out) {
+#pragma unroll
+        for (int e = 0; e < PL; ++e)
+          store_act<T>(a.act_out, r, v * PL + e, a.d / FK, Elem<T>::kParts, vals[e] * a.gamma[v * PL + e]);
       }
     }
   }
-  if (a.stats) {
-    const float mean = a.rms ? 0.f : block_sum(s, scratch) / (float)a.d;
-    float q = 0.f;
-#pragma unroll
-    for (int i = 0; i < MAXV; ++i) {
-      const int v = threadIdx.x + i * 256;
-      if (v < nvec) {
-#pragma unroll
-        for (int e = 0; e < PL; ++e) {
-          const float c = vals[i][e] - mean;
-          q += c * c;
-        }
-      }
-    }
-    const float var = block_sum(q, scratch) / (float)a.d;
-    if (threadIdx.x == 0) {
-      if (DEV) {
-        st_dev(&a.stats[r * 2], mean);
-        st_dev(&a.stats[r * 2 + 1], rsqrtf(var + a.eps));
-      } else {
-        a.stats[r * 2] = mean;
-        a.stats[r * 2 + 1] = rsqrtf(var + a.eps);
-      }
-    }
+  if (a.stat_out) {
+    s1 = block_sum(s1, scratch);
+    s2 = block_sum(s2, scratch);
+    if (threadIdx.x == 0) a.stat_out[r * 2] = s1, a.stat_out[r * 2 + 1] = s2;
   }
 }
 

@@ -27,22 +27,17 @@ struct Layout {
   std::vector<size_t> off_layer;       // start of each layer's block
   size_t layer_bytes;
   size_t lo_ln1_g, lo_ln1_b, lo_ln2_g, lo_ln2_b, lo_wqkv, lo_bqkv, lo_wo, lo_bo, lo_w1, lo_b1, lo_w2, lo_b2;
+  size_t lo_wg_qkv, lo_cb_qkv, lo_wg_1, lo_cb_1;  // gamma / beta+bias folded into the QKV and first FFN matrices
+  size_t off_wg_lm, off_cb_lm;
   size_t off_kv, kv_bytes, off_len;
   size_t off_ws, ws_bytes;             // workspace, doubles as upload staging
   // workspace sub-offsets (relative to off_ws)
-  size_t ws_x, ws_a, ws_qkv, ws_o, ws_u, ws_splitk, splitk_bytes, ws_stat_part, ws_counters, ws_attn_part,
-      ws_argmax;
+  size_t ws_x, ws_a, ws_qkv, ws_o, ws_u, ws_counters, ws_attn_part, ws_argmax;
   int n_counters;
-  // decode step: every buffer one block writes and another block of the same launch reads is
-  // written once per step (single-assignment rule), so each producer has its own
-  size_t ws_xv, xv_stride;        // residual stream versions: [2*Ls + 3][32][d] f32 (last two: group ping-pong)
-  size_t ws_statv;                // norm statistics per version: [2*Ls + 3][32][2]
-  size_t ws_qkv_l, qkv_l_stride;  // per layer: [32][qkv_n] f32
-  size_t ws_o_l, o_l_stride;      // per layer: attention output operand
-  size_t ws_u_l, u_l_stride;      // per layer: FFN activation operand
-  size_t ws_phases, phases_bytes; // the persistent kernel's phase table
-  size_t ws_bar;                  // grid-barrier state (int32 x 2048)
-  size_t ws_trace;                // per-phase clock trace of the persistent kernel (measurement aid)
+  // decode step (rows = batch): residual stream [32][d] f32, operand of the next normalised GEMM
+  // (x * gamma), partial row sums [d/16][32][2], q|k|v [32][qkv_n] f32, attention output and FFN
+  // activation operands
+  size_t ws_xd, ws_ad, ws_statd, ws_qkvd, ws_od, ws_ud;
   size_t total;
 };
 
@@ -66,6 +61,9 @@ struct Shard {
   float2 *rope = nullptr;  // [Smax][Dh/2] (cos, sin)
   std::vector<LayerDev> layers;
   std::vector<FragMat> wqkv, wo, w1, w2;
+  // folded norm vectors of the decode GEMMs (NULL where the model has none)
+  std::vector<float *> wg_qkv, cb_qkv, wg_1, cb_1;
+  float *wg_lm = nullptr, *cb_lm = nullptr;
   // cache context
   char *kv = nullptr;      // [Ls][2][Bmax][Hs][Smax][Dh]
   int32_t *d_len = nullptr;
@@ -74,10 +72,6 @@ struct Shard {
   char *ws = nullptr;
   int interrupt_after = -1;
   bool use_graph = true;
-  int persistent_mode = -1;  // -1: the process default; 0 off; 1 block-body kernel; 2 wave-specialised kernel
-  GraphKey phases_key;   // what the phase table on the device was built for
-  bool phases_valid = false;
-  std::vector<Phase> host_plan;
   std::map<GraphKey, hipGraphExec_t> graphs;
   // per-kernel-class event timing (measurement aid)
   bool timing = false;
@@ -94,6 +88,7 @@ struct Shard {
 
 // shard.hip
 ss_status validate_desc(const ss_model_desc &m, const ss_slice &s, int max_batch, int max_seq);
+void bind_pointers(Shard *sh);  // every device pointer of the shard from base + layout
 
 // decode.hip
 ss_status run_decode_step(Shard *const *group, int n_group, const int32_t *tokens_in, int B, float *logits,
@@ -101,13 +96,5 @@ ss_status run_decode_step(Shard *const *group, int n_group, const int32_t *token
 ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, int B, int S_in, float *logits,
                       int32_t *next_tokens, hipStream_t st);
 void destroy_graphs(Shard *sh);
-
-// step.hip: the whole decode step as one persistent kernel (bf16, head_dim 128, one shard)
-bool persistent_supported(const Shard *sh, int B);
-// step2.hip: the wave-specialised persistent kernel; resident blocks, or 0 if unsupported
-int persistent2_blocks(const Shard *sh, int B);
-ss_status launch_persistent2_step(Shard *sh, const std::vector<Phase> &plan, const GraphKey &key, hipStream_t st);
-ss_status launch_persistent_step(Shard *sh, const std::vector<Phase> &plan, const GraphKey &key, hipStream_t st);
-ss_status persistent_check_abort(const Shard *sh, hipStream_t st);
 
 }  // namespace ss

@@ -84,6 +84,8 @@ bool compute_layout(const ss_model_desc &m, const ss_slice &s, int max_batch, in
   L->off_lm = take(frag_bytes(L->V, d, esz));
   L->off_lnf_g = take((size_t)d * 4);
   L->off_lnf_b = take((size_t)d * 4);
+  L->off_wg_lm = take(align_up((size_t)L->V, 16) * 4);
+  L->off_cb_lm = take(align_up((size_t)L->V, 16) * 4);
   L->off_rope = take((size_t)max_seq * (L->Dh / 2) * sizeof(float2));
   // one layer's block
   size_t lo = 0;
@@ -104,6 +106,10 @@ bool compute_layout(const ss_model_desc &m, const ss_slice &s, int max_batch, in
   L->lo_b1 = ltake((size_t)L->w1_rows * 4);
   L->lo_w2 = ltake(frag_bytes(d, L->Fs, esz));
   L->lo_b2 = ltake((size_t)d * 4);
+  L->lo_wg_qkv = ltake((size_t)L->qkv_n * 4);
+  L->lo_cb_qkv = ltake((size_t)L->qkv_n * 4);
+  L->lo_wg_1 = ltake((size_t)L->w1_rows * 4);
+  L->lo_cb_1 = ltake((size_t)L->w1_rows * 4);
   L->layer_bytes = lo;
   L->off_layer.clear();
   for (int l = 0; l < L->Ls; ++l) L->off_layer.push_back(take(L->layer_bytes));
@@ -118,7 +124,6 @@ bool compute_layout(const ss_model_desc &m, const ss_slice &s, int max_batch, in
     return at;
   };
   const int T = L->Tmax;
-  const int nmax = std::max(std::max(L->qkv_n, L->w1_rows), std::max(d, (int)align_up(L->V, 64)));
   L->ws_x = wtake((size_t)T * d * 4);
   L->ws_a = wtake((size_t)T * d * esz * (esz == 2 ? 2 : 1));  // bf16: hi/lo pairs
   L->ws_qkv = wtake((size_t)T * L->qkv_n * 4);
@@ -126,27 +131,17 @@ bool compute_layout(const ss_model_desc &m, const ss_slice &s, int max_batch, in
   L->ws_u = wtake((size_t)T * L->Fs * esz * (esz == 2 ? 2 : 1));
   {
     const int fk = esz == 2 ? 32 : 16, parts = esz == 2 ? 2 : 1;
-    L->xv_stride = align_up((size_t)32 * d * 4, 256);
-    L->ws_xv = wtake(L->xv_stride * (2 * L->Ls + 3));
-    L->ws_statv = wtake((size_t)(2 * L->Ls + 3) * 64 * 4);
-    L->qkv_l_stride = align_up((size_t)32 * L->qkv_n * 4, 256);
-    L->ws_qkv_l = wtake(L->qkv_l_stride * L->Ls);
-    L->o_l_stride = (size_t)2 * (HD / fk) * parts * 1024;
-    L->ws_o_l = wtake(L->o_l_stride * L->Ls);
-    L->u_l_stride = (size_t)2 * (L->Fs / fk) * parts * 1024;
-    L->ws_u_l = wtake(L->u_l_stride * L->Ls);
-    L->phases_bytes = (size_t)(5 * L->Ls + 2) * 1024;
-    L->ws_phases = wtake(L->phases_bytes);
-    L->ws_trace = wtake((size_t)(5 * L->Ls + 66) * 8);
-    L->ws_bar = wtake((size_t)2048 * 4);  // [0,1024) barrier state, [1024,1536) per-block progress, [1536,..) abort record
+    L->ws_xd = wtake((size_t)32 * d * 4);
+    L->ws_ad = wtake((size_t)2 * (d / fk) * parts * 1024);
+    L->ws_statd = wtake((size_t)(d / 16) * 32 * 2 * 4);
+    L->ws_qkvd = wtake((size_t)32 * L->qkv_n * 4);
+    L->ws_od = wtake((size_t)2 * (HD / fk) * parts * 1024);
+    L->ws_ud = wtake((size_t)2 * (L->Fs / fk) * parts * 1024);
   }
-  L->splitk_bytes = std::min<size_t>((size_t)64 << 20, (size_t)16 * L->Bpad * nmax * 4);
-  L->ws_splitk = wtake(L->splitk_bytes);
-  L->ws_stat_part = wtake((size_t)(ceil_div(d, 48) + 8) * 32 * 2 * 4);
-  L->n_counters = 16 + ceil_div(nmax, 48) + max_batch * L->Hs;
+  L->n_counters = 16 + max_batch * L->Hs;  // [0]: the LM head's arrival counter; [16..): attention, per (row, head)
   L->ws_counters = wtake((size_t)L->n_counters * 4);
   L->ws_attn_part = wtake((size_t)max_batch * L->Hs * L->attn_splits * (L->Dh + 4) * 4);
-  L->ws_argmax = wtake((size_t)(ceil_div(nmax, 48) + 8) * 32 * 8);
+  L->ws_argmax = wtake((size_t)ceil_div(ceil_div(L->V, 16), 2) * 32 * 8);
   // upload staging shares the workspace: it must hold the largest raw tensor slice
   size_t stage = std::max((size_t)L->V * d, (size_t)d * std::max(std::max(HD, L->Fs), 1)) * esz;
   L->ws_bytes = std::max(w, align_up(stage, 256));
@@ -269,6 +264,47 @@ size_t ss_shard_device_bytes(const ss_model_desc *desc, const ss_slice *slice, i
 
 namespace ss {
 
+void bind_pointers(Shard *sh) {
+  const Layout &L = sh->L;
+  const ss_model_desc &m = sh->m;
+  const int FK = m.dtype == SS_DTYPE_BF16 ? 32 : 16, d = L.d, HD = L.Hs * L.Dh;
+  const bool bias = m.has_bias, ln = m.norm == SS_NORM_LAYERNORM, glu = m.act == SS_ACT_SWIGLU;
+  char *base = sh->base;
+  sh->wte = base + L.off_wte;
+  sh->wpe = L.max_pos ? base + L.off_wpe : nullptr;
+  sh->lnf_g = (float *)(base + L.off_lnf_g);
+  sh->lnf_b = ln ? (float *)(base + L.off_lnf_b) : nullptr;
+  sh->wg_lm = ln ? (float *)(base + L.off_wg_lm) : nullptr;
+  sh->cb_lm = ln ? (float *)(base + L.off_cb_lm) : nullptr;
+  sh->rope = (float2 *)(base + L.off_rope);
+  sh->kv = base + L.off_kv;
+  sh->d_len = (int32_t *)(base + L.off_len);
+  sh->ws = base + L.off_ws;
+  sh->lm_head = FragMat{base + L.off_lm, L.V, d, ceil_div(L.V, 16), d / FK};
+  sh->layers.resize(L.Ls);
+  sh->wqkv.resize(L.Ls), sh->wo.resize(L.Ls), sh->w1.resize(L.Ls), sh->w2.resize(L.Ls);
+  sh->wg_qkv.resize(L.Ls), sh->cb_qkv.resize(L.Ls), sh->wg_1.resize(L.Ls), sh->cb_1.resize(L.Ls);
+  for (int l = 0; l < L.Ls; ++l) {
+    char *lb = base + L.off_layer[l];
+    sh->wqkv[l] = FragMat{lb + L.lo_wqkv, L.qkv_n, d, L.qkv_n / 16, d / FK};
+    sh->wo[l] = FragMat{lb + L.lo_wo, d, HD, d / 16, HD / FK};
+    sh->w1[l] = FragMat{lb + L.lo_w1, L.w1_rows, d, L.w1_rows / 16, d / FK};
+    sh->w2[l] = FragMat{lb + L.lo_w2, d, L.Fs, d / 16, L.Fs / FK};
+    LayerDev &D = sh->layers[l];
+    D.ln1_g = (float *)(lb + L.lo_ln1_g), D.ln1_b = ln ? (float *)(lb + L.lo_ln1_b) : nullptr;
+    D.ln2_g = (float *)(lb + L.lo_ln2_g), D.ln2_b = ln ? (float *)(lb + L.lo_ln2_b) : nullptr;
+    D.wqkv = sh->wqkv[l].ptr, D.bqkv = bias ? (float *)(lb + L.lo_bqkv) : nullptr;
+    D.wo = sh->wo[l].ptr, D.bo = bias ? (float *)(lb + L.lo_bo) : nullptr;
+    D.w1 = sh->w1[l].ptr, D.b1 = (bias && !glu) ? (float *)(lb + L.lo_b1) : nullptr;
+    D.w2 = sh->w2[l].ptr, D.b2 = bias ? (float *)(lb + L.lo_b2) : nullptr;
+    // LayerNorm folds gamma and beta (+ bias); RMSNorm needs neither, a bias alone stays a bias
+    sh->wg_qkv[l] = ln ? (float *)(lb + L.lo_wg_qkv) : nullptr;
+    sh->cb_qkv[l] = ln ? (float *)(lb + L.lo_cb_qkv) : const_cast<float *>(D.bqkv);
+    sh->wg_1[l] = ln ? (float *)(lb + L.lo_wg_1) : nullptr;
+    sh->cb_1[l] = ln ? (float *)(lb + L.lo_cb_1) : const_cast<float *>(D.b1);
+  }
+}
+
 template <typename T>
 static ss_status upload_matrix(Shard *sh, hipStream_t st, const void *host, size_t host_ld, size_t row0, size_t col0,
                                size_t rows, size_t cols, bool rows_are_out, void *dst, int k_blocks, int row_tiles,
@@ -322,23 +358,23 @@ static ss_status upload_all(Shard *sh, const ss_weights *P, hipStream_t st) {
     if (!P->wpe) SS_FAIL(SS_EINVAL, "wpe is NULL for a learned-position model");
     SS_HIP(hipMemcpyAsync(sh->wpe, P->wpe, (size_t)L.max_pos * d * sizeof(T), hipMemcpyHostToDevice, st));
   }
-  sh->lm_head = FragMat{sh->base + L.off_lm, L.V, d, ceil_div(L.V, 16), d / FK};
   SS_TRY(upload_matrix<T>(sh, st, P->lm_head, d, 0, 0, L.V, d, true, sh->lm_head.ptr, d / FK, ceil_div(L.V, 16), 1, 0));
   SS_TRY(upload_vec(st, P->lnf_g, 0, d, sh->lnf_g, true));
   SS_TRY(upload_vec(st, P->lnf_b, 0, d, sh->lnf_b, ln));
+  if (ln)
+    SS_TRY(launch_fold_norm(m.dtype, sh->lm_head.ptr, sh->lm_head.row_tiles, sh->lm_head.k_blocks, sh->lnf_g, sh->lnf_b,
+                            nullptr, sh->wg_lm, sh->cb_lm, st));
   for (int l = 0; l < L.Ls; ++l) {
     const ss_layer_weights &W = P->layers[sh->s.layer_lo - P->slice.layer_lo + l];
     char *lb = sh->base + L.off_layer[l];
-    LayerDev &D = sh->layers[l];
-    float *ln1_g = (float *)(lb + L.lo_ln1_g), *ln1_b = (float *)(lb + L.lo_ln1_b);
-    float *ln2_g = (float *)(lb + L.lo_ln2_g), *ln2_b = (float *)(lb + L.lo_ln2_b);
+    const LayerDev &D = sh->layers[l];
+    // the vectors are uploaded to their slots whether or not the model uses them
     float *bqkv = (float *)(lb + L.lo_bqkv), *bo = (float *)(lb + L.lo_bo), *b1 = (float *)(lb + L.lo_b1),
           *b2 = (float *)(lb + L.lo_b2);
-    SS_TRY(upload_vec(st, W.ln1_g, 0, d, ln1_g, true));
-    SS_TRY(upload_vec(st, W.ln1_b, 0, d, ln1_b, ln));
-    SS_TRY(upload_vec(st, W.ln2_g, 0, d, ln2_g, true));
-    SS_TRY(upload_vec(st, W.ln2_b, 0, d, ln2_b, ln));
-    sh->wqkv[l] = FragMat{lb + L.lo_wqkv, L.qkv_n, d, L.qkv_n / 16, d / FK};
+    SS_TRY(upload_vec(st, W.ln1_g, 0, d, (float *)(lb + L.lo_ln1_g), true));
+    SS_TRY(upload_vec(st, W.ln1_b, 0, d, (float *)(lb + L.lo_ln1_b), ln));
+    SS_TRY(upload_vec(st, W.ln2_g, 0, d, (float *)(lb + L.lo_ln2_g), true));
+    SS_TRY(upload_vec(st, W.ln2_b, 0, d, (float *)(lb + L.lo_ln2_b), ln));
     const void *qkvw[3] = {W.wq, W.wk, W.wv};
     const void *qkvb[3] = {W.bq, W.bk, W.bv};
     for (int p = 0; p < 3; ++p) {
@@ -346,10 +382,8 @@ static ss_status upload_all(Shard *sh, const ss_weights *P, hipStream_t st) {
                               HD / 16, 1, p * (HD / 16)));
       SS_TRY(upload_vec(st, qkvb[p], c0, HD, bqkv + p * HD, bias));
     }
-    sh->wo[l] = FragMat{lb + L.lo_wo, d, HD, d / 16, HD / FK};
     SS_TRY(upload_matrix<T>(sh, st, W.wo, d, c0, 0, HD, d, false, sh->wo[l].ptr, HD / FK, d / 16, 1, 0));
     SS_TRY(upload_vec(st, W.bo, 0, d, bo, bias));
-    sh->w1[l] = FragMat{lb + L.lo_w1, L.w1_rows, d, L.w1_rows / 16, d / FK};
     if (m.act == SS_ACT_SWIGLU) {
       SS_TRY(upload_matrix<T>(sh, st, W.wg, Fp, 0, f0, d, L.Fs, false, sh->w1[l].ptr, d / FK, L.Fs / 16, 2, 0));
       SS_TRY(upload_matrix<T>(sh, st, W.wu, Fp, 0, f0, d, L.Fs, false, sh->w1[l].ptr, d / FK, L.Fs / 16, 2, 1));
@@ -357,14 +391,14 @@ static ss_status upload_all(Shard *sh, const ss_weights *P, hipStream_t st) {
       SS_TRY(upload_matrix<T>(sh, st, W.w1, Fp, 0, f0, d, L.Fs, false, sh->w1[l].ptr, d / FK, L.Fs / 16, 1, 0));
       SS_TRY(upload_vec(st, W.b1, f0, L.Fs, b1, bias));
     }
-    sh->w2[l] = FragMat{lb + L.lo_w2, d, L.Fs, d / 16, L.Fs / FK};
     SS_TRY(upload_matrix<T>(sh, st, W.w2, d, f0, 0, L.Fs, d, false, sh->w2[l].ptr, L.Fs / FK, d / 16, 1, 0));
     SS_TRY(upload_vec(st, W.b2, 0, d, b2, bias));
-    D.ln1_g = ln1_g, D.ln1_b = ln ? ln1_b : nullptr, D.ln2_g = ln2_g, D.ln2_b = ln ? ln2_b : nullptr;
-    D.wqkv = sh->wqkv[l].ptr, D.bqkv = bias ? bqkv : nullptr;
-    D.wo = sh->wo[l].ptr, D.bo = bias ? bo : nullptr;
-    D.w1 = sh->w1[l].ptr, D.b1 = (bias && m.act != SS_ACT_SWIGLU) ? b1 : nullptr;
-    D.w2 = sh->w2[l].ptr, D.b2 = bias ? b2 : nullptr;
+    if (ln) {
+      SS_TRY(launch_fold_norm(m.dtype, sh->wqkv[l].ptr, sh->wqkv[l].row_tiles, sh->wqkv[l].k_blocks, D.ln1_g, D.ln1_b, D.bqkv,
+                              sh->wg_qkv[l], sh->cb_qkv[l], st));
+      SS_TRY(launch_fold_norm(m.dtype, sh->w1[l].ptr, sh->w1[l].row_tiles, sh->w1[l].k_blocks, D.ln2_g, D.ln2_b, D.b1,
+                              sh->wg_1[l], sh->cb_1[l], st));
+    }
   }
   return SS_OK;
 }
@@ -397,17 +431,8 @@ ss_status ss_shard_create(const ss_model_desc *desc, const ss_slice *slice, cons
   }
   hipStream_t st = (hipStream_t)hip_stream;
   sh->base = (char *)device_mem;
-  sh->wte = sh->base + L.off_wte;
-  sh->wpe = L.max_pos ? sh->base + L.off_wpe : nullptr;
-  sh->lnf_g = (float *)(sh->base + L.off_lnf_g);
-  sh->lnf_b = desc->norm == SS_NORM_LAYERNORM ? (float *)(sh->base + L.off_lnf_b) : nullptr;
-  sh->rope = (float2 *)(sh->base + L.off_rope);
-  sh->kv = sh->base + L.off_kv;
-  sh->d_len = (int32_t *)(sh->base + L.off_len);
-  sh->ws = sh->base + L.off_ws;
+  bind_pointers(sh);
   sh->h_len.assign(max_batch, 0);
-  sh->layers.resize(L.Ls);
-  sh->wqkv.resize(L.Ls), sh->wo.resize(L.Ls), sh->w1.resize(L.Ls), sh->w2.resize(L.Ls);
   ss_status rc = desc->dtype == SS_DTYPE_BF16 ? upload_all<bf16_t>(sh, parent, st) : upload_all<float>(sh, parent, st);
   if (rc == SS_OK && desc->pos == SS_POS_ROPE) {
     // angles in double on the host, table in float32
@@ -428,7 +453,6 @@ ss_status ss_shard_create(const ss_model_desc *desc, const ss_slice *slice, cons
     hipLaunchKernelGGL(fill_i32, dim3(1), dim3(32), 0, st, sh->d_len, 32, 0);
     int nc = L.n_counters;
     hipLaunchKernelGGL(fill_i32, dim3(ceil_div(nc, 256)), dim3(256), 0, st, (int32_t *)(sh->ws + L.ws_counters), nc, 0);
-    hipLaunchKernelGGL(fill_i32, dim3(8), dim3(256), 0, st, (int32_t *)(sh->ws + L.ws_bar), 2048, 0);
     hipError_t e = hipStreamSynchronize(st);
     if (e != hipSuccess) {
       set_error("shard creation: %s", hipGetErrorString(e));
@@ -465,7 +489,6 @@ ss_status ss_committed_len(const ss_shard *shard, int32_t *out_host, void *hip_s
   const Shard *sh = (const Shard *)shard;
   SS_HIP(hipMemcpyAsync(out_host, sh->d_len, sh->L.Bmax * 4, hipMemcpyDeviceToHost, (hipStream_t)hip_stream));
   SS_HIP(hipStreamSynchronize((hipStream_t)hip_stream));
-  SS_TRY(persistent_check_abort(sh, (hipStream_t)hip_stream));
   return SS_OK;
 }
 
@@ -481,22 +504,6 @@ ss_status ss_debug_interrupt_after_layer(ss_shard *shard, int32_t layer) {
   Shard *sh = (Shard *)shard;
   if (layer < -1 || layer >= sh->L.Ls) SS_FAIL(SS_EINVAL, "layer %d outside the shard's %d layers", layer, sh->L.Ls);
   sh->interrupt_after = layer;
-  return SS_OK;
-}
-
-ss_status ss_debug_read_trace(const ss_shard *shard, uint64_t *out, int32_t n, void *hip_stream) {
-  if (!shard || !out || n < 1) SS_FAIL(SS_EINVAL, "bad argument");
-  const Shard *sh = (const Shard *)shard;
-  if (n > 5 * sh->L.Ls + 66) n = 5 * sh->L.Ls + 66;
-  SS_HIP(hipMemcpyAsync(out, sh->ws + sh->L.ws_trace, (size_t)n * 8, hipMemcpyDeviceToHost, (hipStream_t)hip_stream));
-  SS_HIP(hipStreamSynchronize((hipStream_t)hip_stream));
-  return SS_OK;
-}
-
-ss_status ss_set_persistent(ss_shard *shard, int32_t enabled) {
-  if (!shard) SS_FAIL(SS_EINVAL, "NULL shard");
-  if (enabled < -1 || enabled > 2) SS_FAIL(SS_EINVAL, "persistent mode %d", enabled);
-  ((Shard *)shard)->persistent_mode = enabled;
   return SS_OK;
 }
 

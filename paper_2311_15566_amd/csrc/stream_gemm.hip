@@ -1,0 +1,387 @@
+// The weight-streaming GEMM of the decode step and the fold of a norm's gamma / beta into
+// per-output vectors (see StreamGemmArgs).
+#include <limits.h>
+#include <math.h>
+#include <stdlib.h>
+
+#include "kernels.h"
+#include "mma.h"
+
+namespace ss {
+
+namespace {
+
+constexpr int U = 2;      // fragments per register batch; two batches in flight
+constexpr int NW = 2;     // weight tiles per block
+
+template <int NB, int KSM>
+struct GemmShared {
+  f32x4 red[KSM][NW][NB][64];    // per K slice: the wave's sums [weight tile][batch tile][lane]
+  float stat[KSM * 128];         // row-sum slices [slice][row][2], slices * rows = threads of the block
+  float lg_v[NW][NB * 16];       // logits: best value / index per weight tile and row
+  int lg_i[NW][NB * 16];
+  float fin_v[KSM * 64];         // [slice][row]
+  int fin_i[KSM * 64];
+  int flag;
+};
+
+}  // namespace
+
+// grid = tile pairs, block = a.ks waves.  Wave s streams k blocks [s * per, (s + 1) * per) of
+// both tiles in register batches of U fragments per tile, two batches in flight.
+// KSM: waves per block at most
+template <typename T, int NB, bool GLU, int EPI, int KSM>
+__global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamGemmArgs a) {
+  constexpr int AP = Elem<T>::kParts;
+  constexpr int RB = NB * 16;
+  constexpr int NEP = GLU ? NB : NW * NB;  // waves that run the epilogue
+  constexpr int NWE = GLU ? 2 : 1;         // weight tiles one epilogue wave combines
+  __shared__ GemmShared<NB, KSM> sh;
+  const int tid = threadIdx.x, lane = tid & 63, ks = tid >> 6, KS = blockDim.x >> 6;
+  const int tile0 = blockIdx.x * NW;
+  const int per = (a.k_blocks + KS - 1) / KS;
+  const int k0 = ks * per, k1 = min(a.k_blocks, k0 + per);
+  const int r = lane & 15, q4 = (lane >> 4) * 4;
+
+  bool tile_ok[NW];
+  const u32x4 *wp[NW];
+#pragma unroll
+  for (int j = 0; j < NW; ++j) {
+    tile_ok[j] = tile0 + j < a.row_tiles;
+    wp[j] = (const u32x4 *)a.w + (size_t)(tile0 + j) * a.k_blocks * 64 + lane;
+  }
+  bool row_ok[NB];
+  const u32x4 *ap[NB];
+#pragma unroll
+  for (int t = 0; t < NB; ++t) {
+    row_ok[t] = t * 16 + r < a.B;
+    ap[t] = (const u32x4 *)a.act + (size_t)t * a.k_blocks * AP * 64 + lane;
+  }
+
+  // what the epilogue needs from memory is requested first, so that it has long arrived
+  const bool is_epi = ks < NEP;
+  const int je = GLU ? 0 : ks % NW, te = GLU ? ks : ks / NW;
+  const int b = te * 16 + r;                                        // this lane's batch row
+  const int wrow = (tile0 + je) * 16 + q4;                          // first of its four weight rows
+  const int n0 = GLU ? blockIdx.x * 16 + q4 : wrow;                 // first of its four outputs
+  const bool tile_e_ok = tile0 + je < a.row_tiles;
+  const bool epi_live = is_epi && tile_e_ok && b < a.B && n0 < a.N;
+  f32x4 e_wg[NWE], e_cb[NWE], e_x = {0.f, 0.f, 0.f, 0.f}, e_g = {1.f, 1.f, 1.f, 1.f};
+#pragma unroll
+  for (int jj = 0; jj < NWE; ++jj) {
+    e_wg[jj] = e_cb[jj] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (epi_live) {
+      if (a.wg) e_wg[jj] = *(const f32x4 *)(a.wg + wrow + jj * 16);
+      if (a.cb) e_cb[jj] = *(const f32x4 *)(a.cb + wrow + jj * 16);
+    }
+  }
+  if (EPI == EPI_RESID && epi_live) {
+    e_x = *(const f32x4 *)(a.x_in + (size_t)b * a.N + n0);
+    if (a.act_out) e_g = *(const f32x4 *)(a.g_out + n0);
+  }
+
+  f32x4 acc[NB][NW];
+#pragma unroll
+  for (int t = 0; t < NB; ++t)
+#pragma unroll
+    for (int j = 0; j < NW; ++j) acc[t][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  auto load = [&](u32x4(&w)[NW][U], u32x4(&av)[NB][AP][U], int kb) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool ok = kb + u < k1;
+#pragma unroll
+      for (int j = 0; j < NW; ++j)
+        w[j][u] = (ok && tile_ok[j]) ? __builtin_nontemporal_load(wp[j] + (size_t)(kb + u) * 64) : u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int t = 0; t < NB; ++t)
+#pragma unroll
+        for (int part = 0; part < AP; ++part)
+          av[t][part][u] = (ok && row_ok[t]) ? ap[t][((size_t)(kb + u) * AP + part) * 64] : u32x4{0u, 0u, 0u, 0u};
+    }
+  };
+  auto use = [&](u32x4(&w)[NW][U], u32x4(&av)[NB][AP][U]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int t = 0; t < NB; ++t)
+#pragma unroll
+        for (int part = 0; part < AP; ++part)
+#pragma unroll
+          for (int j = 0; j < NW; ++j) acc[t][j] = Mma<T>::mma(w[j][u], av[t][part][u], acc[t][j]);
+  };
+
+  u32x4 wA[NW][U], aA[NB][AP][U], wB[NW][U], aB[NB][AP][U];
+  load(wA, aA, k0);
+  load(wB, aB, k0 + U);
+
+  // row sums of the normalised input: thread (slice, row) adds the producer's partials slice,
+  // slice + nsl, ...; the slices are added in order in the epilogue
+  const int rbl = a.B <= 8 ? 8 : (a.B <= 16 ? 16 : 32);  // rows padded to a power of two
+  const int nsl = blockDim.x / rbl;
+  if (a.stat_groups > 0) {
+    const int slice = tid / rbl, row = tid % rbl;
+    float s1 = 0.f, s2 = 0.f;
+    if (row < a.B) {
+      const float2 *sp = (const float2 *)a.stat_in + row;
+#pragma unroll 8
+      for (int g = slice; g < a.stat_groups; g += nsl) {
+        const float2 v = sp[(size_t)g * 32];
+        s1 += v.x, s2 += v.y;
+      }
+    }
+    sh.stat[(slice * rbl + row) * 2] = s1, sh.stat[(slice * rbl + row) * 2 + 1] = s2;
+  }
+
+  for (int kb = k0; kb < k1; kb += 2 * U) {
+    use(wA, aA);
+    load(wA, aA, kb + 2 * U);
+    use(wB, aB);
+    load(wB, aB, kb + 3 * U);
+  }
+
+#pragma unroll
+  for (int t = 0; t < NB; ++t)
+#pragma unroll
+    for (int j = 0; j < NW; ++j) sh.red[ks][j][t][lane] = acc[t][j];
+  __syncthreads();
+
+  float bv = -INFINITY;  // EPI_LOGITS: this lane's best
+  int bi = INT_MAX;
+  if (is_epi) {
+    f32x4 sum[NWE];
+#pragma unroll
+    for (int jj = 0; jj < NWE; ++jj) {
+      const int j = GLU ? jj : je;
+      sum[jj] = sh.red[0][j][te][lane];
+      for (int s = 1; s < KS; ++s) sum[jj] += sh.red[s][j][te][lane];
+    }
+    float mean = 0.f, rstd = 1.f;
+    if (a.stat_groups > 0) {
+      float u1 = 0.f, u2 = 0.f;
+      const int br = b < rbl ? b : 0;  // rows past the batch are masked later
+      for (int s = 0; s < nsl; ++s) u1 += sh.stat[(s * rbl + br) * 2], u2 += sh.stat[(s * rbl + br) * 2 + 1];
+      const float inv = 1.0f / (float)a.norm_dim;
+      const float ms = u2 * inv;
+      if (a.rms) {
+        rstd = rsqrtf(ms + a.eps);
+      } else {
+        mean = u1 * inv;
+        rstd = rsqrtf(fmaxf(ms - mean * mean, 0.f) + a.eps);
+      }
+    }
+    float h[NWE][4];  // the product with normalisation and bias applied
+#pragma unroll
+    for (int jj = 0; jj < NWE; ++jj)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) h[jj][i] = rstd * (sum[jj][i] - mean * e_wg[jj][i]) + e_cb[jj][i];
+
+    if (EPI == EPI_F32) {
+      if (epi_live) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (n0 + i < a.N) a.out_f32[(size_t)b * a.ld_out + n0 + i] = h[0][i];
+      }
+    } else if (EPI == EPI_ACT || EPI == EPI_SWIGLU) {
+      if (epi_live) {
+        float u[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) u[i] = GLU ? silu_f(h[0][i]) * h[NWE - 1][i] : act_apply(a.act_kind, h[0][i]);
+        store4_frag<T, false>(a.act_out, b, n0, a.out_k_blocks, AP, u);
+      }
+    } else if (EPI == EPI_RESID) {
+      float s1 = 0.f, s2 = 0.f;
+      if (epi_live) {
+        float v[4], g[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          v[i] = e_x[i] + h[0][i];
+          s1 += v[i], s2 += v[i] * v[i];
+          g[i] = v[i] * e_g[i];
+        }
+        *(f32x4 *)(a.x_out + (size_t)b * a.N + n0) = f32x4{v[0], v[1], v[2], v[3]};
+        if (a.act_out) store4_frag<T, false>(a.act_out, b, n0, a.out_k_blocks, AP, g);
+      }
+      if (a.act_out) {  // partial row sums of this weight tile's 16 features
+        s1 += __shfl_xor(s1, 16), s2 += __shfl_xor(s2, 16);
+        s1 += __shfl_xor(s1, 32), s2 += __shfl_xor(s2, 32);
+        if (lane < 16 && tile_e_ok && b < a.B)
+          ((float2 *)a.stat_out)[(size_t)(tile0 + je) * 32 + b] = make_float2(s1, s2);
+      }
+    } else {  // EPI_LOGITS
+      if (epi_live) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          if (n0 + i < a.N) {
+            if (a.out_f32) a.out_f32[(size_t)b * a.ld_out + n0 + i] = h[0][i];
+            if (h[0][i] > bv) bv = h[0][i], bi = n0 + i;
+          }
+        }
+      }
+#pragma unroll
+      for (int off = 16; off <= 32; off <<= 1) {
+        const float ov = __shfl_xor(bv, off);
+        const int oi = __shfl_xor(bi, off);
+        if (ov > bv || (ov == bv && oi < bi)) bv = ov, bi = oi;
+      }
+      if (lane < 16) sh.lg_v[je][b] = bv, sh.lg_i[je][b] = bi;
+    }
+  }
+  if (EPI != EPI_LOGITS) return;
+
+  // ---- greedy choice over the vocabulary: per-block best, then the last block to arrive scans ----
+  __syncthreads();
+  if (tid < RB) {
+    bv = sh.lg_v[0][tid], bi = sh.lg_i[0][tid];
+#pragma unroll
+    for (int j = 1; j < NW; ++j) {
+      const float ov = sh.lg_v[j][tid];
+      const int oi = sh.lg_i[j][tid];
+      if (ov > bv || (ov == bv && oi < bi)) bv = ov, bi = oi;
+    }
+    st_dev(&a.am_val[(size_t)blockIdx.x * 32 + tid], bv);
+    st_dev(&a.am_idx[(size_t)blockIdx.x * 32 + tid], bi);
+  }
+  if (!arrive_last(a.counter, (int)gridDim.x, &sh.flag)) return;
+  {
+    // thread (slice, row) scans blocks slice, slice + n, ...; ties go to the lowest index whatever
+    // the order, so the merge does not depend on scheduling
+    const int row = tid % rbl, slice = tid / rbl, nslice = blockDim.x / rbl;
+    bv = -INFINITY, bi = INT_MAX;
+    if (row < a.B) {
+#pragma unroll 8
+      for (int g = slice; g < (int)gridDim.x; g += nslice) {
+        const float ov = ld_dev(&a.am_val[(size_t)g * 32 + row]);
+        const int oi = ld_dev(&a.am_idx[(size_t)g * 32 + row]);
+        if (ov > bv || (ov == bv && oi < bi)) bv = ov, bi = oi;
+      }
+    }
+    sh.fin_v[slice * rbl + row] = bv, sh.fin_i[slice * rbl + row] = bi;
+    __syncthreads();
+    if (tid < a.B) {
+      bv = sh.fin_v[tid], bi = sh.fin_i[tid];
+      for (int q = 1; q < nslice; ++q) {
+        const float ov = sh.fin_v[q * rbl + tid];
+        const int oi = sh.fin_i[q * rbl + tid];
+        if (ov > bv || (ov == bv && oi < bi)) bv = ov, bi = oi;
+      }
+      if (a.next_tokens) a.next_tokens[tid] = bi;
+      // token-level commit: the last action of the step
+      for (int q = 0; q < a.n_lens; ++q) a.lens[q][tid] += a.commit_inc;
+    }
+  }
+}
+
+int stream_gemm_blocks(int epi, const StreamGemmArgs &a) {
+  (void)epi;
+  return ceil_div(a.row_tiles, NW);
+}
+
+ss_status check_stream_gemm(int dtype, int epi, const StreamGemmArgs &a) {
+  if (dtype != SS_DTYPE_BF16 && dtype != SS_DTYPE_F32) SS_FAIL(SS_EINVAL, "decode GEMM: dtype %d", dtype);
+  if (a.B < 1 || a.B > 32) SS_FAIL(SS_EINVAL, "decode GEMM: batch %d", a.B);
+  if (a.row_tiles < 1 || a.k_blocks < 1 || (a.ks != 4 && a.ks != 8) || a.N < 1 || a.N > a.row_tiles * 16)
+    SS_FAIL(SS_EINVAL, "decode GEMM: bad shape (tiles %d, k blocks %d, waves %d, N %d)", a.row_tiles, a.k_blocks, a.ks, a.N);
+  if (!a.w || !a.act) SS_FAIL(SS_EINVAL, "decode GEMM: NULL operand");
+  if (a.stat_groups < 0 || (a.stat_groups > 0 && (!a.stat_in || a.norm_dim < 1 || (!a.rms && !a.wg))))
+    SS_FAIL(SS_EINVAL, "decode GEMM: incomplete normalisation arguments");
+  switch (epi) {
+    case EPI_F32:
+      if (!a.out_f32 || a.ld_out < a.N) SS_FAIL(SS_EINVAL, "decode GEMM: bad float output");
+      break;
+    case EPI_SWIGLU:
+      if (a.row_tiles % 2 || a.N * 2 != a.row_tiles * 16) SS_FAIL(SS_EINVAL, "decode GEMM: gate/up tiles must pair up");
+      // fall through
+    case EPI_ACT:
+      if (!a.act_out || a.N % 16 || a.out_k_blocks * (dtype == SS_DTYPE_BF16 ? 32 : 16) < a.N)
+        SS_FAIL(SS_EINVAL, "decode GEMM: bad activation output");
+      break;
+    case EPI_RESID:
+      if (!a.x_in || !a.x_out || a.N != a.row_tiles * 16 || a.stat_groups != 0 || a.wg)
+        SS_FAIL(SS_EINVAL, "decode GEMM: bad residual arguments");
+      if (a.act_out && (!a.g_out || !a.stat_out || a.out_k_blocks * (dtype == SS_DTYPE_BF16 ? 32 : 16) < a.N))
+        SS_FAIL(SS_EINVAL, "decode GEMM: bad residual operand output");
+      break;
+    case EPI_LOGITS:
+      if (!a.am_val || !a.am_idx || !a.counter || a.n_lens < 0 || a.n_lens > 8 || (a.out_f32 && a.ld_out < a.N))
+        SS_FAIL(SS_EINVAL, "decode GEMM: bad logits arguments");
+      break;
+    default: SS_FAIL(SS_EINVAL, "decode GEMM: unknown epilogue %d", epi);
+  }
+  return SS_OK;
+}
+
+template <typename T, int NB, int KSM>
+static void launch_stream_gemm_t(int epi, const StreamGemmArgs &a, dim3 grid, dim3 block, hipStream_t st) {
+#define SS_LAUNCH(GLU, EPI) hipLaunchKernelGGL((stream_gemm<T, NB, GLU, EPI, KSM>), grid, block, 0, st, a)
+  if (epi == EPI_F32) SS_LAUNCH(false, EPI_F32);
+  else if (epi == EPI_ACT) SS_LAUNCH(false, EPI_ACT);
+  else if (epi == EPI_SWIGLU) SS_LAUNCH(true, EPI_SWIGLU);
+  else if (epi == EPI_RESID) SS_LAUNCH(false, EPI_RESID);
+  else SS_LAUNCH(false, EPI_LOGITS);
+#undef SS_LAUNCH
+}
+
+ss_status launch_stream_gemm(int dtype, int epi, const StreamGemmArgs &a, hipStream_t st) {
+  SS_TRY(check_stream_gemm(dtype, epi, a));
+  const dim3 grid(stream_gemm_blocks(epi, a)), block(a.ks * 64);
+  const int nb = a.B <= 16 ? 1 : 2;
+  if (dtype == SS_DTYPE_BF16) {
+    if (nb == 1) launch_stream_gemm_t<bf16_t, 1, 8>(epi, a, grid, block, st);
+    else launch_stream_gemm_t<bf16_t, 2, 8>(epi, a, grid, block, st);
+  } else {
+    if (nb == 1) launch_stream_gemm_t<float, 1, 8>(epi, a, grid, block, st);
+    else launch_stream_gemm_t<float, 2, 8>(epi, a, grid, block, st);
+  }
+  SS_HIP(hipGetLastError());
+  return SS_OK;
+}
+
+// ---------------------------------------------------------------------------
+// wg[row] = sum_k W[row, k] gamma[k],  cb[row] = sum_k W[row, k] beta[k] + bias[row]
+// one wave per weight tile, sums in double
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) fold_norm(const u32x4 *__restrict__ w, int row_tiles, int k_blocks,
+                                                 const float *__restrict__ gamma, const float *__restrict__ beta,
+                                                 const float *__restrict__ bias, float *__restrict__ wg,
+                                                 float *__restrict__ cb) {
+  constexpr int PL = Elem<T>::kPerLane, FK = Elem<T>::kFragK;
+  const int lane = threadIdx.x & 63, tile = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (tile >= row_tiles) return;
+  const int r = lane & 15, kq = lane >> 4;
+  double sg = 0.0, sb = 0.0;
+  for (int kb = 0; kb < k_blocks; ++kb) {
+    const u32x4 raw = w[((size_t)tile * k_blocks + kb) * 64 + lane];
+    T e[PL];
+    __builtin_memcpy(e, &raw, 16);
+#pragma unroll
+    for (int i = 0; i < PL; ++i) {
+      const int k = kb * FK + kq * PL + i;
+      const double wv = (double)Elem<T>::to_f32(e[i]);
+      if (gamma) sg += wv * (double)gamma[k];
+      if (beta) sb += wv * (double)beta[k];
+    }
+  }
+  sg += __shfl_xor(sg, 16), sb += __shfl_xor(sb, 16);
+  sg += __shfl_xor(sg, 32), sb += __shfl_xor(sb, 32);
+  if (lane < 16) {
+    const int row = tile * 16 + r;
+    if (gamma && wg) wg[row] = (float)sg;
+    if (cb) cb[row] = (float)(sb + (bias ? (double)bias[row] : 0.0));
+  }
+}
+
+ss_status launch_fold_norm(int dtype, const void *w, int row_tiles, int k_blocks, const float *gamma, const float *beta,
+                           const float *bias, float *wg, float *cb, hipStream_t st) {
+  if (!w || row_tiles < 1 || k_blocks < 1) SS_FAIL(SS_EINVAL, "fold: bad arguments");
+  const dim3 grid(ceil_div(row_tiles, 4)), block(256);
+  if (dtype == SS_DTYPE_BF16)
+    hipLaunchKernelGGL(fold_norm<bf16_t>, grid, block, 0, st, (const u32x4 *)w, row_tiles, k_blocks, gamma, beta, bias, wg, cb);
+  else
+    hipLaunchKernelGGL(fold_norm<float>, grid, block, 0, st, (const u32x4 *)w, row_tiles, k_blocks, gamma, beta, bias, wg, cb);
+  SS_HIP(hipGetLastError());
+  return SS_OK;
+}
+
+}  // namespace ss
