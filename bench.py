@@ -170,7 +170,8 @@ def main():
                                frac=whole / HBM_PEAK_GBPS)
 
         if not args.no_extras:
-            # ---- kernel classes: the same K steps again, kernel by kernel with HIP events ----
+            # ---- kernel classes: the same K steps again, kernel by kernel, each launch's own begin/end
+            # recorded on a pair of HIP events of the stream it runs on ----
             fresh()
             torch.cuda.synchronize()
             sh.kernel_timing(True)
@@ -194,7 +195,7 @@ def main():
             dom = "resid_gemm"                                   # out-projection + second FFN matrix: most bytes per step
             ms, cnt = tm[dom]
             ach = class_bytes[dom] * K / (ms * 1e-3) / 1e9
-            out["roofline"] = dict(bound="hbm", kernel="skinny_gemm<PRO_ACT,EPI_RESID> (out-projection and FFN-down)",
+            out["roofline"] = dict(bound="hbm", kernel="stream_gemm<EPI_RESID> (out-projection and second FFN matrix, residual epilogue)",
                                    achieved=ach, peak=HBM_PEAK_GBPS, unit="GB/s", frac=ach / HBM_PEAK_GBPS, traffic=None,
                                    bytes_per_launch=class_bytes[dom] * K / cnt, avg_launch_us=ms / cnt * 1e3,
                                    launches=int(cnt))

@@ -174,11 +174,12 @@ ss_status ss_debug_interrupt_after_layer(ss_shard *shard, int32_t layer);
 ss_status ss_set_graph_launch(ss_shard *shard, int32_t enabled);
 
 /* Measurement aid: per-kernel-class timing of decode steps.  While enabled on group[0],
- * ss_decode_step launches kernel by kernel (no graph replay) and brackets every launch with a
- * pair of HIP events on the step's stream.  ss_kernel_timing_read synchronizes the stream,
- * returns the milliseconds and launch counts accumulated per class since the last read
- * (host arrays of 8) and clears them.  Classes: 0 embedding, 1 QKV GEMM, 2 decode attention,
- * 3 out-projection and second-FFN GEMM (the residual epilogue), 4 first-FFN GEMM, 5 LM head. */
+ * ss_decode_step launches kernel by kernel (no graph replay) and every launch records its own
+ * begin and end on a pair of HIP events of the step's stream (the dispatch's timestamps).
+ * ss_kernel_timing_read synchronizes the stream, returns the milliseconds and launch counts
+ * accumulated per class since the last read (host arrays of 8) and clears them.  Classes:
+ * 0 embedding, 1 QKV GEMM, 2 decode attention, 3 out-projection and second-FFN GEMM (the
+ * residual epilogue), 4 first-FFN GEMM, 5 LM head. */
 ss_status ss_kernel_timing(ss_shard *shard, int32_t enabled);
 ss_status ss_kernel_timing_read(ss_shard *shard, double ms[8], int64_t count[8], void *hip_stream);
 

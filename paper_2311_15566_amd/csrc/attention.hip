@@ -26,8 +26,8 @@ ss_status launch_decode_attn(int dtype, const DecodeAttnArgs &a, hipStream_t st)
   dim3 grid(a.B * a.Hs, a.splits);
 #define SS_LAUNCH(KT, AT, DH)                                                                        \
   do {                                                                                               \
-    if (a.waves == 16) hipLaunchKernelGGL((decode_attn<KT, AT, DH, 16>), grid, dim3(1024), 0, st, a); \
-    else hipLaunchKernelGGL((decode_attn<KT, AT, DH, 4>), grid, dim3(256), 0, st, a);                \
+    if (a.waves == 16) SS_LAUNCH_KERNEL((decode_attn<KT, AT, DH, 16>), grid, dim3(1024), 0, st, a); \
+    else SS_LAUNCH_KERNEL((decode_attn<KT, AT, DH, 4>), grid, dim3(256), 0, st, a);                \
   } while (0)
   if (dtype == SS_DTYPE_BF16 && a.kv_dtype == SS_DTYPE_F16) {
     if (a.Dh == 128) SS_LAUNCH(f16_t, bf16_t, 128);

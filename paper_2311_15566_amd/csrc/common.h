@@ -1,6 +1,7 @@
 // Shared declarations of the spotshard HIP library (gfx950 only).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <stdio.h>
 #include <string>
@@ -29,6 +30,24 @@ void set_error(const char *fmt, ...);
   do {                                \
     ss_status s_ = (call);            \
     if (s_ != SS_OK) return s_;       \
+  } while (0)
+
+// ---------------------------------------------------------------------------
+// Launch of a decode-step kernel.  In measurement mode the caller leaves a pair of events here
+// and the launch records the kernel's own begin and end on them (the dispatch's timestamps, as
+// a profiler sees them, with no marker packets between kernels).
+// ---------------------------------------------------------------------------
+struct LaunchTiming {
+  hipEvent_t start = nullptr, stop = nullptr;
+};
+extern thread_local LaunchTiming g_launch_timing;
+#define SS_LAUNCH_KERNEL(kern, grid, block, lds, st, ...)                                                           \
+  do {                                                                                                              \
+    if (::ss::g_launch_timing.start)                                                                                \
+      hipExtLaunchKernelGGL(kern, grid, block, lds, st, ::ss::g_launch_timing.start, ::ss::g_launch_timing.stop, 0, \
+                            __VA_ARGS__);                                                                           \
+    else                                                                                                            \
+      hipLaunchKernelGGL(kern, grid, block, lds, st, __VA_ARGS__);                                                  \
   } while (0)
 
 // ---------------------------------------------------------------------------

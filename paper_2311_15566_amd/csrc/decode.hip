@@ -231,11 +231,12 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
 }
 
 // ---------------------------------------------------------------------------
-// optional event bracket around one launch (measurement aid)
+// measurement aid: the next launch records its begin and end on a pair of the shard's events
 // ---------------------------------------------------------------------------
+thread_local LaunchTiming g_launch_timing;
+
 struct Bracket {
   Shard *sh;
-  hipStream_t st;
   hipEvent_t e0 = nullptr, e1 = nullptr;
   int cls;
   static hipEvent_t get(Shard *sh) {
@@ -248,14 +249,14 @@ struct Bracket {
     if (hipEventCreate(&e) != hipSuccess) return nullptr;
     return e;
   }
-  Bracket(Shard *s, int c, hipStream_t stream) : sh(s), st(stream), cls(c) {
+  Bracket(Shard *s, int c) : sh(s), cls(c) {
     if (!sh->timing) return;
     e0 = get(sh), e1 = get(sh);
-    if (e0) (void)hipEventRecord(e0, st);
+    if (e0 && e1) g_launch_timing.start = e0, g_launch_timing.stop = e1;
   }
   ~Bracket() {
+    g_launch_timing = LaunchTiming();
     if (!sh->timing || !e0 || !e1) return;
-    (void)hipEventRecord(e1, st);
     sh->timed.push_back({cls, e0, e1});
   }
 };
@@ -263,11 +264,11 @@ struct Bracket {
 // one phase as a kernel of its own
 static ss_status launch_phase(Shard *g0, const Phase &ph, hipStream_t st) {
   const int dt = g0->m.dtype;
-  Bracket br(g0, ph.kind, st);
+  Bracket br(g0, ph.kind);
   switch (ph.kind) {
     case PH_EMBED:
-      if (dt == SS_DTYPE_BF16) hipLaunchKernelGGL(embed_rows<bf16_t>, dim3(ph.gx), dim3(256), 0, st, ph.e);
-      else hipLaunchKernelGGL(embed_rows<float>, dim3(ph.gx), dim3(256), 0, st, ph.e);
+      if (dt == SS_DTYPE_BF16) SS_LAUNCH_KERNEL(embed_rows<bf16_t>, dim3(ph.gx), dim3(256), 0, st, ph.e);
+      else SS_LAUNCH_KERNEL(embed_rows<float>, dim3(ph.gx), dim3(256), 0, st, ph.e);
       SS_HIP(hipGetLastError());
       return SS_OK;
     case PH_QKV: return launch_stream_gemm(dt, EPI_F32, ph.g, st);

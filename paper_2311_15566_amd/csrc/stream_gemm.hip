@@ -313,7 +313,7 @@ ss_status check_stream_gemm(int dtype, int epi, const StreamGemmArgs &a) {
 
 template <typename T, int NB, int KSM>
 static void launch_stream_gemm_t(int epi, const StreamGemmArgs &a, dim3 grid, dim3 block, hipStream_t st) {
-#define SS_LAUNCH(GLU, EPI) hipLaunchKernelGGL((stream_gemm<T, NB, GLU, EPI, KSM>), grid, block, 0, st, a)
+#define SS_LAUNCH(GLU, EPI) SS_LAUNCH_KERNEL((stream_gemm<T, NB, GLU, EPI, KSM>), grid, block, 0, st, a)
   if (epi == EPI_F32) SS_LAUNCH(false, EPI_F32);
   else if (epi == EPI_ACT) SS_LAUNCH(false, EPI_ACT);
   else if (epi == EPI_SWIGLU) SS_LAUNCH(true, EPI_SWIGLU);
