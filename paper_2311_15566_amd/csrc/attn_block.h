@@ -69,7 +69,7 @@ template <typename T, typename AT, int DH, int NWV>
 __device__ __forceinline__ void decode_attn_block(const DecodeAttnArgs &a, const int bh, const int sp,
                                                   AttnShared<NWV> &sh) {
   typedef RowGeom<T, DH> Gm;
-  constexpr int EPL = Gm::EPL, LPR = Gm::LPR, G = Gm::G, U = 4;
+  constexpr int EPL = Gm::EPL, LPR = Gm::LPR, G = Gm::G, U = NWV == 16 ? 2 : 4;
   auto &sq = sh.sq;
   auto &sm_m = sh.sm_m;
   auto &sm_l = sh.sm_l;
@@ -85,35 +85,31 @@ __device__ __forceinline__ void decode_attn_block(const DecodeAttnArgs &a, const
   const float scale = rsqrtf((float)DH);
   const float2 *tab = a.rope ? a.rope + (size_t)n * (DH / 2) : nullptr;
   const float *qraw = a.qkv + (size_t)b * 3 * HD + h * DH;
-  __syncthreads();  // the previous user of the shared scratch is done
-  if (tid < DH) sq[tid] = rope_elem(qraw, tid, DH / 2, tab);
-  __syncthreads();
-
   const int c = lane % LPR, g = lane / LPR;
-  float qf[EPL];
-#pragma unroll
-  for (int e = 0; e < EPL; ++e) qf[e] = sq[c * EPL + e];
-
   const int r0 = sp * a.rows_per_block;
   const int r1 = min(r0 + a.rows_per_block, n);
   const char *kbase = a.k_cache + b * a.row_stride + h * a.head_stride;
   const char *vbase = a.v_cache + b * a.row_stride + h * a.head_stride;
   constexpr int ROWB = DH * (int)sizeof(T);
 
+  float qf[EPL];
+  float new_k = 0.f, new_v = 0.f;
   float m = -1e30f, l = 0.f, acc[EPL];
 #pragma unroll
   for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
 
-  for (int base = r0 + wave * (U * G); base < r1; base += NWV * U * G) {
-    u32x4 kr[U], vr[U];
-    int row[U];
+  // register batches of U row groups (K and V), two batches in flight
+  auto load = [&](u32x4(&kr)[U], u32x4(&vr)[U], const int base) {
+    if (base >= r1) return;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      row[u] = base + u * G + g;
-      const int rr = min(row[u], r1 - 1);  // clamp: masked below, stays inside committed rows
+      const int rr = min(base + u * G + g, r1 - 1);  // clamp: masked in consume, stays inside committed rows
       kr[u] = __builtin_nontemporal_load((const u32x4 *)(kbase + (size_t)rr * ROWB) + c);
       vr[u] = __builtin_nontemporal_load((const u32x4 *)(vbase + (size_t)rr * ROWB) + c);
     }
+  };
+  auto consume = [&](u32x4(&kr)[U], u32x4(&vr)[U], const int base) {
+    if (base >= r1) return;
     float s[U];
     float mb = -1e30f;
 #pragma unroll
@@ -125,7 +121,7 @@ __device__ __forceinline__ void decode_attn_block(const DecodeAttnArgs &a, const
       for (int e = 0; e < EPL; ++e) d += qf[e] * kf[e];
 #pragma unroll
       for (int off = 1; off < LPR; off <<= 1) d += __shfl_xor(d, off);
-      s[u] = row[u] < r1 ? d * scale : -INFINITY;
+      s[u] = base + u * G + g < r1 ? d * scale : -INFINITY;
       mb = fmaxf(mb, s[u]);
     }
     const float mn = fmaxf(m, mb);
@@ -143,6 +139,30 @@ __device__ __forceinline__ void decode_attn_block(const DecodeAttnArgs &a, const
       for (int e = 0; e < EPL; ++e) acc[e] += p * vf[e];
     }
     m = mn;
+  };
+  {
+    constexpr int STRIDE = NWV * U * G;
+    u32x4 kA[U], vA[U], kB[U], vB[U];
+    int base = r0 + wave * (U * G);
+    // cache rows do not depend on this step's q: request them first, then stage q
+    load(kA, vA, base);
+    load(kB, vB, base + STRIDE);
+    float kn = 0.f, vraw = 0.f;  // the new token's (rotated) key and value element of thread e
+    if (tid < DH) {
+      kn = rope_elem(qraw + HD, tid, DH / 2, tab);
+      vraw = qraw[2 * HD + tid];
+      sq[tid] = rope_elem(qraw, tid, DH / 2, tab);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) qf[e] = sq[c * EPL + e];
+    for (; base < r1; base += 2 * STRIDE) {
+      consume(kA, vA, base);
+      load(kA, vA, base + 2 * STRIDE);
+      consume(kB, vB, base + STRIDE);
+      load(kB, vB, base + 3 * STRIDE);
+    }
+    new_k = kn, new_v = vraw;
   }
   // merge the G lane groups of the wave
 #pragma unroll
@@ -195,9 +215,8 @@ __device__ __forceinline__ void decode_attn_block(const DecodeAttnArgs &a, const
   // the new token: append as row n (not committed until the step's last kernel), attend to itself
   float vnew = 0.f, prod = 0.f;
   if (tid < DH) {
-    const float kn = rope_elem(qraw + HD, tid, DH / 2, tab);
-    const T kt = Elem<T>::from_f32(kn);
-    const T vt = Elem<T>::from_f32(qraw[2 * HD + tid]);
+    const T kt = Elem<T>::from_f32(new_k);
+    const T vt = Elem<T>::from_f32(new_v);
     ((T *)(a.k_cache + b * a.row_stride + h * a.head_stride + (size_t)n * ROWB))[tid] = kt;
     ((T *)(a.v_cache + b * a.row_stride + h * a.head_stride + (size_t)n * ROWB))[tid] = vt;
     vnew = Elem<T>::to_f32(vt);

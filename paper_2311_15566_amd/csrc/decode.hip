@@ -86,9 +86,11 @@ static ss_status check_group(Shard *const *group, int n_group, int B) {
 
 static void attn_plan(const Layout &L, int B, int *rows_per_block, int *splits, int *waves) {
   const int pairs = std::max(1, B * L.Hs);
-  if (pairs >= 64) {
-    // enough (row, head) pairs to occupy the chip: one block of 16 waves per pair, merged in
-    // LDS, nothing of the softmax goes through memory
+  // one 16-wave block per compute unit at a time: whole pairs pay off from 64 pairs on, unless the
+  // last round of blocks would leave most of the 256 compute units idle
+  const int rounds = ceil_div(pairs, 256);
+  if (pairs >= 64 && (rounds == 1 || pairs * 4 >= rounds * 256 * 3)) {
+    // one block of 16 waves per pair, merged in LDS: nothing of the softmax goes through memory
     *rows_per_block = (int)align_up((size_t)L.Smax, 64), *splits = 1, *waves = 16;
     return;
   }
