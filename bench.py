@@ -89,6 +89,20 @@ def cpu_baseline(w, W, n_ctx, steps=32):
                        f"float32 numpy oracle, {dt:.1f} s timed (+{setup:.0f} s set-up)")
 
 
+def measured_traffic(workload_name, kernel_key):
+    """HBM bytes per launch of a kernel from the committed rocprofv3 --pmc summary (FETCH_SIZE and
+    WRITE_SIZE, each scaled by what the counter reads for a plain copy of known size), or None."""
+    path = os.path.join(ROOT, "profiles", f"decode_step_{workload_name}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) >= 3 and f[0] == "traffic_bytes_per_launch" and f[1] == kernel_key:
+                return float(f[2])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -98,6 +112,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the kernel-class, prefill and repack legs")
     ap.add_argument("--eager", action="store_true", help="launch kernel by kernel instead of replaying a graph")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only copy 1 GiB device to device three times (a kernel of known traffic, for scaling "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs one tensor-parallel shard on ONE GPU; collectives and sharding "
@@ -109,6 +126,15 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs an MI355X"
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps(dict(copy_bytes=1 << 30, copies=3)), flush=True)
+        return
     w = workload(args.workload)
     K, Wm = args.steps, args.warmup
     if K > w.s_max - w.s_in:
@@ -196,7 +222,8 @@ def main():
             ms, cnt = tm[dom]
             ach = class_bytes[dom] * K / (ms * 1e-3) / 1e9
             out["roofline"] = dict(bound="hbm", kernel="stream_gemm<EPI_RESID> (out-projection and second FFN matrix, residual epilogue)",
-                                   achieved=ach, peak=HBM_PEAK_GBPS, unit="GB/s", frac=ach / HBM_PEAK_GBPS, traffic=None,
+                                   achieved=ach, peak=HBM_PEAK_GBPS, unit="GB/s", frac=ach / HBM_PEAK_GBPS,
+                                   traffic=measured_traffic(w.name, "stream_gemm_resid"),
                                    bytes_per_launch=class_bytes[dom] * K / cnt, avg_launch_us=ms / cnt * 1e3,
                                    launches=int(cnt))
             fl = prefill_flops(w)

@@ -45,12 +45,18 @@ __global__ void __launch_bounds__(256) gather_last(const float *x, int S, float 
   const int b = blockIdx.x;
   const float *src = x + ((size_t)b * S + S - 1) * d;
   float *dst = xd + (size_t)b * d;
+  constexpr int PL = Elem<T>::kPerLane;
   float s1 = 0.f, s2 = 0.f;
-  for (int k = threadIdx.x; k < d; k += 256) {
-    const float v = src[k];
-    dst[k] = v;
-    s1 += v, s2 += v * v;
-    store_act<T>(act_out, b, k, d / Elem<T>::kFragK, Elem<T>::kParts, v * gamma[k]);
+  for (int k = threadIdx.x * PL; k < d; k += 256 * PL) {
+    float y[PL];
+#pragma unroll
+    for (int e = 0; e < PL; ++e) {
+      const float v = src[k + e];
+      dst[k + e] = v;
+      s1 += v, s2 += v * v;
+      y[e] = v * gamma[k + e];
+    }
+    store_piece<T>(act_out, b, k, d / Elem<T>::kFragK, y);
   }
   s1 = block_sum(s1, scratch);
   s2 = block_sum(s2, scratch);

@@ -45,6 +45,25 @@ __device__ __forceinline__ void widen16<bf16_t>(const u32x4 &raw, float *out) {
   }
 }
 
+// PL consecutive activations (k a multiple of PL) of row `row` as one 16-byte piece per part
+template <typename T>
+__device__ __forceinline__ void store_piece(void *base, int row, int k, int k_blocks, const float *y) {
+  constexpr int PL = Elem<T>::kPerLane, AP = Elem<T>::kParts;
+  T hi[PL], lo[PL];
+#pragma unroll
+  for (int e = 0; e < PL; ++e) {
+    hi[e] = Elem<T>::from_f32(y[e]);
+    lo[e] = Elem<T>::from_f32(y[e] - Elem<T>::to_f32(hi[e]));
+  }
+  u32x4 w;
+  __builtin_memcpy(&w, hi, 16);
+  *(u32x4 *)((T *)base + frag_offset_parts<T>(row, k, k_blocks, AP, 0)) = w;
+  if (AP > 1) {
+    __builtin_memcpy(&w, lo, 16);
+    *(u32x4 *)((T *)base + frag_offset_parts<T>(row, k, k_blocks, AP, AP - 1)) = w;
+  }
+}
+
 // x[r] = wte[token] (+ wpe[position]) with 16-byte loads, the row held in registers.  With
 // a.act_out set (decode step) also the first GEMM's operand x * gamma and the row's (sum, sum of
 // squares).  d <= 16384.
@@ -76,10 +95,11 @@ __device__ __forceinline__ void embed_row_block(const EmbedArgs &a, const int r,
         s1 += vals[e], s2 += vals[e] * vals[e];
         xo[e] = vals[e];
       }
-      if (a.act_out) {
+      if (a.act_out) {  // the PL elements are one lane's 16-byte piece of the operand fragment(s)
+        float y[PL];
 #pragma unroll
-        for (int e = 0; e < PL; ++e)
-          store_act<T>(a.act_out, r, v * PL + e, a.d / FK, Elem<T>::kParts, vals[e] * a.gamma[v * PL + e]);
+        for (int e = 0; e < PL; ++e) y[e] = vals[e] * a.gamma[v * PL + e];
+        store_piece<T>(a.act_out, r, v * PL, a.d / FK, y);
       }
     }
   }
