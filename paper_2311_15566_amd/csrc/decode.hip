@@ -60,7 +60,7 @@ __global__ void __launch_bounds__(256) gather_last(const float *x, int S, float 
   }
   s1 = block_sum(s1, scratch);
   s2 = block_sum(s2, scratch);
-  if (threadIdx.x == 0) stat_out[b * 2] = s1, stat_out[b * 2 + 1] = s2;
+  if (threadIdx.x == 0) ((f32x4 *)stat_out)[b] = f32x4{s1, s2, 0.f, 0.f};
 }
 
 // ---------------------------------------------------------------------------
@@ -214,7 +214,7 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
       ph.gx = B * L.Hs, ph.gy = a.splits;
       plan->push_back(ph);
     }
-    stat_groups = d / 16;  // from here on the partial sums come from the residual GEMMs' weight tiles
+    stat_groups = d / 32;  // from here on the partial sums come from the residual GEMMs' weight tile pairs
     for (int i = 0; i < n_group; ++i)  // output projection, sum over the group, residual
       resid(i, group[i]->wo[l], group[i]->ws + group[i]->L.ws_od, D0.bo, D0.ln2_g);
     for (int i = 0; i < n_group; ++i) {  // first FFN matrix + activation

@@ -27,7 +27,7 @@ struct StreamGemmArgs {
   int N;                // logical output features (for masking)
   const void *act;      // operand fragments [B tiles][k_blocks][parts]
   // deferred normalisation (stat_groups > 0)
-  const float *stat_in; // [stat_groups][32][2] partial (sum, sum of squares) of the rows of x
+  const float *stat_in; // [stat_groups][32][4]: two partial (sum, sum of squares) pairs of the rows of x per entry
   int stat_groups;
   int norm_dim;         // length of a row of x
   int rms;
@@ -42,7 +42,7 @@ struct StreamGemmArgs {
   void *act_out;        // EPI_ACT / EPI_SWIGLU: activation fragments; EPI_RESID: x_out * g_out (or NULL)
   int out_k_blocks;
   const float *g_out;   // EPI_RESID: gamma of the norm that follows
-  float *stat_out;      // EPI_RESID: [row_tiles][32][2] partial sums of x_out (with act_out)
+  float *stat_out;      // EPI_RESID: [row_tiles / 2][32][4] partial sums of x_out, one pair per weight tile (with act_out)
   int act_kind;
   float *am_val;        // EPI_LOGITS: [blocks][32]
   int *am_idx;
@@ -110,7 +110,7 @@ struct EmbedArgs {
   // decode step only (NULL in the initial phase): operand of the first GEMM and its row sums
   const float *gamma;     // gamma of the first norm
   void *act_out;          // x * gamma as operand fragments [rows / 16][d / FragK][parts]
-  float *stat_out;        // [32][2] (sum x, sum x^2) per row
+  float *stat_out;        // [32][4] (sum x, sum x^2, 0, 0) per row
 };
 
 struct Phase {

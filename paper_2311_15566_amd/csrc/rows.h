@@ -106,7 +106,7 @@ __device__ __forceinline__ void embed_row_block(const EmbedArgs &a, const int r,
   if (a.stat_out) {
     s1 = block_sum(s1, scratch);
     s2 = block_sum(s2, scratch);
-    if (threadIdx.x == 0) a.stat_out[r * 2] = s1, a.stat_out[r * 2 + 1] = s2;
+    if (threadIdx.x == 0) ((f32x4 *)a.stat_out)[r] = f32x4{s1, s2, 0.f, 0.f};
   }
 }
 

@@ -133,7 +133,7 @@ bool compute_layout(const ss_model_desc &m, const ss_slice &s, int max_batch, in
     const int fk = esz == 2 ? 32 : 16, parts = esz == 2 ? 2 : 1;
     L->ws_xd = wtake((size_t)32 * d * 4);
     L->ws_ad = wtake((size_t)2 * (d / fk) * parts * 1024);
-    L->ws_statd = wtake((size_t)(d / 16) * 32 * 2 * 4);
+    L->ws_statd = wtake((size_t)(d / 32) * 32 * 4 * 4);
     L->ws_qkvd = wtake((size_t)32 * L->qkv_n * 4);
     L->ws_od = wtake((size_t)2 * (HD / fk) * parts * 1024);
     L->ws_ud = wtake((size_t)2 * (L->Fs / fk) * parts * 1024);

@@ -115,22 +115,24 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
   load(wA, aA, k0);
   load(wB, aB, k0 + U);
 
-  // row sums of the normalised input: thread (slice, row) adds the producer's partials slice,
-  // slice + nsl, ...; the slices are added in order in the epilogue
+  // Row sums of the normalised input.  The producer left one (sum, sum of squares) pair per 16-row
+  // weight tile and row, two tiles to a float4.  Thread (slice, row) adds float4s slice,
+  // slice + nsl, ...; the slices are added in order in the epilogue.  The first SR of them are
+  // requested here, behind the first weight batches, and added after the main loop, when they
+  // have long arrived: nothing waits for them now.
+  constexpr bool NORMED = EPI != EPI_RESID;
+  constexpr int SR = NORMED ? (GLU ? 2 : 4) : 0;
   const int rbl = a.B <= 8 ? 8 : (a.B <= 16 ? 16 : 32);  // rows padded to a power of two
   const int nsl = blockDim.x / rbl;
-  if (a.stat_groups > 0) {
-    const int slice = tid / rbl, row = tid % rbl;
-    float s1 = 0.f, s2 = 0.f;
-    if (row < a.B) {
-      const float2 *sp = (const float2 *)a.stat_in + row;
-#pragma unroll 8
-      for (int g = slice; g < a.stat_groups; g += nsl) {
-        const float2 v = sp[(size_t)g * 32];
-        s1 += v.x, s2 += v.y;
-      }
+  const int st_slice = tid / rbl, st_row = tid % rbl;
+  const f32x4 *st_p = (const f32x4 *)a.stat_in + st_row;
+  f32x4 st_v[SR > 0 ? SR : 1];
+  if (NORMED) {
+#pragma unroll
+    for (int i = 0; i < SR; ++i) {
+      const int g = st_slice + i * nsl;
+      st_v[i] = (st_row < a.B && g < a.stat_groups) ? st_p[(size_t)g * 32] : f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    sh.stat[(slice * rbl + row) * 2] = s1, sh.stat[(slice * rbl + row) * 2 + 1] = s2;
   }
 
   for (int kb = k0; kb < k1; kb += 2 * U) {
@@ -140,6 +142,14 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
     load(wB, aB, kb + 3 * U);
   }
 
+  if (NORMED && a.stat_groups > 0) {
+    f32x4 sv = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < SR; ++i) sv += st_v[i];
+    if (st_row < a.B)
+      for (int g = st_slice + SR * nsl; g < a.stat_groups; g += nsl) sv += st_p[(size_t)g * 32];  // the rest, if any
+    sh.stat[(st_slice * rbl + st_row) * 2] = sv[0] + sv[2], sh.stat[(st_slice * rbl + st_row) * 2 + 1] = sv[1] + sv[3];
+  }
 #pragma unroll
   for (int t = 0; t < NB; ++t)
 #pragma unroll
@@ -157,7 +167,7 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
       for (int s = 1; s < KS; ++s) sum[jj] += sh.red[s][j][te][lane];
     }
     float mean = 0.f, rstd = 1.f;
-    if (a.stat_groups > 0) {
+    if (NORMED && a.stat_groups > 0) {
       float u1 = 0.f, u2 = 0.f;
       const int br = b < rbl ? b : 0;  // rows past the batch are masked later
       for (int s = 0; s < nsl; ++s) u1 += sh.stat[(s * rbl + br) * 2], u2 += sh.stat[(s * rbl + br) * 2 + 1];
@@ -205,8 +215,8 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
       if (a.act_out) {  // partial row sums of this weight tile's 16 features
         s1 += __shfl_xor(s1, 16), s2 += __shfl_xor(s2, 16);
         s1 += __shfl_xor(s1, 32), s2 += __shfl_xor(s2, 32);
-        if (lane < 16 && tile_e_ok && b < a.B)
-          ((float2 *)a.stat_out)[(size_t)(tile0 + je) * 32 + b] = make_float2(s1, s2);
+        if (lane < 16 && tile_e_ok && b < a.B)  // tile pair blockIdx.x, half je of its float4
+          ((float2 *)a.stat_out)[((size_t)blockIdx.x * 32 + b) * 2 + je] = make_float2(s1, s2);
       }
     } else {  // EPI_LOGITS
       if (epi_live) {
@@ -283,6 +293,7 @@ ss_status check_stream_gemm(int dtype, int epi, const StreamGemmArgs &a) {
   if (a.row_tiles < 1 || a.k_blocks < 1 || (a.ks != 4 && a.ks != 8) || a.N < 1 || a.N > a.row_tiles * 16)
     SS_FAIL(SS_EINVAL, "decode GEMM: bad shape (tiles %d, k blocks %d, waves %d, N %d)", a.row_tiles, a.k_blocks, a.ks, a.N);
   if (!a.w || !a.act) SS_FAIL(SS_EINVAL, "decode GEMM: NULL operand");
+  if (epi == EPI_RESID && a.row_tiles % 2) SS_FAIL(SS_EINVAL, "decode GEMM: residual output needs whole tile pairs");
   if (a.stat_groups < 0 || (a.stat_groups > 0 && (!a.stat_in || a.norm_dim < 1 || (!a.rms && !a.wg))))
     SS_FAIL(SS_EINVAL, "decode GEMM: incomplete normalisation arguments");
   switch (epi) {

@@ -79,7 +79,7 @@ def check(w):
             assert p.gx == w.batch and e.d == d
             rng("x", e.x, p.gx * e.d * 4, regions)
             rng("act_out", e.act_out, nbt * (d // fk) * parts * 1024, regions)
-            rng("stat_out", e.stat_out, 32 * 8, regions)
+            rng("stat_out", e.stat_out, 32 * 16, regions)
             rng("gamma", e.gamma, d * 4, regions)
             stat_groups = 1
         elif p.kind == ATTN:
@@ -103,7 +103,7 @@ def check(w):
             if g.cb: rng("cb", g.cb, g.row_tiles * 16 * 4, regions)
             if p.kind in (QKV, FFN_UP, LM_HEAD):
                 assert g.stat_groups == stat_groups and g.norm_dim == d and g.k_blocks * fk == d
-                rng("stat_in", g.stat_in, g.stat_groups * 32 * 8, regions)
+                rng("stat_in", g.stat_in, g.stat_groups * 32 * 16, regions)
                 assert bool(g.wg) == (w.desc["norm"] == "layernorm")
             else:
                 assert g.stat_groups == 0 and not g.wg
@@ -120,9 +120,9 @@ def check(w):
                 assert g.act_out and g.g_out and g.stat_out          # one shard in the group: always the last
                 rng("act_out", g.act_out, nbt * g.out_k_blocks * parts * 1024, regions)
                 rng("g_out", g.g_out, g.N * 4, regions)
-                rng("stat_out", g.stat_out, g.row_tiles * 32 * 8, regions)
+                rng("stat_out", g.stat_out, (g.row_tiles // 2) * 32 * 16, regions)
                 assert g.out_k_blocks * fk >= g.N
-                stat_groups = g.row_tiles
+                stat_groups = g.row_tiles // 2
             if p.kind == LM_HEAD:
                 assert g.N == w.desc["vocab"]
                 rng("am_val", g.am_val, p.gx * 32 * 4, regions)
