@@ -113,6 +113,9 @@ static void attn_plan(const Layout &L, int B, int *rows_per_block, int *splits, 
 // the decode step as a list of phases
 // ---------------------------------------------------------------------------
 static int pick_ks(int k_blocks) { return k_blocks >= 16 ? 8 : 4; }  // waves per block
+// weight tiles per block: pairs share the activation fragments; single tiles only where pairs
+// would leave half the compute units without a block
+static int pick_nw(int row_tiles) { return ceil_div(row_tiles, 2) < 128 ? 1 : 2; }
 
 // the final norm and the LM head over the rows in the decode buffers, greedy choice, commit
 static Phase lm_head_phase(Shard *const *group, int n_group, int B, int stat_groups, float *logits, int32_t *next_tokens,
@@ -123,7 +126,7 @@ static Phase lm_head_phase(Shard *const *group, int n_group, int B, int stat_gro
   ph.kind = PH_LM_HEAD;
   StreamGemmArgs &a = ph.g;
   a.w = g0->lm_head.ptr, a.row_tiles = g0->lm_head.row_tiles, a.k_blocks = g0->lm_head.k_blocks, a.B = B, a.N = L.V;
-  a.ks = pick_ks(a.k_blocks);
+  a.ks = pick_ks(a.k_blocks), a.nw = 2;
   a.act = g0->ws + L.ws_ad;
   a.stat_in = (const float *)(g0->ws + L.ws_statd), a.stat_groups = stat_groups, a.norm_dim = L.d;
   a.rms = g0->m.norm == SS_NORM_RMSNORM, a.eps = g0->m.norm_eps;
@@ -173,7 +176,7 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
     Phase ph = {};
     ph.kind = PH_RESID, ph.shard = i;
     StreamGemmArgs &a = ph.g;
-    a.w = w.ptr, a.row_tiles = w.row_tiles, a.k_blocks = w.k_blocks, a.ks = pick_ks(a.k_blocks), a.B = B, a.N = d;
+    a.w = w.ptr, a.row_tiles = w.row_tiles, a.k_blocks = w.k_blocks, a.ks = pick_ks(a.k_blocks), a.nw = pick_nw(a.row_tiles), a.B = B, a.N = d;
     a.act = act;
     a.cb = i == 0 ? bias : nullptr;
     a.x_in = x, a.x_out = x;
@@ -190,7 +193,7 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
       ph.kind = PH_QKV, ph.shard = i;
       StreamGemmArgs &a = ph.g;
       a.w = s->wqkv[l].ptr, a.row_tiles = s->wqkv[l].row_tiles, a.k_blocks = s->wqkv[l].k_blocks, a.B = B, a.N = L.qkv_n;
-      a.ks = pick_ks(a.k_blocks);
+      a.ks = pick_ks(a.k_blocks), a.nw = pick_nw(a.row_tiles);
       normed(a, s->wg_qkv[l], s->cb_qkv[l]);
       a.out_f32 = (float *)(s->ws + L.ws_qkvd), a.ld_out = L.qkv_n;
       ph.gx = stream_gemm_blocks(EPI_F32, a), ph.gy = 1;
@@ -224,7 +227,7 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
       ph.kind = PH_FFN_UP, ph.shard = i;
       StreamGemmArgs &a = ph.g;
       a.w = s->w1[l].ptr, a.row_tiles = s->w1[l].row_tiles, a.k_blocks = s->w1[l].k_blocks, a.B = B, a.N = L.Fs;
-      a.ks = pick_ks(a.k_blocks);
+      a.ks = pick_ks(a.k_blocks), a.nw = m.act == SS_ACT_SWIGLU ? 2 : pick_nw(a.row_tiles);
       normed(a, s->wg_1[l], s->cb_1[l]);
       a.act_out = s->ws + L.ws_ud, a.out_k_blocks = L.Fs / FK, a.act_kind = m.act;
       ph.gx = stream_gemm_blocks(m.act == SS_ACT_SWIGLU ? EPI_SWIGLU : EPI_ACT, a), ph.gy = 1;

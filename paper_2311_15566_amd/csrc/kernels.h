@@ -23,6 +23,7 @@ struct StreamGemmArgs {
   int row_tiles;        // 16-row tiles (SwiGLU: gate/up tiles interleaved, 2 per 16 outputs)
   int k_blocks;
   int ks;               // waves per block = slices of K (4 or 8)
+  int nw;               // weight tiles per block: 2 (always for SwiGLU pairs) or 1
   int B;                // live batch rows
   int N;                // logical output features (for masking)
   const void *act;      // operand fragments [B tiles][k_blocks][parts]

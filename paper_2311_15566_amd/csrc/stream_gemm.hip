@@ -12,9 +12,8 @@ namespace ss {
 namespace {
 
 constexpr int U = 2;      // fragments per register batch; two batches in flight
-constexpr int NW = 2;     // weight tiles per block
 
-template <int NB, int KSM>
+template <int NB, int KSM, int NW>
 struct GemmShared {
   f32x4 red[KSM][NW][NB][64];    // per K slice: the wave's sums [weight tile][batch tile][lane]
   float stat[KSM * 128];         // row-sum slices [slice][row][2], slices * rows = threads of the block
@@ -30,13 +29,13 @@ struct GemmShared {
 // grid = tile pairs, block = a.ks waves.  Wave s streams k blocks [s * per, (s + 1) * per) of
 // both tiles in register batches of U fragments per tile, two batches in flight.
 // KSM: waves per block at most
-template <typename T, int NB, bool GLU, int EPI, int KSM>
+template <typename T, int NB, bool GLU, int EPI, int KSM, int NW>
 __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamGemmArgs a) {
   constexpr int AP = Elem<T>::kParts;
   constexpr int RB = NB * 16;
   constexpr int NEP = GLU ? NB : NW * NB;  // waves that run the epilogue
   constexpr int NWE = GLU ? 2 : 1;         // weight tiles one epilogue wave combines
-  __shared__ GemmShared<NB, KSM> sh;
+  __shared__ GemmShared<NB, KSM, NW> sh;
   const int tid = threadIdx.x, lane = tid & 63, ks = tid >> 6, KS = blockDim.x >> 6;
   const int tile0 = blockIdx.x * NW;
   const int per = (a.k_blocks + KS - 1) / KS;
@@ -216,7 +215,7 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
         s1 += __shfl_xor(s1, 16), s2 += __shfl_xor(s2, 16);
         s1 += __shfl_xor(s1, 32), s2 += __shfl_xor(s2, 32);
         if (lane < 16 && tile_e_ok && b < a.B)  // tile pair blockIdx.x, half je of its float4
-          ((float2 *)a.stat_out)[((size_t)blockIdx.x * 32 + b) * 2 + je] = make_float2(s1, s2);
+          ((float2 *)a.stat_out)[((size_t)((tile0 + je) >> 1) * 32 + b) * 2 + ((tile0 + je) & 1)] = make_float2(s1, s2);
       }
     } else {  // EPI_LOGITS
       if (epi_live) {
@@ -283,13 +282,13 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
 }
 
 int stream_gemm_blocks(int epi, const StreamGemmArgs &a) {
-  (void)epi;
-  return ceil_div(a.row_tiles, NW);
+  return ceil_div(a.row_tiles, epi == EPI_SWIGLU ? 2 : a.nw);
 }
 
 ss_status check_stream_gemm(int dtype, int epi, const StreamGemmArgs &a) {
   if (dtype != SS_DTYPE_BF16 && dtype != SS_DTYPE_F32) SS_FAIL(SS_EINVAL, "decode GEMM: dtype %d", dtype);
   if (a.B < 1 || a.B > 32) SS_FAIL(SS_EINVAL, "decode GEMM: batch %d", a.B);
+  if (a.nw != 1 && a.nw != 2) SS_FAIL(SS_EINVAL, "decode GEMM: %d weight tiles per block", a.nw);
   if (a.row_tiles < 1 || a.k_blocks < 1 || (a.ks != 4 && a.ks != 8) || a.N < 1 || a.N > a.row_tiles * 16)
     SS_FAIL(SS_EINVAL, "decode GEMM: bad shape (tiles %d, k blocks %d, waves %d, N %d)", a.row_tiles, a.k_blocks, a.ks, a.N);
   if (!a.w || !a.act) SS_FAIL(SS_EINVAL, "decode GEMM: NULL operand");
@@ -324,12 +323,19 @@ ss_status check_stream_gemm(int dtype, int epi, const StreamGemmArgs &a) {
 
 template <typename T, int NB, int KSM>
 static void launch_stream_gemm_t(int epi, const StreamGemmArgs &a, dim3 grid, dim3 block, hipStream_t st) {
-#define SS_LAUNCH(GLU, EPI) SS_LAUNCH_KERNEL((stream_gemm<T, NB, GLU, EPI, KSM>), grid, block, 0, st, a)
-  if (epi == EPI_F32) SS_LAUNCH(false, EPI_F32);
-  else if (epi == EPI_ACT) SS_LAUNCH(false, EPI_ACT);
-  else if (epi == EPI_SWIGLU) SS_LAUNCH(true, EPI_SWIGLU);
-  else if (epi == EPI_RESID) SS_LAUNCH(false, EPI_RESID);
-  else SS_LAUNCH(false, EPI_LOGITS);
+#define SS_LAUNCH(GLU, EPI, NW) SS_LAUNCH_KERNEL((stream_gemm<T, NB, GLU, EPI, KSM, NW>), grid, block, 0, st, a)
+  if (epi == EPI_SWIGLU) SS_LAUNCH(true, EPI_SWIGLU, 2);
+  else if (a.nw == 1) {
+    if (epi == EPI_F32) SS_LAUNCH(false, EPI_F32, 1);
+    else if (epi == EPI_ACT) SS_LAUNCH(false, EPI_ACT, 1);
+    else if (epi == EPI_RESID) SS_LAUNCH(false, EPI_RESID, 1);
+    else SS_LAUNCH(false, EPI_LOGITS, 1);
+  } else {
+    if (epi == EPI_F32) SS_LAUNCH(false, EPI_F32, 2);
+    else if (epi == EPI_ACT) SS_LAUNCH(false, EPI_ACT, 2);
+    else if (epi == EPI_RESID) SS_LAUNCH(false, EPI_RESID, 2);
+    else SS_LAUNCH(false, EPI_LOGITS, 2);
+  }
 #undef SS_LAUNCH
 }
 

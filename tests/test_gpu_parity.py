@@ -145,6 +145,11 @@ CASES = [
     ("opt66b_m8", "bf16", dict(batch=32, s_in=33, d_model=448, ffn=1152, head_dim=128, n_heads=2)),
     ("gpt20b_m4", "bf16", dict(batch=8, s_in=300, head_dim=128, n_heads=4, steps=4)),
     ("gpt20b_m4", "bf16", dict(batch=3, s_in=130, kv_dtype="bf16")),          # bf16 cache elements
+    # residual rows whose mean is ~25x their spread: the normalisation is applied after the GEMM
+    # (acc - mean * folded gamma), which must not lose the signal to cancellation
+    ("gpt20b_m4", "bf16", dict(batch=6, s_in=40, steps=4, wte_offset=0.5)),
+    ("gpt20b_m4", "f32", dict(batch=2, s_in=20, steps=3, wte_offset=0.5)),
+    ("llama30b_m2", "bf16", dict(batch=4, s_in=40, steps=3, wte_offset=0.5)),
 ]
 
 
@@ -153,11 +158,19 @@ def test_scaled_family_teacher_forced(ss, name, dtype, kw, side_stream):
     import torch
     kw = dict(kw)
     kv_dtype = kw.pop("kv_dtype", None)
+    wte_offset = kw.pop("wte_offset", 0.0)
     w = scaled(name, dtype, **kw)
     if kv_dtype:
         w.desc["kv_dtype"] = kv_dtype
     bf16 = dtype == "bf16"
     W = make_weights(w.desc, tp_slice(w.desc, 0, w.desc["n_layers"], 0, 1), w.seed)   # parent = full model
+    if wte_offset:
+        from synth import bf16_bits_to_f32, f32_to_bf16_bits
+        W["lm_head"] = W["lm_head"].copy()               # the offset goes into the embedding only
+        if bf16:
+            W["wte"] = f32_to_bf16_bits(bf16_bits_to_f32(W["wte"]) + np.float32(wte_offset))
+        else:
+            W["wte"] = (W["wte"] + np.float32(wte_offset)).astype(np.float32)
     toks = make_tokens(w.seed, w.batch, w.s_in, w.desc["vocab"])
     ora = D.OracleShard(w.desc, w.slice, W, w.batch, w.s_max)
     sh = ss.Shard(w.desc, w.slice, W, w.batch, w.s_max)
