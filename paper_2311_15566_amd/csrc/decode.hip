@@ -20,19 +20,25 @@ __global__ void __launch_bounds__(256) embed_rows(EmbedArgs a) {
   embed_row_block<T>(a, blockIdx.x, scratch);
 }
 
-// a = Norm(x) for every token row, written in operand order.  grid = rows.
+// a = Norm(x) for every token row, written in operand order with `parts` fragments per k block.
+// grid = rows.
 template <typename T>
 __global__ void __launch_bounds__(256) norm_rows(const float *x, const float *gamma, const float *beta, void *a_out,
-                                                 int d, int k_blocks, int rms, float eps) {
+                                                 int d, int k_blocks, int parts, int rms, float eps) {
+  constexpr int PL = Elem<T>::kPerLane;
   __shared__ float scratch[4];
   const int r = blockIdx.x;
   const float *xr = x + (size_t)r * d;
   float mean, rstd;
   row_stats(xr, d, rms, eps, scratch, &mean, &rstd);
-  for (int k = threadIdx.x; k < d; k += 256) {
-    float y = (xr[k] - mean) * rstd * gamma[k];
-    if (beta) y += beta[k];
-    store_act<T>(a_out, r, k, k_blocks, Elem<T>::kParts, y);
+  for (int k = threadIdx.x * PL; k < d; k += 256 * PL) {
+    float y[PL];
+#pragma unroll
+    for (int e = 0; e < PL; ++e) {
+      y[e] = (xr[k + e] - mean) * rstd * gamma[k + e];
+      if (beta) y[e] += beta[k + e];
+    }
+    store_piece<T>(a_out, r, k, k_blocks, y, parts);
   }
 }
 
@@ -368,11 +374,14 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, i
     else hipLaunchKernelGGL(embed_rows<float>, dim3(T_live), dim3(256), 0, st, e);
     SS_HIP(hipGetLastError());
   }
+  // (single bf16 activations into the QKV / first FFN GEMMs were tried: the OPT-66B shape then
+  // misses the logits bar at its first token, 6.4e-2)
+  const int nparts = parts;
   auto norm = [&](const float *g, const float *b) -> ss_status {
     if (dt == SS_DTYPE_BF16)
-      hipLaunchKernelGGL(norm_rows<bf16_t>, dim3(T_live), dim3(256), 0, st, x, g, b, abuf, d, d / FK, rms, m.norm_eps);
+      hipLaunchKernelGGL(norm_rows<bf16_t>, dim3(T_live), dim3(256), 0, st, x, g, b, abuf, d, d / FK, nparts, rms, m.norm_eps);
     else
-      hipLaunchKernelGGL(norm_rows<float>, dim3(T_live), dim3(256), 0, st, x, g, b, abuf, d, d / FK, rms, m.norm_eps);
+      hipLaunchKernelGGL(norm_rows<float>, dim3(T_live), dim3(256), 0, st, x, g, b, abuf, d, d / FK, nparts, rms, m.norm_eps);
     SS_HIP(hipGetLastError());
     return SS_OK;
   };
@@ -384,7 +393,7 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, i
       const Layout &L = s->L;
       TileGemmArgs a = {};
       a.w = s->wqkv[l].ptr, a.row_tiles = s->wqkv[l].row_tiles, a.k_blocks = s->wqkv[l].k_blocks;
-      a.act = abuf, a.act_parts = parts, a.T = T, a.T_live = T_live, a.N = L.qkv_n, a.bias = s->layers[l].bqkv;
+      a.act = abuf, a.act_parts = nparts, a.T = T, a.T_live = T_live, a.N = L.qkv_n, a.bias = s->layers[l].bqkv;
       a.out_f32 = (float *)(s->ws + L.ws_qkv), a.ld_out = L.qkv_n;
       SS_TRY(launch_tile_gemm(dt, EPI_F32, a, st));
       PrefillAttnArgs p = {};
@@ -413,7 +422,7 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, i
       const bool glu = m.act == SS_ACT_SWIGLU;
       TileGemmArgs a = {};
       a.w = s->w1[l].ptr, a.row_tiles = s->w1[l].row_tiles, a.k_blocks = s->w1[l].k_blocks;
-      a.act = abuf, a.act_parts = parts, a.T = T, a.T_live = T_live, a.N = L.Fs, a.bias = s->layers[l].b1;
+      a.act = abuf, a.act_parts = nparts, a.T = T, a.T_live = T_live, a.N = L.Fs, a.bias = s->layers[l].b1;
       a.act_out = s->ws + L.ws_u, a.out_k_blocks = L.Fs / FK, a.out_parts = parts, a.act_kind = m.act;
       SS_TRY(launch_tile_gemm(dt, glu ? EPI_SWIGLU : EPI_ACT, a, st));
     }

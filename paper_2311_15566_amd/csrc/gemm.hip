@@ -21,8 +21,24 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
   __shared__ __align__(16) u32x4 lds_a[KS][8][AP][64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave >> 1, wc = wave & 1;
-  const int rt0 = blockIdx.x * 8;   // first weight row tile
-  const int tt0 = blockIdx.y * 8;   // first token tile
+  // Block -> output tile.  Workgroups go to the 8 XCDs round-robin and each XCD has its own L2, so
+  // XCD x takes a contiguous run of the tile list, ordered so that the blocks running together
+  // on it are a few token blocks times a window of row blocks: weight panels are shared by the
+  // token blocks of a group, activation panels by the row blocks of the window.
+  int rb, tb;
+  {
+    constexpr int GT = 4;  // token blocks per group
+    const int nrb = a.n_row_blocks, ntb = a.T / 128, nblk = nrb * ntb;
+    const int pid = blockIdx.x, xcd = pid % 8, local = pid / 8;
+    const int base = nblk / 8, rem = nblk % 8;
+    const int L = xcd * base + min(xcd, rem) + local;
+    const int group = L / (GT * nrb), first_tb = group * GT;
+    const int gsz = min(GT, ntb - first_tb), within = L - group * GT * nrb;
+    tb = first_tb + within % gsz;
+    rb = within / gsz;
+  }
+  const int rt0 = rb * 8;   // first weight row tile
+  const int tt0 = tb * 8;   // first token tile
   const u32x4 *W = (const u32x4 *)a.w;
   const u32x4 *A = (const u32x4 *)a.act;
 
@@ -122,14 +138,15 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
   }
 }
 
-ss_status launch_tile_gemm(int dtype, int epi, const TileGemmArgs &a, hipStream_t st) {
+ss_status launch_tile_gemm(int dtype, int epi, TileGemmArgs a, hipStream_t st) {
   if (a.T < 128 || a.T % 128) SS_FAIL(SS_EINVAL, "prefill GEMM: token count %d is not a multiple of 128", a.T);
   if (a.row_tiles < 1 || a.k_blocks < 1 || a.N % 4) SS_FAIL(SS_EINVAL, "prefill GEMM: bad shape");
   if ((epi == EPI_F32 && (a.ld_out % 4)) || epi == EPI_LOGITS) SS_FAIL(SS_EINVAL, "prefill GEMM: bad epilogue");
   if (a.act_parts != 1 && !(a.act_parts == 2 && dtype == SS_DTYPE_BF16)) SS_FAIL(SS_EINVAL, "prefill GEMM: bad act_parts");
   if ((epi == EPI_ACT || epi == EPI_SWIGLU) && a.out_parts != 1 && !(a.out_parts == 2 && dtype == SS_DTYPE_BF16))
     SS_FAIL(SS_EINVAL, "prefill GEMM: bad out_parts");
-  dim3 grid(ceil_div(a.row_tiles, 8), a.T / 128);
+  a.n_row_blocks = ceil_div(a.row_tiles, 8);
+  dim3 grid(a.n_row_blocks * (a.T / 128));
 #define SS_LAUNCH(TT, EPI, AP) hipLaunchKernelGGL((tile_gemm<TT, EPI, AP>), grid, dim3(256), 0, st, a)
   if (dtype == SS_DTYPE_BF16 && a.act_parts == 2) {
     if (epi == EPI_F32) SS_LAUNCH(bf16_t, EPI_F32, 2);

@@ -78,8 +78,9 @@ struct TileGemmArgs {
   int out_k_blocks;
   int out_parts;
   int act_kind;
+  int n_row_blocks;   // set by the launcher: 128-row blocks of the weight matrix
 };
-ss_status launch_tile_gemm(int dtype, int epi, const TileGemmArgs &a, hipStream_t st);
+ss_status launch_tile_gemm(int dtype, int epi, TileGemmArgs a, hipStream_t st);
 
 // Decode attention over the committed cache (plus the new token), sequence-split.
 struct DecodeAttnArgs {

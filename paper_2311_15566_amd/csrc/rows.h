@@ -47,8 +47,9 @@ __device__ __forceinline__ void widen16<bf16_t>(const u32x4 &raw, float *out) {
 
 // PL consecutive activations (k a multiple of PL) of row `row` as one 16-byte piece per part
 template <typename T>
-__device__ __forceinline__ void store_piece(void *base, int row, int k, int k_blocks, const float *y) {
-  constexpr int PL = Elem<T>::kPerLane, AP = Elem<T>::kParts;
+__device__ __forceinline__ void store_piece(void *base, int row, int k, int k_blocks, const float *y,
+                                            const int AP = Elem<T>::kParts) {
+  constexpr int PL = Elem<T>::kPerLane;
   T hi[PL], lo[PL];
 #pragma unroll
   for (int e = 0; e < PL; ++e) {
