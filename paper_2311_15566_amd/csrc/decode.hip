@@ -20,25 +20,56 @@ __global__ void __launch_bounds__(256) embed_rows(EmbedArgs a) {
   embed_row_block<T>(a, blockIdx.x, scratch);
 }
 
-// a = Norm(x) for every token row, written in operand order with `parts` fragments per k block.
-// grid = rows.
+// a = Norm(x) for a tile of 16 token rows, written in operand order with `parts` fragments per k
+// block.  grid = row tiles, 4 waves; a wave owns whole 1 KiB fragments (lane = kq * 16 + row), so
+// every store is a full coalesced fragment.  Rows past `rows` are written as zeros.
 template <typename T>
 __global__ void __launch_bounds__(256) norm_rows(const float *x, const float *gamma, const float *beta, void *a_out,
-                                                 int d, int k_blocks, int parts, int rms, float eps) {
-  constexpr int PL = Elem<T>::kPerLane;
-  __shared__ float scratch[4];
-  const int r = blockIdx.x;
-  const float *xr = x + (size_t)r * d;
-  float mean, rstd;
-  row_stats(xr, d, rms, eps, scratch, &mean, &rstd);
-  for (int k = threadIdx.x * PL; k < d; k += 256 * PL) {
+                                                 int rows, int d, int k_blocks, int parts, int rms, float eps) {
+  constexpr int PL = Elem<T>::kPerLane, FK = Elem<T>::kFragK;
+  __shared__ float red[4][16];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 15, kq = lane >> 4;
+  const int row = blockIdx.x * 16 + r;
+  const bool live = row < rows;
+  const float *xr = x + (size_t)row * d;
+  // the row's mean, then its centred second moment (two passes, as the definition has it);
+  // lane (kq, r) of wave w covers k blocks w, w + 4, ...; after the first pass the rows are L2 hits
+  float s1 = 0.f;
+  if (live && !rms)
+    for (int kb = wave; kb < k_blocks; kb += 4) {
+#pragma unroll
+      for (int e = 0; e < PL; ++e) s1 += xr[kb * FK + kq * PL + e];
+    }
+  auto tile_reduce = [&](float s) {
+    s += __shfl_xor(s, 16);
+    s += __shfl_xor(s, 32);
+    __syncthreads();  // the previous use of red is over
+    if (lane < 16) red[wave][lane] = s;
+    __syncthreads();
+    return red[0][r] + red[1][r] + red[2][r] + red[3][r];
+  };
+  float mean = 0.f;
+  if (!rms) mean = tile_reduce(s1) / (float)d;
+  float q = 0.f;
+  if (live)
+    for (int kb = wave; kb < k_blocks; kb += 4) {
+#pragma unroll
+      for (int e = 0; e < PL; ++e) {
+        const float c = xr[kb * FK + kq * PL + e] - mean;
+        q += c * c;
+      }
+    }
+  const float rstd = rsqrtf(tile_reduce(q) / (float)d + eps);
+  // normalise and write whole fragments
+  for (int kb = wave; kb < k_blocks; kb += 4) {
     float y[PL];
 #pragma unroll
     for (int e = 0; e < PL; ++e) {
-      y[e] = (xr[k + e] - mean) * rstd * gamma[k + e];
-      if (beta) y[e] += beta[k + e];
+      const int k = kb * FK + kq * PL + e;
+      y[e] = live ? (xr[k] - mean) * rstd * gamma[k] + (beta ? beta[k] : 0.f) : 0.f;
     }
-    store_piece<T>(a_out, r, k, k_blocks, y, parts);
+    store_piece<T>(a_out, blockIdx.x * 16 + r, kb * FK + kq * PL, k_blocks, y, parts);
   }
 }
 
@@ -379,9 +410,9 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, i
   const int nparts = parts;
   auto norm = [&](const float *g, const float *b) -> ss_status {
     if (dt == SS_DTYPE_BF16)
-      hipLaunchKernelGGL(norm_rows<bf16_t>, dim3(T_live), dim3(256), 0, st, x, g, b, abuf, d, d / FK, nparts, rms, m.norm_eps);
+      hipLaunchKernelGGL(norm_rows<bf16_t>, dim3(ceil_div(T_live, 16)), dim3(256), 0, st, x, g, b, abuf, T_live, d, d / FK, nparts, rms, m.norm_eps);
     else
-      hipLaunchKernelGGL(norm_rows<float>, dim3(T_live), dim3(256), 0, st, x, g, b, abuf, d, d / FK, nparts, rms, m.norm_eps);
+      hipLaunchKernelGGL(norm_rows<float>, dim3(ceil_div(T_live, 16)), dim3(256), 0, st, x, g, b, abuf, T_live, d, d / FK, nparts, rms, m.norm_eps);
     SS_HIP(hipGetLastError());
     return SS_OK;
   };

@@ -14,21 +14,6 @@ __device__ __forceinline__ float block_sum(float v, float *scratch) {
   return scratch[0] + scratch[1] + scratch[2] + scratch[3];
 }
 
-__device__ __forceinline__ void row_stats(const float *row, int d, int rms, float eps, float *scratch, float *mean_out,
-                                          float *rstd_out) {
-  float s = 0.f;
-  for (int k = threadIdx.x; k < d; k += 256) s += row[k];
-  const float mean = rms ? 0.f : block_sum(s, scratch) / (float)d;
-  float q = 0.f;
-  for (int k = threadIdx.x; k < d; k += 256) {
-    const float c = row[k] - mean;
-    q += c * c;
-  }
-  const float var = block_sum(q, scratch) / (float)d;
-  *mean_out = mean;
-  *rstd_out = rsqrtf(var + eps);
-}
-
 template <typename T>
 __device__ __forceinline__ void widen16(const u32x4 &raw, float *out);
 template <>
