@@ -404,6 +404,46 @@ def test_repack_layer_and_head_intersection():
     assert not dst[2].any() and not dst[:, :, :, 2:].any()
 
 
+def position_slice(index, D_, P, M, n_layers, n_heads):
+    """(layers, heads) of position `index` of a (D, P, M) configuration, numbered d-major, then
+    stage, then tensor shard."""
+    m = index % M
+    p = (index // M) % P
+    return sl(p * n_layers // P, (p + 1) * n_layers // P, m * n_heads // M, (m + 1) * n_heads // M)
+
+
+def test_device_mapping_example_of_the_paper():
+    """tests/golden/device_mapping_example.txt: the intersection sizes the re-partition reports
+    rank the target positions as the paper's worked example says."""
+    import os
+    cfg = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "device_mapping_example.txt")):
+        f = line.split()
+        if not f or f[0].startswith("#"):
+            continue
+        cfg[f[0]] = f[1:]
+    cur = {k: int(v) for k, v in (t.split("=") for t in cfg["current"])}
+    tgt = {k: int(v) for k, v in (t.split("=") for t in cfg["target"])}
+    src_index = int(cfg["source"][0][1:])
+    best = sorted(int(t[1:]) for t in cfg["best_targets"])
+    n_layers, n_heads, B, S, Dh = 6, 4, 2, 5, 4            # layers divisible by both stage counts
+    rng = np.random.default_rng(11)
+    s_sl = position_slice(src_index, cur["D"], cur["P"], cur["M"], n_layers, n_heads)
+    src = rand_kv(rng, s_sl["layer_hi"] - s_sl["layer_lo"], B, s_sl["head_hi"] - s_sl["head_lo"], S, Dh)
+    n = [S, 3]
+    counts = []
+    for j in range(tgt["D"] * tgt["P"] * tgt["M"]):
+        d_sl = position_slice(j, tgt["D"], tgt["P"], tgt["M"], n_layers, n_heads)
+        dst = np.zeros((d_sl["layer_hi"] - d_sl["layer_lo"], 2, B, d_sl["head_hi"] - d_sl["head_lo"], S, Dh), np.uint16)
+        counts.append(D.kv_repack_arrays(dst, d_sl, src, s_sl, n, [0, 1]))
+    top = max(counts)
+    assert sorted(j for j, c in enumerate(counts) if c == top) == best
+    assert top > 0 and counts.count(top) == len(best)
+    # and the sizes themselves: stage 0 of the target takes layers [0,2) of u_1's [0,3), stage 1 one layer, stage 2 none
+    per_layer = 2 * 2 * (S + 3) * Dh                         # {K,V} x u_1's two heads x committed rows x Dh
+    assert counts == [2 * per_layer, per_layer, 0, 2 * per_layer, per_layer, 0]
+
+
 @pytest.mark.parametrize("M,Mp", [(2, 4), (4, 2), (1, 4), (4, 1)])
 def test_repack_round_trip_is_identity(M, Mp):
     """M-way -> M'-way -> M-way gives back every committed byte (Section 3.3: only the
