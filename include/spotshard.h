@@ -134,6 +134,23 @@ ss_status ss_prefill(ss_shard *const *group, int32_t n_group, const int32_t *tok
 ss_status ss_decode_step(ss_shard *const *group, int32_t n_group, const int32_t *tokens_in,
                          int32_t B, float *logits, int32_t *next_tokens, void *hip_stream);
 
+/* The same two calls for a shard that is one STAGE of a pipeline (Section 2.2, inter-operator
+ * parallelism: consecutive layers grouped into stages, each fed by the one before).  Exactly
+ * one of tokens / hidden_in is given: tokens for the model's first stage, hidden_in (device
+ * float32, [B * S_in, d_model] for the initial phase, [B, d_model] for a step: the previous
+ * stage's hidden_out) for a later one, which then skips the embedding.  With hidden_out (device
+ * float32, same shapes) the shard is not the last stage: the residual stream after its layers
+ * goes there, no final norm or LM head runs (logits and next_tokens must be NULL) and the
+ * commit is the step's last kernel all the same.  hidden_out = NULL: final norm, LM head,
+ * greedy token as in ss_prefill / ss_decode_step, which are these calls with tokens only.
+ * SS_EINVAL if both or neither of tokens / hidden_in are given. */
+ss_status ss_stage_prefill(ss_shard *const *group, int32_t n_group, const int32_t *tokens,
+                           const float *hidden_in, int32_t B, int32_t S_in, float *hidden_out,
+                           float *logits, int32_t *next_tokens, void *hip_stream);
+ss_status ss_stage_decode_step(ss_shard *const *group, int32_t n_group, const int32_t *tokens_in,
+                               const float *hidden_in, int32_t B, float *hidden_out, float *logits,
+                               int32_t *next_tokens, void *hip_stream);
+
 /* Committed lengths as the device holds them: synchronizes the stream, copies
  * n[0..max_batch) to out_host (host int32 [max_batch]). */
 ss_status ss_committed_len(const ss_shard *shard, int32_t *out_host, void *hip_stream);
@@ -179,7 +196,7 @@ ss_status ss_set_graph_launch(ss_shard *shard, int32_t enabled);
  * ss_kernel_timing_read synchronizes the stream, returns the milliseconds and launch counts
  * accumulated per class since the last read (host arrays of 8) and clears them.  Classes:
  * 0 embedding, 1 QKV GEMM, 2 decode attention, 3 out-projection and second-FFN GEMM (the
- * residual epilogue), 4 first-FFN GEMM, 5 LM head. */
+ * residual epilogue), 4 first-FFN GEMM, 5 LM head, 6 the commit kernel of a stage without LM head. */
 ss_status ss_kernel_timing(ss_shard *shard, int32_t enabled);
 ss_status ss_kernel_timing_read(ss_shard *shard, double ms[8], int64_t count[8], void *hip_stream);
 

@@ -213,11 +213,17 @@ def _check_group(group):
                 raise ValueError("FFN slices of a group overlap")
 
 
-def decode_step(group, tokens, rows=None):
+def decode_step(group, tokens, rows=None, hidden_in=None, hidden_out=False):
     """One incremental decoding iteration (Section 2.1) for every batch row in `rows`
     (default: all rows of tokens): consumes token tokens[b] at position n[b], appends
     its key/value as cache row n[b], attends over rows 0..n[b], returns the logits
     [B, V] of the next token and commits n[b] <- n[b] + 1 as the last action.
+
+    Pipeline stages (Section 2.2, inter-operator parallelism): with hidden_in [B, d] the
+    shard is not the model's first stage and starts from the previous stage's output
+    instead of the embedding (tokens is then ignored and may be None); with hidden_out
+    it is not the last stage and returns the residual stream after its layers, [B, d],
+    instead of applying the final norm and the LM head.
 
     group: list of co-resident shards of the same layers with disjoint head / FFN
     slices; their partial attention and FFN outputs are summed where a tensor-parallel
@@ -228,14 +234,15 @@ def decode_step(group, tokens, rows=None):
     g0 = group[0]
     desc = g0.desc
     Dh = desc["head_dim"]
-    tokens = np.asarray(tokens)
-    rows = range(len(tokens)) if rows is None else rows
-    logits = np.zeros((len(tokens), desc["vocab"]), dtype=g0.real)
+    nrows = len(tokens) if hidden_in is None else len(hidden_in)
+    tokens = None if hidden_in is not None else np.asarray(tokens)
+    rows = range(nrows) if rows is None else rows
+    out = np.zeros((nrows, desc["d_model"] if hidden_out else desc["vocab"]), dtype=g0.real)
     for b in rows:
         n = int(g0.n[b])
         if n + 1 > g0.max_seq:
             raise RuntimeError("KV cache full")
-        x = g0._embed(int(tokens[b]), n)
+        x = g0._embed(int(tokens[b]), n) if hidden_in is None else np.asarray(hidden_in[b], dtype=g0.real)
         for li in range(g0.Ls):
             L0 = g0.layers[li]
             a = g0._norm(x, L0["ln1_g"], L0["ln1_b"])
@@ -262,28 +269,38 @@ def decode_step(group, tokens, rows=None):
             if L0["b2"] is not None:
                 z = z + L0["b2"]
             x = x + z
-        xf = g0._norm(x, g0.lnf_g, g0.lnf_b)
-        logits[b] = g0.lm_head @ xf
+        if hidden_out:
+            out[b] = x
+        else:
+            xf = g0._norm(x, g0.lnf_g, g0.lnf_b)
+            out[b] = g0.lm_head @ xf
     for b in rows:                                              # token-level commit
         for s in group:
             s.n[b] += 1
-    return logits
+    return out
 
 
-def prefill(group, tokens):
+def prefill(group, tokens, hidden_in=None, hidden_out=False):
     """The initial phase by definition: S_in incremental iterations from an empty cache,
-    keeping the last logits.  tokens: [B, S_in].  Returns logits [B, V]."""
-    tokens = np.asarray(tokens)
-    logits = None
-    for t in range(tokens.shape[1]):
-        logits = decode_step(group, tokens[:, t])
-    return logits
+    keeping the last logits.  tokens: [B, S_in].  Returns logits [B, V].
+
+    As a pipeline stage: hidden_in [B, S_in, d] replaces the tokens, and with hidden_out
+    the residual stream of every position after the shard's layers, [B, S_in, d], is
+    returned instead of the logits."""
+    S = np.asarray(tokens).shape[1] if hidden_in is None else np.asarray(hidden_in).shape[1]
+    outs = []
+    for t in range(S):
+        outs.append(decode_step(group, None if hidden_in is not None else np.asarray(tokens)[:, t],
+                                hidden_in=None if hidden_in is None else np.asarray(hidden_in)[:, t],
+                                hidden_out=hidden_out))
+    return np.stack(outs, axis=1) if hidden_out else outs[-1]
 
 
-def forward_matrix(group, tokens_row, b=None):
+def forward_matrix(group, tokens_row, b=None, hidden_in=None, hidden_out=False):
     """Full causal recompute (the left-hand form, Eq. (1)) of one sequence from position 0:
     all S tokens at once with an explicit S x S score matrix masked above the diagonal.
-    Returns the logits of every position, [S, V].
+    Returns the logits of every position, [S, V].  hidden_in [S, d] / hidden_out: the
+    pipeline-stage forms of decode_step.
 
     With b given, also stores the keys/values as cache rows [0, S) of batch row b and
     sets n[b] = S (the initial phase in matrix form); the row must be empty before.
@@ -292,12 +309,14 @@ def forward_matrix(group, tokens_row, b=None):
     g0 = group[0]
     desc = g0.desc
     Dh = desc["head_dim"]
-    toks = np.asarray(tokens_row)
-    S = len(toks)
+    S = len(tokens_row) if hidden_in is None else len(hidden_in)
     if b is not None and int(g0.n[b]) != 0:
         raise RuntimeError("matrix-form prefill needs an empty row")
     pos = np.arange(S)
-    X = np.stack([g0._embed(int(t), int(p)) for t, p in zip(toks, pos)])
+    if hidden_in is None:
+        X = np.stack([g0._embed(int(t), int(p)) for t, p in zip(np.asarray(tokens_row), pos)])
+    else:
+        X = np.asarray(hidden_in, dtype=g0.real).copy()
     mask = np.where(pos[None, :] > pos[:, None], -np.inf, 0.0).astype(g0.real)   # [query, key]
     for li in range(g0.Ls):
         L0 = g0.layers[li]
@@ -324,10 +343,12 @@ def forward_matrix(group, tokens_row, b=None):
         if L0["b2"] is not None:
             Z = Z + L0["b2"]
         X = X + Z
-    XF = g0._norm(X, g0.lnf_g, g0.lnf_b)
     if b is not None:
         for s in group:
             s.n[b] = S
+    if hidden_out:
+        return X
+    XF = g0._norm(X, g0.lnf_g, g0.lnf_b)
     return XF @ g0.lm_head.T
 
 

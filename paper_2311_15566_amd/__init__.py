@@ -11,10 +11,13 @@ from .binding import (  # noqa: F401
     SpotShardError,
     committed_len,
     decode_step,
+    device_kv_bytes,
     kv_export,
     kv_import,
     kv_repack,
     lib,
     prefill,
+    stage_decode_step,
+    stage_prefill,
     version,
 )

@@ -62,6 +62,8 @@ def _load():
     L.ss_shard_reset.argtypes = [vp, vp]
     L.ss_prefill.argtypes = [C.POINTER(vp), i32, vp, i32, i32, vp, vp, vp]
     L.ss_decode_step.argtypes = [C.POINTER(vp), i32, vp, i32, vp, vp, vp]
+    L.ss_stage_prefill.argtypes = [C.POINTER(vp), i32, vp, vp, i32, i32, vp, vp, vp, vp]
+    L.ss_stage_decode_step.argtypes = [C.POINTER(vp), i32, vp, vp, i32, vp, vp, vp, vp]
     L.ss_committed_len.argtypes = [vp, C.POINTER(i32), vp]
     L.ss_kv_repack.argtypes = [vp, vp, C.POINTER(i32), i32, C.POINTER(C.c_uint64), vp]
     L.ss_kv_export_bytes.restype = sz
@@ -205,6 +207,23 @@ def decode_step(group, tokens_in, logits=None, next_tokens=None, stream=None):
                               _stream(stream)))
 
 
+def stage_prefill(group, B, S, tokens=None, hidden_in=None, hidden_out=None, logits=None, next_tokens=None, stream=None):
+    """A pipeline stage's initial phase: tokens (device int32 [B, S]) or hidden_in (device float32 [B*S, d]);
+    hidden_out (device float32 [B*S, d]) or logits / next_tokens."""
+    arr, n = _group(group)
+    _check(lib.ss_stage_prefill(arr, n, _dptr(tokens), _dptr(hidden_in), B, S, _dptr(hidden_out), _dptr(logits),
+                                _dptr(next_tokens), _stream(stream)))
+
+
+def stage_decode_step(group, B, tokens_in=None, hidden_in=None, hidden_out=None, logits=None, next_tokens=None,
+                      stream=None):
+    """A pipeline stage's decode step: tokens_in (device int32 [B]) or hidden_in (device float32 [B, d]);
+    hidden_out (device float32 [B, d]) or logits / next_tokens."""
+    arr, n = _group(group)
+    _check(lib.ss_stage_decode_step(arr, n, _dptr(tokens_in), _dptr(hidden_in), B, _dptr(hidden_out), _dptr(logits),
+                                    _dptr(next_tokens), _stream(stream)))
+
+
 def committed_len(shard, stream=None) -> np.ndarray:
     out = (C.c_int32 * shard.max_batch)()
     _check(lib.ss_committed_len(shard.handle, out, _stream(stream)))
@@ -216,6 +235,11 @@ def kv_repack(dst, src, batch_map, first_source=True, stream=None) -> int:
     moved = C.c_uint64(0)
     _check(lib.ss_kv_repack(dst.handle, src.handle, bm, int(first_source), C.byref(moved), _stream(stream)))
     return moved.value
+
+
+def device_kv_bytes(shard) -> int:
+    """Bytes of the committed cache rows the shard holds (what ss_kv_export would write)."""
+    return int(lib.ss_kv_export_bytes(shard.handle))
 
 
 def kv_export(shard, stream=None) -> np.ndarray:

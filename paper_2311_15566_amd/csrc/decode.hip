@@ -100,6 +100,16 @@ __global__ void __launch_bounds__(256) gather_last(const float *x, int S, float 
   if (threadIdx.x == 0) ((f32x4 *)stat_out)[b] = f32x4{s1, s2, 0.f, 0.f};
 }
 
+// token-level commit of a stage that hands hidden states on (no LM head): the last action of its step
+struct CommitArgs {
+  int32_t *lens[8];
+  int n_lens, B, inc;
+};
+__global__ void commit_rows(CommitArgs a) {
+  if ((int)threadIdx.x < a.B)
+    for (int q = 0; q < a.n_lens; ++q) a.lens[q][threadIdx.x] += a.inc;
+}
+
 // ---------------------------------------------------------------------------
 // group checks
 // ---------------------------------------------------------------------------
@@ -182,8 +192,11 @@ static Phase lm_head_phase(Shard *const *group, int n_group, int B, int stat_gro
 // Phases of one decode step, in order.  The residual stream x, the operand of the next normalised
 // GEMM (x * gamma) and the rows' partial sums live in group[0]'s workspace; q|k|v, the attention
 // output and the FFN activation in each shard's own.
-static void build_decode_plan(Shard *const *group, int n_group, const int32_t *tokens_in, int B, float *logits,
-                              int32_t *next_tokens, int stop_after_layer, std::vector<Phase> *plan) {
+// Pipeline stages: hidden_in replaces the token lookup, hidden_out the final norm + LM head (the
+// stage then commits with a kernel of its own).
+static void build_decode_plan(Shard *const *group, int n_group, const int32_t *tokens_in, const float *hidden_in, int B,
+                              float *hidden_out, float *logits, int32_t *next_tokens, int stop_after_layer,
+                              std::vector<Phase> *plan) {
   Shard *g0 = group[0];
   const Layout &L0 = g0->L;
   const ss_model_desc &m = g0->m;
@@ -198,7 +211,7 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
   {
     Phase ph = {};
     ph.kind = PH_EMBED, ph.gx = B, ph.gy = 1;
-    ph.e = EmbedArgs{tokens_in, g0->wte, g0->wpe, g0->d_len, 0, x, d, L0.V, first_gamma, ad, statd};
+    ph.e = EmbedArgs{hidden_in, tokens_in, g0->wte, g0->wpe, g0->d_len, 0, x, d, L0.V, first_gamma, ad, statd};
     plan->push_back(ph);
   }
   int stat_groups = 1;  // partial-sum groups behind the rows in statd
@@ -209,7 +222,8 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
   };
   // sum over the group at a reduce slot: shard i adds its partial to what the previous shards
   // left; the last one also emits the next operand (x * next_gamma) and the partial sums
-  auto resid = [&](int i, const FragMat &w, const void *act, const float *bias, const float *next_gamma) {
+  auto resid = [&](int i, const FragMat &w, const void *act, const float *bias, const float *next_gamma,
+                   float *x_final) {
     Phase ph = {};
     ph.kind = PH_RESID, ph.shard = i;
     StreamGemmArgs &a = ph.g;
@@ -217,7 +231,10 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
     a.act = act;
     a.cb = i == 0 ? bias : nullptr;
     a.x_in = x, a.x_out = x;
-    if (i == n_group - 1) a.act_out = ad, a.out_k_blocks = d / FK, a.g_out = next_gamma, a.stat_out = statd;
+    if (i == n_group - 1) {
+      if (x_final) a.x_out = x_final;  // the stage's output: no next GEMM in this shard
+      else a.act_out = ad, a.out_k_blocks = d / FK, a.g_out = next_gamma, a.stat_out = statd;
+    }
     ph.gx = stream_gemm_blocks(EPI_RESID, a), ph.gy = 1;
     plan->push_back(ph);
   };
@@ -256,7 +273,7 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
     }
     stat_groups = d / 32;  // from here on the partial sums come from the residual GEMMs' weight tile pairs
     for (int i = 0; i < n_group; ++i)  // output projection, sum over the group, residual
-      resid(i, group[i]->wo[l], group[i]->ws + group[i]->L.ws_od, D0.bo, D0.ln2_g);
+      resid(i, group[i]->wo[l], group[i]->ws + group[i]->L.ws_od, D0.bo, D0.ln2_g, nullptr);
     for (int i = 0; i < n_group; ++i) {  // first FFN matrix + activation
       Shard *s = group[i];
       const Layout &L = s->L;
@@ -272,8 +289,17 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
     }
     const float *next_gamma = l + 1 < L0.Ls ? g0->layers[l + 1].ln1_g : g0->lnf_g;
     for (int i = 0; i < n_group; ++i)  // second FFN matrix, sum over the group, residual
-      resid(i, group[i]->w2[l], group[i]->ws + group[i]->L.ws_ud, D0.b2, next_gamma);
+      resid(i, group[i]->w2[l], group[i]->ws + group[i]->L.ws_ud, D0.b2, next_gamma,
+            l + 1 == L0.Ls ? hidden_out : nullptr);
     if (l == stop_after_layer) return;
+  }
+  if (hidden_out) {
+    Phase ph = {};
+    ph.kind = PH_COMMIT, ph.gx = 1, ph.gy = 1;
+    ph.g.B = B, ph.g.n_lens = n_group, ph.g.commit_inc = 1;
+    for (int i = 0; i < n_group; ++i) ph.g.lens[i] = group[i]->d_len;
+    plan->push_back(ph);
+    return;
   }
   plan->push_back(lm_head_phase(group, n_group, B, stat_groups, logits, next_tokens, 1));
 }
@@ -324,14 +350,23 @@ static ss_status launch_phase(Shard *g0, const Phase &ph, hipStream_t st) {
     case PH_RESID: return launch_stream_gemm(dt, EPI_RESID, ph.g, st);
     case PH_FFN_UP: return launch_stream_gemm(dt, g0->m.act == SS_ACT_SWIGLU ? EPI_SWIGLU : EPI_ACT, ph.g, st);
     case PH_LM_HEAD: return launch_stream_gemm(dt, EPI_LOGITS, ph.g, st);
+    case PH_COMMIT: {
+      CommitArgs c = {};
+      c.n_lens = ph.g.n_lens, c.B = ph.g.B, c.inc = ph.g.commit_inc;
+      for (int q = 0; q < c.n_lens; ++q) c.lens[q] = ph.g.lens[q];
+      SS_LAUNCH_KERNEL(commit_rows, dim3(1), dim3(32), 0, st, c);
+      SS_HIP(hipGetLastError());
+      return SS_OK;
+    }
   }
   SS_FAIL(SS_EINVAL, "unknown phase kind %d", ph.kind);
 }
 
-static ss_status enqueue_decode(Shard *const *group, int n_group, const int32_t *tokens_in, int B, float *logits,
-                                int32_t *next_tokens, hipStream_t st, int stop_after_layer) {
+static ss_status enqueue_decode(Shard *const *group, int n_group, const int32_t *tokens_in, const float *hidden_in, int B,
+                                float *hidden_out, float *logits, int32_t *next_tokens, hipStream_t st,
+                                int stop_after_layer) {
   std::vector<Phase> plan;
-  build_decode_plan(group, n_group, tokens_in, B, logits, next_tokens, stop_after_layer, &plan);
+  build_decode_plan(group, n_group, tokens_in, hidden_in, B, hidden_out, logits, next_tokens, stop_after_layer, &plan);
   for (const Phase &ph : plan) SS_TRY(launch_phase(group[0], ph, st));
   if (stop_after_layer >= 0)
     SS_FAIL(SS_EINTR, "decode step interrupted after layer %d; nothing committed", stop_after_layer);
@@ -347,24 +382,26 @@ void destroy_graphs(Shard *sh) {
   sh->free_events.clear();
 }
 
-ss_status run_decode_step(Shard *const *group, int n_group, const int32_t *tokens_in, int B, float *logits,
-                          int32_t *next_tokens, hipStream_t st, int stop_after_layer) {
+ss_status run_decode_step(Shard *const *group, int n_group, const int32_t *tokens_in, const float *hidden_in, int B,
+                          float *hidden_out, float *logits, int32_t *next_tokens, hipStream_t st,
+                          int stop_after_layer) {
   Shard *g0 = group[0];
   GraphKey key;
   key.B = B;
-  key.ptrs = {tokens_in, logits, next_tokens, (const void *)st};
+  key.ptrs = {tokens_in, hidden_in, hidden_out, logits, next_tokens, (const void *)st};
   for (int i = 0; i < n_group; ++i) key.ptrs.push_back(group[i]);
   const bool plain = !g0->timing && stop_after_layer < 0;
   // the NULL stream cannot be captured, and a stream the caller is capturing is left to the caller
   hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
   if (st) SS_HIP(hipStreamIsCapturing(st, &cs));
   const bool graph = g0->use_graph && plain && st != nullptr && cs == hipStreamCaptureStatusNone;
-  if (!graph) return enqueue_decode(group, n_group, tokens_in, B, logits, next_tokens, st, stop_after_layer);
+  if (!graph)
+    return enqueue_decode(group, n_group, tokens_in, hidden_in, B, hidden_out, logits, next_tokens, st, stop_after_layer);
   auto it = g0->graphs.find(key);
   if (it == g0->graphs.end()) {
     hipGraph_t gr = nullptr;
     SS_HIP(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
-    ss_status rc = enqueue_decode(group, n_group, tokens_in, B, logits, next_tokens, st, -1);
+    ss_status rc = enqueue_decode(group, n_group, tokens_in, hidden_in, B, hidden_out, logits, next_tokens, st, -1);
     hipError_t e = hipStreamEndCapture(st, &gr);
     if (rc != SS_OK) {
       if (gr) (void)hipGraphDestroy(gr);
@@ -385,8 +422,8 @@ ss_status run_decode_step(Shard *const *group, int n_group, const int32_t *token
 // ---------------------------------------------------------------------------
 // the initial phase
 // ---------------------------------------------------------------------------
-ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, int B, int S, float *logits,
-                      int32_t *next_tokens, hipStream_t st) {
+ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, const float *hidden_in, int B, int S,
+                      float *hidden_out, float *logits, int32_t *next_tokens, hipStream_t st) {
   Shard *g0 = group[0];
   const Layout &L0 = g0->L;
   const ss_model_desc &m = g0->m;
@@ -400,7 +437,7 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, i
   float *x = (float *)(g0->ws + L0.ws_x);
   void *abuf = g0->ws + L0.ws_a;
   {
-    EmbedArgs e{tokens, g0->wte, g0->wpe, nullptr, S, x, d, L0.V, nullptr, nullptr, nullptr};
+    EmbedArgs e{hidden_in, tokens, g0->wte, g0->wpe, nullptr, S, x, d, L0.V, nullptr, nullptr, nullptr};
     if (dt == SS_DTYPE_BF16) hipLaunchKernelGGL(embed_rows<bf16_t>, dim3(T_live), dim3(256), 0, st, e);
     else hipLaunchKernelGGL(embed_rows<float>, dim3(T_live), dim3(256), 0, st, e);
     SS_HIP(hipGetLastError());
@@ -467,6 +504,15 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, i
       SS_TRY(launch_tile_gemm(dt, EPI_RESID, a, st));
     }
   }
+  if (hidden_out) {  // a stage that hands its hidden states on: copy them out, then commit
+    SS_HIP(hipMemcpyAsync(hidden_out, x, (size_t)T_live * d * 4, hipMemcpyDeviceToDevice, st));
+    CommitArgs c = {};
+    c.n_lens = n_group, c.B = B, c.inc = S;
+    for (int i = 0; i < n_group; ++i) c.lens[i] = group[i]->d_len;
+    hipLaunchKernelGGL(commit_rows, dim3(1), dim3(32), 0, st, c);
+    SS_HIP(hipGetLastError());
+    return SS_OK;
+  }
   float *xd = (float *)(g0->ws + L0.ws_xd);
   void *ad = g0->ws + L0.ws_ad;
   float *statd = (float *)(g0->ws + L0.ws_statd);
@@ -483,10 +529,18 @@ using namespace ss;
 
 extern "C" {
 
-ss_status ss_prefill(ss_shard *const *group_, int32_t n_group, const int32_t *tokens, int32_t B, int32_t S_in,
-                     float *logits, int32_t *next_tokens, void *hip_stream) {
+static ss_status check_stage_io(const void *tokens, const void *hidden_in, const void *hidden_out, const void *logits,
+                                const void *next_tokens) {
+  if ((tokens != nullptr) == (hidden_in != nullptr)) SS_FAIL(SS_EINVAL, "give exactly one of tokens and hidden_in");
+  if (hidden_out && (logits || next_tokens)) SS_FAIL(SS_EINVAL, "a stage with hidden_out produces no logits or tokens");
+  return SS_OK;
+}
+
+ss_status ss_stage_prefill(ss_shard *const *group_, int32_t n_group, const int32_t *tokens, const float *hidden_in,
+                           int32_t B, int32_t S_in, float *hidden_out, float *logits, int32_t *next_tokens,
+                           void *hip_stream) {
   Shard *const *group = (Shard *const *)group_;
-  if (!tokens) SS_FAIL(SS_EINVAL, "tokens is NULL");
+  SS_TRY(check_stage_io(tokens, hidden_in, hidden_out, logits, next_tokens));
   SS_TRY(check_group(group, n_group, B));
   if (S_in < 1) SS_FAIL(SS_EINVAL, "S_in must be positive");
   for (int i = 0; i < n_group; ++i) {
@@ -494,10 +548,16 @@ ss_status ss_prefill(ss_shard *const *group_, int32_t n_group, const int32_t *to
     for (int b = 0; b < B; ++b)
       if (group[i]->h_len[b] != 0) SS_FAIL(SS_ESTATE, "row %d of group[%d] already holds %d tokens", b, i, group[i]->h_len[b]);
   }
-  SS_TRY(run_prefill(group, n_group, tokens, B, S_in, logits, next_tokens, (hipStream_t)hip_stream));
+  SS_TRY(run_prefill(group, n_group, tokens, hidden_in, B, S_in, hidden_out, logits, next_tokens, (hipStream_t)hip_stream));
   for (int i = 0; i < n_group; ++i)
     for (int b = 0; b < B; ++b) group[i]->h_len[b] = S_in;
   return SS_OK;
+}
+
+ss_status ss_prefill(ss_shard *const *group_, int32_t n_group, const int32_t *tokens, int32_t B, int32_t S_in,
+                     float *logits, int32_t *next_tokens, void *hip_stream) {
+  if (!tokens) SS_FAIL(SS_EINVAL, "tokens is NULL");
+  return ss_stage_prefill(group_, n_group, tokens, nullptr, B, S_in, nullptr, logits, next_tokens, hip_stream);
 }
 
 // Host-only check aid: the phase table of one decode step for a shard of the given shape whose
@@ -516,7 +576,7 @@ int32_t ss_debug_plan(const ss_model_desc *desc, const ss_slice *slice, int32_t 
   bind_pointers(&sh);
   Shard *group[1] = {&sh};
   std::vector<Phase> plan;
-  build_decode_plan(group, 1, (const int32_t *)8, B, (float *)16, (int32_t *)24, -1, &plan);
+  build_decode_plan(group, 1, (const int32_t *)8, nullptr, B, nullptr, (float *)16, (int32_t *)24, -1, &plan);
   if (out_total) *out_total = L.total;
   if (out_sizeof_phase) *out_sizeof_phase = sizeof(Phase);
   const int n = (int)plan.size();
@@ -546,10 +606,10 @@ ss_status ss_kernel_timing_read(ss_shard *shard, double ms[8], int64_t count[8],
   return SS_OK;
 }
 
-ss_status ss_decode_step(ss_shard *const *group_, int32_t n_group, const int32_t *tokens_in, int32_t B, float *logits,
-                         int32_t *next_tokens, void *hip_stream) {
+ss_status ss_stage_decode_step(ss_shard *const *group_, int32_t n_group, const int32_t *tokens_in, const float *hidden_in,
+                               int32_t B, float *hidden_out, float *logits, int32_t *next_tokens, void *hip_stream) {
   Shard *const *group = (Shard *const *)group_;
-  if (!tokens_in) SS_FAIL(SS_EINVAL, "tokens_in is NULL");
+  SS_TRY(check_stage_io(tokens_in, hidden_in, hidden_out, logits, next_tokens));
   SS_TRY(check_group(group, n_group, B));
   for (int b = 0; b < B; ++b) {
     const int n = group[0]->h_len[b];
@@ -561,11 +621,18 @@ ss_status ss_decode_step(ss_shard *const *group_, int32_t n_group, const int32_t
   }
   int stop = -1;
   for (int i = 0; i < n_group; ++i) stop = std::max(stop, group[i]->interrupt_after);
-  ss_status rc = run_decode_step(group, n_group, tokens_in, B, logits, next_tokens, (hipStream_t)hip_stream, stop);
+  ss_status rc = run_decode_step(group, n_group, tokens_in, hidden_in, B, hidden_out, logits, next_tokens,
+                                 (hipStream_t)hip_stream, stop);
   if (rc != SS_OK) return rc;  // SS_EINTR: nothing committed
   for (int i = 0; i < n_group; ++i)
     for (int b = 0; b < B; ++b) group[i]->h_len[b] += 1;
   return SS_OK;
+}
+
+ss_status ss_decode_step(ss_shard *const *group_, int32_t n_group, const int32_t *tokens_in, int32_t B, float *logits,
+                         int32_t *next_tokens, void *hip_stream) {
+  if (!tokens_in) SS_FAIL(SS_EINVAL, "tokens_in is NULL");
+  return ss_stage_decode_step(group_, n_group, tokens_in, nullptr, B, nullptr, logits, next_tokens, hip_stream);
 }
 
 }  // extern "C"

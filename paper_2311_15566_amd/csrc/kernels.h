@@ -101,8 +101,9 @@ ss_status launch_decode_attn(int dtype, const DecodeAttnArgs &a, hipStream_t st)
 ss_status check_decode_attn(const DecodeAttnArgs &a);
 
 // One phase of the decode step = one kernel launch.
-enum PhaseKind { PH_EMBED = 0, PH_QKV = 1, PH_ATTN = 2, PH_RESID = 3, PH_FFN_UP = 4, PH_LM_HEAD = 5 };
+enum PhaseKind { PH_EMBED = 0, PH_QKV = 1, PH_ATTN = 2, PH_RESID = 3, PH_FFN_UP = 4, PH_LM_HEAD = 5, PH_COMMIT = 6 };
 struct EmbedArgs {
+  const float *hidden;    // [rows][d] float32: the previous pipeline stage's output, in place of a token lookup; or NULL
   const int32_t *tokens;  // [rows]
   const void *wte, *wpe;  // [V][d], [max_pos][d] or NULL
   const int32_t *lens;    // decode: position = committed length; NULL: position = row % S
@@ -120,7 +121,7 @@ struct Phase {
   int gx, gy;    // blocks: (rows, 1), (tile pairs, 1) or (batch*heads, splits)
   int shard;     // index of the shard in the group that owns the phase's scratch
   EmbedArgs e;
-  StreamGemmArgs g;
+  StreamGemmArgs g;   // PH_COMMIT (a stage that hands on hidden states) uses B, lens, n_lens, commit_inc only
   DecodeAttnArgs at;
 };
 

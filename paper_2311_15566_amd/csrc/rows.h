@@ -50,25 +50,30 @@ __device__ __forceinline__ void store_piece(void *base, int row, int k, int k_bl
   }
 }
 
-// x[r] = wte[token] (+ wpe[position]) with 16-byte loads, the row held in registers.  With
+// x[r] = wte[token] (+ wpe[position]) with 16-byte loads (or the previous stage's hidden row).  With
 // a.act_out set (decode step) also the first GEMM's operand x * gamma and the row's (sum, sum of
 // squares).  d <= 16384.
 template <typename T>
 __device__ __forceinline__ void embed_row_block(const EmbedArgs &a, const int r, float *scratch) {
   constexpr int PL = Elem<T>::kPerLane, FK = Elem<T>::kFragK, MAXV = 64 / PL;
-  int tok = a.tokens[r];
+  int tok = a.hidden ? 0 : a.tokens[r];
   tok = min(max(tok, 0), a.V - 1);
   const int pos = a.lens ? a.lens[r] : (r % a.S);
   const int nvec = a.d / PL;
   const u32x4 *te = (const u32x4 *)((const T *)a.wte + (size_t)tok * a.d);
-  const u32x4 *pe = a.wpe ? (const u32x4 *)((const T *)a.wpe + (size_t)pos * a.d) : nullptr;
+  const u32x4 *pe = (a.wpe && !a.hidden) ? (const u32x4 *)((const T *)a.wpe + (size_t)pos * a.d) : nullptr;
   float s1 = 0.f, s2 = 0.f;
 #pragma unroll
   for (int i = 0; i < MAXV; ++i) {
     const int v = threadIdx.x + i * 256;
     if (v < nvec) {
       float vals[PL];
-      widen16<T>(te[v], vals);
+      if (a.hidden) {
+#pragma unroll
+        for (int e = 0; e < PL; ++e) vals[e] = a.hidden[(size_t)r * a.d + (size_t)v * PL + e];
+      } else {
+        widen16<T>(te[v], vals);
+      }
       if (pe) {
         float p[PL];
         widen16<T>(pe[v], p);

@@ -91,10 +91,11 @@ ss_status validate_desc(const ss_model_desc &m, const ss_slice &s, int max_batch
 void bind_pointers(Shard *sh);  // every device pointer of the shard from base + layout
 
 // decode.hip
-ss_status run_decode_step(Shard *const *group, int n_group, const int32_t *tokens_in, int B, float *logits,
-                          int32_t *next_tokens, hipStream_t st, int stop_after_layer);
-ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, int B, int S_in, float *logits,
-                      int32_t *next_tokens, hipStream_t st);
+ss_status run_decode_step(Shard *const *group, int n_group, const int32_t *tokens_in, const float *hidden_in, int B,
+                          float *hidden_out, float *logits, int32_t *next_tokens, hipStream_t st,
+                          int stop_after_layer);
+ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, const float *hidden_in, int B, int S_in,
+                      float *hidden_out, float *logits, int32_t *next_tokens, hipStream_t st);
 void destroy_graphs(Shard *sh);
 
 }  // namespace ss

@@ -238,6 +238,131 @@ def test_launch_modes_agree(ss, side_stream, name, kw):
             assert np.array_equal(bits(a), bits(b))
 
 
+@pytest.mark.parametrize("name,dtype,kw,cuts,group_m", [
+    ("tiny_gpt", "f32", dict(layers=5, batch=3, s_in=20, steps=4), [0, 2, 3, 5], 1),
+    ("gpt20b_m4", "bf16", dict(layers=4, batch=6, s_in=60, steps=4, head_dim=128, n_heads=4, d_model=512), [0, 1, 4], 1),
+    ("llama30b_m2", "bf16", dict(layers=4, batch=17, s_in=40, steps=3, head_dim=128, n_heads=4, d_model=512), [0, 3, 4], 2),
+])
+def test_pipeline_stages(ss, side_stream, name, dtype, kw, cuts, group_m):
+    """Shards that hold consecutive layer intervals, chained through hidden states (each stage a
+    group of `group_m` tensor-parallel shards), against the oracle of the undivided model."""
+    import torch
+    w = scaled(name, dtype, M=1, m=0, **kw)
+    bf16 = dtype == "bf16"
+    desc, V, d, B, S = w.desc, w.desc["vocab"], w.desc["d_model"], w.batch, w.s_in
+    full = tp_slice(desc, 0, desc["n_layers"], 0, 1)
+    W = make_weights(desc, full, w.seed)
+    toks = make_tokens(w.seed, B, S, V)
+    ora = D.OracleShard(desc, full, W, B, w.s_max)
+    stages = [[ss.Shard(desc, tp_slice(desc, a, b, m, group_m), W, B, w.s_max) for m in range(group_m)]
+              for a, b in zip(cuts, cuts[1:])]
+    logits = torch.empty(B, V, dtype=torch.float32, device="cuda")
+    nxt = torch.empty(B, dtype=torch.int32, device="cuda")
+    hid = [torch.empty(B * S, d, dtype=torch.float32, device="cuda") for _ in stages[:-1]]
+    ref = D.prefill_matrix([ora], toks)
+    for i, g in enumerate(stages):
+        first, last = i == 0, i == len(stages) - 1
+        ss.stage_prefill(g, B, S, tokens=dev(toks) if first else None, hidden_in=None if first else hid[i - 1],
+                         hidden_out=None if last else hid[i], logits=logits if last else None,
+                         next_tokens=nxt if last else None)
+    check_logits(logits.cpu().numpy(), ref, bf16, "prefill")
+    check_ids(nxt.cpu().numpy(), ref, "prefill")
+    hid1 = [torch.empty(B, d, dtype=torch.float32, device="cuda") for _ in stages[:-1]]
+    for step in range(w.steps):
+        tok = D.greedy(ref)
+        ref = D.decode_step([ora], tok)
+        for i, g in enumerate(stages):
+            first, last = i == 0, i == len(stages) - 1
+            ss.stage_decode_step(g, B, tokens_in=dev(tok) if first else None, hidden_in=None if first else hid1[i - 1],
+                                 hidden_out=None if last else hid1[i], logits=logits if last else None,
+                                 next_tokens=nxt if last else None)
+        check_logits(logits.cpu().numpy(), ref, bf16, f"step {step}")
+        check_ids(nxt.cpu().numpy(), ref, f"step {step}")
+    for g in stages:
+        for sh in g:
+            assert list(ss.committed_len(sh)) == [S + w.steps] * B
+    # argument errors: both or neither input, logits from a stage that hands hidden states on
+    g = stages[0]
+    for bad in (dict(), dict(tokens_in=dev(tok), hidden_in=hid1[0]), dict(tokens_in=dev(tok), hidden_out=hid1[0], logits=logits)):
+        with pytest.raises(ss.SpotShardError) as e:
+            ss.stage_decode_step(g, B, **bad)
+        assert e.value.status == 1
+    for g in stages:
+        for sh in g:
+            sh.destroy()
+
+
+@pytest.mark.parametrize("name,dtype", [("tiny_gpt", "f32"), ("llama30b_m2", "bf16")])
+def test_reparallelize_pipeline_2x2_to_3x1(ss, side_stream, name, dtype):
+    """The paper's own example of a configuration change (Section 3.3): (P=2, M=2) -> (P=3, M=1).
+    Every new stage shard collects the layer-and-head intersections it shares with the four old
+    shards (bit-exact against the index formula), then decoding goes on in the new layout and
+    matches the oracle of the undivided model, which never stopped."""
+    import torch
+    bf16 = dtype == "bf16"
+    w = scaled(name, dtype, M=1, m=0, layers=6, n_heads=4, head_dim=128, d_model=512, ffn=768, batch=5, s_in=50, steps=6)
+    desc, V, d, B, S = w.desc, w.desc["vocab"], w.desc["d_model"], w.batch, w.s_in
+    W = make_weights(desc, tp_slice(desc, 0, 6, 0, 1), w.seed)
+    toks = make_tokens(w.seed, B, S, V)
+    ora = D.OracleShard(desc, tp_slice(desc, 0, 6, 0, 1), W, B, w.s_max)
+    old = [[ss.Shard(desc, tp_slice(desc, 3 * p, 3 * p + 3, m, 2), W, B, w.s_max) for m in range(2)] for p in range(2)]
+    new = [[ss.Shard(desc, tp_slice(desc, 2 * p, 2 * p + 2, 0, 1), W, B, w.s_max)] for p in range(3)]
+    logits = torch.empty(B, V, dtype=torch.float32, device="cuda")
+    nxt = torch.empty(B, dtype=torch.int32, device="cuda")
+    hidS = [torch.empty(B * S, d, dtype=torch.float32, device="cuda") for _ in range(2)]
+    hid1 = [torch.empty(B, d, dtype=torch.float32, device="cuda") for _ in range(2)]
+
+    def run(stages, step_fn, hid, **first_kw):
+        for i, g in enumerate(stages):
+            first, last = i == 0, i == len(stages) - 1
+            kw = dict(first_kw) if first else dict(hidden_in=hid[i - 1])
+            kw.update(dict(logits=logits, next_tokens=nxt) if last else dict(hidden_out=hid[i]))
+            step_fn(g, **kw)
+
+    ref = D.prefill_matrix([ora], toks)
+    run(old, lambda g, **kw: ss.stage_prefill(g, B, S, **kw), hidS, tokens=dev(toks))
+    check_logits(logits.cpu().numpy(), ref, bf16, "prefill")
+    for step in range(3):
+        tok = D.greedy(ref)
+        ref = D.decode_step([ora], tok)
+        run(old, lambda g, **kw: ss.stage_decode_step(g, B, **kw), hid1, tokens_in=dev(tok))
+        check_logits(logits.cpu().numpy(), ref, bf16, f"old layout step {step}")
+    # re-partition: every (new, old) pair; pairs that share nothing only pass the lengths on
+    lens = [S + 3] * B
+    total = 0
+    for p, (dst,) in enumerate(new):
+        first = True
+        for stage in old:
+            for src in stage:
+                moved = ss.kv_repack(dst, src, list(range(B)), first_source=first)
+                first = False
+                l_lo, l_hi = max(dst.slice["layer_lo"], src.slice["layer_lo"]), min(dst.slice["layer_hi"], src.slice["layer_hi"])
+                h = src.slice["head_hi"] - src.slice["head_lo"]
+                esz = 2 if bf16 else 4
+                assert moved == max(0, l_hi - l_lo) * 2 * B * h * (S + 3) * 128 * esz
+                total += moved
+        assert list(ss.committed_len(dst)) == lens
+    assert total == sum(ss.device_kv_bytes(sh) for st in old for sh in st)      # nothing lost, nothing twice
+    # bit for bit: each new shard's cache is the old shards' caches cut the new way
+    np_dt = np.uint16 if bf16 else np.uint32
+    def dense(sh):
+        g = sh.geometry()
+        return canonical_to_array(bits(ss.kv_export(sh)), g["layers"], B, g["heads"], S + 3, 128, lens)
+    old_dense = np.concatenate([np.concatenate([dense(sh) for sh in st], axis=3) for st in old], axis=0)   # [6,2,B,4,n,Dh]
+    for p, (dst,) in enumerate(new):
+        assert np.array_equal(dense(dst), old_dense[2 * p:2 * p + 2])
+    # decoding goes on in the new layout
+    for step in range(3, 6):
+        tok = D.greedy(ref)
+        ref = D.decode_step([ora], tok)
+        run(new, lambda g, **kw: ss.stage_decode_step(g, B, **kw), hid1, tokens_in=dev(tok))
+        check_logits(logits.cpu().numpy(), ref, bf16, f"new layout step {step}")
+        check_ids(nxt.cpu().numpy(), ref, f"new layout step {step}")
+    for st in old + new:
+        for sh in st:
+            sh.destroy()
+
+
 def test_ragged_lengths_and_row_independence(ss):
     """Rows at different positions in one batch (imported cache), each row matches the oracle."""
     import torch

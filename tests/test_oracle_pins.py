@@ -120,6 +120,42 @@ def test_incremental_equals_full_recompute_every_position(arch):
 
 
 @pytest.mark.parametrize("arch", ARCHS)
+def test_pipeline_stages_compose_to_the_whole_model(arch):
+    """Section 2.2, inter-operator parallelism: stages of consecutive layers, each fed the hidden
+    states of the one before, compute what the whole model computes, and their caches are the
+    whole model's cache cut by layers (sequential, incremental and matrix forms)."""
+    w = small(arch, layers=5, batch=2)
+    W = make_weights(w.desc, w.slice, w.seed)
+    toks = make_tokens(w.seed, 2, 6, w.desc["vocab"])
+    nxt = make_tokens(w.seed + 1, 2, 3, w.desc["vocab"])
+    cuts = [0, 2, 3, 5]
+    whole = D.OracleShard(w.desc, w.slice, W, 2, 12)
+    stages = [D.OracleShard(w.desc, tp_slice(w.desc, a, b, 0, 1), W, 2, 12) for a, b in zip(cuts, cuts[1:])]
+    ref = D.prefill([whole], toks)
+    h = D.prefill([stages[0]], toks, hidden_out=True)
+    assert h.shape == (2, 6, w.desc["d_model"])
+    h = D.prefill([stages[1]], None, hidden_in=h, hidden_out=True)
+    got = D.prefill([stages[2]], None, hidden_in=h)
+    assert np.abs(got - ref).max() < 1e-12
+    for t in range(3):
+        ref = D.decode_step([whole], nxt[:, t])
+        h = D.decode_step([stages[0]], nxt[:, t], hidden_out=True)
+        h = D.decode_step([stages[1]], None, hidden_in=h, hidden_out=True)
+        got = D.decode_step([stages[2]], None, hidden_in=h)
+        assert np.abs(got - ref).max() < 1e-12
+    for st, (a, b) in zip(stages, zip(cuts, cuts[1:])):
+        assert list(st.n) == [9, 9]
+        assert np.array_equal(st.kv[:, :, :, :, :9], whole.kv[a:b, :, :, :, :9])
+    # a stage's hidden output is not the logits' input until the final norm: it differs from the
+    # whole model's last hidden state unless it IS the last stage
+    fresh = [D.OracleShard(w.desc, tp_slice(w.desc, a, b, 0, 1), W, 2, 12) for a, b in zip(cuts, cuts[1:])]
+    hm = D.forward_matrix([fresh[0]], toks[0], b=0, hidden_out=True)
+    hm = D.forward_matrix([fresh[1]], None, b=0, hidden_in=hm, hidden_out=True)
+    lm = D.forward_matrix([fresh[2]], None, b=0, hidden_in=hm)
+    assert np.abs(lm - D.forward_matrix([D.OracleShard(w.desc, w.slice, W, 2, 12)], toks[0])).max() < 1e-11
+
+
+@pytest.mark.parametrize("arch", ARCHS)
 def test_prefill_matrix_form_fills_the_same_cache(arch):
     w = small(arch)
     W, s1 = build(w)
