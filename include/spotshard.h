@@ -190,6 +190,14 @@ ss_status ss_debug_interrupt_after_layer(ss_shard *shard, int32_t layer);
  * kernels; 0: the kernels one by one.  Both give the same bits. */
 ss_status ss_set_graph_launch(ss_shard *shard, int32_t enabled);
 
+/* Test aid, process-wide: force the launch shape of the decode GEMMs built from now on (shards
+ * that have already replayed a step keep their captured graph): weight tiles per block (1 or 2;
+ * 0 = the library's choice) and, for more than 16 batch rows, whether the two batch tiles go to
+ * separate blocks (2) or not (1; 0 = the library's choice).  The library chooses per shape, by a
+ * rule or, on a shard's first step at a batch size, by timing the candidates on the device
+ * (SS_TUNE=0 in the environment keeps the rule); every shape gives the same bits. */
+ss_status ss_debug_force_gemm_shape(int32_t tiles_per_block, int32_t batch_split);
+
 /* Measurement aid: per-kernel-class timing of decode steps.  While enabled on group[0],
  * ss_decode_step launches kernel by kernel (no graph replay) and every launch records its own
  * begin and end on a pair of HIP events of the step's stream (the dispatch's timestamps).

@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     committed_len,
     decode_step,
     device_kv_bytes,
+    force_gemm_shape,
     kv_export,
     kv_import,
     kv_repack,

@@ -74,6 +74,7 @@ def _load():
     L.ss_set_graph_launch.argtypes = [vp, i32]
     L.ss_shard_geometry.argtypes = [vp, C.POINTER(i32)]
     L.ss_kernel_timing.argtypes = [vp, i32]
+    L.ss_debug_force_gemm_shape.argtypes = [i32, i32]
     L.ss_kernel_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), vp]
     return L
 
@@ -235,6 +236,11 @@ def kv_repack(dst, src, batch_map, first_source=True, stream=None) -> int:
     moved = C.c_uint64(0)
     _check(lib.ss_kv_repack(dst.handle, src.handle, bm, int(first_source), C.byref(moved), _stream(stream)))
     return moved.value
+
+
+def force_gemm_shape(tiles_per_block: int = 0, batch_split: int = 0):
+    """Test aid: force the decode GEMMs' launch shape for plans built from now on (0, 0 = library's choice)."""
+    _check(lib.ss_debug_force_gemm_shape(int(tiles_per_block), int(batch_split)))
 
 
 def device_kv_bytes(shard) -> int:

@@ -4,6 +4,8 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
+#include <tuple>
 
 #include "kernels.h"
 #include "rows.h"
@@ -159,10 +161,54 @@ static void attn_plan(const Layout &L, int B, int *rows_per_block, int *splits, 
 // ---------------------------------------------------------------------------
 // the decode step as a list of phases
 // ---------------------------------------------------------------------------
+// ---------------------------------------------------------------------------
+// Launch shape of a decode GEMM: weight tiles per block (pairs share the activation fragments,
+// single tiles give twice the blocks) and, past 16 batch rows, whether the two batch tiles go to
+// separate blocks.  Neither changes a single bit of the result (the order of every sum is the
+// same), so the choice is free: a rule of thumb until the shape has been timed on this device,
+// then the fastest of the candidates (tune_decode_gemms), kept process-wide per shape.
+// ---------------------------------------------------------------------------
+struct TuneKey {
+  int dtype, epi, row_tiles, k_blocks, B;
+  bool operator<(const TuneKey &o) const {
+    return std::tie(dtype, epi, row_tiles, k_blocks, B) < std::tie(o.dtype, o.epi, o.row_tiles, o.k_blocks, o.B);
+  }
+};
+struct TuneVal {
+  int nw, bt_split;
+};
+static std::map<TuneKey, TuneVal> g_tune;
+static std::mutex g_tune_mu;
+static TuneVal g_forced = {0, 0};  // test aid: 0 = not forced
+
+static std::vector<TuneVal> tune_candidates(int epi, int B) {
+  std::vector<TuneVal> c;
+  for (int nw = 2; nw >= 1; --nw) {
+    if (nw == 1 && (epi == EPI_SWIGLU || epi == EPI_LOGITS)) continue;  // gate/up pairs; the argmax buffers hold one entry per pair
+    for (int bt = 1; bt <= (B > 16 ? 2 : 1); ++bt) c.push_back(TuneVal{nw, bt});
+  }
+  return c;
+}
+static TuneVal tune_rule(int epi, int row_tiles, int B) {
+  const int pairs = ceil_div(row_tiles, 2);
+  TuneVal v;
+  v.bt_split = (B > 16 && pairs * 2 <= 256) ? 2 : 1;
+  v.nw = (epi == EPI_SWIGLU || epi == EPI_LOGITS || pairs * v.bt_split >= 128) ? 2 : 1;
+  return v;
+}
+static void shape_gemm(StreamGemmArgs &a, int dtype, int epi) {
+  TuneVal v = tune_rule(epi, a.row_tiles, a.B);
+  {
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    auto it = g_tune.find(TuneKey{dtype, epi, a.row_tiles, a.k_blocks, a.B});
+    if (it != g_tune.end()) v = it->second;
+    if (g_forced.nw && epi != EPI_SWIGLU && epi != EPI_LOGITS) v.nw = g_forced.nw;
+    if (g_forced.bt_split) v.bt_split = a.B > 16 ? g_forced.bt_split : 1;
+  }
+  a.nw = v.nw, a.bt_split = v.bt_split;
+  a.n_blocks = stream_gemm_blocks(epi, a);
+}
 static int pick_ks(int k_blocks) { return k_blocks >= 16 ? 8 : 4; }  // waves per block
-// weight tiles per block: pairs share the activation fragments; single tiles only where pairs
-// would leave half the compute units without a block
-static int pick_nw(int row_tiles) { return ceil_div(row_tiles, 2) < 128 ? 1 : 2; }
 
 // the final norm and the LM head over the rows in the decode buffers, greedy choice, commit
 static Phase lm_head_phase(Shard *const *group, int n_group, int B, int stat_groups, float *logits, int32_t *next_tokens,
@@ -173,7 +219,7 @@ static Phase lm_head_phase(Shard *const *group, int n_group, int B, int stat_gro
   ph.kind = PH_LM_HEAD;
   StreamGemmArgs &a = ph.g;
   a.w = g0->lm_head.ptr, a.row_tiles = g0->lm_head.row_tiles, a.k_blocks = g0->lm_head.k_blocks, a.B = B, a.N = L.V;
-  a.ks = pick_ks(a.k_blocks), a.nw = 2;
+  a.ks = pick_ks(a.k_blocks);
   a.act = g0->ws + L.ws_ad;
   a.stat_in = (const float *)(g0->ws + L.ws_statd), a.stat_groups = stat_groups, a.norm_dim = L.d;
   a.rms = g0->m.norm == SS_NORM_RMSNORM, a.eps = g0->m.norm_eps;
@@ -185,7 +231,8 @@ static Phase lm_head_phase(Shard *const *group, int n_group, int B, int stat_gro
   a.next_tokens = next_tokens;
   for (int i = 0; i < n_group; ++i) a.lens[i] = group[i]->d_len;
   a.n_lens = n_group, a.commit_inc = commit_inc;
-  ph.gx = stream_gemm_blocks(EPI_LOGITS, a), ph.gy = 1;
+  shape_gemm(a, g0->m.dtype, EPI_LOGITS);
+  ph.gx = a.n_blocks * a.bt_split, ph.gy = 1;
   return ph;
 }
 
@@ -227,7 +274,7 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
     Phase ph = {};
     ph.kind = PH_RESID, ph.shard = i;
     StreamGemmArgs &a = ph.g;
-    a.w = w.ptr, a.row_tiles = w.row_tiles, a.k_blocks = w.k_blocks, a.ks = pick_ks(a.k_blocks), a.nw = pick_nw(a.row_tiles), a.B = B, a.N = d;
+    a.w = w.ptr, a.row_tiles = w.row_tiles, a.k_blocks = w.k_blocks, a.ks = pick_ks(a.k_blocks), a.B = B, a.N = d;
     a.act = act;
     a.cb = i == 0 ? bias : nullptr;
     a.x_in = x, a.x_out = x;
@@ -235,7 +282,8 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
       if (x_final) a.x_out = x_final;  // the stage's output: no next GEMM in this shard
       else a.act_out = ad, a.out_k_blocks = d / FK, a.g_out = next_gamma, a.stat_out = statd;
     }
-    ph.gx = stream_gemm_blocks(EPI_RESID, a), ph.gy = 1;
+    shape_gemm(a, dt, EPI_RESID);
+    ph.gx = a.n_blocks * a.bt_split, ph.gy = 1;
     plan->push_back(ph);
   };
   for (int l = 0; l < L0.Ls; ++l) {
@@ -247,10 +295,11 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
       ph.kind = PH_QKV, ph.shard = i;
       StreamGemmArgs &a = ph.g;
       a.w = s->wqkv[l].ptr, a.row_tiles = s->wqkv[l].row_tiles, a.k_blocks = s->wqkv[l].k_blocks, a.B = B, a.N = L.qkv_n;
-      a.ks = pick_ks(a.k_blocks), a.nw = pick_nw(a.row_tiles);
+      a.ks = pick_ks(a.k_blocks);
       normed(a, s->wg_qkv[l], s->cb_qkv[l]);
       a.out_f32 = (float *)(s->ws + L.ws_qkvd), a.ld_out = L.qkv_n;
-      ph.gx = stream_gemm_blocks(EPI_F32, a), ph.gy = 1;
+      shape_gemm(a, dt, EPI_F32);
+      ph.gx = a.n_blocks * a.bt_split, ph.gy = 1;
       plan->push_back(ph);
     }
     for (int i = 0; i < n_group; ++i) {  // attention over the committed rows + append
@@ -281,10 +330,11 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
       ph.kind = PH_FFN_UP, ph.shard = i;
       StreamGemmArgs &a = ph.g;
       a.w = s->w1[l].ptr, a.row_tiles = s->w1[l].row_tiles, a.k_blocks = s->w1[l].k_blocks, a.B = B, a.N = L.Fs;
-      a.ks = pick_ks(a.k_blocks), a.nw = m.act == SS_ACT_SWIGLU ? 2 : pick_nw(a.row_tiles);
+      a.ks = pick_ks(a.k_blocks);
       normed(a, s->wg_1[l], s->cb_1[l]);
       a.act_out = s->ws + L.ws_ud, a.out_k_blocks = L.Fs / FK, a.act_kind = m.act;
-      ph.gx = stream_gemm_blocks(m.act == SS_ACT_SWIGLU ? EPI_SWIGLU : EPI_ACT, a), ph.gy = 1;
+      shape_gemm(a, dt, m.act == SS_ACT_SWIGLU ? EPI_SWIGLU : EPI_ACT);
+      ph.gx = a.n_blocks * a.bt_split, ph.gy = 1;
       plan->push_back(ph);
     }
     const float *next_gamma = l + 1 < L0.Ls ? g0->layers[l + 1].ln1_g : g0->lnf_g;
@@ -360,6 +410,79 @@ static ss_status launch_phase(Shard *g0, const Phase &ph, hipStream_t st) {
     }
   }
   SS_FAIL(SS_EINVAL, "unknown phase kind %d", ph.kind);
+}
+
+static int gemm_epilogue_of(const Shard *g0, int kind) {
+  switch (kind) {
+    case PH_QKV: return EPI_F32;
+    case PH_RESID: return EPI_RESID;
+    case PH_FFN_UP: return g0->m.act == SS_ACT_SWIGLU ? EPI_SWIGLU : EPI_ACT;
+    case PH_LM_HEAD: return EPI_LOGITS;
+  }
+  return -1;
+}
+
+// Time the candidate launch shapes of every decode GEMM shape of this group at batch B that has
+// not been timed in this process, on the real weights (one launch per layer in turn, so repeats do
+// not hit in the caches), and keep the fastest.  Runs on `st` before the step's own kernels and
+// synchronises; everything it overwrites (q|k|v, operand fragments, row sums, argmax partials,
+// the initial phase's scratch) is rewritten by the step before it is read; nothing is committed.
+static ss_status tune_decode_gemms(Shard *const *group, int n_group, int B, hipStream_t st) {
+  Shard *g0 = group[0];
+  const int dt = g0->m.dtype;
+  std::vector<Phase> plan;
+  build_decode_plan(group, n_group, (const int32_t *)g0->d_len, nullptr, B, nullptr, nullptr, nullptr, -1, &plan);
+  std::map<TuneKey, std::vector<const Phase *>> by_shape;
+  for (const Phase &ph : plan) {
+    const int epi = gemm_epilogue_of(g0, ph.kind);
+    if (epi < 0) continue;
+    const TuneKey key{dt, epi, ph.g.row_tiles, ph.g.k_blocks, B};
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    if (!g_tune.count(key)) by_shape[key].push_back(&ph);
+  }
+  if (by_shape.empty()) return SS_OK;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  SS_HIP(hipEventCreate(&e0));
+  SS_HIP(hipEventCreate(&e1));
+  ss_status rc = SS_OK;
+  for (auto &kv : by_shape) {
+    const TuneKey &key = kv.first;
+    const std::vector<const Phase *> &phs = kv.second;
+    const std::vector<TuneVal> cands = tune_candidates(key.epi, B);
+    TuneVal best = cands[0];
+    float best_ms = -1.f;
+    for (const TuneVal &c : cands) {
+      if (cands.size() == 1) break;
+      const int reps = 4;
+      size_t turn = 0;
+      for (int r = -1; r < reps && rc == SS_OK; ++r) {  // r = -1: an untimed first launch
+        if (r == 0 && hipEventRecord(e0, st) != hipSuccess) rc = SS_EHIP;
+        const Phase *ph = phs[turn++ % phs.size()];
+        const Shard *owner = group[ph->shard];
+        StreamGemmArgs g = ph->g;
+        g.nw = c.nw, g.bt_split = c.bt_split;
+        g.n_blocks = stream_gemm_blocks(key.epi, g);
+        if (key.epi == EPI_RESID) g.x_out = (float *)(owner->ws + owner->L.ws_x);  // leave the residual stream alone
+        if (key.epi == EPI_LOGITS) g.out_f32 = nullptr, g.next_tokens = nullptr, g.n_lens = 0;
+        rc = launch_stream_gemm(dt, key.epi, g, st);
+      }
+      if (rc != SS_OK) break;
+      float ms = 0.f;
+      if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+          hipEventElapsedTime(&ms, e0, e1) != hipSuccess) {
+        set_error("timing a decode GEMM shape failed");
+        rc = SS_EHIP;
+        break;
+      }
+      if (best_ms < 0.f || ms < best_ms) best_ms = ms, best = c;
+    }
+    if (rc != SS_OK) break;
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    g_tune[key] = best;
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  return rc;
 }
 
 static ss_status enqueue_decode(Shard *const *group, int n_group, const int32_t *tokens_in, const float *hidden_in, int B,
@@ -585,6 +708,14 @@ int32_t ss_debug_plan(const ss_model_desc *desc, const ss_slice *slice, int32_t 
   return n;
 }
 
+ss_status ss_debug_force_gemm_shape(int32_t tiles_per_block, int32_t batch_split) {
+  if (tiles_per_block < 0 || tiles_per_block > 2 || batch_split < 0 || batch_split > 2)
+    SS_FAIL(SS_EINVAL, "launch shape (%d, %d)", tiles_per_block, batch_split);
+  std::lock_guard<std::mutex> lock(g_tune_mu);
+  g_forced = TuneVal{tiles_per_block, batch_split};
+  return SS_OK;
+}
+
 ss_status ss_kernel_timing(ss_shard *shard, int32_t enabled) {
   if (!shard) SS_FAIL(SS_EINVAL, "NULL shard");
   ((Shard *)shard)->timing = enabled != 0;
@@ -621,6 +752,19 @@ ss_status ss_stage_decode_step(ss_shard *const *group_, int32_t n_group, const i
   }
   int stop = -1;
   for (int i = 0; i < n_group; ++i) stop = std::max(stop, group[i]->interrupt_after);
+  // first step of these shards at this batch size: time the GEMM launch shapes (not while the
+  // caller is capturing the stream, and not with SS_TUNE=0 in the environment)
+  static const bool tune_on = !(getenv("SS_TUNE") && atoi(getenv("SS_TUNE")) == 0);
+  bool tuned = true;
+  for (int i = 0; i < n_group; ++i) tuned = tuned && group[i]->tuned_B.count(B);
+  if (!tuned && tune_on) {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hip_stream) SS_HIP(hipStreamIsCapturing((hipStream_t)hip_stream, &cs));
+    if (cs == hipStreamCaptureStatusNone) {
+      SS_TRY(tune_decode_gemms(group, n_group, B, (hipStream_t)hip_stream));
+      for (int i = 0; i < n_group; ++i) group[i]->tuned_B.insert(B);
+    }
+  }
   ss_status rc = run_decode_step(group, n_group, tokens_in, hidden_in, B, hidden_out, logits, next_tokens,
                                  (hipStream_t)hip_stream, stop);
   if (rc != SS_OK) return rc;  // SS_EINTR: nothing committed

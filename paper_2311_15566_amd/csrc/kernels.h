@@ -24,6 +24,8 @@ struct StreamGemmArgs {
   int k_blocks;
   int ks;               // waves per block = slices of K (4 or 8)
   int nw;               // weight tiles per block: 2 (always for SwiGLU pairs) or 1
+  int n_blocks;         // tile-pair blocks = ceil(row_tiles / nw)
+  int bt_split;         // 1, or 2: the two 16-row batch tiles of B > 16 go to separate blocks
   int B;                // live batch rows
   int N;                // logical output features (for masking)
   const void *act;      // operand fragments [B tiles][k_blocks][parts]

@@ -73,6 +73,7 @@ struct Shard {
   int interrupt_after = -1;
   bool use_graph = true;
   std::map<GraphKey, hipGraphExec_t> graphs;
+  std::set<int> tuned_B;  // batch sizes whose decode GEMM launch shapes have been timed
   // per-kernel-class event timing (measurement aid)
   bool timing = false;
   struct TimedLaunch { int cls; hipEvent_t e0, e1; };

@@ -16,7 +16,7 @@ constexpr int U = 2;      // fragments per register batch; two batches in flight
 template <int NB, int KSM, int NW>
 struct GemmShared {
   f32x4 red[KSM][NW][NB][64];    // per K slice: the wave's sums [weight tile][batch tile][lane]
-  float stat[KSM * 128];         // row-sum slices [slice][row][2], slices * rows = threads of the block
+  float stat[KSM * 128 * NB];    // row-sum slices [slice][batch tile][row][2], slices * rows = threads of the block
   float lg_v[NW][NB * 16];       // logits: best value / index per weight tile and row
   int lg_i[NW][NB * 16];
   float fin_v[KSM * 64];         // [slice][row]
@@ -37,7 +37,20 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
   constexpr int NWE = GLU ? 2 : 1;         // weight tiles one epilogue wave combines
   __shared__ GemmShared<NB, KSM, NW> sh;
   const int tid = threadIdx.x, lane = tid & 63, ks = tid >> 6, KS = blockDim.x >> 6;
-  const int tile0 = blockIdx.x * NW;
+  // Block -> (tile-pair block, batch tile).  With a.bt_split == 2 (more than 16 batch rows, NB == 1)
+  // the two 16-row batch tiles of a tile pair go to two blocks; workgroups go to the 8 XCDs
+  // round-robin, so the two are numbered 8 apart: same XCD, same L2, the weights come from HBM once.
+  int blk = blockIdx.x, bt = 0;
+  if (a.bt_split == 2) {
+    const int pid = blockIdx.x, nfull = (a.n_blocks / 8) * 16;
+    if (pid < nfull) {
+      blk = (pid / 16) * 8 + (pid % 8), bt = (pid % 16) / 8;
+    } else {
+      blk = (a.n_blocks / 8) * 8 + (pid - nfull) / 2, bt = (pid - nfull) % 2;
+    }
+  }
+  const int row0 = bt * 16;       // first batch row of this block
+  const int tile0 = blk * NW;
   const int per = (a.k_blocks + KS - 1) / KS;
   const int k0 = ks * per, k1 = min(a.k_blocks, k0 + per);
   const int r = lane & 15, q4 = (lane >> 4) * 4;
@@ -53,16 +66,17 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
   const u32x4 *ap[NB];
 #pragma unroll
   for (int t = 0; t < NB; ++t) {
-    row_ok[t] = t * 16 + r < a.B;
-    ap[t] = (const u32x4 *)a.act + (size_t)t * a.k_blocks * AP * 64 + lane;
+    row_ok[t] = row0 + t * 16 + r < a.B;
+    ap[t] = (const u32x4 *)a.act + (size_t)(bt + t) * a.k_blocks * AP * 64 + lane;
   }
 
   // what the epilogue needs from memory is requested first, so that it has long arrived
   const bool is_epi = ks < NEP;
   const int je = GLU ? 0 : ks % NW, te = GLU ? ks : ks / NW;
-  const int b = te * 16 + r;                                        // this lane's batch row
+  const int bl = te * 16 + r;                                       // this lane's batch row within the block
+  const int b = row0 + bl;                                          // ... and in the batch
   const int wrow = (tile0 + je) * 16 + q4;                          // first of its four weight rows
-  const int n0 = GLU ? blockIdx.x * 16 + q4 : wrow;                 // first of its four outputs
+  const int n0 = GLU ? blk * 16 + q4 : wrow;                        // first of its four outputs
   const bool tile_e_ok = tile0 + je < a.row_tiles;
   const bool epi_live = is_epi && tile_e_ok && b < a.B && n0 < a.N;
   f32x4 e_wg[NWE], e_cb[NWE], e_x = {0.f, 0.f, 0.f, 0.f}, e_g = {1.f, 1.f, 1.f, 1.f};
@@ -121,17 +135,23 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
   // have long arrived: nothing waits for them now.
   constexpr bool NORMED = EPI != EPI_RESID;
   constexpr int SR = NORMED ? (GLU ? 2 : 4) : 0;
-  const int rbl = a.B <= 8 ? 8 : (a.B <= 16 ? 16 : 32);  // rows padded to a power of two
+  // (the split of the partials over threads depends on the batch size only, so the sums come out
+  // the same whatever the launch shape: 8 or 16 rows a slice, a thread takes that row of every
+  // batch tile of the block)
+  const int rbl = a.B <= 8 ? 8 : 16;
   const int nsl = blockDim.x / rbl;
-  const int st_slice = tid / rbl, st_row = tid % rbl;
-  const f32x4 *st_p = (const f32x4 *)a.stat_in + st_row;
-  f32x4 st_v[SR > 0 ? SR : 1];
+  const int st_slice = tid / rbl, st_loc = tid % rbl;
+  const f32x4 *st_p = (const f32x4 *)a.stat_in + row0 + st_loc;
+  f32x4 st_v[NB][SR > 0 ? SR : 1];
   if (NORMED) {
 #pragma unroll
-    for (int i = 0; i < SR; ++i) {
-      const int g = st_slice + i * nsl;
-      st_v[i] = (st_row < a.B && g < a.stat_groups) ? st_p[(size_t)g * 32] : f32x4{0.f, 0.f, 0.f, 0.f};
-    }
+    for (int t = 0; t < NB; ++t)
+#pragma unroll
+      for (int i = 0; i < SR; ++i) {
+        const int g = st_slice + i * nsl;
+        st_v[t][i] = (row0 + t * 16 + st_loc < a.B && g < a.stat_groups) ? st_p[(size_t)g * 32 + t * 16]
+                                                                        : f32x4{0.f, 0.f, 0.f, 0.f};
+      }
   }
 
   for (int kb = k0; kb < k1; kb += 2 * U) {
@@ -142,12 +162,16 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
   }
 
   if (NORMED && a.stat_groups > 0) {
-    f32x4 sv = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int i = 0; i < SR; ++i) sv += st_v[i];
-    if (st_row < a.B)
-      for (int g = st_slice + SR * nsl; g < a.stat_groups; g += nsl) sv += st_p[(size_t)g * 32];  // the rest, if any
-    sh.stat[(st_slice * rbl + st_row) * 2] = sv[0] + sv[2], sh.stat[(st_slice * rbl + st_row) * 2 + 1] = sv[1] + sv[3];
+    for (int t = 0; t < NB; ++t) {
+      f32x4 sv = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int i = 0; i < SR; ++i) sv += st_v[t][i];
+      if (row0 + t * 16 + st_loc < a.B)
+        for (int g = st_slice + SR * nsl; g < a.stat_groups; g += nsl) sv += st_p[(size_t)g * 32 + t * 16];  // the rest, if any
+      float *dst = &sh.stat[((st_slice * NB + t) * rbl + st_loc) * 2];
+      dst[0] = sv[0] + sv[2], dst[1] = sv[1] + sv[3];
+    }
   }
 #pragma unroll
   for (int t = 0; t < NB; ++t)
@@ -168,8 +192,11 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
     float mean = 0.f, rstd = 1.f;
     if (NORMED && a.stat_groups > 0) {
       float u1 = 0.f, u2 = 0.f;
-      const int br = b < rbl ? b : 0;  // rows past the batch are masked later
-      for (int s = 0; s < nsl; ++s) u1 += sh.stat[(s * rbl + br) * 2], u2 += sh.stat[(s * rbl + br) * 2 + 1];
+      const int br = r < rbl ? r : 0;  // rows past the batch are masked later
+      for (int s = 0; s < nsl; ++s) {
+        const float *src = &sh.stat[((s * NB + te) * rbl + br) * 2];
+        u1 += src[0], u2 += src[1];
+      }
       const float inv = 1.0f / (float)a.norm_dim;
       const float ms = u2 * inv;
       if (a.rms) {
@@ -233,7 +260,7 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
         const int oi = __shfl_xor(bi, off);
         if (ov > bv || (ov == bv && oi < bi)) bv = ov, bi = oi;
       }
-      if (lane < 16) sh.lg_v[je][b] = bv, sh.lg_i[je][b] = bi;
+      if (lane < 16) sh.lg_v[je][bl] = bv, sh.lg_i[je][bl] = bi;
     }
   }
   if (EPI != EPI_LOGITS) return;
@@ -248,30 +275,31 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
       const int oi = sh.lg_i[j][tid];
       if (ov > bv || (ov == bv && oi < bi)) bv = ov, bi = oi;
     }
-    st_dev(&a.am_val[(size_t)blockIdx.x * 32 + tid], bv);
-    st_dev(&a.am_idx[(size_t)blockIdx.x * 32 + tid], bi);
+    st_dev(&a.am_val[(size_t)blk * 32 + row0 + tid], bv);
+    st_dev(&a.am_idx[(size_t)blk * 32 + row0 + tid], bi);
   }
   if (!arrive_last(a.counter, (int)gridDim.x, &sh.flag)) return;
   {
     // thread (slice, row) scans blocks slice, slice + n, ...; ties go to the lowest index whatever
     // the order, so the merge does not depend on scheduling
-    const int row = tid % rbl, slice = tid / rbl, nslice = blockDim.x / rbl;
+    const int rbf = a.B <= 8 ? 8 : (a.B <= 16 ? 16 : 32);  // all rows of the batch now
+    const int row = tid % rbf, slice = tid / rbf, nslice = blockDim.x / rbf;
     bv = -INFINITY, bi = INT_MAX;
     if (row < a.B) {
 #pragma unroll 8
-      for (int g = slice; g < (int)gridDim.x; g += nslice) {
+      for (int g = slice; g < a.n_blocks; g += nslice) {
         const float ov = ld_dev(&a.am_val[(size_t)g * 32 + row]);
         const int oi = ld_dev(&a.am_idx[(size_t)g * 32 + row]);
         if (ov > bv || (ov == bv && oi < bi)) bv = ov, bi = oi;
       }
     }
-    sh.fin_v[slice * rbl + row] = bv, sh.fin_i[slice * rbl + row] = bi;
+    sh.fin_v[slice * rbf + row] = bv, sh.fin_i[slice * rbf + row] = bi;
     __syncthreads();
     if (tid < a.B) {
       bv = sh.fin_v[tid], bi = sh.fin_i[tid];
       for (int q = 1; q < nslice; ++q) {
-        const float ov = sh.fin_v[q * rbl + tid];
-        const int oi = sh.fin_i[q * rbl + tid];
+        const float ov = sh.fin_v[q * rbf + tid];
+        const int oi = sh.fin_i[q * rbf + tid];
         if (ov > bv || (ov == bv && oi < bi)) bv = ov, bi = oi;
       }
       if (a.next_tokens) a.next_tokens[tid] = bi;
@@ -288,6 +316,8 @@ int stream_gemm_blocks(int epi, const StreamGemmArgs &a) {
 ss_status check_stream_gemm(int dtype, int epi, const StreamGemmArgs &a) {
   if (dtype != SS_DTYPE_BF16 && dtype != SS_DTYPE_F32) SS_FAIL(SS_EINVAL, "decode GEMM: dtype %d", dtype);
   if (a.B < 1 || a.B > 32) SS_FAIL(SS_EINVAL, "decode GEMM: batch %d", a.B);
+  if (a.n_blocks != stream_gemm_blocks(epi, a) || (a.bt_split != 1 && !(a.bt_split == 2 && a.B > 16)))
+    SS_FAIL(SS_EINVAL, "decode GEMM: bad block count / batch split");
   if (a.nw != 1 && a.nw != 2) SS_FAIL(SS_EINVAL, "decode GEMM: %d weight tiles per block", a.nw);
   if (a.row_tiles < 1 || a.k_blocks < 1 || (a.ks != 4 && a.ks != 8) || a.N < 1 || a.N > a.row_tiles * 16)
     SS_FAIL(SS_EINVAL, "decode GEMM: bad shape (tiles %d, k blocks %d, waves %d, N %d)", a.row_tiles, a.k_blocks, a.ks, a.N);
@@ -341,8 +371,8 @@ static void launch_stream_gemm_t(int epi, const StreamGemmArgs &a, dim3 grid, di
 
 ss_status launch_stream_gemm(int dtype, int epi, const StreamGemmArgs &a, hipStream_t st) {
   SS_TRY(check_stream_gemm(dtype, epi, a));
-  const dim3 grid(stream_gemm_blocks(epi, a)), block(a.ks * 64);
-  const int nb = a.B <= 16 ? 1 : 2;
+  const dim3 grid(stream_gemm_blocks(epi, a) * a.bt_split), block(a.ks * 64);
+  const int nb = (a.B <= 16 || a.bt_split == 2) ? 1 : 2;
   if (dtype == SS_DTYPE_BF16) {
     if (nb == 1) launch_stream_gemm_t<bf16_t, 1, 8>(epi, a, grid, block, st);
     else launch_stream_gemm_t<bf16_t, 2, 8>(epi, a, grid, block, st);

@@ -238,6 +238,40 @@ def test_launch_modes_agree(ss, side_stream, name, kw):
             assert np.array_equal(bits(a), bits(b))
 
 
+@pytest.mark.parametrize("name,batch", [("opt66b_m8", 27), ("gpt20b_m4", 7), ("llama30b_m2", 16)])
+def test_gemm_launch_shapes_give_the_same_bits(ss, side_stream, name, batch):
+    """Tiles per block and the split of the batch tiles over blocks are free choices (made per
+    shape, by rule or by timing): every combination must give bit-identical logits and caches."""
+    import torch
+    w = scaled(name, "bf16", batch=batch, s_in=40, steps=3, d_model=512, ffn=1152, head_dim=128, n_heads=4, vocab=2011)
+    W = make_weights(w.desc, w.slice, w.seed)
+    toks = make_tokens(w.seed, w.batch, w.s_in, w.desc["vocab"])
+    forced = make_tokens(w.seed + 1, w.batch, w.steps, w.desc["vocab"])
+    outs = []
+    try:
+        for nw in (1, 2):
+            for bt in ((1, 2) if batch > 16 else (1,)):
+                ss.force_gemm_shape(nw, bt)
+                sh = ss.Shard(w.desc, w.slice, W, w.batch, w.s_max)
+                logits = torch.empty(w.batch, w.desc["vocab"], dtype=torch.float32, device="cuda")
+                nxt = torch.empty(w.batch, dtype=torch.int32, device="cuda")
+                ss.prefill([sh], dev(toks), logits, nxt)
+                run = []
+                for i in range(w.steps):
+                    ss.decode_step([sh], dev(forced[:, i]), logits, nxt)
+                    torch.cuda.synchronize()
+                    run.append(logits.cpu().numpy().copy())
+                    run.append(nxt.cpu().numpy().copy())
+                run.append(ss.kv_export(sh))
+                outs.append(run)
+                sh.destroy()
+    finally:
+        ss.force_gemm_shape(0, 0)
+    for other in outs[1:]:
+        for a, b in zip(outs[0], other):
+            assert np.array_equal(bits(a) if a.dtype != np.int32 else a, bits(b) if b.dtype != np.int32 else b)
+
+
 @pytest.mark.parametrize("name,dtype,kw,cuts,group_m", [
     ("tiny_gpt", "f32", dict(layers=5, batch=3, s_in=20, steps=4), [0, 2, 3, 5], 1),
     ("gpt20b_m4", "bf16", dict(layers=4, batch=6, s_in=60, steps=4, head_dim=128, n_heads=4, d_model=512), [0, 1, 4], 1),

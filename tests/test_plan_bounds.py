@@ -17,7 +17,7 @@ class EmbedArgs(C.Structure):
 
 
 class GemmArgs(C.Structure):
-    _fields_ = [("w", vp), ("row_tiles", i32), ("k_blocks", i32), ("ks", i32), ("nw", i32), ("B", i32), ("N", i32), ("act", vp),
+    _fields_ = [("w", vp), ("row_tiles", i32), ("k_blocks", i32), ("ks", i32), ("nw", i32), ("n_blocks", i32), ("bt_split", i32), ("B", i32), ("N", i32), ("act", vp),
                 ("stat_in", vp), ("stat_groups", i32), ("norm_dim", i32), ("rms", i32), ("eps", f32), ("wg", vp), ("cb", vp),
                 ("out_f32", vp), ("ld_out", i32), ("x_in", vp), ("x_out", vp), ("act_out", vp), ("out_k_blocks", i32),
                 ("g_out", vp), ("stat_out", vp), ("act_kind", i32), ("am_val", vp), ("am_idx", vp), ("counter", vp),
@@ -95,7 +95,8 @@ def check(w):
             assert a.waves in (4, 16)
         else:
             g = p.g
-            assert g.ks in (4, 8) and g.B == w.batch and p.gy == 1 and g.nw in (1, 2) and p.gx == -(-g.row_tiles // g.nw)
+            assert g.ks in (4, 8) and g.B == w.batch and p.gy == 1 and g.nw in (1, 2) and g.n_blocks == -(-g.row_tiles // g.nw)
+            assert (g.bt_split == 1 or (g.bt_split == 2 and g.B > 16)) and p.gx == g.n_blocks * g.bt_split
             assert 1 <= g.N <= g.row_tiles * 16
             rng("w", g.w, g.row_tiles * g.k_blocks * 1024, regions)
             rng("act", g.act, nbt * g.k_blocks * parts * 1024, regions)
@@ -125,8 +126,8 @@ def check(w):
                 stat_groups = g.row_tiles // 2
             if p.kind == LM_HEAD:
                 assert g.N == w.desc["vocab"]
-                rng("am_val", g.am_val, p.gx * 32 * 4, regions)
-                rng("am_idx", g.am_idx, p.gx * 32 * 4, regions)
+                rng("am_val", g.am_val, g.n_blocks * 32 * 4, regions)
+                rng("am_idx", g.am_idx, g.n_blocks * 32 * 4, regions)
                 rng("counter", g.counter, 4, regions)
                 assert g.n_lens == 1 and g.commit_inc == 1
         regions.sort()
