@@ -1,0 +1,190 @@
+// Host-side planning for a change of parallel configuration: context overlap, device mapping
+// (Kuhn-Munkres), migration order, cache discard, just-in-time arrangement.  No GPU.
+#include <stdint.h>
+
+#include <algorithm>
+#include <limits>
+#include <numeric>
+#include <vector>
+
+#include "../../include/spotshard_plan.h"
+
+namespace ss {
+void set_error(const char *fmt, ...);
+}
+#define SS_FAIL(code, ...)        \
+  do {                            \
+    ::ss::set_error(__VA_ARGS__); \
+    return (code);                \
+  } while (0)
+
+static int64_t overlap(int a0, int a1, int b0, int b1) { return std::max(0, std::min(a1, b1) - std::max(a0, b0)); }
+
+static bool slice_ok(const ss_model_desc &m, const ss_slice &s) {
+  return 0 <= s.layer_lo && s.layer_lo <= s.layer_hi && s.layer_hi <= m.n_layers && 0 <= s.head_lo &&
+         s.head_lo <= s.head_hi && s.head_hi <= m.n_heads && 0 <= s.ffn_lo && s.ffn_lo <= s.ffn_hi && s.ffn_hi <= m.ffn;
+}
+
+extern "C" {
+
+ss_status ss_context_overlap(const ss_model_desc *desc, int32_t lm_head_tied, const ss_slice *a, const ss_slice *b,
+                             uint64_t kv_rows, uint64_t *model_bytes, uint64_t *cache_bytes) {
+  if (!desc || !a || !b) SS_FAIL(SS_EINVAL, "NULL argument");
+  const ss_model_desc &m = *desc;
+  if (m.d_model < 1 || m.head_dim < 1 || m.vocab < 1 || !slice_ok(m, *a) || !slice_ok(m, *b))
+    SS_FAIL(SS_EINVAL, "bad model descriptor or slice");
+  const int64_t esz = m.dtype == SS_DTYPE_BF16 ? 2 : 4, kvsz = m.kv_dtype == SS_DTYPE_F32 ? 4 : 2;
+  const int64_t d = m.d_model, Dh = m.head_dim;
+  const int64_t layers = overlap(a->layer_lo, a->layer_hi, b->layer_lo, b->layer_hi);
+  const int64_t heads = overlap(a->head_lo, a->head_hi, b->head_lo, b->head_hi);
+  const int64_t ffn = overlap(a->ffn_lo, a->ffn_hi, b->ffn_lo, b->ffn_hi);
+  const bool ln = m.norm == SS_NORM_LAYERNORM, glu = m.act == SS_ACT_SWIGLU, bias = m.has_bias != 0;
+  // one layer: matrices in the weight type, vectors in float32
+  int64_t per_layer = esz * (3 * d * heads * Dh + heads * Dh * d + (glu ? 2 : 1) * d * ffn + ffn * d);
+  if (bias) per_layer += 4 * (3 * heads * Dh + (glu ? 0 : ffn));   // column-parallel biases follow their columns
+  per_layer += 4 * ((ln ? 4 : 2) * d + (bias ? 2 * d : 0));        // norm gain (and shift) x2, the two row-parallel biases
+  // replicated once per position: embedding, positions, LM head, final norm
+  int64_t shared = esz * ((int64_t)m.vocab * d + (m.pos == SS_POS_LEARNED ? (int64_t)m.max_pos * d : 0) +
+                          (lm_head_tied ? 0 : (int64_t)m.vocab * d)) +
+                   4 * (ln ? 2 : 1) * d;
+  if (model_bytes) *model_bytes = (uint64_t)(layers * per_layer + shared);
+  if (cache_bytes) *cache_bytes = (uint64_t)(layers * 2 * heads * Dh * kvsz) * kv_rows;
+  return SS_OK;
+}
+
+// Kuhn-Munkres in its potentials form on cost = max weight - weight (so a minimum-cost perfect
+// matching is a maximum-weight one); rows are devices, columns positions; O(n^3).
+ss_status ss_match_devices(int32_t n, const uint64_t *weight, int32_t *position_of, uint64_t *total) {
+  if (n < 1 || n > 512 || !weight || !position_of) SS_FAIL(SS_EINVAL, "bad matching arguments");
+  uint64_t wmax = 0;
+  for (int64_t i = 0; i < (int64_t)n * n; ++i) wmax = std::max(wmax, weight[i]);
+  if (wmax > (uint64_t)std::numeric_limits<int64_t>::max() / 4) SS_FAIL(SS_EINVAL, "weights too large");
+  auto cost = [&](int u, int v) { return (int64_t)(wmax - weight[(size_t)u * n + v]); };
+  const int64_t INF = std::numeric_limits<int64_t>::max() / 2;
+  std::vector<int64_t> pu(n + 1, 0), pv(n + 1, 0), minv(n + 1);
+  std::vector<int> row_of(n + 1, 0), way(n + 1, 0);  // row_of[col]: 1-based row matched to the column
+  std::vector<char> used(n + 1);
+  for (int u = 1; u <= n; ++u) {
+    row_of[0] = u;
+    int j0 = 0;
+    std::fill(minv.begin(), minv.end(), INF);
+    std::fill(used.begin(), used.end(), 0);
+    do {
+      used[j0] = 1;
+      const int i0 = row_of[j0];
+      int64_t delta = INF;
+      int j1 = 0;
+      for (int j = 1; j <= n; ++j) {
+        if (used[j]) continue;
+        const int64_t cur = cost(i0 - 1, j - 1) - pu[i0] - pv[j];
+        if (cur < minv[j]) minv[j] = cur, way[j] = j0;
+        if (minv[j] < delta) delta = minv[j], j1 = j;
+      }
+      for (int j = 0; j <= n; ++j) {
+        if (used[j]) pu[row_of[j]] += delta, pv[j] -= delta;
+        else minv[j] -= delta;
+      }
+      j0 = j1;
+    } while (row_of[j0] != 0);
+    do {
+      const int j1 = way[j0];
+      row_of[j0] = row_of[j1];
+      j0 = j1;
+    } while (j0);
+  }
+  uint64_t sum = 0;
+  for (int j = 1; j <= n; ++j) {
+    position_of[row_of[j] - 1] = j - 1;
+    sum += weight[(size_t)(row_of[j] - 1) * n + (j - 1)];
+  }
+  if (total) *total = sum;
+  return SS_OK;
+}
+
+ss_status ss_migration_order(int32_t n_layers, int32_t n_instances, const int64_t *delta, int64_t u_max,
+                             int32_t *order) {
+  if (n_layers < 1 || n_instances < 1 || !delta || !order) SS_FAIL(SS_EINVAL, "bad migration-order arguments");
+  std::vector<int64_t> U(n_instances, 0);
+  std::vector<int> left;
+  int n_out = 0;
+  auto peak_after = [&](int l) {
+    int64_t mx = std::numeric_limits<int64_t>::min();
+    for (int i = 0; i < n_instances; ++i) mx = std::max(mx, U[i] + delta[(size_t)l * n_instances + i]);
+    return mx;
+  };
+  auto apply = [&](int l) {
+    for (int i = 0; i < n_instances; ++i) U[i] += delta[(size_t)l * n_instances + i];
+    order[n_out++] = l;
+  };
+  for (int l = 0; l < n_layers; ++l) {
+    if (peak_after(l) <= u_max) apply(l);
+    else left.push_back(l);
+  }
+  while (!left.empty()) {
+    size_t best = 0;
+    int64_t best_peak = peak_after(left[0]);
+    for (size_t k = 1; k < left.size(); ++k) {
+      const int64_t p = peak_after(left[k]);
+      if (p < best_peak) best_peak = p, best = k;
+    }
+    apply(left[best]);
+    left.erase(left.begin() + best);
+  }
+  return SS_OK;
+}
+
+ss_status ss_progressive_plan(int32_t n_layers, const int32_t *order, const int32_t *stage_of_layer, int32_t n_stages,
+                              int32_t *kind, int32_t *arg) {
+  if (n_layers < 1 || n_stages < 1 || !order || !stage_of_layer || !kind || !arg) SS_FAIL(SS_EINVAL, "bad plan arguments");
+  std::vector<int> waiting(n_stages, 0);
+  std::vector<char> seen(n_layers, 0);
+  for (int l = 0; l < n_layers; ++l) {
+    if (stage_of_layer[l] < 0 || stage_of_layer[l] >= n_stages) SS_FAIL(SS_EINVAL, "layer %d has no stage", l);
+    waiting[stage_of_layer[l]]++;
+  }
+  for (int p = 0; p < n_stages; ++p)
+    if (waiting[p] == 0) SS_FAIL(SS_EINVAL, "stage %d has no layer", p);
+  int k = 0;
+  kind[k] = SS_PLAN_MIGRATE_CACHE, arg[k++] = -1;
+  for (int i = 0; i < n_layers; ++i) {
+    const int l = order[i];
+    if (l < 0 || l >= n_layers || seen[l]) SS_FAIL(SS_EINVAL, "order is not a permutation of the layers");
+    seen[l] = 1;
+    kind[k] = SS_PLAN_MIGRATE_LAYER, arg[k++] = l;
+    if (--waiting[stage_of_layer[l]] == 0) kind[k] = SS_PLAN_START_STAGE, arg[k++] = stage_of_layer[l];
+  }
+  return SS_OK;
+}
+
+ss_status ss_rows_to_keep(int32_t n_rows, const int32_t *lens, int32_t keep, int32_t n_dst, int32_t *batch_map) {
+  if (n_rows < 0 || keep < 0 || n_dst < 0 || (n_rows && !lens) || (n_dst && !batch_map)) SS_FAIL(SS_EINVAL, "bad arguments");
+  std::vector<int> rows;
+  for (int r = 0; r < n_rows; ++r) {
+    if (lens[r] < 0) SS_FAIL(SS_EINVAL, "negative length");
+    if (lens[r] > 0) rows.push_back(r);
+  }
+  std::stable_sort(rows.begin(), rows.end(), [&](int x, int y) { return lens[x] > lens[y]; });
+  if ((int)rows.size() > std::min(keep, n_dst)) rows.resize(std::min(keep, n_dst));
+  std::sort(rows.begin(), rows.end());
+  for (int b = 0; b < n_dst; ++b) batch_map[b] = b < (int)rows.size() ? rows[b] : -1;
+  return SS_OK;
+}
+
+int32_t ss_jit_iterations(int32_t acquisition, int32_t s_out, const double *l_exe, double t_grace, double t_mig) {
+  if (s_out < 0 || !l_exe) return 0;
+  int s = 0;
+  if (!acquisition) {
+    for (int k = 0; k <= s_out; ++k)
+      if (l_exe[k] < t_grace - t_mig) s = k;
+  } else {
+    s = s_out;
+    for (int k = 0; k <= s_out; ++k)
+      if (l_exe[k] >= t_grace) {
+        s = k;
+        break;
+      }
+  }
+  return t_mig < l_exe[s] ? s : 0;
+}
+
+}  // extern "C"

@@ -6,20 +6,24 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "spotshard.h")
+import glob
+HEADERS = sorted(glob.glob(os.path.join(ROOT, "include", "*.h")))
 LIB = os.path.join(ROOT, "paper_2311_15566_amd", "libspotshard.so")
 
 
 def declared_symbols():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(ss_[a-z0-9_]+)\s*\(", text)))
+    syms = set()
+    for h in HEADERS:
+        text = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
+        syms |= set(re.findall(r"\b(ss_[a-z0-9_]+)\s*\(", text))
+    return sorted(syms)
 
 
 def test_header_declares_the_boundary():
     syms = declared_symbols()
     for must in ("ss_shard_create", "ss_prefill", "ss_decode_step", "ss_kv_repack", "ss_committed_len",
-                 "ss_kv_export", "ss_kv_import", "ss_shard_device_bytes", "ss_last_error"):
+                 "ss_kv_export", "ss_kv_import", "ss_shard_device_bytes", "ss_last_error", "ss_stage_decode_step",
+                 "ss_match_devices", "ss_migration_order"):
         assert must in syms
 
 
