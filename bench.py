@@ -254,6 +254,28 @@ def main():
                                      note="traffic = bytes read + bytes written; payload = half")
                 for p in parts:
                     p.destroy()
+                # ---- model-context re-slice: the same two half-width shards built out of the resident one ----
+                half = sub_slice_of(w.slice, 0, 2)
+                nb = ss.binding.device_bytes(w.desc, half, w.batch, w.s_max)
+                mem = torch.zeros(nb, dtype=torch.uint8, device="cuda")
+                ss.Shard.from_resident(w.desc, half, [sh], w.batch, w.s_max, mem=mem).destroy()     # untimed first touch
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                moved = 0
+                for p in range(2):
+                    r = ss.Shard.from_resident(w.desc, sub_slice_of(w.slice, p, 2), [sh], w.batch, w.s_max, mem=mem)
+                    moved += r.bytes_copied
+                    r.destroy()
+                dt_r = time.perf_counter() - t0
+                t0 = time.perf_counter()
+                ss.Shard(w.desc, half, W, w.batch, w.s_max).destroy()
+                dt_host = time.perf_counter() - t0
+                out["reslice"] = dict(bytes_copied=moved // 2, ms=dt_r / 2 * 1e3, traffic_GBps=2 * moved / dt_r / 1e9,
+                                      frac=2 * moved / dt_r / 1e9 / HBM_PEAK_GBPS, from_host_ms=dt_host * 1e3,
+                                      note="one half-width shard's model context copied out of the resident shard "
+                                           "(wall time of the call, which synchronizes); from_host_ms: the same shard "
+                                           "uploaded from host tensors")
+                del mem
         else:
             out["roofline"] = dict(bound="hbm", kernel="whole decode step", achieved=whole, peak=HBM_PEAK_GBPS,
                                    unit="GB/s", frac=whole / HBM_PEAK_GBPS, traffic=None)

@@ -103,6 +103,23 @@ ss_status ss_shard_create(const ss_model_desc *desc, const ss_slice *slice,
                           void *device_mem, size_t device_bytes, void *hip_stream,
                           ss_shard **out);
 
+/* Model-context migration on one device (Section 3.3: the device mapper maximises the model
+ * parameters a device can re-use in its new position): a shard for `slice` whose model context is
+ * copied, device to device, out of resident shards of the same model instead of being uploaded
+ * again.  Every (layer, head) and (layer, FFN column) of `slice` must be held by one of
+ * `sources` (in any order; FFN columns shared with a source in multiples of 64), else SS_EINVAL.
+ * The result is bit-identical to what ss_shard_create builds from the host tensors; its cache is
+ * empty.  The sources are only read.  Synchronizes the stream.  bytes_copied (host, may be NULL)
+ * receives the bytes of model context moved. */
+ss_status ss_shard_create_from_resident(const ss_model_desc *desc, const ss_slice *slice,
+                                        ss_shard *const *sources, int32_t n_sources, int32_t max_batch,
+                                        int32_t max_seq, void *device_mem, size_t device_bytes,
+                                        void *hip_stream, ss_shard **out, uint64_t *bytes_copied);
+
+/* Bytes at the start of a shard's device_mem that hold its model context (everything before the
+ * cache): what a byte-for-byte comparison of two shards' model context covers. */
+size_t ss_shard_model_context_bytes(const ss_shard *shard);
+
 ss_status ss_shard_destroy(ss_shard *shard); /* frees the host object only */
 
 /* Drop the cache context: every committed length back to 0 (Section 4.2: a

@@ -74,6 +74,9 @@ def _load():
     L.ss_set_graph_launch.argtypes = [vp, i32]
     L.ss_shard_geometry.argtypes = [vp, C.POINTER(i32)]
     L.ss_kernel_timing.argtypes = [vp, i32]
+    L.ss_shard_create_from_resident.argtypes = [vp, vp, C.POINTER(vp), i32, i32, i32, vp, C.c_size_t, vp, C.POINTER(vp), C.POINTER(C.c_uint64)]
+    L.ss_shard_model_context_bytes.argtypes = [vp]
+    L.ss_shard_model_context_bytes.restype = C.c_size_t
     L.ss_debug_force_gemm_shape.argtypes = [i32, i32]
     L.ss_kernel_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), vp]
     return L
@@ -141,7 +144,7 @@ class Shard:
         if nbytes == 0:
             # let create produce the error text
             nbytes = 256
-        self.mem = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        self.mem = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")   # gaps between tensors stay zero
         layers = (LayerWeights * len(parent["layers"]))()
         for i, Lw in enumerate(parent["layers"]):
             for f in _LAYER_FIELDS:
@@ -153,6 +156,32 @@ class Shard:
         _check(lib.ss_shard_create(C.byref(d), C.byref(s), C.byref(w), max_batch, max_seq,
                                    C.c_void_p(self.mem.data_ptr()), nbytes, _stream(stream), C.byref(h)))
         self.handle = h
+
+    @classmethod
+    def from_resident(cls, desc: dict, slc: dict, sources, max_batch: int, max_seq: int, stream=None, mem=None):
+        """A shard whose model context is copied out of resident shards (device to device).
+        mem: a zeroed uint8 CUDA tensor of at least device_bytes(...) to build it in, or None."""
+        import torch
+        self = cls.__new__(cls)
+        self.desc, self.slice = dict(desc), dict(slc)
+        self.max_batch, self.max_seq = max_batch, max_seq
+        d, s = _desc(desc), _slice(slc)
+        nbytes = lib.ss_shard_device_bytes(C.byref(d), C.byref(s), max_batch, max_seq) or 256
+        self.mem = mem if mem is not None else torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+        nbytes = self.mem.numel()
+        arr = (C.c_void_p * len(sources))(*[x.handle for x in sources])
+        h, moved = C.c_void_p(), C.c_uint64()
+        self.handle = None
+        _check(lib.ss_shard_create_from_resident(C.byref(d), C.byref(s), arr, len(sources), max_batch, max_seq,
+                                                 C.c_void_p(self.mem.data_ptr()), nbytes, _stream(stream), C.byref(h),
+                                                 C.byref(moved)))
+        self.handle = h
+        self.bytes_copied = moved.value
+        return self
+
+    def model_context(self):
+        """The bytes of device memory that hold the model context (a view, uint8)."""
+        return self.mem[:lib.ss_shard_model_context_bytes(self.handle)]
 
     def destroy(self):
         if self.handle is not None:

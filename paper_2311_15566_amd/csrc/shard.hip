@@ -240,6 +240,59 @@ __global__ void __launch_bounds__(256) kv_repack_kernel(RepackArgs a) {
   for (; i < v1; i += 256) __builtin_nontemporal_store(__builtin_nontemporal_load(s + i), d + i);
 }
 
+// ---------------------------------------------------------------------------
+// Model-context re-slice: batched strided copies between resident shards.  A descriptor is
+// `rows` runs of `row_bytes` (a multiple of 16) with their own strides in source and
+// destination; block b finds its descriptor by bisection over the descriptors' first blocks and
+// copies up to 64 KiB of it with 16-byte accesses.
+// ---------------------------------------------------------------------------
+struct Copy2D {
+  const char *src;
+  char *dst;
+  uint64_t src_stride, dst_stride;
+  uint32_t rows, row_bytes;
+  uint32_t rows_per_block;  // >= 1; when 1, a row may take several blocks of chunk_vec vectors
+  uint32_t blocks_per_row;  // >= 1
+  uint32_t first_block;
+  uint32_t pad;
+};
+
+__global__ void __launch_bounds__(256) copy2d_kernel(const Copy2D *__restrict__ desc, int n_desc) {
+  int lo = 0, hi = n_desc - 1;
+  while (lo < hi) {  // last descriptor whose first block is <= blockIdx.x
+    const int mid = (lo + hi + 1) >> 1;
+    if (desc[mid].first_block <= blockIdx.x) lo = mid;
+    else hi = mid - 1;
+  }
+  const Copy2D c = desc[lo];
+  const uint32_t local = blockIdx.x - c.first_block;
+  const uint32_t row_vec = c.row_bytes >> 4;
+  if (c.rows_per_block > 1) {
+    const uint32_t r0 = local * c.rows_per_block, r1 = min(c.rows, r0 + c.rows_per_block);
+    const uint32_t total = (r1 - r0) * row_vec;
+    for (uint32_t i = threadIdx.x; i < total; i += 256) {
+      const uint32_t r = r0 + i / row_vec, v = i % row_vec;
+      const u32x4 x = __builtin_nontemporal_load((const u32x4 *)(c.src + (size_t)r * c.src_stride) + v);
+      __builtin_nontemporal_store(x, (u32x4 *)(c.dst + (size_t)r * c.dst_stride) + v);
+    }
+  } else {
+    const uint32_t r = local / c.blocks_per_row, part = local % c.blocks_per_row;
+    const uint32_t v0 = part * 4096u, v1 = min(row_vec, v0 + 4096u);
+    const u32x4 *sp = (const u32x4 *)(c.src + (size_t)r * c.src_stride);
+    u32x4 *dp = (u32x4 *)(c.dst + (size_t)r * c.dst_stride);
+    uint32_t i = v0 + threadIdx.x;
+    for (; i + 768 < v1; i += 1024) {
+      const u32x4 x0 = __builtin_nontemporal_load(sp + i), x1 = __builtin_nontemporal_load(sp + i + 256);
+      const u32x4 x2 = __builtin_nontemporal_load(sp + i + 512), x3 = __builtin_nontemporal_load(sp + i + 768);
+      __builtin_nontemporal_store(x0, dp + i);
+      __builtin_nontemporal_store(x1, dp + i + 256);
+      __builtin_nontemporal_store(x2, dp + i + 512);
+      __builtin_nontemporal_store(x3, dp + i + 768);
+    }
+    for (; i < v1; i += 256) __builtin_nontemporal_store(__builtin_nontemporal_load(sp + i), dp + i);
+  }
+}
+
 }  // namespace ss
 
 using namespace ss;
@@ -403,6 +456,28 @@ static ss_status upload_all(Shard *sh, const ss_weights *P, hipStream_t st) {
   return SS_OK;
 }
 
+// what creation does after the model context is in place: RoPE table, empty cache, counters
+static ss_status finish_create(Shard *sh, hipStream_t st, bool rope_in_place = false) {
+  const Layout &L = sh->L;
+  if (sh->m.pos == SS_POS_ROPE && !rope_in_place) {
+    // angles in double on the host, table in float32
+    std::vector<float2> tab((size_t)L.Smax * (L.Dh / 2));
+    for (int p = 0; p < L.Smax; ++p)
+      for (int i = 0; i < L.Dh / 2; ++i) {
+        double ang = (double)p * pow((double)sh->m.rope_theta, -2.0 * i / L.Dh);
+        tab[(size_t)p * (L.Dh / 2) + i] = make_float2((float)cos(ang), (float)sin(ang));
+      }
+    SS_HIP(hipMemcpyAsync(sh->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice, st));
+    SS_HIP(hipStreamSynchronize(st));
+  }
+  hipLaunchKernelGGL(fill_i32, dim3(1), dim3(32), 0, st, sh->d_len, 32, 0);
+  const int nc = L.n_counters;
+  hipLaunchKernelGGL(fill_i32, dim3(ceil_div(nc, 256)), dim3(256), 0, st, (int32_t *)(sh->ws + L.ws_counters), nc, 0);
+  SS_HIP(hipGetLastError());
+  SS_HIP(hipStreamSynchronize(st));
+  return SS_OK;
+}
+
 }  // namespace ss
 
 extern "C" {
@@ -434,37 +509,17 @@ ss_status ss_shard_create(const ss_model_desc *desc, const ss_slice *slice, cons
   bind_pointers(sh);
   sh->h_len.assign(max_batch, 0);
   ss_status rc = desc->dtype == SS_DTYPE_BF16 ? upload_all<bf16_t>(sh, parent, st) : upload_all<float>(sh, parent, st);
-  if (rc == SS_OK && desc->pos == SS_POS_ROPE) {
-    // angles in double on the host, table in float32
-    std::vector<float2> tab((size_t)max_seq * (L.Dh / 2));
-    for (int p = 0; p < max_seq; ++p)
-      for (int i = 0; i < L.Dh / 2; ++i) {
-        double ang = (double)p * pow((double)desc->rope_theta, -2.0 * i / L.Dh);
-        tab[(size_t)p * (L.Dh / 2) + i] = make_float2((float)cos(ang), (float)sin(ang));
-      }
-    hipError_t e = hipMemcpyAsync(sh->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice, st);
-    if (e == hipSuccess) e = hipStreamSynchronize(st);
-    if (e != hipSuccess) {
-      set_error("rope table upload: %s", hipGetErrorString(e));
-      rc = SS_EHIP;
-    }
-  }
-  if (rc == SS_OK) {
-    hipLaunchKernelGGL(fill_i32, dim3(1), dim3(32), 0, st, sh->d_len, 32, 0);
-    int nc = L.n_counters;
-    hipLaunchKernelGGL(fill_i32, dim3(ceil_div(nc, 256)), dim3(256), 0, st, (int32_t *)(sh->ws + L.ws_counters), nc, 0);
-    hipError_t e = hipStreamSynchronize(st);
-    if (e != hipSuccess) {
-      set_error("shard creation: %s", hipGetErrorString(e));
-      rc = SS_EHIP;
-    }
-  }
+  if (rc == SS_OK) rc = finish_create(sh, st);
   if (rc != SS_OK) {
     delete sh;
     return rc;
   }
   *out = (ss_shard *)sh;
   return SS_OK;
+}
+
+size_t ss_shard_model_context_bytes(const ss_shard *shard) {
+  return shard ? ((const Shard *)shard)->L.off_kv : 0;
 }
 
 ss_status ss_shard_destroy(ss_shard *shard) {
@@ -510,6 +565,196 @@ ss_status ss_debug_interrupt_after_layer(ss_shard *shard, int32_t layer) {
 ss_status ss_set_graph_launch(ss_shard *shard, int32_t enabled) {
   if (!shard) SS_FAIL(SS_EINVAL, "NULL shard");
   ((Shard *)shard)->use_graph = enabled != 0;
+  return SS_OK;
+}
+
+// ---------------------------------------------------------------------------
+// a shard whose model context comes from resident shards
+// ---------------------------------------------------------------------------
+ss_status ss_shard_create_from_resident(const ss_model_desc *desc, const ss_slice *slice, ss_shard *const *sources,
+                                        int32_t n_sources, int32_t max_batch, int32_t max_seq, void *device_mem,
+                                        size_t device_bytes, void *hip_stream, ss_shard **out, uint64_t *bytes_copied) {
+  if (!desc || !slice || !sources || n_sources < 1 || !device_mem || !out) SS_FAIL(SS_EINVAL, "NULL argument");
+  *out = nullptr;
+  SS_TRY(validate_desc(*desc, *slice, max_batch, max_seq));
+  if (((uintptr_t)device_mem) & 255) SS_FAIL(SS_EINVAL, "device_mem must be 256-byte aligned");
+  std::vector<const Shard *> src(n_sources);
+  for (int i = 0; i < n_sources; ++i) {
+    src[i] = (const Shard *)sources[i];
+    if (!src[i]) SS_FAIL(SS_EINVAL, "sources[%d] is NULL", i);
+    const ss_model_desc &o = src[i]->m;
+    if (o.n_layers != desc->n_layers || o.d_model != desc->d_model || o.n_heads != desc->n_heads ||
+        o.head_dim != desc->head_dim || o.ffn != desc->ffn || o.vocab != desc->vocab || o.max_pos != desc->max_pos ||
+        o.norm != desc->norm || o.act != desc->act || o.pos != desc->pos || o.has_bias != desc->has_bias ||
+        o.dtype != desc->dtype)
+      SS_FAIL(SS_EINVAL, "sources[%d] holds another model", i);
+  }
+  Shard *sh = new (std::nothrow) Shard();
+  if (!sh) SS_FAIL(SS_ENOMEM, "host allocation failed");
+  sh->m = *desc, sh->s = *slice;
+  compute_layout(*desc, *slice, max_batch, max_seq, &sh->L);
+  const Layout &L = sh->L;
+  if (device_bytes < L.total) {
+    delete sh;
+    SS_FAIL(SS_ENOMEM, "device_mem holds %zu bytes, the shard needs %zu", device_bytes, L.total);
+  }
+  sh->base = (char *)device_mem;
+  bind_pointers(sh);
+  sh->h_len.assign(max_batch, 0);
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int d = L.d, Dh = L.Dh, esz = L.esz, FK = esz == 2 ? 32 : 16;
+  const bool ln = desc->norm == SS_NORM_LAYERNORM, glu = desc->act == SS_ACT_SWIGLU, bias = desc->has_bias != 0;
+
+  std::vector<Copy2D> jobs;
+  uint64_t total_bytes = 0;
+  auto add = [&](const void *s_, void *d_, uint32_t rows, size_t row_bytes, size_t s_stride, size_t d_stride) {
+    if (!rows || !row_bytes) return;
+    // one run of many bytes is as good as rows of 64 KiB
+    if (rows == 1 && row_bytes > 65536) {
+      const uint32_t full = (uint32_t)(row_bytes / 65536);
+      const size_t rest = row_bytes - (size_t)full * 65536;
+      jobs.push_back(Copy2D{(const char *)s_, (char *)d_, 65536, 65536, full, 65536, 1, 1, 0, 0});
+      if (rest) jobs.push_back(Copy2D{(const char *)s_ + (size_t)full * 65536, (char *)d_ + (size_t)full * 65536, 0, 0, 1, (uint32_t)rest, 1, 1, 0, 0});
+    } else {
+      jobs.push_back(Copy2D{(const char *)s_, (char *)d_, s_stride, d_stride, rows, (uint32_t)row_bytes, 1, 1, 0, 0});
+    }
+    total_bytes += (uint64_t)rows * row_bytes;
+  };
+  ss_status rc = SS_OK;
+  auto fail = [&](const char *what, int l) {
+    set_error("the sources do not hold %s of layer %d that the new slice needs", what, l);
+    rc = SS_EINVAL;
+  };
+
+  // replicated context from the first source
+  const Shard *s0 = src[0];
+  add(s0->wte, sh->wte, 1, (size_t)L.V * d * esz, 0, 0);
+  if (L.max_pos) add(s0->wpe, sh->wpe, 1, (size_t)L.max_pos * d * esz, 0, 0);
+  add(s0->lm_head.ptr, sh->lm_head.ptr, 1, (size_t)sh->lm_head.row_tiles * sh->lm_head.k_blocks * 1024, 0, 0);
+  add(s0->lnf_g, sh->lnf_g, 1, (size_t)d * 4, 0, 0);
+  if (ln) {
+    add(s0->lnf_b, sh->lnf_b, 1, (size_t)d * 4, 0, 0);
+    add(s0->wg_lm, sh->wg_lm, 1, align_up((size_t)L.V, 16) * 4, 0, 0);
+    add(s0->cb_lm, sh->cb_lm, 1, align_up((size_t)L.V, 16) * 4, 0, 0);
+  }
+  // the rotation table is indexed by position: a source's table covers ours if it is as long
+  bool rope_copied = false;
+  if (desc->pos == SS_POS_ROPE && s0->L.Smax >= L.Smax && s0->m.rope_theta == desc->rope_theta) {
+    add(s0->rope, sh->rope, 1, (size_t)L.Smax * (Dh / 2) * sizeof(float2), 0, 0);
+    rope_copied = true;
+  }
+  const int kbd = d / FK;  // k blocks of a d-long reduction
+  for (int l = 0; l < L.Ls && rc == SS_OK; ++l) {
+    const int gl = slice->layer_lo + l;  // layer of the model
+    char *lb = sh->base + L.off_layer[l];
+    bool vectors_done = false, progress = true;
+    int heads_done = 0, cols_done = 0;
+    // sources in any order: keep passing over them while one of them extends the covered prefix
+    while (progress && rc == SS_OK && (heads_done < L.Hs || cols_done < L.Fs || !vectors_done)) {
+    progress = false;
+    for (const Shard *q : src) {
+      if (gl < q->s.layer_lo || gl >= q->s.layer_hi) continue;
+      const Layout &Q = q->L;
+      const char *qb = q->base + Q.off_layer[gl - q->s.layer_lo];
+      if (!vectors_done) {  // replicated vectors of the layer
+        add(qb + Q.lo_ln1_g, lb + L.lo_ln1_g, 1, (size_t)d * 4, 0, 0);
+        add(qb + Q.lo_ln2_g, lb + L.lo_ln2_g, 1, (size_t)d * 4, 0, 0);
+        if (ln) add(qb + Q.lo_ln1_b, lb + L.lo_ln1_b, 1, (size_t)d * 4, 0, 0), add(qb + Q.lo_ln2_b, lb + L.lo_ln2_b, 1, (size_t)d * 4, 0, 0);
+        if (bias) add(qb + Q.lo_bo, lb + L.lo_bo, 1, (size_t)d * 4, 0, 0), add(qb + Q.lo_b2, lb + L.lo_b2, 1, (size_t)d * 4, 0, 0);
+        vectors_done = progress = true;
+      }
+      // heads the source adds to what is already covered (sources are taken in order; heads
+      // must come as a contiguous run continuing the covered prefix)
+      const int h0 = std::max(slice->head_lo + heads_done, q->s.head_lo), h1 = std::min(slice->head_hi, q->s.head_hi);
+      if (h0 == slice->head_lo + heads_done && h1 > h0) {
+        const int nh = h1 - h0, hs = h0 - q->s.head_lo, hd = h0 - slice->head_lo;
+        const size_t head_frag_bytes = (size_t)(Dh / 16) * kbd * 1024;  // one head's tiles of one of q, k, v
+        for (int p = 0; p < 3; ++p) {
+          add(qb + Q.lo_wqkv + ((size_t)p * Q.Hs + hs) * head_frag_bytes, lb + L.lo_wqkv + ((size_t)p * L.Hs + hd) * head_frag_bytes,
+              1, (size_t)nh * head_frag_bytes, 0, 0);
+          if (bias) add(qb + Q.lo_bqkv + ((size_t)p * Q.Hs + hs) * Dh * 4, lb + L.lo_bqkv + ((size_t)p * L.Hs + hd) * Dh * 4, 1, (size_t)nh * Dh * 4, 0, 0);
+          if (ln) {
+            add(qb + Q.lo_wg_qkv + ((size_t)p * Q.Hs + hs) * Dh * 4, lb + L.lo_wg_qkv + ((size_t)p * L.Hs + hd) * Dh * 4, 1, (size_t)nh * Dh * 4, 0, 0);
+            add(qb + Q.lo_cb_qkv + ((size_t)p * Q.Hs + hs) * Dh * 4, lb + L.lo_cb_qkv + ((size_t)p * L.Hs + hd) * Dh * 4, 1, (size_t)nh * Dh * 4, 0, 0);
+          }
+        }
+        // output projection: every row tile, the k blocks of these heads
+        const size_t hk = (size_t)(Dh / FK) * 1024;  // one head's k blocks of one row tile
+        add(qb + Q.lo_wo + hs * hk, lb + L.lo_wo + hd * hk, d / 16, nh * hk, (size_t)Q.Hs * hk, (size_t)L.Hs * hk);
+        heads_done += nh;
+        progress = true;
+      }
+      const int f0 = std::max(slice->ffn_lo + cols_done, q->s.ffn_lo), f1 = std::min(slice->ffn_hi, q->s.ffn_hi);
+      if (f0 == slice->ffn_lo + cols_done && f1 > f0) {
+        const int nf = f1 - f0, fs = f0 - q->s.ffn_lo, fd = f0 - slice->ffn_lo;
+        if (nf % 64 || fs % 64 || fd % 64) {
+          set_error("FFN columns shared with a source must come in multiples of 64");
+          rc = SS_EINVAL;
+          break;
+        }
+        const int c1 = glu ? 2 : 1;  // gate/up tiles are interleaved: two tiles per 16 columns
+        add(qb + Q.lo_w1 + (size_t)(fs / 16) * c1 * kbd * 1024, lb + L.lo_w1 + (size_t)(fd / 16) * c1 * kbd * 1024, 1,
+            (size_t)(nf / 16) * c1 * kbd * 1024, 0, 0);
+        if (bias && !glu) add(qb + Q.lo_b1 + (size_t)fs * 4, lb + L.lo_b1 + (size_t)fd * 4, 1, (size_t)nf * 4, 0, 0);
+        if (ln) {
+          add(qb + Q.lo_wg_1 + (size_t)fs * c1 * 4, lb + L.lo_wg_1 + (size_t)fd * c1 * 4, 1, (size_t)nf * c1 * 4, 0, 0);
+          add(qb + Q.lo_cb_1 + (size_t)fs * c1 * 4, lb + L.lo_cb_1 + (size_t)fd * c1 * 4, 1, (size_t)nf * c1 * 4, 0, 0);
+        }
+        const size_t fk = 1024;  // one k block of one row tile
+        add(qb + Q.lo_w2 + (size_t)(fs / FK) * fk, lb + L.lo_w2 + (size_t)(fd / FK) * fk, d / 16, (size_t)(nf / FK) * fk,
+            (size_t)(Q.Fs / FK) * fk, (size_t)(L.Fs / FK) * fk);
+        cols_done += nf;
+        progress = true;
+      }
+    }
+    }
+    if (rc != SS_OK) break;
+    if (!vectors_done) fail("the norm vectors", gl);
+    else if (heads_done != L.Hs) fail("all the heads", gl);
+    else if (cols_done != L.Fs) fail("all the FFN columns", gl);
+  }
+  // the descriptors go through the new shard's own workspace
+  if (rc == SS_OK) {
+    uint32_t blocks = 0;
+    for (Copy2D &c : jobs) {
+      if (c.row_bytes % 16 || ((uintptr_t)c.src & 15) || ((uintptr_t)c.dst & 15) || c.src_stride % 16 || c.dst_stride % 16) {
+        set_error("internal: a re-slice copy is not 16-byte aligned");
+        rc = SS_EINVAL;
+        break;
+      }
+      c.first_block = blocks;
+      if (c.row_bytes >= 65536) {
+        c.rows_per_block = 1, c.blocks_per_row = (uint32_t)ceil_div((int)(c.row_bytes >> 4), 4096);
+        blocks += c.rows * c.blocks_per_row;
+      } else {
+        c.rows_per_block = std::max<uint32_t>(2, 65536 / c.row_bytes), c.blocks_per_row = 1;
+        blocks += (c.rows + c.rows_per_block - 1) / c.rows_per_block;
+      }
+    }
+    if (rc == SS_OK && jobs.size() * sizeof(Copy2D) > L.ws_bytes) {
+      set_error("re-slice: %zu copy descriptors do not fit the workspace", jobs.size());
+      rc = SS_EINVAL;
+    }
+    if (rc == SS_OK) {
+      hipError_t e = hipMemcpyAsync(sh->ws, jobs.data(), jobs.size() * sizeof(Copy2D), hipMemcpyHostToDevice, st);
+      if (e == hipSuccess) {
+        hipLaunchKernelGGL(copy2d_kernel, dim3(blocks), dim3(256), 0, st, (const Copy2D *)sh->ws, (int)jobs.size());
+        e = hipGetLastError();
+      }
+      if (e == hipSuccess) e = hipStreamSynchronize(st);  // the host descriptor array dies with this call
+      if (e != hipSuccess) {
+        set_error("re-slice: %s", hipGetErrorString(e));
+        rc = SS_EHIP;
+      }
+    }
+  }
+  if (rc == SS_OK) rc = finish_create(sh, st, rope_copied);
+  if (rc != SS_OK) {
+    delete sh;
+    return rc;
+  }
+  if (bytes_copied) *bytes_copied = total_bytes;
+  *out = (ss_shard *)sh;
   return SS_OK;
 }
 

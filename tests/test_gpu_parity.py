@@ -397,6 +397,57 @@ def test_reparallelize_pipeline_2x2_to_3x1(ss, side_stream, name, dtype):
             sh.destroy()
 
 
+@pytest.mark.parametrize("name,dtype", [("tiny_gpt", "f32"), ("gpt20b_m4", "bf16"), ("llama30b_m2", "bf16"), ("opt66b_m8", "bf16")])
+def test_model_context_reslice_is_bit_identical(ss, side_stream, name, dtype):
+    """Shards built out of resident shards (split, merge, and the paper's (P=2,M=2) -> (P=3,M=1))
+    hold, byte for byte, the model context that creation from the host tensors gives, and decode
+    to the same bits."""
+    import torch
+    w = scaled(name, dtype, M=1, m=0, layers=6, n_heads=4, head_dim=128, d_model=512, ffn=768, batch=3, s_in=20, steps=2)
+    desc, B = w.desc, w.batch
+    W = make_weights(desc, tp_slice(desc, 0, 6, 0, 1), w.seed)
+    toks = make_tokens(w.seed, B, w.s_in, desc["vocab"])
+    old = [ss.Shard(desc, tp_slice(desc, 3 * p, 3 * p + 3, m, 2), W, B, w.s_max) for p in range(2) for m in range(2)]
+    whole = ss.Shard(desc, tp_slice(desc, 0, 6, 0, 1), W, B, w.s_max)
+    quarters = [ss.Shard(desc, tp_slice(desc, 0, 6, m, 4), W, B, w.s_max) for m in range(4)]
+    cases = [(tp_slice(desc, 2 * p, 2 * p + 2, 0, 1), old[::-1]) for p in range(3)]              # (2,2) -> (3,1), sources in any order
+    cases += [(tp_slice(desc, 0, 6, m, 2), quarters) for m in range(2)]                          # merge 4 -> 2
+    cases += [(tp_slice(desc, 1, 5, 1, 4), [whole])]                                             # split out of the whole model
+    moved_total = 0
+    for slc, sources in cases:
+        a = ss.Shard.from_resident(desc, slc, sources, B, w.s_max)
+        b = ss.Shard(desc, slc, W, B, w.s_max)
+        assert a.bytes_copied > 0
+        moved_total += a.bytes_copied
+        assert torch.equal(a.model_context(), b.model_context())
+        # and they run: same bits out of both
+        outs = []
+        for sh in (a, b):
+            d = desc["d_model"]
+            first, last = slc["layer_lo"] == 0, slc["layer_hi"] == 6
+            hin = None if first else (torch.arange(B * w.s_in * d, device="cuda", dtype=torch.float32).reshape(B * w.s_in, d) % 7 - 3) * 0.1
+            hout = None if last else torch.empty(B * w.s_in, d, dtype=torch.float32, device="cuda")
+            logits = torch.empty(B, desc["vocab"], dtype=torch.float32, device="cuda") if last else None
+            ss.stage_prefill([sh], B, w.s_in, tokens=dev(toks) if first else None, hidden_in=hin, hidden_out=hout, logits=logits)
+            h1 = None if first else hin[:B].contiguous()
+            o1 = None if last else torch.empty(B, d, dtype=torch.float32, device="cuda")
+            ss.stage_decode_step([sh], B, tokens_in=dev(toks[:, 0]) if first else None, hidden_in=h1, hidden_out=o1, logits=logits)
+            torch.cuda.synchronize()
+            outs.append(((logits if last else hout).cpu().numpy().copy(), (logits if last else o1).cpu().numpy().copy(), ss.kv_export(sh)))
+        for x, y in zip(*outs):
+            assert np.array_equal(bits(x), bits(y))
+        a.destroy(); b.destroy()
+    # sources that do not cover the new slice are refused
+    with pytest.raises(ss.SpotShardError) as e:
+        ss.Shard.from_resident(desc, tp_slice(desc, 0, 6, 0, 1), old[:3], B, w.s_max)
+    assert e.value.status == 1
+    with pytest.raises(ss.SpotShardError) as e:
+        ss.Shard.from_resident(desc, tp_slice(desc, 0, 6, 0, 2), quarters[1:], B, w.s_max)
+    assert e.value.status == 1
+    for sh in old + quarters + [whole]:
+        sh.destroy()
+
+
 def test_ragged_lengths_and_row_independence(ss):
     """Rows at different positions in one batch (imported cache), each row matches the oracle."""
     import torch
