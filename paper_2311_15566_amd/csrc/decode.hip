@@ -22,59 +22,6 @@ __global__ void __launch_bounds__(256) embed_rows(EmbedArgs a) {
   embed_row_block<T>(a, blockIdx.x, scratch);
 }
 
-// a = Norm(x) for a tile of 16 token rows, written in operand order with `parts` fragments per k
-// block.  grid = row tiles, 4 waves; a wave owns whole 1 KiB fragments (lane = kq * 16 + row), so
-// every store is a full coalesced fragment.  Rows past `rows` are written as zeros.
-template <typename T>
-__global__ void __launch_bounds__(256) norm_rows(const float *x, const float *gamma, const float *beta, void *a_out,
-                                                 int rows, int d, int k_blocks, int parts, int rms, float eps) {
-  constexpr int PL = Elem<T>::kPerLane, FK = Elem<T>::kFragK;
-  __shared__ float red[4][16];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int r = lane & 15, kq = lane >> 4;
-  const int row = blockIdx.x * 16 + r;
-  const bool live = row < rows;
-  const float *xr = x + (size_t)row * d;
-  // the row's mean, then its centred second moment (two passes, as the definition has it);
-  // lane (kq, r) of wave w covers k blocks w, w + 4, ...; after the first pass the rows are L2 hits
-  float s1 = 0.f;
-  if (live && !rms)
-    for (int kb = wave; kb < k_blocks; kb += 4) {
-#pragma unroll
-      for (int e = 0; e < PL; ++e) s1 += xr[kb * FK + kq * PL + e];
-    }
-  auto tile_reduce = [&](float s) {
-    s += __shfl_xor(s, 16);
-    s += __shfl_xor(s, 32);
-    __syncthreads();  // the previous use of red is over
-    if (lane < 16) red[wave][lane] = s;
-    __syncthreads();
-    return red[0][r] + red[1][r] + red[2][r] + red[3][r];
-  };
-  float mean = 0.f;
-  if (!rms) mean = tile_reduce(s1) / (float)d;
-  float q = 0.f;
-  if (live)
-    for (int kb = wave; kb < k_blocks; kb += 4) {
-#pragma unroll
-      for (int e = 0; e < PL; ++e) {
-        const float c = xr[kb * FK + kq * PL + e] - mean;
-        q += c * c;
-      }
-    }
-  const float rstd = rsqrtf(tile_reduce(q) / (float)d + eps);
-  // normalise and write whole fragments
-  for (int kb = wave; kb < k_blocks; kb += 4) {
-    float y[PL];
-#pragma unroll
-    for (int e = 0; e < PL; ++e) {
-      const int k = kb * FK + kq * PL + e;
-      y[e] = live ? (xr[k] - mean) * rstd * gamma[k] + (beta ? beta[k] : 0.f) : 0.f;
-    }
-    store_piece<T>(a_out, blockIdx.x * 16 + r, kb * FK + kq * PL, k_blocks, y, parts);
-  }
-}
-
 // last prompt position of every sequence -> the decode step's residual rows, with the final
 // norm's operand (x * gamma) and the rows' (sum, sum of squares)
 template <typename T>
@@ -559,32 +506,43 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, c
     if (T > group[i]->L.Tmax) SS_FAIL(SS_EINVAL, "%d prompt tokens exceed group[%d]'s workspace (%d)", T_live, i, group[i]->L.Tmax);
   float *x = (float *)(g0->ws + L0.ws_x);
   void *abuf = g0->ws + L0.ws_a;
+  float2 *pstat = (float2 *)(g0->ws + L0.ws_pstat);
+  float2 *mr = pstat + (size_t)2 * ceil_div(d, 128) * L0.Tmax;  // (mean, rstd) per token
+  // Norms are deferred (see TileGemmArgs): the producer of x writes x * gamma as the next
+  // GEMM's operand and partial row sums; that GEMM's epilogue normalises.
+  // (single bf16 activations into the QKV / first FFN GEMMs were tried: the OPT-66B shape then
+  // misses the logits bar at its first token, 6.4e-2)
   {
-    EmbedArgs e{hidden_in, tokens, g0->wte, g0->wpe, nullptr, S, x, d, L0.V, nullptr, nullptr, nullptr};
+    EmbedArgs e{hidden_in, tokens, g0->wte, g0->wpe, nullptr, S, x, d, L0.V, g0->layers[0].ln1_g, abuf, nullptr, pstat};
     if (dt == SS_DTYPE_BF16) hipLaunchKernelGGL(embed_rows<bf16_t>, dim3(T_live), dim3(256), 0, st, e);
     else hipLaunchKernelGGL(embed_rows<float>, dim3(T_live), dim3(256), 0, st, e);
     SS_HIP(hipGetLastError());
   }
-  // (single bf16 activations into the QKV / first FFN GEMMs were tried: the OPT-66B shape then
-  // misses the logits bar at its first token, 6.4e-2)
-  const int nparts = parts;
-  auto norm = [&](const float *g, const float *b) -> ss_status {
-    if (dt == SS_DTYPE_BF16)
-      hipLaunchKernelGGL(norm_rows<bf16_t>, dim3(ceil_div(T_live, 16)), dim3(256), 0, st, x, g, b, abuf, T_live, d, d / FK, nparts, rms, m.norm_eps);
-    else
-      hipLaunchKernelGGL(norm_rows<float>, dim3(ceil_div(T_live, 16)), dim3(256), 0, st, x, g, b, abuf, T_live, d, d / FK, nparts, rms, m.norm_eps);
-    SS_HIP(hipGetLastError());
-    return SS_OK;
+  int stat_groups = 1;
+  auto normed = [&](TileGemmArgs &a, const float *wg, const float *cb) {
+    a.act = abuf, a.act_parts = parts, a.mr_in = mr, a.wg = wg, a.cb = cb;
+  };
+  auto row_stats = [&]() { return launch_row_stats(pstat, stat_groups, T, d, rms, m.norm_eps, mr, st); };
+  // sum over the group at a reduce slot: shard i adds its partial to what the previous shards left;
+  // the last one also emits the next operand and the partial sums
+  auto resid = [&](int i, const FragMat &w, const void *act, const float *bias, const float *next_gamma) -> ss_status {
+    TileGemmArgs a = {};
+    a.w = w.ptr, a.row_tiles = w.row_tiles, a.k_blocks = w.k_blocks;
+    a.act = act, a.act_parts = parts, a.T = T, a.T_live = T_live, a.N = d, a.bias = i == 0 ? bias : nullptr;
+    a.x_resid = x;
+    if (i == n_group - 1 && next_gamma) a.g_out = next_gamma, a.norm_out = abuf, a.norm_parts = parts, a.stat_out = pstat;
+    return launch_tile_gemm(dt, EPI_RESID, a, st);
   };
   for (int l = 0; l < L0.Ls; ++l) {
     const LayerDev &D0 = g0->layers[l];
-    SS_TRY(norm(D0.ln1_g, D0.ln1_b));
+    SS_TRY(row_stats());
     for (int i = 0; i < n_group; ++i) {
       Shard *s = group[i];
       const Layout &L = s->L;
       TileGemmArgs a = {};
       a.w = s->wqkv[l].ptr, a.row_tiles = s->wqkv[l].row_tiles, a.k_blocks = s->wqkv[l].k_blocks;
-      a.act = abuf, a.act_parts = nparts, a.T = T, a.T_live = T_live, a.N = L.qkv_n, a.bias = s->layers[l].bqkv;
+      a.T = T, a.T_live = T_live, a.N = L.qkv_n;
+      normed(a, s->wg_qkv[l], s->cb_qkv[l]);
       a.out_f32 = (float *)(s->ws + L.ws_qkv), a.ld_out = L.qkv_n;
       SS_TRY(launch_tile_gemm(dt, EPI_F32, a, st));
       PrefillAttnArgs p = {};
@@ -597,35 +555,23 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, c
       SS_TRY(launch_prefill_kv_write(dt, p, st));
       SS_TRY(launch_prefill_attn(dt, p, st));
     }
-    for (int i = 0; i < n_group; ++i) {
-      Shard *s = group[i];
-      const Layout &L = s->L;
-      TileGemmArgs a = {};
-      a.w = s->wo[l].ptr, a.row_tiles = s->wo[l].row_tiles, a.k_blocks = s->wo[l].k_blocks;
-      a.act = s->ws + L.ws_o, a.act_parts = parts, a.T = T, a.T_live = T_live, a.N = d, a.bias = i == 0 ? D0.bo : nullptr;
-      a.x_resid = x;
-      SS_TRY(launch_tile_gemm(dt, EPI_RESID, a, st));
-    }
-    SS_TRY(norm(D0.ln2_g, D0.ln2_b));
+    stat_groups = 2 * ceil_div(d / 16, 8);  // from here on: one partial per 64-feature band of the residual GEMMs
+    for (int i = 0; i < n_group; ++i) SS_TRY(resid(i, group[i]->wo[l], group[i]->ws + group[i]->L.ws_o, D0.bo, D0.ln2_g));
+    SS_TRY(row_stats());
     for (int i = 0; i < n_group; ++i) {
       Shard *s = group[i];
       const Layout &L = s->L;
       const bool glu = m.act == SS_ACT_SWIGLU;
       TileGemmArgs a = {};
       a.w = s->w1[l].ptr, a.row_tiles = s->w1[l].row_tiles, a.k_blocks = s->w1[l].k_blocks;
-      a.act = abuf, a.act_parts = nparts, a.T = T, a.T_live = T_live, a.N = L.Fs, a.bias = s->layers[l].b1;
+      a.T = T, a.T_live = T_live, a.N = L.Fs;
+      normed(a, s->wg_1[l], s->cb_1[l]);
       a.act_out = s->ws + L.ws_u, a.out_k_blocks = L.Fs / FK, a.out_parts = parts, a.act_kind = m.act;
       SS_TRY(launch_tile_gemm(dt, glu ? EPI_SWIGLU : EPI_ACT, a, st));
     }
-    for (int i = 0; i < n_group; ++i) {
-      Shard *s = group[i];
-      const Layout &L = s->L;
-      TileGemmArgs a = {};
-      a.w = s->w2[l].ptr, a.row_tiles = s->w2[l].row_tiles, a.k_blocks = s->w2[l].k_blocks;
-      a.act = s->ws + L.ws_u, a.act_parts = parts, a.T = T, a.T_live = T_live, a.N = d, a.bias = i == 0 ? D0.b2 : nullptr;
-      a.x_resid = x;
-      SS_TRY(launch_tile_gemm(dt, EPI_RESID, a, st));
-    }
+    // the last layer's output goes to the next stage or to gather_last, which read x
+    const float *next_gamma = l + 1 < L0.Ls ? g0->layers[l + 1].ln1_g : nullptr;
+    for (int i = 0; i < n_group; ++i) SS_TRY(resid(i, group[i]->w2[l], group[i]->ws + group[i]->L.ws_u, D0.b2, next_gamma));
   }
   if (hidden_out) {  // a stage that hands its hidden states on: copy them out, then commit
     SS_HIP(hipMemcpyAsync(hidden_out, x, (size_t)T_live * d * 4, hipMemcpyDeviceToDevice, st));

@@ -97,36 +97,76 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
   }
 
   const int q4 = (lane >> 4) * 4, tl = lane & 15;
+  const float *cbp = a.mr_in ? a.cb : a.bias;
+  const float *wgp = a.mr_in ? a.wg : nullptr;
+  // the product of weight row n0 + e and this lane's token, with the deferred norm and the bias applied
+  auto finish = [&](const f32x4 &c, const int n0, const float2 mr, float (&v)[4]) {
+    f32x4 wg = {0.f, 0.f, 0.f, 0.f}, cb = {0.f, 0.f, 0.f, 0.f};
+    if (wgp) wg = *(const f32x4 *)(wgp + n0);
+    if (cbp) cb = *(const f32x4 *)(cbp + n0);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = mr.y * (c[e] - mr.x * wg[e]) + cb[e];
+  };
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int tok = (tt0 + wc * 4 + j) * 16 + tl;
+    const bool tok_live = tok < a.T_live;
     if (EPI == EPI_SWIGLU) {
+      const float2 mr = a.mr_in ? a.mr_in[tok] : make_float2(0.f, 1.f);
 #pragma unroll
       for (int i = 0; i < 4; i += 2) {
         const int rt = rt0 + wr * 4 + i;  // gate tile; rt + 1 is the matching up tile
         const int n0 = (rt >> 1) * 16 + q4;
-        if (rt + 1 < a.row_tiles && n0 < a.N) {
-          float u[4];
+        if (tok_live && rt + 1 < a.row_tiles && n0 < a.N) {
+          float gt[4], up[4], u[4];
+          finish(acc[i][j], rt * 16 + q4, mr, gt);
+          finish(acc[i + 1][j], (rt + 1) * 16 + q4, mr, up);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) u[e] = silu_f(acc[i][j][e]) * acc[i + 1][j][e];
+          for (int e = 0; e < 4; ++e) u[e] = silu_f(gt[e]) * up[e];
           store4_frag<T, false>(a.act_out, tok, n0, a.out_k_blocks, a.out_parts, u);
         }
       }
-    } else {
+    } else if (EPI == EPI_RESID) {
+      float s1 = 0.f, s2 = 0.f;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int rt = rt0 + wr * 4 + i;
         const int n0 = rt * 16 + q4;
-        if (rt < a.row_tiles && n0 < a.N) {
+        if (tok_live && rt < a.row_tiles && n0 < a.N) {
+          f32x4 *xp = (f32x4 *)(a.x_resid + (size_t)tok * a.N + n0);
+          const f32x4 x = *xp;
           float v[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = acc[i][j][e] + (a.bias ? a.bias[n0 + e] : 0.f);
+          for (int e = 0; e < 4; ++e) v[e] = x[e] + (acc[i][j][e] + (a.bias ? a.bias[n0 + e] : 0.f));
+          *xp = f32x4{v[0], v[1], v[2], v[3]};
+          if (a.g_out) {
+            const f32x4 g = *(const f32x4 *)(a.g_out + n0);
+            float y[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              s1 += v[e], s2 += v[e] * v[e];
+              y[e] = v[e] * g[e];
+            }
+            store4_frag<T, false>(a.norm_out, tok, n0, a.N / Elem<T>::kFragK, a.norm_parts, y);
+          }
+        }
+      }
+      if (a.g_out) {  // the wave's 64 features of this token
+        s1 += __shfl_xor(s1, 16), s2 += __shfl_xor(s2, 16);
+        s1 += __shfl_xor(s1, 32), s2 += __shfl_xor(s2, 32);
+        if (lane < 16) a.stat_out[(size_t)(rb * 2 + wr) * a.T + tok] = make_float2(s1, s2);
+      }
+    } else {
+      const float2 mr = a.mr_in ? a.mr_in[tok] : make_float2(0.f, 1.f);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int rt = rt0 + wr * 4 + i;
+        const int n0 = rt * 16 + q4;
+        if (tok_live && rt < a.row_tiles && n0 < a.N) {
+          float v[4];
+          finish(acc[i][j], n0, mr, v);
           if (EPI == EPI_F32) {
             *(f32x4 *)(a.out_f32 + (size_t)tok * a.ld_out + n0) = f32x4{v[0], v[1], v[2], v[3]};
-          } else if (EPI == EPI_RESID) {
-            f32x4 *xp = (f32x4 *)(a.x_resid + (size_t)tok * a.N + n0);
-            f32x4 x = *xp;
-            *xp = f32x4{x[0] + v[0], x[1] + v[1], x[2] + v[2], x[3] + v[3]};
           } else {  // EPI_ACT
             const float w[4] = {act_apply(a.act_kind, v[0]), act_apply(a.act_kind, v[1]), act_apply(a.act_kind, v[2]),
                                 act_apply(a.act_kind, v[3])};
@@ -138,6 +178,42 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
   }
 }
 
+__global__ void __launch_bounds__(256) row_stats(const float2 *part, int groups, int T, float inv_dim, int rms, float eps,
+                                                 float2 *mr) {
+  const int tok = blockIdx.x * 256 + threadIdx.x;
+  if (tok >= T) return;
+  float u1 = 0.f, u2 = 0.f;
+  int g = 0;
+  for (; g + 8 <= groups; g += 8) {  // eight loads in flight; the sums stay in group order
+    float2 v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = part[(size_t)(g + i) * T + tok];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) u1 += v[i].x, u2 += v[i].y;
+  }
+  for (; g < groups; ++g) {
+    const float2 v = part[(size_t)g * T + tok];
+    u1 += v.x, u2 += v.y;
+  }
+  const float ms = u2 * inv_dim;
+  float mean = 0.f, rstd;
+  if (rms) {
+    rstd = rsqrtf(ms + eps);
+  } else {
+    mean = u1 * inv_dim;
+    rstd = rsqrtf(fmaxf(ms - mean * mean, 0.f) + eps);
+  }
+  mr[tok] = make_float2(mean, rstd);
+}
+
+ss_status launch_row_stats(const float2 *part, int groups, int T, int norm_dim, int rms, float eps, float2 *mr,
+                           hipStream_t st) {
+  if (!part || !mr || groups < 1 || T < 1 || norm_dim < 1) SS_FAIL(SS_EINVAL, "row statistics: bad arguments");
+  hipLaunchKernelGGL(row_stats, dim3(ceil_div(T, 256)), dim3(256), 0, st, part, groups, T, 1.0f / (float)norm_dim, rms, eps, mr);
+  SS_HIP(hipGetLastError());
+  return SS_OK;
+}
+
 ss_status launch_tile_gemm(int dtype, int epi, TileGemmArgs a, hipStream_t st) {
   if (a.T < 128 || a.T % 128) SS_FAIL(SS_EINVAL, "prefill GEMM: token count %d is not a multiple of 128", a.T);
   if (a.row_tiles < 1 || a.k_blocks < 1 || a.N % 4) SS_FAIL(SS_EINVAL, "prefill GEMM: bad shape");
@@ -145,6 +221,12 @@ ss_status launch_tile_gemm(int dtype, int epi, TileGemmArgs a, hipStream_t st) {
   if (a.act_parts != 1 && !(a.act_parts == 2 && dtype == SS_DTYPE_BF16)) SS_FAIL(SS_EINVAL, "prefill GEMM: bad act_parts");
   if ((epi == EPI_ACT || epi == EPI_SWIGLU) && a.out_parts != 1 && !(a.out_parts == 2 && dtype == SS_DTYPE_BF16))
     SS_FAIL(SS_EINVAL, "prefill GEMM: bad out_parts");
+  if (epi == EPI_RESID && a.g_out) {
+    const int fk = dtype == SS_DTYPE_BF16 ? 32 : 16;
+    if (!a.norm_out || !a.stat_out || a.N % fk || a.N != a.row_tiles * 16 ||
+        (a.norm_parts != 1 && !(a.norm_parts == 2 && dtype == SS_DTYPE_BF16)))
+      SS_FAIL(SS_EINVAL, "prefill GEMM: bad next-operand arguments");
+  }
   a.n_row_blocks = ceil_div(a.row_tiles, 8);
   dim3 grid(a.n_row_blocks * (a.T / 128));
 #define SS_LAUNCH(TT, EPI, AP) hipLaunchKernelGGL((tile_gemm<TT, EPI, AP>), grid, dim3(256), 0, st, a)

@@ -63,6 +63,11 @@ ss_status launch_fold_norm(int dtype, const void *w, int row_tiles, int k_blocks
                            const float *bias, float *wg, float *cb, hipStream_t st);
 
 // Prefill GEMM: out[t, n] = sum_k act[t, k] * W[n, k] over T tokens (multiple of 128), MFMA-bound.
+// Norms are deferred as in the decode GEMM: the residual epilogue of the last shard of a group
+// also writes the next GEMM's operand x * gamma and, per token, the partial (sum x, sum x^2) of
+// each 64-feature band a wave owns; a small kernel adds the partials up in band order into the
+// token's (mean, rstd), and the GEMM that consumes the operand applies
+// rstd * (acc - mean * wg[n]) + cb[n].  Tokens past T_live are computed but never stored.
 struct TileGemmArgs {
   const void *w;      // weight fragments
   int row_tiles;      // 16-row weight tiles (SwiGLU: 2 per 16 outputs, interleaved)
@@ -72,10 +77,18 @@ struct TileGemmArgs {
   int T;              // tokens (padded to 128)
   int T_live;         // tokens that exist
   int N;
-  const float *bias;
+  const float *bias;  // plain bias (mr_in NULL), or NULL
+  // deferred normalisation of the input (mr_in != NULL): bias is not read
+  const float2 *mr_in;    // [T] (mean, rstd) of the rows of x
+  const float *wg;    // [row_tiles * 16] or NULL (RMSNorm)
+  const float *cb;    // [row_tiles * 16] folded beta and bias, or the plain bias, or NULL
   float *out_f32;     // EPI_F32: [T][ld_out]
   int ld_out;
   float *x_resid;     // EPI_RESID: [T][N]
+  const float *g_out; // EPI_RESID: gamma of the norm that follows, or NULL: no operand for a next GEMM
+  void *norm_out;     // EPI_RESID with g_out: x * g_out as fragments [T/16][N / FragK][norm_parts]
+  int norm_parts;
+  float2 *stat_out;   // EPI_RESID with g_out: [2 * n_row_blocks][T]
   void *act_out;      // EPI_ACT / EPI_SWIGLU: fragments [T/16][out_k_blocks][out_parts]
   int out_k_blocks;
   int out_parts;
@@ -83,6 +96,9 @@ struct TileGemmArgs {
   int n_row_blocks;   // set by the launcher: 128-row blocks of the weight matrix
 };
 ss_status launch_tile_gemm(int dtype, int epi, TileGemmArgs a, hipStream_t st);
+// (mean, rstd) per token from `groups` partial (sum, sum of squares) pairs laid out [groups][T]
+ss_status launch_row_stats(const float2 *part, int groups, int T, int norm_dim, int rms, float eps, float2 *mr,
+                           hipStream_t st);
 
 // Decode attention over the committed cache (plus the new token), sequence-split.
 struct DecodeAttnArgs {
@@ -112,10 +128,12 @@ struct EmbedArgs {
   int S;
   float *x;               // [rows][d]
   int d, V;
-  // decode step only (NULL in the initial phase): operand of the first GEMM and its row sums
+  // operand of the first GEMM (x * gamma) and, in the decode step, its row sums
   const float *gamma;     // gamma of the first norm
   void *act_out;          // x * gamma as operand fragments [rows / 16][d / FragK][parts]
   float *stat_out;        // [32][4] (sum x, sum x^2, 0, 0) per row
+  // initial phase: the same operand for all prompt tokens, and the row sums as one group of partials
+  float2 *pstat_out;      // [rows] (sum x, sum x^2), or NULL
 };
 
 struct Phase {

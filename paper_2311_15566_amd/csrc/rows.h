@@ -94,10 +94,13 @@ __device__ __forceinline__ void embed_row_block(const EmbedArgs &a, const int r,
       }
     }
   }
-  if (a.stat_out) {
+  if (a.stat_out || a.pstat_out) {
     s1 = block_sum(s1, scratch);
     s2 = block_sum(s2, scratch);
-    if (threadIdx.x == 0) ((f32x4 *)a.stat_out)[r] = f32x4{s1, s2, 0.f, 0.f};
+    if (threadIdx.x == 0) {
+      if (a.stat_out) ((f32x4 *)a.stat_out)[r] = f32x4{s1, s2, 0.f, 0.f};
+      if (a.pstat_out) a.pstat_out[r] = make_float2(s1, s2);
+    }
   }
 }
 

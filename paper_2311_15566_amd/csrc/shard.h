@@ -18,7 +18,7 @@ struct Layout {
   int Ls, Hs, Fs, d, Dh, V, max_pos, Bmax, Smax;
   int esz;             // bytes per element of the model dtype
   int Bpad;            // max_batch rounded up to 16
-  int Tmax;            // prefill tokens the workspace holds (Bmax*Smax rounded up to 16)
+  int Tmax;            // prefill tokens the workspace holds (Bmax*Smax rounded up to 128)
   int qkv_n;           // 3*Hs*Dh
   int w1_rows;         // Fs or 2*Fs
   int attn_splits;     // sequence splits of decode attention at Smax
@@ -33,6 +33,7 @@ struct Layout {
   size_t off_ws, ws_bytes;             // workspace, doubles as upload staging
   // workspace sub-offsets (relative to off_ws)
   size_t ws_x, ws_a, ws_qkv, ws_o, ws_u, ws_counters, ws_attn_part, ws_argmax;
+  size_t ws_pstat;     // initial phase: partial row sums [2 * ceil(d / 128)][Tmax] float2, then (mean, rstd) [Tmax]
   int n_counters;
   // decode step (rows = batch): residual stream [32][d] f32, operand of the next normalised GEMM
   // (x * gamma), partial row sums [d/16][32][2], q|k|v [32][qkv_n] f32, attention output and FFN

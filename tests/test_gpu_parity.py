@@ -59,7 +59,7 @@ def bits(a):
     return a.view(np.uint16) if a.dtype.itemsize == 2 else a.view(np.uint32)
 
 
-def check_logits(got, ref, bf16, what=""):
+def check_logits(got, ref, bf16, what="", f32_rel=1e-5):
     ref = np.asarray(ref, dtype=np.float64)
     got = np.asarray(got, dtype=np.float64)
     err = np.abs(got - ref).max()
@@ -67,7 +67,7 @@ def check_logits(got, ref, bf16, what=""):
     if bf16:
         assert err < MAX_ABS and rel < REL_L2, f"{what}: max-abs {err:.3e} rel-L2 {rel:.3e}"
     else:
-        assert err < 1e-4 and rel < 1e-5, f"{what}: max-abs {err:.3e} rel-L2 {rel:.3e}"
+        assert err < 1e-4 and rel < f32_rel, f"{what}: max-abs {err:.3e} rel-L2 {rel:.3e}"
     return err, rel
 
 
@@ -148,7 +148,9 @@ CASES = [
     # residual rows whose mean is ~25x their spread: the normalisation is applied after the GEMM
     # (acc - mean * folded gamma), which must not lose the signal to cancellation
     ("gpt20b_m4", "bf16", dict(batch=6, s_in=40, steps=4, wte_offset=0.5)),
-    ("gpt20b_m4", "f32", dict(batch=2, s_in=20, steps=3, wte_offset=0.5)),
+    # (float32: acc and mean * folded gamma are each ~25x the result and the variance is the difference of two
+    # numbers ~625x its size, so float32 rounding of ~1e-7 shows up ~25-600x larger: bar 3e-5 instead of 1e-5)
+    ("gpt20b_m4", "f32", dict(batch=2, s_in=20, steps=3, wte_offset=0.5, f32_rel=3e-5)),
     ("llama30b_m2", "bf16", dict(batch=4, s_in=40, steps=3, wte_offset=0.5)),
 ]
 
@@ -159,6 +161,7 @@ def test_scaled_family_teacher_forced(ss, name, dtype, kw, side_stream):
     kw = dict(kw)
     kv_dtype = kw.pop("kv_dtype", None)
     wte_offset = kw.pop("wte_offset", 0.0)
+    f32_rel = kw.pop("f32_rel", 1e-5)
     w = scaled(name, dtype, **kw)
     if kv_dtype:
         w.desc["kv_dtype"] = kv_dtype
@@ -179,13 +182,13 @@ def test_scaled_family_teacher_forced(ss, name, dtype, kw, side_stream):
     nxt = torch.empty(w.batch, dtype=torch.int32, device="cuda")
     ref = D.prefill_matrix([ora], toks)
     ss.prefill([sh], dev(toks), logits, nxt)
-    check_logits(logits.cpu().numpy(), ref, bf16, "prefill")
+    check_logits(logits.cpu().numpy(), ref, bf16, "prefill", f32_rel)
     check_ids(nxt.cpu().numpy(), ref, "prefill")
     for step in range(w.steps):
         tok = D.greedy(ref)                              # teacher forcing: the oracle's token
         ref = D.decode_step([ora], tok)
         ss.decode_step([sh], dev(tok), logits, nxt)
-        check_logits(logits.cpu().numpy(), ref, bf16, f"step {step}")
+        check_logits(logits.cpu().numpy(), ref, bf16, f"step {step}", f32_rel)
         check_ids(nxt.cpu().numpy(), ref, f"step {step}")
     assert list(ss.committed_len(sh)) == [w.s_in + w.steps] * w.batch
     # the cache the GPU built equals the oracle's up to the cache precision
