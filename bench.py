@@ -231,6 +231,30 @@ def main():
             out["prefill"] = dict(ms=prefill_ms, tokens=w.batch * w.s_in, TFLOPs=fl / (prefill_ms * 1e-3) / 1e12,
                                   peak=peak, frac=fl / (prefill_ms * 1e-3) / 1e12 / peak)
 
+            # ---- measured cost model (Section 5; Eq. 1): iteration time over context length, from this run ----
+            if K >= 32:
+                from paper_2311_15566_amd import plan as P
+                fresh()
+                chunk = max(8, K // 8)
+                marks = [torch.cuda.Event(enable_timing=True) for _ in range(K // chunk + 1)]
+                marks[0].record()
+                for i in range(K // chunk):
+                    for _ in range(chunk):
+                        ss.decode_step([sh], nxt, logits, nxt)
+                    marks[i + 1].record()
+                torch.cuda.synchronize()
+                samples = [(w.batch, w.s_in + i * chunk + chunk // 2, marks[i].elapsed_time(marks[i + 1]) / chunk)
+                           for i in range(K // chunk)]
+                cm = P.cost_fit(samples, [(w.batch, w.s_in, prefill_ms)])
+                steps_fit = (K // chunk) * chunk
+                l_exe = P.cost_l_exe(cm, w.batch, w.s_in, steps_fit)
+                measured = prefill_ms + sum(ms * chunk for _, _, ms in samples)
+                out["cost_model"] = dict(dec_base_ms=cm.dec_base_ms[0], dec_per_cached_token_us=cm.dec_per_row_ms[0] * 1e3,
+                                         prefill_ms_per_token=cm.pre_per_token_ms[0], samples=len(samples),
+                                         l_exe_ms=l_exe[-1], measured_ms=measured, s_in=w.s_in, s_out=steps_fit,
+                                         note="least-squares line through the mean iteration time of each run of "
+                                              f"{chunk} steps; l_exe = Eq. (1) from the fit, measured = the same steps timed")
+
             # ---- KV re-partition of this shard's cache into two half-width shards ----
             g = shard_dims(w)
             if g["Hs"] % 2 == 0 and g["Fs"] % 128 == 0:

@@ -1,8 +1,8 @@
 /*
  * spotshard - host-side planning for a change of parallel configuration (after SpotServe,
  * arXiv 2311.15566): how much context two positions share, which device should take which
- * position, in what order the layers' context moves, which requests keep their cache, and how
- * many decoding iterations fit into a grace period.  Plain host arithmetic on small inputs: no
+ * position, in what order the layers' context moves, which requests keep their cache, how
+ * many decoding iterations fit into a grace period, and what an inference costs.  Plain host arithmetic on small inputs: no
  * GPU, no allocation that outlives a call; every pointer is a host pointer.  Same ss_status and
  * ss_last_error() as spotshard.h.
  */
@@ -65,6 +65,39 @@ ss_status ss_rows_to_keep(int32_t n_rows, const int32_t *lens, int32_t keep, int
  * with l_exe[S] >= t_grace (s_out if none).  If t_mig >= l_exe[S] the arrangement would only add
  * latency and 0 is returned (re-route instead). */
 int32_t ss_jit_iterations(int32_t acquisition, int32_t s_out, const double *l_exe, double t_grace, double t_mig);
+
+/* Measured cost model (Section 5: a cost model and an offline profiler estimate the inference
+ * latency in advance; here the profile is a handful of timings taken on the running shard).
+ * t_exe of Eq. (1): the initial phase over s_in tokens per sequence costs
+ * pre_base_ms + pre_per_token_ms * s_in, an incremental iteration with n tokens already cached
+ * costs dec_base_ms + dec_per_row_ms * n (the weights are streamed once whatever n is, the cache
+ * rows once each: both terms are linear).  One line per batch size, fitted by least squares;
+ * between two fitted batch sizes the predicted times are interpolated linearly, outside them the
+ * nearest one is used. */
+enum { SS_COST_MAX_BATCHES = 16 };
+typedef struct {
+  int32_t batch;    /* sequences in the batch */
+  int32_t length;   /* decode sample: tokens already cached; initial-phase sample: s_in */
+  double ms;        /* measured time of one iteration (or the mean of several around `length`) */
+} ss_cost_sample;
+typedef struct {
+  int32_t n_batches;
+  int32_t batch[SS_COST_MAX_BATCHES];   /* ascending */
+  double dec_base_ms[SS_COST_MAX_BATCHES], dec_per_row_ms[SS_COST_MAX_BATCHES];
+  double pre_base_ms[SS_COST_MAX_BATCHES], pre_per_token_ms[SS_COST_MAX_BATCHES];
+} ss_cost_model;
+
+/* Least-squares lines through the samples of each batch size.  A batch size with samples at one
+ * length only gets a constant (decode) or a line through the origin (initial phase); a batch
+ * size needs at least one decode sample, without initial-phase samples its two initial-phase
+ * coefficients are 0.  At most SS_COST_MAX_BATCHES distinct batch sizes.  Caller owns everything. */
+ss_status ss_cost_fit(const ss_cost_sample *decode, int32_t n_decode, const ss_cost_sample *prefill, int32_t n_prefill,
+                      ss_cost_model *model);
+
+/* Eq. (1): l_exe[S] = t_exe(s_in) + sum_{i=1..S} t_exe(s_in + i) for S = 0 .. s_out, in ms: the
+ * table ss_jit_iterations takes.  The i-th incremental iteration runs with s_in + i - 1 tokens
+ * cached.  With dec_per_row_ms = 0 this is Eq. (2). */
+ss_status ss_cost_l_exe(const ss_cost_model *model, int32_t batch, int32_t s_in, int32_t s_out, double *l_exe);
 
 #ifdef __cplusplus
 }

@@ -129,3 +129,38 @@ def jit_iterations(acquisition, l_exe, t_grace, t_mig):
         lasts = [S for S in range(s_out + 1) if l_exe[S] >= t_grace]
         s = min(lasts) if lasts else s_out
     return s if t_mig < l_exe[s] else 0
+
+
+def cost_fit(decode, prefill=()):
+    """Section 5's cost model from measured samples (batch, length, ms): per batch size the
+    least-squares line of an incremental iteration's time over the cached length and of the
+    initial phase's time over the prompt length (numpy's polynomial fit).  Samples at a single
+    length give a constant (decode) or a line through the origin (initial phase)."""
+    model = {}
+    for b in sorted({s[0] for s in decode}):
+        def line(samples, through_origin):
+            x = np.array([s[1] for s in samples if s[0] == b], dtype=np.float64)
+            y = np.array([s[2] for s in samples if s[0] == b], dtype=np.float64)
+            if len(x) == 0:
+                return 0.0, 0.0
+            if len(set(x.tolist())) > 1:
+                c1, c0 = np.polyfit(x, y, 1)
+                return float(c0), float(c1)
+            return (0.0, float(y.mean() / x.mean())) if through_origin else (float(y.mean()), 0.0)
+        model[b] = dict(dec=line(decode, False), pre=line(prefill, True))
+    return model
+
+
+def cost_l_exe(model, batch, s_in, s_out):
+    """Eq. (1) as written: the initial phase, then one incremental iteration per output token,
+    the i-th with s_in + i - 1 tokens cached; times of a batch size between two fitted ones are
+    interpolated linearly, outside them the nearest is taken."""
+    bs = sorted(model)
+
+    def t(kind, x):
+        vals = [model[b][kind][0] + model[b][kind][1] * x for b in bs]
+        return float(np.interp(batch, bs, vals))
+    out = [t("pre", s_in)]
+    for i in range(1, s_out + 1):
+        out.append(out[-1] + t("dec", s_in + i - 1))
+    return out

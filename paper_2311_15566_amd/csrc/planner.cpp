@@ -1,10 +1,11 @@
 // Host-side planning for a change of parallel configuration: context overlap, device mapping
-// (Kuhn-Munkres), migration order, cache discard, just-in-time arrangement.  No GPU.
+// (Kuhn-Munkres), migration order, cache discard, just-in-time arrangement, measured cost model.  No GPU.
 #include <stdint.h>
 
 #include <algorithm>
 #include <limits>
 #include <numeric>
+#include <utility>
 #include <vector>
 
 #include "../../include/spotshard_plan.h"
@@ -185,6 +186,77 @@ int32_t ss_jit_iterations(int32_t acquisition, int32_t s_out, const double *l_ex
       }
   }
   return t_mig < l_exe[s] ? s : 0;
+}
+
+// least-squares line y = c0 + c1 * x through the points; one distinct x: a constant (through_origin: c1 = y / x)
+static void fit_line(const std::vector<std::pair<double, double>> &pts, bool through_origin, double *c0, double *c1) {
+  double mx = 0, my = 0;
+  for (auto &p : pts) mx += p.first, my += p.second;
+  mx /= (double)pts.size(), my /= (double)pts.size();
+  double sxx = 0, sxy = 0;
+  for (auto &p : pts) sxx += (p.first - mx) * (p.first - mx), sxy += (p.first - mx) * (p.second - my);
+  if (sxx > 0) {
+    *c1 = sxy / sxx, *c0 = my - *c1 * mx;
+  } else if (through_origin && mx > 0) {
+    *c0 = 0, *c1 = my / mx;
+  } else {
+    *c0 = my, *c1 = 0;
+  }
+}
+
+ss_status ss_cost_fit(const ss_cost_sample *decode, int32_t n_decode, const ss_cost_sample *prefill, int32_t n_prefill,
+                      ss_cost_model *model) {
+  if (!model || n_decode < 1 || !decode || n_prefill < 0 || (n_prefill && !prefill)) SS_FAIL(SS_EINVAL, "bad arguments");
+  std::vector<int> batches;
+  for (int i = 0; i < n_decode; ++i) {
+    if (decode[i].batch < 1 || decode[i].length < 0 || !(decode[i].ms >= 0)) SS_FAIL(SS_EINVAL, "bad decode sample %d", i);
+    batches.push_back(decode[i].batch);
+  }
+  std::sort(batches.begin(), batches.end());
+  batches.erase(std::unique(batches.begin(), batches.end()), batches.end());
+  if ((int)batches.size() > SS_COST_MAX_BATCHES) SS_FAIL(SS_EINVAL, "more than %d batch sizes", SS_COST_MAX_BATCHES);
+  for (int i = 0; i < n_prefill; ++i) {
+    if (prefill[i].length < 1 || !(prefill[i].ms >= 0)) SS_FAIL(SS_EINVAL, "bad initial-phase sample %d", i);
+    if (!std::binary_search(batches.begin(), batches.end(), prefill[i].batch))
+      SS_FAIL(SS_EINVAL, "initial-phase sample %d: batch size %d has no decode sample", i, prefill[i].batch);
+  }
+  *model = ss_cost_model{};
+  model->n_batches = (int)batches.size();
+  for (int b = 0; b < model->n_batches; ++b) {
+    model->batch[b] = batches[b];
+    std::vector<std::pair<double, double>> pts;
+    for (int i = 0; i < n_decode; ++i)
+      if (decode[i].batch == batches[b]) pts.push_back({(double)decode[i].length, decode[i].ms});
+    fit_line(pts, false, &model->dec_base_ms[b], &model->dec_per_row_ms[b]);
+    pts.clear();
+    for (int i = 0; i < n_prefill; ++i)
+      if (prefill[i].batch == batches[b]) pts.push_back({(double)prefill[i].length, prefill[i].ms});
+    if (!pts.empty()) fit_line(pts, true, &model->pre_base_ms[b], &model->pre_per_token_ms[b]);
+  }
+  return SS_OK;
+}
+
+ss_status ss_cost_l_exe(const ss_cost_model *model, int32_t batch, int32_t s_in, int32_t s_out, double *l_exe) {
+  if (!model || !l_exe || model->n_batches < 1 || model->n_batches > SS_COST_MAX_BATCHES || batch < 1 || s_in < 1 || s_out < 0)
+    SS_FAIL(SS_EINVAL, "bad arguments");
+  // the fitted batch sizes around `batch` and the weight of the upper one
+  int hi = 0;
+  while (hi < model->n_batches && model->batch[hi] < batch) ++hi;
+  int lo = hi;
+  double w = 0;
+  if (hi == model->n_batches) {
+    lo = hi = model->n_batches - 1;
+  } else if (model->batch[hi] != batch && hi > 0) {
+    lo = hi - 1;
+    w = (double)(batch - model->batch[lo]) / (double)(model->batch[hi] - model->batch[lo]);
+  }
+  auto mix = [&](const double *base, const double *slope, double x) {
+    return (1 - w) * (base[lo] + slope[lo] * x) + w * (base[hi] + slope[hi] * x);
+  };
+  l_exe[0] = mix(model->pre_base_ms, model->pre_per_token_ms, (double)s_in);
+  for (int i = 1; i <= s_out; ++i)
+    l_exe[i] = l_exe[i - 1] + mix(model->dec_base_ms, model->dec_per_row_ms, (double)(s_in + i - 1));
+  return SS_OK;
 }
 
 }  // extern "C"

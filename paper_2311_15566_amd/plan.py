@@ -15,6 +15,20 @@ lib.ss_progressive_plan.argtypes = [i32, C.POINTER(i32), C.POINTER(i32), i32, C.
 lib.ss_rows_to_keep.argtypes = [i32, C.POINTER(i32), i32, i32, C.POINTER(i32)]
 lib.ss_jit_iterations.argtypes = [i32, i32, C.POINTER(C.c_double), C.c_double, C.c_double]
 lib.ss_jit_iterations.restype = i32
+
+
+class CostSample(C.Structure):
+    _fields_ = [("batch", i32), ("length", i32), ("ms", C.c_double)]
+
+
+class CostModel(C.Structure):
+    _fields_ = [("n_batches", i32), ("batch", i32 * 16), ("dec_base_ms", C.c_double * 16), ("dec_per_row_ms", C.c_double * 16),
+                ("pre_base_ms", C.c_double * 16), ("pre_per_token_ms", C.c_double * 16)]
+
+
+lib.ss_cost_fit.argtypes = [C.POINTER(CostSample), i32, C.POINTER(CostSample), i32, C.POINTER(CostModel)]
+lib.ss_cost_l_exe.argtypes = [C.POINTER(CostModel), i32, i32, i32, C.POINTER(C.c_double)]
+lib.ss_cost_fit.restype = lib.ss_cost_l_exe.restype = i32
 for f in (lib.ss_context_overlap, lib.ss_match_devices, lib.ss_migration_order, lib.ss_progressive_plan, lib.ss_rows_to_keep):
     f.restype = i32
 
@@ -63,3 +77,18 @@ def rows_to_keep(lens, keep: int, n_dst: int):
 def jit_iterations(acquisition: bool, l_exe, t_grace: float, t_mig: float) -> int:
     t = (C.c_double * len(l_exe))(*[float(v) for v in l_exe])
     return int(lib.ss_jit_iterations(int(acquisition), len(l_exe) - 1, t, float(t_grace), float(t_mig)))
+
+
+def cost_fit(decode, prefill=()) -> CostModel:
+    """decode / prefill: sequences of (batch, length, ms)."""
+    d = (CostSample * len(decode))(*[CostSample(int(b), int(n), float(ms)) for b, n, ms in decode])
+    p = (CostSample * max(len(prefill), 1))(*[CostSample(int(b), int(n), float(ms)) for b, n, ms in prefill])
+    m = CostModel()
+    _check(lib.ss_cost_fit(d, len(decode), p, len(prefill), C.byref(m)))
+    return m
+
+
+def cost_l_exe(model: CostModel, batch: int, s_in: int, s_out: int):
+    out = (C.c_double * (s_out + 1))()
+    _check(lib.ss_cost_l_exe(C.byref(model), batch, s_in, s_out, out))
+    return list(out)

@@ -209,3 +209,65 @@ def test_jit_iterations():
         t = np.concatenate([[0.0], np.cumsum(rng.uniform(0.01, 1.0, size=n))])
         args = (bool(rng.integers(0, 2)), list(t), float(rng.uniform(0, 12)), float(rng.uniform(0, 3)))
         assert P.jit_iterations(*args) == O.jit_iterations(*args)
+
+
+# ----------------------------------------------------------------------------
+# measured cost model (Section 5) and Eq. (1) / Eq. (2)
+# ----------------------------------------------------------------------------
+def test_cost_model_pins():
+    """The oracle against what the mathematics fixes: exact data is recovered, Eq. (1) summed in
+    closed form, Eq. (2) as the special case of a constant iteration time."""
+    dec = [(8, n, 0.8 + 2e-4 * n) for n in (512, 544, 576, 640)] + [(16, n, 1.1 + 3e-4 * n) for n in (100, 900)]
+    pre = [(8, 512, 28.0), (16, 256, 20.0), (16, 1024, 92.0)]
+    m = O.cost_fit(dec, pre)
+    assert np.allclose(m[8]["dec"], (0.8, 2e-4)) and np.allclose(m[16]["dec"], (1.1, 3e-4))
+    assert np.allclose(m[8]["pre"], (0.0, 28.0 / 512))                       # one length: through the origin
+    assert np.allclose(m[16]["pre"], (20.0 - 256 * (72.0 / 768), 72.0 / 768))
+    # Eq. (1): arithmetic series in closed form
+    l = O.cost_l_exe(m, 8, 512, 128)
+    assert len(l) == 129 and np.isclose(l[0], 28.0)
+    assert np.isclose(l[128], 28.0 + 128 * 0.8 + 2e-4 * (128 * 512 + 127 * 128 / 2))
+    assert all(b > a for a, b in zip(l, l[1:]))
+    # Eq. (2): a constant per-iteration time gives t_exe(S_in) + S_out * t_exe(1)
+    flat = O.cost_fit([(4, 300, 0.5)], [(4, 300, 9.0)])
+    assert np.allclose(O.cost_l_exe(flat, 4, 300, 40), [9.0 + 0.5 * s for s in range(41)])
+    # a batch size half-way between two fitted ones costs the mean of their times; outside: the nearest
+    l12 = O.cost_l_exe(m, 12, 256, 10)
+    l8, l16 = O.cost_l_exe(m, 8, 256, 10), O.cost_l_exe(m, 16, 256, 10)
+    assert np.allclose(l12, [(a + b) / 2 for a, b in zip(l8, l16)])
+    assert np.allclose(O.cost_l_exe(m, 64, 256, 10), l16) and np.allclose(O.cost_l_exe(m, 1, 256, 10), l8)
+    # noisy samples: the fit is the least-squares line (normal equations written out)
+    rng = np.random.default_rng(5)
+    x = rng.integers(1, 2000, size=30)
+    y = 0.7 + 1e-4 * x + rng.normal(0, 0.01, size=30)
+    A = np.stack([np.ones(30), x.astype(np.float64)], axis=1)
+    c0, c1 = np.linalg.solve(A.T @ A, A.T @ y)
+    assert np.allclose(O.cost_fit([(2, int(a), float(b)) for a, b in zip(x, y)])[2]["dec"], (c0, c1))
+
+
+def test_cost_model_matches_oracle():
+    rng = np.random.default_rng(77)
+    for case in range(40):
+        batches = sorted(set(int(b) for b in rng.integers(1, 40, size=int(rng.integers(1, 5)))))
+        dec, pre = [], []
+        for b in batches:
+            for _ in range(int(rng.integers(1, 6))):
+                dec.append((b, int(rng.integers(0, 3000)), float(rng.uniform(0.2, 5.0))))
+            for _ in range(int(rng.integers(0, 4))):
+                pre.append((b, int(rng.integers(1, 2049)), float(rng.uniform(1.0, 200.0))))
+        mo, mc = O.cost_fit(dec, pre), P.cost_fit(dec, pre)
+        assert mc.n_batches == len(batches) and list(mc.batch[:mc.n_batches]) == batches
+        for i, b in enumerate(batches):
+            assert np.allclose((mc.dec_base_ms[i], mc.dec_per_row_ms[i]), mo[b]["dec"], rtol=1e-9, atol=1e-9)
+            assert np.allclose((mc.pre_base_ms[i], mc.pre_per_token_ms[i]), mo[b]["pre"], rtol=1e-9, atol=1e-9)
+        for _ in range(5):
+            b, s_in, s_out = int(rng.integers(1, 50)), int(rng.integers(1, 1500)), int(rng.integers(0, 200))
+            assert np.allclose(P.cost_l_exe(mc, b, s_in, s_out), O.cost_l_exe(mo, b, s_in, s_out), rtol=1e-9, atol=1e-9)
+    # the table feeds the just-in-time arrangement
+    m = P.cost_fit([(8, 512, 0.9), (8, 640, 0.92)], [(8, 512, 27.0)])
+    l = P.cost_l_exe(m, 8, 512, 128)
+    assert P.jit_iterations(False, l, 100.0, 20.0) == O.jit_iterations(False, l, 100.0, 20.0) > 0
+    with pytest.raises(Exception):
+        P.cost_fit([], [])
+    with pytest.raises(Exception):
+        P.cost_fit([(8, 10, 1.0)], [(4, 10, 1.0)])               # initial-phase sample of a batch size without decode samples
