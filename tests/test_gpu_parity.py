@@ -577,6 +577,69 @@ def test_resume_on_repartitioned_shards_matches_uninterrupted(ss, side_stream):
         s.destroy()
 
 
+def test_cache_discard_keeps_the_most_progressed_requests(ss, side_stream):
+    """Section 3.3, cache discard: requests with ragged progress; the new configuration holds
+    fewer of them; the planner picks the most-progressed ones, the re-partition moves exactly
+    their rows (bit-exact against the oracle's), decoding goes on for them."""
+    import torch
+    from oracle import planner as OP
+    from paper_2311_15566_amd import plan as P
+    w = scaled("gpt20b_m4", "bf16", n_heads=8, head_dim=128, d_model=512, ffn=1024, layers=2, M=2, m=1,
+               batch=6, s_in=37, steps=10, s_max=64)
+    W = make_weights(w.desc, w.slice, w.seed)
+    toks = make_tokens(w.seed, w.batch, w.s_in, w.desc["vocab"])
+    V = w.desc["vocab"]
+    ora = D.OracleShard(w.desc, w.slice, W, 6, w.s_max)
+    sh = ss.Shard(w.desc, w.slice, W, 6, w.s_max)
+    logits = torch.empty(6, V, dtype=torch.float32, device="cuda")
+    ref = D.prefill_matrix([ora], toks)
+    ss.prefill([sh], dev(toks), logits, None)
+    check_logits(logits.cpu().numpy(), ref, True, "prefill")
+    # ragged progress: all six rows 2 steps, rows 0-3 three more, rows 0-1 two more
+    for nb, steps in ((6, 2), (4, 3), (2, 2)):
+        for _ in range(steps):
+            tok = D.greedy(ref[:nb])
+            ref_step = D.decode_step([ora], tok, rows=list(range(nb)))
+            ss.decode_step([sh], dev(tok), logits[:nb], None)
+            check_logits(logits[:nb].cpu().numpy(), ref_step, True, f"ragged phase B={nb}")
+            ref = ref_step
+    lens = [w.s_in + 7, w.s_in + 7, w.s_in + 5, w.s_in + 5, w.s_in + 2, w.s_in + 2]
+    assert list(ss.committed_len(sh)) == lens == list(ora.n)
+    # shuffle the rows so that the longest are not a prefix (a re-partition onto the same slice)
+    perm = [5, 2, 0, 4, 1, 3]
+    ora2, sh2 = D.OracleShard(w.desc, w.slice, W, 6, w.s_max), ss.Shard(w.desc, w.slice, W, 6, w.s_max)
+    D.kv_repack(ora2, ora, perm)
+    ss.kv_repack(sh2, sh, perm)
+    lens2 = [lens[r] for r in perm]
+    assert list(ss.committed_len(sh2)) == lens2
+    # the new configuration holds 3 requests in shards of 4 rows
+    bmap = P.rows_to_keep(lens2, 3, 4)
+    assert bmap == OP.rows_to_keep(lens2, 3, 4) == sorted(sorted(range(6), key=lambda r: (-lens2[r], r))[:3]) + [-1]
+    quarter = [sub_slice_of(w.slice, p, 2) for p in range(2)]
+    opair = [D.OracleShard(w.desc, q, W, 4, w.s_max) for q in quarter]
+    pair = [ss.Shard(w.desc, q, W, 4, w.s_max) for q in quarter]
+    for o, g in zip(opair, pair):
+        D.kv_repack(o, ora2, bmap)
+        ss.kv_repack(g, sh2, bmap)
+        assert list(ss.committed_len(g)) == list(o.n)
+    kept_lens = [lens2[r] for r in bmap[:3]]
+    assert sorted(kept_lens, reverse=True) == sorted(lens, reverse=True)[:3]
+    # what moved is what the oracle moved, up to the cache's storage precision (both come from their own decode)
+    for o, g in zip(opair, pair):
+        got = ss.kv_export(g).astype(np.float32)
+        assert got.shape == D.kv_canonical(o).shape and np.abs(got - D.kv_canonical(o)).max() < 4e-3
+    # decoding goes on for the kept requests only
+    tok = np.array([7, 11, 13], dtype=np.int32)
+    for step in range(3):
+        ref = D.decode_step(opair, tok)
+        ss.decode_step(pair, dev(tok), logits[:3], None)
+        check_logits(logits[:3].cpu().numpy(), ref, True, f"after discard, step {step}")
+        tok = D.greedy(ref).astype(np.int32)
+    assert list(ss.committed_len(pair[0])) == [n + 3 for n in kept_lens] + [0]
+    for s_ in [sh, sh2] + pair:
+        s_.destroy()
+
+
 def test_interrupted_step_commits_nothing_and_retry_is_identical(ss, side_stream):
     import torch
     w = scaled("tiny_gpt", "bf16", batch=3, s_in=20, steps=2)
