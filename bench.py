@@ -173,10 +173,16 @@ def main():
         prefill_ms = e0.elapsed_time(e1)
 
         # ---- the timed region: exactly K decode steps ----
+        # (an event every `chunk` steps, for the cost model below: a marker in the stream, no wait)
+        chunk = max(8, K // 8)
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(K // chunk + 1)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(K):
+        marks[0].record()
+        for i in range(K):
             ss.decode_step([sh], nxt, logits, nxt)
+            if (i + 1) % chunk == 0:
+                marks[(i + 1) // chunk].record()
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         final_ids = nxt.cpu().numpy().copy()
@@ -231,18 +237,9 @@ def main():
             out["prefill"] = dict(ms=prefill_ms, tokens=w.batch * w.s_in, TFLOPs=fl / (prefill_ms * 1e-3) / 1e12,
                                   peak=peak, frac=fl / (prefill_ms * 1e-3) / 1e12 / peak)
 
-            # ---- measured cost model (Section 5; Eq. 1): iteration time over context length, from this run ----
-            if K >= 32:
+            # ---- measured cost model (Section 5; Eq. 1): iteration time over context length, from the timed steps ----
+            if K // chunk >= 2:
                 from paper_2311_15566_amd import plan as P
-                fresh()
-                chunk = max(8, K // 8)
-                marks = [torch.cuda.Event(enable_timing=True) for _ in range(K // chunk + 1)]
-                marks[0].record()
-                for i in range(K // chunk):
-                    for _ in range(chunk):
-                        ss.decode_step([sh], nxt, logits, nxt)
-                    marks[i + 1].record()
-                torch.cuda.synchronize()
                 samples = [(w.batch, w.s_in + i * chunk + chunk // 2, marks[i].elapsed_time(marks[i + 1]) / chunk)
                            for i in range(K // chunk)]
                 cm = P.cost_fit(samples, [(w.batch, w.s_in, prefill_ms)])
@@ -253,7 +250,7 @@ def main():
                                          prefill_ms_per_token=cm.pre_per_token_ms[0], samples=len(samples),
                                          l_exe_ms=l_exe[-1], measured_ms=measured, s_in=w.s_in, s_out=steps_fit,
                                          note="least-squares line through the mean iteration time of each run of "
-                                              f"{chunk} steps; l_exe = Eq. (1) from the fit, measured = the same steps timed")
+                                              f"{chunk} timed steps; l_exe = Eq. (1) from the fit, measured = the same steps timed")
 
             # ---- KV re-partition of this shard's cache into two half-width shards ----
             g = shard_dims(w)

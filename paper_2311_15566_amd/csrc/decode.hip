@@ -128,12 +128,14 @@ static std::map<TuneKey, TuneVal> g_tune;
 static std::mutex g_tune_mu;
 static TuneVal g_forced = {0, 0};  // test aid: 0 = not forced
 
-static std::vector<TuneVal> tune_candidates(int epi, int B) {
+static TuneVal tune_rule(int epi, int row_tiles, int B);
+// Timed candidates: the split of the batch tiles over blocks (B > 16).  The number of weight tiles
+// per block follows the rule: timed in isolation the GEMMs run out of the memory-side cache, where
+// one tile per block can look faster than it is inside a step that streams every weight once.
+static std::vector<TuneVal> tune_candidates(int epi, int row_tiles, int B) {
   std::vector<TuneVal> c;
-  for (int nw = 2; nw >= 1; --nw) {
-    if (nw == 1 && (epi == EPI_SWIGLU || epi == EPI_LOGITS)) continue;  // gate/up pairs; the argmax buffers hold one entry per pair
-    for (int bt = 1; bt <= (B > 16 ? 2 : 1); ++bt) c.push_back(TuneVal{nw, bt});
-  }
+  const int nw = tune_rule(epi, row_tiles, B).nw;
+  for (int bt = 1; bt <= (B > 16 ? 2 : 1); ++bt) c.push_back(TuneVal{nw, bt});
   return c;
 }
 static TuneVal tune_rule(int epi, int row_tiles, int B) {
@@ -395,12 +397,16 @@ static ss_status tune_decode_gemms(Shard *const *group, int n_group, int B, hipS
   for (auto &kv : by_shape) {
     const TuneKey &key = kv.first;
     const std::vector<const Phase *> &phs = kv.second;
-    const std::vector<TuneVal> cands = tune_candidates(key.epi, B);
-    TuneVal best = cands[0];
-    float best_ms = -1.f;
+    const std::vector<TuneVal> cands = tune_candidates(key.epi, key.row_tiles, B);
+    // the rule's shape stays unless another one is clearly (3 %) faster: near-equal shapes would
+    // otherwise flip from run to run on timing noise
+    const TuneVal rule = tune_rule(key.epi, key.row_tiles, B);
+    TuneVal best = rule;
+    float best_ms = -1.f, rule_ms = -1.f;
+    std::vector<std::pair<float, TuneVal>> timed;
     for (const TuneVal &c : cands) {
       if (cands.size() == 1) break;
-      const int reps = 4;
+      const int reps = 8;
       size_t turn = 0;
       for (int r = -1; r < reps && rc == SS_OK; ++r) {  // r = -1: an untimed first launch
         if (r == 0 && hipEventRecord(e0, st) != hipSuccess) rc = SS_EHIP;
@@ -421,9 +427,16 @@ static ss_status tune_decode_gemms(Shard *const *group, int n_group, int B, hipS
         rc = SS_EHIP;
         break;
       }
-      if (best_ms < 0.f || ms < best_ms) best_ms = ms, best = c;
+      timed.push_back({ms, c});
+      if (c.nw == rule.nw && c.bt_split == rule.bt_split) rule_ms = ms;
     }
     if (rc != SS_OK) break;
+    for (auto &t : timed) {
+      const bool is_rule = t.second.nw == rule.nw && t.second.bt_split == rule.bt_split;
+      const float bar = (rule_ms >= 0.f && !is_rule) ? 0.97f * rule_ms : rule_ms;
+      if (is_rule) continue;
+      if ((bar < 0.f || t.first < bar) && (best_ms < 0.f || t.first < best_ms)) best_ms = t.first, best = t.second;
+    }
     std::lock_guard<std::mutex> lock(g_tune_mu);
     g_tune[key] = best;
   }
