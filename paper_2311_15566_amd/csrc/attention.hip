@@ -2,6 +2,7 @@
 // append of the new token fused in, and the causal attention of the initial phase.
 #include "attn_block.h"
 #include "kernels.h"
+#include "mma.h"
 
 #include <math.h>
 
@@ -154,13 +155,181 @@ __global__ void __launch_bounds__(256) prefill_attn(PrefillAttnArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// causal attention of the initial phase on the matrix cores (half-precision cache).
+//
+// prefill_vt_write: this layer's value rows, transposed: vt[(b*Hs + h)][dim][pos], pos < s_pad
+// (a multiple of 64), zeros past S, so that the P.V product finds the key index contiguous.
+// grid = (B*Hs, s_pad/64); a tile of 64 positions x DH dims goes through LDS.
+// ---------------------------------------------------------------------------
+template <int DH>
+__global__ void __launch_bounds__(256) prefill_vt_write(PrefillAttnArgs a) {
+  __shared__ f16_t tile[64][DH + 2];
+  const int tid = threadIdx.x, bh = blockIdx.x, p0 = blockIdx.y * 64;
+  const int b = bh / a.Hs, h = bh - b * a.Hs;
+  const char *vbase = a.v_cache + b * a.row_stride + h * a.head_stride;
+  constexpr int RP = DH / 8;  // 16-byte pieces per row
+  for (int p = tid; p < 64 * RP; p += 256) {
+    const int row = p / RP, pc = p - row * RP;
+    u32x4 raw = {0u, 0u, 0u, 0u};
+    if (p0 + row < a.S) raw = *((const u32x4 *)(vbase + (size_t)(p0 + row) * DH * sizeof(f16_t)) + pc);
+    f16_t v[8];
+    __builtin_memcpy(v, &raw, 16);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) tile[row][pc * 8 + e] = v[e];
+  }
+  __syncthreads();
+  f16_t *out = (f16_t *)a.vt + (size_t)bh * DH * a.s_pad + p0;
+  for (int p = tid; p < DH * 8; p += 256) {
+    const int dim = p >> 3, pc = p & 7;
+    f16_t v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = tile[pc * 8 + e][dim];
+    u32x4 raw;
+    __builtin_memcpy(&raw, v, 16);
+    *(u32x4 *)(out + (size_t)dim * a.s_pad + pc * 8) = raw;
+  }
+}
+
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+// grid = (B*Hs, ceil(S/64)); block = 4 waves, wave w owns queries 64*qt + 16*w .. + 15.
+// Keys go 32 at a time through a double-buffered LDS tile in operand order.  Per 16 keys:
+//   scores^T = K . Q^T   (16x16x32 products over the head dims): lane (g, r) gets the scores of keys
+//                        4g .. 4g+3 against query r, so a query's softmax state lives in lane r of
+//                        each of the four lane groups;
+//   out^T   += V^T . P^T (16x16x16 products over the keys): those four probabilities are exactly the
+//                        lane's piece of the P operand, nothing is exchanged between lanes.
+// Scores are kept in log2 units (the scale carries log2 e).  q and the probabilities enter the
+// products as halves, keys and values at cache precision.
+template <typename AT, int DH>
+__global__ void __launch_bounds__(256) prefill_attn_mfma(PrefillAttnArgs a) {
+  constexpr int TK = 32, KC = DH / 32, DT = DH / 16;
+  __shared__ __align__(16) u32x4 lds_k[2][2][KC][64];  // [buffer][16-key subtile][32-dim block][lane]
+  __shared__ __align__(16) uint2 lds_v[2][2][DT][64];  // [buffer][16-key subtile][16-dim tile][lane]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 15, g = lane >> 4;
+  const int bh = blockIdx.x, qt = gridDim.y - 1 - blockIdx.y;  // the longest tiles start first
+  const int b = bh / a.Hs, h = bh - b * a.Hs;
+  const int HD = a.Hs * DH;
+  const int q0 = qt * 64 + wave * 16, qi = q0 + r;
+  const float sc = rsqrtf((float)DH) * 1.4426950408889634f;
+  f16x8 qf[KC];
+  {
+    const float *qrow = a.qkv + ((size_t)(b * a.S + min(qi, a.S - 1))) * 3 * HD + h * DH;
+#pragma unroll
+    for (int c = 0; c < KC; ++c)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) qf[c][e] = (f16_t)(qrow[c * 32 + g * 8 + e] * sc);
+  }
+  f32x4 acc[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m = -1e30f, l = 0.f;
+  const char *kbase = a.k_cache + b * a.row_stride + h * a.head_stride;
+  const f16_t *vt = (const f16_t *)a.vt + (size_t)bh * DH * a.s_pad;
+  const int last_key = min(a.S, (qt + 1) * 64);
+  const int n_tiles = (last_key + TK - 1) / TK;
+
+  // staging: 32 keys x DH halves of K = 4*DH pieces of 16 bytes, and as many of V^T (DH dims x 32 keys)
+  constexpr int NP = 4 * DH / 256;  // pieces per thread and operand
+  u32x4 kreg[NP], vreg[NP];
+  auto fetch = [&](int t) {
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      const int p = tid + 256 * i;
+      const int key = p / (DH / 8), pc = p % (DH / 8);
+      const int kr = min(t * TK + key, a.S - 1);  // clamped: masked below
+      kreg[i] = *((const u32x4 *)(kbase + (size_t)kr * DH * sizeof(f16_t)) + pc);
+      const int dim = p >> 2, kp = p & 3;         // 8 keys of one dim (inside s_pad, zeros past S)
+      vreg[i] = *(const u32x4 *)(vt + (size_t)dim * a.s_pad + t * TK + kp * 8);
+    }
+  };
+  auto stash = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      const int p = tid + 256 * i;
+      const int key = p / (DH / 8), pc = p % (DH / 8);
+      lds_k[buf][key >> 4][pc >> 2][(pc & 3) * 16 + (key & 15)] = kreg[i];
+      const int dim = p >> 2, kp = p & 3;
+      uint2 *dst = &lds_v[buf][kp >> 1][dim >> 4][((kp & 1) * 2) * 16 + (dim & 15)];
+      dst[0] = make_uint2(vreg[i][0], vreg[i][1]);    // keys 8*(kp&1) .. + 3 of the subtile
+      dst[16] = make_uint2(vreg[i][2], vreg[i][3]);   // the next four: lane group + 1
+    }
+  };
+  fetch(0);
+  stash(0);
+  __syncthreads();
+  for (int t = 0; t < n_tiles; ++t) {
+    const int buf = t & 1;
+    const bool more = t + 1 < n_tiles;
+    if (more) fetch(t + 1);
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+      const int key0 = t * TK + st * 16;
+      if (key0 > q0 + 15 || key0 >= a.S) continue;  // nothing of this subtile is visible to the wave's queries
+      f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int c = 0; c < KC; ++c)
+        s = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, lds_k[buf][st][c][lane]), qf[c], s, 0, 0, 0);
+      float mx = -INFINITY;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int key = key0 + g * 4 + i;
+        s[i] = (key <= qi && key < a.S) ? s[i] : -INFINITY;
+        mx = fmaxf(mx, s[i]);
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float mn = fmaxf(m, mx);
+      const float alpha = __builtin_amdgcn_exp2f(m - mn);
+      f16x4 pf;
+      float ps = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float p = __builtin_amdgcn_exp2f(s[i] - mn);
+        ps += p;
+        pf[i] = (f16_t)p;
+      }
+      l = l * alpha + ps;
+      m = mn;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        acc[dt] *= alpha;
+        acc[dt] = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4, lds_v[buf][st][dt][lane]), pf, acc[dt], 0, 0, 0);
+      }
+    }
+    if (more) stash(buf ^ 1);  // last read in the previous iteration, before its barrier
+    __syncthreads();
+  }
+  l += __shfl_xor(l, 16);
+  l += __shfl_xor(l, 32);
+  if (qi < a.S) {
+    const float inv = 1.0f / l;
+    const int tok = b * a.S + qi;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      const float v[4] = {acc[dt][0] * inv, acc[dt][1] * inv, acc[dt][2] * inv, acc[dt][3] * inv};
+      store4_frag<AT, false>(a.o_out, tok, h * DH + dt * 16 + g * 4, HD / Elem<AT>::kFragK, Elem<AT>::kParts, v);
+    }
+  }
+}
+
 ss_status launch_prefill_attn(int dtype, const PrefillAttnArgs &a, hipStream_t st) {
   if (a.S < 1 || a.S > a.Smax || a.B < 1 || (a.Dh != 64 && a.Dh != 128)) SS_FAIL(SS_EINVAL, "prefill attention: bad shape");
   dim3 grid(a.B * a.Hs, ceil_div(a.S, 64));
 #define SS_LAUNCH(KT, AT, DH) hipLaunchKernelGGL((prefill_attn<KT, AT, DH>), grid, dim3(256), 0, st, a)
-  if (dtype == SS_DTYPE_BF16 && a.kv_dtype == SS_DTYPE_F16) {
-    if (a.Dh == 128) SS_LAUNCH(f16_t, bf16_t, 128);
-    else SS_LAUNCH(f16_t, bf16_t, 64);
+  if (dtype == SS_DTYPE_BF16 && a.kv_dtype == SS_DTYPE_F16) {  // the default cache type: matrix cores
+    if (!a.vt || a.s_pad < a.S || a.s_pad % 64) SS_FAIL(SS_EINVAL, "prefill attention: no room for the transposed values");
+    dim3 tgrid(a.B * a.Hs, a.s_pad / 64);
+    if (a.Dh == 128) {
+      hipLaunchKernelGGL((prefill_vt_write<128>), tgrid, dim3(256), 0, st, a);
+      hipLaunchKernelGGL((prefill_attn_mfma<bf16_t, 128>), grid, dim3(256), 0, st, a);
+    } else {
+      hipLaunchKernelGGL((prefill_vt_write<64>), tgrid, dim3(256), 0, st, a);
+      hipLaunchKernelGGL((prefill_attn_mfma<bf16_t, 64>), grid, dim3(256), 0, st, a);
+    }
   } else if (dtype == SS_DTYPE_BF16 && a.kv_dtype == SS_DTYPE_BF16) {
     if (a.Dh == 128) SS_LAUNCH(bf16_t, bf16_t, 128);
     else SS_LAUNCH(bf16_t, bf16_t, 64);

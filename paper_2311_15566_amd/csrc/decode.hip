@@ -565,6 +565,7 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, c
       p.rope = m.pos == SS_POS_ROPE ? s->rope : nullptr;
       p.o_out = s->ws + L.ws_o;
       p.B = B, p.S = S, p.Hs = L.Hs, p.Dh = L.Dh, p.Smax = L.Smax, p.kv_dtype = s->m.kv_dtype;
+      p.vt = s->ws + L.ws_vt, p.s_pad = (int)align_up((size_t)S, 64);
       SS_TRY(launch_prefill_kv_write(dt, p, st));
       SS_TRY(launch_prefill_attn(dt, p, st));
     }

@@ -154,6 +154,8 @@ struct PrefillAttnArgs {
   void *o_out;          // fragments [T/16][Hs*Dh / FragK][parts of the operand type]
   int B, S, Hs, Dh, Smax;
   int kv_dtype;
+  void *vt;             // half-precision cache: scratch for the transposed values [B*Hs][Dh][s_pad]
+  int s_pad;            // S rounded up to 64
 };
 ss_status launch_prefill_kv_write(int dtype, const PrefillAttnArgs &a, hipStream_t st);
 ss_status launch_prefill_attn(int dtype, const PrefillAttnArgs &a, hipStream_t st);

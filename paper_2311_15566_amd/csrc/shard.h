@@ -33,6 +33,7 @@ struct Layout {
   size_t off_ws, ws_bytes;             // workspace, doubles as upload staging
   // workspace sub-offsets (relative to off_ws)
   size_t ws_x, ws_a, ws_qkv, ws_o, ws_u, ws_counters, ws_attn_part, ws_argmax;
+  size_t ws_vt;        // initial phase: one layer's values transposed, [Bmax*Hs][Dh][Smax rounded up to 64] halves
   size_t ws_pstat;     // initial phase: partial row sums [2 * ceil(d / 128)][Tmax] float2, then (mean, rstd) [Tmax]
   int n_counters;
   // decode step (rows = batch): residual stream [32][d] f32, operand of the next normalised GEMM
