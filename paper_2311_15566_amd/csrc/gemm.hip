@@ -27,7 +27,7 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
   // token blocks of a group, activation panels by the row blocks of the window.
   int rb, tb;
   {
-    constexpr int GT = 4;  // token blocks per group
+    constexpr int GT = 8;  // token blocks per group
     const int nrb = a.n_row_blocks, ntb = a.T / 128, nblk = nrb * ntb;
     const int pid = blockIdx.x, xcd = pid % 8, local = pid / 8;
     const int base = nblk / 8, rem = nblk % 8;
