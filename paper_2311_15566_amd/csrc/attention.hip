@@ -325,14 +325,14 @@ ss_status launch_prefill_attn(int dtype, const PrefillAttnArgs &a, hipStream_t s
     dim3 tgrid(a.B * a.Hs, a.s_pad / 64);
     if (a.Dh == 128) {
       hipLaunchKernelGGL((prefill_vt_write<128>), tgrid, dim3(256), 0, st, a);
-      hipLaunchKernelGGL((prefill_attn_mfma<bf16_t, 128>), grid, dim3(256), 0, st, a);
+      hipLaunchKernelGGL((prefill_attn_mfma<f16_t, 128>), grid, dim3(256), 0, st, a);
     } else {
       hipLaunchKernelGGL((prefill_vt_write<64>), tgrid, dim3(256), 0, st, a);
-      hipLaunchKernelGGL((prefill_attn_mfma<bf16_t, 64>), grid, dim3(256), 0, st, a);
+      hipLaunchKernelGGL((prefill_attn_mfma<f16_t, 64>), grid, dim3(256), 0, st, a);
     }
-  } else if (dtype == SS_DTYPE_BF16 && a.kv_dtype == SS_DTYPE_BF16) {
-    if (a.Dh == 128) SS_LAUNCH(bf16_t, bf16_t, 128);
-    else SS_LAUNCH(bf16_t, bf16_t, 64);
+  } else if (dtype == SS_DTYPE_BF16 && a.kv_dtype == SS_DTYPE_BF16) {  // output: single half-precision fragments
+    if (a.Dh == 128) SS_LAUNCH(bf16_t, f16_t, 128);
+    else SS_LAUNCH(bf16_t, f16_t, 64);
   } else if (dtype == SS_DTYPE_F32 && a.kv_dtype == SS_DTYPE_F32) {
     if (a.Dh == 128) SS_LAUNCH(float, float, 128);
     else SS_LAUNCH(float, float, 64);

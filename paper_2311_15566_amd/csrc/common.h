@@ -77,6 +77,8 @@ typedef _Float16 f16_t;   // IEEE half: a KV-cache element type
 template <typename T> struct Elem;
 template <> struct Elem<f16_t> {
   static constexpr int kPerLane = 8;
+  static constexpr int kFragK = 32;
+  static constexpr int kParts = 1;     // as a GEMM operand of the initial phase: 11 significant bits, one fragment
   __host__ __device__ static float to_f32(f16_t v) { return (float)v; }
   // round-to-nearest-even, saturating at the largest finite half
   __host__ __device__ static f16_t from_f32(float v) {

@@ -14,8 +14,10 @@ namespace ss {
 // tiled prefill GEMM: block = 128 output features x 128 tokens, 4 waves of 64 x 64,
 // K advanced two fragments at a time through LDS with register prefetch of the next stage.
 // ---------------------------------------------------------------------------
-template <typename T, int EPI, int AP>
+// H16: half-precision single-part activations against bf16 weights converted when they are staged
+template <typename T, int EPI, int AP, bool H16 = false>
 __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
+  static_assert(!H16 || (AP == 1 && sizeof(T) == 2), "half-precision operands: one part, 16-bit weights");
   constexpr int KS = 2;  // k fragments per stage
   __shared__ __align__(16) u32x4 lds_w[KS][8][64];
   __shared__ __align__(16) u32x4 lds_a[KS][8][AP][64];
@@ -72,7 +74,7 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
     for (int r = 0; r < 4; ++r) {
       const int p = tid + 256 * r;
       const int ks = p >> 9, tile = (p >> 6) & 7, ln = p & 63;
-      lds_w[ks][tile][ln] = pw[r];
+      lds_w[ks][tile][ln] = H16 ? bf16x8_to_f16x8(pw[r]) : pw[r];
 #pragma unroll
       for (int part = 0; part < AP; ++part) lds_a[ks][tile][part][ln] = pa[r][part];
     }
@@ -91,7 +93,7 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-          for (int j = 0; j < 4; ++j) acc[i][j] = Mma<T>::mma(wf[i], af[j], acc[i][j]);
+          for (int j = 0; j < 4; ++j) acc[i][j] = H16 ? mma_f16(wf[i], af[j], acc[i][j]) : Mma<T>::mma(wf[i], af[j], acc[i][j]);
       }
     }
   }
@@ -100,7 +102,7 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
   const float *cbp = a.mr_in ? a.cb : a.bias;
   const float *wgp = a.mr_in ? a.wg : nullptr;
   // the product of weight row n0 + e and this lane's token, with the deferred norm and the bias applied
-  auto finish = [&](const f32x4 &c, const int n0, const float2 mr, float (&v)[4]) {
+  auto finish = [&](const f32x4 &c, const int n0, const float2 mr, float (&v)[4]) {  // mr = (mean - centre, rstd)
     f32x4 wg = {0.f, 0.f, 0.f, 0.f}, cb = {0.f, 0.f, 0.f, 0.f};
     if (wgp) wg = *(const f32x4 *)(wgp + n0);
     if (cbp) cb = *(const f32x4 *)(cbp + n0);
@@ -112,7 +114,7 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
     const int tok = (tt0 + wc * 4 + j) * 16 + tl;
     const bool tok_live = tok < a.T_live;
     if (EPI == EPI_SWIGLU) {
-      const float2 mr = a.mr_in ? a.mr_in[tok] : make_float2(0.f, 1.f);
+      const float2 mr = a.mr_in ? make_float2(a.mr_in[tok][2], a.mr_in[tok][1]) : make_float2(0.f, 1.f);
 #pragma unroll
       for (int i = 0; i < 4; i += 2) {
         const int rt = rt0 + wr * 4 + i;  // gate tile; rt + 1 is the matching up tile
@@ -123,11 +125,13 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
           finish(acc[i + 1][j], (rt + 1) * 16 + q4, mr, up);
 #pragma unroll
           for (int e = 0; e < 4; ++e) u[e] = silu_f(gt[e]) * up[e];
-          store4_frag<T, false>(a.act_out, tok, n0, a.out_k_blocks, a.out_parts, u);
+          if (sizeof(T) == 2 && a.out_f16) store4_frag<f16_t, false>(a.act_out, tok, n0, a.out_k_blocks, 1, u);
+          else store4_frag<T, false>(a.act_out, tok, n0, a.out_k_blocks, a.out_parts, u);
         }
       }
     } else if (EPI == EPI_RESID) {
       float s1 = 0.f, s2 = 0.f;
+      const float cen = a.g_out ? a.c_in[tok][0] : 0.f;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int rt = rt0 + wr * 4 + i;
@@ -144,10 +148,12 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
             float y[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              s1 += v[e], s2 += v[e] * v[e];
-              y[e] = v[e] * g[e];
+              const float t = v[e] - cen;
+              s1 += t, s2 += t * t;
+              y[e] = t * g[e];
             }
-            store4_frag<T, false>(a.norm_out, tok, n0, a.N / Elem<T>::kFragK, a.norm_parts, y);
+            if (sizeof(T) == 2 && a.norm_f16) store4_frag<f16_t, false>(a.norm_out, tok, n0, a.N / Elem<T>::kFragK, 1, y);
+            else store4_frag<T, false>(a.norm_out, tok, n0, a.N / Elem<T>::kFragK, a.norm_parts, y);
           }
         }
       }
@@ -157,7 +163,7 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
         if (lane < 16) a.stat_out[(size_t)(rb * 2 + wr) * a.T + tok] = make_float2(s1, s2);
       }
     } else {
-      const float2 mr = a.mr_in ? a.mr_in[tok] : make_float2(0.f, 1.f);
+      const float2 mr = a.mr_in ? make_float2(a.mr_in[tok][2], a.mr_in[tok][1]) : make_float2(0.f, 1.f);
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int rt = rt0 + wr * 4 + i;
@@ -170,7 +176,8 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
           } else {  // EPI_ACT
             const float w[4] = {act_apply(a.act_kind, v[0]), act_apply(a.act_kind, v[1]), act_apply(a.act_kind, v[2]),
                                 act_apply(a.act_kind, v[3])};
-            store4_frag<T, false>(a.act_out, tok, n0, a.out_k_blocks, a.out_parts, w);
+            if (sizeof(T) == 2 && a.out_f16) store4_frag<f16_t, false>(a.act_out, tok, n0, a.out_k_blocks, 1, w);
+            else store4_frag<T, false>(a.act_out, tok, n0, a.out_k_blocks, a.out_parts, w);
           }
         }
       }
@@ -179,9 +186,10 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
 }
 
 __global__ void __launch_bounds__(256) row_stats(const float2 *part, int groups, int T, float inv_dim, int rms, float eps,
-                                                 float2 *mr) {
+                                                 f32x4 *mr) {
   const int tok = blockIdx.x * 256 + threadIdx.x;
   if (tok >= T) return;
+  const float c = mr[tok][0];  // the centre the partial sums were taken about
   float u1 = 0.f, u2 = 0.f;
   int g = 0;
   for (; g + 8 <= groups; g += 8) {  // eight loads in flight; the sums stay in group order
@@ -196,17 +204,15 @@ __global__ void __launch_bounds__(256) row_stats(const float2 *part, int groups,
     u1 += v.x, u2 += v.y;
   }
   const float ms = u2 * inv_dim;
-  float mean = 0.f, rstd;
-  if (rms) {
-    rstd = rsqrtf(ms + eps);
+  if (rms) {  // c = 0
+    mr[tok] = f32x4{0.f, rsqrtf(ms + eps), 0.f, 0.f};
   } else {
-    mean = u1 * inv_dim;
-    rstd = rsqrtf(fmaxf(ms - mean * mean, 0.f) + eps);
+    const float delta = u1 * inv_dim;  // mean - c
+    mr[tok] = f32x4{c + delta, rsqrtf(fmaxf(ms - delta * delta, 0.f) + eps), delta, 0.f};
   }
-  mr[tok] = make_float2(mean, rstd);
 }
 
-ss_status launch_row_stats(const float2 *part, int groups, int T, int norm_dim, int rms, float eps, float2 *mr,
+ss_status launch_row_stats(const float2 *part, int groups, int T, int norm_dim, int rms, float eps, f32x4 *mr,
                            hipStream_t st) {
   if (!part || !mr || groups < 1 || T < 1 || norm_dim < 1) SS_FAIL(SS_EINVAL, "row statistics: bad arguments");
   hipLaunchKernelGGL(row_stats, dim3(ceil_div(T, 256)), dim3(256), 0, st, part, groups, T, 1.0f / (float)norm_dim, rms, eps, mr);
@@ -219,18 +225,28 @@ ss_status launch_tile_gemm(int dtype, int epi, TileGemmArgs a, hipStream_t st) {
   if (a.row_tiles < 1 || a.k_blocks < 1 || a.N % 4) SS_FAIL(SS_EINVAL, "prefill GEMM: bad shape");
   if ((epi == EPI_F32 && (a.ld_out % 4)) || epi == EPI_LOGITS) SS_FAIL(SS_EINVAL, "prefill GEMM: bad epilogue");
   if (a.act_parts != 1 && !(a.act_parts == 2 && dtype == SS_DTYPE_BF16)) SS_FAIL(SS_EINVAL, "prefill GEMM: bad act_parts");
+  if ((a.act_f16 && (dtype != SS_DTYPE_BF16 || a.act_parts != 1)) || (a.out_f16 && (dtype != SS_DTYPE_BF16 || a.out_parts != 1)))
+    SS_FAIL(SS_EINVAL, "prefill GEMM: half-precision operands need a bf16 model and one part");
   if ((epi == EPI_ACT || epi == EPI_SWIGLU) && a.out_parts != 1 && !(a.out_parts == 2 && dtype == SS_DTYPE_BF16))
     SS_FAIL(SS_EINVAL, "prefill GEMM: bad out_parts");
   if (epi == EPI_RESID && a.g_out) {
     const int fk = dtype == SS_DTYPE_BF16 ? 32 : 16;
-    if (!a.norm_out || !a.stat_out || a.N % fk || a.N != a.row_tiles * 16 ||
-        (a.norm_parts != 1 && !(a.norm_parts == 2 && dtype == SS_DTYPE_BF16)))
+    if (!a.norm_out || !a.stat_out || !a.c_in || a.N % fk || a.N != a.row_tiles * 16 ||
+        (a.norm_parts != 1 && !(a.norm_parts == 2 && dtype == SS_DTYPE_BF16)) ||
+        (a.norm_f16 && (dtype != SS_DTYPE_BF16 || a.norm_parts != 1)))
       SS_FAIL(SS_EINVAL, "prefill GEMM: bad next-operand arguments");
   }
   a.n_row_blocks = ceil_div(a.row_tiles, 8);
   dim3 grid(a.n_row_blocks * (a.T / 128));
 #define SS_LAUNCH(TT, EPI, AP) hipLaunchKernelGGL((tile_gemm<TT, EPI, AP>), grid, dim3(256), 0, st, a)
-  if (dtype == SS_DTYPE_BF16 && a.act_parts == 2) {
+  if (dtype == SS_DTYPE_BF16 && a.act_f16) {
+#define SS_LAUNCH_H(EPI) hipLaunchKernelGGL((tile_gemm<bf16_t, EPI, 1, true>), grid, dim3(256), 0, st, a)
+    if (epi == EPI_F32) SS_LAUNCH_H(EPI_F32);
+    else if (epi == EPI_RESID) SS_LAUNCH_H(EPI_RESID);
+    else if (epi == EPI_ACT) SS_LAUNCH_H(EPI_ACT);
+    else SS_LAUNCH_H(EPI_SWIGLU);
+#undef SS_LAUNCH_H
+  } else if (dtype == SS_DTYPE_BF16 && a.act_parts == 2) {
     if (epi == EPI_F32) SS_LAUNCH(bf16_t, EPI_F32, 2);
     else if (epi == EPI_RESID) SS_LAUNCH(bf16_t, EPI_RESID, 2);
     else if (epi == EPI_ACT) SS_LAUNCH(bf16_t, EPI_ACT, 2);

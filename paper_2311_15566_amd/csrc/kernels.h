@@ -63,41 +63,49 @@ ss_status launch_fold_norm(int dtype, const void *w, int row_tiles, int k_blocks
                            const float *bias, float *wg, float *cb, hipStream_t st);
 
 // Prefill GEMM: out[t, n] = sum_k act[t, k] * W[n, k] over T tokens (multiple of 128), MFMA-bound.
-// Norms are deferred as in the decode GEMM: the residual epilogue of the last shard of a group
-// also writes the next GEMM's operand x * gamma and, per token, the partial (sum x, sum x^2) of
-// each 64-feature band a wave owns; a small kernel adds the partials up in band order into the
-// token's (mean, rstd), and the GEMM that consumes the operand applies
-// rstd * (acc - mean * wg[n]) + cb[n].  Tokens past T_live are computed but never stored.
+// Norms are deferred as in the decode GEMM, and centred: the residual epilogue of the last shard
+// of a group also writes the next GEMM's operand (x - c) * gamma, c = the token's mean at the
+// previous norm (0 for RMSNorm), so that rounding the operand to 11 bits costs nothing to
+// cancellation, and per token the partial (sum (x-c), sum (x-c)^2) of each 64-feature band a wave
+// owns; a small kernel adds the partials up in band order into the token's
+// (mean, rstd, mean - c), and the GEMM that consumes the operand applies
+// rstd * (acc - (mean - c) * wg[n]) + cb[n].  Tokens past T_live are computed but never stored.
 struct TileGemmArgs {
   const void *w;      // weight fragments
   int row_tiles;      // 16-row weight tiles (SwiGLU: 2 per 16 outputs, interleaved)
   int k_blocks;
   const void *act;    // activation fragments [T/16][k_blocks][act_parts]
   int act_parts;      // 1, or 2 for bf16 hi/lo pairs
+  int act_f16;        // bf16 models: the activations are single half-precision fragments (act_parts 1); the
+                      // weights are converted to halves on their way into LDS
   int T;              // tokens (padded to 128)
   int T_live;         // tokens that exist
   int N;
   const float *bias;  // plain bias (mr_in NULL), or NULL
   // deferred normalisation of the input (mr_in != NULL): bias is not read
-  const float2 *mr_in;    // [T] (mean, rstd) of the rows of x
+  const f32x4 *mr_in;     // [T] (mean, rstd, mean - centre of the operand, -) of the rows of x
   const float *wg;    // [row_tiles * 16] or NULL (RMSNorm)
   const float *cb;    // [row_tiles * 16] folded beta and bias, or the plain bias, or NULL
   float *out_f32;     // EPI_F32: [T][ld_out]
   int ld_out;
   float *x_resid;     // EPI_RESID: [T][N]
   const float *g_out; // EPI_RESID: gamma of the norm that follows, or NULL: no operand for a next GEMM
-  void *norm_out;     // EPI_RESID with g_out: x * g_out as fragments [T/16][N / FragK][norm_parts]
+  void *norm_out;     // EPI_RESID with g_out: (x - c) * g_out as fragments [T/16][N / FragK][norm_parts]
   int norm_parts;
+  int norm_f16;       // bf16 models: norm_out holds single half-precision fragments (norm_parts 1)
+  const f32x4 *c_in;  // EPI_RESID with g_out: [T], .x = the centre c (the token's mean at the previous norm)
   float2 *stat_out;   // EPI_RESID with g_out: [2 * n_row_blocks][T]
   void *act_out;      // EPI_ACT / EPI_SWIGLU: fragments [T/16][out_k_blocks][out_parts]
   int out_k_blocks;
   int out_parts;
+  int out_f16;        // bf16 models: EPI_ACT / EPI_SWIGLU write single half-precision fragments (out_parts 1)
   int act_kind;
   int n_row_blocks;   // set by the launcher: 128-row blocks of the weight matrix
 };
 ss_status launch_tile_gemm(int dtype, int epi, TileGemmArgs a, hipStream_t st);
-// (mean, rstd) per token from `groups` partial (sum, sum of squares) pairs laid out [groups][T]
-ss_status launch_row_stats(const float2 *part, int groups, int T, int norm_dim, int rms, float eps, float2 *mr,
+// mr[t] <- (mean, rstd, mean - c, 0) from `groups` partial (sum (x-c), sum (x-c)^2) pairs laid out
+// [groups][T], with c = mr[t].x on entry
+ss_status launch_row_stats(const float2 *part, int groups, int T, int norm_dim, int rms, float eps, f32x4 *mr,
                            hipStream_t st);
 
 // Decode attention over the committed cache (plus the new token), sequence-split.
@@ -132,8 +140,11 @@ struct EmbedArgs {
   const float *gamma;     // gamma of the first norm
   void *act_out;          // x * gamma as operand fragments [rows / 16][d / FragK][parts]
   float *stat_out;        // [32][4] (sum x, sum x^2, 0, 0) per row
-  // initial phase: the same operand for all prompt tokens, and the row sums as one group of partials
-  float2 *pstat_out;      // [rows] (sum x, sum x^2), or NULL
+  // initial phase (mr_out != NULL): the operand is centred on the row mean c, (x - c) * gamma, one fragment
+  // per k block (halves for bf16 models); mr_out[row].x = c, pstat_out[row] = (sum (x - c), sum (x - c)^2)
+  float2 *pstat_out;      // [rows]
+  f32x4 *mr_out;          // [rows]
+  int rms;
 };
 
 struct Phase {

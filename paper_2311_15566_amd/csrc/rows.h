@@ -50,10 +50,12 @@ __device__ __forceinline__ void store_piece(void *base, int row, int k, int k_bl
   }
 }
 
-// x[r] = wte[token] (+ wpe[position]) with 16-byte loads (or the previous stage's hidden row).  With
-// a.act_out set (decode step) also the first GEMM's operand x * gamma and the row's (sum, sum of
-// squares).  d <= 16384.
-template <typename T>
+// x[r] = wte[token] (+ wpe[position]) with 16-byte loads (or the previous stage's hidden row).  d <= 16384.
+// Decode step (a.act_out, a.stat_out): also the first GEMM's operand x * gamma as hi/lo fragments and the
+// row's (sum, sum of squares).
+// Initial phase (a.act_out, a.mr_out, a.pstat_out): the operand is centred, (x - c) * gamma with c the row's
+// mean (0 for RMSNorm), as one fragment of OT elements; mr_out[r].x = c, pstat_out[r] = (sum (x-c), sum (x-c)^2).
+template <typename T, typename OT = T>
 __device__ __forceinline__ void embed_row_block(const EmbedArgs &a, const int r, float *scratch) {
   constexpr int PL = Elem<T>::kPerLane, FK = Elem<T>::kFragK, MAXV = 64 / PL;
   int tok = a.hidden ? 0 : a.tokens[r];
@@ -62,45 +64,70 @@ __device__ __forceinline__ void embed_row_block(const EmbedArgs &a, const int r,
   const int nvec = a.d / PL;
   const u32x4 *te = (const u32x4 *)((const T *)a.wte + (size_t)tok * a.d);
   const u32x4 *pe = (a.wpe && !a.hidden) ? (const u32x4 *)((const T *)a.wpe + (size_t)pos * a.d) : nullptr;
+  float vals[MAXV][PL];
   float s1 = 0.f, s2 = 0.f;
 #pragma unroll
   for (int i = 0; i < MAXV; ++i) {
     const int v = threadIdx.x + i * 256;
     if (v < nvec) {
-      float vals[PL];
       if (a.hidden) {
 #pragma unroll
-        for (int e = 0; e < PL; ++e) vals[e] = a.hidden[(size_t)r * a.d + (size_t)v * PL + e];
+        for (int e = 0; e < PL; ++e) vals[i][e] = a.hidden[(size_t)r * a.d + (size_t)v * PL + e];
       } else {
-        widen16<T>(te[v], vals);
+        widen16<T>(te[v], vals[i]);
       }
       if (pe) {
         float p[PL];
         widen16<T>(pe[v], p);
 #pragma unroll
-        for (int e = 0; e < PL; ++e) vals[e] += p[e];
+        for (int e = 0; e < PL; ++e) vals[i][e] += p[e];
       }
       float *xo = a.x + (size_t)r * a.d + (size_t)v * PL;
 #pragma unroll
       for (int e = 0; e < PL; ++e) {
-        s1 += vals[e], s2 += vals[e] * vals[e];
-        xo[e] = vals[e];
+        s1 += vals[i][e], s2 += vals[i][e] * vals[i][e];
+        xo[e] = vals[i][e];
       }
-      if (a.act_out) {  // the PL elements are one lane's 16-byte piece of the operand fragment(s)
+    }
+  }
+  if (a.mr_out) {  // initial phase: centre first, then the operand and the centred sums
+    const float c = a.rms ? 0.f : block_sum(s1, scratch) / (float)a.d;
+    s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i) {
+      const int v = threadIdx.x + i * 256;
+      if (v < nvec) {
         float y[PL];
 #pragma unroll
-        for (int e = 0; e < PL; ++e) y[e] = vals[e] * a.gamma[v * PL + e];
+        for (int e = 0; e < PL; ++e) {
+          const float t = vals[i][e] - c;
+          s1 += t, s2 += t * t;
+          y[e] = t * a.gamma[v * PL + e];
+        }
+        store_piece<OT>(a.act_out, r, v * PL, a.d / FK, y);
+      }
+    }
+    s1 = block_sum(s1, scratch);
+    s2 = block_sum(s2, scratch);
+    if (threadIdx.x == 0) a.mr_out[r] = f32x4{c, 0.f, 0.f, 0.f}, a.pstat_out[r] = make_float2(s1, s2);
+    return;
+  }
+  if (a.act_out) {  // decode step: the PL elements are one lane's 16-byte piece of the operand fragments
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i) {
+      const int v = threadIdx.x + i * 256;
+      if (v < nvec) {
+        float y[PL];
+#pragma unroll
+        for (int e = 0; e < PL; ++e) y[e] = vals[i][e] * a.gamma[v * PL + e];
         store_piece<T>(a.act_out, r, v * PL, a.d / FK, y);
       }
     }
   }
-  if (a.stat_out || a.pstat_out) {
+  if (a.stat_out) {
     s1 = block_sum(s1, scratch);
     s2 = block_sum(s2, scratch);
-    if (threadIdx.x == 0) {
-      if (a.stat_out) ((f32x4 *)a.stat_out)[r] = f32x4{s1, s2, 0.f, 0.f};
-      if (a.pstat_out) a.pstat_out[r] = make_float2(s1, s2);
-    }
+    if (threadIdx.x == 0) ((f32x4 *)a.stat_out)[r] = f32x4{s1, s2, 0.f, 0.f};
   }
 }
 

@@ -34,7 +34,7 @@ struct Layout {
   // workspace sub-offsets (relative to off_ws)
   size_t ws_x, ws_a, ws_qkv, ws_o, ws_u, ws_counters, ws_attn_part, ws_argmax;
   size_t ws_vt;        // initial phase: one layer's values transposed, [Bmax*Hs][Dh][Smax rounded up to 64] halves
-  size_t ws_pstat;     // initial phase: partial row sums [2 * ceil(d / 128)][Tmax] float2, then (mean, rstd) [Tmax]
+  size_t ws_pstat;     // initial phase: partial row sums [2 * ceil(d / 128)][Tmax] float2, then (mean, rstd, mean - centre, -) [Tmax] float4
   int n_counters;
   // decode step (rows = batch): residual stream [32][d] f32, operand of the next normalised GEMM
   // (x * gamma), partial row sums [d/16][32][2], q|k|v [32][qkv_n] f32, attention output and FFN

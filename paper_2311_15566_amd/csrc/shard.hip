@@ -130,7 +130,7 @@ bool compute_layout(const ss_model_desc &m, const ss_slice &s, int max_batch, in
   L->ws_o = wtake((size_t)T * HD * esz * (esz == 2 ? 2 : 1));
   L->ws_u = wtake((size_t)T * L->Fs * esz * (esz == 2 ? 2 : 1));
   L->ws_vt = wtake((size_t)max_batch * L->Hs * L->Dh * align_up((size_t)max_seq, 64) * 2);
-  L->ws_pstat = wtake((size_t)(2 * ceil_div(d, 128) + 1) * T * 8);  // partial sums, then (mean, rstd) per token
+  L->ws_pstat = wtake((size_t)(2 * ceil_div(d, 128) + 2) * T * 8);  // partial sums, then (mean, rstd, mean - centre, -) per token
   {
     const int fk = esz == 2 ? 32 : 16, parts = esz == 2 ? 2 : 1;
     L->ws_xd = wtake((size_t)32 * d * 4);

@@ -150,7 +150,7 @@ CASES = [
     ("gpt20b_m4", "bf16", dict(batch=6, s_in=40, steps=4, wte_offset=0.5)),
     # (float32: acc and mean * folded gamma are each ~25x the result and the variance is the difference of two
     # numbers ~625x its size, so float32 rounding of ~1e-7 shows up ~25-600x larger: bar 3e-5 instead of 1e-5)
-    ("gpt20b_m4", "f32", dict(batch=2, s_in=20, steps=3, wte_offset=0.5, f32_rel=3e-5)),
+    ("gpt20b_m4", "f32", dict(batch=2, s_in=20, steps=3, wte_offset=0.5, f32_rel=1e-5)),
     ("llama30b_m2", "bf16", dict(batch=4, s_in=40, steps=3, wte_offset=0.5)),
 ]
 
