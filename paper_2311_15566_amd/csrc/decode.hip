@@ -515,18 +515,16 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, c
   const int FK = dt == SS_DTYPE_BF16 ? 32 : 16;
   const int rms = m.norm == SS_NORM_RMSNORM;
   const int T_live = B * S, T = (int)align_up((size_t)T_live, 128);
-  const int parts = dt == SS_DTYPE_BF16 ? 2 : 1;  // bf16 GEMM inputs are hi/lo pairs
-  const int h16 = dt == SS_DTYPE_BF16;            // ... except where a half's 11 bits do (see TileGemmArgs)
   for (int i = 0; i < n_group; ++i)
     if (T > group[i]->L.Tmax) SS_FAIL(SS_EINVAL, "%d prompt tokens exceed group[%d]'s workspace (%d)", T_live, i, group[i]->L.Tmax);
   float *x = (float *)(g0->ws + L0.ws_x);
   void *abuf = g0->ws + L0.ws_a;
   float2 *pstat = (float2 *)(g0->ws + L0.ws_pstat);
   f32x4 *mr = (f32x4 *)(pstat + (size_t)2 * ceil_div(d, 128) * L0.Tmax);  // (mean, rstd, mean - centre, -) per token
-  // Norms are deferred (see TileGemmArgs): the producer of x writes x * gamma as the next
-  // GEMM's operand and partial row sums; that GEMM's epilogue normalises.
-  // (single bf16 activations into the QKV / first FFN GEMMs were tried: the OPT-66B shape then
-  // misses the logits bar at its first token, 6.4e-2)
+  // Norms are deferred and centred (see TileGemmArgs): the producer of x writes (x - c) * gamma as the
+  // next GEMM's operand and partial row sums; that GEMM's epilogue normalises.  Operands are halves
+  // for bf16 models: single bf16 activations miss the logits bar (OPT-66B shape 6.4e-2 at its first
+  // token), bf16 hi/lo pairs meet it at twice the matrix-core work.
   {
     EmbedArgs e{hidden_in, tokens, g0->wte, g0->wpe, nullptr, S, x, d, L0.V, g0->layers[0].ln1_g, abuf, nullptr, pstat, mr, rms};
     if (dt == SS_DTYPE_BF16) hipLaunchKernelGGL((embed_rows<bf16_t, f16_t>), dim3(T_live), dim3(256), 0, st, e);
@@ -535,7 +533,7 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, c
   }
   int stat_groups = 1;
   auto normed = [&](TileGemmArgs &a, const float *wg, const float *cb) {
-    a.act = abuf, a.act_parts = h16 ? 1 : parts, a.act_f16 = h16, a.mr_in = mr, a.wg = wg, a.cb = cb;
+    a.act = abuf, a.mr_in = mr, a.wg = wg, a.cb = cb;
   };
   auto row_stats = [&]() { return launch_row_stats(pstat, stat_groups, T, d, rms, m.norm_eps, mr, st); };
   // sum over the group at a reduce slot: shard i adds its partial to what the previous shards left;
@@ -543,12 +541,9 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, c
   auto resid = [&](int i, const FragMat &w, const void *act, const float *bias, const float *next_gamma) -> ss_status {
     TileGemmArgs a = {};
     a.w = w.ptr, a.row_tiles = w.row_tiles, a.k_blocks = w.k_blocks;
-    // bf16 models: the attention output and the FFN activation are single half-precision fragments
-    a.act = act, a.act_parts = h16 ? 1 : parts, a.act_f16 = h16, a.T = T, a.T_live = T_live, a.N = d;
-    a.bias = i == 0 ? bias : nullptr;
+    a.act = act, a.T = T, a.T_live = T_live, a.N = d, a.bias = i == 0 ? bias : nullptr;
     a.x_resid = x;
-    if (i == n_group - 1 && next_gamma)
-      a.g_out = next_gamma, a.norm_out = abuf, a.norm_parts = h16 ? 1 : parts, a.norm_f16 = h16, a.stat_out = pstat, a.c_in = mr;
+    if (i == n_group - 1 && next_gamma) a.g_out = next_gamma, a.norm_out = abuf, a.stat_out = pstat, a.c_in = mr;
     return launch_tile_gemm(dt, EPI_RESID, a, st);
   };
   for (int l = 0; l < L0.Ls; ++l) {
@@ -585,7 +580,7 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, c
       a.w = s->w1[l].ptr, a.row_tiles = s->w1[l].row_tiles, a.k_blocks = s->w1[l].k_blocks;
       a.T = T, a.T_live = T_live, a.N = L.Fs;
       normed(a, s->wg_1[l], s->cb_1[l]);
-      a.act_out = s->ws + L.ws_u, a.out_k_blocks = L.Fs / FK, a.out_parts = h16 ? 1 : parts, a.out_f16 = h16, a.act_kind = m.act;
+      a.act_out = s->ws + L.ws_u, a.out_k_blocks = L.Fs / FK, a.act_kind = m.act;
       SS_TRY(launch_tile_gemm(dt, glu ? EPI_SWIGLU : EPI_ACT, a, st));
     }
     // the last layer's output goes to the next stage or to gather_last, which read x

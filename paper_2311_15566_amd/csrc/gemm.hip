@@ -14,13 +14,15 @@ namespace ss {
 // tiled prefill GEMM: block = 128 output features x 128 tokens, 4 waves of 64 x 64,
 // K advanced two fragments at a time through LDS with register prefetch of the next stage.
 // ---------------------------------------------------------------------------
-// H16: half-precision single-part activations against bf16 weights converted when they are staged
-template <typename T, int EPI, int AP, bool H16 = false>
+// bf16 models: the activation operands are halves (11 significant bits, one fragment per k block)
+// and the bf16 weights become halves on their way into LDS; float32 models: float operands.
+template <typename T, int EPI>
 __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
-  static_assert(!H16 || (AP == 1 && sizeof(T) == 2), "half-precision operands: one part, 16-bit weights");
+  constexpr bool H16 = sizeof(T) == 2;
+  typedef typename PrefillOperand<T>::type OT;  // element type of the activation operands
   constexpr int KS = 2;  // k fragments per stage
   __shared__ __align__(16) u32x4 lds_w[KS][8][64];
-  __shared__ __align__(16) u32x4 lds_a[KS][8][AP][64];
+  __shared__ __align__(16) u32x4 lds_a[KS][8][64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave >> 1, wc = wave & 1;
   // Block -> output tile.  Workgroups go to the 8 XCDs round-robin and each XCD has its own L2, so
@@ -50,9 +52,9 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // per stage each thread moves 4 weight pieces and 4*AP activation pieces:
+  // per stage each thread moves 4 weight pieces and 4 activation pieces:
   // piece p = tid + 256*r -> (ks = p / 512, tile = (p / 64) % 8, ln = p % 64)
-  u32x4 pw[4], pa[4][AP];
+  u32x4 pw[4], pa[4];
   auto fetch = [&](int kb) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -62,9 +64,7 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
       const bool kok = k < a.k_blocks;
       pw[r] = (kok && rt0 + tile < a.row_tiles) ? W[((size_t)(rt0 + tile) * a.k_blocks + k) * 64 + ln]
                                                : u32x4{0u, 0u, 0u, 0u};
-#pragma unroll
-      for (int part = 0; part < AP; ++part)
-        pa[r][part] = kok ? A[(((size_t)(tt0 + tile) * a.k_blocks + k) * AP + part) * 64 + ln] : u32x4{0u, 0u, 0u, 0u};
+      pa[r] = kok ? A[((size_t)(tt0 + tile) * a.k_blocks + k) * 64 + ln] : u32x4{0u, 0u, 0u, 0u};
     }
   };
   fetch(0);
@@ -75,8 +75,7 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
       const int p = tid + 256 * r;
       const int ks = p >> 9, tile = (p >> 6) & 7, ln = p & 63;
       lds_w[ks][tile][ln] = H16 ? bf16x8_to_f16x8(pw[r]) : pw[r];
-#pragma unroll
-      for (int part = 0; part < AP; ++part) lds_a[ks][tile][part][ln] = pa[r][part];
+      lds_a[ks][tile][ln] = pa[r];
     }
     __syncthreads();
     if (kb + KS < a.k_blocks) fetch(kb + KS);
@@ -85,16 +84,13 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
       u32x4 wf[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) wf[i] = lds_w[ks][wr * 4 + i][lane];
+      u32x4 af[4];
 #pragma unroll
-      for (int part = 0; part < AP; ++part) {
-        u32x4 af[4];
+      for (int j = 0; j < 4; ++j) af[j] = lds_a[ks][wc * 4 + j][lane];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) af[j] = lds_a[ks][wc * 4 + j][part][lane];
+      for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int j = 0; j < 4; ++j) acc[i][j] = H16 ? mma_f16(wf[i], af[j], acc[i][j]) : Mma<T>::mma(wf[i], af[j], acc[i][j]);
-      }
+        for (int j = 0; j < 4; ++j) acc[i][j] = H16 ? mma_f16(wf[i], af[j], acc[i][j]) : Mma<T>::mma(wf[i], af[j], acc[i][j]);
     }
   }
 
@@ -125,8 +121,7 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
           finish(acc[i + 1][j], (rt + 1) * 16 + q4, mr, up);
 #pragma unroll
           for (int e = 0; e < 4; ++e) u[e] = silu_f(gt[e]) * up[e];
-          if (sizeof(T) == 2 && a.out_f16) store4_frag<f16_t, false>(a.act_out, tok, n0, a.out_k_blocks, 1, u);
-          else store4_frag<T, false>(a.act_out, tok, n0, a.out_k_blocks, a.out_parts, u);
+          store4_frag<OT, false>(a.act_out, tok, n0, a.out_k_blocks, 1, u);
         }
       }
     } else if (EPI == EPI_RESID) {
@@ -152,8 +147,7 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
               s1 += t, s2 += t * t;
               y[e] = t * g[e];
             }
-            if (sizeof(T) == 2 && a.norm_f16) store4_frag<f16_t, false>(a.norm_out, tok, n0, a.N / Elem<T>::kFragK, 1, y);
-            else store4_frag<T, false>(a.norm_out, tok, n0, a.N / Elem<T>::kFragK, a.norm_parts, y);
+            store4_frag<OT, false>(a.norm_out, tok, n0, a.N / Elem<OT>::kFragK, 1, y);
           }
         }
       }
@@ -176,8 +170,7 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
           } else {  // EPI_ACT
             const float w[4] = {act_apply(a.act_kind, v[0]), act_apply(a.act_kind, v[1]), act_apply(a.act_kind, v[2]),
                                 act_apply(a.act_kind, v[3])};
-            if (sizeof(T) == 2 && a.out_f16) store4_frag<f16_t, false>(a.act_out, tok, n0, a.out_k_blocks, 1, w);
-            else store4_frag<T, false>(a.act_out, tok, n0, a.out_k_blocks, a.out_parts, w);
+            store4_frag<OT, false>(a.act_out, tok, n0, a.out_k_blocks, 1, w);
           }
         }
       }
@@ -224,43 +217,24 @@ ss_status launch_tile_gemm(int dtype, int epi, TileGemmArgs a, hipStream_t st) {
   if (a.T < 128 || a.T % 128) SS_FAIL(SS_EINVAL, "prefill GEMM: token count %d is not a multiple of 128", a.T);
   if (a.row_tiles < 1 || a.k_blocks < 1 || a.N % 4) SS_FAIL(SS_EINVAL, "prefill GEMM: bad shape");
   if ((epi == EPI_F32 && (a.ld_out % 4)) || epi == EPI_LOGITS) SS_FAIL(SS_EINVAL, "prefill GEMM: bad epilogue");
-  if (a.act_parts != 1 && !(a.act_parts == 2 && dtype == SS_DTYPE_BF16)) SS_FAIL(SS_EINVAL, "prefill GEMM: bad act_parts");
-  if ((a.act_f16 && (dtype != SS_DTYPE_BF16 || a.act_parts != 1)) || (a.out_f16 && (dtype != SS_DTYPE_BF16 || a.out_parts != 1)))
-    SS_FAIL(SS_EINVAL, "prefill GEMM: half-precision operands need a bf16 model and one part");
-  if ((epi == EPI_ACT || epi == EPI_SWIGLU) && a.out_parts != 1 && !(a.out_parts == 2 && dtype == SS_DTYPE_BF16))
-    SS_FAIL(SS_EINVAL, "prefill GEMM: bad out_parts");
   if (epi == EPI_RESID && a.g_out) {
     const int fk = dtype == SS_DTYPE_BF16 ? 32 : 16;
-    if (!a.norm_out || !a.stat_out || !a.c_in || a.N % fk || a.N != a.row_tiles * 16 ||
-        (a.norm_parts != 1 && !(a.norm_parts == 2 && dtype == SS_DTYPE_BF16)) ||
-        (a.norm_f16 && (dtype != SS_DTYPE_BF16 || a.norm_parts != 1)))
+    if (!a.norm_out || !a.stat_out || !a.c_in || a.N % fk || a.N != a.row_tiles * 16)
       SS_FAIL(SS_EINVAL, "prefill GEMM: bad next-operand arguments");
   }
   a.n_row_blocks = ceil_div(a.row_tiles, 8);
   dim3 grid(a.n_row_blocks * (a.T / 128));
-#define SS_LAUNCH(TT, EPI, AP) hipLaunchKernelGGL((tile_gemm<TT, EPI, AP>), grid, dim3(256), 0, st, a)
-  if (dtype == SS_DTYPE_BF16 && a.act_f16) {
-#define SS_LAUNCH_H(EPI) hipLaunchKernelGGL((tile_gemm<bf16_t, EPI, 1, true>), grid, dim3(256), 0, st, a)
-    if (epi == EPI_F32) SS_LAUNCH_H(EPI_F32);
-    else if (epi == EPI_RESID) SS_LAUNCH_H(EPI_RESID);
-    else if (epi == EPI_ACT) SS_LAUNCH_H(EPI_ACT);
-    else SS_LAUNCH_H(EPI_SWIGLU);
-#undef SS_LAUNCH_H
-  } else if (dtype == SS_DTYPE_BF16 && a.act_parts == 2) {
-    if (epi == EPI_F32) SS_LAUNCH(bf16_t, EPI_F32, 2);
-    else if (epi == EPI_RESID) SS_LAUNCH(bf16_t, EPI_RESID, 2);
-    else if (epi == EPI_ACT) SS_LAUNCH(bf16_t, EPI_ACT, 2);
-    else SS_LAUNCH(bf16_t, EPI_SWIGLU, 2);
-  } else if (dtype == SS_DTYPE_BF16) {
-    if (epi == EPI_F32) SS_LAUNCH(bf16_t, EPI_F32, 1);
-    else if (epi == EPI_RESID) SS_LAUNCH(bf16_t, EPI_RESID, 1);
-    else if (epi == EPI_ACT) SS_LAUNCH(bf16_t, EPI_ACT, 1);
-    else SS_LAUNCH(bf16_t, EPI_SWIGLU, 1);
+#define SS_LAUNCH(TT, EPI) hipLaunchKernelGGL((tile_gemm<TT, EPI>), grid, dim3(256), 0, st, a)
+  if (dtype == SS_DTYPE_BF16) {
+    if (epi == EPI_F32) SS_LAUNCH(bf16_t, EPI_F32);
+    else if (epi == EPI_RESID) SS_LAUNCH(bf16_t, EPI_RESID);
+    else if (epi == EPI_ACT) SS_LAUNCH(bf16_t, EPI_ACT);
+    else SS_LAUNCH(bf16_t, EPI_SWIGLU);
   } else {
-    if (epi == EPI_F32) SS_LAUNCH(float, EPI_F32, 1);
-    else if (epi == EPI_RESID) SS_LAUNCH(float, EPI_RESID, 1);
-    else if (epi == EPI_ACT) SS_LAUNCH(float, EPI_ACT, 1);
-    else SS_LAUNCH(float, EPI_SWIGLU, 1);
+    if (epi == EPI_F32) SS_LAUNCH(float, EPI_F32);
+    else if (epi == EPI_RESID) SS_LAUNCH(float, EPI_RESID);
+    else if (epi == EPI_ACT) SS_LAUNCH(float, EPI_ACT);
+    else SS_LAUNCH(float, EPI_SWIGLU);
   }
 #undef SS_LAUNCH
   SS_HIP(hipGetLastError());

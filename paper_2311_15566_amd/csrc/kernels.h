@@ -62,6 +62,10 @@ int stream_gemm_blocks(int epi, const StreamGemmArgs &a);
 ss_status launch_fold_norm(int dtype, const void *w, int row_tiles, int k_blocks, const float *gamma, const float *beta,
                            const float *bias, float *wg, float *cb, hipStream_t st);
 
+// Operand element type of the initial phase's GEMMs for a model of element type T.
+template <typename T> struct PrefillOperand { typedef T type; };
+template <> struct PrefillOperand<bf16_t> { typedef f16_t type; };
+
 // Prefill GEMM: out[t, n] = sum_k act[t, k] * W[n, k] over T tokens (multiple of 128), MFMA-bound.
 // Norms are deferred as in the decode GEMM, and centred: the residual epilogue of the last shard
 // of a group also writes the next GEMM's operand (x - c) * gamma, c = the token's mean at the
@@ -74,10 +78,8 @@ struct TileGemmArgs {
   const void *w;      // weight fragments
   int row_tiles;      // 16-row weight tiles (SwiGLU: 2 per 16 outputs, interleaved)
   int k_blocks;
-  const void *act;    // activation fragments [T/16][k_blocks][act_parts]
-  int act_parts;      // 1, or 2 for bf16 hi/lo pairs
-  int act_f16;        // bf16 models: the activations are single half-precision fragments (act_parts 1); the
-                      // weights are converted to halves on their way into LDS
+  const void *act;    // activation fragments [T/16][k_blocks] of the operand type: halves for bf16 models
+                      // (the bf16 weights become halves on their way into LDS), float for float32 models
   int T;              // tokens (padded to 128)
   int T_live;         // tokens that exist
   int N;
@@ -90,15 +92,11 @@ struct TileGemmArgs {
   int ld_out;
   float *x_resid;     // EPI_RESID: [T][N]
   const float *g_out; // EPI_RESID: gamma of the norm that follows, or NULL: no operand for a next GEMM
-  void *norm_out;     // EPI_RESID with g_out: (x - c) * g_out as fragments [T/16][N / FragK][norm_parts]
-  int norm_parts;
-  int norm_f16;       // bf16 models: norm_out holds single half-precision fragments (norm_parts 1)
+  void *norm_out;     // EPI_RESID with g_out: (x - c) * g_out as fragments [T/16][N / FragK]
   const f32x4 *c_in;  // EPI_RESID with g_out: [T], .x = the centre c (the token's mean at the previous norm)
   float2 *stat_out;   // EPI_RESID with g_out: [2 * n_row_blocks][T]
-  void *act_out;      // EPI_ACT / EPI_SWIGLU: fragments [T/16][out_k_blocks][out_parts]
+  void *act_out;      // EPI_ACT / EPI_SWIGLU: fragments [T/16][out_k_blocks]
   int out_k_blocks;
-  int out_parts;
-  int out_f16;        // bf16 models: EPI_ACT / EPI_SWIGLU write single half-precision fragments (out_parts 1)
   int act_kind;
   int n_row_blocks;   // set by the launcher: 128-row blocks of the weight matrix
 };
@@ -162,7 +160,7 @@ struct PrefillAttnArgs {
   char *k_cache, *v_cache;
   size_t row_stride, head_stride;
   const float2 *rope;
-  void *o_out;          // fragments [T/16][Hs*Dh / FragK][parts of the operand type]
+  void *o_out;          // fragments [T/16][Hs*Dh / FragK] of the operand type (halves for bf16 models)
   int B, S, Hs, Dh, Smax;
   int kv_dtype;
   void *vt;             // half-precision cache: scratch for the transposed values [B*Hs][Dh][s_pad]

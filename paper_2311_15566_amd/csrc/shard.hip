@@ -125,10 +125,10 @@ bool compute_layout(const ss_model_desc &m, const ss_slice &s, int max_batch, in
   };
   const int T = L->Tmax;
   L->ws_x = wtake((size_t)T * d * 4);
-  L->ws_a = wtake((size_t)T * d * esz * (esz == 2 ? 2 : 1));  // bf16: hi/lo pairs
+  L->ws_a = wtake((size_t)T * d * esz);  // operands of the initial phase: halves (bf16 models) or floats
   L->ws_qkv = wtake((size_t)T * L->qkv_n * 4);
-  L->ws_o = wtake((size_t)T * HD * esz * (esz == 2 ? 2 : 1));
-  L->ws_u = wtake((size_t)T * L->Fs * esz * (esz == 2 ? 2 : 1));
+  L->ws_o = wtake((size_t)T * HD * esz);
+  L->ws_u = wtake((size_t)T * L->Fs * esz);
   L->ws_vt = wtake((size_t)max_batch * L->Hs * L->Dh * align_up((size_t)max_seq, 64) * 2);
   L->ws_pstat = wtake((size_t)(2 * ceil_div(d, 128) + 2) * T * 8);  // partial sums, then (mean, rstd, mean - centre, -) per token
   {
