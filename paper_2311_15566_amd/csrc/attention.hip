@@ -30,12 +30,12 @@ ss_status launch_decode_attn(int dtype, const DecodeAttnArgs &a, hipStream_t st)
     if (a.waves == 16) SS_LAUNCH_KERNEL((decode_attn<KT, AT, DH, 16>), grid, dim3(1024), 0, st, a); \
     else SS_LAUNCH_KERNEL((decode_attn<KT, AT, DH, 4>), grid, dim3(256), 0, st, a);                \
   } while (0)
-  if (dtype == SS_DTYPE_BF16 && a.kv_dtype == SS_DTYPE_F16) {
-    if (a.Dh == 128) SS_LAUNCH(f16_t, bf16_t, 128);
-    else SS_LAUNCH(f16_t, bf16_t, 64);
+  if (dtype == SS_DTYPE_BF16 && a.kv_dtype == SS_DTYPE_F16) {  // bf16 models: the output operand is halves
+    if (a.Dh == 128) SS_LAUNCH(f16_t, f16_t, 128);
+    else SS_LAUNCH(f16_t, f16_t, 64);
   } else if (dtype == SS_DTYPE_BF16 && a.kv_dtype == SS_DTYPE_BF16) {
-    if (a.Dh == 128) SS_LAUNCH(bf16_t, bf16_t, 128);
-    else SS_LAUNCH(bf16_t, bf16_t, 64);
+    if (a.Dh == 128) SS_LAUNCH(bf16_t, f16_t, 128);
+    else SS_LAUNCH(bf16_t, f16_t, 64);
   } else if (dtype == SS_DTYPE_F32 && a.kv_dtype == SS_DTYPE_F32) {
     if (a.Dh == 128) SS_LAUNCH(float, float, 128);
     else SS_LAUNCH(float, float, 64);
@@ -151,7 +151,7 @@ __global__ void __launch_bounds__(256) prefill_attn(PrefillAttnArgs a) {
     const int tok = b * a.S + qi;
 #pragma unroll
     for (int e = 0; e < DP; ++e)
-      store_act<AT>(a.o_out, tok, h * DH + part * DP + e, HD / Elem<AT>::kFragK, Elem<AT>::kParts, acc[e] * inv);
+      store_act<AT>(a.o_out, tok, h * DH + part * DP + e, HD / Elem<AT>::kFragK, 1, acc[e] * inv);
   }
 }
 
@@ -311,7 +311,7 @@ __global__ void __launch_bounds__(256) prefill_attn_mfma(PrefillAttnArgs a) {
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
       const float v[4] = {acc[dt][0] * inv, acc[dt][1] * inv, acc[dt][2] * inv, acc[dt][3] * inv};
-      store4_frag<AT, false>(a.o_out, tok, h * DH + dt * 16 + g * 4, HD / Elem<AT>::kFragK, Elem<AT>::kParts, v);
+      store4_frag<AT, false>(a.o_out, tok, h * DH + dt * 16 + g * 4, HD / Elem<AT>::kFragK, 1, v);
     }
   }
 }

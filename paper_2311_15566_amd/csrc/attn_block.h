@@ -6,7 +6,7 @@
 
 namespace ss {
 
-// KT: cache element type; AT: activation operand type of the GEMM that consumes the output
+// T: cache element type; AT: element type of the operand of the GEMM that consumes the output
 template <typename T, int DH> struct RowGeom {
   static constexpr int EPL = Elem<T>::kPerLane;      // elements per lane (16 bytes)
   static constexpr int LPR = DH / EPL;               // lanes per cache row
@@ -236,23 +236,15 @@ __device__ __forceinline__ void decode_attn_block(const DecodeAttnArgs &a, const
     const float Lf = Lsum * f0 + p;
     const float o = (A * f0 + p * vnew) / Lf;
     // neighbouring dims pair up so that the operand buffer is written in whole words
-    constexpr int AP = Elem<AT>::kParts;
     const float o_next = __shfl_xor(o, 1);
     if (sizeof(AT) == 4) {
-      float *p = (float *)a.o_out + frag_offset_parts<AT>(b, h * DH + tid, HD / Elem<AT>::kFragK, AP, 0);
+      float *p = (float *)a.o_out + frag_offset<AT>(b, h * DH + tid, HD / Elem<AT>::kFragK);
       st_dev(p, o);
     } else if ((tid & 1) == 0) {
-      const int k = h * DH + tid;
-      const AT h0 = Elem<AT>::from_f32(o), h1 = Elem<AT>::from_f32(o_next);
-#pragma unroll
-      for (int part = 0; part < AP; ++part) {
-        AT w[2];
-        w[0] = part == 0 ? h0 : Elem<AT>::from_f32(o - Elem<AT>::to_f32(h0));
-        w[1] = part == 0 ? h1 : Elem<AT>::from_f32(o_next - Elem<AT>::to_f32(h1));
-        uint32_t word;
-        __builtin_memcpy(&word, w, 4);
-        st_dev((uint32_t *)((AT *)a.o_out + frag_offset_parts<AT>(b, k, HD / Elem<AT>::kFragK, AP, part)), word);
-      }
+      const AT w[2] = {Elem<AT>::from_f32(o), Elem<AT>::from_f32(o_next)};
+      uint32_t word;
+      __builtin_memcpy(&word, w, 4);
+      st_dev((uint32_t *)((AT *)a.o_out + frag_offset<AT>(b, h * DH + tid, HD / Elem<AT>::kFragK)), word);
     }
   }
 }

@@ -78,7 +78,7 @@ template <typename T> struct Elem;
 template <> struct Elem<f16_t> {
   static constexpr int kPerLane = 8;
   static constexpr int kFragK = 32;
-  static constexpr int kParts = 1;     // as a GEMM operand of the initial phase: 11 significant bits, one fragment
+  static constexpr int kParts = 1;     // the activation operand type of bf16 models: 11 significant bits
   __host__ __device__ static float to_f32(f16_t v) { return (float)v; }
   // round-to-nearest-even, saturating at the largest finite half
   __host__ __device__ static f16_t from_f32(float v) {
@@ -96,11 +96,9 @@ template <> struct Elem<float> {
 template <> struct Elem<bf16_t> {
   static constexpr int kPerLane = 8;
   static constexpr int kFragK = 32;
-  // bf16 activations that feed a weight-streaming GEMM are carried as hi + lo pairs
-  // (x = hi + lo, both bf16, ~16 mantissa bits): two fragments per k block, two MFMAs per
-  // weight fragment.  The matrix cores idle in these HBM-bound kernels, and the logits
-  // error drops from ~7e-3 to ~3.6e-3 relative (what the bf16 KV cache alone costs).
-  static constexpr int kParts = 2;
+  // (activations of bf16 models are never stored as bf16: 8 significant bits miss the logits bar on
+  // the larger shapes; the GEMM operands are halves, see Operand)
+  static constexpr int kParts = 1;
   __host__ __device__ static float to_f32(bf16_t v) { return bf16_to_f32(v); }
   __host__ __device__ static bf16_t from_f32(float v) { return f32_to_bf16(v); }
 };

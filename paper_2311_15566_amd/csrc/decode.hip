@@ -16,18 +16,18 @@ namespace ss {
 // ---------------------------------------------------------------------------
 // row kernels
 // ---------------------------------------------------------------------------
-// OT: element type of the operand the initial phase writes (halves for bf16 models)
-template <typename T, typename OT = T>
+template <typename T>
 __global__ void __launch_bounds__(256) embed_rows(EmbedArgs a) {
   __shared__ float scratch[4];
-  embed_row_block<T, OT>(a, blockIdx.x, scratch);
+  embed_row_block<T>(a, blockIdx.x, scratch);
 }
 
 // last prompt position of every sequence -> the decode step's residual rows, with the final
-// norm's operand (x * gamma) and the rows' (sum, sum of squares)
+// norm's operand (x - c) * gamma, c the row's mean (RMSNorm: 0), the centred sums and c
 template <typename T>
 __global__ void __launch_bounds__(256) gather_last(const float *x, int S, float *xd, const float *gamma, void *act_out,
-                                                   float *stat_out, int d) {
+                                                   float *stat_out, float *cen_out, int d, int rms) {
+  typedef typename Operand<T>::type OT;
   __shared__ float scratch[4];
   const int b = blockIdx.x;
   const float *src = x + ((size_t)b * S + S - 1) * d;
@@ -35,19 +35,31 @@ __global__ void __launch_bounds__(256) gather_last(const float *x, int S, float 
   constexpr int PL = Elem<T>::kPerLane;
   float s1 = 0.f, s2 = 0.f;
   for (int k = threadIdx.x * PL; k < d; k += 256 * PL) {
-    float y[PL];
 #pragma unroll
     for (int e = 0; e < PL; ++e) {
       const float v = src[k + e];
       dst[k + e] = v;
-      s1 += v, s2 += v * v;
-      y[e] = v * gamma[k + e];
+      s1 += v;
     }
-    store_piece<T>(act_out, b, k, d / Elem<T>::kFragK, y);
+  }
+  const float c = rms ? 0.f : block_sum(s1, scratch) / (float)d;
+  s1 = 0.f;
+  for (int k = threadIdx.x * PL; k < d; k += 256 * PL) {
+    float y[PL];
+#pragma unroll
+    for (int e = 0; e < PL; ++e) {
+      const float t = src[k + e] - c;
+      s1 += t, s2 += t * t;
+      y[e] = t * gamma[k + e];
+    }
+    store_piece<OT>(act_out, b, k, d / Elem<T>::kFragK, y);
   }
   s1 = block_sum(s1, scratch);
   s2 = block_sum(s2, scratch);
-  if (threadIdx.x == 0) ((f32x4 *)stat_out)[b] = f32x4{s1, s2, 0.f, 0.f};
+  if (threadIdx.x == 0) {
+    ((f32x4 *)stat_out)[b] = f32x4{s1, s2, 0.f, 0.f};
+    if (cen_out) cen_out[b] = c;
+  }
 }
 
 // token-level commit of a stage that hands hidden states on (no LM head): the last action of its step
@@ -203,19 +215,21 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
   float *x = (float *)(g0->ws + L0.ws_xd);
   void *ad = g0->ws + L0.ws_ad;
   float *statd = (float *)(g0->ws + L0.ws_statd);
+  float *cen = rms ? nullptr : (float *)(g0->ws + L0.ws_cen);  // the rows' means at the last norm: centres of the next operand
   const float *first_gamma = g0->layers[0].ln1_g;
   plan->clear();
   {
     Phase ph = {};
     ph.kind = PH_EMBED, ph.gx = B, ph.gy = 1;
-    ph.e = EmbedArgs{hidden_in, tokens_in, g0->wte, g0->wpe, g0->d_len, 0, x, d, L0.V, first_gamma, ad, statd};
+    ph.e = EmbedArgs{hidden_in, tokens_in, g0->wte, g0->wpe, g0->d_len, 0, x, d, L0.V, first_gamma, ad, rms, statd, cen};
     plan->push_back(ph);
   }
   int stat_groups = 1;  // partial-sum groups behind the rows in statd
   // a GEMM whose input is Norm(x): operand x * gamma from the producer of x, statistics deferred
-  auto normed = [&](StreamGemmArgs &a, const float *wg, const float *cb) {
+  auto normed = [&](StreamGemmArgs &a, const float *wg, const float *cb, int shard) {
     a.act = ad, a.stat_in = statd, a.stat_groups = stat_groups, a.norm_dim = d, a.rms = rms, a.eps = m.norm_eps;
     a.wg = wg, a.cb = cb;
+    if (shard == 0) a.cen = cen, a.publish = 1;  // one consumer leaves the new mean for the next producer
   };
   // sum over the group at a reduce slot: shard i adds its partial to what the previous shards
   // left; the last one also emits the next operand (x * next_gamma) and the partial sums
@@ -230,7 +244,7 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
     a.x_in = x, a.x_out = x;
     if (i == n_group - 1) {
       if (x_final) a.x_out = x_final;  // the stage's output: no next GEMM in this shard
-      else a.act_out = ad, a.out_k_blocks = d / FK, a.g_out = next_gamma, a.stat_out = statd;
+      else a.act_out = ad, a.out_k_blocks = d / FK, a.g_out = next_gamma, a.stat_out = statd, a.cen = cen;
     }
     shape_gemm(a, dt, EPI_RESID);
     ph.gx = a.n_blocks * a.bt_split, ph.gy = 1;
@@ -246,7 +260,7 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
       StreamGemmArgs &a = ph.g;
       a.w = s->wqkv[l].ptr, a.row_tiles = s->wqkv[l].row_tiles, a.k_blocks = s->wqkv[l].k_blocks, a.B = B, a.N = L.qkv_n;
       a.ks = pick_ks(a.k_blocks);
-      normed(a, s->wg_qkv[l], s->cb_qkv[l]);
+      normed(a, s->wg_qkv[l], s->cb_qkv[l], i);
       a.out_f32 = (float *)(s->ws + L.ws_qkvd), a.ld_out = L.qkv_n;
       shape_gemm(a, dt, EPI_F32);
       ph.gx = a.n_blocks * a.bt_split, ph.gy = 1;
@@ -281,7 +295,7 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
       StreamGemmArgs &a = ph.g;
       a.w = s->w1[l].ptr, a.row_tiles = s->w1[l].row_tiles, a.k_blocks = s->w1[l].k_blocks, a.B = B, a.N = L.Fs;
       a.ks = pick_ks(a.k_blocks);
-      normed(a, s->wg_1[l], s->cb_1[l]);
+      normed(a, s->wg_1[l], s->cb_1[l], i);
       a.act_out = s->ws + L.ws_ud, a.out_k_blocks = L.Fs / FK, a.act_kind = m.act;
       shape_gemm(a, dt, m.act == SS_ACT_SWIGLU ? EPI_SWIGLU : EPI_ACT);
       ph.gx = a.n_blocks * a.bt_split, ph.gy = 1;
@@ -526,9 +540,9 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, c
   // for bf16 models: single bf16 activations miss the logits bar (OPT-66B shape 6.4e-2 at its first
   // token), bf16 hi/lo pairs meet it at twice the matrix-core work.
   {
-    EmbedArgs e{hidden_in, tokens, g0->wte, g0->wpe, nullptr, S, x, d, L0.V, g0->layers[0].ln1_g, abuf, nullptr, pstat, mr, rms};
-    if (dt == SS_DTYPE_BF16) hipLaunchKernelGGL((embed_rows<bf16_t, f16_t>), dim3(T_live), dim3(256), 0, st, e);
-    else hipLaunchKernelGGL((embed_rows<float, float>), dim3(T_live), dim3(256), 0, st, e);
+    EmbedArgs e{hidden_in, tokens, g0->wte, g0->wpe, nullptr, S, x, d, L0.V, g0->layers[0].ln1_g, abuf, rms, nullptr, nullptr, pstat, mr};
+    if (dt == SS_DTYPE_BF16) hipLaunchKernelGGL(embed_rows<bf16_t>, dim3(T_live), dim3(256), 0, st, e);
+    else hipLaunchKernelGGL(embed_rows<float>, dim3(T_live), dim3(256), 0, st, e);
     SS_HIP(hipGetLastError());
   }
   int stat_groups = 1;
@@ -599,8 +613,9 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, c
   float *xd = (float *)(g0->ws + L0.ws_xd);
   void *ad = g0->ws + L0.ws_ad;
   float *statd = (float *)(g0->ws + L0.ws_statd);
-  if (dt == SS_DTYPE_BF16) hipLaunchKernelGGL(gather_last<bf16_t>, dim3(B), dim3(256), 0, st, x, S, xd, g0->lnf_g, ad, statd, d);
-  else hipLaunchKernelGGL(gather_last<float>, dim3(B), dim3(256), 0, st, x, S, xd, g0->lnf_g, ad, statd, d);
+  float *cen = rms ? nullptr : (float *)(g0->ws + L0.ws_cen);
+  if (dt == SS_DTYPE_BF16) hipLaunchKernelGGL(gather_last<bf16_t>, dim3(B), dim3(256), 0, st, x, S, xd, g0->lnf_g, ad, statd, cen, d, rms);
+  else hipLaunchKernelGGL(gather_last<float>, dim3(B), dim3(256), 0, st, x, S, xd, g0->lnf_g, ad, statd, cen, d, rms);
   SS_HIP(hipGetLastError());
   const Phase ph = lm_head_phase(group, n_group, B, 1, logits, next_tokens, S);
   return launch_stream_gemm(dt, EPI_LOGITS, ph.g, st);

@@ -19,7 +19,7 @@ namespace ss {
 template <typename T, int EPI>
 __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
   constexpr bool H16 = sizeof(T) == 2;
-  typedef typename PrefillOperand<T>::type OT;  // element type of the activation operands
+  typedef typename Operand<T>::type OT;  // element type of the activation operands
   constexpr int KS = 2;  // k fragments per stage
   __shared__ __align__(16) u32x4 lds_w[KS][8][64];
   __shared__ __align__(16) u32x4 lds_a[KS][8][64];

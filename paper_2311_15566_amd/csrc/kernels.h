@@ -7,17 +7,26 @@ namespace ss {
 
 enum Epilogue { EPI_F32 = 0, EPI_RESID = 1, EPI_ACT = 2, EPI_SWIGLU = 3, EPI_LOGITS = 4 };
 
+// Element type of the activation operands of the GEMMs for a model of element type T: halves for
+// bf16 models (11 significant bits; the bf16 weights, 8 bits, convert exactly and become halves in
+// registers or on their way into LDS), floats for float32 models.
+template <typename T> struct Operand { typedef T type; };
+template <> struct Operand<bf16_t> { typedef f16_t type; };
+
 // Weight-streaming GEMM of the decode step: out[b, n] = sum_k act[b, k] * W[n, k], b < B <= 32.
 // HBM-bound.  One block owns a pair of 16-row weight tiles (SwiGLU: a gate/up pair) over the
 // whole of K; its waves split K between them, each streaming 1 KiB weight fragments and the
 // matching activation fragments (from L2) straight into registers, and add their sums up
 // through LDS, so nothing of the product goes through memory and no block waits for another.
 //
-// Deferred normalisation: where the GEMM input is Norm(x) = (x - mean) * rstd * gamma + beta, the
-// operand holds x * gamma (written by the producer of x before the row statistics exist) and the
-// epilogue applies  rstd * (acc - mean * wg[n]) + cb[n]  with wg[n] = sum_k W[n,k] gamma[k] and
-// cb[n] = sum_k W[n,k] beta[k] + bias[n], both folded when the weights are uploaded.  mean and
-// rstd come from the producer's per-tile partial sums (sum x, sum x^2), added in tile order.
+// Deferred, centred normalisation: where the GEMM input is Norm(x) = (x - mean) * rstd * gamma + beta,
+// the operand holds (x - c) * gamma, written by the producer of x before the row statistics exist,
+// with c the row's mean at the previous norm (the embedding uses the row's own mean; RMSNorm: c = 0),
+// so that rounding the operand to 11 bits loses nothing to cancellation.  The epilogue applies
+// rstd * (acc - (mean - c) * wg[n]) + cb[n]  with wg[n] = sum_k W[n,k] gamma[k] and
+// cb[n] = sum_k W[n,k] beta[k] + bias[n], both folded when the weights are uploaded.  mean - c and
+// rstd come from the producer's per-tile partial sums (sum (x-c), sum (x-c)^2), added in tile order.
+// The first block of shard 0's consumer leaves the new mean in `cen` for the next producer.
 struct StreamGemmArgs {
   const void *w;        // weight fragments [row_tiles][k_blocks]
   int row_tiles;        // 16-row tiles (SwiGLU: gate/up tiles interleaved, 2 per 16 outputs)
@@ -28,9 +37,11 @@ struct StreamGemmArgs {
   int bt_split;         // 1, or 2: the two 16-row batch tiles of B > 16 go to separate blocks
   int B;                // live batch rows
   int N;                // logical output features (for masking)
-  const void *act;      // operand fragments [B tiles][k_blocks][parts]
+  const void *act;      // operand fragments [B tiles][k_blocks]
   // deferred normalisation (stat_groups > 0)
-  const float *stat_in; // [stat_groups][32][4]: two partial (sum, sum of squares) pairs of the rows of x per entry
+  const float *stat_in; // [stat_groups][32][4]: two partial (sum, sum of squares) pairs of the rows of x - c per entry
+  float *cen;           // [32] or NULL (RMSNorm).  Consumer with publish: cen[b] += mean - c by block 0; EPI_RESID: the centre c
+  int publish;
   int stat_groups;
   int norm_dim;         // length of a row of x
   int rms;
@@ -42,10 +53,10 @@ struct StreamGemmArgs {
   int ld_out;
   const float *x_in;    // EPI_RESID: residual stream before this GEMM, [B][N]
   float *x_out;         // EPI_RESID: after it (may equal x_in)
-  void *act_out;        // EPI_ACT / EPI_SWIGLU: activation fragments; EPI_RESID: x_out * g_out (or NULL)
+  void *act_out;        // EPI_ACT / EPI_SWIGLU: activation fragments; EPI_RESID: (x_out - c) * g_out (or NULL)
   int out_k_blocks;
   const float *g_out;   // EPI_RESID: gamma of the norm that follows
-  float *stat_out;      // EPI_RESID: [row_tiles / 2][32][4] partial sums of x_out, one pair per weight tile (with act_out)
+  float *stat_out;      // EPI_RESID: [row_tiles / 2][32][4] partial sums of x_out - c, one pair per weight tile (with act_out)
   int act_kind;
   float *am_val;        // EPI_LOGITS: [blocks][32]
   int *am_idx;
@@ -61,10 +72,6 @@ int stream_gemm_blocks(int epi, const StreamGemmArgs &a);
 // wg / cb of a weight matrix in fragment order (gamma NULL: wg is not written)
 ss_status launch_fold_norm(int dtype, const void *w, int row_tiles, int k_blocks, const float *gamma, const float *beta,
                            const float *bias, float *wg, float *cb, hipStream_t st);
-
-// Operand element type of the initial phase's GEMMs for a model of element type T.
-template <typename T> struct PrefillOperand { typedef T type; };
-template <> struct PrefillOperand<bf16_t> { typedef f16_t type; };
 
 // Prefill GEMM: out[t, n] = sum_k act[t, k] * W[n, k] over T tokens (multiple of 128), MFMA-bound.
 // Norms are deferred as in the decode GEMM, and centred: the residual epilogue of the last shard
@@ -115,7 +122,7 @@ struct DecodeAttnArgs {
   const float2 *rope;   // [Smax][Dh/2] or NULL
   float *part;          // [B*Hs][splits][Dh+4]
   int *counters;        // [B*Hs]
-  void *o_out;          // fragments [nb][Hs*Dh / FragK]
+  void *o_out;          // operand fragments [nb][Hs*Dh / FragK]
   int B, Hs, Dh, Smax;
   int kv_dtype;         // cache element type (SS_DTYPE_*)
   int rows_per_block, splits;
@@ -134,15 +141,16 @@ struct EmbedArgs {
   int S;
   float *x;               // [rows][d]
   int d, V;
-  // operand of the first GEMM (x * gamma) and, in the decode step, its row sums
+  // operand of the first GEMM, centred on the row's mean c (RMSNorm: c = 0): (x - c) * gamma
   const float *gamma;     // gamma of the first norm
-  void *act_out;          // x * gamma as operand fragments [rows / 16][d / FragK][parts]
-  float *stat_out;        // [32][4] (sum x, sum x^2, 0, 0) per row
-  // initial phase (mr_out != NULL): the operand is centred on the row mean c, (x - c) * gamma, one fragment
-  // per k block (halves for bf16 models); mr_out[row].x = c, pstat_out[row] = (sum (x - c), sum (x - c)^2)
+  void *act_out;          // operand fragments [rows / 16][d / FragK]
+  int rms;
+  // decode step: the row's centred sums and its centre
+  float *stat_out;        // [32][4] (sum (x-c), sum (x-c)^2, 0, 0) per row
+  float *cen_out;         // [32]
+  // initial phase: pstat_out[row] = (sum (x-c), sum (x-c)^2), mr_out[row].x = c
   float2 *pstat_out;      // [rows]
   f32x4 *mr_out;          // [rows]
-  int rms;
 };
 
 struct Phase {

@@ -30,34 +30,27 @@ __device__ __forceinline__ void widen16<bf16_t>(const u32x4 &raw, float *out) {
   }
 }
 
-// PL consecutive activations (k a multiple of PL) of row `row` as one 16-byte piece per part
-template <typename T>
-__device__ __forceinline__ void store_piece(void *base, int row, int k, int k_blocks, const float *y,
-                                            const int AP = Elem<T>::kParts) {
-  constexpr int PL = Elem<T>::kPerLane;
-  T hi[PL], lo[PL];
+// PL consecutive activations (k a multiple of PL) of row `row` as the lane's 16-byte piece of an operand fragment
+template <typename OT>
+__device__ __forceinline__ void store_piece(void *base, int row, int k, int k_blocks, const float *y) {
+  constexpr int PL = Elem<OT>::kPerLane;
+  OT h[PL];
 #pragma unroll
-  for (int e = 0; e < PL; ++e) {
-    hi[e] = Elem<T>::from_f32(y[e]);
-    lo[e] = Elem<T>::from_f32(y[e] - Elem<T>::to_f32(hi[e]));
-  }
+  for (int e = 0; e < PL; ++e) h[e] = Elem<OT>::from_f32(y[e]);
   u32x4 w;
-  __builtin_memcpy(&w, hi, 16);
-  *(u32x4 *)((T *)base + frag_offset_parts<T>(row, k, k_blocks, AP, 0)) = w;
-  if (AP > 1) {
-    __builtin_memcpy(&w, lo, 16);
-    *(u32x4 *)((T *)base + frag_offset_parts<T>(row, k, k_blocks, AP, AP - 1)) = w;
-  }
+  __builtin_memcpy(&w, h, 16);
+  *(u32x4 *)((OT *)base + frag_offset<OT>(row, k, k_blocks)) = w;
 }
 
-// x[r] = wte[token] (+ wpe[position]) with 16-byte loads (or the previous stage's hidden row).  d <= 16384.
-// Decode step (a.act_out, a.stat_out): also the first GEMM's operand x * gamma as hi/lo fragments and the
-// row's (sum, sum of squares).
-// Initial phase (a.act_out, a.mr_out, a.pstat_out): the operand is centred, (x - c) * gamma with c the row's
-// mean (0 for RMSNorm), as one fragment of OT elements; mr_out[r].x = c, pstat_out[r] = (sum (x-c), sum (x-c)^2).
-template <typename T, typename OT = T>
+// x[r] = wte[token] (+ wpe[position]) with 16-byte loads (or the previous stage's hidden row), d <= 16384,
+// and the first GEMM's operand, centred on the row's mean c (RMSNorm: c = 0): (x - c) * gamma as
+// fragments of OT elements, with the centred sums (sum (x-c), sum (x-c)^2) and c itself where the
+// caller asks for them (decode step: stat_out, cen_out; initial phase: pstat_out, mr_out).
+template <typename T>
 __device__ __forceinline__ void embed_row_block(const EmbedArgs &a, const int r, float *scratch) {
+  typedef typename Operand<T>::type OT;
   constexpr int PL = Elem<T>::kPerLane, FK = Elem<T>::kFragK, MAXV = 64 / PL;
+  static_assert(Elem<OT>::kPerLane == PL && Elem<OT>::kFragK == FK, "operand and weight fragments have one geometry");
   int tok = a.hidden ? 0 : a.tokens[r];
   tok = min(max(tok, 0), a.V - 1);
   const int pos = a.lens ? a.lens[r] : (r % a.S);
@@ -65,7 +58,7 @@ __device__ __forceinline__ void embed_row_block(const EmbedArgs &a, const int r,
   const u32x4 *te = (const u32x4 *)((const T *)a.wte + (size_t)tok * a.d);
   const u32x4 *pe = (a.wpe && !a.hidden) ? (const u32x4 *)((const T *)a.wpe + (size_t)pos * a.d) : nullptr;
   float vals[MAXV][PL];
-  float s1 = 0.f, s2 = 0.f;
+  float s1 = 0.f;
 #pragma unroll
   for (int i = 0; i < MAXV; ++i) {
     const int v = threadIdx.x + i * 256;
@@ -85,49 +78,36 @@ __device__ __forceinline__ void embed_row_block(const EmbedArgs &a, const int r,
       float *xo = a.x + (size_t)r * a.d + (size_t)v * PL;
 #pragma unroll
       for (int e = 0; e < PL; ++e) {
-        s1 += vals[i][e], s2 += vals[i][e] * vals[i][e];
+        s1 += vals[i][e];
         xo[e] = vals[i][e];
       }
     }
   }
-  if (a.mr_out) {  // initial phase: centre first, then the operand and the centred sums
-    const float c = a.rms ? 0.f : block_sum(s1, scratch) / (float)a.d;
-    s1 = 0.f, s2 = 0.f;
+  if (!a.act_out) return;
+  const float c = a.rms ? 0.f : block_sum(s1, scratch) / (float)a.d;
+  float s2 = 0.f;
+  s1 = 0.f;
 #pragma unroll
-    for (int i = 0; i < MAXV; ++i) {
-      const int v = threadIdx.x + i * 256;
-      if (v < nvec) {
-        float y[PL];
+  for (int i = 0; i < MAXV; ++i) {
+    const int v = threadIdx.x + i * 256;
+    if (v < nvec) {
+      float y[PL];
 #pragma unroll
-        for (int e = 0; e < PL; ++e) {
-          const float t = vals[i][e] - c;
-          s1 += t, s2 += t * t;
-          y[e] = t * a.gamma[v * PL + e];
-        }
-        store_piece<OT>(a.act_out, r, v * PL, a.d / FK, y);
+      for (int e = 0; e < PL; ++e) {
+        const float t = vals[i][e] - c;
+        s1 += t, s2 += t * t;
+        y[e] = t * a.gamma[v * PL + e];
       }
-    }
-    s1 = block_sum(s1, scratch);
-    s2 = block_sum(s2, scratch);
-    if (threadIdx.x == 0) a.mr_out[r] = f32x4{c, 0.f, 0.f, 0.f}, a.pstat_out[r] = make_float2(s1, s2);
-    return;
-  }
-  if (a.act_out) {  // decode step: the PL elements are one lane's 16-byte piece of the operand fragments
-#pragma unroll
-    for (int i = 0; i < MAXV; ++i) {
-      const int v = threadIdx.x + i * 256;
-      if (v < nvec) {
-        float y[PL];
-#pragma unroll
-        for (int e = 0; e < PL; ++e) y[e] = vals[i][e] * a.gamma[v * PL + e];
-        store_piece<T>(a.act_out, r, v * PL, a.d / FK, y);
-      }
+      store_piece<OT>(a.act_out, r, v * PL, a.d / FK, y);
     }
   }
-  if (a.stat_out) {
-    s1 = block_sum(s1, scratch);
-    s2 = block_sum(s2, scratch);
-    if (threadIdx.x == 0) ((f32x4 *)a.stat_out)[r] = f32x4{s1, s2, 0.f, 0.f};
+  s1 = block_sum(s1, scratch);
+  s2 = block_sum(s2, scratch);
+  if (threadIdx.x == 0) {
+    if (a.stat_out) ((f32x4 *)a.stat_out)[r] = f32x4{s1, s2, 0.f, 0.f};
+    if (a.cen_out) a.cen_out[r] = c;
+    if (a.pstat_out) a.pstat_out[r] = make_float2(s1, s2);
+    if (a.mr_out) a.mr_out[r] = f32x4{c, 0.f, 0.f, 0.f};
   }
 }
 

@@ -37,9 +37,9 @@ struct Layout {
   size_t ws_pstat;     // initial phase: partial row sums [2 * ceil(d / 128)][Tmax] float2, then (mean, rstd, mean - centre, -) [Tmax] float4
   int n_counters;
   // decode step (rows = batch): residual stream [32][d] f32, operand of the next normalised GEMM
-  // (x * gamma), partial row sums [d/16][32][2], q|k|v [32][qkv_n] f32, attention output and FFN
-  // activation operands
-  size_t ws_xd, ws_ad, ws_statd, ws_qkvd, ws_od, ws_ud;
+  // ((x - c) * gamma), partial row sums [d/16][32][2], the rows' centres [32], q|k|v [32][qkv_n] f32,
+  // attention output and FFN activation operands
+  size_t ws_xd, ws_ad, ws_statd, ws_cen, ws_qkvd, ws_od, ws_ud;
   size_t total;
 };
 

@@ -31,7 +31,8 @@ struct GemmShared {
 // KSM: waves per block at most
 template <typename T, int NB, bool GLU, int EPI, int KSM, int NW>
 __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamGemmArgs a) {
-  constexpr int AP = Elem<T>::kParts;
+  typedef typename Operand<T>::type OT;  // element type of the activation operands
+  constexpr bool H16 = sizeof(T) == 2;     // bf16 weights become halves in registers
   constexpr int RB = NB * 16;
   constexpr int NEP = GLU ? NB : NW * NB;  // waves that run the epilogue
   constexpr int NWE = GLU ? 2 : 1;         // weight tiles one epilogue wave combines
@@ -67,7 +68,7 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
 #pragma unroll
   for (int t = 0; t < NB; ++t) {
     row_ok[t] = row0 + t * 16 + r < a.B;
-    ap[t] = (const u32x4 *)a.act + (size_t)(bt + t) * a.k_blocks * AP * 64 + lane;
+    ap[t] = (const u32x4 *)a.act + (size_t)(bt + t) * a.k_blocks * 64 + lane;
   }
 
   // what the epilogue needs from memory is requested first, so that it has long arrived
@@ -80,6 +81,8 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
   const bool tile_e_ok = tile0 + je < a.row_tiles;
   const bool epi_live = is_epi && tile_e_ok && b < a.B && n0 < a.N;
   f32x4 e_wg[NWE], e_cb[NWE], e_x = {0.f, 0.f, 0.f, 0.f}, e_g = {1.f, 1.f, 1.f, 1.f};
+  float e_cen = 0.f;  // EPI_RESID: the centre of the operand it writes; a publishing consumer: the centre of the one it reads
+  if (is_epi && a.cen && b < a.B && (EPI == EPI_RESID || (a.publish && blk == 0))) e_cen = a.cen[b];
 #pragma unroll
   for (int jj = 0; jj < NWE; ++jj) {
     e_wg[jj] = e_cb[jj] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -99,7 +102,7 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
 #pragma unroll
     for (int j = 0; j < NW; ++j) acc[t][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  auto load = [&](u32x4(&w)[NW][U], u32x4(&av)[NB][AP][U], int kb) {
+  auto load = [&](u32x4(&w)[NW][U], u32x4(&av)[NB][U], int kb) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const bool ok = kb + u < k1;
@@ -107,24 +110,21 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
       for (int j = 0; j < NW; ++j)
         w[j][u] = (ok && tile_ok[j]) ? __builtin_nontemporal_load(wp[j] + (size_t)(kb + u) * 64) : u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
-      for (int t = 0; t < NB; ++t)
-#pragma unroll
-        for (int part = 0; part < AP; ++part)
-          av[t][part][u] = (ok && row_ok[t]) ? ap[t][((size_t)(kb + u) * AP + part) * 64] : u32x4{0u, 0u, 0u, 0u};
+      for (int t = 0; t < NB; ++t) av[t][u] = (ok && row_ok[t]) ? ap[t][(size_t)(kb + u) * 64] : u32x4{0u, 0u, 0u, 0u};
     }
   };
-  auto use = [&](u32x4(&w)[NW][U], u32x4(&av)[NB][AP][U]) {
+  auto use = [&](u32x4(&w)[NW][U], u32x4(&av)[NB][U]) {
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
-      for (int t = 0; t < NB; ++t)
+      for (int j = 0; j < NW; ++j) {
+        const u32x4 wf = H16 ? bf16x8_to_f16x8(w[j][u]) : w[j][u];
 #pragma unroll
-        for (int part = 0; part < AP; ++part)
-#pragma unroll
-          for (int j = 0; j < NW; ++j) acc[t][j] = Mma<T>::mma(w[j][u], av[t][part][u], acc[t][j]);
+        for (int t = 0; t < NB; ++t) acc[t][j] = H16 ? mma_f16(wf, av[t][u], acc[t][j]) : Mma<T>::mma(wf, av[t][u], acc[t][j]);
+      }
   };
 
-  u32x4 wA[NW][U], aA[NB][AP][U], wB[NW][U], aB[NB][AP][U];
+  u32x4 wA[NW][U], aA[NB][U], wB[NW][U], aB[NB][U];
   load(wA, aA, k0);
   load(wB, aB, k0 + U);
 
@@ -189,7 +189,7 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
       sum[jj] = sh.red[0][j][te][lane];
       for (int s = 1; s < KS; ++s) sum[jj] += sh.red[s][j][te][lane];
     }
-    float mean = 0.f, rstd = 1.f;
+    float mean = 0.f, rstd = 1.f;  // mean: of the centred rows, i.e. mean(x) - c
     if (NORMED && a.stat_groups > 0) {
       float u1 = 0.f, u2 = 0.f;
       const int br = r < rbl ? r : 0;  // rows past the batch are masked later
@@ -204,6 +204,8 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
       } else {
         mean = u1 * inv;
         rstd = rsqrtf(fmaxf(ms - mean * mean, 0.f) + a.eps);
+        // the next producer centres on this norm's mean (one lane per row, first block, first tile)
+        if (a.publish && a.cen && blk == 0 && je == 0 && lane < 16 && b < a.B) a.cen[b] = e_cen + mean;
       }
     }
     float h[NWE][4];  // the product with normalisation and bias applied
@@ -223,7 +225,7 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
         float u[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) u[i] = GLU ? silu_f(h[0][i]) * h[NWE - 1][i] : act_apply(a.act_kind, h[0][i]);
-        store4_frag<T, false>(a.act_out, b, n0, a.out_k_blocks, AP, u);
+        store4_frag<OT, false>(a.act_out, b, n0, a.out_k_blocks, 1, u);
       }
     } else if (EPI == EPI_RESID) {
       float s1 = 0.f, s2 = 0.f;
@@ -232,11 +234,12 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           v[i] = e_x[i] + h[0][i];
-          s1 += v[i], s2 += v[i] * v[i];
-          g[i] = v[i] * e_g[i];
+          const float t = v[i] - e_cen;
+          s1 += t, s2 += t * t;
+          g[i] = t * e_g[i];
         }
         *(f32x4 *)(a.x_out + (size_t)b * a.N + n0) = f32x4{v[0], v[1], v[2], v[3]};
-        if (a.act_out) store4_frag<T, false>(a.act_out, b, n0, a.out_k_blocks, AP, g);
+        if (a.act_out) store4_frag<OT, false>(a.act_out, b, n0, a.out_k_blocks, 1, g);
       }
       if (a.act_out) {  // partial row sums of this weight tile's 16 features
         s1 += __shfl_xor(s1, 16), s2 += __shfl_xor(s2, 16);

@@ -13,12 +13,12 @@ vp, i32, f32, sz = C.c_void_p, C.c_int32, C.c_float, C.c_size_t
 
 class EmbedArgs(C.Structure):
     _fields_ = [("hidden", vp), ("tokens", vp), ("wte", vp), ("wpe", vp), ("lens", vp), ("S", i32), ("x", vp), ("d", i32), ("V", i32),
-                ("gamma", vp), ("act_out", vp), ("stat_out", vp), ("pstat_out", vp), ("mr_out", vp), ("rms", i32)]
+                ("gamma", vp), ("act_out", vp), ("rms", i32), ("stat_out", vp), ("cen_out", vp), ("pstat_out", vp), ("mr_out", vp)]
 
 
 class GemmArgs(C.Structure):
     _fields_ = [("w", vp), ("row_tiles", i32), ("k_blocks", i32), ("ks", i32), ("nw", i32), ("n_blocks", i32), ("bt_split", i32), ("B", i32), ("N", i32), ("act", vp),
-                ("stat_in", vp), ("stat_groups", i32), ("norm_dim", i32), ("rms", i32), ("eps", f32), ("wg", vp), ("cb", vp),
+                ("stat_in", vp), ("cen", vp), ("publish", i32), ("stat_groups", i32), ("norm_dim", i32), ("rms", i32), ("eps", f32), ("wg", vp), ("cb", vp),
                 ("out_f32", vp), ("ld_out", i32), ("x_in", vp), ("x_out", vp), ("act_out", vp), ("out_k_blocks", i32),
                 ("g_out", vp), ("stat_out", vp), ("act_kind", i32), ("am_val", vp), ("am_idx", vp), ("counter", vp),
                 ("next_tokens", vp), ("lens", vp * 8), ("n_lens", i32), ("commit_inc", i32)]
@@ -55,7 +55,7 @@ def plan(w):
 def check(w):
     ph, base, total = plan(w)
     bf16 = w.desc["dtype"] == "bf16"
-    esz, parts, fk = (2, 2, 32) if bf16 else (4, 1, 16)
+    esz, parts, fk = (2, 1, 32) if bf16 else (4, 1, 16)      # operands: one fragment of halves / floats per k block
     kvsz = 4 if not bf16 else 2
     glu = w.desc["act"] == "swiglu"
     d = w.desc["d_model"]
@@ -81,6 +81,8 @@ def check(w):
             rng("act_out", e.act_out, nbt * (d // fk) * parts * 1024, regions)
             rng("stat_out", e.stat_out, 32 * 16, regions)
             rng("gamma", e.gamma, d * 4, regions)
+            assert bool(e.cen_out) == (w.desc["norm"] == "layernorm") and not e.pstat_out and not e.mr_out
+            rng("cen_out", e.cen_out, 32 * 4, regions)
             stat_groups = 1
         elif p.kind == ATTN:
             a = p.at
@@ -106,6 +108,10 @@ def check(w):
                 assert g.stat_groups == stat_groups and g.norm_dim == d and g.k_blocks * fk == d
                 rng("stat_in", g.stat_in, g.stat_groups * 32 * 16, regions)
                 assert bool(g.wg) == (w.desc["norm"] == "layernorm")
+                # the consumer of shard 0 leaves the new mean for the next producer (not the LM head: nothing follows)
+                assert g.publish == (0 if p.kind == LM_HEAD else 1) or not g.cen
+                assert bool(g.cen) == (w.desc["norm"] == "layernorm" and p.kind != LM_HEAD)
+                rng("cen", g.cen, 32 * 4, regions)
             else:
                 assert g.stat_groups == 0 and not g.wg
             if p.kind == QKV:
@@ -122,6 +128,8 @@ def check(w):
                 rng("act_out", g.act_out, nbt * g.out_k_blocks * parts * 1024, regions)
                 rng("g_out", g.g_out, g.N * 4, regions)
                 rng("stat_out", g.stat_out, (g.row_tiles // 2) * 32 * 16, regions)
+                assert bool(g.cen) == (w.desc["norm"] == "layernorm") and not g.publish
+                rng("cen", g.cen, 32 * 4, regions)
                 assert g.out_k_blocks * fk >= g.N
                 stat_groups = g.row_tiles // 2
             if p.kind == LM_HEAD:
