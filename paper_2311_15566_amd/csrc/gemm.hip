@@ -14,8 +14,7 @@ namespace ss {
 // tiled prefill GEMM: block = 128 output features x 128 tokens, 4 waves of 64 x 64,
 // K advanced two fragments at a time through LDS with register prefetch of the next stage.
 // ---------------------------------------------------------------------------
-// bf16 models: the activation operands are halves (11 significant bits, one fragment per k block)
-// and the bf16 weights become halves on their way into LDS; float32 models: float operands.
+// bf16 models: the activation operands and the stored weight fragments are halves; float32 models: floats.
 template <typename T, int EPI>
 __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
   constexpr bool H16 = sizeof(T) == 2;
@@ -74,7 +73,7 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
     for (int r = 0; r < 4; ++r) {
       const int p = tid + 256 * r;
       const int ks = p >> 9, tile = (p >> 6) & 7, ln = p & 63;
-      lds_w[ks][tile][ln] = H16 ? bf16x8_to_f16x8(pw[r]) : pw[r];
+      lds_w[ks][tile][ln] = pw[r];
       lds_a[ks][tile][ln] = pa[r];
     }
     __syncthreads();

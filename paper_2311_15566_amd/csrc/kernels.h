@@ -7,9 +7,11 @@ namespace ss {
 
 enum Epilogue { EPI_F32 = 0, EPI_RESID = 1, EPI_ACT = 2, EPI_SWIGLU = 3, EPI_LOGITS = 4 };
 
-// Element type of the activation operands of the GEMMs for a model of element type T: halves for
-// bf16 models (11 significant bits; the bf16 weights, 8 bits, convert exactly and become halves in
-// registers or on their way into LDS), floats for float32 models.
+// Element type of both operands of the GEMMs for a model of element type T.  bf16 models: halves.
+// Activations need more than bf16's 8 significant bits to stay under the logits bar, a half has 11;
+// the matrix cores take both operands in one type, so the weight fragments are stored as halves too
+// (converted at upload: exact for magnitudes from 2^-17 up, an 8-bit significand fits into 11 bits;
+// smaller ones round into the half format's last subnormal bits).  float32 models: floats.
 template <typename T> struct Operand { typedef T type; };
 template <> struct Operand<bf16_t> { typedef f16_t type; };
 
@@ -85,8 +87,7 @@ struct TileGemmArgs {
   const void *w;      // weight fragments
   int row_tiles;      // 16-row weight tiles (SwiGLU: 2 per 16 outputs, interleaved)
   int k_blocks;
-  const void *act;    // activation fragments [T/16][k_blocks] of the operand type: halves for bf16 models
-                      // (the bf16 weights become halves on their way into LDS), float for float32 models
+  const void *act;    // activation fragments [T/16][k_blocks] of the operand type
   int T;              // tokens (padded to 128)
   int T_live;         // tokens that exist
   int N;

@@ -22,25 +22,11 @@ template <> struct Mma<float> {
   }
 };
 
-// the same product on half-precision operands (weights converted from bf16 on their way into LDS)
+// the same product on half-precision operands (bf16 models: weight fragments are stored as halves)
 typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
 __device__ __forceinline__ f32x4 mma_f16(u32x4 w, u32x4 a, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, w), __builtin_bit_cast(f16x8_t, a), c, 0, 0, 0);
 }
-// Eight bf16 -> eight halves, element order kept.  Exact for magnitudes in [2^-14, 65504] (8 significant
-// bits fit into 11); smaller ones lose low bits to the half format's subnormals (toward zero).
-__device__ __forceinline__ u32x4 bf16x8_to_f16x8(u32x4 w) {
-  typedef __fp16 f16x2_t __attribute__((ext_vector_type(2)));
-  u32x4 out;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const float lo = __uint_as_float(w[i] << 16), hi = __uint_as_float(w[i] & 0xffff0000u);
-    const f16x2_t h = __builtin_amdgcn_cvt_pkrtz(lo, hi);
-    out[i] = __builtin_bit_cast(uint32_t, h);
-  }
-  return out;
-}
-
 __device__ __forceinline__ float act_apply(int kind, float h) {
   if (kind == SS_ACT_GELU_TANH) return 0.5f * h * (1.0f + tanhf(0.7978845608028654f * (h + 0.044715f * h * h * h)));
   return fmaxf(h, 0.0f);  // SS_ACT_RELU

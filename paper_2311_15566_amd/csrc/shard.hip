@@ -158,7 +158,7 @@ bool compute_layout(const ss_model_desc &m, const ss_slice &s, int max_batch, in
 // ---------------------------------------------------------------------------
 // src: raw slice; element (n, k) at src[n*sn + k*sk].  dst: fragments; logical row tile t of
 // the slice lands at tile t*tile_mul + tile_add (SwiGLU gate/up interleave).  Rows >= N and
-// k >= K are zero-filled.
+// k >= K are zero-filled.  The fragments hold the GEMM operand type (bf16 weights become halves).
 template <typename T>
 __global__ void __launch_bounds__(256) shuffle_to_frags(const T *__restrict__ src, T *__restrict__ dst, int N, int K,
                                                         size_t sn, size_t sk, int k_blocks, int tile_mul,
@@ -178,9 +178,11 @@ __global__ void __launch_bounds__(256) shuffle_to_frags(const T *__restrict__ sr
       int k = k0 + j;
       v[j] = (n < N && k < K) ? src[(size_t)n * sn + (size_t)k * sk] : (T)0;
     }
-    T *o = dst + ((size_t)(t * tile_mul + tile_add) * k_blocks + kb) * (64 * PL) + lane * PL;
+    typedef typename Operand<T>::type WT;
+    static_assert(sizeof(WT) == sizeof(T), "operand and weight elements have one size");
+    WT *o = (WT *)dst + ((size_t)(t * tile_mul + tile_add) * k_blocks + kb) * (64 * PL) + lane * PL;
 #pragma unroll
-    for (int j = 0; j < PL; ++j) o[j] = v[j];
+    for (int j = 0; j < PL; ++j) o[j] = Elem<WT>::from_f32(Elem<T>::to_f32(v[j]));
   }
 }
 

@@ -32,7 +32,7 @@ struct GemmShared {
 template <typename T, int NB, bool GLU, int EPI, int KSM, int NW>
 __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamGemmArgs a) {
   typedef typename Operand<T>::type OT;  // element type of the activation operands
-  constexpr bool H16 = sizeof(T) == 2;     // bf16 weights become halves in registers
+  constexpr bool H16 = sizeof(T) == 2;     // bf16 models: weight fragments are stored as halves
   constexpr int RB = NB * 16;
   constexpr int NEP = GLU ? NB : NW * NB;  // waves that run the epilogue
   constexpr int NWE = GLU ? 2 : 1;         // weight tiles one epilogue wave combines
@@ -118,9 +118,8 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
     for (int u = 0; u < U; ++u)
 #pragma unroll
       for (int j = 0; j < NW; ++j) {
-        const u32x4 wf = H16 ? bf16x8_to_f16x8(w[j][u]) : w[j][u];
 #pragma unroll
-        for (int t = 0; t < NB; ++t) acc[t][j] = H16 ? mma_f16(wf, av[t][u], acc[t][j]) : Mma<T>::mma(wf, av[t][u], acc[t][j]);
+        for (int t = 0; t < NB; ++t) acc[t][j] = H16 ? mma_f16(w[j][u], av[t][u], acc[t][j]) : Mma<T>::mma(w[j][u], av[t][u], acc[t][j]);
       }
   };
 
@@ -396,6 +395,7 @@ __global__ void __launch_bounds__(256) fold_norm(const u32x4 *__restrict__ w, in
                                                  const float *__restrict__ gamma, const float *__restrict__ beta,
                                                  const float *__restrict__ bias, float *__restrict__ wg,
                                                  float *__restrict__ cb) {
+  typedef typename Operand<T>::type WT;  // the fragments hold the weights in the operand type
   constexpr int PL = Elem<T>::kPerLane, FK = Elem<T>::kFragK;
   const int lane = threadIdx.x & 63, tile = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (tile >= row_tiles) return;
@@ -403,12 +403,12 @@ __global__ void __launch_bounds__(256) fold_norm(const u32x4 *__restrict__ w, in
   double sg = 0.0, sb = 0.0;
   for (int kb = 0; kb < k_blocks; ++kb) {
     const u32x4 raw = w[((size_t)tile * k_blocks + kb) * 64 + lane];
-    T e[PL];
+    WT e[PL];
     __builtin_memcpy(e, &raw, 16);
 #pragma unroll
     for (int i = 0; i < PL; ++i) {
       const int k = kb * FK + kq * PL + i;
-      const double wv = (double)Elem<T>::to_f32(e[i]);
+      const double wv = (double)Elem<WT>::to_f32(e[i]);
       if (gamma) sg += wv * (double)gamma[k];
       if (beta) sb += wv * (double)beta[k];
     }
