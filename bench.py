@@ -192,7 +192,7 @@ def main():
         step_bytes, class_bytes, attn_bytes, weight_bytes = algorithmic_bytes(w, n_list)
         out = dict(metric="decode tokens/s per TP shard on 1 GPU", value=w.batch * K / dt, unit="tokens/s", n_gpus=1,
                    steps=K, warmup=Wm, ms_per_step=dt / K * 1e3, higher_is_better=True, scaling="weak",
-                   vs_baseline=None, dtype=w.desc["dtype"], data="synthetic",
+                   vs_baseline=None, dtype={"bf16": "f16", "f32": "f32"}[w.desc["dtype"]], data="synthetic",
                    config=dict(workload=f"{w.name}: {shard_dims(w)['Ls']} layers, d={w.desc['d_model']}, "
                                         f"{shard_dims(w)['Hs']} heads x {w.desc['head_dim']}, FFN {shard_dims(w)['Fs']}, "
                                         f"vocab {V}, batch {w.batch}, prompt {w.s_in}, {K} decode steps",
@@ -233,7 +233,7 @@ def main():
                                    bytes_per_launch=class_bytes[dom] * K / cnt, avg_launch_us=ms / cnt * 1e3,
                                    launches=int(cnt))
             fl = prefill_flops(w)
-            peak = MFMA_PEAK_TFLOPS[w.desc["dtype"]]
+            peak = MFMA_PEAK_TFLOPS[w.desc["dtype"]]       # halves and bf16 share one matrix-core peak
             out["prefill"] = dict(ms=prefill_ms, tokens=w.batch * w.s_in, TFLOPs=fl / (prefill_ms * 1e-3) / 1e12,
                                   peak=peak, frac=fl / (prefill_ms * 1e-3) / 1e12 / peak)
 

@@ -47,7 +47,10 @@ typedef struct {
   int32_t n_layers, d_model, n_heads, head_dim, ffn, vocab;
   int32_t max_pos;  /* rows of the learned position table (0 for RoPE) */
   int32_t norm, act, pos, has_bias;
-  int32_t dtype;    /* weights (and the matrix-core operand type): SS_DTYPE_F32 or SS_DTYPE_BF16 */
+  int32_t dtype;    /* element type of the weights handed over: SS_DTYPE_F32 or SS_DTYPE_BF16.  A bf16 model is
+                       computed with IEEE-half matrix-core operands and float32 accumulation: activations are
+                       rounded to halves (11 significant bits; bf16's 8 miss the logits bar), and the weight
+                       matrices are held as halves (exact for magnitudes from 2^-17 up, saturating at +-65504). */
   int32_t kv_dtype; /* cache element: SS_DTYPE_F32 for an f32 model; SS_DTYPE_F16 or SS_DTYPE_BF16
                        (both 2 bytes) for a bf16 model.  Half keeps 3 more mantissa bits: bf16 keys
                        alone cost ~4e-3 relative logits error at the OPT-66B shape, half ~6e-4;
