@@ -289,13 +289,18 @@ def main():
                     r.destroy()
                 dt_r = time.perf_counter() - t0
                 t0 = time.perf_counter()
-                ss.Shard(w.desc, half, W, w.batch, w.s_max).destroy()
+                from_host = ss.Shard(w.desc, sub_slice_of(w.slice, 1, 2), W, w.batch, w.s_max)
+                torch.cuda.synchronize()
                 dt_host = time.perf_counter() - t0
+                # `mem` still holds the second half-width shard's model context: byte for byte what the upload made
+                n_ctx_bytes = from_host.model_context().numel()
+                assert torch.equal(mem[:n_ctx_bytes], from_host.model_context()), "re-sliced model context differs from the uploaded one"
+                from_host.destroy()
                 out["reslice"] = dict(bytes_copied=moved // 2, ms=dt_r / 2 * 1e3, traffic_GBps=2 * moved / dt_r / 1e9,
                                       frac=2 * moved / dt_r / 1e9 / HBM_PEAK_GBPS, from_host_ms=dt_host * 1e3,
                                       note="one half-width shard's model context copied out of the resident shard "
                                            "(wall time of the call, which synchronizes); from_host_ms: the same shard "
-                                           "uploaded from host tensors")
+                                           "uploaded from host tensors (the two compared byte for byte)")
                 del mem
         else:
             out["roofline"] = dict(bound="hbm", kernel="whole decode step", achieved=whole, peak=HBM_PEAK_GBPS,
