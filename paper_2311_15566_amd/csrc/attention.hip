@@ -151,7 +151,7 @@ __global__ void __launch_bounds__(256) prefill_attn(PrefillAttnArgs a) {
     const int tok = b * a.S + qi;
 #pragma unroll
     for (int e = 0; e < DP; ++e)
-      store_act<AT>(a.o_out, tok, h * DH + part * DP + e, HD / Elem<AT>::kFragK, 1, acc[e] * inv);
+      store_act<AT>(a.o_out, tok, h * DH + part * DP + e, HD / Elem<AT>::kFragK, acc[e] * inv);
   }
 }
 
@@ -311,7 +311,7 @@ __global__ void __launch_bounds__(256) prefill_attn_mfma(PrefillAttnArgs a) {
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
       const float v[4] = {acc[dt][0] * inv, acc[dt][1] * inv, acc[dt][2] * inv, acc[dt][3] * inv};
-      store4_frag<AT, false>(a.o_out, tok, h * DH + dt * 16 + g * 4, HD / Elem<AT>::kFragK, 1, v);
+      store4_frag<AT, false>(a.o_out, tok, h * DH + dt * 16 + g * 4, HD / Elem<AT>::kFragK, v);
     }
   }
 }

@@ -78,7 +78,6 @@ template <typename T> struct Elem;
 template <> struct Elem<f16_t> {
   static constexpr int kPerLane = 8;
   static constexpr int kFragK = 32;
-  static constexpr int kParts = 1;     // the activation operand type of bf16 models: 11 significant bits
   __host__ __device__ static float to_f32(f16_t v) { return (float)v; }
   // round-to-nearest-even, saturating at the largest finite half
   __host__ __device__ static f16_t from_f32(float v) {
@@ -89,7 +88,6 @@ template <> struct Elem<f16_t> {
 template <> struct Elem<float> {
   static constexpr int kPerLane = 4;   // elements in a lane's 16-byte piece
   static constexpr int kFragK = 16;    // k extent of one 1 KiB operand fragment
-  static constexpr int kParts = 1;     // fragments per activation k block
   __host__ __device__ static float to_f32(float v) { return v; }
   __host__ __device__ static float from_f32(float v) { return v; }
 };
@@ -98,7 +96,6 @@ template <> struct Elem<bf16_t> {
   static constexpr int kFragK = 32;
   // (activations of bf16 models are never stored as bf16: 8 significant bits miss the logits bar on
   // the larger shapes; the GEMM operands are halves, see Operand)
-  static constexpr int kParts = 1;
   __host__ __device__ static float to_f32(bf16_t v) { return bf16_to_f32(v); }
   __host__ __device__ static bf16_t from_f32(float v) { return f32_to_bf16(v); }
 };
@@ -162,22 +159,10 @@ __device__ __forceinline__ bool arrive_last(int *counter, int expected, int *s_f
 }
 #endif
 
-// Activation operand with `parts` fragments per k block: [row tile][k block][part][lane][PerLane].
+// store a float activation into an operand buffer
 template <typename T>
-__host__ __device__ inline size_t frag_offset_parts(int row, int k, int k_blocks, int parts, int part) {
-  constexpr int PL = Elem<T>::kPerLane, FK = Elem<T>::kFragK;
-  size_t frag = ((size_t)(row >> 4) * k_blocks + (k / FK)) * parts + part;
-  int kk = k % FK;
-  int lane = (kk / PL) * 16 + (row & 15);
-  return frag * (64 * PL) + lane * PL + (kk % PL);
-}
-// store a float activation into a (possibly hi/lo split) operand buffer
-template <typename T>
-__device__ inline void store_act(void *base, int row, int k, int k_blocks, int parts, float v) {
-  T *b = (T *)base;
-  const T hi = Elem<T>::from_f32(v);
-  b[frag_offset_parts<T>(row, k, k_blocks, parts, 0)] = hi;
-  if (parts > 1) b[frag_offset_parts<T>(row, k, k_blocks, parts, 1)] = Elem<T>::from_f32(v - Elem<T>::to_f32(hi));
+__device__ inline void store_act(void *base, int row, int k, int k_blocks, float v) {
+  ((T *)base)[frag_offset<T>(row, k, k_blocks)] = Elem<T>::from_f32(v);
 }
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }

@@ -120,7 +120,7 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
           finish(acc[i + 1][j], (rt + 1) * 16 + q4, mr, up);
 #pragma unroll
           for (int e = 0; e < 4; ++e) u[e] = silu_f(gt[e]) * up[e];
-          store4_frag<OT, false>(a.act_out, tok, n0, a.out_k_blocks, 1, u);
+          store4_frag<OT, false>(a.act_out, tok, n0, a.out_k_blocks, u);
         }
       }
     } else if (EPI == EPI_RESID) {
@@ -146,7 +146,7 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
               s1 += t, s2 += t * t;
               y[e] = t * g[e];
             }
-            store4_frag<OT, false>(a.norm_out, tok, n0, a.N / Elem<OT>::kFragK, 1, y);
+            store4_frag<OT, false>(a.norm_out, tok, n0, a.N / Elem<OT>::kFragK, y);
           }
         }
       }
@@ -169,7 +169,7 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
           } else {  // EPI_ACT
             const float w[4] = {act_apply(a.act_kind, v[0]), act_apply(a.act_kind, v[1]), act_apply(a.act_kind, v[2]),
                                 act_apply(a.act_kind, v[3])};
-            store4_frag<OT, false>(a.act_out, tok, n0, a.out_k_blocks, 1, w);
+            store4_frag<OT, false>(a.act_out, tok, n0, a.out_k_blocks, w);
           }
         }
       }

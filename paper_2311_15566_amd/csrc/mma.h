@@ -33,28 +33,20 @@ __device__ __forceinline__ float act_apply(int kind, float h) {
 }
 __device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)); }
 
-// Four consecutive activations (k a multiple of 4) into an operand buffer with `parts`
-// fragments per k block, as whole 32-bit words.  DEV: device-scope (write-through) stores, for
-// buffers another block of the same launch reads.
+// Four consecutive activations (k a multiple of 4) into an operand buffer, as whole 32-bit words.
+// DEV: device-scope (write-through) stores, for buffers another block of the same launch reads.
 template <typename T, bool DEV>
-__device__ __forceinline__ void store4_frag(void *base, int row, int k, int k_blocks, int parts, const float (&v)[4]) {
-  T hi[4];
+__device__ __forceinline__ void store4_frag(void *base, int row, int k, int k_blocks, const float (&v)[4]) {
+  T w[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) hi[i] = Elem<T>::from_f32(v[i]);
+  for (int i = 0; i < 4; ++i) w[i] = Elem<T>::from_f32(v[i]);
+  uint32_t words[sizeof(T)];  // 4 elements = sizeof(T) words
+  __builtin_memcpy(words, w, 4 * sizeof(T));
+  uint32_t *p = (uint32_t *)((T *)base + frag_offset<T>(row, k, k_blocks));
 #pragma unroll
-  for (int part = 0; part < 2; ++part) {
-    if (part >= parts) break;
-    T w[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) w[i] = part == 0 ? hi[i] : Elem<T>::from_f32(v[i] - Elem<T>::to_f32(hi[i]));
-    uint32_t words[sizeof(T)];  // 4 elements = sizeof(T) words
-    __builtin_memcpy(words, w, 4 * sizeof(T));
-    uint32_t *p = (uint32_t *)((T *)base + frag_offset_parts<T>(row, k, k_blocks, parts, part));
-#pragma unroll
-    for (int i = 0; i < (int)sizeof(T); ++i) {
-      if (DEV) st_dev(p + i, words[i]);
-      else p[i] = words[i];
-    }
+  for (int i = 0; i < (int)sizeof(T); ++i) {
+    if (DEV) st_dev(p + i, words[i]);
+    else p[i] = words[i];
   }
 }
 

@@ -132,14 +132,14 @@ bool compute_layout(const ss_model_desc &m, const ss_slice &s, int max_batch, in
   L->ws_vt = wtake((size_t)max_batch * L->Hs * L->Dh * align_up((size_t)max_seq, 64) * 2);
   L->ws_pstat = wtake((size_t)(2 * ceil_div(d, 128) + 2) * T * 8);  // partial sums, then (mean, rstd, mean - centre, -) per token
   {
-    const int fk = esz == 2 ? 32 : 16, parts = 1;
+    const int fk = esz == 2 ? 32 : 16;  // one 1 KiB operand fragment per 16 rows and k block
     L->ws_xd = wtake((size_t)32 * d * 4);
-    L->ws_ad = wtake((size_t)2 * (d / fk) * parts * 1024);
+    L->ws_ad = wtake((size_t)2 * (d / fk) * 1024);
     L->ws_statd = wtake((size_t)(d / 32) * 32 * 4 * 4);
     L->ws_cen = wtake((size_t)32 * 4);
     L->ws_qkvd = wtake((size_t)32 * L->qkv_n * 4);
-    L->ws_od = wtake((size_t)2 * (HD / fk) * parts * 1024);
-    L->ws_ud = wtake((size_t)2 * (L->Fs / fk) * parts * 1024);
+    L->ws_od = wtake((size_t)2 * (HD / fk) * 1024);
+    L->ws_ud = wtake((size_t)2 * (L->Fs / fk) * 1024);
   }
   L->n_counters = 16 + max_batch * L->Hs;  // [0]: the LM head's arrival counter; [16..): attention, per (row, head)
   L->ws_counters = wtake((size_t)L->n_counters * 4);

@@ -224,7 +224,7 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
         float u[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) u[i] = GLU ? silu_f(h[0][i]) * h[NWE - 1][i] : act_apply(a.act_kind, h[0][i]);
-        store4_frag<OT, false>(a.act_out, b, n0, a.out_k_blocks, 1, u);
+        store4_frag<OT, false>(a.act_out, b, n0, a.out_k_blocks, u);
       }
     } else if (EPI == EPI_RESID) {
       float s1 = 0.f, s2 = 0.f;
@@ -238,7 +238,7 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
           g[i] = t * e_g[i];
         }
         *(f32x4 *)(a.x_out + (size_t)b * a.N + n0) = f32x4{v[0], v[1], v[2], v[3]};
-        if (a.act_out) store4_frag<OT, false>(a.act_out, b, n0, a.out_k_blocks, 1, g);
+        if (a.act_out) store4_frag<OT, false>(a.act_out, b, n0, a.out_k_blocks, g);
       }
       if (a.act_out) {  // partial row sums of this weight tile's 16 features
         s1 += __shfl_xor(s1, 16), s2 += __shfl_xor(s2, 16);
