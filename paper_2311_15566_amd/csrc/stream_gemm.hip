@@ -16,7 +16,7 @@ constexpr int U = 2;      // fragments per register batch; two batches in flight
 template <int NB, int KSM, int NW>
 struct GemmShared {
   f32x4 red[KSM][NW][NB][64];    // per K slice: the wave's sums [weight tile][batch tile][lane]
-  float stat[KSM * 128 * NB];    // row-sum slices [slice][batch tile][row][2], slices * rows = threads of the block
+  float stat[KSM * NB * 16 * 2]; // row sums per wave: [wave][batch tile][row][2]
   float lg_v[NW][NB * 16];       // logits: best value / index per weight tile and row
   int lg_i[NW][NB * 16];
   float fin_v[KSM * 64];         // [slice][row]
@@ -129,9 +129,10 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
 
   // Row sums of the normalised input.  The producer left one (sum, sum of squares) pair per 16-row
   // weight tile and row, two tiles to a float4.  Thread (slice, row) adds float4s slice,
-  // slice + nsl, ...; the slices are added in order in the epilogue.  The first SR of them are
-  // requested here, behind the first weight batches, and added after the main loop, when they
-  // have long arrived: nothing waits for them now.
+  // slice + nsl, ...; the slices of a wave are then added by a butterfly over its lanes and the
+  // waves in order in the epilogue.  The first SR float4s are requested here, behind the first
+  // weight batches, and added after the main loop, when they have long arrived: nothing waits
+  // for them now.
   constexpr bool NORMED = EPI != EPI_RESID;
   constexpr int SR = NORMED ? (GLU ? 2 : 4) : 0;
   // (the split of the partials over threads depends on the batch size only, so the sums come out
@@ -168,8 +169,13 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
       for (int i = 0; i < SR; ++i) sv += st_v[t][i];
       if (row0 + t * 16 + st_loc < a.B)
         for (int g = st_slice + SR * nsl; g < a.stat_groups; g += nsl) sv += st_p[(size_t)g * 32 + t * 16];  // the rest, if any
-      float *dst = &sh.stat[((st_slice * NB + t) * rbl + st_loc) * 2];
-      dst[0] = sv[0] + sv[2], dst[1] = sv[1] + sv[3];
+      // lanes loc, loc + rbl, loc + 2 rbl, ... of the wave hold the slices of row loc
+      float s1 = sv[0] + sv[2], s2 = sv[1] + sv[3];
+      for (int off = rbl; off < 64; off <<= 1) s1 += __shfl_xor(s1, off), s2 += __shfl_xor(s2, off);
+      if (lane < rbl) {
+        float *dst = &sh.stat[((ks * NB + t) * 16 + lane) * 2];
+        dst[0] = s1, dst[1] = s2;
+      }
     }
   }
 #pragma unroll
@@ -192,8 +198,8 @@ __global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamG
     if (NORMED && a.stat_groups > 0) {
       float u1 = 0.f, u2 = 0.f;
       const int br = r < rbl ? r : 0;  // rows past the batch are masked later
-      for (int s = 0; s < nsl; ++s) {
-        const float *src = &sh.stat[((s * NB + te) * rbl + br) * 2];
+      for (int s = 0; s < KS; ++s) {
+        const float *src = &sh.stat[((s * NB + te) * 16 + br) * 2];
         u1 += src[0], u2 += src[1];
       }
       const float inv = 1.0f / (float)a.norm_dim;
