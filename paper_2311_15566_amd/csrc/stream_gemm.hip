@@ -30,7 +30,7 @@ struct GemmShared {
 // both tiles in register batches of U fragments per tile, two batches in flight.
 // KSM: waves per block at most
 template <typename T, int NB, bool GLU, int EPI, int KSM, int NW>
-__global__ void __launch_bounds__(KSM * 64, NB == 1 ? 4 : 2) stream_gemm(StreamGemmArgs a) {
+__global__ void __launch_bounds__(KSM * 64, 2) stream_gemm(StreamGemmArgs a) {
   typedef typename Operand<T>::type OT;  // element type of the activation operands
   constexpr bool H16 = sizeof(T) == 2;     // bf16 models: weight fragments are stored as halves
   constexpr int RB = NB * 16;
