@@ -528,7 +528,7 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, c
   const int dt = m.dtype, d = L0.d;
   const int FK = dt == SS_DTYPE_BF16 ? 32 : 16;
   const int rms = m.norm == SS_NORM_RMSNORM;
-  const int T_live = B * S, T = (int)align_up((size_t)T_live, 128);
+  const int T_live = B * S, T = (int)align_up((size_t)T_live, 256);
   for (int i = 0; i < n_group; ++i)
     if (T > group[i]->L.Tmax) SS_FAIL(SS_EINVAL, "%d prompt tokens exceed group[%d]'s workspace (%d)", T_live, i, group[i]->L.Tmax);
   float *x = (float *)(g0->ws + L0.ws_x);

@@ -11,17 +11,30 @@
 namespace ss {
 
 // ---------------------------------------------------------------------------
-// tiled prefill GEMM: block = 128 output features x 128 tokens, 4 waves of 64 x 64,
-// K advanced two fragments at a time through LDS with register prefetch of the next stage.
+// tiled prefill GEMM: block = 128 output features x 256 tokens, 4 waves of 64 x 128.
+// One k fragment per stage; the stages go from global memory straight into a ring of two LDS
+// buffers (no registers in between), the next stage in flight while this one is multiplied.
+// Per matrix-core instruction a wave reads 3/8 of a fragment from LDS (1/2 with 64 x 64 wave
+// tiles): LDS bandwidth, not the matrix cores, bounds this loop.
 // ---------------------------------------------------------------------------
+// s_waitcnt with only the vector-memory counter set (gfx9 encoding: vmcnt = simm16[3:0] and
+// simm16[15:14]; the export and LDS counters stay at their maxima, i.e. are not waited for)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
 // bf16 models: the activation operands and the stored weight fragments are halves; float32 models: floats.
-template <typename T, int EPI>
-__global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
+// Either way a fragment is 64 lanes x 16 bytes, so the loop is the same.
+// NJ: token tiles of a wave, 8 (block of 256 tokens, two blocks per compute unit) or 4 (128 tokens, four)
+template <typename T, int EPI, int NJ>
+__global__ void __launch_bounds__(256, NJ == 8 ? 2 : 4) tile_gemm(TileGemmArgs a) {
   constexpr bool H16 = sizeof(T) == 2;
   typedef typename Operand<T>::type OT;  // element type of the activation operands
-  constexpr int KS = 2;  // k fragments per stage
-  __shared__ __align__(16) u32x4 lds_w[KS][8][64];
-  __shared__ __align__(16) u32x4 lds_a[KS][8][64];
+  constexpr int MI = 4;                  // weight row tiles of a wave
+  constexpr int BMT = 2 * MI, BTT = 2 * NJ;
+  constexpr int STAGE = (BMT + BTT) * 64;  // 16-byte pieces per stage: weight fragments, then activation fragments
+  __shared__ __align__(16) u32x4 lds[2 * STAGE];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave >> 1, wc = wave & 1;
   // Block -> output tile.  Workgroups go to the 8 XCDs round-robin and each XCD has its own L2, so
@@ -31,7 +44,7 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
   int rb, tb;
   {
     constexpr int GT = 8;  // token blocks per group
-    const int nrb = a.n_row_blocks, ntb = a.T / 128, nblk = nrb * ntb;
+    const int nrb = a.n_row_blocks, ntb = a.T / (BTT * 16), nblk = nrb * ntb;
     const int pid = blockIdx.x, xcd = pid % 8, local = pid / 8;
     const int base = nblk / 8, rem = nblk % 8;
     const int L = xcd * base + min(xcd, rem) + local;
@@ -40,57 +53,51 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
     tb = first_tb + within % gsz;
     rb = within / gsz;
   }
-  const int rt0 = rb * 8;   // first weight row tile
-  const int tt0 = tb * 8;   // first token tile
+  const int rt0 = rb * BMT;   // first weight row tile
+  const int tt0 = tb * BTT;   // first token tile
   const u32x4 *W = (const u32x4 *)a.w;
   const u32x4 *A = (const u32x4 *)a.act;
 
-  f32x4 acc[4][4];
+  f32x4 acc[MI][NJ];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < NJ; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // per stage each thread moves 4 weight pieces and 4 activation pieces:
-  // piece p = tid + 256*r -> (ks = p / 512, tile = (p / 64) % 8, ln = p % 64)
-  u32x4 pw[4], pa[4];
-  auto fetch = [&](int kb) {
+  // Stage k -> buffer buf: every wave brings 2 weight and 4 activation fragments, each as one
+  // 1 KiB load that the hardware writes to LDS at (wave-uniform base) + lane * 16.  Row tiles
+  // past the matrix repeat the last one (in bounds; their outputs are never stored).
+  auto issue = [&](int k, int buf) {
+    u32x4 *st = lds + buf * STAGE;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int p = tid + 256 * r;
-      const int ks = p >> 9, tile = (p >> 6) & 7, ln = p & 63;
-      const int k = kb + ks;
-      const bool kok = k < a.k_blocks;
-      pw[r] = (kok && rt0 + tile < a.row_tiles) ? W[((size_t)(rt0 + tile) * a.k_blocks + k) * 64 + ln]
-                                               : u32x4{0u, 0u, 0u, 0u};
-      pa[r] = kok ? A[((size_t)(tt0 + tile) * a.k_blocks + k) * 64 + ln] : u32x4{0u, 0u, 0u, 0u};
+    for (int r = 0; r < BMT / 4; ++r) {
+      const int tile = wave + 4 * r;
+      const int rt = min(rt0 + tile, a.row_tiles - 1);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(W + ((size_t)rt * a.k_blocks + k) * 64 + lane),
+                                       (__attribute__((address_space(3))) void *)(st + tile * 64), 16, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < BTT / 4; ++r) {
+      const int tile = wave + 4 * r;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(A + ((size_t)(tt0 + tile) * a.k_blocks + k) * 64 + lane),
+                                       (__attribute__((address_space(3))) void *)(st + (BMT + tile) * 64), 16, 0, 0);
     }
   };
-  fetch(0);
-  for (int kb = 0; kb < a.k_blocks; kb += KS) {
-    __syncthreads();
+  issue(0, 0);
+  for (int k = 0; k < a.k_blocks; ++k) {
+    wait_vmcnt<0>();   // this wave's share of stage k has landed
+    __syncthreads();   // everyone's has, and everyone is done reading the other buffer (stage k - 1)
+    if (k + 1 < a.k_blocks) issue(k + 1, (k + 1) & 1);
+    const u32x4 *st = lds + (k & 1) * STAGE;
+    u32x4 wf[MI], af[NJ];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int p = tid + 256 * r;
-      const int ks = p >> 9, tile = (p >> 6) & 7, ln = p & 63;
-      lds_w[ks][tile][ln] = pw[r];
-      lds_a[ks][tile][ln] = pa[r];
-    }
-    __syncthreads();
-    if (kb + KS < a.k_blocks) fetch(kb + KS);
+    for (int i = 0; i < MI; ++i) wf[i] = st[(wr * MI + i) * 64 + lane];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      u32x4 wf[4];
+    for (int j = 0; j < NJ; ++j) af[j] = st[(BMT + wc * NJ + j) * 64 + lane];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) wf[i] = lds_w[ks][wr * 4 + i][lane];
-      u32x4 af[4];
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) af[j] = lds_a[ks][wc * 4 + j][lane];
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = H16 ? mma_f16(wf[i], af[j], acc[i][j]) : Mma<T>::mma(wf[i], af[j], acc[i][j]);
-    }
+      for (int j = 0; j < NJ; ++j) acc[i][j] = H16 ? mma_f16(wf[i], af[j], acc[i][j]) : Mma<T>::mma(wf[i], af[j], acc[i][j]);
   }
 
   const int q4 = (lane >> 4) * 4, tl = lane & 15;
@@ -105,14 +112,14 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
     for (int e = 0; e < 4; ++e) v[e] = mr.y * (c[e] - mr.x * wg[e]) + cb[e];
   };
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int tok = (tt0 + wc * 4 + j) * 16 + tl;
+  for (int j = 0; j < NJ; ++j) {
+    const int tok = (tt0 + wc * NJ + j) * 16 + tl;
     const bool tok_live = tok < a.T_live;
     if (EPI == EPI_SWIGLU) {
       const float2 mr = a.mr_in ? make_float2(a.mr_in[tok][2], a.mr_in[tok][1]) : make_float2(0.f, 1.f);
 #pragma unroll
-      for (int i = 0; i < 4; i += 2) {
-        const int rt = rt0 + wr * 4 + i;  // gate tile; rt + 1 is the matching up tile
+      for (int i = 0; i < MI; i += 2) {
+        const int rt = rt0 + wr * MI + i;  // gate tile; rt + 1 is the matching up tile
         const int n0 = (rt >> 1) * 16 + q4;
         if (tok_live && rt + 1 < a.row_tiles && n0 < a.N) {
           float gt[4], up[4], u[4];
@@ -127,8 +134,8 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
       float s1 = 0.f, s2 = 0.f;
       const float cen = a.g_out ? a.c_in[tok][0] : 0.f;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int rt = rt0 + wr * 4 + i;
+      for (int i = 0; i < MI; ++i) {
+        const int rt = rt0 + wr * MI + i;
         const int n0 = rt * 16 + q4;
         if (tok_live && rt < a.row_tiles && n0 < a.N) {
           f32x4 *xp = (f32x4 *)(a.x_resid + (size_t)tok * a.N + n0);
@@ -158,8 +165,8 @@ __global__ void __launch_bounds__(256) tile_gemm(TileGemmArgs a) {
     } else {
       const float2 mr = a.mr_in ? make_float2(a.mr_in[tok][2], a.mr_in[tok][1]) : make_float2(0.f, 1.f);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int rt = rt0 + wr * 4 + i;
+      for (int i = 0; i < MI; ++i) {
+        const int rt = rt0 + wr * MI + i;
         const int n0 = rt * 16 + q4;
         if (tok_live && rt < a.row_tiles && n0 < a.N) {
           float v[4];
@@ -213,7 +220,7 @@ ss_status launch_row_stats(const float2 *part, int groups, int T, int norm_dim, 
 }
 
 ss_status launch_tile_gemm(int dtype, int epi, TileGemmArgs a, hipStream_t st) {
-  if (a.T < 128 || a.T % 128) SS_FAIL(SS_EINVAL, "prefill GEMM: token count %d is not a multiple of 128", a.T);
+  if (a.T < 256 || a.T % 256) SS_FAIL(SS_EINVAL, "prefill GEMM: token count %d is not a multiple of 256", a.T);
   if (a.row_tiles < 1 || a.k_blocks < 1 || a.N % 4) SS_FAIL(SS_EINVAL, "prefill GEMM: bad shape");
   if ((epi == EPI_F32 && (a.ld_out % 4)) || epi == EPI_LOGITS) SS_FAIL(SS_EINVAL, "prefill GEMM: bad epilogue");
   if (epi == EPI_RESID && a.g_out) {
@@ -222,8 +229,16 @@ ss_status launch_tile_gemm(int dtype, int epi, TileGemmArgs a, hipStream_t st) {
       SS_FAIL(SS_EINVAL, "prefill GEMM: bad next-operand arguments");
   }
   a.n_row_blocks = ceil_div(a.row_tiles, 8);
-  dim3 grid(a.n_row_blocks * (a.T / 128));
-#define SS_LAUNCH(TT, EPI) hipLaunchKernelGGL((tile_gemm<TT, EPI>), grid, dim3(256), 0, st, a)
+  // Token block: measured on the GPT-20B, LLaMA-30B and OPT-66B shard shapes, 256-token blocks win by
+  // 15-22 % once the output has about nine thousand 128 x 128 tiles (less LDS and L2 traffic per
+  // flop), 128-token blocks by 1-10 % below that (more blocks to spread over the compute units).
+  if (a.tok_tiles != 4 && a.tok_tiles != 8) a.tok_tiles = (long)a.n_row_blocks * (a.T / 128) >= 9216 ? 8 : 4;
+  dim3 grid(a.n_row_blocks * (a.T / (a.tok_tiles * 32)));
+#define SS_LAUNCH(TT, EPI)                                                                          \
+  do {                                                                                              \
+    if (a.tok_tiles == 8) hipLaunchKernelGGL((tile_gemm<TT, EPI, 8>), grid, dim3(256), 0, st, a);   \
+    else hipLaunchKernelGGL((tile_gemm<TT, EPI, 4>), grid, dim3(256), 0, st, a);                    \
+  } while (0)
   if (dtype == SS_DTYPE_BF16) {
     if (epi == EPI_F32) SS_LAUNCH(bf16_t, EPI_F32);
     else if (epi == EPI_RESID) SS_LAUNCH(bf16_t, EPI_RESID);

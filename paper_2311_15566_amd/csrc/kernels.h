@@ -75,7 +75,7 @@ int stream_gemm_blocks(int epi, const StreamGemmArgs &a);
 ss_status launch_fold_norm(int dtype, const void *w, int row_tiles, int k_blocks, const float *gamma, const float *beta,
                            const float *bias, float *wg, float *cb, hipStream_t st);
 
-// Prefill GEMM: out[t, n] = sum_k act[t, k] * W[n, k] over T tokens (multiple of 128), MFMA-bound.
+// Prefill GEMM: out[t, n] = sum_k act[t, k] * W[n, k] over T tokens (multiple of 256), MFMA-bound.
 // Norms are deferred as in the decode GEMM, and centred: the residual epilogue of the last shard
 // of a group also writes the next GEMM's operand (x - c) * gamma, c = the token's mean at the
 // previous norm (0 for RMSNorm), so that rounding the operand to 11 bits costs nothing to
@@ -88,7 +88,7 @@ struct TileGemmArgs {
   int row_tiles;      // 16-row weight tiles (SwiGLU: 2 per 16 outputs, interleaved)
   int k_blocks;
   const void *act;    // activation fragments [T/16][k_blocks] of the operand type
-  int T;              // tokens (padded to 128)
+  int T;              // tokens (padded to 256)
   int T_live;         // tokens that exist
   int N;
   const float *bias;  // plain bias (mr_in NULL), or NULL
@@ -107,6 +107,7 @@ struct TileGemmArgs {
   int out_k_blocks;
   int act_kind;
   int n_row_blocks;   // set by the launcher: 128-row blocks of the weight matrix
+  int tok_tiles;      // token tiles per wave, 8 or 4: blocks of 256 or 128 tokens (anything else: the launcher chooses)
 };
 ss_status launch_tile_gemm(int dtype, int epi, TileGemmArgs a, hipStream_t st);
 // mr[t] <- (mean, rstd, mean - c, 0) from `groups` partial (sum (x-c), sum (x-c)^2) pairs laid out

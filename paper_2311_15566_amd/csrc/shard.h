@@ -18,7 +18,7 @@ struct Layout {
   int Ls, Hs, Fs, d, Dh, V, max_pos, Bmax, Smax;
   int esz;             // bytes per element of the model dtype
   int Bpad;            // max_batch rounded up to 16
-  int Tmax;            // prefill tokens the workspace holds (Bmax*Smax rounded up to 128)
+  int Tmax;            // prefill tokens the workspace holds (Bmax*Smax rounded up to 256, the prefill GEMM's token block)
   int qkv_n;           // 3*Hs*Dh
   int w1_rows;         // Fs or 2*Fs
   int attn_splits;     // sequence splits of decode attention at Smax

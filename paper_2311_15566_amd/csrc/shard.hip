@@ -68,7 +68,7 @@ bool compute_layout(const ss_model_desc &m, const ss_slice &s, int max_batch, in
   L->Smax = max_seq;
   L->esz = m.dtype == SS_DTYPE_BF16 ? 2 : 4;
   L->Bpad = (int)align_up(max_batch, 16);
-  L->Tmax = (int)align_up((size_t)max_batch * max_seq, 128);
+  L->Tmax = (int)align_up((size_t)max_batch * max_seq, 256);
   L->qkv_n = 3 * L->Hs * L->Dh;
   L->w1_rows = m.act == SS_ACT_SWIGLU ? 2 * L->Fs : L->Fs;
   L->attn_splits = ceil_div(max_seq, 64);
