@@ -218,6 +218,11 @@ ss_status ss_set_graph_launch(ss_shard *shard, int32_t enabled);
  * (SS_TUNE=0 in the environment keeps the rule); every shape gives the same bits. */
 ss_status ss_debug_force_gemm_shape(int32_t tiles_per_block, int32_t batch_split);
 
+/* Test aid, process-wide: force the token block of the initial phase's tiled GEMMs (Eq. (2)'s
+ * first iteration over all prompt tokens): 128 or 256 tokens per block; 0 = the library's choice,
+ * which goes by the size of the output.  Both give the same bits.  SS_EINVAL for any other value. */
+ss_status ss_debug_force_prefill_block(int32_t tokens_per_block);
+
 /* Measurement aid: per-kernel-class timing of decode steps.  While enabled on group[0],
  * ss_decode_step launches kernel by kernel (no graph replay) and every launch records its own
  * begin and end on a pair of HIP events of the step's stream (the dispatch's timestamps).

@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     decode_step,
     device_kv_bytes,
     force_gemm_shape,
+    force_prefill_block,
     kv_export,
     kv_import,
     kv_repack,

@@ -78,6 +78,7 @@ def _load():
     L.ss_shard_model_context_bytes.argtypes = [vp]
     L.ss_shard_model_context_bytes.restype = C.c_size_t
     L.ss_debug_force_gemm_shape.argtypes = [i32, i32]
+    L.ss_debug_force_prefill_block.argtypes = [i32]
     L.ss_kernel_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), vp]
     return L
 
@@ -270,6 +271,11 @@ def kv_repack(dst, src, batch_map, first_source=True, stream=None) -> int:
 def force_gemm_shape(tiles_per_block: int = 0, batch_split: int = 0):
     """Test aid: force the decode GEMMs' launch shape for plans built from now on (0, 0 = library's choice)."""
     _check(lib.ss_debug_force_gemm_shape(int(tiles_per_block), int(batch_split)))
+
+
+def force_prefill_block(tokens_per_block: int = 0):
+    """Test aid: force the token block (128 or 256) of the initial phase's GEMMs (0 = library's choice)."""
+    _check(lib.ss_debug_force_prefill_block(int(tokens_per_block)))
 
 
 def device_kv_bytes(shard) -> int:

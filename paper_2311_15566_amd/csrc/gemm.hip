@@ -7,6 +7,7 @@
 #include <stdlib.h>
 
 #include <algorithm>
+#include <atomic>
 
 namespace ss {
 
@@ -219,6 +220,8 @@ ss_status launch_row_stats(const float2 *part, int groups, int T, int norm_dim, 
   return SS_OK;
 }
 
+static std::atomic<int> g_forced_tok_tiles{0};  // test aid: 0 = not forced
+
 ss_status launch_tile_gemm(int dtype, int epi, TileGemmArgs a, hipStream_t st) {
   if (a.T < 256 || a.T % 256) SS_FAIL(SS_EINVAL, "prefill GEMM: token count %d is not a multiple of 256", a.T);
   if (a.row_tiles < 1 || a.k_blocks < 1 || a.N % 4) SS_FAIL(SS_EINVAL, "prefill GEMM: bad shape");
@@ -232,6 +235,7 @@ ss_status launch_tile_gemm(int dtype, int epi, TileGemmArgs a, hipStream_t st) {
   // Token block: measured on the GPT-20B, LLaMA-30B and OPT-66B shard shapes, 256-token blocks win by
   // 15-22 % once the output has about nine thousand 128 x 128 tiles (less LDS and L2 traffic per
   // flop), 128-token blocks by 1-10 % below that (more blocks to spread over the compute units).
+  if (g_forced_tok_tiles.load()) a.tok_tiles = g_forced_tok_tiles.load();
   if (a.tok_tiles != 4 && a.tok_tiles != 8) a.tok_tiles = (long)a.n_row_blocks * (a.T / 128) >= 9216 ? 8 : 4;
   dim3 grid(a.n_row_blocks * (a.T / (a.tok_tiles * 32)));
 #define SS_LAUNCH(TT, EPI)                                                                          \
@@ -256,3 +260,11 @@ ss_status launch_tile_gemm(int dtype, int epi, TileGemmArgs a, hipStream_t st) {
 }
 
 }  // namespace ss
+
+extern "C" ss_status ss_debug_force_prefill_block(int32_t tokens_per_block) {
+  using namespace ss;
+  if (tokens_per_block != 0 && tokens_per_block != 128 && tokens_per_block != 256)
+    SS_FAIL(SS_EINVAL, "token block %d (0, 128 or 256)", tokens_per_block);
+  g_forced_tok_tiles.store(tokens_per_block / 32);
+  return SS_OK;
+}

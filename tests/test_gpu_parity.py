@@ -275,6 +275,38 @@ def test_gemm_launch_shapes_give_the_same_bits(ss, side_stream, name, batch):
             assert np.array_equal(bits(a) if a.dtype != np.int32 else a, bits(b) if b.dtype != np.int32 else b)
 
 
+@pytest.mark.parametrize("name,dtype,batch,s_in", [("gpt20b_m4", "bf16", 3, 111), ("llama30b_m2", "bf16", 5, 77), ("tiny_gpt", "f32", 2, 150)])
+def test_prefill_token_blocks_give_the_same_bits(ss, side_stream, name, dtype, batch, s_in):
+    """The initial phase's GEMMs run with 128- or 256-token blocks (chosen by output size): both
+    walk k in the same order, so logits, first tokens and caches must agree bit for bit — here
+    on token counts and feature counts that are multiples of neither block."""
+    import torch
+    if name == "tiny_gpt":
+        w = scaled(name, dtype, layers=2, batch=batch, s_in=s_in, steps=1)
+    else:
+        w = scaled(name, dtype, layers=2, batch=batch, s_in=s_in, steps=1, d_model=448, ffn=1152, head_dim=64, n_heads=4, vocab=1511)
+    W = make_weights(w.desc, w.slice, w.seed)
+    toks = make_tokens(w.seed, w.batch, w.s_in, w.desc["vocab"])
+    outs = []
+    try:
+        for block in (128, 256, 0):
+            ss.force_prefill_block(block)
+            sh = ss.Shard(w.desc, w.slice, W, w.batch, w.s_max)
+            logits = torch.empty(w.batch, w.desc["vocab"], dtype=torch.float32, device="cuda")
+            nxt = torch.empty(w.batch, dtype=torch.int32, device="cuda")
+            ss.prefill([sh], dev(toks), logits, nxt)
+            torch.cuda.synchronize()
+            outs.append([logits.cpu().numpy().copy(), nxt.cpu().numpy().copy(), ss.kv_export(sh)])
+            sh.destroy()
+    finally:
+        ss.force_prefill_block(0)
+    with pytest.raises(Exception):
+        ss.force_prefill_block(64)
+    for other in outs[1:]:
+        for a, b in zip(outs[0], other):
+            assert np.array_equal(bits(a) if a.dtype != np.int32 else a, bits(b) if b.dtype != np.int32 else b)
+
+
 @pytest.mark.parametrize("name,dtype,kw,cuts,group_m", [
     ("tiny_gpt", "f32", dict(layers=5, batch=3, s_in=20, steps=4), [0, 2, 3, 5], 1),
     ("gpt20b_m4", "bf16", dict(layers=4, batch=6, s_in=60, steps=4, head_dim=128, n_heads=4, d_model=512), [0, 1, 4], 1),
