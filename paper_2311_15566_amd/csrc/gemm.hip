@@ -8,15 +8,16 @@
 
 #include <algorithm>
 #include <atomic>
+#include <mutex>
 
 namespace ss {
 
 // ---------------------------------------------------------------------------
-// tiled prefill GEMM: block = 128 output features x 256 tokens, 4 waves of 64 x 128.
-// One k fragment per stage; the stages go from global memory straight into a ring of two LDS
-// buffers (no registers in between), the next stage in flight while this one is multiplied.
-// Per matrix-core instruction a wave reads 3/8 of a fragment from LDS (1/2 with 64 x 64 wave
-// tiles): LDS bandwidth, not the matrix cores, bounds this loop.
+// tiled prefill GEMM: block = 128 output features x 128 or 256 tokens, 4 waves of 64 x 64 or 64 x 128.
+// One k fragment per stage; the stages go from global memory straight into a ring of three LDS
+// buffers (no registers in between): while stage k is multiplied, stage k + 1 has landed or is
+// landing and stage k + 2 is requested.  Per matrix-core instruction a wave reads 3/8 of a
+// fragment from LDS (1/2 with 64 x 64 wave tiles).
 // ---------------------------------------------------------------------------
 // s_waitcnt with only the vector-memory counter set (gfx9 encoding: vmcnt = simm16[3:0] and
 // simm16[15:14]; the export and LDS counters stay at their maxima, i.e. are not waited for)
@@ -27,15 +28,18 @@ __device__ __forceinline__ void wait_vmcnt() {
 
 // bf16 models: the activation operands and the stored weight fragments are halves; float32 models: floats.
 // Either way a fragment is 64 lanes x 16 bytes, so the loop is the same.
-// NJ: token tiles of a wave, 8 (block of 256 tokens, two blocks per compute unit) or 4 (128 tokens, four)
+constexpr int kTileGemmRing = 3;  // LDS stages
+
+// NJ: token tiles of a wave, 8 (block of 256 tokens, two blocks per compute unit) or 4 (128 tokens, three)
 template <typename T, int EPI, int NJ>
-__global__ void __launch_bounds__(256, NJ == 8 ? 2 : 4) tile_gemm(TileGemmArgs a) {
+__global__ void __launch_bounds__(256, NJ == 8 ? 2 : 3) tile_gemm(TileGemmArgs a) {
   constexpr bool H16 = sizeof(T) == 2;
   typedef typename Operand<T>::type OT;  // element type of the activation operands
   constexpr int MI = 4;                  // weight row tiles of a wave
   constexpr int BMT = 2 * MI, BTT = 2 * NJ;
   constexpr int STAGE = (BMT + BTT) * 64;  // 16-byte pieces per stage: weight fragments, then activation fragments
-  __shared__ __align__(16) u32x4 lds[2 * STAGE];
+  constexpr int LPS = (BMT + BTT) / 4;     // loads a wave issues per stage
+  extern __shared__ __align__(16) u32x4 lds[];  // kTileGemmRing stages
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave >> 1, wc = wave & 1;
   // Block -> output tile.  Workgroups go to the 8 XCDs round-robin and each XCD has its own L2, so
@@ -85,11 +89,17 @@ __global__ void __launch_bounds__(256, NJ == 8 ? 2 : 4) tile_gemm(TileGemmArgs a
     }
   };
   issue(0, 0);
+  if (a.k_blocks > 1) issue(1, 1);
   for (int k = 0; k < a.k_blocks; ++k) {
-    wait_vmcnt<0>();   // this wave's share of stage k has landed
-    __syncthreads();   // everyone's has, and everyone is done reading the other buffer (stage k - 1)
-    if (k + 1 < a.k_blocks) issue(k + 1, (k + 1) & 1);
-    const u32x4 *st = lds + (k & 1) * STAGE;
+    // This wave's share of stage k has landed (loads complete in order; the stage after it may
+    // still be in flight).  The barrier then says that everyone's has, and that everyone has the
+    // operands of stage k - 1 in registers (LDS counter at zero), so that buffer can be refilled.
+    // Not __syncthreads(): its fence would also wait for the loads in flight.
+    if (k + 1 < a.k_blocks) wait_vmcnt<LPS>();
+    else wait_vmcnt<0>();
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    if (k + 2 < a.k_blocks) issue(k + 2, (k + 2) % kTileGemmRing);
+    const u32x4 *st = lds + (k % kTileGemmRing) * STAGE;
     u32x4 wf[MI], af[NJ];
 #pragma unroll
     for (int i = 0; i < MI; ++i) wf[i] = st[(wr * MI + i) * 64 + lane];
@@ -222,6 +232,19 @@ ss_status launch_row_stats(const float2 *part, int groups, int T, int norm_dim, 
 
 static std::atomic<int> g_forced_tok_tiles{0};  // test aid: 0 = not forced
 
+template <typename T, int EPI, int NJ>
+static ss_status launch_one(const TileGemmArgs &a, dim3 grid, hipStream_t st) {
+  constexpr size_t lds_bytes = (size_t)kTileGemmRing * (8 + 2 * NJ) * 1024;  // 48 / 72 KiB: above the 64 KiB that need no opt-in
+  static std::once_flag once;
+  static hipError_t attr = hipSuccess;
+  std::call_once(once, [] {
+    attr = hipFuncSetAttribute((const void *)tile_gemm<T, EPI, NJ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+  });
+  if (attr != hipSuccess) SS_FAIL(SS_EHIP, "prefill GEMM: %zu bytes of LDS refused: %s", lds_bytes, hipGetErrorString(attr));
+  hipLaunchKernelGGL((tile_gemm<T, EPI, NJ>), grid, dim3(256), lds_bytes, st, a);
+  return SS_OK;
+}
+
 ss_status launch_tile_gemm(int dtype, int epi, TileGemmArgs a, hipStream_t st) {
   if (a.T < 256 || a.T % 256) SS_FAIL(SS_EINVAL, "prefill GEMM: token count %d is not a multiple of 256", a.T);
   if (a.row_tiles < 1 || a.k_blocks < 1 || a.N % 4) SS_FAIL(SS_EINVAL, "prefill GEMM: bad shape");
@@ -232,16 +255,17 @@ ss_status launch_tile_gemm(int dtype, int epi, TileGemmArgs a, hipStream_t st) {
       SS_FAIL(SS_EINVAL, "prefill GEMM: bad next-operand arguments");
   }
   a.n_row_blocks = ceil_div(a.row_tiles, 8);
-  // Token block: measured on the GPT-20B, LLaMA-30B and OPT-66B shard shapes, 256-token blocks win by
-  // 15-22 % once the output has about nine thousand 128 x 128 tiles (less LDS and L2 traffic per
-  // flop), 128-token blocks by 1-10 % below that (more blocks to spread over the compute units).
+  // Token block: measured on every GEMM shape of the GPT-20B, LLaMA-30B and OPT-66B shards, 256-token
+  // blocks win by 3-9 % where the output has a few rounds of them (16384 tokens: fewer LDS and L2
+  // reads per flop), 128-token blocks by 7-17 % on the 4096-token shapes (more blocks to spread over
+  // the compute units) and by 8 % on a short reduction (1152), where a block is mostly epilogue.
   if (g_forced_tok_tiles.load()) a.tok_tiles = g_forced_tok_tiles.load();
-  if (a.tok_tiles != 4 && a.tok_tiles != 8) a.tok_tiles = (long)a.n_row_blocks * (a.T / 128) >= 9216 ? 8 : 4;
+  if (a.tok_tiles != 4 && a.tok_tiles != 8) a.tok_tiles = ((long)a.n_row_blocks * (a.T / 128) >= 2048 && a.k_blocks >= 64) ? 8 : 4;
   dim3 grid(a.n_row_blocks * (a.T / (a.tok_tiles * 32)));
-#define SS_LAUNCH(TT, EPI)                                                                          \
-  do {                                                                                              \
-    if (a.tok_tiles == 8) hipLaunchKernelGGL((tile_gemm<TT, EPI, 8>), grid, dim3(256), 0, st, a);   \
-    else hipLaunchKernelGGL((tile_gemm<TT, EPI, 4>), grid, dim3(256), 0, st, a);                    \
+#define SS_LAUNCH(TT, EPI)                                                \
+  do {                                                                    \
+    if (a.tok_tiles == 8) SS_TRY((launch_one<TT, EPI, 8>(a, grid, st)));  \
+    else SS_TRY((launch_one<TT, EPI, 4>(a, grid, st)));                   \
   } while (0)
   if (dtype == SS_DTYPE_BF16) {
     if (epi == EPI_F32) SS_LAUNCH(bf16_t, EPI_F32);
