@@ -48,30 +48,61 @@ ss_status launch_decode_attn(int dtype, const DecodeAttnArgs &a, hipStream_t st)
 }
 
 // ---------------------------------------------------------------------------
-// initial phase: rotate q (in place) and k, write K/V rows of all prompt positions
-// grid = (T tokens, Hs); block = DH threads
+// initial phase: rotate q (in place) and k, write K/V rows of all prompt positions.
+// DH/8 threads per (token, head), each with four dims of both halves of the head (a rotation
+// pairs dim e with e + DH/2); 256 threads per block.
 // ---------------------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ void store4_cache(T *dst, const f32x4 &v) {
+  T t[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) t[i] = Elem<T>::from_f32(v[i]);
+  if constexpr (sizeof(T) == 2) {
+    uint2 raw;
+    __builtin_memcpy(&raw, t, 8);
+    *(uint2 *)dst = raw;
+  } else {
+    *(f32x4 *)dst = v;
+  }
+}
+
 template <typename T, int DH>
-__global__ void __launch_bounds__(DH) prefill_kv_write(PrefillAttnArgs a) {
-  const int t = blockIdx.x, h = blockIdx.y, e = threadIdx.x;
+__global__ void __launch_bounds__(256) prefill_kv_write(PrefillAttnArgs a) {
+  constexpr int HALF = DH / 2, TPP = HALF / 4, PPB = 256 / TPP;
+  const int pair = blockIdx.x * PPB + threadIdx.x / TPP;
+  if (pair >= a.B * a.S * a.Hs) return;
+  const int t = pair / a.Hs, h = pair - t * a.Hs, e0 = (threadIdx.x % TPP) * 4;
   const int b = t / a.S, pos = t - b * a.S;
   const int HD = a.Hs * DH;
-  float *row = a.qkv + (size_t)t * 3 * HD;
-  const float2 *tab = a.rope ? a.rope + (size_t)pos * (DH / 2) : nullptr;
-  const float q = rope_elem(row + h * DH, e, DH / 2, tab);
-  const float k = rope_elem(row + HD + h * DH, e, DH / 2, tab);
-  const float v = row[2 * HD + h * DH + e];
-  __syncthreads();  // every thread has read its pair before q is overwritten
-  row[h * DH + e] = q;
+  float *row = a.qkv + (size_t)t * 3 * HD + h * DH;
+  f32x4 qlo = *(const f32x4 *)(row + e0), qhi = *(const f32x4 *)(row + HALF + e0);
+  f32x4 klo = *(const f32x4 *)(row + HD + e0), khi = *(const f32x4 *)(row + HD + HALF + e0);
+  const f32x4 vlo = *(const f32x4 *)(row + 2 * HD + e0), vhi = *(const f32x4 *)(row + 2 * HD + HALF + e0);
+  if (a.rope) {
+    const float2 *tab = a.rope + (size_t)pos * HALF + e0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float2 cs = tab[i];
+      const float ql = qlo[i] * cs.x - qhi[i] * cs.y, qh = qlo[i] * cs.y + qhi[i] * cs.x;
+      const float kl = klo[i] * cs.x - khi[i] * cs.y, kh = klo[i] * cs.y + khi[i] * cs.x;
+      qlo[i] = ql, qhi[i] = qh, klo[i] = kl, khi[i] = kh;
+    }
+    *(f32x4 *)(row + e0) = qlo;
+    *(f32x4 *)(row + HALF + e0) = qhi;
+  }
   const size_t off = b * a.row_stride + h * a.head_stride + (size_t)pos * DH * sizeof(T);
-  ((T *)(a.k_cache + off))[e] = Elem<T>::from_f32(k);
-  ((T *)(a.v_cache + off))[e] = Elem<T>::from_f32(v);
+  T *kc = (T *)(a.k_cache + off), *vc = (T *)(a.v_cache + off);
+  store4_cache<T>(kc + e0, klo);
+  store4_cache<T>(kc + HALF + e0, khi);
+  store4_cache<T>(vc + e0, vlo);
+  store4_cache<T>(vc + HALF + e0, vhi);
 }
 
 ss_status launch_prefill_kv_write(int dtype, const PrefillAttnArgs &a, hipStream_t st) {
   if (a.S < 1 || a.S > a.Smax || a.B < 1 || (a.Dh != 64 && a.Dh != 128)) SS_FAIL(SS_EINVAL, "prefill KV write: bad shape");
-  dim3 grid(a.B * a.S, a.Hs);
-#define SS_LAUNCH(KT, DH) hipLaunchKernelGGL((prefill_kv_write<KT, DH>), grid, dim3(DH), 0, st, a)
+  const int pairs_per_block = 256 / (a.Dh / 8);
+  dim3 grid(ceil_div(a.B * a.S * a.Hs, pairs_per_block));
+#define SS_LAUNCH(KT, DH) hipLaunchKernelGGL((prefill_kv_write<KT, DH>), grid, dim3(256), 0, st, a)
   (void)dtype;
   if (a.kv_dtype == SS_DTYPE_F16) {
     if (a.Dh == 128) SS_LAUNCH(f16_t, 128);
