@@ -152,6 +152,10 @@ CASES = [
     # numbers ~625x its size, so float32 rounding of ~1e-7 shows up ~25-600x larger: bar 3e-5 instead of 1e-5)
     ("gpt20b_m4", "f32", dict(batch=2, s_in=20, steps=3, wte_offset=0.5, f32_rel=1e-5)),
     ("llama30b_m2", "bf16", dict(batch=4, s_in=40, steps=3, wte_offset=0.5)),
+    # the narrowest shapes the library takes: one head of 64 and 64 FFN columns per shard, every reduction 2 k
+    # fragments long (shorter than the prefill GEMM's LDS ring and than the decode GEMM's wave count)
+    ("gpt20b_m4", "bf16", dict(d_model=64, n_heads=2, head_dim=64, ffn=128, vocab=777, batch=2, s_in=9, steps=3)),
+    ("llama30b_m2", "bf16", dict(d_model=64, n_heads=2, head_dim=64, ffn=128, vocab=777, batch=2, s_in=9, steps=3)),
 ]
 
 
