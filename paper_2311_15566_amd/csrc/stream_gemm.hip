@@ -294,11 +294,22 @@ __global__ void __launch_bounds__(KSM * 64, 2) stream_gemm(StreamGemmArgs a) {
     const int row = tid % rbf, slice = tid / rbf, nslice = blockDim.x / rbf;
     bv = -INFINITY, bi = INT_MAX;
     if (row < a.B) {
-#pragma unroll 8
-      for (int g = slice; g < a.n_blocks; g += nslice) {
-        const float ov = ld_dev(&a.am_val[(size_t)g * 32 + row]);
-        const int oi = ld_dev(&a.am_idx[(size_t)g * 32 + row]);
-        if (ov > bv || (ov == bv && oi < bi)) bv = ov, bi = oi;
+      // this scan is the step's serial tail: all of a thread's loads (they miss every cache) go out
+      // together, 32 blocks a batch, instead of a few at a time
+      constexpr int MB = 32;
+      for (int g0 = slice; g0 < a.n_blocks; g0 += nslice * MB) {
+        float ov[MB];
+        int oi[MB];
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+          const int g = g0 + i * nslice;
+          const bool ok = g < a.n_blocks;
+          ov[i] = ok ? ld_dev(&a.am_val[(size_t)g * 32 + row]) : -INFINITY;
+          oi[i] = ok ? ld_dev(&a.am_idx[(size_t)g * 32 + row]) : INT_MAX;
+        }
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+          if (ov[i] > bv || (ov[i] == bv && oi[i] < bi)) bv = ov[i], bi = oi[i];
       }
     }
     sh.fin_v[slice * rbf + row] = bv, sh.fin_i[slice * rbf + row] = bi;
