@@ -229,7 +229,8 @@ ss_status ss_debug_force_prefill_block(int32_t tokens_per_block);
  * ss_kernel_timing_read synchronizes the stream, returns the milliseconds and launch counts
  * accumulated per class since the last read (host arrays of 8) and clears them.  Classes:
  * 0 embedding, 1 QKV GEMM, 2 decode attention, 3 out-projection and second-FFN GEMM (the
- * residual epilogue), 4 first-FFN GEMM, 5 LM head, 6 the commit kernel of a stage without LM head. */
+ * residual epilogue), 4 first-FFN GEMM, 5 LM head, 6 the kernel that ends a step (greedy choice among
+ * the LM head's per-block candidates, if there is an LM head, then the token-level commit). */
 ss_status ss_kernel_timing(ss_shard *shard, int32_t enabled);
 ss_status ss_kernel_timing_read(ss_shard *shard, double ms[8], int64_t count[8], void *hip_stream);
 

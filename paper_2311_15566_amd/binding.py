@@ -211,7 +211,7 @@ class Shard:
     def kernel_timing_read(self, stream=None):
         ms, cnt = (C.c_double * 8)(), (C.c_int64 * 8)()
         _check(lib.ss_kernel_timing_read(self.handle, ms, cnt, _stream(stream)))
-        names = ("embed", "qkv_gemm", "decode_attn", "resid_gemm", "ffn_up_gemm", "lm_head", "stage_commit")
+        names = ("embed", "qkv_gemm", "decode_attn", "resid_gemm", "ffn_up_gemm", "lm_head", "commit")
         return {n: (ms[i], cnt[i]) for i, n in enumerate(names)}
 
     def geometry(self):

@@ -62,14 +62,57 @@ __global__ void __launch_bounds__(256) gather_last(const float *x, int S, float 
   }
 }
 
-// token-level commit of a stage that hands hidden states on (no LM head): the last action of its step
+// The last kernel of a step, one block per batch row: after an LM head, the greedy choice among
+// the per-block candidates (highest logit, lowest index on ties: the result does not depend on
+// the order they are looked at) -> next_tokens; then the token-level commit, n[b] += inc for every
+// shard of the group: the last action of the step.  A stage that hands hidden states on has no
+// candidates (am_val NULL) and only commits.
 struct CommitArgs {
+  const float *am_val;  // [32][n_blocks] or NULL
+  const int *am_idx;
+  int n_blocks;
+  int32_t *next_tokens;  // [B] or NULL
   int32_t *lens[8];
   int n_lens, B, inc;
 };
-__global__ void commit_rows(CommitArgs a) {
-  if ((int)threadIdx.x < a.B)
-    for (int q = 0; q < a.n_lens; ++q) a.lens[q][threadIdx.x] += a.inc;
+__global__ void __launch_bounds__(256) choose_and_commit(CommitArgs a) {
+  __shared__ float s_v[256];
+  __shared__ int s_i[256];
+  const int row = blockIdx.x, tid = threadIdx.x;
+  if (a.am_val && a.next_tokens) {
+    float bv = -INFINITY;
+    int bi = INT_MAX;
+    const float *v = a.am_val + (size_t)row * a.n_blocks;
+    const int *ix = a.am_idx + (size_t)row * a.n_blocks;
+    for (int g = tid; g < a.n_blocks; g += 256) {
+      const float ov = v[g];
+      const int oi = ix[g];
+      if (ov > bv || (ov == bv && oi < bi)) bv = ov, bi = oi;
+    }
+    s_v[tid] = bv, s_i[tid] = bi;
+    __syncthreads();
+    for (int half = 128; half > 0; half >>= 1) {
+      if (tid < half) {
+        const float ov = s_v[tid + half];
+        const int oi = s_i[tid + half];
+        if (ov > s_v[tid] || (ov == s_v[tid] && oi < s_i[tid])) s_v[tid] = ov, s_i[tid] = oi;
+      }
+      __syncthreads();
+    }
+    if (tid == 0) a.next_tokens[row] = s_i[0];
+  }
+  if (tid == 0)
+    for (int q = 0; q < a.n_lens; ++q) a.lens[q][row] += a.inc;
+}
+static ss_status launch_commit(const StreamGemmArgs &g, hipStream_t st) {
+  if (g.B < 1 || g.B > 32 || g.n_lens < 0 || g.n_lens > 8) SS_FAIL(SS_EINVAL, "commit: batch %d, %d shards", g.B, g.n_lens);
+  CommitArgs c = {};
+  c.am_val = g.am_val, c.am_idx = g.am_idx, c.n_blocks = g.n_blocks, c.next_tokens = g.next_tokens;
+  c.n_lens = g.n_lens, c.B = g.B, c.inc = g.commit_inc;
+  for (int q = 0; q < c.n_lens; ++q) c.lens[q] = g.lens[q];
+  SS_LAUNCH_KERNEL(choose_and_commit, dim3(g.B), dim3(256), 0, st, c);
+  SS_HIP(hipGetLastError());
+  return SS_OK;
 }
 
 // ---------------------------------------------------------------------------
@@ -189,7 +232,6 @@ static Phase lm_head_phase(Shard *const *group, int n_group, int B, int stat_gro
   a.out_f32 = logits, a.ld_out = L.V;
   a.am_val = (float *)(g0->ws + L.ws_argmax);
   a.am_idx = (int *)(a.am_val + (size_t)ceil_div(a.row_tiles, 2) * 32);
-  a.counter = (int *)(g0->ws + L.ws_counters);
   a.next_tokens = next_tokens;
   for (int i = 0; i < n_group; ++i) a.lens[i] = group[i]->d_len;
   a.n_lens = n_group, a.commit_inc = commit_inc;
@@ -309,13 +351,16 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
   }
   if (hidden_out) {
     Phase ph = {};
-    ph.kind = PH_COMMIT, ph.gx = 1, ph.gy = 1;
+    ph.kind = PH_COMMIT, ph.gx = B, ph.gy = 1;
     ph.g.B = B, ph.g.n_lens = n_group, ph.g.commit_inc = 1;
     for (int i = 0; i < n_group; ++i) ph.g.lens[i] = group[i]->d_len;
     plan->push_back(ph);
     return;
   }
-  plan->push_back(lm_head_phase(group, n_group, B, stat_groups, logits, next_tokens, 1));
+  Phase lm = lm_head_phase(group, n_group, B, stat_groups, logits, next_tokens, 1);
+  plan->push_back(lm);
+  lm.kind = PH_COMMIT, lm.gx = B, lm.gy = 1;  // picks the tokens among the LM head's candidates, then commits
+  plan->push_back(lm);
 }
 
 // ---------------------------------------------------------------------------
@@ -364,14 +409,7 @@ static ss_status launch_phase(Shard *g0, const Phase &ph, hipStream_t st) {
     case PH_RESID: return launch_stream_gemm(dt, EPI_RESID, ph.g, st);
     case PH_FFN_UP: return launch_stream_gemm(dt, g0->m.act == SS_ACT_SWIGLU ? EPI_SWIGLU : EPI_ACT, ph.g, st);
     case PH_LM_HEAD: return launch_stream_gemm(dt, EPI_LOGITS, ph.g, st);
-    case PH_COMMIT: {
-      CommitArgs c = {};
-      c.n_lens = ph.g.n_lens, c.B = ph.g.B, c.inc = ph.g.commit_inc;
-      for (int q = 0; q < c.n_lens; ++q) c.lens[q] = ph.g.lens[q];
-      SS_LAUNCH_KERNEL(commit_rows, dim3(1), dim3(32), 0, st, c);
-      SS_HIP(hipGetLastError());
-      return SS_OK;
-    }
+    case PH_COMMIT: return launch_commit(ph.g, st);
   }
   SS_FAIL(SS_EINVAL, "unknown phase kind %d", ph.kind);
 }
@@ -603,12 +641,10 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, c
   }
   if (hidden_out) {  // a stage that hands its hidden states on: copy them out, then commit
     SS_HIP(hipMemcpyAsync(hidden_out, x, (size_t)T_live * d * 4, hipMemcpyDeviceToDevice, st));
-    CommitArgs c = {};
-    c.n_lens = n_group, c.B = B, c.inc = S;
+    StreamGemmArgs c = {};
+    c.n_lens = n_group, c.B = B, c.commit_inc = S;
     for (int i = 0; i < n_group; ++i) c.lens[i] = group[i]->d_len;
-    hipLaunchKernelGGL(commit_rows, dim3(1), dim3(32), 0, st, c);
-    SS_HIP(hipGetLastError());
-    return SS_OK;
+    return launch_commit(c, st);
   }
   float *xd = (float *)(g0->ws + L0.ws_xd);
   void *ad = g0->ws + L0.ws_ad;
@@ -618,7 +654,8 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, c
   else hipLaunchKernelGGL(gather_last<float>, dim3(B), dim3(256), 0, st, x, S, xd, g0->lnf_g, ad, statd, cen, d, rms);
   SS_HIP(hipGetLastError());
   const Phase ph = lm_head_phase(group, n_group, B, 1, logits, next_tokens, S);
-  return launch_stream_gemm(dt, EPI_LOGITS, ph.g, st);
+  SS_TRY(launch_stream_gemm(dt, EPI_LOGITS, ph.g, st));
+  return launch_commit(ph.g, st);
 }
 
 }  // namespace ss

@@ -60,11 +60,11 @@ struct StreamGemmArgs {
   const float *g_out;   // EPI_RESID: gamma of the norm that follows
   float *stat_out;      // EPI_RESID: [row_tiles / 2][32][4] partial sums of x_out - c, one pair per weight tile (with act_out)
   int act_kind;
-  float *am_val;        // EPI_LOGITS: [blocks][32]
-  int *am_idx;
-  int *counter;         // EPI_LOGITS: arrival counter of the grid
-  int32_t *next_tokens;
-  int32_t *lens[8];     // EPI_LOGITS: committed lengths to advance (all shards of the group)
+  float *am_val;        // EPI_LOGITS: [32][n_blocks] best logit of each block per batch row (written; chosen among by PH_COMMIT)
+  int *am_idx;          //             and its vocabulary index (lowest on ties)
+  // PH_COMMIT only (the kernel that ends a step; the GEMM kernels do not read these)
+  int32_t *next_tokens; // [B] or NULL
+  int32_t *lens[8];     // committed lengths to advance (all shards of the group)
   int n_lens;
   int commit_inc;
 };
@@ -160,7 +160,7 @@ struct Phase {
   int gx, gy;    // blocks: (rows, 1), (tile pairs, 1) or (batch*heads, splits)
   int shard;     // index of the shard in the group that owns the phase's scratch
   EmbedArgs e;
-  StreamGemmArgs g;   // PH_COMMIT (a stage that hands on hidden states) uses B, lens, n_lens, commit_inc only
+  StreamGemmArgs g;   // PH_COMMIT uses B, lens, n_lens, commit_inc and, after an LM head, am_val, am_idx, n_blocks, next_tokens
   DecodeAttnArgs at;
 };
 

@@ -19,9 +19,6 @@ struct GemmShared {
   float stat[KSM * NB * 16 * 2]; // row sums per wave: [wave][batch tile][row][2]
   float lg_v[NW][NB * 16];       // logits: best value / index per weight tile and row
   int lg_i[NW][NB * 16];
-  float fin_v[KSM * 64];         // [slice][row]
-  int fin_i[KSM * 64];
-  int flag;
 };
 
 }  // namespace
@@ -273,9 +270,11 @@ __global__ void __launch_bounds__(KSM * 64, 2) stream_gemm(StreamGemmArgs a) {
   }
   if (EPI != EPI_LOGITS) return;
 
-  // ---- greedy choice over the vocabulary: per-block best, then the last block to arrive scans ----
+  // ---- greedy choice over the vocabulary: this block's best per batch row; the step's last kernel
+  // (choose_and_commit) picks among the blocks.  No block waits for another and nothing is counted:
+  // a device-wide counter that every block bumps and reads back costs the step some 70 us.
   __syncthreads();
-  if (tid < RB) {
+  if (tid < RB && row0 + tid < a.B) {
     bv = sh.lg_v[0][tid], bi = sh.lg_i[0][tid];
 #pragma unroll
     for (int j = 1; j < NW; ++j) {
@@ -283,48 +282,8 @@ __global__ void __launch_bounds__(KSM * 64, 2) stream_gemm(StreamGemmArgs a) {
       const int oi = sh.lg_i[j][tid];
       if (ov > bv || (ov == bv && oi < bi)) bv = ov, bi = oi;
     }
-    st_dev(&a.am_val[(size_t)blk * 32 + row0 + tid], bv);
-    st_dev(&a.am_idx[(size_t)blk * 32 + row0 + tid], bi);
-  }
-  if (!arrive_last(a.counter, (int)gridDim.x, &sh.flag)) return;
-  {
-    // thread (slice, row) scans blocks slice, slice + n, ...; ties go to the lowest index whatever
-    // the order, so the merge does not depend on scheduling
-    const int rbf = a.B <= 8 ? 8 : (a.B <= 16 ? 16 : 32);  // all rows of the batch now
-    const int row = tid % rbf, slice = tid / rbf, nslice = blockDim.x / rbf;
-    bv = -INFINITY, bi = INT_MAX;
-    if (row < a.B) {
-      // this scan is the step's serial tail: all of a thread's loads (they miss every cache) go out
-      // together, 32 blocks a batch, instead of a few at a time
-      constexpr int MB = 32;
-      for (int g0 = slice; g0 < a.n_blocks; g0 += nslice * MB) {
-        float ov[MB];
-        int oi[MB];
-#pragma unroll
-        for (int i = 0; i < MB; ++i) {
-          const int g = g0 + i * nslice;
-          const bool ok = g < a.n_blocks;
-          ov[i] = ok ? ld_dev(&a.am_val[(size_t)g * 32 + row]) : -INFINITY;
-          oi[i] = ok ? ld_dev(&a.am_idx[(size_t)g * 32 + row]) : INT_MAX;
-        }
-#pragma unroll
-        for (int i = 0; i < MB; ++i)
-          if (ov[i] > bv || (ov[i] == bv && oi[i] < bi)) bv = ov[i], bi = oi[i];
-      }
-    }
-    sh.fin_v[slice * rbf + row] = bv, sh.fin_i[slice * rbf + row] = bi;
-    __syncthreads();
-    if (tid < a.B) {
-      bv = sh.fin_v[tid], bi = sh.fin_i[tid];
-      for (int q = 1; q < nslice; ++q) {
-        const float ov = sh.fin_v[q * rbf + tid];
-        const int oi = sh.fin_i[q * rbf + tid];
-        if (ov > bv || (ov == bv && oi < bi)) bv = ov, bi = oi;
-      }
-      if (a.next_tokens) a.next_tokens[tid] = bi;
-      // token-level commit: the last action of the step
-      for (int q = 0; q < a.n_lens; ++q) a.lens[q][tid] += a.commit_inc;
-    }
+    a.am_val[(size_t)(row0 + tid) * a.n_blocks + blk] = bv;   // [row][block]: a row's candidates are contiguous
+    a.am_idx[(size_t)(row0 + tid) * a.n_blocks + blk] = bi;
   }
 }
 
@@ -362,7 +321,7 @@ ss_status check_stream_gemm(int dtype, int epi, const StreamGemmArgs &a) {
         SS_FAIL(SS_EINVAL, "decode GEMM: bad residual operand output");
       break;
     case EPI_LOGITS:
-      if (!a.am_val || !a.am_idx || !a.counter || a.n_lens < 0 || a.n_lens > 8 || (a.out_f32 && a.ld_out < a.N))
+      if (!a.am_val || !a.am_idx || (a.out_f32 && a.ld_out < a.N))
         SS_FAIL(SS_EINVAL, "decode GEMM: bad logits arguments");
       break;
     default: SS_FAIL(SS_EINVAL, "decode GEMM: unknown epilogue %d", epi);

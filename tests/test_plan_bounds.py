@@ -20,7 +20,7 @@ class GemmArgs(C.Structure):
     _fields_ = [("w", vp), ("row_tiles", i32), ("k_blocks", i32), ("ks", i32), ("nw", i32), ("n_blocks", i32), ("bt_split", i32), ("B", i32), ("N", i32), ("act", vp),
                 ("stat_in", vp), ("cen", vp), ("publish", i32), ("stat_groups", i32), ("norm_dim", i32), ("rms", i32), ("eps", f32), ("wg", vp), ("cb", vp),
                 ("out_f32", vp), ("ld_out", i32), ("x_in", vp), ("x_out", vp), ("act_out", vp), ("out_k_blocks", i32),
-                ("g_out", vp), ("stat_out", vp), ("act_kind", i32), ("am_val", vp), ("am_idx", vp), ("counter", vp),
+                ("g_out", vp), ("stat_out", vp), ("act_kind", i32), ("am_val", vp), ("am_idx", vp),
                 ("next_tokens", vp), ("lens", vp * 8), ("n_lens", i32), ("commit_inc", i32)]
 
 
@@ -38,7 +38,7 @@ lib = B.lib
 lib.ss_debug_plan.restype = i32
 lib.ss_debug_plan.argtypes = [C.POINTER(B.ModelDesc), C.POINTER(B.Slice), i32, i32, i32, C.c_uint64, vp, i32,
                               C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
-EMBED, QKV, ATTN, RESID, FFN_UP, LM_HEAD = range(6)
+EMBED, QKV, ATTN, RESID, FFN_UP, LM_HEAD, COMMIT = range(7)
 
 
 def plan(w):
@@ -69,7 +69,7 @@ def check(w):
         regions.append((ptr, ptr + nbytes, label, inplace))
 
     layers = w.slice["layer_hi"] - w.slice["layer_lo"]
-    assert [p.kind for p in ph] == [EMBED] + [QKV, ATTN, RESID, FFN_UP, RESID] * layers + [LM_HEAD]
+    assert [p.kind for p in ph] == [EMBED] + [QKV, ATTN, RESID, FFN_UP, RESID] * layers + [LM_HEAD, COMMIT]
     stat_groups = None
     for i, p in enumerate(ph):
         regions = []
@@ -95,6 +95,13 @@ def check(w):
             rng("vcache", a.v_cache, span, regions)
             assert a.splits * a.rows_per_block >= a.Smax and p.gx == a.B * a.Hs and p.gy == a.splits
             assert a.waves in (4, 16)
+        elif p.kind == COMMIT:
+            g = p.g
+            assert p.gx == w.batch == g.B and g.n_lens == 1 and g.commit_inc == 1
+            lm = ph[i - 1].g                                  # picks among the candidates the LM head left
+            assert ph[i - 1].kind == LM_HEAD and (g.am_val, g.am_idx, g.n_blocks) == (lm.am_val, lm.am_idx, lm.n_blocks)
+            rng("am_val", g.am_val, 32 * g.n_blocks * 4, regions)
+            rng("am_idx", g.am_idx, 32 * g.n_blocks * 4, regions)
         else:
             g = p.g
             assert g.ks in (4, 8) and g.B == w.batch and p.gy == 1 and g.nw in (1, 2) and g.n_blocks == -(-g.row_tiles // g.nw)
@@ -134,10 +141,8 @@ def check(w):
                 stat_groups = g.row_tiles // 2
             if p.kind == LM_HEAD:
                 assert g.N == w.desc["vocab"]
-                rng("am_val", g.am_val, g.n_blocks * 32 * 4, regions)
-                rng("am_idx", g.am_idx, g.n_blocks * 32 * 4, regions)
-                rng("counter", g.counter, 4, regions)
-                assert g.n_lens == 1 and g.commit_inc == 1
+                rng("am_val", g.am_val, 32 * g.n_blocks * 4, regions)     # [32 rows][blocks]
+                rng("am_idx", g.am_idx, 32 * g.n_blocks * 4, regions)
         regions.sort()
         for (a0, a1, la, _), (b0, b1, lb, _) in zip(regions, regions[1:]):
             if b0 < a1 and not ({la, lb} <= {"kcache", "vcache"}):
