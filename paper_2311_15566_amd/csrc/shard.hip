@@ -141,7 +141,7 @@ bool compute_layout(const ss_model_desc &m, const ss_slice &s, int max_batch, in
     L->ws_od = wtake((size_t)2 * (HD / fk) * 1024);
     L->ws_ud = wtake((size_t)2 * (L->Fs / fk) * 1024);
   }
-  L->n_counters = 16 + max_batch * L->Hs;  // [0]: the LM head's arrival counter; [16..): attention, per (row, head)
+  L->n_counters = 16 + max_batch * L->Hs;  // [16..): decode attention's arrival counters, per (row, head); [0..16) unused
   L->ws_counters = wtake((size_t)L->n_counters * 4);
   L->ws_attn_part = wtake((size_t)max_batch * L->Hs * L->attn_splits * (L->Dh + 4) * 4);
   L->ws_argmax = wtake((size_t)ceil_div(ceil_div(L->V, 16), 2) * 32 * 8);
