@@ -84,10 +84,20 @@ __global__ void __launch_bounds__(256) choose_and_commit(CommitArgs a) {
     int bi = INT_MAX;
     const float *v = a.am_val + (size_t)row * a.n_blocks;
     const int *ix = a.am_idx + (size_t)row * a.n_blocks;
-    for (int g = tid; g < a.n_blocks; g += 256) {
-      const float ov = v[g];
-      const int oi = ix[g];
-      if (ov > bv || (ov == bv && oi < bi)) bv = ov, bi = oi;
+    constexpr int MB = 8;  // requests a thread makes in one go: the candidates come from memory, one round trip for 2048 blocks
+    for (int g0 = tid; g0 < a.n_blocks; g0 += 256 * MB) {
+      float ov[MB];
+      int oi[MB];
+#pragma unroll
+      for (int i = 0; i < MB; ++i) {
+        const int g = g0 + i * 256;
+        const bool ok = g < a.n_blocks;
+        ov[i] = ok ? v[g] : -INFINITY;
+        oi[i] = ok ? ix[g] : INT_MAX;
+      }
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+        if (ov[i] > bv || (ov[i] == bv && oi[i] < bi)) bv = ov[i], bi = oi[i];
     }
     s_v[tid] = bv, s_i[tid] = bi;
     __syncthreads();
