@@ -188,17 +188,24 @@ __global__ void __launch_bounds__(KSM * 64, 2) stream_gemm(StreamGemmArgs a) {
 #pragma unroll
     for (int jj = 0; jj < NWE; ++jj) {
       const int j = GLU ? jj : je;
-      sum[jj] = sh.red[0][j][te][lane];
-      for (int s = 1; s < KS; ++s) sum[jj] += sh.red[s][j][te][lane];
+      f32x4 part[KSM];  // all slices requested before the first is added: one LDS round trip, not KS
+#pragma unroll
+      for (int s = 0; s < KSM; ++s) part[s] = sh.red[s < KS ? s : 0][j][te][lane];
+      sum[jj] = part[0];
+#pragma unroll
+      for (int s = 1; s < KSM; ++s)
+        if (s < KS) sum[jj] += part[s];
     }
     float mean = 0.f, rstd = 1.f;  // mean: of the centred rows, i.e. mean(x) - c
     if (NORMED && a.stat_groups > 0) {
       float u1 = 0.f, u2 = 0.f;
       const int br = r < rbl ? r : 0;  // rows past the batch are masked later
-      for (int s = 0; s < KS; ++s) {
-        const float *src = &sh.stat[((s * NB + te) * 16 + br) * 2];
-        u1 += src[0], u2 += src[1];
-      }
+      float2 sp[KSM];
+#pragma unroll
+      for (int s = 0; s < KSM; ++s) sp[s] = *(const float2 *)&sh.stat[(((s < KS ? s : 0) * NB + te) * 16 + br) * 2];
+#pragma unroll
+      for (int s = 0; s < KSM; ++s)
+        if (s < KS) u1 += sp[s].x, u2 += sp[s].y;
       const float inv = 1.0f / (float)a.norm_dim;
       const float ms = u2 * inv;
       if (a.rms) {
