@@ -279,6 +279,36 @@ def test_gemm_launch_shapes_give_the_same_bits(ss, side_stream, name, batch):
             assert np.array_equal(bits(a) if a.dtype != np.int32 else a, bits(b) if b.dtype != np.int32 else b)
 
 
+@pytest.mark.parametrize("name,dtype,batch", [("llama30b_m2", "bf16", 5), ("llama30b_m2", "f32", 2), ("opt66b_m8", "bf16", 19)])
+def test_exact_ties_go_to_the_lowest_index(ss, name, dtype, batch):
+    """Greedy choice with exact ties: every row of the LM head is the same vector, so all logits of a
+    batch row are bit-identical whichever block computes them, and the token must be 0 in the
+    initial phase and in every step (the choice among the blocks' candidates must not depend on
+    the order they are looked at)."""
+    import torch
+    w = scaled(name, dtype, layers=2, batch=batch, s_in=12, steps=3, d_model=256, ffn=512, head_dim=64, n_heads=4, vocab=3001)
+    W = dict(make_weights(w.desc, w.slice, w.seed))
+    lm = W["lm_head"].copy()
+    lm[:] = lm[7]
+    W["lm_head"] = lm
+    if w.desc.get("tied_lm_head", False):
+        W["wte"] = lm
+    toks = make_tokens(w.seed, w.batch, w.s_in, w.desc["vocab"])
+    sh = ss.Shard(w.desc, w.slice, W, w.batch, w.s_max)
+    V = w.desc["vocab"]
+    logits = torch.empty(w.batch, V, dtype=torch.float32, device="cuda")
+    nxt = torch.full((w.batch,), -1, dtype=torch.int32, device="cuda")
+    ss.prefill([sh], dev(toks), logits, nxt)
+    for step in range(w.steps + 1):
+        torch.cuda.synchronize()
+        lg = logits.cpu().numpy()
+        assert np.all(bits(lg) == bits(lg)[:, :1]), "logits of one row differ although every LM head row is the same"
+        assert np.array_equal(nxt.cpu().numpy(), np.zeros(w.batch, dtype=np.int32))
+        if step < w.steps:
+            ss.decode_step([sh], nxt, logits, nxt)
+    sh.destroy()
+
+
 @pytest.mark.parametrize("name,dtype,batch,s_in", [("gpt20b_m4", "bf16", 3, 111), ("llama30b_m2", "bf16", 5, 77), ("tiny_gpt", "f32", 2, 150)])
 def test_prefill_token_blocks_give_the_same_bits(ss, side_stream, name, dtype, batch, s_in):
     """The initial phase's GEMMs run with 128- or 256-token blocks (chosen by output size): both
