@@ -52,20 +52,6 @@ ss_status launch_decode_attn(int dtype, const DecodeAttnArgs &a, hipStream_t st)
 // DH/8 threads per (token, head), each with four dims of both halves of the head (a rotation
 // pairs dim e with e + DH/2); 256 threads per block.
 // ---------------------------------------------------------------------------
-template <typename T>
-__device__ __forceinline__ void store4_cache(T *dst, const f32x4 &v) {
-  T t[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) t[i] = Elem<T>::from_f32(v[i]);
-  if constexpr (sizeof(T) == 2) {
-    uint2 raw;
-    __builtin_memcpy(&raw, t, 8);
-    *(uint2 *)dst = raw;
-  } else {
-    *(f32x4 *)dst = v;
-  }
-}
-
 template <typename T, int DH>
 __global__ void __launch_bounds__(256) prefill_kv_write(PrefillAttnArgs a) {
   constexpr int HALF = DH / 2, TPP = HALF / 4, PPB = 256 / TPP;

@@ -159,6 +159,21 @@ __device__ __forceinline__ bool arrive_last(int *counter, int expected, int *s_f
 }
 #endif
 
+// four consecutive cache elements (one 8- or 16-byte store) from four floats
+template <typename T>
+__device__ __forceinline__ void store4_cache(T *dst, const f32x4 &v) {
+  T t[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) t[i] = Elem<T>::from_f32(v[i]);
+  if constexpr (sizeof(T) == 2) {
+    uint2 raw;
+    __builtin_memcpy(&raw, t, 8);
+    *(uint2 *)dst = raw;
+  } else {
+    *(f32x4 *)dst = v;
+  }
+}
+
 // store a float activation into an operand buffer
 template <typename T>
 __device__ inline void store_act(void *base, int row, int k, int k_blocks, float v) {

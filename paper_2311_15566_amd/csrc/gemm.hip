@@ -183,7 +183,19 @@ __global__ void __launch_bounds__(256, NJ == 8 ? 2 : 3) tile_gemm(TileGemmArgs a
           float v[4];
           finish(acc[i][j], n0, mr, v);
           if (EPI == EPI_F32) {
-            *(f32x4 *)(a.out_f32 + (size_t)tok * a.ld_out + n0) = f32x4{v[0], v[1], v[2], v[3]};
+            const f32x4 o = {v[0], v[1], v[2], v[3]};
+            const int HD = a.kv_Hs * a.kv_Dh;
+            if (a.k_cache && n0 >= HD) {  // a key or value piece: into the cache row of (sequence, position), not the q|k|v buffer
+              const int is_v = n0 >= 2 * HD, f = n0 - (1 + is_v) * HD, hh = f / a.kv_Dh, dim = f - hh * a.kv_Dh;
+              const int b = tok / a.kv_S, pos = tok - b * a.kv_S;
+              char *row = (is_v ? a.v_cache : a.k_cache) + b * a.kv_row_stride + hh * a.kv_head_stride;
+              const size_t e = (size_t)pos * a.kv_Dh + dim;
+              if (a.kv_dtype == SS_DTYPE_F16) store4_cache<f16_t>((f16_t *)row + e, o);
+              else if (a.kv_dtype == SS_DTYPE_BF16) store4_cache<bf16_t>((bf16_t *)row + e, o);
+              else store4_cache<float>((float *)row + e, o);
+            } else {
+              *(f32x4 *)(a.out_f32 + (size_t)tok * a.ld_out + n0) = o;
+            }
           } else {  // EPI_ACT
             const float w[4] = {act_apply(a.act_kind, v[0]), act_apply(a.act_kind, v[1]), act_apply(a.act_kind, v[2]),
                                 act_apply(a.act_kind, v[3])};
@@ -249,6 +261,9 @@ ss_status launch_tile_gemm(int dtype, int epi, TileGemmArgs a, hipStream_t st) {
   if (a.T < 256 || a.T % 256) SS_FAIL(SS_EINVAL, "prefill GEMM: token count %d is not a multiple of 256", a.T);
   if (a.row_tiles < 1 || a.k_blocks < 1 || a.N % 4) SS_FAIL(SS_EINVAL, "prefill GEMM: bad shape");
   if ((epi == EPI_F32 && (a.ld_out % 4)) || epi == EPI_LOGITS) SS_FAIL(SS_EINVAL, "prefill GEMM: bad epilogue");
+  if (a.k_cache && (epi != EPI_F32 || !a.v_cache || a.kv_S < 1 || a.kv_Dh % 4 || a.N != 3 * a.kv_Hs * a.kv_Dh ||
+                    (a.kv_dtype != SS_DTYPE_F16 && a.kv_dtype != SS_DTYPE_BF16 && a.kv_dtype != SS_DTYPE_F32)))
+    SS_FAIL(SS_EINVAL, "prefill GEMM: bad cache arguments");
   if (epi == EPI_RESID && a.g_out) {
     const int fk = dtype == SS_DTYPE_BF16 ? 32 : 16;
     if (!a.norm_out || !a.stat_out || !a.c_in || a.N % fk || a.N != a.row_tiles * 16)

@@ -98,6 +98,11 @@ struct TileGemmArgs {
   const float *cb;    // [row_tiles * 16] folded beta and bias, or the plain bias, or NULL
   float *out_f32;     // EPI_F32: [T][ld_out]
   int ld_out;
+  // EPI_F32 of a fused q|k|v matrix without rotary positions (k_cache != NULL): the k and v columns go straight
+  // into the cache rows of token t = b * kv_S + pos, rounded as the cache stores them; only q goes to out_f32
+  char *k_cache, *v_cache;  // this layer's planes
+  size_t kv_row_stride, kv_head_stride;  // bytes
+  int kv_S, kv_Hs, kv_Dh, kv_dtype;
   float *x_resid;     // EPI_RESID: [T][N]
   const float *g_out; // EPI_RESID: gamma of the norm that follows, or NULL: no operand for a next GEMM
   void *norm_out;     // EPI_RESID with g_out: (x - c) * g_out as fragments [T/16][N / FragK]
