@@ -256,7 +256,8 @@ __global__ void __launch_bounds__(256) prefill_attn_mfma(PrefillAttnArgs a) {
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
       const int p = tid + 256 * i;
-      const int key = p / (DH / 8), pc = p % (DH / 8);
+      // a wave takes one whole LDS fragment (16 keys x 4 pieces): lane l holds key l & 15, piece l >> 4 of it
+      const int key = (p >> 6) / KC * 16 + (p & 15), pc = (p >> 6) % KC * 4 + ((p >> 4) & 3);
       const int kr = min(t * TK + key, a.S - 1);  // clamped: masked below
       kreg[i] = *((const u32x4 *)(kbase + (size_t)kr * DH * sizeof(f16_t)) + pc);
       const int dim = p >> 2, kp = p & 3;         // 8 keys of one dim (inside s_pad, zeros past S)
@@ -267,8 +268,7 @@ __global__ void __launch_bounds__(256) prefill_attn_mfma(PrefillAttnArgs a) {
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
       const int p = tid + 256 * i;
-      const int key = p / (DH / 8), pc = p % (DH / 8);
-      lds_k[buf][key >> 4][pc >> 2][(pc & 3) * 16 + (key & 15)] = kreg[i];
+      lds_k[buf][(p >> 6) / KC][(p >> 6) % KC][p & 63] = kreg[i];  // consecutive lanes, consecutive 16 bytes: no bank conflicts
       const int dim = p >> 2, kp = p & 3;
       uint2 *dst = &lds_v[buf][kp >> 1][dim >> 4][((kp & 1) * 2) * 16 + (dim & 15)];
       dst[0] = make_uint2(vreg[i][0], vreg[i][1]);    // keys 8*(kp&1) .. + 3 of the subtile
