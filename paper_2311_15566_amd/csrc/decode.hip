@@ -209,6 +209,9 @@ static TuneVal tune_rule(int epi, int row_tiles, int B) {
   TuneVal v;
   v.bt_split = (B > 16 && pairs * 2 <= 256) ? 2 : 1;
   v.nw = (epi == EPI_SWIGLU || epi == EPI_LOGITS || pairs * v.bt_split >= 128) ? 2 : 1;
+  // a few more tile pairs than the 256 compute units: the blocks of a second, mostly empty round would each
+  // run at what one compute unit takes in; three tiles a block keep it to one round
+  if ((epi == EPI_F32 || epi == EPI_ACT) && v.bt_split == 1 && pairs > 256 && ceil_div(row_tiles, 3) <= 256) v.nw = 3;
   return v;
 }
 static void shape_gemm(StreamGemmArgs &a, int dtype, int epi) {
@@ -221,6 +224,7 @@ static void shape_gemm(StreamGemmArgs &a, int dtype, int epi) {
     if (g_forced.bt_split) v.bt_split = a.B > 16 ? g_forced.bt_split : 1;
   }
   a.nw = v.nw, a.bt_split = v.bt_split;
+  if (a.nw == 3 && a.ks != 8) a.nw = 2;  // three tiles need six epilogue waves
   a.n_blocks = stream_gemm_blocks(epi, a);
 }
 static int pick_ks(int k_blocks) { return k_blocks >= 16 ? 8 : 4; }  // waves per block
@@ -476,7 +480,7 @@ static ss_status tune_decode_gemms(Shard *const *group, int n_group, int B, hipS
         const Phase *ph = phs[turn++ % phs.size()];
         const Shard *owner = group[ph->shard];
         StreamGemmArgs g = ph->g;
-        g.nw = c.nw, g.bt_split = c.bt_split;
+        g.nw = (c.nw == 3 && g.ks != 8) ? 2 : c.nw, g.bt_split = c.bt_split;
         g.n_blocks = stream_gemm_blocks(key.epi, g);
         if (key.epi == EPI_RESID) g.x_out = (float *)(owner->ws + owner->L.ws_x);  // leave the residual stream alone
         if (key.epi == EPI_LOGITS) g.out_f32 = nullptr, g.next_tokens = nullptr, g.n_lens = 0;

@@ -303,7 +303,8 @@ ss_status check_stream_gemm(int dtype, int epi, const StreamGemmArgs &a) {
   if (a.B < 1 || a.B > 32) SS_FAIL(SS_EINVAL, "decode GEMM: batch %d", a.B);
   if (a.n_blocks != stream_gemm_blocks(epi, a) || (a.bt_split != 1 && !(a.bt_split == 2 && a.B > 16)))
     SS_FAIL(SS_EINVAL, "decode GEMM: bad block count / batch split");
-  if (a.nw != 1 && a.nw != 2) SS_FAIL(SS_EINVAL, "decode GEMM: %d weight tiles per block", a.nw);
+  if (a.nw != 1 && a.nw != 2 && !(a.nw == 3 && (epi == EPI_F32 || epi == EPI_ACT) && a.ks == 8))
+    SS_FAIL(SS_EINVAL, "decode GEMM: %d weight tiles per block", a.nw);
   if (a.row_tiles < 1 || a.k_blocks < 1 || (a.ks != 4 && a.ks != 8) || a.N < 1 || a.N > a.row_tiles * 16)
     SS_FAIL(SS_EINVAL, "decode GEMM: bad shape (tiles %d, k blocks %d, waves %d, N %d)", a.row_tiles, a.k_blocks, a.ks, a.N);
   if (!a.w || !a.act) SS_FAIL(SS_EINVAL, "decode GEMM: NULL operand");
@@ -340,7 +341,10 @@ template <typename T, int NB, int KSM>
 static void launch_stream_gemm_t(int epi, const StreamGemmArgs &a, dim3 grid, dim3 block, hipStream_t st) {
 #define SS_LAUNCH(GLU, EPI, NW) SS_LAUNCH_KERNEL((stream_gemm<T, NB, GLU, EPI, KSM, NW>), grid, block, 0, st, a)
   if (epi == EPI_SWIGLU) SS_LAUNCH(true, EPI_SWIGLU, 2);
-  else if (a.nw == 1) {
+  else if (a.nw == 3) {  // q|k|v and first-FFN matrices with more tile pairs than compute units
+    if (epi == EPI_F32) SS_LAUNCH(false, EPI_F32, 3);
+    else SS_LAUNCH(false, EPI_ACT, 3);
+  } else if (a.nw == 1) {
     if (epi == EPI_F32) SS_LAUNCH(false, EPI_F32, 1);
     else if (epi == EPI_ACT) SS_LAUNCH(false, EPI_ACT, 1);
     else if (epi == EPI_RESID) SS_LAUNCH(false, EPI_RESID, 1);

@@ -104,7 +104,8 @@ def check(w):
             rng("am_idx", g.am_idx, 32 * g.n_blocks * 4, regions)
         else:
             g = p.g
-            assert g.ks in (4, 8) and g.B == w.batch and p.gy == 1 and g.nw in (1, 2) and g.n_blocks == -(-g.row_tiles // g.nw)
+            assert g.ks in (4, 8) and g.B == w.batch and p.gy == 1 and g.nw in (1, 2, 3) and g.n_blocks == -(-g.row_tiles // g.nw)
+            assert g.nw < 3 or (p.kind in (QKV, FFN_UP) and not glu or p.kind == QKV) and g.ks == 8
             assert (g.bt_split == 1 or (g.bt_split == 2 and g.B > 16)) and p.gx == g.n_blocks * g.bt_split
             assert 1 <= g.N <= g.row_tiles * 16
             rng("w", g.w, g.row_tiles * g.k_blocks * 1024, regions)
