@@ -47,6 +47,17 @@ __device__ __forceinline__ float rope_elem(const float *v, int e, int half, cons
   float2 cs = tab[e - half];
   return v[e - half] * cs.y + v[e] * cs.x;
 }
+// the same where the vector arrives as two partial sums (v2 != NULL): v + v2, element by element
+__device__ __forceinline__ float rope_elem2(const float *v, const float *v2, int e, int half, const float2 *tab) {
+  if (!v2) return rope_elem(v, e, half, tab);
+  if (!tab) return v[e] + v2[e];
+  if (e < half) {
+    float2 cs = tab[e];
+    return (v[e] + v2[e]) * cs.x - (v[e + half] + v2[e + half]) * cs.y;
+  }
+  float2 cs = tab[e - half];
+  return (v[e - half] + v2[e - half]) * cs.y + (v[e] + v2[e]) * cs.x;
+}
 
 // ---------------------------------------------------------------------------
 // decode attention.  grid = (B*Hs, splits); block = NWV waves.
@@ -85,6 +96,7 @@ __device__ __forceinline__ void decode_attn_block(const DecodeAttnArgs &a, const
   const float scale = rsqrtf((float)DH);
   const float2 *tab = a.rope ? a.rope + (size_t)n * (DH / 2) : nullptr;
   const float *qraw = a.qkv + (size_t)b * 3 * HD + h * DH;
+  const float *qraw2 = a.qkv2 ? a.qkv2 + (size_t)b * 3 * HD + h * DH : nullptr;
   const int c = lane % LPR, g = lane / LPR;
   const int r0 = sp * a.rows_per_block;
   const int r1 = min(r0 + a.rows_per_block, n);
@@ -149,9 +161,9 @@ __device__ __forceinline__ void decode_attn_block(const DecodeAttnArgs &a, const
     load(kB, vB, base + STRIDE);
     float kn = 0.f, vraw = 0.f;  // the new token's (rotated) key and value element of thread e
     if (tid < DH) {
-      kn = rope_elem(qraw + HD, tid, DH / 2, tab);
-      vraw = qraw[2 * HD + tid];
-      sq[tid] = rope_elem(qraw, tid, DH / 2, tab);
+      kn = rope_elem2(qraw + HD, qraw2 ? qraw2 + HD : nullptr, tid, DH / 2, tab);
+      vraw = qraw[2 * HD + tid] + (qraw2 ? qraw2[2 * HD + tid] : 0.f);
+      sq[tid] = rope_elem2(qraw, qraw2, tid, DH / 2, tab);
     }
     __syncthreads();
 #pragma unroll

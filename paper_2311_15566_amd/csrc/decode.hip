@@ -225,6 +225,17 @@ static void shape_gemm(StreamGemmArgs &a, int dtype, int epi) {
   }
   a.nw = v.nw, a.bt_split = v.bt_split;
   if (a.nw == 3 && a.ks != 8) a.nw = 2;  // three tiles need six epilogue waves
+  // A q|k|v matrix with fewer tile pairs than compute units (every block bound by what one unit takes
+  // in): K in two halves, three tiles a block, so that more units share the bytes more evenly; the two
+  // partial sums are added by the attention kernel.  Not with a forced shape (a test aid).
+  a.k_split = 1, a.part_stride = 0;
+  {
+    const int pairs = ceil_div(a.row_tiles, 2);
+    const bool forced = g_forced.nw || g_forced.bt_split;
+    if (epi == EPI_F32 && a.split_ok && !forced && a.B <= 16 && a.bt_split == 1 && a.ks == 8 && a.k_blocks >= 64 && pairs >= 100 &&
+        pairs < 256 && ceil_div(a.row_tiles, 3) * 2 <= 256)
+      a.nw = 3, a.k_split = 2, a.part_stride = (size_t)32 * a.ld_out;
+  }
   a.n_blocks = stream_gemm_blocks(epi, a);
 }
 static int pick_ks(int k_blocks) { return k_blocks >= 16 ? 8 : 4; }  // waves per block
@@ -306,6 +317,7 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
     ph.gx = a.n_blocks * a.bt_split, ph.gy = 1;
     plan->push_back(ph);
   };
+  size_t qkv_split[8] = {0};  // per shard of the group: distance (floats) to the second partial q|k|v, 0 = one sum
   for (int l = 0; l < L0.Ls; ++l) {
     const LayerDev &D0 = g0->layers[l];
     for (int i = 0; i < n_group; ++i) {  // QKV projection of the new token
@@ -318,8 +330,10 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
       a.ks = pick_ks(a.k_blocks);
       normed(a, s->wg_qkv[l], s->cb_qkv[l], i);
       a.out_f32 = (float *)(s->ws + L.ws_qkvd), a.ld_out = L.qkv_n;
+      a.split_ok = 1;  // the consumer (decode attention) can add two partial sums
       shape_gemm(a, dt, EPI_F32);
-      ph.gx = a.n_blocks * a.bt_split, ph.gy = 1;
+      ph.gx = a.n_blocks * a.bt_split * a.k_split, ph.gy = 1;
+      qkv_split[i] = a.k_split == 2 ? a.part_stride : 0;
       plan->push_back(ph);
     }
     for (int i = 0; i < n_group; ++i) {  // attention over the committed rows + append
@@ -329,6 +343,7 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
       ph.kind = PH_ATTN, ph.shard = i;
       DecodeAttnArgs &a = ph.at;
       a.qkv = (const float *)(s->ws + L.ws_qkvd);
+      a.qkv2 = qkv_split[i] ? a.qkv + qkv_split[i] : nullptr;
       a.k_cache = s->kv_ptr(l, 0), a.v_cache = s->kv_ptr(l, 1);
       a.row_stride = s->kv_row_stride(), a.head_stride = s->kv_head_stride();
       a.lens = s->d_len, a.rope = m.pos == SS_POS_ROPE ? s->rope : nullptr;

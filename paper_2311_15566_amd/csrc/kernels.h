@@ -53,6 +53,9 @@ struct StreamGemmArgs {
   // epilogues
   float *out_f32;       // EPI_F32 / EPI_LOGITS: [B][ld_out]
   int ld_out;
+  int k_split;          // EPI_F32: 2 = two blocks per tile group over half of K each, partial outputs at out_f32 and
+  size_t part_stride;   //   out_f32 + part_stride (floats) for the consumer to add up; 0 or 1 = whole K per block
+  int split_ok;         //   set by the plan where the consumer can add two partial sums (the launch rule may then split)
   const float *x_in;    // EPI_RESID: residual stream before this GEMM, [B][N]
   float *x_out;         // EPI_RESID: after it (may equal x_in)
   void *act_out;        // EPI_ACT / EPI_SWIGLU: activation fragments; EPI_RESID: (x_out - c) * g_out (or NULL)
@@ -123,6 +126,7 @@ ss_status launch_row_stats(const float2 *part, int groups, int T, int norm_dim, 
 // Decode attention over the committed cache (plus the new token), sequence-split.
 struct DecodeAttnArgs {
   const float *qkv;     // [B][3*Hs*Dh] float32: q | k | v of the new token, biases applied
+  const float *qkv2;    // a second partial sum of the same shape to add to qkv (the GEMM split K over two blocks), or NULL
   char *k_cache, *v_cache;   // this layer's planes: [Bmax][Hs][Smax][Dh]
   size_t row_stride, head_stride;  // bytes
   const int32_t *lens;  // committed lengths (device)

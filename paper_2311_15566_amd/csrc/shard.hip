@@ -137,7 +137,7 @@ bool compute_layout(const ss_model_desc &m, const ss_slice &s, int max_batch, in
     L->ws_ad = wtake((size_t)2 * (d / fk) * 1024);
     L->ws_statd = wtake((size_t)(d / 32) * 32 * 4 * 4);
     L->ws_cen = wtake((size_t)32 * 4);
-    L->ws_qkvd = wtake((size_t)32 * L->qkv_n * 4);
+    L->ws_qkvd = wtake((size_t)2 * 32 * L->qkv_n * 4);  // two partial sums when the GEMM splits K over blocks
     L->ws_od = wtake((size_t)2 * (HD / fk) * 1024);
     L->ws_ud = wtake((size_t)2 * (L->Fs / fk) * 1024);
   }

@@ -47,10 +47,17 @@ __global__ void __launch_bounds__(KSM * 64, 2) stream_gemm(StreamGemmArgs a) {
       blk = (a.n_blocks / 8) * 8 + (pid - nfull) / 2, bt = (pid - nfull) % 2;
     }
   }
+  // EPI_F32 with a.k_split == 2: two blocks per tile group, each over half of K; they leave two
+  // partial outputs (out_f32 and out_f32 + part_stride) that the consumer adds up, so neither
+  // waits for the other.  The second half contributes acc * rstd only (no mean, no bias).
+  int kh = 0;
+  if (EPI == EPI_F32 && a.k_split == 2) kh = blk & 1, blk >>= 1;
   const int row0 = bt * 16;       // first batch row of this block
   const int tile0 = blk * NW;
-  const int per = (a.k_blocks + KS - 1) / KS;
-  const int k0 = ks * per, k1 = min(a.k_blocks, k0 + per);
+  const int k_half = (EPI == EPI_F32 && a.k_split == 2) ? (a.k_blocks + 1) / 2 : a.k_blocks;
+  const int k_lo = kh * k_half, k_hi = min(a.k_blocks, k_lo + k_half);
+  const int per = (k_hi - k_lo + KS - 1) / KS;
+  const int k0 = k_lo + ks * per, k1 = min(k_hi, k0 + per);
   const int r = lane & 15, q4 = (lane >> 4) * 4;
 
   bool tile_ok[NW];
@@ -79,11 +86,11 @@ __global__ void __launch_bounds__(KSM * 64, 2) stream_gemm(StreamGemmArgs a) {
   const bool epi_live = is_epi && tile_e_ok && b < a.B && n0 < a.N;
   f32x4 e_wg[NWE], e_cb[NWE], e_x = {0.f, 0.f, 0.f, 0.f}, e_g = {1.f, 1.f, 1.f, 1.f};
   float e_cen = 0.f;  // EPI_RESID: the centre of the operand it writes; a publishing consumer: the centre of the one it reads
-  if (is_epi && a.cen && b < a.B && (EPI == EPI_RESID || (a.publish && blk == 0))) e_cen = a.cen[b];
+  if (is_epi && a.cen && b < a.B && (EPI == EPI_RESID || (a.publish && blk == 0 && kh == 0))) e_cen = a.cen[b];
 #pragma unroll
   for (int jj = 0; jj < NWE; ++jj) {
     e_wg[jj] = e_cb[jj] = f32x4{0.f, 0.f, 0.f, 0.f};
-    if (epi_live) {
+    if (epi_live && kh == 0) {
       if (a.wg) e_wg[jj] = *(const f32x4 *)(a.wg + wrow + jj * 16);
       if (a.cb) e_cb[jj] = *(const f32x4 *)(a.cb + wrow + jj * 16);
     }
@@ -214,7 +221,7 @@ __global__ void __launch_bounds__(KSM * 64, 2) stream_gemm(StreamGemmArgs a) {
         mean = u1 * inv;
         rstd = rsqrtf(fmaxf(ms - mean * mean, 0.f) + a.eps);
         // the next producer centres on this norm's mean (one lane per row, first block, first tile)
-        if (a.publish && a.cen && blk == 0 && je == 0 && lane < 16 && b < a.B) a.cen[b] = e_cen + mean;
+        if (a.publish && a.cen && blk == 0 && kh == 0 && je == 0 && lane < 16 && b < a.B) a.cen[b] = e_cen + mean;
       }
     }
     float h[NWE][4];  // the product with normalisation and bias applied
@@ -227,7 +234,7 @@ __global__ void __launch_bounds__(KSM * 64, 2) stream_gemm(StreamGemmArgs a) {
       if (epi_live) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-          if (n0 + i < a.N) a.out_f32[(size_t)b * a.ld_out + n0 + i] = h[0][i];
+          if (n0 + i < a.N) a.out_f32[(size_t)kh * a.part_stride + (size_t)b * a.ld_out + n0 + i] = h[0][i];
       }
     } else if (EPI == EPI_ACT || EPI == EPI_SWIGLU) {
       if (epi_live) {
@@ -308,6 +315,9 @@ ss_status check_stream_gemm(int dtype, int epi, const StreamGemmArgs &a) {
   if (a.row_tiles < 1 || a.k_blocks < 1 || (a.ks != 4 && a.ks != 8) || a.N < 1 || a.N > a.row_tiles * 16)
     SS_FAIL(SS_EINVAL, "decode GEMM: bad shape (tiles %d, k blocks %d, waves %d, N %d)", a.row_tiles, a.k_blocks, a.ks, a.N);
   if (!a.w || !a.act) SS_FAIL(SS_EINVAL, "decode GEMM: NULL operand");
+  if (a.k_split != 0 && a.k_split != 1 &&
+      !(a.k_split == 2 && epi == EPI_F32 && a.bt_split == 1 && a.k_blocks >= 2 * a.ks && a.part_stride >= (size_t)a.B * a.ld_out))
+    SS_FAIL(SS_EINVAL, "decode GEMM: bad split of K over blocks");
   if (epi == EPI_RESID && a.row_tiles % 2) SS_FAIL(SS_EINVAL, "decode GEMM: residual output needs whole tile pairs");
   if (a.stat_groups < 0 || (a.stat_groups > 0 && (!a.stat_in || a.norm_dim < 1 || (!a.rms && !a.wg))))
     SS_FAIL(SS_EINVAL, "decode GEMM: incomplete normalisation arguments");
@@ -360,7 +370,7 @@ static void launch_stream_gemm_t(int epi, const StreamGemmArgs &a, dim3 grid, di
 
 ss_status launch_stream_gemm(int dtype, int epi, const StreamGemmArgs &a, hipStream_t st) {
   SS_TRY(check_stream_gemm(dtype, epi, a));
-  const dim3 grid(stream_gemm_blocks(epi, a) * a.bt_split), block(a.ks * 64);
+  const dim3 grid(stream_gemm_blocks(epi, a) * a.bt_split * (a.k_split == 2 ? 2 : 1)), block(a.ks * 64);
   const int nb = (a.B <= 16 || a.bt_split == 2) ? 1 : 2;
   if (dtype == SS_DTYPE_BF16) {
     if (nb == 1) launch_stream_gemm_t<bf16_t, 1, 8>(epi, a, grid, block, st);
