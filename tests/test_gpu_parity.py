@@ -156,6 +156,10 @@ CASES = [
     # fragments long (shorter than the prefill GEMM's LDS ring and than the decode GEMM's wave count)
     ("gpt20b_m4", "bf16", dict(d_model=64, n_heads=2, head_dim=64, ffn=128, vocab=777, batch=2, s_in=9, steps=3)),
     ("llama30b_m2", "bf16", dict(d_model=64, n_heads=2, head_dim=64, ffn=128, vocab=777, batch=2, s_in=9, steps=3)),
+    # q|k|v matrices wide enough for the two launch shapes that only the full-size shards reach otherwise:
+    # 108 tile pairs (K split over two blocks, partial sums added by the attention kernel) and 264 (three tiles a block)
+    ("gpt20b_m4", "bf16", dict(d_model=2048, n_heads=18, head_dim=128, ffn=1024, vocab=1511, layers=2, batch=5, s_in=21, steps=3)),
+    ("llama30b_m2", "bf16", dict(d_model=2048, n_heads=44, head_dim=128, ffn=1024, vocab=1511, layers=2, batch=9, s_in=21, steps=3)),
 ]
 
 
