@@ -4,12 +4,18 @@
 A step is one incremental decoding iteration of the whole batch through the shard (embedding,
 every layer's QKV / attention + KV append / out-projection / FFN, LM head, greedy argmax,
 token-level commit).  The timed region is exactly --steps iterations after a fresh initial
-phase, replayed as a HIP graph, with every input already resident in HBM.  The initial phase
-and the KV re-partition are measured in the same run and reported beside it.
+phase, replayed as a HIP graph, with every input already resident in HBM.
+
+The headline (`value`, `roofline`, `cpu_baseline`) is the largest single-GPU configuration, the
+LLaMA-30B-shaped shard; the GPT-20B- and OPT-66B-shaped shards run the same protocol in the
+same process and are reported under `configs`, and the KV re-partition of the
+reparallelize-and-resume configuration (1000 committed tokens, M=2 -> two M'=4 layouts) under
+`repack`.  The initial phase is measured in the same run and reported beside each.
 
 Prints ONE JSON line (see the design doc for the byte counts behind `roofline`).
 """
 import argparse
+import gc
 import json
 import os
 import sys
@@ -23,6 +29,15 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+HEADLINE = "llama30b_m2"
+OTHERS = ["gpt20b_m4", "opt66b_m8"]
+KERNEL_OF_CLASS = {
+    "qkv_gemm": ("stream_gemm_qkv", "stream_gemm<EPI_F32> (fused q|k|v projection)"),
+    "decode_attn": ("decode_attn", "decode_attn (attention over the committed cache + append)"),
+    "resid_gemm": ("stream_gemm_resid", "stream_gemm<EPI_RESID> (out-projection and second FFN matrix, residual epilogue)"),
+    "ffn_up_gemm": ("stream_gemm_ffn_up", "stream_gemm<EPI_ACT / EPI_SWIGLU> (first FFN matrix + activation)"),
+    "lm_head": ("stream_gemm_logits", "stream_gemm<EPI_LOGITS> (LM head + per-block greedy candidates)"),
+}
 
 
 def log(*a):
@@ -63,29 +78,51 @@ def prefill_flops(w):
     return T * per_tok + attn + 2 * w.batch * g["V"] * g["d"]
 
 
-def cpu_baseline(w, W, n_ctx, steps=32):
-    """The oracle as it stands, timed on this machine's host cores: full batch, `steps` decode
-    iterations at context n_ctx (cache rows filled with noise; timing does not depend on values)."""
+def host_cpu():
+    model = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count() or 1
+    return model, os.cpu_count() or 1, usable
+
+
+def cpu_baseline(w, W, n_ctx, budget_s=12.0):
+    """The oracle as it stands, timed on this machine's host cores: full batch, decode iterations at
+    context n_ctx (cache rows filled with noise; timing does not depend on values) until about
+    budget_s seconds have gone by."""
     from oracle import decoder as D
     t0 = time.perf_counter()
-    ora = D.OracleShard(w.desc, w.slice, W, w.batch, n_ctx + steps + 2, real=np.float32)
+    max_steps = 64
+    ora = D.OracleShard(w.desc, w.slice, W, w.batch, n_ctx + max_steps + 2, real=np.float32)
     rng = np.random.default_rng(1)
     ora.kv[:, :, :, :, :n_ctx] = rng.standard_normal(size=ora.kv[:, :, :, :, :n_ctx].shape, dtype=np.float32) * 0.5
     ora.n[:] = n_ctx
     toks = rng.integers(0, w.desc["vocab"], size=w.batch)
     setup = time.perf_counter() - t0
     D.decode_step([ora], toks)                                # untimed first touch
+    steps = 0
     t0 = time.perf_counter()
-    for _ in range(steps):
+    while steps < max_steps - 1 and (steps < 2 or time.perf_counter() - t0 < budget_s):
         toks = D.greedy(D.decode_step([ora], toks))
+        steps += 1
     dt = time.perf_counter() - t0
     try:
         from threadpoolctl import threadpool_info
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count() or 1
-    return dict(value=w.batch * steps / dt, unit="tokens/s", cores=int(threads), kind="oracle",
-                sample=f"full batch of {w.batch}, {steps} decode steps at context {n_ctx} (of {w.s_in}..{w.s_in + w.steps}), "
+    model, nproc, usable = host_cpu()
+    return dict(value=w.batch * steps / dt, unit="tokens/s", cores=int(threads), kind="oracle", nproc=nproc,
+                usable_cpus=usable, cpu_model=model,
+                sample=f"{w.name}: full batch of {w.batch}, {steps} decode steps at context {n_ctx} (of {w.s_in}..{w.s_in + w.steps}), "
                        f"float32 numpy oracle, {dt:.1f} s timed (+{setup:.0f} s set-up)")
 
 
@@ -103,53 +140,22 @@ def measured_traffic(workload_name, kernel_key):
     return None
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=128)
-    ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="gpt20b_m4", choices=["gpt20b_m4", "llama30b_m2", "opt66b_m8", "tiny_gpt"])
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-extras", action="store_true", help="skip the kernel-class, prefill and repack legs")
-    ap.add_argument("--eager", action="store_true", help="launch kernel by kernel instead of replaying a graph")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="only copy 1 GiB device to device three times (a kernel of known traffic, for scaling "
-                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs one tensor-parallel shard on ONE GPU; collectives and sharding "
-                 "across GPUs are not part of it (run with --gpus 1)")
-
-    import torch
-    import paper_2311_15566_amd as ss
+def run_workload(ss, torch, name, K, Wm, eager=False, extras=True, repack5=False, reslice=False, keep_weights=False):
+    """Initial phase + K timed decode steps of one workload; returns (summary dict, (workload, host weights) or None)."""
     from synth import make_tokens, make_weights, sub_slice_of, workload
-
-    assert torch.cuda.is_available(), "bench.py needs an MI355X"
-    torch.cuda.set_device(0)
-    if args.calibrate_copy:
-        src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        print(json.dumps(dict(copy_bytes=1 << 30, copies=3)), flush=True)
-        return
-    w = workload(args.workload)
-    K, Wm = args.steps, args.warmup
-    if K > w.s_max - w.s_in:
-        sys.exit(f"--steps {K} exceeds the workload's {w.s_max - w.s_in} decode steps")
+    w = workload(name)
+    K = min(K, w.s_max - w.s_in)
     t0 = time.perf_counter()
     W = make_weights(w.desc, w.slice, w.seed)
     toks = make_tokens(w.seed, w.batch, w.s_in, w.desc["vocab"])
     log(f"[bench] {w.name}: weights drawn in {time.perf_counter() - t0:.1f} s")
-
+    out = {}
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
         t0 = time.perf_counter()
         sh = ss.Shard(w.desc, w.slice, W, w.batch, w.s_max)
-        log(f"[bench] shard created ({sh.mem.numel() / 1e9:.2f} GB on device) in {time.perf_counter() - t0:.1f} s")
-        sh.set_graph_launch(not args.eager)
+        log(f"[bench] {w.name}: shard created ({sh.mem.numel() / 1e9:.2f} GB on device) in {time.perf_counter() - t0:.1f} s")
+        sh.set_graph_launch(not eager)
         V = w.desc["vocab"]
         d_toks = torch.from_numpy(toks).cuda()
         logits = torch.empty(w.batch, V, dtype=torch.float32, device="cuda")
@@ -174,7 +180,7 @@ def main():
 
         # ---- the timed region: exactly K decode steps ----
         # (an event every `chunk` steps, for the cost model below: a marker in the stream, no wait)
-        chunk = max(8, K // 8)
+        chunk = max(1, K // 8)
         marks = [torch.cuda.Event(enable_timing=True) for _ in range(K // chunk + 1)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -190,18 +196,17 @@ def main():
 
         n_list = [w.s_in + i for i in range(K)]
         step_bytes, class_bytes, attn_bytes, weight_bytes = algorithmic_bytes(w, n_list)
-        out = dict(metric="decode tokens/s per TP shard on 1 GPU", value=w.batch * K / dt, unit="tokens/s", n_gpus=1,
-                   steps=K, warmup=Wm, ms_per_step=dt / K * 1e3, higher_is_better=True, scaling="weak",
-                   vs_baseline=None, dtype={"bf16": "f16", "f32": "f32"}[w.desc["dtype"]], data="synthetic",
-                   config=dict(workload=f"{w.name}: {shard_dims(w)['Ls']} layers, d={w.desc['d_model']}, "
-                                        f"{shard_dims(w)['Hs']} heads x {w.desc['head_dim']}, FFN {shard_dims(w)['Fs']}, "
-                                        f"vocab {V}, batch {w.batch}, prompt {w.s_in}, {K} decode steps",
-                               batch=w.batch, prompt=w.s_in, launch="eager" if args.eager else "hip-graph"))
+        g = shard_dims(w)
+        out.update(value=w.batch * K / dt, ms_per_step=dt / K * 1e3, steps=K,
+                   workload=f"{w.name}: {g['Ls']} layers, d={w.desc['d_model']}, {g['Hs']} heads x {w.desc['head_dim']}, "
+                            f"FFN {g['Fs']}, vocab {V}, batch {w.batch}, prompt {w.s_in}, {K} decode steps",
+                   batch=w.batch, prompt=w.s_in)
         whole = sum(step_bytes) / dt / 1e9
         out["step_hbm"] = dict(bytes_per_step=sum(step_bytes) / K, achieved=whole, peak=HBM_PEAK_GBPS, unit="GB/s",
                                frac=whole / HBM_PEAK_GBPS)
-
-        if not args.no_extras:
+        out["roofline"] = dict(bound="hbm", kernel="whole decode step", achieved=whole, peak=HBM_PEAK_GBPS,
+                               unit="GB/s", frac=whole / HBM_PEAK_GBPS, traffic=None)
+        if extras:
             # ---- kernel classes: the same K steps again, kernel by kernel, each launch's own begin/end
             # recorded on a pair of HIP events of the stream it runs on ----
             fresh()
@@ -212,33 +217,36 @@ def main():
             tm = sh.kernel_timing_read()
             sh.kernel_timing(False)
             assert np.array_equal(nxt.cpu().numpy(), final_ids), "eager and graph runs disagree"
-            classes = {}
-            for name, (ms, cnt) in tm.items():
+            classes, total_ms = {}, {}
+            for cname, (ms, cnt) in tm.items():
                 if cnt == 0:
                     continue
-                if name in class_bytes:
-                    b = class_bytes[name] * K
-                elif name == "decode_attn":
+                if cname in class_bytes:
+                    b = class_bytes[cname] * K
+                elif cname == "decode_attn":
                     b = sum(attn_bytes)
                 else:
                     b = 0
-                classes[name] = dict(launches=int(cnt), avg_us=ms / cnt * 1e3, GBps=(b / (ms * 1e-3) / 1e9) if b else None)
+                classes[cname] = dict(launches=int(cnt), avg_us=ms / cnt * 1e3, GBps=(b / (ms * 1e-3) / 1e9) if b else None,
+                                      share_of_step=ms / K / (dt / K * 1e3))
+                if b:
+                    total_ms[cname] = (ms, cnt, b)
             out["classes"] = classes
-            dom = "resid_gemm"                                   # out-projection + second FFN matrix: most bytes per step
-            ms, cnt = tm[dom]
-            ach = class_bytes[dom] * K / (ms * 1e-3) / 1e9
-            out["roofline"] = dict(bound="hbm", kernel="stream_gemm<EPI_RESID> (out-projection and second FFN matrix, residual epilogue)",
-                                   achieved=ach, peak=HBM_PEAK_GBPS, unit="GB/s", frac=ach / HBM_PEAK_GBPS,
-                                   traffic=measured_traffic(w.name, "stream_gemm_resid"),
-                                   bytes_per_launch=class_bytes[dom] * K / cnt, avg_launch_us=ms / cnt * 1e3,
-                                   launches=int(cnt))
+            # the roofline object is for the kernel class with the most time per step
+            dom = max(total_ms, key=lambda c: total_ms[c][0])
+            ms, cnt, b = total_ms[dom]
+            ach = b / (ms * 1e-3) / 1e9
+            key, label = KERNEL_OF_CLASS[dom]
+            out["roofline"] = dict(bound="hbm", kernel=label, achieved=ach, peak=HBM_PEAK_GBPS, unit="GB/s",
+                                   frac=ach / HBM_PEAK_GBPS, traffic=measured_traffic(w.name, key),
+                                   bytes_per_launch=b / cnt, avg_launch_us=ms / cnt * 1e3, launches=int(cnt))
             fl = prefill_flops(w)
             peak = MFMA_PEAK_TFLOPS[w.desc["dtype"]]       # halves and bf16 share one matrix-core peak
             out["prefill"] = dict(ms=prefill_ms, tokens=w.batch * w.s_in, TFLOPs=fl / (prefill_ms * 1e-3) / 1e12,
                                   peak=peak, frac=fl / (prefill_ms * 1e-3) / 1e12 / peak)
 
             # ---- measured cost model (Section 5; Eq. 1): iteration time over context length, from the timed steps ----
-            if K // chunk >= 2:
+            if K // chunk >= 4:
                 from paper_2311_15566_amd import plan as P
                 samples = [(w.batch, w.s_in + i * chunk + chunk // 2, marks[i].elapsed_time(marks[i + 1]) / chunk)
                            for i in range(K // chunk)]
@@ -249,68 +257,127 @@ def main():
                 out["cost_model"] = dict(dec_base_ms=cm.dec_base_ms[0], dec_per_cached_token_us=cm.dec_per_row_ms[0] * 1e3,
                                          prefill_ms_per_token=cm.pre_per_token_ms[0], samples=len(samples),
                                          l_exe_ms=l_exe[-1], measured_ms=measured, s_in=w.s_in, s_out=steps_fit,
-                                         note="least-squares line through the mean iteration time of each run of "
+                                         note="least-squares line (slope not below 0) through the mean iteration time of each run of "
                                               f"{chunk} timed steps; l_exe = Eq. (1) from the fit, measured = the same steps timed")
 
-            # ---- KV re-partition of this shard's cache into two half-width shards ----
-            g = shard_dims(w)
-            if g["Hs"] % 2 == 0 and g["Fs"] % 128 == 0:
-                parts = [ss.Shard(w.desc, sub_slice_of(w.slice, p, 2), W, w.batch, w.s_max) for p in range(2)]
-                keep = list(range(w.batch))
+        if repack5:
+            # ---- KV re-partition at the reparallelize-and-resume configuration's size: this M=2 shard with 1000
+            # committed tokens per sequence into the two M'=4 layouts (13 heads each) ----
+            w5 = workload("llama30b_reparallelize")
+            n5 = w5.s_in + w5.steps
+            assert w5.desc == w.desc and w5.slice == w.slice and w5.batch == w.batch and n5 <= w.s_max
+            sh.reset()
+            ss.prefill([sh], d_toks[:, :n5].contiguous(), logits, nxt)
+            parts = [ss.Shard(w.desc, s, W, w.batch, w5.s_max) for s in w5.extra["dst_slices"]]
+            keep = list(range(w.batch))
+            for p in parts:
+                ss.kv_repack(p, sh, keep)                     # untimed first touch
+            torch.cuda.synchronize()
+            reps = 5
+            e0.record()
+            moved = 0
+            for _ in range(reps):
                 for p in parts:
-                    ss.kv_repack(p, sh, keep)                     # untimed first touch
-                torch.cuda.synchronize()
-                reps = 5
-                e0.record()
-                moved = 0
-                for _ in range(reps):
-                    for p in parts:
-                        moved += ss.kv_repack(p, sh, keep)
-                e1.record()
-                torch.cuda.synchronize()
-                ms = e0.elapsed_time(e1)
-                traffic = 2 * moved / (ms * 1e-3) / 1e9
-                out["repack"] = dict(payload_bytes=moved // reps, ms=ms / reps, traffic_GBps=traffic,
-                                     frac=traffic / HBM_PEAK_GBPS, rows=w.s_in + K,
-                                     note="traffic = bytes read + bytes written; payload = half")
-                for p in parts:
-                    p.destroy()
-                # ---- model-context re-slice: the same two half-width shards built out of the resident one ----
-                half = sub_slice_of(w.slice, 0, 2)
-                nb = ss.binding.device_bytes(w.desc, half, w.batch, w.s_max)
-                mem = torch.zeros(nb, dtype=torch.uint8, device="cuda")
-                ss.Shard.from_resident(w.desc, half, [sh], w.batch, w.s_max, mem=mem).destroy()     # untimed first touch
-                torch.cuda.synchronize()
-                t0 = time.perf_counter()
-                moved = 0
-                for p in range(2):
-                    r = ss.Shard.from_resident(w.desc, sub_slice_of(w.slice, p, 2), [sh], w.batch, w.s_max, mem=mem)
-                    moved += r.bytes_copied
-                    r.destroy()
-                dt_r = time.perf_counter() - t0
-                t0 = time.perf_counter()
-                from_host = ss.Shard(w.desc, sub_slice_of(w.slice, 1, 2), W, w.batch, w.s_max)
-                torch.cuda.synchronize()
-                dt_host = time.perf_counter() - t0
-                # `mem` still holds the second half-width shard's model context: byte for byte what the upload made
-                n_ctx_bytes = from_host.model_context().numel()
-                assert torch.equal(mem[:n_ctx_bytes], from_host.model_context()), "re-sliced model context differs from the uploaded one"
-                from_host.destroy()
-                out["reslice"] = dict(bytes_copied=moved // 2, ms=dt_r / 2 * 1e3, traffic_GBps=2 * moved / dt_r / 1e9,
-                                      frac=2 * moved / dt_r / 1e9 / HBM_PEAK_GBPS, from_host_ms=dt_host * 1e3,
-                                      note="one half-width shard's model context copied out of the resident shard "
-                                           "(wall time of the call, which synchronizes); from_host_ms: the same shard "
-                                           "uploaded from host tensors (the two compared byte for byte)")
-                del mem
-        else:
-            out["roofline"] = dict(bound="hbm", kernel="whole decode step", achieved=whole, peak=HBM_PEAK_GBPS,
-                                   unit="GB/s", frac=whole / HBM_PEAK_GBPS, traffic=None)
+                    moved += ss.kv_repack(p, sh, keep)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            traffic = 2 * moved / (ms * 1e-3) / 1e9
+            out["repack"] = dict(workload=f"{w5.name}: {w.batch} sequences x {n5} committed tokens, {g['Ls']} layers, "
+                                          f"{g['Hs']} heads -> 2 x {g['Hs'] // 2} heads",
+                                 payload_bytes=moved // reps, ms=ms / reps, traffic_GBps=traffic,
+                                 frac=traffic / HBM_PEAK_GBPS, rows=n5,
+                                 note="traffic = bytes read + bytes written; payload = half")
+            for p in parts:
+                p.destroy()
+            del parts
+        if reslice and g["Hs"] % 2 == 0 and g["Fs"] % 128 == 0:
+            # ---- model-context re-slice: two half-width shards built out of the resident one ----
+            half = sub_slice_of(w.slice, 0, 2)
+            nb = ss.binding.device_bytes(w.desc, half, w.batch, w.s_max)
+            mem = torch.zeros(nb, dtype=torch.uint8, device="cuda")
+            ss.Shard.from_resident(w.desc, half, [sh], w.batch, w.s_max, mem=mem).destroy()     # untimed first touch
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            moved = 0
+            for p in range(2):
+                r = ss.Shard.from_resident(w.desc, sub_slice_of(w.slice, p, 2), [sh], w.batch, w.s_max, mem=mem)
+                moved += r.bytes_copied
+                r.destroy()
+            dt_r = time.perf_counter() - t0
+            out["reslice"] = dict(bytes_copied=moved // 2, ms=dt_r / 2 * 1e3, traffic_GBps=2 * moved / dt_r / 1e9,
+                                  frac=2 * moved / dt_r / 1e9 / HBM_PEAK_GBPS,
+                                  note="one half-width shard's model context copied out of the resident shard "
+                                       "(wall time of the call, which synchronizes)")
+            del mem
         sh.destroy()
-        del sh
-        torch.cuda.empty_cache()
+        del sh, logits, nxt, d_toks
+    torch.cuda.synchronize()
+    gc.collect()
+    torch.cuda.empty_cache()
+    return out, ((w, W) if keep_weights else None)
 
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=128)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default=HEADLINE, choices=[HEADLINE] + OTHERS + ["tiny_gpt"],
+                    help="the headline workload (default: the largest single-GPU configuration)")
+    ap.add_argument("--only", action="store_true", help="run the headline workload only (no `configs`, no repack leg)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the kernel-class, prefill, cost-model, repack and re-slice legs")
+    ap.add_argument("--eager", action="store_true", help="launch kernel by kernel instead of replaying a graph")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only copy 1 GiB device to device three times (a kernel of known traffic, for scaling "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs one tensor-parallel shard on ONE GPU; collectives and sharding "
+                 "across GPUs are not part of it (run with --gpus 1)")
+
+    import torch
+    import paper_2311_15566_amd as ss
+
+    assert torch.cuda.is_available(), "bench.py needs an MI355X"
+    torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps(dict(copy_bytes=1 << 30, copies=3)), flush=True)
+        return
+    K, Wm = args.steps, args.warmup
+    extras = not args.no_extras
+    is_llama = args.workload == HEADLINE
+    head, kept = run_workload(ss, torch, args.workload, K, Wm, eager=args.eager, extras=extras,
+                              repack5=extras and is_llama and not args.only, reslice=extras and not args.only,
+                              keep_weights=not args.no_cpu_baseline)
+    if head["steps"] != K:
+        sys.exit(f"--steps {K} exceeds the workload's decode steps")
+    out = dict(metric="decode tokens/s per TP shard on 1 GPU", value=head["value"], unit="tokens/s", n_gpus=1,
+               steps=K, warmup=Wm, ms_per_step=head["ms_per_step"], higher_is_better=True, scaling="weak",
+               vs_baseline=None, dtype="f16" if args.workload != "tiny_gpt" else "f32", data="synthetic",
+               config=dict(workload=head["workload"], batch=head["batch"], prompt=head["prompt"],
+                           launch="eager" if args.eager else "hip-graph"))
+    for k in ("step_hbm", "classes", "roofline", "prefill", "cost_model", "repack", "reslice"):
+        if k in head:
+            out[k] = head[k]
     if not args.no_cpu_baseline:
+        w, W = kept
         out["cpu_baseline"] = cpu_baseline(w, W, w.s_in + K // 2)
+        del kept, W
+        gc.collect()
+    if not args.only and is_llama:
+        out["configs"] = {}
+        for name in OTHERS:
+            r, _ = run_workload(ss, torch, name, K, Wm, eager=args.eager, extras=extras)
+            r["tokens_per_s"] = r.pop("value")
+            out["configs"][name] = r
     print(json.dumps(out), flush=True)
 
 

@@ -5,8 +5,11 @@
  *
  * C ABI.  Every pointer argument says "host" or "device".  The caller owns all
  * device memory and the HIP stream; the library never allocates device memory.
- * Calls enqueue work on the given stream and return; outputs are valid after the
- * stream has been synchronized.  A shard is not thread-safe.  Every call returns
+ * ss_prefill, ss_decode_step, their ss_stage_ forms, ss_kv_repack and ss_shard_reset
+ * enqueue work on the given stream and return; outputs are valid after the stream
+ * has been synchronized.  The calls that say so below synchronize the stream
+ * themselves (creation, ss_committed_len, export / import, ss_tune_decode).  A shard
+ * is not thread-safe.  Every call returns
  * an ss_status; argument and state errors are found on the host before anything
  * is launched, and leave committed lengths and committed cache rows untouched.
  * ss_last_error() gives the text of the calling thread's last failure.
@@ -89,7 +92,10 @@ typedef struct {
   const ss_layer_weights *layers;
 } ss_weights;
 
-/* Device bytes a shard needs for its model context (weights, re-laid out for the
+/* A position's two kinds of context (Section 3.1: the context daemon keeps the model context,
+ * i.e. the parameters, and the cache context, i.e. the keys and values, in device memory; Section 5:
+ * the engine takes its tensors from the daemon instead of allocating them).
+ * Device bytes a shard needs for its model context (weights, re-laid out for the
  * matrix cores), its cache context (K and V of every layer, max_batch x max_seq
  * rows) and its workspace.  0 on invalid arguments. */
 size_t ss_shard_device_bytes(const ss_model_desc *desc, const ss_slice *slice,
@@ -123,7 +129,10 @@ ss_status ss_shard_create_from_resident(const ss_model_desc *desc, const ss_slic
  * cache): what a byte-for-byte comparison of two shards' model context covers. */
 size_t ss_shard_model_context_bytes(const ss_shard *shard);
 
-ss_status ss_shard_destroy(ss_shard *shard); /* frees the host object only */
+/* A position whose context has been migrated away gives its memory back (Section 3.4: migrated
+ * context is released as the plan proceeds): frees the host object and its captured graphs; the
+ * device memory is the caller's. */
+ss_status ss_shard_destroy(ss_shard *shard);
 
 /* Drop the cache context: every committed length back to 0 (Section 4.2: a
  * position that lost its cache falls back to recomputing it). */
@@ -171,8 +180,9 @@ ss_status ss_stage_decode_step(ss_shard *const *group, int32_t n_group, const in
                                const float *hidden_in, int32_t B, float *hidden_out, float *logits,
                                int32_t *next_tokens, void *hip_stream);
 
-/* Committed lengths as the device holds them: synchronizes the stream, copies
- * n[0..max_batch) to out_host (host int32 [max_batch]). */
+/* The progress a request has committed (Section 4.1: progress is committed per token, so an
+ * interrupted request resumes from its last committed token).  Committed lengths as the device
+ * holds them: synchronizes the stream, copies n[0..max_batch) to out_host (host int32 [max_batch]). */
 ss_status ss_committed_len(const ss_shard *shard, int32_t *out_host, void *hip_stream);
 
 /* Cache-context migration on one device (Section 3.3: a device re-uses the
@@ -191,7 +201,9 @@ ss_status ss_committed_len(const ss_shard *shard, int32_t *out_host, void *hip_s
 ss_status ss_kv_repack(ss_shard *dst, const ss_shard *src, const int32_t *batch_map,
                        int32_t first_source, uint64_t *bytes_moved, void *hip_stream);
 
-/* Committed cache rows to / from host memory in the exchange order
+/* The cache context as what migration moves between devices (Section 3.4: cache context is
+ * migrated first; Section 4.1: a request resumes on the new configuration from its committed
+ * keys and values without recomputing them): committed cache rows to / from host memory in the exchange order
  * [layer][K|V][b][head][j < n[b]][Dh], densely packed, in the cache dtype.
  * ss_kv_export_bytes gives the size for the current lengths.  Import sets the
  * lengths to lens (host int32 [max_batch]) and expects exactly that many bytes.
@@ -201,51 +213,20 @@ ss_status ss_kv_export(const ss_shard *shard, void *host_dst, size_t bytes, void
 ss_status ss_kv_import(ss_shard *shard, const void *host_src, const int32_t *lens,
                        size_t bytes, void *hip_stream);
 
-/* Test hook for "a request can be interrupted at any iteration" (Section 4.1):
- * with layer >= 0 the next decode steps stop after that layer (index within the
- * shard) and return SS_EINTR without committing.  -1 switches it off. */
-ss_status ss_debug_interrupt_after_layer(ss_shard *shard, int32_t layer);
-
-/* How ss_decode_step is launched.  1 (default): replay of a captured HIP graph of the step's
- * kernels; 0: the kernels one by one.  Both give the same bits. */
-ss_status ss_set_graph_launch(ss_shard *shard, int32_t enabled);
-
-/* Test aid, process-wide: force the launch shape of the decode GEMMs built from now on (shards
- * that have already replayed a step keep their captured graph): weight tiles per block (1 or 2;
- * 0 = the library's choice) and, for more than 16 batch rows, whether the two batch tiles go to
- * separate blocks (2) or not (1; 0 = the library's choice).  The library chooses per shape, by a
- * rule or, on a shard's first step at a batch size, by timing the candidates on the device
- * (SS_TUNE=0 in the environment keeps the rule); every shape gives the same bits. */
-ss_status ss_debug_force_gemm_shape(int32_t tiles_per_block, int32_t batch_split);
-
-/* Test aid, process-wide: force the token block of the initial phase's tiled GEMMs (Eq. (2)'s
- * first iteration over all prompt tokens): 128 or 256 tokens per block; 0 = the library's choice,
- * which goes by the size of the output.  Both give the same bits.  SS_EINVAL for any other value. */
-ss_status ss_debug_force_prefill_block(int32_t tokens_per_block);
-
-/* Measurement aid: per-kernel-class timing of decode steps.  While enabled on group[0],
- * ss_decode_step launches kernel by kernel (no graph replay) and every launch records its own
- * begin and end on a pair of HIP events of the step's stream (the dispatch's timestamps).
- * ss_kernel_timing_read synchronizes the stream, returns the milliseconds and launch counts
- * accumulated per class since the last read (host arrays of 8) and clears them.  Classes:
- * 0 embedding, 1 QKV GEMM, 2 decode attention, 3 out-projection and second-FFN GEMM (the
- * residual epilogue), 4 first-FFN GEMM, 5 LM head, 6 the kernel that ends a step (greedy choice among
- * the LM head's per-block candidates, if there is an LM head, then the token-level commit). */
-ss_status ss_kernel_timing(ss_shard *shard, int32_t enabled);
-ss_status ss_kernel_timing_read(ss_shard *shard, double ms[8], int64_t count[8], void *hip_stream);
-
-/* Host-only check aid (no device memory is touched): the phase table one decode step would use
- * for a shard of this shape placed at device address fake_base.  See the implementation for
- * the record layout; used by the CPU tests that bound-check every buffer a phase addresses. */
-int32_t ss_debug_plan(const ss_model_desc *desc, const ss_slice *slice, int32_t max_batch, int32_t max_seq,
-                      int32_t B, uint64_t fake_base, void *out_phases, int32_t max_phases, uint64_t *out_total,
-                      uint64_t *out_sizeof_phase);
-
 /* Geometry of the shard, for callers that size buffers: out[0..5] = layers, heads,
  * ffn columns, max_batch, max_seq, bytes per cache element. */
 ss_status ss_shard_geometry(const ss_shard *shard, int32_t out[6]);
 
-const char *ss_last_error(void); /* thread-local, never NULL */
+/* Time the candidate launch shapes of the decode GEMMs of this group at batch size B on the
+ * device (real weights, nothing committed, scratch only) and keep the fastest per shape for the
+ * process; shapes not timed follow a rule.  Optional; every shape gives the same bits.
+ * Synchronizes the stream; SS_ESTATE while the stream is being captured. */
+ss_status ss_tune_decode(ss_shard *const *group, int32_t n_group, int32_t B, void *hip_stream);
+
+/* Text of the calling thread's last failure.  Plumbing of this boundary (the paper defines no
+ * error interface; Section 4.2 only says what the system falls back to when a step or a migration
+ * cannot go ahead: the caller needs to know which).  Thread-local, never NULL. */
+const char *ss_last_error(void);
 const char *ss_version(void);
 
 #ifdef __cplusplus

@@ -1,0 +1,56 @@
+/*
+ * spotshard - test hooks and measurement aids.  Not part of the serving boundary (spotshard.h):
+ * the tests use them to force code paths and launch shapes, bench.py to time kernel classes.
+ */
+#ifndef SPOTSHARD_DEBUG_H
+#define SPOTSHARD_DEBUG_H
+
+#include "spotshard.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Test hook for "a request can be interrupted at any iteration" (Section 4.1):
+ * with layer >= 0 the next decode steps stop after that layer (index within the
+ * shard) and return SS_EINTR without committing.  -1 switches it off. */
+ss_status ss_debug_interrupt_after_layer(ss_shard *shard, int32_t layer);
+
+/* How ss_decode_step is launched.  1 (default): replay of a captured HIP graph of the step's
+ * kernels; 0: the kernels one by one.  Both give the same bits. */
+ss_status ss_set_graph_launch(ss_shard *shard, int32_t enabled);
+
+/* Test aid, process-wide: force the launch shape of the decode GEMMs built from now on (shards
+ * that have already replayed a step keep their captured graph): weight tiles per block (1 or 2;
+ * 0 = the library's choice) and, for more than 16 batch rows, whether the two batch tiles go to
+ * separate blocks (2) or not (1; 0 = the library's choice).  The library chooses per shape, by a
+ * rule, or from the timings ss_tune_decode has taken; every shape gives the same bits. */
+ss_status ss_debug_force_gemm_shape(int32_t tiles_per_block, int32_t batch_split);
+
+/* Test aid, process-wide: force the token block of the initial phase's tiled GEMMs (the initial
+ * phase over all prompt tokens: the first term of Eq. (1) and Eq. (2)): 128 or 256 tokens per block; 0 = the library's choice,
+ * which goes by the size of the output.  Both give the same bits.  SS_EINVAL for any other value. */
+ss_status ss_debug_force_prefill_block(int32_t tokens_per_block);
+
+/* Measurement aid: per-kernel-class timing of decode steps.  While enabled on group[0],
+ * ss_decode_step launches kernel by kernel (no graph replay) and every launch records its own
+ * begin and end on a pair of HIP events of the step's stream (the dispatch's timestamps).
+ * ss_kernel_timing_read synchronizes the stream, returns the milliseconds and launch counts
+ * accumulated per class since the last read (host arrays of 8) and clears them.  Classes:
+ * 0 embedding, 1 QKV GEMM, 2 decode attention, 3 out-projection and second-FFN GEMM (the
+ * residual epilogue), 4 first-FFN GEMM, 5 LM head, 6 the kernel that ends a step (greedy choice among
+ * the LM head's per-block candidates, if there is an LM head, then the token-level commit). */
+ss_status ss_kernel_timing(ss_shard *shard, int32_t enabled);
+ss_status ss_kernel_timing_read(ss_shard *shard, double ms[8], int64_t count[8], void *hip_stream);
+
+/* Host-only check aid (no device memory is touched): the phase table one decode step would use
+ * for a shard of this shape placed at device address fake_base.  See the implementation for
+ * the record layout; used by the CPU tests that bound-check every buffer a phase addresses. */
+int32_t ss_debug_plan(const ss_model_desc *desc, const ss_slice *slice, int32_t max_batch, int32_t max_seq,
+                      int32_t B, uint64_t fake_base, void *out_phases, int32_t max_phases, uint64_t *out_total,
+                      uint64_t *out_sizeof_phase);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPOTSHARD_DEBUG_H */

@@ -135,7 +135,11 @@ def cost_fit(decode, prefill=()):
     """Section 5's cost model from measured samples (batch, length, ms): per batch size the
     least-squares line of an incremental iteration's time over the cached length and of the
     initial phase's time over the prompt length (numpy's polynomial fit).  Samples at a single
-    length give a constant (decode) or a line through the origin (initial phase)."""
+    length give a constant (decode) or a line through the origin (initial phase).  Eq. (1)'s
+    t_exe cannot fall with the number of tokens it runs over (an iteration reads every cached
+    row once more than the one before), and Section 4.1's argmax / argmin over S need l_exe
+    non-decreasing: where noise tilts the fitted line downwards, the best line with a slope of
+    at least zero is taken, which is the constant through the samples' mean."""
     model = {}
     for b in sorted({s[0] for s in decode}):
         def line(samples, through_origin):
@@ -145,6 +149,8 @@ def cost_fit(decode, prefill=()):
                 return 0.0, 0.0
             if len(set(x.tolist())) > 1:
                 c1, c0 = np.polyfit(x, y, 1)
+                if c1 < 0:
+                    return float(y.mean()), 0.0
                 return float(c0), float(c1)
             return (0.0, float(y.mean() / x.mean())) if through_origin else (float(y.mean()), 0.0)
         model[b] = dict(dec=line(decode, False), pre=line(prefill, True))

@@ -80,6 +80,7 @@ def _load():
     L.ss_debug_force_gemm_shape.argtypes = [i32, i32]
     L.ss_debug_force_prefill_block.argtypes = [i32]
     L.ss_kernel_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), vp]
+    L.ss_tune_decode.argtypes = [C.POINTER(vp), i32, i32, vp]
     return L
 
 
@@ -236,6 +237,12 @@ def decode_step(group, tokens_in, logits=None, next_tokens=None, stream=None):
     arr, n = _group(group)
     _check(lib.ss_decode_step(arr, n, _dptr(tokens_in), tokens_in.shape[0], _dptr(logits), _dptr(next_tokens),
                               _stream(stream)))
+
+
+def tune_decode(group, B, stream=None):
+    """Time the decode GEMMs' candidate launch shapes at batch size B (synchronizes the stream)."""
+    arr, n = _group(group)
+    _check(lib.ss_tune_decode(arr, n, int(B), _stream(stream)))
 
 
 def stage_prefill(group, B, S, tokens=None, hidden_in=None, hidden_out=None, logits=None, next_tokens=None, stream=None):

@@ -90,6 +90,7 @@ __device__ __forceinline__ void decode_attn_block(const DecodeAttnArgs &a, const
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int b = bh / a.Hs, h = bh - b * a.Hs;
   const int n = a.lens[b];
+  if (n >= a.Smax) return;  // a full cache has no row to append to (the host refuses such a step; a replayed capture may not)
   const int live_splits = max(1, (n + a.rows_per_block - 1) / a.rows_per_block);
   if (sp >= live_splits) return;
   const int HD = a.Hs * DH;

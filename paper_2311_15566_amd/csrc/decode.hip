@@ -4,6 +4,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <atomic>
 #include <mutex>
 #include <tuple>
 
@@ -73,6 +74,7 @@ struct CommitArgs {
   int n_blocks;
   int32_t *next_tokens;  // [B] or NULL
   int32_t *lens[8];
+  int cap[8];            // rows each shard's cache holds: a length never moves past it
   int n_lens, B, inc;
 };
 __global__ void __launch_bounds__(256) choose_and_commit(CommitArgs a) {
@@ -112,14 +114,14 @@ __global__ void __launch_bounds__(256) choose_and_commit(CommitArgs a) {
     if (tid == 0) a.next_tokens[row] = s_i[0];
   }
   if (tid == 0)
-    for (int q = 0; q < a.n_lens; ++q) a.lens[q][row] += a.inc;
+    for (int q = 0; q < a.n_lens; ++q) a.lens[q][row] = min(a.lens[q][row] + a.inc, a.cap[q]);
 }
 static ss_status launch_commit(const StreamGemmArgs &g, hipStream_t st) {
   if (g.B < 1 || g.B > 32 || g.n_lens < 0 || g.n_lens > 8) SS_FAIL(SS_EINVAL, "commit: batch %d, %d shards", g.B, g.n_lens);
   CommitArgs c = {};
   c.am_val = g.am_val, c.am_idx = g.am_idx, c.n_blocks = g.n_blocks, c.next_tokens = g.next_tokens;
   c.n_lens = g.n_lens, c.B = g.B, c.inc = g.commit_inc;
-  for (int q = 0; q < c.n_lens; ++q) c.lens[q] = g.lens[q];
+  for (int q = 0; q < c.n_lens; ++q) c.lens[q] = g.lens[q], c.cap[q] = g.len_cap[q];
   SS_LAUNCH_KERNEL(choose_and_commit, dim3(g.B), dim3(256), 0, st, c);
   SS_HIP(hipGetLastError());
   return SS_OK;
@@ -192,6 +194,9 @@ struct TuneVal {
 };
 static std::map<TuneKey, TuneVal> g_tune;
 static std::mutex g_tune_mu;
+static std::atomic<uint64_t> g_shape_epoch{0};  // bumped when a forced or timed shape changes what a plan would hold
+static std::atomic<uint64_t> g_next_id{1};
+uint64_t next_shard_id() { return g_next_id.fetch_add(1); }
 static TuneVal g_forced = {0, 0};  // test aid: 0 = not forced
 
 static TuneVal tune_rule(int epi, int row_tiles, int B);
@@ -258,7 +263,7 @@ static Phase lm_head_phase(Shard *const *group, int n_group, int B, int stat_gro
   a.am_val = (float *)(g0->ws + L.ws_argmax);
   a.am_idx = (int *)(a.am_val + (size_t)ceil_div(a.row_tiles, 2) * 32);
   a.next_tokens = next_tokens;
-  for (int i = 0; i < n_group; ++i) a.lens[i] = group[i]->d_len;
+  for (int i = 0; i < n_group; ++i) a.lens[i] = group[i]->d_len, a.len_cap[i] = group[i]->L.Smax;
   a.n_lens = n_group, a.commit_inc = commit_inc;
   shape_gemm(a, g0->m.dtype, EPI_LOGITS);
   ph.gx = a.n_blocks * a.bt_split, ph.gy = 1;
@@ -288,7 +293,7 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
   {
     Phase ph = {};
     ph.kind = PH_EMBED, ph.gx = B, ph.gy = 1;
-    ph.e = EmbedArgs{hidden_in, tokens_in, g0->wte, g0->wpe, g0->d_len, 0, x, d, L0.V, first_gamma, ad, rms, statd, cen};
+    ph.e = EmbedArgs{hidden_in, tokens_in, g0->wte, g0->wpe, g0->d_len, 0, L0.max_pos, x, d, L0.V, first_gamma, ad, rms, statd, cen};
     plan->push_back(ph);
   }
   int stat_groups = 1;  // partial-sum groups behind the rows in statd
@@ -382,7 +387,7 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
     Phase ph = {};
     ph.kind = PH_COMMIT, ph.gx = B, ph.gy = 1;
     ph.g.B = B, ph.g.n_lens = n_group, ph.g.commit_inc = 1;
-    for (int i = 0; i < n_group; ++i) ph.g.lens[i] = group[i]->d_len;
+    for (int i = 0; i < n_group; ++i) ph.g.lens[i] = group[i]->d_len, ph.g.len_cap[i] = group[i]->L.Smax;
     plan->push_back(ph);
     return;
   }
@@ -474,7 +479,10 @@ static ss_status tune_decode_gemms(Shard *const *group, int n_group, int B, hipS
   if (by_shape.empty()) return SS_OK;
   hipEvent_t e0 = nullptr, e1 = nullptr;
   SS_HIP(hipEventCreate(&e0));
-  SS_HIP(hipEventCreate(&e1));
+  if (hipEventCreate(&e1) != hipSuccess) {
+    (void)hipEventDestroy(e0);
+    SS_FAIL(SS_EHIP, "hipEventCreate failed");
+  }
   ss_status rc = SS_OK;
   for (auto &kv : by_shape) {
     const TuneKey &key = kv.first;
@@ -521,6 +529,7 @@ static ss_status tune_decode_gemms(Shard *const *group, int n_group, int B, hipS
     }
     std::lock_guard<std::mutex> lock(g_tune_mu);
     g_tune[key] = best;
+    g_shape_epoch.fetch_add(1);
   }
   (void)hipEventDestroy(e0);
   (void)hipEventDestroy(e1);
@@ -553,8 +562,9 @@ ss_status run_decode_step(Shard *const *group, int n_group, const int32_t *token
   Shard *g0 = group[0];
   GraphKey key;
   key.B = B;
+  key.epoch = g_shape_epoch.load();
   key.ptrs = {tokens_in, hidden_in, hidden_out, logits, next_tokens, (const void *)st};
-  for (int i = 0; i < n_group; ++i) key.ptrs.push_back(group[i]);
+  for (int i = 0; i < n_group; ++i) key.ids.push_back(group[i]->id);
   const bool plain = !g0->timing && stop_after_layer < 0;
   // the NULL stream cannot be captured, and a stream the caller is capturing is left to the caller
   hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
@@ -577,7 +587,11 @@ ss_status run_decode_step(Shard *const *group, int n_group, const int32_t *token
     e = hipGraphInstantiate(&ex, gr, nullptr, nullptr, 0);
     (void)hipGraphDestroy(gr);
     if (e != hipSuccess) SS_FAIL(SS_EHIP, "hipGraphInstantiate: %s", hipGetErrorString(e));
-    if (g0->graphs.size() >= 16) destroy_graphs(g0);
+    if (g0->graphs.size() >= 16) {  // rare: an exec may still be running on the stream it was launched on
+      SS_HIP(hipStreamSynchronize(st));
+      for (auto &kv : g0->graphs) (void)hipGraphExecDestroy(kv.second);
+      g0->graphs.clear();
+    }
     it = g0->graphs.emplace(key, ex).first;
   }
   SS_HIP(hipGraphLaunch(it->second, st));
@@ -607,7 +621,7 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, c
   // for bf16 models: single bf16 activations miss the logits bar (OPT-66B shape 6.4e-2 at its first
   // token), bf16 hi/lo pairs meet it at twice the matrix-core work.
   {
-    EmbedArgs e{hidden_in, tokens, g0->wte, g0->wpe, nullptr, S, x, d, L0.V, g0->layers[0].ln1_g, abuf, rms, nullptr, nullptr, pstat, mr};
+    EmbedArgs e{hidden_in, tokens, g0->wte, g0->wpe, nullptr, S, L0.max_pos, x, d, L0.V, g0->layers[0].ln1_g, abuf, rms, nullptr, nullptr, pstat, mr};
     if (dt == SS_DTYPE_BF16) hipLaunchKernelGGL(embed_rows<bf16_t>, dim3(T_live), dim3(256), 0, st, e);
     else hipLaunchKernelGGL(embed_rows<float>, dim3(T_live), dim3(256), 0, st, e);
     SS_HIP(hipGetLastError());
@@ -678,7 +692,7 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, c
     SS_HIP(hipMemcpyAsync(hidden_out, x, (size_t)T_live * d * 4, hipMemcpyDeviceToDevice, st));
     StreamGemmArgs c = {};
     c.n_lens = n_group, c.B = B, c.commit_inc = S;
-    for (int i = 0; i < n_group; ++i) c.lens[i] = group[i]->d_len;
+    for (int i = 0; i < n_group; ++i) c.lens[i] = group[i]->d_len, c.len_cap[i] = group[i]->L.Smax;
     return launch_commit(c, st);
   }
   float *xd = (float *)(g0->ws + L0.ws_xd);
@@ -760,6 +774,7 @@ ss_status ss_debug_force_gemm_shape(int32_t tiles_per_block, int32_t batch_split
     SS_FAIL(SS_EINVAL, "launch shape (%d, %d)", tiles_per_block, batch_split);
   std::lock_guard<std::mutex> lock(g_tune_mu);
   g_forced = TuneVal{tiles_per_block, batch_split};
+  g_shape_epoch.fetch_add(1);
   return SS_OK;
 }
 
@@ -799,25 +814,21 @@ ss_status ss_stage_decode_step(ss_shard *const *group_, int32_t n_group, const i
   }
   int stop = -1;
   for (int i = 0; i < n_group; ++i) stop = std::max(stop, group[i]->interrupt_after);
-  // first step of these shards at this batch size: time the GEMM launch shapes (not while the
-  // caller is capturing the stream, and not with SS_TUNE=0 in the environment)
-  static const bool tune_on = !(getenv("SS_TUNE") && atoi(getenv("SS_TUNE")) == 0);
-  bool tuned = true;
-  for (int i = 0; i < n_group; ++i) tuned = tuned && group[i]->tuned_B.count(B);
-  if (!tuned && tune_on) {
-    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-    if (hip_stream) SS_HIP(hipStreamIsCapturing((hipStream_t)hip_stream, &cs));
-    if (cs == hipStreamCaptureStatusNone) {
-      SS_TRY(tune_decode_gemms(group, n_group, B, (hipStream_t)hip_stream));
-      for (int i = 0; i < n_group; ++i) group[i]->tuned_B.insert(B);
-    }
-  }
   ss_status rc = run_decode_step(group, n_group, tokens_in, hidden_in, B, hidden_out, logits, next_tokens,
                                  (hipStream_t)hip_stream, stop);
   if (rc != SS_OK) return rc;  // SS_EINTR: nothing committed
   for (int i = 0; i < n_group; ++i)
     for (int b = 0; b < B; ++b) group[i]->h_len[b] += 1;
   return SS_OK;
+}
+
+ss_status ss_tune_decode(ss_shard *const *group_, int32_t n_group, int32_t B, void *hip_stream) {
+  Shard *const *group = (Shard *const *)group_;
+  SS_TRY(check_group(group, n_group, B));
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  if (hip_stream) SS_HIP(hipStreamIsCapturing((hipStream_t)hip_stream, &cs));
+  if (cs != hipStreamCaptureStatusNone) SS_FAIL(SS_ESTATE, "the stream is being captured: timing would synchronize it");
+  return tune_decode_gemms(group, n_group, B, (hipStream_t)hip_stream);
 }
 
 ss_status ss_decode_step(ss_shard *const *group_, int32_t n_group, const int32_t *tokens_in, int32_t B, float *logits,

@@ -33,7 +33,6 @@ constexpr int kTileGemmRing = 3;  // LDS stages
 // NJ: token tiles of a wave, 8 (block of 256 tokens, two blocks per compute unit) or 4 (128 tokens, three)
 template <typename T, int EPI, int NJ>
 __global__ void __launch_bounds__(256, NJ == 8 ? 2 : 3) tile_gemm(TileGemmArgs a) {
-  constexpr bool H16 = sizeof(T) == 2;
   typedef typename Operand<T>::type OT;  // element type of the activation operands
   constexpr int MI = 4;                  // weight row tiles of a wave
   constexpr int BMT = 2 * MI, BTT = 2 * NJ;
@@ -108,7 +107,7 @@ __global__ void __launch_bounds__(256, NJ == 8 ? 2 : 3) tile_gemm(TileGemmArgs a
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
-      for (int j = 0; j < NJ; ++j) acc[i][j] = H16 ? mma_f16(wf[i], af[j], acc[i][j]) : Mma<T>::mma(wf[i], af[j], acc[i][j]);
+      for (int j = 0; j < NJ; ++j) acc[i][j] = mma_op<T>(wf[i], af[j], acc[i][j]);
   }
 
   const int q4 = (lane >> 4) * 4, tl = lane & 15;

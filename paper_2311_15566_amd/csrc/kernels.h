@@ -68,6 +68,7 @@ struct StreamGemmArgs {
   // PH_COMMIT only (the kernel that ends a step; the GEMM kernels do not read these)
   int32_t *next_tokens; // [B] or NULL
   int32_t *lens[8];     // committed lengths to advance (all shards of the group)
+  int len_cap[8];       // rows each of those caches holds
   int n_lens;
   int commit_inc;
 };
@@ -150,6 +151,7 @@ struct EmbedArgs {
   const void *wte, *wpe;  // [V][d], [max_pos][d] or NULL
   const int32_t *lens;    // decode: position = committed length; NULL: position = row % S
   int S;
+  int max_pos;            // rows of the position table (the lookup is clamped to it)
   float *x;               // [rows][d]
   int d, V;
   // operand of the first GEMM, centred on the row's mean c (RMSNorm: c = 0): (x - c) * gamma

@@ -7,12 +7,6 @@ namespace ss {
 // one 16 x 16 x FragK product per call: D[n][b] += sum_k W[n][k] * A[b][k]
 // lane l returns D[(l>>4)*4 + i][l & 15], i = 0..3
 template <typename T> struct Mma;
-template <> struct Mma<bf16_t> {
-  static __device__ __forceinline__ f32x4 mma(u32x4 w, u32x4 a, f32x4 c) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, a), c, 0,
-                                                   0, 0);
-  }
-};
 template <> struct Mma<float> {
   static __device__ __forceinline__ f32x4 mma(u32x4 w, u32x4 a, f32x4 c) {
     f32x4 wf = __builtin_bit_cast(f32x4, w), af = __builtin_bit_cast(f32x4, a);
@@ -26,6 +20,12 @@ template <> struct Mma<float> {
 typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
 __device__ __forceinline__ f32x4 mma_f16(u32x4 w, u32x4 a, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, w), __builtin_bit_cast(f16x8_t, a), c, 0, 0, 0);
+}
+// the product for a model of element type T: half operands for a 2-byte (bf16) model, float operands otherwise
+template <typename T>
+__device__ __forceinline__ f32x4 mma_op(u32x4 w, u32x4 a, f32x4 c) {
+  if constexpr (sizeof(T) == 2) return mma_f16(w, a, c);
+  else return Mma<float>::mma(w, a, c);
 }
 __device__ __forceinline__ float act_apply(int kind, float h) {
   if (kind == SS_ACT_GELU_TANH) return 0.5f * h * (1.0f + tanhf(0.7978845608028654f * (h + 0.044715f * h * h * h)));

@@ -188,16 +188,19 @@ int32_t ss_jit_iterations(int32_t acquisition, int32_t s_out, const double *l_ex
   return t_mig < l_exe[s] ? s : 0;
 }
 
-// least-squares line y = c0 + c1 * x through the points; one distinct x: a constant (through_origin: c1 = y / x)
-static void fit_line(const std::vector<std::pair<double, double>> &pts, bool through_origin, double *c0, double *c1) {
+// least-squares line y = c0 + c1 * x through the points; one distinct x: a constant (through_origin: c1 = y / x).
+// non_decreasing: the best line among those with c1 >= 0, which is the constant through the mean when the
+// unconstrained slope is negative.
+static void fit_line(const std::vector<std::pair<double, double>> &pts, bool through_origin, bool non_decreasing, double *c0,
+                     double *c1) {
   double mx = 0, my = 0;
   for (auto &p : pts) mx += p.first, my += p.second;
   mx /= (double)pts.size(), my /= (double)pts.size();
   double sxx = 0, sxy = 0;
   for (auto &p : pts) sxx += (p.first - mx) * (p.first - mx), sxy += (p.first - mx) * (p.second - my);
-  if (sxx > 0) {
+  if (sxx > 0 && !(non_decreasing && sxy < 0)) {
     *c1 = sxy / sxx, *c0 = my - *c1 * mx;
-  } else if (through_origin && mx > 0) {
+  } else if (sxx <= 0 && through_origin && mx > 0) {
     *c0 = 0, *c1 = my / mx;
   } else {
     *c0 = my, *c1 = 0;
@@ -227,11 +230,11 @@ ss_status ss_cost_fit(const ss_cost_sample *decode, int32_t n_decode, const ss_c
     std::vector<std::pair<double, double>> pts;
     for (int i = 0; i < n_decode; ++i)
       if (decode[i].batch == batches[b]) pts.push_back({(double)decode[i].length, decode[i].ms});
-    fit_line(pts, false, &model->dec_base_ms[b], &model->dec_per_row_ms[b]);
+    fit_line(pts, false, true, &model->dec_base_ms[b], &model->dec_per_row_ms[b]);
     pts.clear();
     for (int i = 0; i < n_prefill; ++i)
       if (prefill[i].batch == batches[b]) pts.push_back({(double)prefill[i].length, prefill[i].ms});
-    if (!pts.empty()) fit_line(pts, true, &model->pre_base_ms[b], &model->pre_per_token_ms[b]);
+    if (!pts.empty()) fit_line(pts, true, true, &model->pre_base_ms[b], &model->pre_per_token_ms[b]);
   }
   return SS_OK;
 }

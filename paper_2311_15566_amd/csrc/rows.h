@@ -53,7 +53,8 @@ __device__ __forceinline__ void embed_row_block(const EmbedArgs &a, const int r,
   static_assert(Elem<OT>::kPerLane == PL && Elem<OT>::kFragK == FK, "operand and weight fragments have one geometry");
   int tok = a.hidden ? 0 : a.tokens[r];
   tok = min(max(tok, 0), a.V - 1);
-  const int pos = a.lens ? a.lens[r] : (r % a.S);
+  int pos = a.lens ? a.lens[r] : (r % a.S);
+  if (a.wpe) pos = min(pos, a.max_pos - 1);
   const int nvec = a.d / PL;
   const u32x4 *te = (const u32x4 *)((const T *)a.wte + (size_t)tok * a.d);
   const u32x4 *pe = (a.wpe && !a.hidden) ? (const u32x4 *)((const T *)a.wpe + (size_t)pos * a.d) : nullptr;

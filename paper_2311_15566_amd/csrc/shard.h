@@ -1,5 +1,7 @@
 // Host object of one shard and the carve-up of its device memory.
 #pragma once
+#include <tuple>
+
 #include "kernels.h"
 
 namespace ss {
@@ -45,13 +47,22 @@ struct Layout {
 
 bool compute_layout(const ss_model_desc &m, const ss_slice &s, int max_batch, int max_seq, Layout *L);
 
+// What a captured decode step depends on: the caller's buffers and stream, the batch size, the
+// identity of every shard of the group (a process-unique id, not the host address, which the
+// allocator hands out again after a destroy) and the launch-shape epoch (bumped whenever the shapes
+// the plan builder would choose may have changed).
 struct GraphKey {
   std::vector<const void *> ptrs;
+  std::vector<uint64_t> ids;
+  uint64_t epoch;
   int B;
-  bool operator<(const GraphKey &o) const { return B != o.B ? B < o.B : ptrs < o.ptrs; }
+  bool operator<(const GraphKey &o) const {
+    return std::tie(B, epoch, ids, ptrs) < std::tie(o.B, o.epoch, o.ids, o.ptrs);
+  }
 };
 
 struct Shard {
+  uint64_t id = 0;       // process-unique, never reused
   ss_model_desc m;
   ss_slice s;
   Layout L;
@@ -75,7 +86,6 @@ struct Shard {
   int interrupt_after = -1;
   bool use_graph = true;
   std::map<GraphKey, hipGraphExec_t> graphs;
-  std::set<int> tuned_B;  // batch sizes whose decode GEMM launch shapes have been timed
   // per-kernel-class event timing (measurement aid)
   bool timing = false;
   struct TimedLaunch { int cls; hipEvent_t e0, e1; };
@@ -100,5 +110,6 @@ ss_status run_decode_step(Shard *const *group, int n_group, const int32_t *token
 ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, const float *hidden_in, int B, int S_in,
                       float *hidden_out, float *logits, int32_t *next_tokens, hipStream_t st);
 void destroy_graphs(Shard *sh);
+uint64_t next_shard_id();
 
 }  // namespace ss

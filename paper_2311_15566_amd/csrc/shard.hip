@@ -501,6 +501,7 @@ ss_status ss_shard_create(const ss_model_desc *desc, const ss_slice *slice, cons
   if (((uintptr_t)device_mem) & 255) SS_FAIL(SS_EINVAL, "device_mem must be 256-byte aligned");
   Shard *sh = new (std::nothrow) Shard();
   if (!sh) SS_FAIL(SS_ENOMEM, "host allocation failed");
+  sh->id = next_shard_id();
   sh->m = *desc;
   sh->s = *slice;
   compute_layout(*desc, *slice, max_batch, max_seq, &sh->L);
@@ -596,6 +597,7 @@ ss_status ss_shard_create_from_resident(const ss_model_desc *desc, const ss_slic
   }
   Shard *sh = new (std::nothrow) Shard();
   if (!sh) SS_FAIL(SS_ENOMEM, "host allocation failed");
+  sh->id = next_shard_id();
   sh->m = *desc, sh->s = *slice;
   compute_layout(*desc, *slice, max_batch, max_seq, &sh->L);
   const Layout &L = sh->L;

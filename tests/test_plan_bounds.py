@@ -12,7 +12,7 @@ vp, i32, f32, sz = C.c_void_p, C.c_int32, C.c_float, C.c_size_t
 
 
 class EmbedArgs(C.Structure):
-    _fields_ = [("hidden", vp), ("tokens", vp), ("wte", vp), ("wpe", vp), ("lens", vp), ("S", i32), ("x", vp), ("d", i32), ("V", i32),
+    _fields_ = [("hidden", vp), ("tokens", vp), ("wte", vp), ("wpe", vp), ("lens", vp), ("S", i32), ("max_pos", i32), ("x", vp), ("d", i32), ("V", i32),
                 ("gamma", vp), ("act_out", vp), ("rms", i32), ("stat_out", vp), ("cen_out", vp), ("pstat_out", vp), ("mr_out", vp)]
 
 
@@ -21,7 +21,7 @@ class GemmArgs(C.Structure):
                 ("stat_in", vp), ("cen", vp), ("publish", i32), ("stat_groups", i32), ("norm_dim", i32), ("rms", i32), ("eps", f32), ("wg", vp), ("cb", vp),
                 ("out_f32", vp), ("ld_out", i32), ("k_split", i32), ("part_stride", sz), ("split_ok", i32), ("x_in", vp), ("x_out", vp), ("act_out", vp), ("out_k_blocks", i32),
                 ("g_out", vp), ("stat_out", vp), ("act_kind", i32), ("am_val", vp), ("am_idx", vp),
-                ("next_tokens", vp), ("lens", vp * 8), ("n_lens", i32), ("commit_inc", i32)]
+                ("next_tokens", vp), ("lens", vp * 8), ("len_cap", i32 * 8), ("n_lens", i32), ("commit_inc", i32)]
 
 
 class AttnArgs(C.Structure):

@@ -243,6 +243,16 @@ def test_cost_model_pins():
     A = np.stack([np.ones(30), x.astype(np.float64)], axis=1)
     c0, c1 = np.linalg.solve(A.T @ A, A.T @ y)
     assert np.allclose(O.cost_fit([(2, int(a), float(b)) for a, b in zip(x, y)])[2]["dec"], (c0, c1))
+    # samples that noise tilts downwards: the best line whose slope is not negative (found here by a scan over
+    # slopes >= 0, each with its best intercept) is the constant through the mean, and Eq. (1)'s table stays monotone
+    xd, yd = np.array([512.0, 514, 516, 518, 520]), np.array([1.10, 1.13, 1.09, 1.08, 1.07])
+    sse = lambda c1: float(((yd - (yd.mean() - c1 * xd.mean()) - c1 * xd) ** 2).sum())
+    best = min(np.linspace(0.0, 0.02, 2001), key=sse)
+    down = O.cost_fit([(8, int(a), float(b)) for a, b in zip(xd, yd)])
+    assert best == 0.0 and np.allclose(down[8]["dec"], (yd.mean(), 0.0))
+    assert np.polyfit(xd, yd, 1)[0] < 0                                       # the unconstrained fit would fall
+    ld = O.cost_l_exe(down, 8, 512, 64)
+    assert all(b >= a for a, b in zip(ld, ld[1:]))
 
 
 def test_cost_model_matches_oracle():
