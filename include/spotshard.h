@@ -8,7 +8,7 @@
  * ss_prefill, ss_decode_step, their ss_stage_ forms, ss_kv_repack and ss_shard_reset
  * enqueue work on the given stream and return; outputs are valid after the stream
  * has been synchronized.  The calls that say so below synchronize the stream
- * themselves (creation, ss_committed_len, export / import, ss_tune_decode).  A shard
+ * themselves (creation, ss_committed_len, export / import).  A shard
  * is not thread-safe.  Every call returns
  * an ss_status; argument and state errors are found on the host before anything
  * is launched, and leave committed lengths and committed cache rows untouched.
@@ -216,12 +216,6 @@ ss_status ss_kv_import(ss_shard *shard, const void *host_src, const int32_t *len
 /* Geometry of the shard, for callers that size buffers: out[0..5] = layers, heads,
  * ffn columns, max_batch, max_seq, bytes per cache element. */
 ss_status ss_shard_geometry(const ss_shard *shard, int32_t out[6]);
-
-/* Time the candidate launch shapes of the decode GEMMs of this group at batch size B on the
- * device (real weights, nothing committed, scratch only) and keep the fastest per shape for the
- * process; shapes not timed follow a rule.  Optional; every shape gives the same bits.
- * Synchronizes the stream; SS_ESTATE while the stream is being captured. */
-ss_status ss_tune_decode(ss_shard *const *group, int32_t n_group, int32_t B, void *hip_stream);
 
 /* Text of the calling thread's last failure.  Plumbing of this boundary (the paper defines no
  * error interface; Section 4.2 only says what the system falls back to when a step or a migration

@@ -20,12 +20,13 @@ ss_status ss_debug_interrupt_after_layer(ss_shard *shard, int32_t layer);
  * kernels; 0: the kernels one by one.  Both give the same bits. */
 ss_status ss_set_graph_launch(ss_shard *shard, int32_t enabled);
 
-/* Test aid, process-wide: force the launch shape of the decode GEMMs built from now on (shards
- * that have already replayed a step keep their captured graph): weight tiles per block (1 or 2;
- * 0 = the library's choice) and, for more than 16 batch rows, whether the two batch tiles go to
- * separate blocks (2) or not (1; 0 = the library's choice).  The library chooses per shape, by a
- * rule, or from the timings ss_tune_decode has taken; every shape gives the same bits. */
-ss_status ss_debug_force_gemm_shape(int32_t tiles_per_block, int32_t batch_split);
+/* Test aid, process-wide: force the launch shape of the decode GEMMs built from now on (a shard's
+ * captured graphs are keyed by the forced shape, so the change takes effect at once): weight tiles per
+ * block at most (1, 2, 3 or 6; where a GEMM has no such kernel instance the nearest one; 0 = the
+ * library's choice) and the slices the q|k|v GEMM cuts K into (1..8; 0 = the library's choice; other
+ * GEMMs never cut K).  The library chooses per shape by a cost rule.  The tiles per block never change
+ * a bit of the result; the number of K slices changes the order of the q|k|v sums. */
+ss_status ss_debug_force_gemm_shape(int32_t tiles_per_block, int32_t k_slices);
 
 /* Test aid, process-wide: force the token block of the initial phase's tiled GEMMs (the initial
  * phase over all prompt tokens: the first term of Eq. (1) and Eq. (2)): 128 or 256 tokens per block; 0 = the library's choice,

@@ -80,7 +80,6 @@ def _load():
     L.ss_debug_force_gemm_shape.argtypes = [i32, i32]
     L.ss_debug_force_prefill_block.argtypes = [i32]
     L.ss_kernel_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), vp]
-    L.ss_tune_decode.argtypes = [C.POINTER(vp), i32, i32, vp]
     return L
 
 
@@ -239,12 +238,6 @@ def decode_step(group, tokens_in, logits=None, next_tokens=None, stream=None):
                               _stream(stream)))
 
 
-def tune_decode(group, B, stream=None):
-    """Time the decode GEMMs' candidate launch shapes at batch size B (synchronizes the stream)."""
-    arr, n = _group(group)
-    _check(lib.ss_tune_decode(arr, n, int(B), _stream(stream)))
-
-
 def stage_prefill(group, B, S, tokens=None, hidden_in=None, hidden_out=None, logits=None, next_tokens=None, stream=None):
     """A pipeline stage's initial phase: tokens (device int32 [B, S]) or hidden_in (device float32 [B*S, d]);
     hidden_out (device float32 [B*S, d]) or logits / next_tokens."""
@@ -275,9 +268,9 @@ def kv_repack(dst, src, batch_map, first_source=True, stream=None) -> int:
     return moved.value
 
 
-def force_gemm_shape(tiles_per_block: int = 0, batch_split: int = 0):
+def force_gemm_shape(tiles_per_block: int = 0, k_slices: int = 0):
     """Test aid: force the decode GEMMs' launch shape for plans built from now on (0, 0 = library's choice)."""
-    _check(lib.ss_debug_force_gemm_shape(int(tiles_per_block), int(batch_split)))
+    _check(lib.ss_debug_force_gemm_shape(int(tiles_per_block), int(k_slices)))
 
 
 def force_prefill_block(tokens_per_block: int = 0):

@@ -37,28 +37,6 @@ __device__ __forceinline__ void unpack16<f16_t>(const u32x4 &raw, float *out) {
   for (int i = 0; i < 8; ++i) out[i] = (float)h[i];
 }
 
-// q, k of the new token at position pos, rotated (half-split pairing) when a table is given.
-__device__ __forceinline__ float rope_elem(const float *v, int e, int half, const float2 *tab) {
-  if (!tab) return v[e];
-  if (e < half) {
-    float2 cs = tab[e];
-    return v[e] * cs.x - v[e + half] * cs.y;
-  }
-  float2 cs = tab[e - half];
-  return v[e - half] * cs.y + v[e] * cs.x;
-}
-// the same where the vector arrives as two partial sums (v2 != NULL): v + v2, element by element
-__device__ __forceinline__ float rope_elem2(const float *v, const float *v2, int e, int half, const float2 *tab) {
-  if (!v2) return rope_elem(v, e, half, tab);
-  if (!tab) return v[e] + v2[e];
-  if (e < half) {
-    float2 cs = tab[e];
-    return (v[e] + v2[e]) * cs.x - (v[e + half] + v2[e + half]) * cs.y;
-  }
-  float2 cs = tab[e - half];
-  return (v[e - half] + v2[e - half]) * cs.y + (v[e] + v2[e]) * cs.x;
-}
-
 // ---------------------------------------------------------------------------
 // decode attention.  grid = (B*Hs, splits); block = NWV waves.
 // Block (bh, s) covers committed rows [s*rpb, min((s+1)*rpb, n)); a lane group of LPR lanes
@@ -97,7 +75,7 @@ __device__ __forceinline__ void decode_attn_block(const DecodeAttnArgs &a, const
   const float scale = rsqrtf((float)DH);
   const float2 *tab = a.rope ? a.rope + (size_t)n * (DH / 2) : nullptr;
   const float *qraw = a.qkv + (size_t)b * 3 * HD + h * DH;
-  const float *qraw2 = a.qkv2 ? a.qkv2 + (size_t)b * 3 * HD + h * DH : nullptr;
+  const int qparts = a.qkv_parts > 1 ? a.qkv_parts : 1;
   const int c = lane % LPR, g = lane / LPR;
   const int r0 = sp * a.rows_per_block;
   const int r1 = min(r0 + a.rows_per_block, n);
@@ -162,9 +140,25 @@ __device__ __forceinline__ void decode_attn_block(const DecodeAttnArgs &a, const
     load(kB, vB, base + STRIDE);
     float kn = 0.f, vraw = 0.f;  // the new token's (rotated) key and value element of thread e
     if (tid < DH) {
-      kn = rope_elem2(qraw + HD, qraw2 ? qraw2 + HD : nullptr, tid, DH / 2, tab);
-      vraw = qraw[2 * HD + tid] + (qraw2 ? qraw2[2 * HD + tid] : 0.f);
-      sq[tid] = rope_elem2(qraw, qraw2, tid, DH / 2, tab);
+      // q | k | v of the new token: the GEMM's partial sums (it may have cut K into slices) added in slice
+      // order; q and k rotated to position n (half-split pairing) when the model has a rotation table
+      auto at = [&](int off) {
+        float v = qraw[off];
+        for (int p = 1; p < qparts; ++p) v += qraw[(size_t)p * a.qkv_stride + off];
+        return v;
+      };
+      constexpr int HALF = DH / 2;
+      const int e = tid, eo = e < HALF ? e + HALF : e - HALF;
+      float qe = at(e), ke = at(HD + e);
+      vraw = at(2 * HD + e);
+      if (tab) {
+        const float qo = at(eo), ko = at(HD + eo);
+        const float2 cs = tab[e < HALF ? e : e - HALF];
+        if (e < HALF) qe = qe * cs.x - qo * cs.y, ke = ke * cs.x - ko * cs.y;
+        else qe = qo * cs.y + qe * cs.x, ke = ko * cs.y + ke * cs.x;
+      }
+      kn = ke;
+      sq[tid] = qe;
     }
     __syncthreads();
 #pragma unroll

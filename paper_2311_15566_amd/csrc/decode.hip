@@ -3,6 +3,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <math.h>
+
 #include <algorithm>
 #include <atomic>
 #include <mutex>
@@ -177,71 +179,117 @@ static void attn_plan(const Layout &L, int B, int *rows_per_block, int *splits, 
 // the decode step as a list of phases
 // ---------------------------------------------------------------------------
 // ---------------------------------------------------------------------------
-// Launch shape of a decode GEMM: weight tiles per block (pairs share the activation fragments,
-// single tiles give twice the blocks) and, past 16 batch rows, whether the two batch tiles go to
-// separate blocks.  Neither changes a single bit of the result (the order of every sum is the
-// same), so the choice is free: a rule of thumb until the shape has been timed on this device,
-// then the fastest of the candidates (tune_decode_gemms), kept process-wide per shape.
+// Launch shape of a decode GEMM: the kernel instance (weight tiles per block at most), the number
+// of blocks the tiles are shared out over and, for the q|k|v GEMM, the slices K is cut into.  None
+// of the first two changes a single bit of the result (the order of every sum is the same), so the
+// choice is free; it is made per shape by a small cost model fitted to what this device shows
+// (kernel-class timings inside decode steps of the three large shards, a dozen shapes each):
+//  - a compute unit takes in about 45 GB/s whatever the source (weights from HBM, activation
+//    fragments from L2), so with at most one block a unit the largest block decides; a block reads
+//    its activation fragments once for all its tiles: more tiles a block, fewer bytes a unit;
+//  - a long stream from HBM runs at about 6.8 TB/s;
+//  - a kernel takes about the 6-norm of the two (near-equal bounds cost more than either);
+//  - at equal largest block, more blocks are slower (about 0.09 % of the HBM time per block), so
+//    an uneven share-out over all units loses to fewer blocks of one size;
+//  - with several rounds of blocks, instances that fit twice on a unit (up to 2 tiles a block for
+//    up to 16 batch rows, 1 tile above) stream about 15 % faster than the others, and the last
+//    round costs about half a block;
+//  - partial q|k|v sums cost the attention kernel that adds them a microsecond or two.
 // ---------------------------------------------------------------------------
-struct TuneKey {
-  int dtype, epi, row_tiles, k_blocks, B;
-  bool operator<(const TuneKey &o) const {
-    return std::tie(dtype, epi, row_tiles, k_blocks, B) < std::tie(o.dtype, o.epi, o.row_tiles, o.k_blocks, o.B);
+struct GemmShape {
+  int nw, n_blocks, k_split;
+};
+struct ShapeKey {
+  int epi, row_tiles, k_blocks, B, ks, split_max, split_cost_x10, forced_nw, forced_split;
+  bool operator<(const ShapeKey &o) const {
+    return std::tie(epi, row_tiles, k_blocks, B, ks, split_max, split_cost_x10, forced_nw, forced_split) <
+           std::tie(o.epi, o.row_tiles, o.k_blocks, o.B, o.ks, o.split_max, o.split_cost_x10, o.forced_nw, o.forced_split);
   }
 };
-struct TuneVal {
-  int nw, bt_split;
-};
-static std::map<TuneKey, TuneVal> g_tune;
-static std::mutex g_tune_mu;
-static std::atomic<uint64_t> g_shape_epoch{0};  // bumped when a forced or timed shape changes what a plan would hold
+static std::map<ShapeKey, GemmShape> g_shapes;
+static std::mutex g_shape_mu;
+static std::atomic<uint64_t> g_shape_epoch{0};  // bumped when a forced shape changes what a plan would hold
 static std::atomic<uint64_t> g_next_id{1};
 uint64_t next_shard_id() { return g_next_id.fetch_add(1); }
-static TuneVal g_forced = {0, 0};  // test aid: 0 = not forced
+static int g_forced_nw = 0, g_forced_split = 0;  // test aids: 0 = the rule's choice
 
-static TuneVal tune_rule(int epi, int row_tiles, int B);
-// Timed candidates: the split of the batch tiles over blocks (B > 16).  The number of weight tiles
-// per block follows the rule: timed in isolation the GEMMs run out of the memory-side cache, where
-// one tile per block can look faster than it is inside a step that streams every weight once.
-static std::vector<TuneVal> tune_candidates(int epi, int row_tiles, int B) {
-  std::vector<TuneVal> c;
-  const int nw = tune_rule(epi, row_tiles, B).nw;
-  for (int bt = 1; bt <= (B > 16 ? 2 : 1); ++bt) c.push_back(TuneVal{nw, bt});
-  return c;
-}
-static TuneVal tune_rule(int epi, int row_tiles, int B) {
-  const int pairs = ceil_div(row_tiles, 2);
-  TuneVal v;
-  v.bt_split = (B > 16 && pairs * 2 <= 256) ? 2 : 1;
-  v.nw = (epi == EPI_SWIGLU || epi == EPI_LOGITS || pairs * v.bt_split >= 128) ? 2 : 1;
-  // a few more tile pairs than the 256 compute units: the blocks of a second, mostly empty round would each
-  // run at what one compute unit takes in; three tiles a block keep it to one round
-  if ((epi == EPI_F32 || epi == EPI_ACT) && v.bt_split == 1 && pairs > 256 && ceil_div(row_tiles, 3) <= 256) v.nw = 3;
-  return v;
-}
-static void shape_gemm(StreamGemmArgs &a, int dtype, int epi) {
-  TuneVal v = tune_rule(epi, a.row_tiles, a.B);
-  {
-    std::lock_guard<std::mutex> lock(g_tune_mu);
-    auto it = g_tune.find(TuneKey{dtype, epi, a.row_tiles, a.k_blocks, a.B});
-    if (it != g_tune.end()) v = it->second;
-    if (g_forced.nw && epi != EPI_SWIGLU && epi != EPI_LOGITS) v.nw = g_forced.nw;
-    if (g_forced.bt_split) v.bt_split = a.B > 16 ? g_forced.bt_split : 1;
+constexpr int kComputeUnits = 256;
+constexpr double kUnitKiBPerUs = 45.0e9 / 1024.0 / 1.0e6;   // what one compute unit takes in
+constexpr double kHbmKiBPerUs = 6.8e12 / 1024.0 / 1.0e6;    // a long stream from HBM
+
+// estimated microseconds of streaming (without the few microseconds every launch costs); two_fit: two blocks of the instance fit on a unit
+static double shape_cost(int tu, int units, int k_blocks, double act, bool two_fit, int n_blocks, int S, double split_cost) {
+  const int upb = ceil_div(units, n_blocks);                  // units of the largest block
+  const double kslice = (double)ceil_div(k_blocks, S);
+  const int blocks = n_blocks * S;
+  const double largest = ((double)upb * tu + act) * kslice;   // KiB the largest block takes in
+  double t_cu;
+  if (blocks <= kComputeUnits) {
+    t_cu = largest / kUnitKiBPerUs;
+  } else {
+    const double total = ((double)units * tu + (double)n_blocks * act) * k_blocks;  // KiB all blocks take in
+    t_cu = total / (kComputeUnits * kUnitKiBPerUs) * (two_fit ? 1.0 : 1.15) + 0.5 * largest / kUnitKiBPerUs;
   }
-  a.nw = v.nw, a.bt_split = v.bt_split;
-  if (a.nw == 3 && a.ks != 8) a.nw = 2;  // three tiles need six epilogue waves
-  // A q|k|v matrix with fewer tile pairs than compute units (every block bound by what one unit takes
-  // in): K in two halves, three tiles a block, so that more units share the bytes more evenly; the two
-  // partial sums are added by the attention kernel.  Not with a forced shape (a test aid).
-  a.k_split = 1, a.part_stride = 0;
-  {
-    const int pairs = ceil_div(a.row_tiles, 2);
-    const bool forced = g_forced.nw || g_forced.bt_split;
-    if (epi == EPI_F32 && a.split_ok && !forced && a.B <= 16 && a.bt_split == 1 && a.ks == 8 && a.k_blocks >= 64 && pairs >= 100 &&
-        pairs < 256 && ceil_div(a.row_tiles, 3) * 2 <= 256)
-      a.nw = 3, a.k_split = 2, a.part_stride = (size_t)32 * a.ld_out;
+  const double t_hbm = (double)units * tu * k_blocks / kHbmKiBPerUs;
+  const double norm6 = std::pow(std::pow(t_cu, 6.0) + std::pow(t_hbm, 6.0), 1.0 / 6.0);
+  return norm6 + 0.00086 * t_hbm * std::min(blocks, kComputeUnits) + (S > 1 ? split_cost + 0.3 * (S - 2) : 0.0);
+}
+
+static GemmShape shape_rule(int epi, int row_tiles, int k_blocks, int B, int ks, int split_max, double split_cost,
+                            int forced_nw, int forced_split) {
+  const int tu = epi == EPI_SWIGLU ? 2 : 1, units = row_tiles / tu;
+  const double act = B <= 8 ? 0.5 : (B <= 16 ? 1.0 : 2.0);   // KiB of activation fragments per k block a block reads
+  const bool wide = B <= 16 && (epi == EPI_F32 || epi == EPI_SWIGLU);
+  std::vector<int> instances;
+  if (epi == EPI_SWIGLU) instances = {2};
+  else instances = {1, 2, 3};
+  if (wide) instances.push_back(6);
+  if (forced_nw) {  // the nearest instance this GEMM has
+    int nw = forced_nw;
+    if (epi == EPI_SWIGLU) nw = (forced_nw >= 6 && wide) ? 6 : 2;
+    else if (nw > 3) nw = (nw == 6 && wide) ? 6 : 3;
+    instances = {nw};
   }
-  a.n_blocks = stream_gemm_blocks(epi, a);
+  GemmShape best = {0, 0, 1};
+  double best_t = 0;
+  for (int S = 1; S <= std::max(1, split_max); ++S) {
+    if (forced_split && S != forced_split) continue;
+    if (S > 1 && k_blocks < S * ks) continue;
+    for (int nw : instances) {
+      const int upb_max = nw / tu;
+      const bool two_fit = B <= 16 ? nw <= 2 : nw <= 1;
+      // block counts worth a look: the fewest for every size of the largest block (with a forced instance: its full size only)
+      for (int upb = upb_max; upb >= 1; --upb) {
+        const int n_blocks = ceil_div(units, upb);
+        if (ceil_div(units, n_blocks) != upb) continue;       // the same share-out as a smaller size
+        const double t = shape_cost(tu, units, k_blocks, act, two_fit, n_blocks, S, split_cost);
+        if (!best.nw || t < best_t) best = {nw, n_blocks, S}, best_t = t;
+        if (forced_nw) break;
+      }
+    }
+  }
+  if (!best.nw) best = {epi == EPI_SWIGLU ? 2 : 1, units, 1};
+  return best;
+}
+
+static void shape_gemm(StreamGemmArgs &a, int epi) {
+  const int split_max = (epi == EPI_F32 && a.split_ok > 1) ? std::min(a.split_ok, 8) : 1;
+  GemmShape v;
+  {
+    std::lock_guard<std::mutex> lock(g_shape_mu);
+    const int forced_split = std::min(g_forced_split, split_max);
+    const ShapeKey key{epi, a.row_tiles, a.k_blocks, a.B, a.ks, split_max, (int)(a.split_cost_us * 10.f), g_forced_nw, forced_split};
+    auto it = g_shapes.find(key);
+    if (it == g_shapes.end())
+      it = g_shapes.emplace(key, shape_rule(epi, a.row_tiles, a.k_blocks, a.B, a.ks, split_max, a.split_cost_us, g_forced_nw, forced_split)).first;
+    v = it->second;
+  }
+  a.nw = v.nw, a.n_blocks = v.n_blocks, a.k_split = v.k_split;
+  {
+    const int units = epi == EPI_SWIGLU ? a.row_tiles / 2 : a.row_tiles;
+    a.u_base = units / a.n_blocks, a.u_rem = units % a.n_blocks, a.k_slice = ceil_div(a.k_blocks, std::max(1, a.k_split));
+  }
+  a.part_stride = v.k_split > 1 ? (size_t)32 * a.ld_out : 0;
 }
 static int pick_ks(int k_blocks) { return k_blocks >= 16 ? 8 : 4; }  // waves per block
 
@@ -253,20 +301,21 @@ static Phase lm_head_phase(Shard *const *group, int n_group, int B, int stat_gro
   Phase ph = {};
   ph.kind = PH_LM_HEAD;
   StreamGemmArgs &a = ph.g;
+  a.zero_frag = g0->zero_frag;
   a.w = g0->lm_head.ptr, a.row_tiles = g0->lm_head.row_tiles, a.k_blocks = g0->lm_head.k_blocks, a.B = B, a.N = L.V;
   a.ks = pick_ks(a.k_blocks);
-  a.act = g0->ws + L.ws_ad;
-  a.stat_in = (const float *)(g0->ws + L.ws_statd), a.stat_groups = stat_groups, a.norm_dim = L.d;
+  a.act = g0->dec_at(L.ws_ad);
+  a.stat_in = (const float *)(g0->dec_at(L.ws_statd)), a.stat_groups = stat_groups, a.norm_dim = L.d;
   a.rms = g0->m.norm == SS_NORM_RMSNORM, a.eps = g0->m.norm_eps;
   a.wg = g0->wg_lm, a.cb = g0->cb_lm;
   a.out_f32 = logits, a.ld_out = L.V;
-  a.am_val = (float *)(g0->ws + L.ws_argmax);
-  a.am_idx = (int *)(a.am_val + (size_t)ceil_div(a.row_tiles, 2) * 32);
+  a.am_val = (float *)(g0->dec_at(L.ws_argmax));
   a.next_tokens = next_tokens;
   for (int i = 0; i < n_group; ++i) a.lens[i] = group[i]->d_len, a.len_cap[i] = group[i]->L.Smax;
   a.n_lens = n_group, a.commit_inc = commit_inc;
-  shape_gemm(a, g0->m.dtype, EPI_LOGITS);
-  ph.gx = a.n_blocks * a.bt_split, ph.gy = 1;
+  shape_gemm(a, EPI_LOGITS);
+  a.am_idx = (int *)(a.am_val + (size_t)32 * a.n_blocks);  // [32][n_blocks] values, then as many indices
+  ph.gx = a.n_blocks, ph.gy = 1;
   return ph;
 }
 
@@ -284,10 +333,10 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
   const int dt = m.dtype, d = L0.d;
   const int FK = dt == SS_DTYPE_BF16 ? 32 : 16;
   const int rms = m.norm == SS_NORM_RMSNORM;
-  float *x = (float *)(g0->ws + L0.ws_xd);
-  void *ad = g0->ws + L0.ws_ad;
-  float *statd = (float *)(g0->ws + L0.ws_statd);
-  float *cen = rms ? nullptr : (float *)(g0->ws + L0.ws_cen);  // the rows' means at the last norm: centres of the next operand
+  float *x = (float *)(g0->dec_at(L0.ws_xd));
+  void *ad = g0->dec_at(L0.ws_ad);
+  float *statd = (float *)(g0->dec_at(L0.ws_statd));
+  float *cen = rms ? nullptr : (float *)(g0->dec_at(L0.ws_cen));  // the rows' means at the last norm: centres of the next operand
   const float *first_gamma = g0->layers[0].ln1_g;
   plan->clear();
   {
@@ -310,6 +359,7 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
     Phase ph = {};
     ph.kind = PH_RESID, ph.shard = i;
     StreamGemmArgs &a = ph.g;
+    a.zero_frag = g0->zero_frag;
     a.w = w.ptr, a.row_tiles = w.row_tiles, a.k_blocks = w.k_blocks, a.ks = pick_ks(a.k_blocks), a.B = B, a.N = d;
     a.act = act;
     a.cb = i == 0 ? bias : nullptr;
@@ -318,11 +368,12 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
       if (x_final) a.x_out = x_final;  // the stage's output: no next GEMM in this shard
       else a.act_out = ad, a.out_k_blocks = d / FK, a.g_out = next_gamma, a.stat_out = statd, a.cen = cen;
     }
-    shape_gemm(a, dt, EPI_RESID);
-    ph.gx = a.n_blocks * a.bt_split, ph.gy = 1;
+    shape_gemm(a, EPI_RESID);
+    ph.gx = a.n_blocks, ph.gy = 1;
     plan->push_back(ph);
   };
-  size_t qkv_split[8] = {0};  // per shard of the group: distance (floats) to the second partial q|k|v, 0 = one sum
+  int qkv_parts[8] = {0};     // per shard of the group: partial q|k|v sums its GEMM leaves and their distance (floats)
+  size_t qkv_stride[8] = {0};
   for (int l = 0; l < L0.Ls; ++l) {
     const LayerDev &D0 = g0->layers[l];
     for (int i = 0; i < n_group; ++i) {  // QKV projection of the new token
@@ -331,14 +382,16 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
       Phase ph = {};
       ph.kind = PH_QKV, ph.shard = i;
       StreamGemmArgs &a = ph.g;
+      a.zero_frag = s->zero_frag;
       a.w = s->wqkv[l].ptr, a.row_tiles = s->wqkv[l].row_tiles, a.k_blocks = s->wqkv[l].k_blocks, a.B = B, a.N = L.qkv_n;
       a.ks = pick_ks(a.k_blocks);
       normed(a, s->wg_qkv[l], s->cb_qkv[l], i);
-      a.out_f32 = (float *)(s->ws + L.ws_qkvd), a.ld_out = L.qkv_n;
-      a.split_ok = 1;  // the consumer (decode attention) can add two partial sums
-      shape_gemm(a, dt, EPI_F32);
-      ph.gx = a.n_blocks * a.bt_split * a.k_split, ph.gy = 1;
-      qkv_split[i] = a.k_split == 2 ? a.part_stride : 0;
+      a.out_f32 = (float *)(s->dec_at(L.ws_qkvd)), a.ld_out = L.qkv_n;
+      a.split_ok = kQkvParts;  // the consumer (decode attention) adds up to that many partial sums,
+      a.split_cost_us = m.pos == SS_POS_ROPE ? 2.5f : 1.0f;  // which costs it this much (more where it rotates q and k: measured)
+      shape_gemm(a, EPI_F32);
+      ph.gx = a.n_blocks * a.k_split, ph.gy = 1;
+      qkv_parts[i] = a.k_split, qkv_stride[i] = a.part_stride;
       plan->push_back(ph);
     }
     for (int i = 0; i < n_group; ++i) {  // attention over the committed rows + append
@@ -347,14 +400,14 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
       Phase ph = {};
       ph.kind = PH_ATTN, ph.shard = i;
       DecodeAttnArgs &a = ph.at;
-      a.qkv = (const float *)(s->ws + L.ws_qkvd);
-      a.qkv2 = qkv_split[i] ? a.qkv + qkv_split[i] : nullptr;
+      a.qkv = (const float *)(s->dec_at(L.ws_qkvd));
+      a.qkv_parts = qkv_parts[i], a.qkv_stride = qkv_stride[i];
       a.k_cache = s->kv_ptr(l, 0), a.v_cache = s->kv_ptr(l, 1);
       a.row_stride = s->kv_row_stride(), a.head_stride = s->kv_head_stride();
       a.lens = s->d_len, a.rope = m.pos == SS_POS_ROPE ? s->rope : nullptr;
-      a.part = (float *)(s->ws + L.ws_attn_part);
-      a.counters = (int *)(s->ws + L.ws_counters) + 16;
-      a.o_out = s->ws + L.ws_od;
+      a.part = (float *)(s->dec_at(L.ws_attn_part));
+      a.counters = (int *)(s->dec_at(L.ws_counters)) + 16;
+      a.o_out = s->dec_at(L.ws_od);
       a.B = B, a.Hs = L.Hs, a.Dh = L.Dh, a.Smax = L.Smax, a.kv_dtype = s->m.kv_dtype;
       attn_plan(L, B, &a.rows_per_block, &a.splits, &a.waves);
       ph.gx = B * L.Hs, ph.gy = a.splits;
@@ -362,24 +415,25 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
     }
     stat_groups = d / 32;  // from here on the partial sums come from the residual GEMMs' weight tile pairs
     for (int i = 0; i < n_group; ++i)  // output projection, sum over the group, residual
-      resid(i, group[i]->wo[l], group[i]->ws + group[i]->L.ws_od, D0.bo, D0.ln2_g, nullptr);
+      resid(i, group[i]->wo[l], group[i]->dec_at(group[i]->L.ws_od), D0.bo, D0.ln2_g, nullptr);
     for (int i = 0; i < n_group; ++i) {  // first FFN matrix + activation
       Shard *s = group[i];
       const Layout &L = s->L;
       Phase ph = {};
       ph.kind = PH_FFN_UP, ph.shard = i;
       StreamGemmArgs &a = ph.g;
+      a.zero_frag = s->zero_frag;
       a.w = s->w1[l].ptr, a.row_tiles = s->w1[l].row_tiles, a.k_blocks = s->w1[l].k_blocks, a.B = B, a.N = L.Fs;
       a.ks = pick_ks(a.k_blocks);
       normed(a, s->wg_1[l], s->cb_1[l], i);
-      a.act_out = s->ws + L.ws_ud, a.out_k_blocks = L.Fs / FK, a.act_kind = m.act;
-      shape_gemm(a, dt, m.act == SS_ACT_SWIGLU ? EPI_SWIGLU : EPI_ACT);
-      ph.gx = a.n_blocks * a.bt_split, ph.gy = 1;
+      a.act_out = s->dec_at(L.ws_ud), a.out_k_blocks = L.Fs / FK, a.act_kind = m.act;
+      shape_gemm(a, m.act == SS_ACT_SWIGLU ? EPI_SWIGLU : EPI_ACT);
+      ph.gx = a.n_blocks, ph.gy = 1;
       plan->push_back(ph);
     }
     const float *next_gamma = l + 1 < L0.Ls ? g0->layers[l + 1].ln1_g : g0->lnf_g;
     for (int i = 0; i < n_group; ++i)  // second FFN matrix, sum over the group, residual
-      resid(i, group[i]->w2[l], group[i]->ws + group[i]->L.ws_ud, D0.b2, next_gamma,
+      resid(i, group[i]->w2[l], group[i]->dec_at(group[i]->L.ws_ud), D0.b2, next_gamma,
             l + 1 == L0.Ls ? hidden_out : nullptr);
     if (l == stop_after_layer) return;
   }
@@ -448,98 +502,10 @@ static ss_status launch_phase(Shard *g0, const Phase &ph, hipStream_t st) {
   SS_FAIL(SS_EINVAL, "unknown phase kind %d", ph.kind);
 }
 
-static int gemm_epilogue_of(const Shard *g0, int kind) {
-  switch (kind) {
-    case PH_QKV: return EPI_F32;
-    case PH_RESID: return EPI_RESID;
-    case PH_FFN_UP: return g0->m.act == SS_ACT_SWIGLU ? EPI_SWIGLU : EPI_ACT;
-    case PH_LM_HEAD: return EPI_LOGITS;
-  }
-  return -1;
-}
-
-// Time the candidate launch shapes of every decode GEMM shape of this group at batch B that has
-// not been timed in this process, on the real weights (one launch per layer in turn, so repeats do
-// not hit in the caches), and keep the fastest.  Runs on `st` before the step's own kernels and
-// synchronises; everything it overwrites (q|k|v, operand fragments, row sums, argmax partials,
-// the initial phase's scratch) is rewritten by the step before it is read; nothing is committed.
-static ss_status tune_decode_gemms(Shard *const *group, int n_group, int B, hipStream_t st) {
-  Shard *g0 = group[0];
-  const int dt = g0->m.dtype;
-  std::vector<Phase> plan;
-  build_decode_plan(group, n_group, (const int32_t *)g0->d_len, nullptr, B, nullptr, nullptr, nullptr, -1, &plan);
-  std::map<TuneKey, std::vector<const Phase *>> by_shape;
-  for (const Phase &ph : plan) {
-    const int epi = gemm_epilogue_of(g0, ph.kind);
-    if (epi < 0) continue;
-    const TuneKey key{dt, epi, ph.g.row_tiles, ph.g.k_blocks, B};
-    std::lock_guard<std::mutex> lock(g_tune_mu);
-    if (!g_tune.count(key)) by_shape[key].push_back(&ph);
-  }
-  if (by_shape.empty()) return SS_OK;
-  hipEvent_t e0 = nullptr, e1 = nullptr;
-  SS_HIP(hipEventCreate(&e0));
-  if (hipEventCreate(&e1) != hipSuccess) {
-    (void)hipEventDestroy(e0);
-    SS_FAIL(SS_EHIP, "hipEventCreate failed");
-  }
-  ss_status rc = SS_OK;
-  for (auto &kv : by_shape) {
-    const TuneKey &key = kv.first;
-    const std::vector<const Phase *> &phs = kv.second;
-    const std::vector<TuneVal> cands = tune_candidates(key.epi, key.row_tiles, B);
-    // the rule's shape stays unless another one is clearly (3 %) faster: near-equal shapes would
-    // otherwise flip from run to run on timing noise
-    const TuneVal rule = tune_rule(key.epi, key.row_tiles, B);
-    TuneVal best = rule;
-    float best_ms = -1.f, rule_ms = -1.f;
-    std::vector<std::pair<float, TuneVal>> timed;
-    for (const TuneVal &c : cands) {
-      if (cands.size() == 1) break;
-      const int reps = 8;
-      size_t turn = 0;
-      for (int r = -1; r < reps && rc == SS_OK; ++r) {  // r = -1: an untimed first launch
-        if (r == 0 && hipEventRecord(e0, st) != hipSuccess) rc = SS_EHIP;
-        const Phase *ph = phs[turn++ % phs.size()];
-        const Shard *owner = group[ph->shard];
-        StreamGemmArgs g = ph->g;
-        g.nw = (c.nw == 3 && g.ks != 8) ? 2 : c.nw, g.bt_split = c.bt_split;
-        g.n_blocks = stream_gemm_blocks(key.epi, g);
-        if (key.epi == EPI_RESID) g.x_out = (float *)(owner->ws + owner->L.ws_x);  // leave the residual stream alone
-        if (key.epi == EPI_LOGITS) g.out_f32 = nullptr, g.next_tokens = nullptr, g.n_lens = 0;
-        rc = launch_stream_gemm(dt, key.epi, g, st);
-      }
-      if (rc != SS_OK) break;
-      float ms = 0.f;
-      if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
-          hipEventElapsedTime(&ms, e0, e1) != hipSuccess) {
-        set_error("timing a decode GEMM shape failed");
-        rc = SS_EHIP;
-        break;
-      }
-      timed.push_back({ms, c});
-      if (c.nw == rule.nw && c.bt_split == rule.bt_split) rule_ms = ms;
-    }
-    if (rc != SS_OK) break;
-    for (auto &t : timed) {
-      const bool is_rule = t.second.nw == rule.nw && t.second.bt_split == rule.bt_split;
-      const float bar = (rule_ms >= 0.f && !is_rule) ? 0.97f * rule_ms : rule_ms;
-      if (is_rule) continue;
-      if ((bar < 0.f || t.first < bar) && (best_ms < 0.f || t.first < best_ms)) best_ms = t.first, best = t.second;
-    }
-    std::lock_guard<std::mutex> lock(g_tune_mu);
-    g_tune[key] = best;
-    g_shape_epoch.fetch_add(1);
-  }
-  (void)hipEventDestroy(e0);
-  (void)hipEventDestroy(e1);
-  return rc;
-}
-
 static ss_status enqueue_decode(Shard *const *group, int n_group, const int32_t *tokens_in, const float *hidden_in, int B,
                                 float *hidden_out, float *logits, int32_t *next_tokens, hipStream_t st,
                                 int stop_after_layer) {
-  std::vector<Phase> plan;
+  static thread_local std::vector<Phase> plan;  // kept between steps: no host allocation after a thread's first step
   build_decode_plan(group, n_group, tokens_in, hidden_in, B, hidden_out, logits, next_tokens, stop_after_layer, &plan);
   for (const Phase &ph : plan) SS_TRY(launch_phase(group[0], ph, st));
   if (stop_after_layer >= 0)
@@ -695,10 +661,10 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, c
     for (int i = 0; i < n_group; ++i) c.lens[i] = group[i]->d_len, c.len_cap[i] = group[i]->L.Smax;
     return launch_commit(c, st);
   }
-  float *xd = (float *)(g0->ws + L0.ws_xd);
-  void *ad = g0->ws + L0.ws_ad;
-  float *statd = (float *)(g0->ws + L0.ws_statd);
-  float *cen = rms ? nullptr : (float *)(g0->ws + L0.ws_cen);
+  float *xd = (float *)(g0->dec_at(L0.ws_xd));
+  void *ad = g0->dec_at(L0.ws_ad);
+  float *statd = (float *)(g0->dec_at(L0.ws_statd));
+  float *cen = rms ? nullptr : (float *)(g0->dec_at(L0.ws_cen));
   if (dt == SS_DTYPE_BF16) hipLaunchKernelGGL(gather_last<bf16_t>, dim3(B), dim3(256), 0, st, x, S, xd, g0->lnf_g, ad, statd, cen, d, rms);
   else hipLaunchKernelGGL(gather_last<float>, dim3(B), dim3(256), 0, st, x, S, xd, g0->lnf_g, ad, statd, cen, d, rms);
   SS_HIP(hipGetLastError());
@@ -769,11 +735,11 @@ int32_t ss_debug_plan(const ss_model_desc *desc, const ss_slice *slice, int32_t 
   return n;
 }
 
-ss_status ss_debug_force_gemm_shape(int32_t tiles_per_block, int32_t batch_split) {
-  if (tiles_per_block < 0 || tiles_per_block > 2 || batch_split < 0 || batch_split > 2)
-    SS_FAIL(SS_EINVAL, "launch shape (%d, %d)", tiles_per_block, batch_split);
-  std::lock_guard<std::mutex> lock(g_tune_mu);
-  g_forced = TuneVal{tiles_per_block, batch_split};
+ss_status ss_debug_force_gemm_shape(int32_t tiles_per_block, int32_t k_slices) {
+  if (tiles_per_block < 0 || tiles_per_block > 6 || k_slices < 0 || k_slices > 8)
+    SS_FAIL(SS_EINVAL, "launch shape (%d, %d)", tiles_per_block, k_slices);
+  std::lock_guard<std::mutex> lock(g_shape_mu);
+  g_forced_nw = tiles_per_block, g_forced_split = k_slices;
   g_shape_epoch.fetch_add(1);
   return SS_OK;
 }
@@ -799,10 +765,8 @@ ss_status ss_kernel_timing_read(ss_shard *shard, double ms[8], int64_t count[8],
   return SS_OK;
 }
 
-ss_status ss_stage_decode_step(ss_shard *const *group_, int32_t n_group, const int32_t *tokens_in, const float *hidden_in,
-                               int32_t B, float *hidden_out, float *logits, int32_t *next_tokens, void *hip_stream) {
-  Shard *const *group = (Shard *const *)group_;
-  SS_TRY(check_stage_io(tokens_in, hidden_in, hidden_out, logits, next_tokens));
+// what every decode-step entry point checks on the host before anything is launched
+static ss_status check_decode_state(Shard *const *group, int n_group, int B) {
   SS_TRY(check_group(group, n_group, B));
   for (int b = 0; b < B; ++b) {
     const int n = group[0]->h_len[b];
@@ -812,6 +776,14 @@ ss_status ss_stage_decode_step(ss_shard *const *group_, int32_t n_group, const i
       if (n + 1 > group[i]->L.Smax) SS_FAIL(SS_ESTATE, "row %d: cache of group[%d] is full (%d rows)", b, i, n);
     }
   }
+  return SS_OK;
+}
+
+ss_status ss_stage_decode_step(ss_shard *const *group_, int32_t n_group, const int32_t *tokens_in, const float *hidden_in,
+                               int32_t B, float *hidden_out, float *logits, int32_t *next_tokens, void *hip_stream) {
+  Shard *const *group = (Shard *const *)group_;
+  SS_TRY(check_stage_io(tokens_in, hidden_in, hidden_out, logits, next_tokens));
+  SS_TRY(check_decode_state(group, n_group, B));
   int stop = -1;
   for (int i = 0; i < n_group; ++i) stop = std::max(stop, group[i]->interrupt_after);
   ss_status rc = run_decode_step(group, n_group, tokens_in, hidden_in, B, hidden_out, logits, next_tokens,
@@ -820,15 +792,6 @@ ss_status ss_stage_decode_step(ss_shard *const *group_, int32_t n_group, const i
   for (int i = 0; i < n_group; ++i)
     for (int b = 0; b < B; ++b) group[i]->h_len[b] += 1;
   return SS_OK;
-}
-
-ss_status ss_tune_decode(ss_shard *const *group_, int32_t n_group, int32_t B, void *hip_stream) {
-  Shard *const *group = (Shard *const *)group_;
-  SS_TRY(check_group(group, n_group, B));
-  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-  if (hip_stream) SS_HIP(hipStreamIsCapturing((hipStream_t)hip_stream, &cs));
-  if (cs != hipStreamCaptureStatusNone) SS_FAIL(SS_ESTATE, "the stream is being captured: timing would synchronize it");
-  return tune_decode_gemms(group, n_group, B, (hipStream_t)hip_stream);
 }
 
 ss_status ss_decode_step(ss_shard *const *group_, int32_t n_group, const int32_t *tokens_in, int32_t B, float *logits,

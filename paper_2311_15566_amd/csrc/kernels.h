@@ -6,6 +6,7 @@
 namespace ss {
 
 enum Epilogue { EPI_F32 = 0, EPI_RESID = 1, EPI_ACT = 2, EPI_SWIGLU = 3, EPI_LOGITS = 4 };
+constexpr int kQkvParts = 8;  // partial q|k|v sums a decode step's workspace holds (slices the q|k|v GEMM may cut K into)
 
 // Element type of both operands of the GEMMs for a model of element type T.  bf16 models: halves.
 // Activations need more than bf16's 8 significant bits to stay under the logits bar, a half has 11;
@@ -16,10 +17,13 @@ template <typename T> struct Operand { typedef T type; };
 template <> struct Operand<bf16_t> { typedef f16_t type; };
 
 // Weight-streaming GEMM of the decode step: out[b, n] = sum_k act[b, k] * W[n, k], b < B <= 32.
-// HBM-bound.  One block owns a pair of 16-row weight tiles (SwiGLU: a gate/up pair) over the
-// whole of K; its waves split K between them, each streaming 1 KiB weight fragments and the
-// matching activation fragments (from L2) straight into registers, and add their sums up
-// through LDS, so nothing of the product goes through memory and no block waits for another.
+// HBM-bound.  The matrix's 16-row weight tiles (SwiGLU: gate/up pairs) are shared out evenly over
+// n_blocks blocks, at most nw tiles each, over the whole of K (the q|k|v GEMM may also cut K into
+// k_split slices for k_split times the blocks: its consumer adds the partial outputs); a block's
+// waves split its K range between them, each streaming 1 KiB weight fragments and the matching
+// activation fragments (from L2, shared by all the block's tiles) straight into registers, and add
+// their sums up through LDS, so nothing of the product goes through memory and no block waits for
+// another.
 //
 // Deferred, centred normalisation: where the GEMM input is Norm(x) = (x - mean) * rstd * gamma + beta,
 // the operand holds (x - c) * gamma, written by the producer of x before the row statistics exist,
@@ -34,12 +38,14 @@ struct StreamGemmArgs {
   int row_tiles;        // 16-row tiles (SwiGLU: gate/up tiles interleaved, 2 per 16 outputs)
   int k_blocks;
   int ks;               // waves per block = slices of K (4 or 8)
-  int nw;               // weight tiles per block: 2 (always for SwiGLU pairs) or 1
-  int n_blocks;         // tile-pair blocks = ceil(row_tiles / nw)
-  int bt_split;         // 1, or 2: the two 16-row batch tiles of B > 16 go to separate blocks
+  int nw;               // weight tiles per block at most (the kernel instance): 1, 2, 3 or 6; SwiGLU: 2 or 6 (whole pairs)
+  int n_blocks;         // blocks the tiles (SwiGLU: pairs) are shared out over, evenly: ceil(units / n_blocks) * tiles per unit <= nw
+  int u_base, u_rem;    // units / n_blocks and units % n_blocks: block g owns u_base + (g < u_rem) units, in order
+  int k_slice;          // k blocks a block covers: ceil(k_blocks / max(1, k_split))
   int B;                // live batch rows
   int N;                // logical output features (for masking)
   const void *act;      // operand fragments [B tiles][k_blocks]
+  const void *zero_frag;  // 1 KiB of zeros: the activation fragment of a batch row or a k block that does not exist
   // deferred normalisation (stat_groups > 0)
   const float *stat_in; // [stat_groups][32][4]: two partial (sum, sum of squares) pairs of the rows of x - c per entry
   float *cen;           // [32] or NULL (RMSNorm).  Consumer with publish: cen[b] += mean - c by block 0; EPI_RESID: the centre c
@@ -53,9 +59,10 @@ struct StreamGemmArgs {
   // epilogues
   float *out_f32;       // EPI_F32 / EPI_LOGITS: [B][ld_out]
   int ld_out;
-  int k_split;          // EPI_F32: 2 = two blocks per tile group over half of K each, partial outputs at out_f32 and
-  size_t part_stride;   //   out_f32 + part_stride (floats) for the consumer to add up; 0 or 1 = whole K per block
-  int split_ok;         //   set by the plan where the consumer can add two partial sums (the launch rule may then split)
+  int k_split;          // EPI_F32: S = 2..8 blocks per tile group over a slice of K each, partial outputs at
+  size_t part_stride;   //   out_f32 + s * part_stride (floats) for the consumer to add up in order; 0 or 1 = whole K per block
+  int split_ok;         //   the most slices the consumer can add (0 or 1: none; set by the plan, the launch rule may then split)
+  float split_cost_us;  //   and what adding partial sums costs the consumer (microseconds, for the launch rule)
   const float *x_in;    // EPI_RESID: residual stream before this GEMM, [B][N]
   float *x_out;         // EPI_RESID: after it (may equal x_in)
   void *act_out;        // EPI_ACT / EPI_SWIGLU: activation fragments; EPI_RESID: (x_out - c) * g_out (or NULL)
@@ -74,7 +81,7 @@ struct StreamGemmArgs {
 };
 ss_status launch_stream_gemm(int dtype, int epi, const StreamGemmArgs &a, hipStream_t st);
 ss_status check_stream_gemm(int dtype, int epi, const StreamGemmArgs &a);  // the shape checks the launcher makes
-int stream_gemm_blocks(int epi, const StreamGemmArgs &a);
+int stream_gemm_units_per_block(int epi, const StreamGemmArgs &a);  // units (tiles, SwiGLU: pairs) of the largest block
 // wg / cb of a weight matrix in fragment order (gamma NULL: wg is not written)
 ss_status launch_fold_norm(int dtype, const void *w, int row_tiles, int k_blocks, const float *gamma, const float *beta,
                            const float *bias, float *wg, float *cb, hipStream_t st);
@@ -127,7 +134,8 @@ ss_status launch_row_stats(const float2 *part, int groups, int T, int norm_dim, 
 // Decode attention over the committed cache (plus the new token), sequence-split.
 struct DecodeAttnArgs {
   const float *qkv;     // [B][3*Hs*Dh] float32: q | k | v of the new token, biases applied
-  const float *qkv2;    // a second partial sum of the same shape to add to qkv (the GEMM split K over two blocks), or NULL
+  int qkv_parts;        // partial sums of that shape to add up in order (the GEMM cut K into slices), qkv_stride floats apart; 0 or 1: none
+  size_t qkv_stride;
   char *k_cache, *v_cache;   // this layer's planes: [Bmax][Hs][Smax][Dh]
   size_t row_stride, head_stride;  // bytes
   const int32_t *lens;  // committed lengths (device)

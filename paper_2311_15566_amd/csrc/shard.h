@@ -31,7 +31,7 @@ struct Layout {
   size_t lo_ln1_g, lo_ln1_b, lo_ln2_g, lo_ln2_b, lo_wqkv, lo_bqkv, lo_wo, lo_bo, lo_w1, lo_b1, lo_w2, lo_b2;
   size_t lo_wg_qkv, lo_cb_qkv, lo_wg_1, lo_cb_1;  // gamma / beta+bias folded into the QKV and first FFN matrices
   size_t off_wg_lm, off_cb_lm;
-  size_t off_kv, kv_bytes, off_len;
+  size_t off_kv, kv_bytes, off_len, off_zero;  // off_zero: 1 KiB of zeros (an operand fragment of nothing)
   size_t off_ws, ws_bytes;             // workspace, doubles as upload staging
   // workspace sub-offsets (relative to off_ws)
   size_t ws_x, ws_a, ws_qkv, ws_o, ws_u, ws_counters, ws_attn_part, ws_argmax;
@@ -42,6 +42,8 @@ struct Layout {
   // ((x - c) * gamma), partial row sums [d/16][32][2], the rows' centres [32], q|k|v [32][qkv_n] f32,
   // attention output and FFN activation operands
   size_t ws_xd, ws_ad, ws_statd, ws_cen, ws_qkvd, ws_od, ws_ud;
+  size_t ws_dec_end;   // the decode step's scratch is workspace bytes [ws_xd, ws_dec_end): the buffers above, then
+                       // the attention counters and partials and the LM head's candidates
   size_t total;
 };
 
@@ -80,9 +82,12 @@ struct Shard {
   // cache context
   char *kv = nullptr;      // [Ls][2][Bmax][Hs][Smax][Dh]
   int32_t *d_len = nullptr;
+  void *zero_frag = nullptr;
   std::vector<int32_t> h_len;  // host mirror of the committed lengths
   // workspace
   char *ws = nullptr;
+  char *dec = nullptr;   // where the decode step's scratch starts: ws + L.ws_xd, unless a call puts it elsewhere
+  char *dec_at(size_t ws_off) const { return dec + (ws_off - L.ws_xd); }  // a decode-scratch buffer by its workspace offset
   int interrupt_after = -1;
   bool use_graph = true;
   std::map<GraphKey, hipGraphExec_t> graphs;

@@ -116,6 +116,7 @@ bool compute_layout(const ss_model_desc &m, const ss_slice &s, int max_batch, in
   L->kv_bytes = (size_t)L->Ls * 2 * max_batch * L->Hs * max_seq * L->Dh * esz;
   L->off_kv = take(L->kv_bytes);
   L->off_len = take((size_t)32 * 4);
+  L->off_zero = take((size_t)1024);
   // workspace
   size_t w = 0;
   auto wtake = [&](size_t bytes) {
@@ -137,14 +138,15 @@ bool compute_layout(const ss_model_desc &m, const ss_slice &s, int max_batch, in
     L->ws_ad = wtake((size_t)2 * (d / fk) * 1024);
     L->ws_statd = wtake((size_t)(d / 32) * 32 * 4 * 4);
     L->ws_cen = wtake((size_t)32 * 4);
-    L->ws_qkvd = wtake((size_t)2 * 32 * L->qkv_n * 4);  // two partial sums when the GEMM splits K over blocks
+    L->ws_qkvd = wtake((size_t)kQkvParts * 32 * L->qkv_n * 4);  // partial sums when the GEMM cuts K into slices
     L->ws_od = wtake((size_t)2 * (HD / fk) * 1024);
     L->ws_ud = wtake((size_t)2 * (L->Fs / fk) * 1024);
   }
   L->n_counters = 16 + max_batch * L->Hs;  // [16..): decode attention's arrival counters, per (row, head); [0..16) unused
   L->ws_counters = wtake((size_t)L->n_counters * 4);
   L->ws_attn_part = wtake((size_t)max_batch * L->Hs * L->attn_splits * (L->Dh + 4) * 4);
-  L->ws_argmax = wtake((size_t)ceil_div(ceil_div(L->V, 16), 2) * 32 * 8);
+  L->ws_argmax = wtake((size_t)ceil_div(L->V, 16) * 32 * 8);  // per LM-head block and row a best logit and its index; at most a block per weight tile
+  L->ws_dec_end = w;
   // upload staging shares the workspace: it must hold the largest raw tensor slice
   size_t stage = std::max((size_t)L->V * d, (size_t)d * std::max(std::max(HD, L->Fs), 1)) * esz;
   L->ws_bytes = std::max(w, align_up(stage, 256));
@@ -337,7 +339,9 @@ void bind_pointers(Shard *sh) {
   sh->rope = (float2 *)(base + L.off_rope);
   sh->kv = base + L.off_kv;
   sh->d_len = (int32_t *)(base + L.off_len);
+  sh->zero_frag = base + L.off_zero;
   sh->ws = base + L.off_ws;
+  sh->dec = sh->ws + L.ws_xd;
   sh->lm_head = FragMat{base + L.off_lm, L.V, d, ceil_div(L.V, 16), d / FK};
   sh->layers.resize(L.Ls);
   sh->wqkv.resize(L.Ls), sh->wo.resize(L.Ls), sh->w1.resize(L.Ls), sh->w2.resize(L.Ls);
@@ -476,6 +480,7 @@ static ss_status finish_create(Shard *sh, hipStream_t st, bool rope_in_place = f
     SS_HIP(hipStreamSynchronize(st));
   }
   hipLaunchKernelGGL(fill_i32, dim3(1), dim3(32), 0, st, sh->d_len, 32, 0);
+  hipLaunchKernelGGL(fill_i32, dim3(1), dim3(256), 0, st, (int32_t *)sh->zero_frag, 256, 0);
   const int nc = L.n_counters;
   hipLaunchKernelGGL(fill_i32, dim3(ceil_div(nc, 256)), dim3(256), 0, st, (int32_t *)(sh->ws + L.ws_counters), nc, 0);
   SS_HIP(hipGetLastError());

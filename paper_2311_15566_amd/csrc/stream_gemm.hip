@@ -23,10 +23,10 @@ struct GemmShared {
 
 }  // namespace
 
-// grid = groups x K slices, block = a.ks waves.  Group g owns the weight tiles of units
-// [g * units / n_blocks, (g + 1) * units / n_blocks) (a unit is one 16-row tile, or a gate/up pair of
-// them): at most NW tiles, fewer where the units do not divide evenly, so every group's share of the
-// matrix differs by one unit at most.  Wave s streams k blocks [s * per, (s + 1) * per) of the block's
+// grid = groups x K slices, block = a.ks waves.  The units (a unit is one 16-row weight tile, or a
+// gate/up pair of them) are shared out over the n_blocks groups in order, units / n_blocks each and
+// one more for the first units % n_blocks groups: at most NW tiles a group, and no two groups' shares
+// differ by more than one unit.  Wave s streams k blocks [s * per, (s + 1) * per) of the block's
 // K slice for all its tiles in register batches of U fragments per tile, two batches in flight, and
 // shares the activation fragments between the tiles.
 // KSM: waves per block at most.  NW: weight tiles per block at most.
@@ -40,30 +40,35 @@ __global__ void __launch_bounds__(KSM * 64, 2) stream_gemm(StreamGemmArgs a) {
   constexpr int NIT = (NITEMS + 3) / 4;    // items per wave at most (a block has 4 or 8 waves)
   static_assert(NW % TU == 0, "a block holds whole units");
   __shared__ GemmShared<NB, KSM, NW> sh;
-  const int tid = threadIdx.x, lane = tid & 63, ks = tid >> 6, KS = blockDim.x >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, KS = blockDim.x >> 6;
+  // The wave's number as a scalar: everything derived from it (its k range, its epilogue items) is then
+  // wave-uniform for the compiler too, and the branches on it are real branches.  (A matrix-core
+  // instruction runs whatever the lane mask says, so it must never sit in a block that is merely
+  // masked off: with a k range the compiler takes for lane-dependent, a skipped batch's products
+  // were added all the same, from registers nothing had been loaded into.)
+  const int ks = __builtin_amdgcn_readfirstlane(tid >> 6);
   // Block -> (group, K slice).  EPI_F32 with a.k_split = S > 1: S blocks per group, each over one
   // slice of K; they leave S partial outputs (out_f32 + kh * part_stride) that the consumer adds up
   // in slice order, so no block waits for another.  Slices after the first contribute acc * rstd
   // only (no mean, no bias).
-  const int S = (EPI == EPI_F32 && a.k_split > 1) ? a.k_split : 1;
-  const int grp = blockIdx.x / S, kh = blockIdx.x - grp * S;
-  const int units = a.row_tiles / TU;
-  const int u0 = (int)((long)grp * units / a.n_blocks), u1 = (int)((long)(grp + 1) * units / a.n_blocks);
+  int grp = blockIdx.x, kh = 0;
+  if (EPI == EPI_F32 && a.k_split > 1) grp = blockIdx.x / a.k_split, kh = blockIdx.x - grp * a.k_split;
+  // the first u_rem groups own u_base + 1 units, the others u_base (no division here: every block would pay for it)
+  const int u0 = grp * a.u_base + min(grp, a.u_rem);
   const int tile0 = u0 * TU;
-  const int cnt = (u1 - u0) * TU;          // tiles of this block (<= NW: checked on the host)
-  const int k_slice = (a.k_blocks + S - 1) / S;
-  const int k_lo = kh * k_slice, k_hi = min(a.k_blocks, k_lo + k_slice);
-  const int per = (k_hi - k_lo + KS - 1) / KS;
+  const int cnt = (a.u_base + (grp < a.u_rem ? 1 : 0)) * TU;  // tiles of this block (<= NW: checked on the host)
+  const int k_lo = kh * a.k_slice, k_hi = min(a.k_blocks, k_lo + a.k_slice);
+  const int per = (k_hi - k_lo + KS - 1) >> (KS == 8 ? 3 : 2);  // KS is 4 or 8
   const int k0 = k_lo + ks * per, k1 = min(k_hi, k0 + per);
   const int r = lane & 15, q4 = (lane >> 4) * 4;
 
-  bool tile_ok[NW];
+  // Every load of the main loop is unconditional: a tile past the block's share streams the block's
+  // first tile again (its sums are never stored), a batch row past the batch and a k block past the
+  // wave's range read a fragment of zeros.  Loads under lane- or tile-dependent branches make the
+  // compiler wait for them where the branches meet, in the middle of the requests.
   const u32x4 *wp[NW];
 #pragma unroll
-  for (int j = 0; j < NW; ++j) {
-    tile_ok[j] = j < cnt;
-    wp[j] = (const u32x4 *)a.w + (size_t)(tile0 + j) * a.k_blocks * 64 + lane;
-  }
+  for (int j = 0; j < NW; ++j) wp[j] = (const u32x4 *)a.w + (size_t)(tile0 + (j < cnt ? j : 0)) * a.k_blocks * 64 + lane;
   bool row_ok[NB];
   const u32x4 *ap[NB];
 #pragma unroll
@@ -71,17 +76,20 @@ __global__ void __launch_bounds__(KSM * 64, 2) stream_gemm(StreamGemmArgs a) {
     row_ok[t] = t * 16 + r < a.B;
     ap[t] = (const u32x4 *)a.act + (size_t)t * a.k_blocks * 64 + lane;
   }
+  const u32x4 *zfrag = (const u32x4 *)a.zero_frag + lane;  // 1 KiB of zeros (in the shard's memory: a pointer of the same kind as the others)
 
-  // what the epilogue needs from memory is requested first, so that it has long arrived.
+  // What the epilogue needs from memory is requested first, so that it has long arrived.  Every
+  // request is unconditional (where there is nothing to read it goes to the start of the weights,
+  // always valid, and the value is dropped in the epilogue): a load under a branch makes the
+  // compiler wait for it where the branches meet, i.e. before the weight stream starts.
   // Epilogue item i = (unit i % NU, batch tile i / NU); wave ks takes items ks, ks + KS, ...
   bool it_live[NIT];          // the item exists and this lane's row and outputs are inside the problem
   int it_b[NIT], it_n0[NIT];  // this lane's batch row and the first of its four outputs
   f32x4 e_wg[NIT][TU], e_cb[NIT][TU], e_x[NIT], e_g[NIT];
-  float e_cen = 0.f;  // EPI_RESID: the centre of the operand it writes; a publishing consumer: the centre of the one it reads
-  {
-    const int b0 = (ks / NU) * 16 + r;  // the row of this wave's first item
-    if (ks < NITEMS && a.cen && b0 < a.B && (EPI == EPI_RESID || (a.publish && grp == 0 && kh == 0))) e_cen = a.cen[b0];
-  }
+  float e_cen[NIT];           // EPI_RESID: the centre of the operand it writes; a publishing consumer: the centre of the one it reads
+  const float *dummy = (const float *)a.w;
+  const bool first_slice = kh == 0;
+  const bool want_cen = a.cen && (EPI == EPI_RESID || (a.publish && grp == 0 && first_slice));
 #pragma unroll
   for (int it = 0; it < NIT; ++it) {
     const int item = ks + it * KS;
@@ -90,21 +98,18 @@ __global__ void __launch_bounds__(KSM * 64, 2) stream_gemm(StreamGemmArgs a) {
     const int wrow = (tile0 + je * TU) * 16 + q4;            // first of its four weight rows (gate rows for a pair)
     const int n0 = GLU ? (u0 + je) * 16 + q4 : wrow;
     it_b[it] = b, it_n0[it] = n0;
-    it_live[it] = item < NITEMS && je * TU < cnt && b < a.B && n0 < a.N;
-    e_x[it] = f32x4{0.f, 0.f, 0.f, 0.f}, e_g[it] = f32x4{1.f, 1.f, 1.f, 1.f};
+    const bool live = item < NITEMS && je * TU < cnt && b < a.B && n0 < a.N;
+    it_live[it] = live;
+    e_cen[it] = *((want_cen && item < NITEMS && b < a.B) ? a.cen + b : dummy);
 #pragma unroll
     for (int jj = 0; jj < TU; ++jj) {
-      e_wg[it][jj] = e_cb[it][jj] = f32x4{0.f, 0.f, 0.f, 0.f};
-      if (it_live[it] && kh == 0) {
-        if (a.wg) e_wg[it][jj] = *(const f32x4 *)(a.wg + wrow + jj * 16);
-        if (a.cb) e_cb[it][jj] = *(const f32x4 *)(a.cb + wrow + jj * 16);
-      }
+      e_wg[it][jj] = *(const f32x4 *)((live && first_slice && a.wg) ? a.wg + wrow + jj * 16 : dummy);
+      e_cb[it][jj] = *(const f32x4 *)((live && first_slice && a.cb) ? a.cb + wrow + jj * 16 : dummy);
     }
-    if (EPI == EPI_RESID && it_live[it]) {
-      e_x[it] = *(const f32x4 *)(a.x_in + (size_t)b * a.N + n0);
-      if (a.act_out) e_g[it] = *(const f32x4 *)(a.g_out + n0);
+    if (EPI == EPI_RESID) {
+      e_x[it] = *(const f32x4 *)(live ? a.x_in + (size_t)b * a.N + n0 : dummy);
+      e_g[it] = *(const f32x4 *)((live && a.act_out) ? a.g_out + n0 : dummy);
     }
-    if (EPI == EPI_RESID && it > 0 && item < NITEMS && a.cen && b < a.B && it_b[0] != b) e_cen = e_cen;  // (rows of later items: see below)
   }
 
   f32x4 acc[NB][NW];
@@ -113,18 +118,21 @@ __global__ void __launch_bounds__(KSM * 64, 2) stream_gemm(StreamGemmArgs a) {
 #pragma unroll
     for (int j = 0; j < NW; ++j) acc[t][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+  const int k_last = max(k1 - 1, k_lo);  // a k block that exists, for requests past the wave's range (the matching activations are zeros)
   auto load = [&](u32x4(&w)[NW][U], u32x4(&av)[NB][U], int kb) {
+    if (kb >= k1) return;  // wave-uniform: nothing of this batch is inside the range, and use() skips it too
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const bool ok = kb + u < k1;
+      const size_t off = (size_t)min(kb + u, k_last) * 64;
 #pragma unroll
-      for (int j = 0; j < NW; ++j)
-        w[j][u] = (ok && tile_ok[j]) ? __builtin_nontemporal_load(wp[j] + (size_t)(kb + u) * 64) : u32x4{0u, 0u, 0u, 0u};
+      for (int j = 0; j < NW; ++j) w[j][u] = __builtin_nontemporal_load(wp[j] + off);
 #pragma unroll
-      for (int t = 0; t < NB; ++t) av[t][u] = (ok && row_ok[t]) ? ap[t][(size_t)(kb + u) * 64] : u32x4{0u, 0u, 0u, 0u};
+      for (int t = 0; t < NB; ++t) av[t][u] = *((ok && row_ok[t]) ? ap[t] + off : zfrag);
     }
   };
-  auto use = [&](u32x4(&w)[NW][U], u32x4(&av)[NB][U]) {
+  auto use = [&](u32x4(&w)[NW][U], u32x4(&av)[NB][U], int kb) {
+    if (kb >= k1) return;
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -160,15 +168,14 @@ __global__ void __launch_bounds__(KSM * 64, 2) stream_gemm(StreamGemmArgs a) {
 #pragma unroll
       for (int i = 0; i < SR; ++i) {
         const int g = st_slice + i * nsl;
-        st_v[t][i] = (t * 16 + st_loc < a.B && g < a.stat_groups) ? st_p[(size_t)g * 32 + t * 16]
-                                                                 : f32x4{0.f, 0.f, 0.f, 0.f};
+        st_v[t][i] = *((t * 16 + st_loc < a.B && g < a.stat_groups) ? st_p + (size_t)g * 32 + t * 16 : (const f32x4 *)a.zero_frag);
       }
   }
 
   for (int kb = k0; kb < k1; kb += 2 * U) {
-    use(wA, aA);
+    use(wA, aA, kb);
     load(wA, aA, kb + 2 * U);
-    use(wB, aB);
+    use(wB, aB, kb + U);
     load(wB, aB, kb + 3 * U);
   }
 
@@ -235,14 +242,16 @@ __global__ void __launch_bounds__(KSM * 64, 2) stream_gemm(StreamGemmArgs a) {
         mean = u1 * inv;
         rstd = rsqrtf(fmaxf(ms - mean * mean, 0.f) + a.eps);
         // the next producer centres on this norm's mean (one lane per row, first block, first unit)
-        if (a.publish && a.cen && grp == 0 && kh == 0 && je == 0 && lane < 16 && b < a.B) a.cen[b] = (it == 0 ? e_cen : a.cen[b]) + mean;
+        if (a.publish && a.cen && grp == 0 && first_slice && je == 0 && lane < 16 && b < a.B) a.cen[b] = e_cen[it] + mean;
       }
     }
     float h[TU][4];  // the product with normalisation and bias applied
+    const bool has_wg = epi_live && first_slice && a.wg, has_cb = epi_live && first_slice && a.cb;
 #pragma unroll
     for (int jj = 0; jj < TU; ++jj)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) h[jj][i] = rstd * (sum[jj][i] - mean * e_wg[it][jj][i]) + e_cb[it][jj][i];
+      for (int i = 0; i < 4; ++i)
+        h[jj][i] = rstd * (sum[jj][i] - (has_wg ? mean * e_wg[it][jj][i] : 0.f)) + (has_cb ? e_cb[it][jj][i] : 0.f);
 
     if (EPI == EPI_F32) {
       if (epi_live) {
@@ -260,14 +269,14 @@ __global__ void __launch_bounds__(KSM * 64, 2) stream_gemm(StreamGemmArgs a) {
     } else if (EPI == EPI_RESID) {
       float s1 = 0.f, s2 = 0.f;
       if (epi_live) {
-        const float cen = it == 0 ? e_cen : (a.cen ? a.cen[b] : 0.f);
+        const float cen = a.cen ? e_cen[it] : 0.f;
         float v[4], g[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           v[i] = e_x[it][i] + h[0][i];
           const float t = v[i] - cen;
           s1 += t, s2 += t * t;
-          g[i] = t * e_g[it][i];
+          g[i] = a.act_out ? t * e_g[it][i] : 0.f;
         }
         *(f32x4 *)(a.x_out + (size_t)b * a.N + n0) = f32x4{v[0], v[1], v[2], v[3]};
         if (a.act_out) store4_frag<OT, false>(a.act_out, b, n0, a.out_k_blocks, g);
@@ -316,6 +325,108 @@ __global__ void __launch_bounds__(KSM * 64, 2) stream_gemm(StreamGemmArgs a) {
     a.am_val[(size_t)tid * a.n_blocks + grp] = bv;   // [row][block]: a row's candidates are contiguous
     a.am_idx[(size_t)tid * a.n_blocks + grp] = bi;
   }
+}
+
+// units a block owns at most when n_blocks groups share the matrix evenly
+int stream_gemm_units_per_block(int epi, const StreamGemmArgs &a) {
+  const int units = epi == EPI_SWIGLU ? a.row_tiles / 2 : a.row_tiles;
+  return a.n_blocks > 0 ? ceil_div(units, a.n_blocks) : 0;
+}
+
+ss_status check_stream_gemm(int dtype, int epi, const StreamGemmArgs &a) {
+  if (dtype != SS_DTYPE_BF16 && dtype != SS_DTYPE_F32) SS_FAIL(SS_EINVAL, "decode GEMM: dtype %d", dtype);
+  if (a.B < 1 || a.B > 32) SS_FAIL(SS_EINVAL, "decode GEMM: batch %d", a.B);
+  const int tu = epi == EPI_SWIGLU ? 2 : 1, units = a.row_tiles / tu;
+  if (a.row_tiles < 1 || a.k_blocks < 1 || (a.ks != 4 && a.ks != 8) || a.N < 1 || a.N > a.row_tiles * 16)
+    SS_FAIL(SS_EINVAL, "decode GEMM: bad shape (tiles %d, k blocks %d, waves %d, N %d)", a.row_tiles, a.k_blocks, a.ks, a.N);
+  // instances: 1, 2 or 3 tiles a block; a gate/up pair; or the wide blocks (6 tiles) for up to 16 batch rows
+  const bool wide_ok = a.B <= 16 && (epi == EPI_F32 || epi == EPI_SWIGLU);
+  const bool nw_ok = epi == EPI_SWIGLU ? (a.nw == 2 || (a.nw == 6 && wide_ok)) : ((a.nw >= 1 && a.nw <= 3) || (a.nw == 6 && wide_ok));
+  if (!nw_ok) SS_FAIL(SS_EINVAL, "decode GEMM: %d weight tiles per block", a.nw);
+  if (a.n_blocks < 1 || a.n_blocks > units || stream_gemm_units_per_block(epi, a) * tu > a.nw)
+    SS_FAIL(SS_EINVAL, "decode GEMM: %d blocks of at most %d tiles do not cover %d tiles", a.n_blocks, a.nw, a.row_tiles);
+  if (a.u_base != units / a.n_blocks || a.u_rem != units % a.n_blocks || a.k_slice != ceil_div(a.k_blocks, a.k_split > 1 ? a.k_split : 1))
+    SS_FAIL(SS_EINVAL, "decode GEMM: the shares (%d units, %d more for the first %d blocks, %d k blocks a slice) do not fit the shape",
+            a.u_base, 1, a.u_rem, a.k_slice);
+  if (!a.w || !a.act || !a.zero_frag) SS_FAIL(SS_EINVAL, "decode GEMM: NULL operand");
+  if (a.k_split != 0 && a.k_split != 1 &&
+      !(a.k_split >= 2 && a.k_split <= 8 && epi == EPI_F32 && a.k_blocks >= a.k_split * a.ks &&
+        a.part_stride >= (size_t)a.B * a.ld_out))
+    SS_FAIL(SS_EINVAL, "decode GEMM: bad split of K over blocks");
+  if (epi == EPI_RESID && a.row_tiles % 2) SS_FAIL(SS_EINVAL, "decode GEMM: residual output needs whole tile pairs");
+  if (a.stat_groups < 0 || (a.stat_groups > 0 && (!a.stat_in || a.norm_dim < 1 || (!a.rms && !a.wg))))
+    SS_FAIL(SS_EINVAL, "decode GEMM: incomplete normalisation arguments");
+  switch (epi) {
+    case EPI_F32:
+      if (!a.out_f32 || a.ld_out < a.N) SS_FAIL(SS_EINVAL, "decode GEMM: bad float output");
+      break;
+    case EPI_SWIGLU:
+      if (a.row_tiles % 2 || a.N * 2 != a.row_tiles * 16) SS_FAIL(SS_EINVAL, "decode GEMM: gate/up tiles must pair up");
+      // fall through
+    case EPI_ACT:
+      if (!a.act_out || a.N % 16 || a.out_k_blocks * (dtype == SS_DTYPE_BF16 ? 32 : 16) < a.N)
+        SS_FAIL(SS_EINVAL, "decode GEMM: bad activation output");
+      break;
+    case EPI_RESID:
+      if (!a.x_in || !a.x_out || a.N != a.row_tiles * 16 || a.stat_groups != 0 || a.wg)
+        SS_FAIL(SS_EINVAL, "decode GEMM: bad residual arguments");
+      if (a.act_out && (!a.g_out || !a.stat_out || a.out_k_blocks * (dtype == SS_DTYPE_BF16 ? 32 : 16) < a.N))
+        SS_FAIL(SS_EINVAL, "decode GEMM: bad residual operand output");
+      break;
+    case EPI_LOGITS:
+      if (!a.am_val || !a.am_idx || (a.out_f32 && a.ld_out < a.N))
+        SS_FAIL(SS_EINVAL, "decode GEMM: bad logits arguments");
+      break;
+    default: SS_FAIL(SS_EINVAL, "decode GEMM: unknown epilogue %d", epi);
+  }
+  return SS_OK;
+}
+
+template <typename T, int NB, int KSM>
+static void launch_stream_gemm_t(int epi, const StreamGemmArgs &a, dim3 grid, dim3 block, hipStream_t st) {
+#define SS_LAUNCH(GLU, EPI, NW) SS_LAUNCH_KERNEL((stream_gemm<T, NB, GLU, EPI, KSM, NW>), grid, block, 0, st, a)
+  if (epi == EPI_SWIGLU) {
+    if constexpr (NB == 1) {
+      if (a.nw == 6) {
+        SS_LAUNCH(true, EPI_SWIGLU, 6);
+        return;
+      }
+    }
+    SS_LAUNCH(true, EPI_SWIGLU, 2);
+  } else if (a.nw == 6) {  // wide blocks: q|k|v
+    if constexpr (NB == 1) SS_LAUNCH(false, EPI_F32, 6);
+  } else if (a.nw == 3) {
+    if (epi == EPI_F32) SS_LAUNCH(false, EPI_F32, 3);
+    else if (epi == EPI_ACT) SS_LAUNCH(false, EPI_ACT, 3);
+    else if (epi == EPI_RESID) SS_LAUNCH(false, EPI_RESID, 3);
+    else SS_LAUNCH(false, EPI_LOGITS, 3);
+  } else if (a.nw == 1) {
+    if (epi == EPI_F32) SS_LAUNCH(false, EPI_F32, 1);
+    else if (epi == EPI_ACT) SS_LAUNCH(false, EPI_ACT, 1);
+    else if (epi == EPI_RESID) SS_LAUNCH(false, EPI_RESID, 1);
+    else SS_LAUNCH(false, EPI_LOGITS, 1);
+  } else {
+    if (epi == EPI_F32) SS_LAUNCH(false, EPI_F32, 2);
+    else if (epi == EPI_ACT) SS_LAUNCH(false, EPI_ACT, 2);
+    else if (epi == EPI_RESID) SS_LAUNCH(false, EPI_RESID, 2);
+    else SS_LAUNCH(false, EPI_LOGITS, 2);
+  }
+#undef SS_LAUNCH
+}
+
+ss_status launch_stream_gemm(int dtype, int epi, const StreamGemmArgs &a, hipStream_t st) {
+  SS_TRY(check_stream_gemm(dtype, epi, a));
+  const dim3 grid(a.n_blocks * (a.k_split > 1 ? a.k_split : 1)), block(a.ks * 64);
+  const int nb = a.B <= 16 ? 1 : 2;
+  if (dtype == SS_DTYPE_BF16) {
+    if (nb == 1) launch_stream_gemm_t<bf16_t, 1, 8>(epi, a, grid, block, st);
+    else launch_stream_gemm_t<bf16_t, 2, 8>(epi, a, grid, block, st);
+  } else {
+    if (nb == 1) launch_stream_gemm_t<float, 1, 8>(epi, a, grid, block, st);
+    else launch_stream_gemm_t<float, 2, 8>(epi, a, grid, block, st);
+  }
+  SS_HIP(hipGetLastError());
+  return SS_OK;
 }
 
 // ---------------------------------------------------------------------------

@@ -251,18 +251,23 @@ def test_launch_modes_agree(ss, side_stream, name, kw):
 
 @pytest.mark.parametrize("name,batch", [("opt66b_m8", 27), ("gpt20b_m4", 7), ("llama30b_m2", 16)])
 def test_gemm_launch_shapes_give_the_same_bits(ss, side_stream, name, batch):
-    """Tiles per block and the split of the batch tiles over blocks are free choices (made per
-    shape, by rule or by timing): every combination must give bit-identical logits and caches."""
+    """Weight tiles per block (and with them the number of blocks the tiles are shared out over) are a free
+    choice, made per shape by a cost rule: every choice must give bit-identical logits, tokens and caches.
+    The slices the q|k|v GEMM cuts K into change the order of its sums: for every slice count the logits
+    must meet the oracle's, and all tile counts must agree bit for bit."""
     import torch
-    w = scaled(name, "bf16", batch=batch, s_in=40, steps=3, d_model=512, ffn=1152, head_dim=128, n_heads=4, vocab=2011)
+    w = scaled(name, "bf16", batch=batch, s_in=40, steps=3, d_model=1024, ffn=1152, head_dim=128, n_heads=6, vocab=2011)
     W = make_weights(w.desc, w.slice, w.seed)
     toks = make_tokens(w.seed, w.batch, w.s_in, w.desc["vocab"])
     forced = make_tokens(w.seed + 1, w.batch, w.steps, w.desc["vocab"])
-    outs = []
+    ora = D.OracleShard(w.desc, w.slice, W, w.batch, w.s_max)
+    D.prefill_matrix([ora], toks)                            # fills the oracle's cache rows [0, s_in)
+    refs = [D.decode_step([ora], forced[:, i]) for i in range(w.steps)]
     try:
-        for nw in (1, 2):
-            for bt in ((1, 2) if batch > 16 else (1,)):
-                ss.force_gemm_shape(nw, bt)
+        for slices in (1, 2, 4):
+            outs = []
+            for nw in (0, 1, 2, 3, 6):
+                ss.force_gemm_shape(nw, slices)
                 sh = ss.Shard(w.desc, w.slice, W, w.batch, w.s_max)
                 logits = torch.empty(w.batch, w.desc["vocab"], dtype=torch.float32, device="cuda")
                 nxt = torch.empty(w.batch, dtype=torch.int32, device="cuda")
@@ -273,14 +278,16 @@ def test_gemm_launch_shapes_give_the_same_bits(ss, side_stream, name, batch):
                     torch.cuda.synchronize()
                     run.append(logits.cpu().numpy().copy())
                     run.append(nxt.cpu().numpy().copy())
+                    if nw == 0:
+                        check_logits(run[-2], refs[i], True, f"{slices} K slices, step {i}")
                 run.append(ss.kv_export(sh))
                 outs.append(run)
                 sh.destroy()
+            for other in outs[1:]:
+                for a, b in zip(outs[0], other):
+                    assert np.array_equal(bits(a) if a.dtype != np.int32 else a, bits(b) if b.dtype != np.int32 else b)
     finally:
         ss.force_gemm_shape(0, 0)
-    for other in outs[1:]:
-        for a, b in zip(outs[0], other):
-            assert np.array_equal(bits(a) if a.dtype != np.int32 else a, bits(b) if b.dtype != np.int32 else b)
 
 
 @pytest.mark.parametrize("name,dtype,batch", [("llama30b_m2", "bf16", 5), ("llama30b_m2", "f32", 2), ("opt66b_m8", "bf16", 19)])

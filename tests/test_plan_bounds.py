@@ -17,15 +17,15 @@ class EmbedArgs(C.Structure):
 
 
 class GemmArgs(C.Structure):
-    _fields_ = [("w", vp), ("row_tiles", i32), ("k_blocks", i32), ("ks", i32), ("nw", i32), ("n_blocks", i32), ("bt_split", i32), ("B", i32), ("N", i32), ("act", vp),
+    _fields_ = [("w", vp), ("row_tiles", i32), ("k_blocks", i32), ("ks", i32), ("nw", i32), ("n_blocks", i32), ("u_base", i32), ("u_rem", i32), ("k_slice", i32), ("B", i32), ("N", i32), ("act", vp), ("zero_frag", vp),
                 ("stat_in", vp), ("cen", vp), ("publish", i32), ("stat_groups", i32), ("norm_dim", i32), ("rms", i32), ("eps", f32), ("wg", vp), ("cb", vp),
-                ("out_f32", vp), ("ld_out", i32), ("k_split", i32), ("part_stride", sz), ("split_ok", i32), ("x_in", vp), ("x_out", vp), ("act_out", vp), ("out_k_blocks", i32),
+                ("out_f32", vp), ("ld_out", i32), ("k_split", i32), ("part_stride", sz), ("split_ok", i32), ("split_cost_us", f32), ("x_in", vp), ("x_out", vp), ("act_out", vp), ("out_k_blocks", i32),
                 ("g_out", vp), ("stat_out", vp), ("act_kind", i32), ("am_val", vp), ("am_idx", vp),
                 ("next_tokens", vp), ("lens", vp * 8), ("len_cap", i32 * 8), ("n_lens", i32), ("commit_inc", i32)]
 
 
 class AttnArgs(C.Structure):
-    _fields_ = [("qkv", vp), ("qkv2", vp), ("k_cache", vp), ("v_cache", vp), ("row_stride", sz), ("head_stride", sz), ("lens", vp),
+    _fields_ = [("qkv", vp), ("qkv_parts", i32), ("qkv_stride", sz), ("k_cache", vp), ("v_cache", vp), ("row_stride", sz), ("head_stride", sz), ("lens", vp),
                 ("rope", vp), ("part", vp), ("counters", vp), ("o_out", vp), ("B", i32), ("Hs", i32), ("Dh", i32),
                 ("Smax", i32), ("kv_dtype", i32), ("rows_per_block", i32), ("splits", i32), ("waves", i32)]
 
@@ -87,7 +87,9 @@ def check(w):
         elif p.kind == ATTN:
             a = p.at
             rng("qkv", a.qkv, a.B * 3 * a.Hs * a.Dh * 4, regions)
-            rng("qkv2", a.qkv2, a.B * 3 * a.Hs * a.Dh * 4, regions)
+            for part in range(1, max(1, a.qkv_parts)):
+                assert a.qkv_stride >= a.B * 3 * a.Hs * a.Dh and a.qkv_parts <= 8
+                rng("qkv part %d" % part, a.qkv + part * a.qkv_stride * 4, a.B * 3 * a.Hs * a.Dh * 4, regions)
             rng("part", a.part, a.B * a.Hs * a.splits * (a.Dh + 4) * 4, regions)
             rng("counters", a.counters, a.B * a.Hs * 4, regions)
             rng("o_out", a.o_out, nbt * (a.Hs * a.Dh // fk) * parts * 1024, regions)
@@ -105,12 +107,17 @@ def check(w):
             rng("am_idx", g.am_idx, 32 * g.n_blocks * 4, regions)
         else:
             g = p.g
-            assert g.ks in (4, 8) and g.B == w.batch and p.gy == 1 and g.nw in (1, 2, 3) and g.n_blocks == -(-g.row_tiles // g.nw)
-            assert g.nw < 3 or (p.kind in (QKV, FFN_UP) and not glu or p.kind == QKV) and g.ks == 8
-            assert (g.bt_split == 1 or (g.bt_split == 2 and g.B > 16)) and p.gx == g.n_blocks * g.bt_split * max(1, g.k_split)
+            tu = 2 if (glu and p.kind == FFN_UP) else 1                      # weight tiles per unit (a gate/up pair)
+            units = g.row_tiles // tu
+            assert g.ks in (4, 8) and g.B == w.batch and p.gy == 1
+            assert g.nw in ((2, 6) if tu == 2 else (1, 2, 3, 6)) and (g.nw != 6 or (g.B <= 16 and p.kind in (QKV, FFN_UP)))
+            assert 1 <= g.n_blocks <= units and -(-units // g.n_blocks) * tu <= g.nw   # the largest block fits the kernel instance
+            assert p.gx == g.n_blocks * max(1, g.k_split)
+            assert (g.u_base, g.u_rem) == divmod(units, g.n_blocks) and g.k_slice == -(-g.k_blocks // max(1, g.k_split))
             assert 1 <= g.N <= g.row_tiles * 16
             rng("w", g.w, g.row_tiles * g.k_blocks * 1024, regions)
             rng("act", g.act, nbt * g.k_blocks * parts * 1024, regions)
+            rng("zero_frag", g.zero_frag, 1024, regions)
             if g.wg: rng("wg", g.wg, g.row_tiles * 16 * 4, regions)
             if g.cb: rng("cb", g.cb, g.row_tiles * 16 * 4, regions)
             if p.kind in (QKV, FFN_UP, LM_HEAD):
@@ -123,15 +130,18 @@ def check(w):
                 rng("cen", g.cen, 32 * 4, regions)
             else:
                 assert g.stat_groups == 0 and not g.wg
-            assert g.k_split in (0, 1) or (g.k_split == 2 and p.kind == QKV and g.bt_split == 1 and g.B <= 16 and g.k_blocks >= 2 * g.ks)
+            assert g.k_split in (0, 1) or (2 <= g.k_split <= 8 and p.kind == QKV and g.k_blocks >= g.k_split * g.ks)
             if p.kind == QKV:
                 rng("out_f32", g.out_f32, g.B * g.ld_out * 4, regions)
-                if g.k_split == 2:                         # the second partial sum, added up by the attention kernel
+                nxt = ph[i + 1]
+                assert nxt.kind == ATTN and nxt.at.qkv == g.out_f32
+                if g.k_split > 1:                          # the partial sums, added up by the attention kernel
                     assert g.part_stride >= g.B * g.ld_out
-                    rng("out_f32 (second half of K)", g.out_f32 + g.part_stride * 4, g.B * g.ld_out * 4, regions)
-                    assert ph[i + 1].kind == ATTN and ph[i + 1].at.qkv2 == g.out_f32 + g.part_stride * 4
+                    for part in range(1, g.k_split):
+                        rng("out_f32 (K slice %d)" % part, g.out_f32 + part * g.part_stride * 4, g.B * g.ld_out * 4, regions)
+                    assert nxt.at.qkv_parts == g.k_split and nxt.at.qkv_stride == g.part_stride
                 else:
-                    assert ph[i + 1].kind != ATTN or not ph[i + 1].at.qkv2
+                    assert nxt.at.qkv_parts in (0, 1)
                 assert g.ld_out >= g.N
             if p.kind == FFN_UP:
                 assert g.N * (2 if glu else 1) == g.row_tiles * 16
