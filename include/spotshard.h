@@ -163,6 +163,21 @@ ss_status ss_prefill(ss_shard *const *group, int32_t n_group, const int32_t *tok
 ss_status ss_decode_step(ss_shard *const *group, int32_t n_group, const int32_t *tokens_in,
                          int32_t B, float *logits, int32_t *next_tokens, void *hip_stream);
 
+/* ss_decode_step for callers that cannot allocate device memory or let the library do so (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same
+ * iteration with the same kernels and the same bits, but the step's scratch (residual rows,
+ * operand fragments, row sums, q|k|v, attention partials and counters, LM-head candidates) lives
+ * in a static device array of ss_static_scratch_bytes() = 32 MiB that every device the library
+ * runs on holds until the process ends, the kernels are launched one by one (no graph is
+ * instantiated), and no hipMalloc / hipFree or allocating library routine is called.  The caller
+ * still passes the inputs and outputs; the shards' caches and weights stay where they are.
+ * SS_ENOMEM if a step of this group needs more scratch than the array holds (nothing is launched);
+ * otherwise the errors of ss_decode_step.  Every call on a device shares that device's array:
+ * calls that overlap on one device (two streams, two threads) race; calls in stream order are fine. */
+size_t ss_static_scratch_bytes(void);
+ss_status ss_decode_step_static(ss_shard *const *group, int32_t n_group, const int32_t *tokens_in,
+                                int32_t B, float *logits, int32_t *next_tokens, void *hip_stream);
+
 /* The same two calls for a shard that is one STAGE of a pipeline (Section 2.2, inter-operator
  * parallelism: consecutive layers grouped into stages, each fed by the one before).  Exactly
  * one of tokens / hidden_in is given: tokens for the model's first stage, hidden_in (device

@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     SpotShardError,
     committed_len,
     decode_step,
+    decode_step_static,
     device_kv_bytes,
     force_gemm_shape,
     force_prefill_block,
@@ -21,5 +22,6 @@ from .binding import (  # noqa: F401
     prefill,
     stage_decode_step,
     stage_prefill,
+    static_scratch_bytes,
     version,
 )

@@ -62,6 +62,9 @@ def _load():
     L.ss_shard_reset.argtypes = [vp, vp]
     L.ss_prefill.argtypes = [C.POINTER(vp), i32, vp, i32, i32, vp, vp, vp]
     L.ss_decode_step.argtypes = [C.POINTER(vp), i32, vp, i32, vp, vp, vp]
+    L.ss_decode_step_static.argtypes = [C.POINTER(vp), i32, vp, i32, vp, vp, vp]
+    L.ss_static_scratch_bytes.restype = sz
+    L.ss_static_scratch_bytes.argtypes = []
     L.ss_stage_prefill.argtypes = [C.POINTER(vp), i32, vp, vp, i32, i32, vp, vp, vp, vp]
     L.ss_stage_decode_step.argtypes = [C.POINTER(vp), i32, vp, vp, i32, vp, vp, vp, vp]
     L.ss_committed_len.argtypes = [vp, C.POINTER(i32), vp]
@@ -236,6 +239,17 @@ def decode_step(group, tokens_in, logits=None, next_tokens=None, stream=None):
     arr, n = _group(group)
     _check(lib.ss_decode_step(arr, n, _dptr(tokens_in), tokens_in.shape[0], _dptr(logits), _dptr(next_tokens),
                               _stream(stream)))
+
+
+def decode_step_static(group, tokens_in, logits=None, next_tokens=None, stream=None):
+    """ss_decode_step with the step's scratch in the library's static device array (allocates nothing)."""
+    arr, n = _group(group)
+    _check(lib.ss_decode_step_static(arr, n, _dptr(tokens_in), tokens_in.shape[0], _dptr(logits), _dptr(next_tokens),
+                                     _stream(stream)))
+
+
+def static_scratch_bytes() -> int:
+    return int(lib.ss_static_scratch_bytes())
 
 
 def stage_prefill(group, B, S, tokens=None, hidden_in=None, hidden_out=None, logits=None, next_tokens=None, stream=None):

@@ -14,6 +14,14 @@
 #include "rows.h"
 #include "shard.h"
 
+// Scratch of ss_decode_step_static: the buffers a decode step keeps between its kernels (residual
+// rows, operand fragments, row sums, q|k|v, attention partials and counters, the LM head's
+// candidates), for callers that cannot allocate.  Every device the library runs on holds its own
+// copy of this array until the process ends; host code reaches it through the address
+// hipGetSymbolAddress gives per device, never through the name.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace ss {
 
 // ---------------------------------------------------------------------------
@@ -798,6 +806,73 @@ ss_status ss_decode_step(ss_shard *const *group_, int32_t n_group, const int32_t
                          int32_t *next_tokens, void *hip_stream) {
   if (!tokens_in) SS_FAIL(SS_EINVAL, "tokens_in is NULL");
   return ss_stage_decode_step(group_, n_group, tokens_in, nullptr, B, nullptr, logits, next_tokens, hip_stream);
+}
+
+// ---------------------------------------------------------------------------
+// The decode step for callers that cannot allocate: the step's scratch is the static device
+// array `scratch` instead of the shards' workspaces, the kernels are launched one by one (a graph
+// would have to be instantiated), and nothing is allocated on the device.
+// ---------------------------------------------------------------------------
+__global__ void zero_i32(int32_t *p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
+constexpr int kMaxDevices = 64;
+static char *g_scratch_ptr[kMaxDevices];  // the device address of `scratch` on each device
+static std::mutex g_scratch_mu;
+
+size_t ss_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+ss_status ss_decode_step_static(ss_shard *const *group_, int32_t n_group, const int32_t *tokens_in, int32_t B,
+                                float *logits, int32_t *next_tokens, void *hip_stream) {
+  if (!tokens_in) SS_FAIL(SS_EINVAL, "tokens_in is NULL");
+  Shard *const *group = (Shard *const *)group_;
+  SS_TRY(check_decode_state(group, n_group, B));
+  for (int i = 0; i < n_group; ++i)
+    if (group[i]->timing) SS_FAIL(SS_ESTATE, "kernel timing is on for group[%d]: its events would have to be created", i);
+  // this device's copy of the array (looked up once per device, with the device current)
+  int dev = -1;
+  SS_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) SS_FAIL(SS_EINVAL, "device %d outside [0,%d)", dev, kMaxDevices);
+  char *base = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+      void *p = nullptr;
+      SS_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+      if (!p) SS_FAIL(SS_EHIP, "hipGetSymbolAddress gave no address for the static scratch");
+      g_scratch_ptr[dev] = (char *)p;
+    }
+    base = g_scratch_ptr[dev];
+  }
+  // every shard of the group gets its slice of the array
+  size_t offs[8], total = 0;
+  for (int i = 0; i < n_group; ++i) {
+    offs[i] = total;
+    total += align_up(group[i]->L.ws_dec_end - group[i]->L.ws_xd, 256);
+  }
+  if (total > kStaticScratchBytes)
+    SS_FAIL(SS_ENOMEM, "a decode step of this group needs %zu bytes of scratch, the static array holds %zu", total,
+            kStaticScratchBytes);
+  hipStream_t st = (hipStream_t)hip_stream;
+  char *saved[8];
+  for (int i = 0; i < n_group; ++i) saved[i] = group[i]->dec, group[i]->dec = base + offs[i];
+  ss_status rc = SS_OK;
+  // the array keeps the last call's bytes: the attention kernels' arrival counters must start at zero
+  for (int i = 0; i < n_group && rc == SS_OK; ++i) {
+    const int nc = group[i]->L.n_counters;
+    hipLaunchKernelGGL(zero_i32, dim3(ceil_div(nc, 256)), dim3(256), 0, st, (int32_t *)group[i]->dec_at(group[i]->L.ws_counters), nc);
+    if (hipGetLastError() != hipSuccess) set_error("clearing the static scratch's counters failed"), rc = SS_EHIP;
+  }
+  int stop = -1;
+  for (int i = 0; i < n_group; ++i) stop = std::max(stop, group[i]->interrupt_after);
+  if (rc == SS_OK) rc = enqueue_decode(group, n_group, tokens_in, nullptr, B, nullptr, logits, next_tokens, st, stop);
+  for (int i = 0; i < n_group; ++i) group[i]->dec = saved[i];
+  if (rc != SS_OK) return rc;  // SS_EINTR: nothing committed
+  for (int i = 0; i < n_group; ++i)
+    for (int b = 0; b < B; ++b) group[i]->h_len[b] += 1;
+  return SS_OK;
 }
 
 }  // extern "C"
