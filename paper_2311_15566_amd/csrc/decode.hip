@@ -350,7 +350,7 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
   {
     Phase ph = {};
     ph.kind = PH_EMBED, ph.gx = B, ph.gy = 1;
-    ph.e = EmbedArgs{hidden_in, tokens_in, g0->wte, g0->wpe, g0->d_len, 0, L0.max_pos, x, d, L0.V, first_gamma, ad, rms, statd, cen};
+    ph.e = EmbedArgs{hidden_in, tokens_in, g0->wte, g0->wpe, g0->d_len, 0, L0.max_pos, x, d, L0.V, first_gamma, ad, nullptr, rms, statd, cen};
     plan->push_back(ph);
   }
   int stat_groups = 1;  // partial-sum groups behind the rows in statd
@@ -588,6 +588,7 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, c
     if (T > group[i]->L.Tmax) SS_FAIL(SS_EINVAL, "%d prompt tokens exceed group[%d]'s workspace (%d)", T_live, i, group[i]->L.Tmax);
   float *x = (float *)(g0->ws + L0.ws_x);
   void *abuf = g0->ws + L0.ws_a;
+  void *abuf_lo = L0.two_part_qk ? g0->ws + L0.ws_a_lo : nullptr;  // low parts of the q|k|v GEMM's operand
   float2 *pstat = (float2 *)(g0->ws + L0.ws_pstat);
   f32x4 *mr = (f32x4 *)(pstat + (size_t)2 * ceil_div(d, 128) * L0.Tmax);  // (mean, rstd, mean - centre, -) per token
   // Norms are deferred and centred (see TileGemmArgs): the producer of x writes (x - c) * gamma as the
@@ -595,7 +596,7 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, c
   // for bf16 models: single bf16 activations miss the logits bar (OPT-66B shape 6.4e-2 at its first
   // token), bf16 hi/lo pairs meet it at twice the matrix-core work.
   {
-    EmbedArgs e{hidden_in, tokens, g0->wte, g0->wpe, nullptr, S, L0.max_pos, x, d, L0.V, g0->layers[0].ln1_g, abuf, rms, nullptr, nullptr, pstat, mr};
+    EmbedArgs e{hidden_in, tokens, g0->wte, g0->wpe, nullptr, S, L0.max_pos, x, d, L0.V, g0->layers[0].ln1_g, abuf, abuf_lo, rms, nullptr, nullptr, pstat, mr};
     if (dt == SS_DTYPE_BF16) hipLaunchKernelGGL(embed_rows<bf16_t>, dim3(T_live), dim3(256), 0, st, e);
     else hipLaunchKernelGGL(embed_rows<float>, dim3(T_live), dim3(256), 0, st, e);
     SS_HIP(hipGetLastError());
@@ -607,12 +608,15 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, c
   auto row_stats = [&]() { return launch_row_stats(pstat, stat_groups, T, d, rms, m.norm_eps, mr, st); };
   // sum over the group at a reduce slot: shard i adds its partial to what the previous shards left;
   // the last one also emits the next operand and the partial sums
-  auto resid = [&](int i, const FragMat &w, const void *act, const float *bias, const float *next_gamma) -> ss_status {
+  auto resid = [&](int i, const FragMat &w, const void *act, const float *bias, const float *next_gamma, bool feeds_qkv) -> ss_status {
     TileGemmArgs a = {};
     a.w = w.ptr, a.row_tiles = w.row_tiles, a.k_blocks = w.k_blocks;
     a.act = act, a.T = T, a.T_live = T_live, a.N = d, a.bias = i == 0 ? bias : nullptr;
     a.x_resid = x;
-    if (i == n_group - 1 && next_gamma) a.g_out = next_gamma, a.norm_out = abuf, a.stat_out = pstat, a.c_in = mr;
+    if (i == n_group - 1 && next_gamma) {
+      a.g_out = next_gamma, a.norm_out = abuf, a.stat_out = pstat, a.c_in = mr;
+      if (feeds_qkv) a.norm_out_lo = abuf_lo;
+    }
     return launch_tile_gemm(dt, EPI_RESID, a, st);
   };
   for (int l = 0; l < L0.Ls; ++l) {
@@ -625,6 +629,7 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, c
       a.w = s->wqkv[l].ptr, a.row_tiles = s->wqkv[l].row_tiles, a.k_blocks = s->wqkv[l].k_blocks;
       a.T = T, a.T_live = T_live, a.N = L.qkv_n;
       normed(a, s->wg_qkv[l], s->cb_qkv[l]);
+      if (abuf_lo) a.act_lo = abuf_lo, a.lo_row_begin = 0, a.lo_row_end = 2 * L.Hs * L.Dh / 16;  // the q and k rows
       a.out_f32 = (float *)(s->ws + L.ws_qkv), a.ld_out = L.qkv_n;
       const bool rope_model = m.pos == SS_POS_ROPE;
       if (!rope_model) {  // nothing to rotate: the GEMM's epilogue writes the cache rows itself
@@ -645,7 +650,7 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, c
       SS_TRY(launch_prefill_attn(dt, p, st));
     }
     stat_groups = 2 * ceil_div(d / 16, 8);  // from here on: one partial per 64-feature band of the residual GEMMs
-    for (int i = 0; i < n_group; ++i) SS_TRY(resid(i, group[i]->wo[l], group[i]->ws + group[i]->L.ws_o, D0.bo, D0.ln2_g));
+    for (int i = 0; i < n_group; ++i) SS_TRY(resid(i, group[i]->wo[l], group[i]->ws + group[i]->L.ws_o, D0.bo, D0.ln2_g, false));
     SS_TRY(row_stats());
     for (int i = 0; i < n_group; ++i) {
       Shard *s = group[i];
@@ -660,7 +665,7 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, c
     }
     // the last layer's output goes to the next stage or to gather_last, which read x
     const float *next_gamma = l + 1 < L0.Ls ? g0->layers[l + 1].ln1_g : nullptr;
-    for (int i = 0; i < n_group; ++i) SS_TRY(resid(i, group[i]->w2[l], group[i]->ws + group[i]->L.ws_u, D0.b2, next_gamma));
+    for (int i = 0; i < n_group; ++i) SS_TRY(resid(i, group[i]->w2[l], group[i]->ws + group[i]->L.ws_u, D0.b2, next_gamma, true));
   }
   if (hidden_out) {  // a stage that hands its hidden states on: copy them out, then commit
     SS_HIP(hipMemcpyAsync(hidden_out, x, (size_t)T_live * d * 4, hipMemcpyDeviceToDevice, st));

@@ -61,6 +61,10 @@ __global__ void __launch_bounds__(256, NJ == 8 ? 2 : 3) tile_gemm(TileGemmArgs a
   const int tt0 = tb * BTT;   // first token tile
   const u32x4 *W = (const u32x4 *)a.w;
   const u32x4 *A = (const u32x4 *)a.act;
+  // A two-part operand (block-uniform): the reduction runs twice, over the high parts and then, with the same
+  // weights, over the low parts, into the same sums.
+  const u32x4 *A_lo = (a.act_lo && rt0 >= a.lo_row_begin && rt0 < a.lo_row_end) ? (const u32x4 *)a.act_lo : nullptr;
+  const int n_stages = A_lo ? 2 * a.k_blocks : a.k_blocks;
 
   f32x4 acc[MI][NJ];
 #pragma unroll
@@ -71,7 +75,10 @@ __global__ void __launch_bounds__(256, NJ == 8 ? 2 : 3) tile_gemm(TileGemmArgs a
   // Stage k -> buffer buf: every wave brings 2 weight and 4 activation fragments, each as one
   // 1 KiB load that the hardware writes to LDS at (wave-uniform base) + lane * 16.  Row tiles
   // past the matrix repeat the last one (in bounds; their outputs are never stored).
-  auto issue = [&](int k, int buf) {
+  auto issue = [&](int stage, int buf) {
+    const bool second = stage >= a.k_blocks;
+    const int k = second ? stage - a.k_blocks : stage;
+    const u32x4 *Ak = second ? A_lo : A;
     u32x4 *st = lds + buf * STAGE;
 #pragma unroll
     for (int r = 0; r < BMT / 4; ++r) {
@@ -83,21 +90,21 @@ __global__ void __launch_bounds__(256, NJ == 8 ? 2 : 3) tile_gemm(TileGemmArgs a
 #pragma unroll
     for (int r = 0; r < BTT / 4; ++r) {
       const int tile = wave + 4 * r;
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(A + ((size_t)(tt0 + tile) * a.k_blocks + k) * 64 + lane),
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(Ak + ((size_t)(tt0 + tile) * a.k_blocks + k) * 64 + lane),
                                        (__attribute__((address_space(3))) void *)(st + (BMT + tile) * 64), 16, 0, 0);
     }
   };
   issue(0, 0);
-  if (a.k_blocks > 1) issue(1, 1);
-  for (int k = 0; k < a.k_blocks; ++k) {
+  if (n_stages > 1) issue(1, 1);
+  for (int k = 0; k < n_stages; ++k) {
     // This wave's share of stage k has landed (loads complete in order; the stage after it may
     // still be in flight).  The barrier then says that everyone's has, and that everyone has the
     // operands of stage k - 1 in registers (LDS counter at zero), so that buffer can be refilled.
     // Not __syncthreads(): its fence would also wait for the loads in flight.
-    if (k + 1 < a.k_blocks) wait_vmcnt<LPS>();
+    if (k + 1 < n_stages) wait_vmcnt<LPS>();
     else wait_vmcnt<0>();
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    if (k + 2 < a.k_blocks) issue(k + 2, (k + 2) % kTileGemmRing);
+    if (k + 2 < n_stages) issue(k + 2, (k + 2) % kTileGemmRing);
     const u32x4 *st = lds + (k % kTileGemmRing) * STAGE;
     u32x4 wf[MI], af[NJ];
 #pragma unroll
@@ -164,6 +171,12 @@ __global__ void __launch_bounds__(256, NJ == 8 ? 2 : 3) tile_gemm(TileGemmArgs a
               y[e] = t * g[e];
             }
             store4_frag<OT, false>(a.norm_out, tok, n0, a.N / Elem<OT>::kFragK, y);
+            if (a.norm_out_lo) {
+              float lo[4];
+#pragma unroll
+              for (int e = 0; e < 4; ++e) lo[e] = y[e] - Elem<OT>::to_f32(Elem<OT>::from_f32(y[e]));
+              store4_frag<OT, false>(a.norm_out_lo, tok, n0, a.N / Elem<OT>::kFragK, lo);
+            }
           }
         }
       }
@@ -263,6 +276,9 @@ ss_status launch_tile_gemm(int dtype, int epi, TileGemmArgs a, hipStream_t st) {
   if (a.k_cache && (epi != EPI_F32 || !a.v_cache || a.kv_S < 1 || a.kv_Dh % 4 || a.N != 3 * a.kv_Hs * a.kv_Dh ||
                     (a.kv_dtype != SS_DTYPE_F16 && a.kv_dtype != SS_DTYPE_BF16 && a.kv_dtype != SS_DTYPE_F32)))
     SS_FAIL(SS_EINVAL, "prefill GEMM: bad cache arguments");
+  if (a.act_lo && (epi != EPI_F32 || a.lo_row_begin < 0 || a.lo_row_begin % 8 || a.lo_row_end < a.lo_row_begin || a.lo_row_end % 8))
+    SS_FAIL(SS_EINVAL, "prefill GEMM: a two-part operand goes with the float epilogue and whole row blocks");
+  if (a.norm_out_lo && !(epi == EPI_RESID && a.g_out)) SS_FAIL(SS_EINVAL, "prefill GEMM: low parts without an operand output");
   if (epi == EPI_RESID && a.g_out) {
     const int fk = dtype == SS_DTYPE_BF16 ? 32 : 16;
     if (!a.norm_out || !a.stat_out || !a.c_in || a.N % fk || a.N != a.row_tiles * 16)

@@ -99,6 +99,8 @@ struct TileGemmArgs {
   int row_tiles;      // 16-row weight tiles (SwiGLU: 2 per 16 outputs, interleaved)
   int k_blocks;
   const void *act;    // activation fragments [T/16][k_blocks] of the operand type
+  const void *act_lo; // or NULL.  The low parts of a two-part operand (act + act_lo carries twice the significant bits):
+  int lo_row_begin, lo_row_end;  //   weight row tiles [lo_row_begin, lo_row_end) (multiples of 8) run the reduction a second time over act_lo
   int T;              // tokens (padded to 256)
   int T_live;         // tokens that exist
   int N;
@@ -117,6 +119,7 @@ struct TileGemmArgs {
   float *x_resid;     // EPI_RESID: [T][N]
   const float *g_out; // EPI_RESID: gamma of the norm that follows, or NULL: no operand for a next GEMM
   void *norm_out;     // EPI_RESID with g_out: (x - c) * g_out as fragments [T/16][N / FragK]
+  void *norm_out_lo;  // or NULL: what rounding norm_out to the operand type lost, as fragments of the same shape
   const f32x4 *c_in;  // EPI_RESID with g_out: [T], .x = the centre c (the token's mean at the previous norm)
   float2 *stat_out;   // EPI_RESID with g_out: [2 * n_row_blocks][T]
   void *act_out;      // EPI_ACT / EPI_SWIGLU: fragments [T/16][out_k_blocks]
@@ -165,6 +168,7 @@ struct EmbedArgs {
   // operand of the first GEMM, centred on the row's mean c (RMSNorm: c = 0): (x - c) * gamma
   const float *gamma;     // gamma of the first norm
   void *act_out;          // operand fragments [rows / 16][d / FragK]
+  void *act_lo_out;       // or NULL: what rounding act_out to the operand type lost, as fragments of the same shape
   int rms;
   // decode step: the row's centred sums and its centre
   float *stat_out;        // [32][4] (sum (x-c), sum (x-c)^2, 0, 0) per row

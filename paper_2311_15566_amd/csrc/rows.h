@@ -100,6 +100,12 @@ __device__ __forceinline__ void embed_row_block(const EmbedArgs &a, const int r,
         y[e] = t * a.gamma[v * PL + e];
       }
       store_piece<OT>(a.act_out, r, v * PL, a.d / FK, y);
+      if (a.act_lo_out) {
+        float lo[PL];
+#pragma unroll
+        for (int e = 0; e < PL; ++e) lo[e] = y[e] - Elem<OT>::to_f32(Elem<OT>::from_f32(y[e]));
+        store_piece<OT>(a.act_lo_out, r, v * PL, a.d / FK, lo);
+      }
     }
   }
   s1 = block_sum(s1, scratch);

@@ -24,6 +24,7 @@ struct Layout {
   int qkv_n;           // 3*Hs*Dh
   int w1_rows;         // Fs or 2*Fs
   int attn_splits;     // sequence splits of decode attention at Smax
+  bool two_part_qk;    // initial phase: the q and k columns of the q|k|v GEMM take a two-part (high + low halves) operand
   // offsets into device_mem
   size_t off_wte, off_wpe, off_lm, off_lnf_g, off_lnf_b, off_rope;
   std::vector<size_t> off_layer;       // start of each layer's block
@@ -34,7 +35,7 @@ struct Layout {
   size_t off_kv, kv_bytes, off_len, off_zero;  // off_zero: 1 KiB of zeros (an operand fragment of nothing)
   size_t off_ws, ws_bytes;             // workspace, doubles as upload staging
   // workspace sub-offsets (relative to off_ws)
-  size_t ws_x, ws_a, ws_qkv, ws_o, ws_u, ws_counters, ws_attn_part, ws_argmax;
+  size_t ws_x, ws_a, ws_a_lo, ws_qkv, ws_o, ws_u, ws_counters, ws_attn_part, ws_argmax;  // ws_a_lo: low parts of the q|k|v operand of the initial phase (two_part_qk), else unused
   size_t ws_vt;        // initial phase: one layer's values transposed, [Bmax*Hs][Dh][Smax rounded up to 64] halves
   size_t ws_pstat;     // initial phase: partial row sums [2 * ceil(d / 128)][Tmax] float2, then (mean, rstd, mean - centre, -) [Tmax] float4
   int n_counters;

@@ -127,6 +127,11 @@ bool compute_layout(const ss_model_desc &m, const ss_slice &s, int max_batch, in
   const int T = L->Tmax;
   L->ws_x = wtake((size_t)T * d * 4);
   L->ws_a = wtake((size_t)T * d * esz);  // operands of the initial phase: halves (bf16 models) or floats
+  // Models with rotary positions: their attention scores are several times more sensitive to the rounding of
+  // the normalised input to 11 bits than the others', and the prompt's keys carry that error into every later
+  // step, so the initial phase computes q and k from a two-part operand (22 bits).
+  L->two_part_qk = m.pos == SS_POS_ROPE && m.dtype == SS_DTYPE_BF16;
+  L->ws_a_lo = wtake(L->two_part_qk ? (size_t)T * d * esz : 0);
   L->ws_qkv = wtake((size_t)T * L->qkv_n * 4);
   L->ws_o = wtake((size_t)T * HD * esz);
   L->ws_u = wtake((size_t)T * L->Fs * esz);

@@ -70,9 +70,13 @@ def oracle_rows(w, W, seq_rows):
     return out
 
 
-def run_decode_case(ss, name):
+def run_decode_case(ss, name, seed=None, headroom=None):
+    """seed: another draw of the same shape (weights, prompt, forced tokens); headroom: a tighter max-abs the
+    worst case must stay under (a guard against drifting towards the bar, not the bar itself)."""
     import torch
     w = workload(name)
+    if seed is not None:
+        w.seed = seed
     t0 = time.time()
     W = make_weights(w.desc, w.slice, w.seed)
     prompt = make_tokens(w.seed, w.batch, w.s_in, w.desc["vocab"])
@@ -107,8 +111,10 @@ def run_decode_case(ss, name):
             e = compare(got_l[i, r], ref[r][pos], f"{name} row {rows[r]} step {i}")
             check_id(int(got_i[i, r]), ref[r][pos], f"{name} row {rows[r]} step {i}")
             worst = (max(worst[0], e[0]), max(worst[1], e[1]))
-    say(f"  {name}: worst max-abs {worst[0]:.3e}, worst rel-L2 {worst[1]:.3e} over {2 * (w.steps + 1)} (row, step) pairs")
+    say(f"  {name} (seed {w.seed}): worst max-abs {worst[0]:.3e}, worst rel-L2 {worst[1]:.3e} over {2 * (w.steps + 1)} (row, step) pairs")
     sh.destroy()
+    if headroom is not None:
+        assert worst[0] < headroom, f"{name} seed {w.seed}: worst max-abs {worst[0]:.3e} has drifted to the {MAX_ABS} bar"
 
 
 def test_fullsize_gpt20b_m4(ss, side_stream):
@@ -119,8 +125,11 @@ def test_fullsize_opt66b_m8(ss, side_stream):
     run_decode_case(ss, "opt66b_m8")
 
 
-def test_fullsize_llama30b_m2(ss, side_stream):
-    run_decode_case(ss, "llama30b_m2")
+@pytest.mark.parametrize("seed", [None, 2003, 3003])
+def test_fullsize_llama30b_m2(ss, side_stream, seed):
+    """The shape whose logits error is the largest of the three (15 layers of rotary attention): three draws,
+    each also held to a margin under the bar."""
+    run_decode_case(ss, "llama30b_m2", seed=seed, headroom=4.8e-2)
 
 
 def export_dense(ss, shard, lens):

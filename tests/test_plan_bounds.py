@@ -13,7 +13,7 @@ vp, i32, f32, sz = C.c_void_p, C.c_int32, C.c_float, C.c_size_t
 
 class EmbedArgs(C.Structure):
     _fields_ = [("hidden", vp), ("tokens", vp), ("wte", vp), ("wpe", vp), ("lens", vp), ("S", i32), ("max_pos", i32), ("x", vp), ("d", i32), ("V", i32),
-                ("gamma", vp), ("act_out", vp), ("rms", i32), ("stat_out", vp), ("cen_out", vp), ("pstat_out", vp), ("mr_out", vp)]
+                ("gamma", vp), ("act_out", vp), ("act_lo_out", vp), ("rms", i32), ("stat_out", vp), ("cen_out", vp), ("pstat_out", vp), ("mr_out", vp)]
 
 
 class GemmArgs(C.Structure):
