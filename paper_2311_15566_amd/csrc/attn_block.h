@@ -140,19 +140,26 @@ __device__ __forceinline__ void decode_attn_block(const DecodeAttnArgs &a, const
     load(kB, vB, base + STRIDE);
     float kn = 0.f, vraw = 0.f;  // the new token's (rotated) key and value element of thread e
     if (tid < DH) {
-      // q | k | v of the new token: the GEMM's partial sums (it may have cut K into slices) added in slice
-      // order; q and k rotated to position n (half-split pairing) when the model has a rotation table
-      auto at = [&](int off) {
-        float v = qraw[off];
-        for (int p = 1; p < qparts; ++p) v += qraw[(size_t)p * a.qkv_stride + off];
-        return v;
-      };
+      // q | k | v of the new token: the GEMM's partial sums (it may have cut K into slices), all requested at
+      // once and then added in slice order; q and k rotated to position n (half-split pairing) when the
+      // model has a rotation table
       constexpr int HALF = DH / 2;
       const int e = tid, eo = e < HALF ? e + HALF : e - HALF;
-      float qe = at(e), ke = at(HD + e);
-      vraw = at(2 * HD + e);
+      float pq[kQkvParts], pk[kQkvParts], pv[kQkvParts], pqo[kQkvParts], pko[kQkvParts];
+#pragma unroll
+      for (int p = 0; p < kQkvParts; ++p) {
+        if (p < qparts) {  // block-uniform
+          const float *src = qraw + (size_t)p * a.qkv_stride;
+          pq[p] = src[e], pk[p] = src[HD + e], pv[p] = src[2 * HD + e];
+          pqo[p] = src[eo], pko[p] = src[HD + eo];  // the rotation partners (unused without a table)
+        }
+      }
+      float qe = pq[0], ke = pk[0], qo = pqo[0], ko = pko[0];
+      vraw = pv[0];
+#pragma unroll
+      for (int p = 1; p < kQkvParts; ++p)
+        if (p < qparts) qe += pq[p], ke += pk[p], vraw += pv[p], qo += pqo[p], ko += pko[p];
       if (tab) {
-        const float qo = at(eo), ko = at(HD + eo);
         const float2 cs = tab[e < HALF ? e : e - HALF];
         if (e < HALF) qe = qe * cs.x - qo * cs.y, ke = ke * cs.x - ko * cs.y;
         else qe = qo * cs.y + qe * cs.x, ke = ko * cs.y + ke * cs.x;
@@ -209,13 +216,28 @@ __device__ __forceinline__ void decode_attn_block(const DecodeAttnArgs &a, const
     }
     if (!arrive_last(&a.counters[bh], live_splits, &s_flag)) return;
     if (tid < DH) {
+      // the partials in batches of eight splits, every load of a batch requested before the first is used
+      // (one round trip a batch); same order of additions as split by split, with a running maximum
       M = -1e30f, Lsum = 0.f, A = 0.f;
-      for (int s2 = 0; s2 < live_splits; ++s2) M = fmaxf(M, ld_dev(part + (size_t)s2 * (DH + 4) + DH));
-      for (int s2 = 0; s2 < live_splits; ++s2) {
-        const float *p = part + (size_t)s2 * (DH + 4);
-        const float f = __expf(ld_dev(p + DH) - M);
-        Lsum += ld_dev(p + DH + 1) * f;
-        A += ld_dev(p + tid) * f;
+      for (int s0 = 0; s0 < live_splits; s0 += 8) {
+        float pm[8], pl[8], pa[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          if (s0 + i < live_splits) {  // block-uniform
+            const float *p = part + (size_t)(s0 + i) * (DH + 4);
+            pm[i] = ld_dev(p + DH), pl[i] = ld_dev(p + DH + 1), pa[i] = ld_dev(p + tid);
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          if (s0 + i < live_splits) {
+            const float mn = fmaxf(M, pm[i]);
+            const float f0 = __expf(M - mn), f1 = __expf(pm[i] - mn);
+            Lsum = Lsum * f0 + pl[i] * f1;
+            A = A * f0 + pa[i] * f1;
+            M = mn;
+          }
+        }
       }
     }
   }
