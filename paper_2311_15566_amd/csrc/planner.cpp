@@ -6,6 +6,7 @@
 #include <limits>
 #include <numeric>
 #include <utility>
+#include <iterator>
 #include <vector>
 
 #include "../../include/spotshard_plan.h"
@@ -105,31 +106,36 @@ ss_status ss_match_devices(int32_t n, const uint64_t *weight, int32_t *position_
 ss_status ss_migration_order(int32_t n_layers, int32_t n_instances, const int64_t *delta, int64_t u_max,
                              int32_t *order) {
   if (n_layers < 1 || n_instances < 1 || !delta || !order) SS_FAIL(SS_EINVAL, "bad migration-order arguments");
-  std::vector<int64_t> U(n_instances, 0);
-  std::vector<int> left;
-  int n_out = 0;
-  auto peak_after = [&](int l) {
-    int64_t mx = std::numeric_limits<int64_t>::min();
-    for (int i = 0; i < n_instances; ++i) mx = std::max(mx, U[i] + delta[(size_t)l * n_instances + i]);
-    return mx;
+  // usage[i]: instance i's buffer memory after the layers placed so far
+  std::vector<int64_t> usage(n_instances, 0);
+  auto peak_with = [&](int l) {
+    const int64_t *d = delta + (size_t)l * n_instances;
+    int64_t peak = usage[0] + d[0];
+    for (int i = 1; i < n_instances; ++i) peak = std::max(peak, usage[i] + d[i]);
+    return peak;
   };
-  auto apply = [&](int l) {
-    for (int i = 0; i < n_instances; ++i) U[i] += delta[(size_t)l * n_instances + i];
-    order[n_out++] = l;
+  auto place = [&](int l) {
+    const int64_t *d = delta + (size_t)l * n_instances;
+    for (int i = 0; i < n_instances; ++i) usage[i] += d[i];
   };
-  for (int l = 0; l < n_layers; ++l) {
-    if (peak_after(l) <= u_max) apply(l);
-    else left.push_back(l);
-  }
-  while (!left.empty()) {
-    size_t best = 0;
-    int64_t best_peak = peak_after(left[0]);
-    for (size_t k = 1; k < left.size(); ++k) {
-      const int64_t p = peak_after(left[k]);
-      if (p < best_peak) best_peak = p, best = k;
-    }
-    apply(left[best]);
-    left.erase(left.begin() + best);
+  // The order is a partition of the layer list followed by a selection sort of its second part.
+  // Front part: one in-order sweep keeps every layer that fits under u_max on top of the layers kept before it
+  // (partition_copy visits its input once, front to back); the others are set aside in index order.
+  std::vector<int32_t> all(n_layers), late;
+  std::iota(all.begin(), all.end(), 0);
+  late.reserve(n_layers);
+  int32_t *front_end = std::partition_copy(all.begin(), all.end(), order, std::back_inserter(late), [&](int32_t l) {
+                         if (peak_with(l) > u_max) return false;
+                         place(l);
+                         return true;
+                       }).first;
+  // Back part: of the layers set aside, always the one that leaves the lowest peak goes next (min_element takes the
+  // first of equals, and rotating it to the front keeps the rest in index order: lowest index on ties).
+  std::copy(late.begin(), late.end(), front_end);
+  for (int32_t *next = front_end; next != order + n_layers; ++next) {
+    int32_t *pick = std::min_element(next, order + n_layers, [&](int32_t a, int32_t b) { return peak_with(a) < peak_with(b); });
+    std::rotate(next, pick, pick + 1);
+    place(*next);
   }
   return SS_OK;
 }
@@ -137,22 +143,27 @@ ss_status ss_migration_order(int32_t n_layers, int32_t n_instances, const int64_
 ss_status ss_progressive_plan(int32_t n_layers, const int32_t *order, const int32_t *stage_of_layer, int32_t n_stages,
                               int32_t *kind, int32_t *arg) {
   if (n_layers < 1 || n_stages < 1 || !order || !stage_of_layer || !kind || !arg) SS_FAIL(SS_EINVAL, "bad plan arguments");
-  std::vector<int> waiting(n_stages, 0);
-  std::vector<char> seen(n_layers, 0);
-  for (int l = 0; l < n_layers; ++l) {
-    if (stage_of_layer[l] < 0 || stage_of_layer[l] >= n_stages) SS_FAIL(SS_EINVAL, "layer %d has no stage", l);
-    waiting[stage_of_layer[l]]++;
-  }
-  for (int p = 0; p < n_stages; ++p)
-    if (waiting[p] == 0) SS_FAIL(SS_EINVAL, "stage %d has no layer", p);
-  int k = 0;
-  kind[k] = SS_PLAN_MIGRATE_CACHE, arg[k++] = -1;
+  // A stage can start right after the slot of `order` in which the last of its layers arrives: find that slot
+  // for every stage first, then write the plan out in one go.
+  std::vector<int> slot_of_layer(n_layers, -1), last_slot(n_stages, -1);
   for (int i = 0; i < n_layers; ++i) {
     const int l = order[i];
-    if (l < 0 || l >= n_layers || seen[l]) SS_FAIL(SS_EINVAL, "order is not a permutation of the layers");
-    seen[l] = 1;
-    kind[k] = SS_PLAN_MIGRATE_LAYER, arg[k++] = l;
-    if (--waiting[stage_of_layer[l]] == 0) kind[k] = SS_PLAN_START_STAGE, arg[k++] = stage_of_layer[l];
+    if (l < 0 || l >= n_layers || slot_of_layer[l] >= 0) SS_FAIL(SS_EINVAL, "order is not a permutation of the layers");
+    slot_of_layer[l] = i;
+  }
+  for (int l = 0; l < n_layers; ++l) {
+    const int p = stage_of_layer[l];
+    if (p < 0 || p >= n_stages) SS_FAIL(SS_EINVAL, "layer %d has no stage", l);
+    last_slot[p] = std::max(last_slot[p], slot_of_layer[l]);
+  }
+  for (int p = 0; p < n_stages; ++p)
+    if (last_slot[p] < 0) SS_FAIL(SS_EINVAL, "stage %d has no layer", p);
+  int k = 0;
+  kind[k] = SS_PLAN_MIGRATE_CACHE, arg[k++] = -1;   // the cache context goes first
+  for (int i = 0; i < n_layers; ++i) {
+    const int p = stage_of_layer[order[i]];
+    kind[k] = SS_PLAN_MIGRATE_LAYER, arg[k++] = order[i];
+    if (last_slot[p] == i) kind[k] = SS_PLAN_START_STAGE, arg[k++] = p;
   }
   return SS_OK;
 }
