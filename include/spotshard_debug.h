@@ -23,9 +23,11 @@ ss_status ss_set_graph_launch(ss_shard *shard, int32_t enabled);
 /* Test aid, process-wide: force the launch shape of the decode GEMMs built from now on (a shard's
  * captured graphs are keyed by the forced shape, so the change takes effect at once): weight tiles per
  * block at most (1, 2, 3 or 6; where a GEMM has no such kernel instance the nearest one; 0 = the
- * library's choice) and the slices the q|k|v GEMM cuts K into (1..8; 0 = the library's choice; other
- * GEMMs never cut K).  The library chooses per shape by a cost rule.  The tiles per block never change
- * a bit of the result; the number of K slices changes the order of the q|k|v sums. */
+ * library's choice) and the slices the q|k|v GEMM cuts K into (1..8; 0 = the library's choice; with more
+ * than 16 batch rows the first FFN matrix of a model without gate is cut the same way and its activation
+ * becomes a kernel of its own; other GEMMs never cut K).  The library chooses per shape by a cost rule.
+ * The tiles per block never change a bit of the result; the number of K slices changes the order of the
+ * sums. */
 ss_status ss_debug_force_gemm_shape(int32_t tiles_per_block, int32_t k_slices);
 
 /* Test aid, process-wide: force the token block of the initial phase's tiled GEMMs (the initial

@@ -50,6 +50,11 @@ def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
                           "(there is no CPU fallback)")
+    # PyTorch first: its wheel brings a HIP runtime of its own and loads it into the global symbol scope.  The
+    # library's HIP calls (its kernels' registration at load time included) must end up in that same runtime, or
+    # the streams and device pointers PyTorch hands over belong to a runtime the library's calls do not reach
+    # (seen as "no ROCm-capable device is detected" on the first copy).
+    import torch  # noqa: F401
     L = C.CDLL(LIB_PATH)
     vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
     L.ss_last_error.restype = C.c_char_p

@@ -206,12 +206,13 @@ static void attn_plan(const Layout &L, int B, int *rows_per_block, int *splits, 
 // ---------------------------------------------------------------------------
 struct GemmShape {
   int nw, n_blocks, k_split;
+  double est_us;  // the rule's estimate of the streaming time
 };
 struct ShapeKey {
-  int epi, row_tiles, k_blocks, B, ks, split_max, split_cost_x10, forced_nw, forced_split;
+  int epi, row_tiles, k_blocks, B, ks, split_max, split_cost_x10, forced_nw, forced_split, stat_groups;
   bool operator<(const ShapeKey &o) const {
-    return std::tie(epi, row_tiles, k_blocks, B, ks, split_max, split_cost_x10, forced_nw, forced_split) <
-           std::tie(o.epi, o.row_tiles, o.k_blocks, o.B, o.ks, o.split_max, o.split_cost_x10, o.forced_nw, o.forced_split);
+    return std::tie(epi, row_tiles, k_blocks, B, ks, split_max, split_cost_x10, forced_nw, forced_split, stat_groups) <
+           std::tie(o.epi, o.row_tiles, o.k_blocks, o.B, o.ks, o.split_max, o.split_cost_x10, o.forced_nw, o.forced_split, o.stat_groups);
   }
 };
 static std::map<ShapeKey, GemmShape> g_shapes;
@@ -220,22 +221,35 @@ static std::atomic<uint64_t> g_shape_epoch{0};  // bumped when a forced shape ch
 static std::atomic<uint64_t> g_next_id{1};
 uint64_t next_shard_id() { return g_next_id.fetch_add(1); }
 static int g_forced_nw = 0, g_forced_split = 0;  // test aids: 0 = the rule's choice
+static int forced_k_slices() {
+  std::lock_guard<std::mutex> lock(g_shape_mu);
+  return g_forced_split;
+}
 
 constexpr int kComputeUnits = 256;
 constexpr double kUnitKiBPerUs = 45.0e9 / 1024.0 / 1.0e6;   // what one compute unit takes in
 constexpr double kHbmKiBPerUs = 6.8e12 / 1024.0 / 1.0e6;    // a long stream from HBM
 
 // estimated microseconds of streaming (without the few microseconds every launch costs); two_fit: two blocks of the instance fit on a unit
-static double shape_cost(int tu, int units, int k_blocks, double act, bool two_fit, int n_blocks, int S, double split_cost) {
+static double shape_cost(int tu, int units, int k_blocks, double act, double stat_kib, bool two_fit, int n_blocks, int S, double split_cost) {
   const int upb = ceil_div(units, n_blocks);                  // units of the largest block
   const double kslice = (double)ceil_div(k_blocks, S);
   const int blocks = n_blocks * S;
-  const double largest = ((double)upb * tu + act) * kslice;   // KiB the largest block takes in
+  const double largest = ((double)upb * tu + act) * kslice + stat_kib;   // KiB the largest block takes in
   double t_cu;
   if (blocks <= kComputeUnits) {
     t_cu = largest / kUnitKiBPerUs;
+  } else if (act >= 2.0) {
+    // More than 16 batch rows (one block a unit at a time, every block bound by the unit's intake): the blocks run in
+    // rounds of 256, and a round takes what its largest block takes; a few blocks over a multiple of 256 cost a whole
+    // round (measured on the OPT-66B shape's LM head: 524 blocks of 6 tiles took as long as 1048 of 3).  The blocks
+    // with one unit more come first, so only the first rounds hold them.
+    const int rounds = ceil_div(blocks, kComputeUnits), big = units % n_blocks == 0 ? blocks : (units % n_blocks) * S;
+    const double smaller = ((double)(units / n_blocks) * tu + act) * kslice + stat_kib;
+    t_cu = 0.0;
+    for (int r = 0; r < rounds; ++r) t_cu += (r * kComputeUnits < big ? largest : smaller) / kUnitKiBPerUs;
   } else {
-    const double total = ((double)units * tu + (double)n_blocks * act) * k_blocks;  // KiB all blocks take in
+    const double total = ((double)units * tu + (double)n_blocks * act) * k_blocks + (double)blocks * stat_kib;  // KiB all blocks take in
     t_cu = total / (kComputeUnits * kUnitKiBPerUs) * (two_fit ? 1.0 : 1.15) + 0.5 * largest / kUnitKiBPerUs;
   }
   const double t_hbm = (double)units * tu * k_blocks / kHbmKiBPerUs;
@@ -244,10 +258,17 @@ static double shape_cost(int tu, int units, int k_blocks, double act, bool two_f
 }
 
 static GemmShape shape_rule(int epi, int row_tiles, int k_blocks, int B, int ks, int split_max, double split_cost,
-                            int forced_nw, int forced_split) {
+                            int forced_nw, int forced_split, int stat_groups) {
   const int tu = epi == EPI_SWIGLU ? 2 : 1, units = row_tiles / tu;
   const double act = B <= 8 ? 0.5 : (B <= 16 ? 1.0 : 2.0);   // KiB of activation fragments per k block a block reads
-  const bool wide = B <= 16 && (epi == EPI_F32 || epi == EPI_SWIGLU);
+  // six tiles a block: gate/up pairs and float output for up to 16 rows; for more rows float output only where the block adds
+  // up no row statistics (that instance has no registers left to request them early), and the logits (a kernel long
+  // enough not to mind)
+  const bool wide = B <= 16 ? (epi == EPI_F32 || epi == EPI_SWIGLU) : ((epi == EPI_F32 && stat_groups == 0) || epi == EPI_LOGITS);
+  // KiB of the producer's partial row sums every block of a normalised GEMM reads (a float4 per pair of weight tiles and
+  // row): counted for more than 16 rows, where they reach 147 KiB a block on the OPT-66B shape; the constants for up to
+  // 16 rows were fitted with them inside
+  const double stat_kib = B > 16 ? (double)stat_groups * B * 16.0 / 1024.0 : 0.0;
   std::vector<int> instances;
   if (epi == EPI_SWIGLU) instances = {2};
   else instances = {1, 2, 3};
@@ -258,7 +279,7 @@ static GemmShape shape_rule(int epi, int row_tiles, int k_blocks, int B, int ks,
     else if (nw > 3) nw = (nw == 6 && wide) ? 6 : 3;
     instances = {nw};
   }
-  GemmShape best = {0, 0, 1};
+  GemmShape best = {0, 0, 1, 0.0};
   double best_t = 0;
   for (int S = 1; S <= std::max(1, split_max); ++S) {
     if (forced_split && S != forced_split) continue;
@@ -270,26 +291,35 @@ static GemmShape shape_rule(int epi, int row_tiles, int k_blocks, int B, int ks,
       for (int upb = upb_max; upb >= 1; --upb) {
         const int n_blocks = ceil_div(units, upb);
         if (ceil_div(units, n_blocks) != upb) continue;       // the same share-out as a smaller size
-        const double t = shape_cost(tu, units, k_blocks, act, two_fit, n_blocks, S, split_cost);
-        if (!best.nw || t < best_t) best = {nw, n_blocks, S}, best_t = t;
+        const double t = shape_cost(tu, units, k_blocks, act, stat_kib, two_fit, n_blocks, S, split_cost);
+        if (!best.nw || t < best_t) best = {nw, n_blocks, S, t}, best_t = t;
         if (forced_nw) break;
+      }
+      // more than 16 rows and several rounds: block counts that fill whole rounds
+      if (B > 16 && !forced_nw && S == 1) {
+        for (int n_blocks = 2 * kComputeUnits; n_blocks <= units; n_blocks += kComputeUnits) {
+          if (ceil_div(units, n_blocks) > upb_max) continue;
+          const double t = shape_cost(tu, units, k_blocks, act, stat_kib, two_fit, n_blocks, S, split_cost);
+          if (!best.nw || t < best_t) best = {nw, n_blocks, S, t}, best_t = t;
+        }
       }
     }
   }
-  if (!best.nw) best = {epi == EPI_SWIGLU ? 2 : 1, units, 1};
+  if (!best.nw) best = {epi == EPI_SWIGLU ? 2 : 1, units, 1, 0.0};
   return best;
 }
 
-static void shape_gemm(StreamGemmArgs &a, int epi) {
+// fills in the launch shape; returns the rule's estimate of the streaming time (us)
+static double shape_gemm(StreamGemmArgs &a, int epi) {
   const int split_max = (epi == EPI_F32 && a.split_ok > 1) ? std::min(a.split_ok, 8) : 1;
   GemmShape v;
   {
     std::lock_guard<std::mutex> lock(g_shape_mu);
     const int forced_split = std::min(g_forced_split, split_max);
-    const ShapeKey key{epi, a.row_tiles, a.k_blocks, a.B, a.ks, split_max, (int)(a.split_cost_us * 10.f), g_forced_nw, forced_split};
+    const ShapeKey key{epi, a.row_tiles, a.k_blocks, a.B, a.ks, split_max, (int)(a.split_cost_us * 10.f), g_forced_nw, forced_split, a.stat_groups};
     auto it = g_shapes.find(key);
     if (it == g_shapes.end())
-      it = g_shapes.emplace(key, shape_rule(epi, a.row_tiles, a.k_blocks, a.B, a.ks, split_max, a.split_cost_us, g_forced_nw, forced_split)).first;
+      it = g_shapes.emplace(key, shape_rule(epi, a.row_tiles, a.k_blocks, a.B, a.ks, split_max, a.split_cost_us, g_forced_nw, forced_split, a.stat_groups)).first;
     v = it->second;
   }
   a.nw = v.nw, a.n_blocks = v.n_blocks, a.k_split = v.k_split;
@@ -298,6 +328,7 @@ static void shape_gemm(StreamGemmArgs &a, int epi) {
     a.u_base = units / a.n_blocks, a.u_rem = units % a.n_blocks, a.k_slice = ceil_div(a.k_blocks, std::max(1, a.k_split));
   }
   a.part_stride = v.k_split > 1 ? (size_t)32 * a.ld_out : 0;
+  return v.est_us;
 }
 static int pick_ks(int k_blocks) { return k_blocks >= 16 ? 8 : 4; }  // waves per block
 
@@ -435,8 +466,35 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
       a.ks = pick_ks(a.k_blocks);
       normed(a, s->wg_1[l], s->cb_1[l], i);
       a.act_out = s->dec_at(L.ws_ud), a.out_k_blocks = L.Fs / FK, a.act_kind = m.act;
-      shape_gemm(a, m.act == SS_ACT_SWIGLU ? EPI_SWIGLU : EPI_ACT);
-      ph.gx = a.n_blocks, ph.gy = 1;
+      const double whole = shape_gemm(a, m.act == SS_ACT_SWIGLU ? EPI_SWIGLU : EPI_ACT);
+      // More than 16 batch rows: every block reads two activation fragments per k block whatever its tiles, and
+      // the tiles alone fill few compute units.  K in slices (float partial outputs, wide blocks) streams faster
+      // and costs one more small kernel, which adds the slices up and applies the activation.
+      if (B > 16 && L.ffnpart_bytes && m.act != SS_ACT_SWIGLU && forced_k_slices() != 1) {
+        Phase cut = ph;
+        StreamGemmArgs &c = cut.g;
+        c.act_out = nullptr, c.out_k_blocks = 0;
+        // raw partial products: the normalisation moves to the kernel that adds them up
+        c.stat_in = nullptr, c.stat_groups = 0, c.wg = nullptr, c.cb = nullptr, c.cen = nullptr, c.publish = 0;
+        c.out_f32 = (float *)(s->dec_at(L.ws_ffnpart)), c.ld_out = L.Fs;
+        c.split_ok = kQkvParts, c.split_cost_us = 4.0f;  // the extra kernel
+        const double sliced = shape_gemm(c, EPI_F32);
+        if (c.k_split > 1 && (forced_k_slices() > 1 || sliced < whole)) {
+          cut.gx = c.n_blocks * c.k_split, cut.gy = 1, cut.epi = EPI_F32;
+          plan->push_back(cut);
+          Phase fx = {};
+          fx.kind = PH_FFN_ACT, fx.shard = i;
+          StreamGemmArgs &f = fx.g;
+          f.B = B, f.N = L.Fs, f.out_f32 = c.out_f32, f.ld_out = c.ld_out, f.k_split = c.k_split, f.part_stride = c.part_stride;
+          f.act_out = a.act_out, f.out_k_blocks = a.out_k_blocks, f.act_kind = m.act;
+          f.stat_in = a.stat_in, f.stat_groups = a.stat_groups, f.norm_dim = a.norm_dim, f.rms = a.rms, f.eps = a.eps;
+          f.wg = a.wg, f.cb = a.cb, f.cen = a.cen, f.publish = a.publish;
+          fx.gx = act_fixup_blocks(f), fx.gy = B;
+          plan->push_back(fx);
+          continue;
+        }
+      }
+      ph.gx = a.n_blocks, ph.gy = 1, ph.epi = m.act == SS_ACT_SWIGLU ? EPI_SWIGLU : EPI_ACT;
       plan->push_back(ph);
     }
     const float *next_gamma = l + 1 < L0.Ls ? g0->layers[l + 1].ln1_g : g0->lnf_g;
@@ -493,7 +551,7 @@ struct Bracket {
 // one phase as a kernel of its own
 static ss_status launch_phase(Shard *g0, const Phase &ph, hipStream_t st) {
   const int dt = g0->m.dtype;
-  Bracket br(g0, ph.kind);
+  Bracket br(g0, ph.kind == PH_FFN_ACT ? (int)PH_FFN_UP : ph.kind);  // the sliced first FFN matrix and its activation kernel are one class
   switch (ph.kind) {
     case PH_EMBED:
       if (dt == SS_DTYPE_BF16) SS_LAUNCH_KERNEL(embed_rows<bf16_t>, dim3(ph.gx), dim3(256), 0, st, ph.e);
@@ -503,7 +561,8 @@ static ss_status launch_phase(Shard *g0, const Phase &ph, hipStream_t st) {
     case PH_QKV: return launch_stream_gemm(dt, EPI_F32, ph.g, st);
     case PH_ATTN: return launch_decode_attn(dt, ph.at, st);
     case PH_RESID: return launch_stream_gemm(dt, EPI_RESID, ph.g, st);
-    case PH_FFN_UP: return launch_stream_gemm(dt, g0->m.act == SS_ACT_SWIGLU ? EPI_SWIGLU : EPI_ACT, ph.g, st);
+    case PH_FFN_UP: return launch_stream_gemm(dt, ph.epi, ph.g, st);
+    case PH_FFN_ACT: return launch_act_fixup(dt, ph.g, st);
     case PH_LM_HEAD: return launch_stream_gemm(dt, EPI_LOGITS, ph.g, st);
     case PH_COMMIT: return launch_commit(ph.g, st);
   }

@@ -82,6 +82,10 @@ struct StreamGemmArgs {
 ss_status launch_stream_gemm(int dtype, int epi, const StreamGemmArgs &a, hipStream_t st);
 ss_status check_stream_gemm(int dtype, int epi, const StreamGemmArgs &a);  // the shape checks the launcher makes
 int stream_gemm_units_per_block(int epi, const StreamGemmArgs &a);  // units (tiles, SwiGLU: pairs) of the largest block
+// the activation of a first FFN matrix whose K was cut into slices: adds the partial outputs, writes operand fragments
+ss_status launch_act_fixup(int dtype, const StreamGemmArgs &a, hipStream_t st);
+ss_status check_act_fixup(int dtype, const StreamGemmArgs &a);
+int act_fixup_blocks(const StreamGemmArgs &a);
 // wg / cb of a weight matrix in fragment order (gamma NULL: wg is not written)
 ss_status launch_fold_norm(int dtype, const void *w, int row_tiles, int k_blocks, const float *gamma, const float *beta,
                            const float *bias, float *wg, float *cb, hipStream_t st);
@@ -155,7 +159,8 @@ ss_status launch_decode_attn(int dtype, const DecodeAttnArgs &a, hipStream_t st)
 ss_status check_decode_attn(const DecodeAttnArgs &a);
 
 // One phase of the decode step = one kernel launch.
-enum PhaseKind { PH_EMBED = 0, PH_QKV = 1, PH_ATTN = 2, PH_RESID = 3, PH_FFN_UP = 4, PH_LM_HEAD = 5, PH_COMMIT = 6 };
+enum PhaseKind { PH_EMBED = 0, PH_QKV = 1, PH_ATTN = 2, PH_RESID = 3, PH_FFN_UP = 4, PH_LM_HEAD = 5, PH_COMMIT = 6,
+                 PH_FFN_ACT = 7 /* the activation of a first FFN matrix whose K was cut into slices */ };
 struct EmbedArgs {
   const float *hidden;    // [rows][d] float32: the previous pipeline stage's output, in place of a token lookup; or NULL
   const int32_t *tokens;  // [rows]
@@ -182,6 +187,7 @@ struct Phase {
   int kind;      // PhaseKind; also the timing class
   int gx, gy;    // blocks: (rows, 1), (tile pairs, 1) or (batch*heads, splits)
   int shard;     // index of the shard in the group that owns the phase's scratch
+  int epi;       // PH_FFN_UP: the GEMM's epilogue (activation, gate/up pair, or float partial outputs of K slices)
   EmbedArgs e;
   StreamGemmArgs g;   // PH_COMMIT uses B, lens, n_lens, commit_inc and, after an LM head, am_val, am_idx, n_blocks, next_tokens
   DecodeAttnArgs at;

@@ -43,6 +43,7 @@ struct Layout {
   // ((x - c) * gamma), partial row sums [d/16][32][2], the rows' centres [32], q|k|v [32][qkv_n] f32,
   // attention output and FFN activation operands
   size_t ws_xd, ws_ad, ws_statd, ws_cen, ws_qkvd, ws_od, ws_ud;
+  size_t ws_ffnpart, ffnpart_bytes;  // partial outputs of a first FFN matrix whose K is cut into slices (more than 16 batch rows, no gate): [kQkvParts][32][Fs] float32, else 0 bytes
   size_t ws_dec_end;   // the decode step's scratch is workspace bytes [ws_xd, ws_dec_end): the buffers above, then
                        // the attention counters and partials and the LM head's candidates
   size_t total;

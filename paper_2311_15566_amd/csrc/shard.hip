@@ -151,6 +151,8 @@ bool compute_layout(const ss_model_desc &m, const ss_slice &s, int max_batch, in
   L->ws_counters = wtake((size_t)L->n_counters * 4);
   L->ws_attn_part = wtake((size_t)max_batch * L->Hs * L->attn_splits * (L->Dh + 4) * 4);
   L->ws_argmax = wtake((size_t)ceil_div(L->V, 16) * 32 * 8);  // per LM-head block and row a best logit and its index; at most a block per weight tile
+  L->ffnpart_bytes = (max_batch > 16 && m.act != SS_ACT_SWIGLU) ? (size_t)kQkvParts * 32 * L->Fs * 4 : 0;
+  L->ws_ffnpart = wtake(L->ffnpart_bytes);
   L->ws_dec_end = w;
   // upload staging shares the workspace: it must hold the largest raw tensor slice
   size_t stage = std::max((size_t)L->V * d, (size_t)d * std::max(std::max(HD, L->Fs), 1)) * esz;

@@ -4,6 +4,8 @@
 #include <math.h>
 #include <stdlib.h>
 
+#include <atomic>
+
 #include "kernels.h"
 #include "mma.h"
 
@@ -39,7 +41,13 @@ __global__ void __launch_bounds__(KSM * 64, 2) stream_gemm(StreamGemmArgs a) {
   constexpr int NITEMS = NU * NB;          // epilogue items: (unit, batch tile)
   constexpr int NIT = (NITEMS + 3) / 4;    // items per wave at most (a block has 4 or 8 waves)
   static_assert(NW % TU == 0, "a block holds whole units");
-  __shared__ GemmShared<NB, KSM, NW> sh;
+  // The waves' sums meet in LDS.  The widest instance (6 tiles x 2 batch tiles) needs more than the 64 KiB a
+  // kernel may declare, and takes its LDS at launch instead.
+  typedef GemmShared<NB, KSM, NW> Shared;
+  constexpr bool DYN_LDS = sizeof(Shared) > 64 * 1024;
+  extern __shared__ __align__(16) unsigned char dyn_lds[];
+  __shared__ __align__(16) unsigned char fix_lds[DYN_LDS ? 16 : sizeof(Shared)];
+  Shared &sh = *reinterpret_cast<Shared *>(DYN_LDS ? dyn_lds : fix_lds);
   const int tid = threadIdx.x, lane = tid & 63, KS = blockDim.x >> 6;
   // The wave's number as a scalar: everything derived from it (its k range, its epilogue items) is then
   // wave-uniform for the compiler too, and the branches on it are real branches.  (A matrix-core
@@ -153,7 +161,7 @@ __global__ void __launch_bounds__(KSM * 64, 2) stream_gemm(StreamGemmArgs a) {
   // weight batches, and added after the main loop, when they have long arrived: nothing waits
   // for them now.
   constexpr bool NORMED = EPI != EPI_RESID;
-  constexpr int SR = NORMED ? (GLU ? 2 : 4) : 0;
+  constexpr int SR = NORMED ? (NB * NW >= 12 ? 1 : (GLU ? 2 : 4)) : 0;  // (the widest instance has no registers to spare)
   // (the split of the partials over threads depends on the batch size only, so the sums come out
   // the same whatever the launch shape: 8 or 16 rows a slice, a thread takes that row of every
   // batch tile of the block)
@@ -339,8 +347,9 @@ ss_status check_stream_gemm(int dtype, int epi, const StreamGemmArgs &a) {
   const int tu = epi == EPI_SWIGLU ? 2 : 1, units = a.row_tiles / tu;
   if (a.row_tiles < 1 || a.k_blocks < 1 || (a.ks != 4 && a.ks != 8) || a.N < 1 || a.N > a.row_tiles * 16)
     SS_FAIL(SS_EINVAL, "decode GEMM: bad shape (tiles %d, k blocks %d, waves %d, N %d)", a.row_tiles, a.k_blocks, a.ks, a.N);
-  // instances: 1, 2 or 3 tiles a block; a gate/up pair; or the wide blocks (6 tiles) for up to 16 batch rows
-  const bool wide_ok = a.B <= 16 && (epi == EPI_F32 || epi == EPI_SWIGLU);
+  // instances: 1, 2 or 3 tiles a block; a gate/up pair; or the wide blocks (6 tiles): float output, gate/up pairs for up
+  // to 16 batch rows, logits for more
+  const bool wide_ok = epi == EPI_F32 || (epi == EPI_SWIGLU && a.B <= 16) || (epi == EPI_LOGITS && a.B > 16);
   const bool nw_ok = epi == EPI_SWIGLU ? (a.nw == 2 || (a.nw == 6 && wide_ok)) : ((a.nw >= 1 && a.nw <= 3) || (a.nw == 6 && wide_ok));
   if (!nw_ok) SS_FAIL(SS_EINVAL, "decode GEMM: %d weight tiles per block", a.nw);
   if (a.n_blocks < 1 || a.n_blocks > units || stream_gemm_units_per_block(epi, a) * tu > a.nw)
@@ -382,19 +391,43 @@ ss_status check_stream_gemm(int dtype, int epi, const StreamGemmArgs &a) {
   return SS_OK;
 }
 
+// the widest instance: LDS above the static limit is asked for once per process, then at every launch
+template <typename T, int NB, int KSM, int EPI>
+static ss_status launch_wide(const StreamGemmArgs &a, dim3 grid, dim3 block, hipStream_t st) {
+  constexpr size_t lds = sizeof(GemmShared<NB, KSM, 6>);
+  if constexpr (lds > 64 * 1024) {
+    static std::atomic<bool> allowed[64];  // per device
+    int dev = 0;
+    SS_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) SS_FAIL(SS_EINVAL, "decode GEMM: device %d", dev);
+    if (!allowed[dev].load()) {
+      SS_HIP(hipFuncSetAttribute((const void *)stream_gemm<T, NB, false, EPI, KSM, 6>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 (int)lds));
+      allowed[dev].store(true);
+    }
+    SS_LAUNCH_KERNEL((stream_gemm<T, NB, false, EPI, KSM, 6>), grid, block, lds, st, a);
+  } else {
+    SS_LAUNCH_KERNEL((stream_gemm<T, NB, false, EPI, KSM, 6>), grid, block, 0, st, a);
+  }
+  return SS_OK;
+}
+
 template <typename T, int NB, int KSM>
-static void launch_stream_gemm_t(int epi, const StreamGemmArgs &a, dim3 grid, dim3 block, hipStream_t st) {
+static ss_status launch_stream_gemm_t(int epi, const StreamGemmArgs &a, dim3 grid, dim3 block, hipStream_t st) {
 #define SS_LAUNCH(GLU, EPI, NW) SS_LAUNCH_KERNEL((stream_gemm<T, NB, GLU, EPI, KSM, NW>), grid, block, 0, st, a)
   if (epi == EPI_SWIGLU) {
     if constexpr (NB == 1) {
       if (a.nw == 6) {
         SS_LAUNCH(true, EPI_SWIGLU, 6);
-        return;
+        return SS_OK;
       }
     }
     SS_LAUNCH(true, EPI_SWIGLU, 2);
-  } else if (a.nw == 6) {  // wide blocks: q|k|v
-    if constexpr (NB == 1) SS_LAUNCH(false, EPI_F32, 6);
+  } else if (a.nw == 6) {  // wide blocks: float output; logits for more than 16 batch rows
+    if constexpr (NB == 2) {
+      if (epi == EPI_LOGITS) return launch_wide<T, NB, KSM, EPI_LOGITS>(a, grid, block, st);
+    }
+    return launch_wide<T, NB, KSM, EPI_F32>(a, grid, block, st);
   } else if (a.nw == 3) {
     if (epi == EPI_F32) SS_LAUNCH(false, EPI_F32, 3);
     else if (epi == EPI_ACT) SS_LAUNCH(false, EPI_ACT, 3);
@@ -412,6 +445,7 @@ static void launch_stream_gemm_t(int epi, const StreamGemmArgs &a, dim3 grid, di
     else SS_LAUNCH(false, EPI_LOGITS, 2);
   }
 #undef SS_LAUNCH
+  return SS_OK;
 }
 
 ss_status launch_stream_gemm(int dtype, int epi, const StreamGemmArgs &a, hipStream_t st) {
@@ -419,12 +453,108 @@ ss_status launch_stream_gemm(int dtype, int epi, const StreamGemmArgs &a, hipStr
   const dim3 grid(a.n_blocks * (a.k_split > 1 ? a.k_split : 1)), block(a.ks * 64);
   const int nb = a.B <= 16 ? 1 : 2;
   if (dtype == SS_DTYPE_BF16) {
-    if (nb == 1) launch_stream_gemm_t<bf16_t, 1, 8>(epi, a, grid, block, st);
-    else launch_stream_gemm_t<bf16_t, 2, 8>(epi, a, grid, block, st);
+    if (nb == 1) SS_TRY((launch_stream_gemm_t<bf16_t, 1, 8>(epi, a, grid, block, st)));
+    else SS_TRY((launch_stream_gemm_t<bf16_t, 2, 8>(epi, a, grid, block, st)));
   } else {
-    if (nb == 1) launch_stream_gemm_t<float, 1, 8>(epi, a, grid, block, st);
-    else launch_stream_gemm_t<float, 2, 8>(epi, a, grid, block, st);
+    if (nb == 1) SS_TRY((launch_stream_gemm_t<float, 1, 8>(epi, a, grid, block, st)));
+    else SS_TRY((launch_stream_gemm_t<float, 2, 8>(epi, a, grid, block, st)));
   }
+  SS_HIP(hipGetLastError());
+  return SS_OK;
+}
+
+// ---------------------------------------------------------------------------
+// The first FFN matrix with K cut into slices (more than 16 batch rows, where the tiles alone fill too
+// few compute units and every block pays for the whole activation slab): the GEMM leaves S raw
+// partial products in float32 (EPI_F32 above, without normalisation or bias: its blocks then read no row
+// statistics at all, which at d = 9216 are 147 KB a block), and this kernel adds them in slice order,
+// applies the deferred normalisation rstd * (sum - (mean - c) * wg[n]) + cb[n] and the activation, and
+// writes the second FFN matrix's operand fragments.
+// grid = (ceil(N / 1024), B): a block takes 1024 consecutive features of one batch row, a thread four;
+// the row's statistics are added up by the block itself (thread t the producer's partials t, t + 256, ...;
+// the threads in order of their number: a fixed order).  a.out_f32 / part_stride / ld_out / k_split
+// describe the partials, a.stat_in ... a.cb the normalisation (as for the GEMMs), a.act_out /
+// out_k_blocks / act_kind the output.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) act_fixup(StreamGemmArgs a) {
+  typedef typename Operand<T>::type OT;
+  __shared__ float2 s_part[256];
+  __shared__ float s_mean, s_rstd;
+  const int tid = threadIdx.x, b = blockIdx.y;
+  const int n0 = (blockIdx.x * 256 + tid) * 4;
+  const bool live = n0 < a.N;
+  // everything from memory is requested first: the partial products, the folded vectors, the row's partial sums
+  const float *src = a.out_f32 + (size_t)b * a.ld_out + (live ? n0 : 0);
+  f32x4 part[kQkvParts];
+#pragma unroll
+  for (int s = 0; s < kQkvParts; ++s)
+    if (s < a.k_split) part[s] = *(const f32x4 *)(src + (size_t)s * a.part_stride);
+  f32x4 wg = {0.f, 0.f, 0.f, 0.f}, cb = {0.f, 0.f, 0.f, 0.f};
+  if (a.wg) wg = *(const f32x4 *)(a.wg + (live ? n0 : 0));
+  if (a.cb) cb = *(const f32x4 *)(a.cb + (live ? n0 : 0));
+  float mean = 0.f, rstd = 1.f;
+  if (a.stat_groups > 0) {
+    f32x4 sv = {0.f, 0.f, 0.f, 0.f};
+    for (int g = tid; g < a.stat_groups; g += 256) sv += ((const f32x4 *)a.stat_in)[(size_t)g * 32 + b];
+    s_part[tid] = make_float2(sv[0] + sv[2], sv[1] + sv[3]);
+    __syncthreads();
+    if (tid < 64) {  // one wave: 4 partials a lane in order, then the lanes by a butterfly (a fixed order)
+      float u1 = 0.f, u2 = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) u1 += s_part[tid * 4 + i].x, u2 += s_part[tid * 4 + i].y;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) u1 += __shfl_xor(u1, off), u2 += __shfl_xor(u2, off);
+      if (tid == 0) {
+        const float inv = 1.0f / (float)a.norm_dim;
+        const float ms = u2 * inv;
+        float m = 0.f, r;
+        if (a.rms) {
+          r = rsqrtf(ms + a.eps);
+        } else {
+          m = u1 * inv;
+          r = rsqrtf(fmaxf(ms - m * m, 0.f) + a.eps);
+          // the next producer centres on this norm's mean (one block per row)
+          if (a.publish && a.cen && blockIdx.x == 0) a.cen[b] = a.cen[b] + m;
+        }
+        s_mean = m, s_rstd = r;
+      }
+    }
+    __syncthreads();
+    mean = s_mean, rstd = s_rstd;
+  }
+  if (!live) return;
+  f32x4 h = part[0];
+#pragma unroll
+  for (int s = 1; s < kQkvParts; ++s)
+    if (s < a.k_split) h += part[s];
+  float u[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) u[i] = act_apply(a.act_kind, rstd * (h[i] - mean * wg[i]) + cb[i]);
+  store4_frag<OT, false>(a.act_out, b, n0, a.out_k_blocks, u);
+}
+
+ss_status check_act_fixup(int dtype, const StreamGemmArgs &a) {
+  if (dtype != SS_DTYPE_BF16 && dtype != SS_DTYPE_F32) SS_FAIL(SS_EINVAL, "activation of the sliced FFN GEMM: dtype %d", dtype);
+  if (a.B < 1 || a.B > 32 || a.N < 16 || a.N % 16 || a.ld_out < a.N || a.ld_out % 4)
+    SS_FAIL(SS_EINVAL, "activation of the sliced FFN GEMM: bad shape (batch %d, N %d, row length %d)", a.B, a.N, a.ld_out);
+  if (a.k_split < 2 || a.k_split > kQkvParts || a.part_stride < (size_t)a.B * a.ld_out || a.part_stride % 4)
+    SS_FAIL(SS_EINVAL, "activation of the sliced FFN GEMM: %d slices, %zu floats apart", a.k_split, a.part_stride);
+  if (!a.out_f32 || !a.act_out || a.out_k_blocks * (dtype == SS_DTYPE_BF16 ? 32 : 16) < a.N)
+    SS_FAIL(SS_EINVAL, "activation of the sliced FFN GEMM: bad buffers");
+  if (a.stat_groups < 0 || (a.stat_groups > 0 && (!a.stat_in || a.norm_dim < 1 || (!a.rms && !a.wg))))
+    SS_FAIL(SS_EINVAL, "activation of the sliced FFN GEMM: incomplete normalisation arguments");
+  if (a.act_kind != SS_ACT_GELU_TANH && a.act_kind != SS_ACT_RELU) SS_FAIL(SS_EINVAL, "activation of the sliced FFN GEMM: kind %d", a.act_kind);
+  return SS_OK;
+}
+
+int act_fixup_blocks(const StreamGemmArgs &a) { return ceil_div(a.N, 1024); }  // per batch row
+
+ss_status launch_act_fixup(int dtype, const StreamGemmArgs &a, hipStream_t st) {
+  SS_TRY(check_act_fixup(dtype, a));
+  const dim3 grid(act_fixup_blocks(a), a.B), block(256);
+  if (dtype == SS_DTYPE_BF16) SS_LAUNCH_KERNEL(act_fixup<bf16_t>, grid, block, 0, st, a);
+  else SS_LAUNCH_KERNEL(act_fixup<float>, grid, block, 0, st, a);
   SS_HIP(hipGetLastError());
   return SS_OK;
 }

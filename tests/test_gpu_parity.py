@@ -253,7 +253,8 @@ def test_launch_modes_agree(ss, side_stream, name, kw):
 def test_gemm_launch_shapes_give_the_same_bits(ss, side_stream, name, batch):
     """Weight tiles per block (and with them the number of blocks the tiles are shared out over) are a free
     choice, made per shape by a cost rule: every choice must give bit-identical logits, tokens and caches.
-    The slices the q|k|v GEMM cuts K into change the order of its sums: for every slice count the logits
+    The slices the q|k|v GEMM cuts K into (and, with more than 16 batch rows, the first FFN matrix, whose
+    activation then is a kernel of its own) change the order of the sums: for every slice count the logits
     must meet the oracle's, and all tile counts must agree bit for bit."""
     import torch
     w = scaled(name, "bf16", batch=batch, s_in=40, steps=3, d_model=1024, ffn=1152, head_dim=128, n_heads=6, vocab=2011)

@@ -31,14 +31,15 @@ class AttnArgs(C.Structure):
 
 
 class Phase(C.Structure):
-    _fields_ = [("kind", i32), ("gx", i32), ("gy", i32), ("shard", i32), ("e", EmbedArgs), ("g", GemmArgs), ("at", AttnArgs)]
+    _fields_ = [("kind", i32), ("gx", i32), ("gy", i32), ("shard", i32), ("epi", i32), ("e", EmbedArgs), ("g", GemmArgs), ("at", AttnArgs)]
 
 
 lib = B.lib
 lib.ss_debug_plan.restype = i32
 lib.ss_debug_plan.argtypes = [C.POINTER(B.ModelDesc), C.POINTER(B.Slice), i32, i32, i32, C.c_uint64, vp, i32,
                               C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
-EMBED, QKV, ATTN, RESID, FFN_UP, LM_HEAD, COMMIT = range(7)
+EMBED, QKV, ATTN, RESID, FFN_UP, LM_HEAD, COMMIT, FFN_ACT = range(8)
+EPI_F32, EPI_RESID, EPI_ACT, EPI_SWIGLU, EPI_LOGITS = range(5)
 
 
 def plan(w):
@@ -69,7 +70,10 @@ def check(w):
         regions.append((ptr, ptr + nbytes, label, inplace))
 
     layers = w.slice["layer_hi"] - w.slice["layer_lo"]
-    assert [p.kind for p in ph] == [EMBED] + [QKV, ATTN, RESID, FFN_UP, RESID] * layers + [LM_HEAD, COMMIT]
+    # (a first FFN matrix whose K is cut into slices is followed by the kernel that adds the slices and applies the activation)
+    assert [p.kind for p in ph if p.kind != FFN_ACT] == [EMBED] + [QKV, ATTN, RESID, FFN_UP, RESID] * layers + [LM_HEAD, COMMIT]
+    for i, p in enumerate(ph[:-1]):
+        assert (p.kind == FFN_UP and p.epi == EPI_F32) == (ph[i + 1].kind == FFN_ACT)
     stat_groups = None
     for i, p in enumerate(ph):
         regions = []
@@ -98,6 +102,23 @@ def check(w):
             rng("vcache", a.v_cache, span, regions)
             assert a.splits * a.rows_per_block >= a.Smax and p.gx == a.B * a.Hs and p.gy == a.splits
             assert a.waves in (4, 16)
+        elif p.kind == FFN_ACT:
+            g, up = p.g, ph[i - 1].g
+            assert ph[i - 1].kind == FFN_UP and ph[i - 1].epi == EPI_F32 and w.batch > 16 and not glu
+            assert (g.out_f32, g.ld_out, g.k_split, g.part_stride, g.B, g.N) == (up.out_f32, up.ld_out, up.k_split, up.part_stride, up.B, up.N)
+            assert 2 <= g.k_split <= 8 and g.part_stride >= g.B * g.ld_out and g.part_stride % 4 == 0 and g.ld_out % 4 == 0 and g.N % 16 == 0
+            assert p.gx == -(-g.N // 1024) and p.gy == g.B        # a block: 1024 features of one batch row
+            # the normalisation the sliced GEMM left out
+            assert g.stat_groups == stat_groups and g.norm_dim == d and g.publish == 1
+            rng("stat_in", g.stat_in, g.stat_groups * 32 * 16, regions)
+            assert bool(g.wg) == (w.desc["norm"] == "layernorm") == bool(g.cen) and g.cb
+            if g.wg: rng("wg", g.wg, g.N * 4, regions)
+            rng("cb", g.cb, g.N * 4, regions)
+            rng("cen", g.cen, 32 * 4, regions)
+            for part in range(g.k_split):
+                rng("partial (K slice %d)" % part, g.out_f32 + part * g.part_stride * 4, g.B * g.ld_out * 4, regions)
+            rng("act_out", g.act_out, nbt * g.out_k_blocks * parts * 1024, regions)
+            assert g.out_k_blocks * fk >= g.N and ph[i + 1].kind == RESID and ph[i + 1].g.act == g.act_out
         elif p.kind == COMMIT:
             g = p.g
             assert p.gx == w.batch == g.B and g.n_lens == 1 and g.commit_inc == 1
@@ -110,7 +131,12 @@ def check(w):
             tu = 2 if (glu and p.kind == FFN_UP) else 1                      # weight tiles per unit (a gate/up pair)
             units = g.row_tiles // tu
             assert g.ks in (4, 8) and g.B == w.batch and p.gy == 1
-            assert g.nw in ((2, 6) if tu == 2 else (1, 2, 3, 6)) and (g.nw != 6 or (g.B <= 16 and p.kind in (QKV, FFN_UP)))
+            sliced_ffn = p.kind == FFN_UP and p.epi == EPI_F32
+            if p.kind == FFN_UP:
+                assert p.epi == (EPI_SWIGLU if glu else EPI_ACT) or (sliced_ffn and not glu and g.B > 16)
+            # six tiles a block: float output (q|k|v, the sliced first FFN matrix), gate/up pairs for up to 16 rows, logits for more
+            assert g.nw in ((2, 6) if tu == 2 else (1, 2, 3, 6))
+            assert g.nw != 6 or p.kind == QKV or sliced_ffn or (tu == 2 and g.B <= 16) or (p.kind == LM_HEAD and g.B > 16)
             assert 1 <= g.n_blocks <= units and -(-units // g.n_blocks) * tu <= g.nw   # the largest block fits the kernel instance
             assert p.gx == g.n_blocks * max(1, g.k_split)
             assert (g.u_base, g.u_rem) == divmod(units, g.n_blocks) and g.k_slice == -(-g.k_blocks // max(1, g.k_split))
@@ -120,7 +146,9 @@ def check(w):
             rng("zero_frag", g.zero_frag, 1024, regions)
             if g.wg: rng("wg", g.wg, g.row_tiles * 16 * 4, regions)
             if g.cb: rng("cb", g.cb, g.row_tiles * 16 * 4, regions)
-            if p.kind in (QKV, FFN_UP, LM_HEAD):
+            if sliced_ffn:      # raw partial products: normalisation and bias are applied by the kernel that adds them up
+                assert g.stat_groups == 0 and not g.wg and not g.cb and not g.cen and not g.publish and g.k_blocks * fk == d
+            elif p.kind in (QKV, FFN_UP, LM_HEAD):
                 assert g.stat_groups == stat_groups and g.norm_dim == d and g.k_blocks * fk == d
                 rng("stat_in", g.stat_in, g.stat_groups * 32 * 16, regions)
                 assert bool(g.wg) == (w.desc["norm"] == "layernorm")
@@ -130,7 +158,8 @@ def check(w):
                 rng("cen", g.cen, 32 * 4, regions)
             else:
                 assert g.stat_groups == 0 and not g.wg
-            assert g.k_split in (0, 1) or (2 <= g.k_split <= 8 and p.kind == QKV and g.k_blocks >= g.k_split * g.ks)
+            assert g.k_split in (0, 1) or (2 <= g.k_split <= 8 and (p.kind == QKV or sliced_ffn) and g.k_blocks >= g.k_split * g.ks)
+            assert not sliced_ffn or g.k_split >= 2
             if p.kind == QKV:
                 rng("out_f32", g.out_f32, g.B * g.ld_out * 4, regions)
                 nxt = ph[i + 1]
@@ -145,8 +174,13 @@ def check(w):
                 assert g.ld_out >= g.N
             if p.kind == FFN_UP:
                 assert g.N * (2 if glu else 1) == g.row_tiles * 16
-                rng("act_out", g.act_out, nbt * g.out_k_blocks * parts * 1024, regions)
-                assert g.out_k_blocks * fk >= g.N
+                if sliced_ffn:
+                    assert not g.act_out and g.ld_out >= g.N and g.part_stride >= g.B * g.ld_out
+                    for part in range(g.k_split):
+                        rng("out_f32 (K slice %d)" % part, g.out_f32 + part * g.part_stride * 4, g.B * g.ld_out * 4, regions)
+                else:
+                    rng("act_out", g.act_out, nbt * g.out_k_blocks * parts * 1024, regions)
+                    assert g.out_k_blocks * fk >= g.N
             if p.kind == RESID:
                 assert g.N == d == g.row_tiles * 16 and g.x_in == g.x_out
                 rng("x", g.x_in, g.B * g.N * 4, regions)
