@@ -193,8 +193,17 @@ __global__ void __launch_bounds__(KSM * 64, 2) stream_gemm(StreamGemmArgs a) {
       f32x4 sv = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int i = 0; i < SR; ++i) sv += st_v[t][i];
-      if (t * 16 + st_loc < a.B)
-        for (int g = st_slice + SR * nsl; g < a.stat_groups; g += nsl) sv += st_p[(size_t)g * 32 + t * 16];  // the rest, if any
+      // the rest, if any: four requests at a time (a request per trip would wait for each in turn), added in the same order
+      if (t * 16 + st_loc < a.B) {
+        for (int g = st_slice + SR * nsl; g < a.stat_groups; g += 4 * nsl) {
+          f32x4 more[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            more[i] = *(g + i * nsl < a.stat_groups ? st_p + (size_t)(g + i * nsl) * 32 + t * 16 : (const f32x4 *)a.zero_frag);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) sv += more[i];
+        }
+      }
       // lanes loc, loc + rbl, loc + 2 rbl, ... of the wave hold the slices of row loc
       float s1 = sv[0] + sv[2], s2 = sv[1] + sv[3];
       for (int off = rbl; off < 64; off <<= 1) s1 += __shfl_xor(s1, off), s2 += __shfl_xor(s2, off);
