@@ -291,6 +291,42 @@ def test_gemm_launch_shapes_give_the_same_bits(ss, side_stream, name, batch):
         ss.force_gemm_shape(0, 0)
 
 
+@pytest.mark.parametrize("name,dtype,batch,slices", [("opt66b_m8", "f32", 19, 2), ("gpt20b_m4", "f32", 32, 3), ("gpt20b_m4", "bf16", 23, 2),
+                                                     ("opt66b_m8", "bf16", 32, 0)])
+def test_sliced_first_ffn_matrix_of_a_group(ss, side_stream, name, dtype, batch, slices):
+    """More than 16 batch rows: the first FFN matrix leaves raw partial products of K slices and a kernel of its own
+    adds them up, normalises and applies the activation.  Both shards of a tensor-parallel pair do so (only the first
+    leaves the new mean for the next producer), 1152 FFN columns each (a ragged second block per row in that kernel);
+    logits against the oracle of the pair at every step, float32 to the float32 bar."""
+    import torch
+    w = scaled(name, dtype, batch=batch, s_in=24, steps=3, d_model=512, ffn=2304, head_dim=64, n_heads=8, vocab=1201)
+    bf16 = dtype == "bf16"
+    parent = tp_slice(w.desc, 0, w.desc["n_layers"], 0, 1)
+    W = make_weights(w.desc, parent, w.seed)
+    slices_ = [tp_slice(w.desc, w.slice["layer_lo"], w.slice["layer_hi"], m, 2) for m in range(2)]
+    toks = make_tokens(w.seed, w.batch, w.s_in, w.desc["vocab"])
+    oras = [D.OracleShard(w.desc, sl, W, w.batch, w.s_max) for sl in slices_]
+    try:
+        ss.force_gemm_shape(0, slices)
+        shards = [ss.Shard(w.desc, sl, W, w.batch, w.s_max) for sl in slices_]
+        logits = torch.empty(w.batch, w.desc["vocab"], dtype=torch.float32, device="cuda")
+        nxt = torch.empty(w.batch, dtype=torch.int32, device="cuda")
+        ref = D.prefill_matrix(oras, toks)
+        ss.prefill(shards, dev(toks), logits, nxt)
+        check_logits(logits.cpu().numpy(), ref, bf16, "prefill")
+        for step in range(w.steps):
+            tok = D.greedy(ref)
+            ref = D.decode_step(oras, tok)
+            ss.decode_step(shards, dev(tok), logits, nxt)
+            check_logits(logits.cpu().numpy(), ref, bf16, f"step {step}")
+            check_ids(nxt.cpu().numpy(), ref, f"step {step}")
+        for sh in shards:
+            assert list(ss.committed_len(sh)) == [w.s_in + w.steps] * w.batch
+            sh.destroy()
+    finally:
+        ss.force_gemm_shape(0, 0)
+
+
 @pytest.mark.parametrize("name,dtype,batch", [("llama30b_m2", "bf16", 5), ("llama30b_m2", "f32", 2), ("opt66b_m8", "bf16", 19)])
 def test_exact_ties_go_to_the_lowest_index(ss, name, dtype, batch):
     """Greedy choice with exact ties: every row of the LM head is the same vector, so all logits of a

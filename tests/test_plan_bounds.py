@@ -217,3 +217,19 @@ def test_scaled_shapes(batch):
             for dtype in ("bf16", "f32"):
                 w = scaled_workload(name, layers=2, M=2, m=1, batch=batch, s_in=300, steps=20, dtype=dtype, **dims)
                 assert check(w) == []
+
+
+def test_forced_k_slices_reach_the_first_ffn_matrix_above_16_rows():
+    """With K slices forced, a model without gate at more than 16 batch rows plans the sliced first FFN matrix and its
+    activation kernel in every layer (and passes the bound checks); at 16 rows or with a gate it does not."""
+    dims = dict(d_model=1024, n_heads=8, head_dim=128, ffn=4096, vocab=5000)
+    try:
+        B.force_gemm_shape(0, 2)
+        for name, batch, want in (("opt66b_m8", 17, True), ("gpt20b_m4", 32, True), ("gpt20b_m4", 16, False), ("llama30b_m2", 32, False)):
+            for dtype in ("bf16", "f32"):
+                w = scaled_workload(name, layers=2, M=2, m=1, batch=batch, s_in=300, steps=20, dtype=dtype, **dims)
+                assert check(w) == []
+                kinds = [p.kind for p in plan(w)[0]]
+                assert kinds.count(FFN_ACT) == (2 if want else 0), (name, batch, dtype)
+    finally:
+        B.force_gemm_shape(0, 0)
