@@ -140,7 +140,8 @@ def measured_traffic(workload_name, kernel_key):
     return None
 
 
-def run_workload(ss, torch, name, K, Wm, eager=False, extras=True, repack5=False, reslice=False, keep_weights=False):
+def run_workload(ss, torch, name, K, Wm, eager=False, extras=True, repack5=False, reslice=False, keep_weights=False,
+                 cpu_repack=False):
     """Initial phase + K timed decode steps of one workload; returns (summary dict, (workload, host weights) or None)."""
     from synth import make_tokens, make_weights, sub_slice_of, workload
     w = workload(name)
@@ -291,6 +292,20 @@ def run_workload(ss, torch, name, K, Wm, eager=False, extras=True, repack5=False
             for p in parts:
                 p.destroy()
             del parts
+            if cpu_repack:
+                # the oracle's re-partition (its index formula as it stands, one core) on a bounded sample of the
+                # same move: one layer of it, the same 16 rows x 1000 tokens, 26 heads -> the first 13
+                from oracle import decoder as D
+                s_src, s_dst = dict(w.slice, layer_lo=0, layer_hi=1), dict(w5.extra["dst_slices"][0], layer_lo=0, layer_hi=1)
+                src_kv = np.ones((1, 2, w.batch, g["Hs"], w5.s_max, g["Dh"]), dtype=np.uint16)
+                dst_kv = np.zeros((1, 2, w.batch, g["Hs"] // 2, w5.s_max, g["Dh"]), dtype=np.uint16)
+                t0 = time.time()
+                elems = D.kv_repack_arrays(dst_kv, s_dst, src_kv, s_src, [n5] * w.batch, keep)
+                dt_cpu = time.time() - t0
+                out["repack"]["cpu_baseline"] = dict(traffic_GBps=2 * elems * 2 / dt_cpu / 1e9, cores=1, kind="oracle",
+                                                     sample=f"one layer of the same move ({elems * 2 / 1e6:.0f} MB payload), "
+                                                            f"{dt_cpu:.1f} s")
+                del src_kv, dst_kv
         if reslice and g["Hs"] % 2 == 0 and g["Fs"] % 128 == 0:
             # ---- model-context re-slice: two half-width shards built out of the resident one ----
             half = sub_slice_of(w.slice, 0, 2)
@@ -356,7 +371,7 @@ def main():
     is_llama = args.workload == HEADLINE
     head, kept = run_workload(ss, torch, args.workload, K, Wm, eager=args.eager, extras=extras,
                               repack5=extras and is_llama and not args.only, reslice=extras and not args.only,
-                              keep_weights=not args.no_cpu_baseline)
+                              keep_weights=not args.no_cpu_baseline, cpu_repack=not args.no_cpu_baseline)
     if head["steps"] != K:
         sys.exit(f"--steps {K} exceeds the workload's decode steps")
     out = dict(metric="decode tokens/s per TP shard on 1 GPU", value=head["value"], unit="tokens/s", n_gpus=1,
