@@ -27,11 +27,23 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-@pytest.mark.parametrize("name,dtype,group_m", [("llama30b_m2", "bf16", 1), ("gpt20b_m4", "bf16", 2), ("tiny_gpt", "f32", 1)])
-def test_static_scratch_step_matches_the_allocating_one(ss, name, dtype, group_m):
+@pytest.mark.parametrize("name,dtype,group_m,batch,slices", [("llama30b_m2", "bf16", 1, 6, 0), ("gpt20b_m4", "bf16", 2, 6, 0),
+                                                             ("tiny_gpt", "f32", 1, 6, 0),
+                                                             # more than 16 rows, no gate: the first FFN matrix in K slices, its
+                                                             # partial products in the static array too
+                                                             ("opt66b_m8", "bf16", 1, 20, 2)])
+def test_static_scratch_step_matches_the_allocating_one(ss, name, dtype, group_m, batch, slices):
+    try:
+        ss.force_gemm_shape(0, slices)
+        _static_against_allocating(ss, name, dtype, group_m, batch)
+    finally:
+        ss.force_gemm_shape(0, 0)
+
+
+def _static_against_allocating(ss, name, dtype, group_m, batch):
     import torch
     w = scaled_workload(name, d_model=512, n_heads=4, head_dim=128, ffn=1152, vocab=1511, layers=3, M=1, m=0,
-                        batch=6, s_in=45, steps=4, dtype=dtype)
+                        batch=batch, s_in=45, steps=4, dtype=dtype)
     desc, B, V = w.desc, w.batch, w.desc["vocab"]
     full = tp_slice(desc, 0, 3, 0, 1)
     W = make_weights(desc, full, w.seed)
