@@ -8,15 +8,18 @@
 
 namespace ss {
 
-template <typename T, typename AT, int DH, int NWV>
+template <typename T, typename AT, int DH, int NWV, bool RAW>
 __global__ void __launch_bounds__(NWV * 64) decode_attn(DecodeAttnArgs a) {
   __shared__ AttnShared<NWV> sh;
-  decode_attn_block<T, AT, DH, NWV>(a, blockIdx.x, blockIdx.y, sh);
+  decode_attn_block<T, AT, DH, NWV, RAW>(a, blockIdx.x, blockIdx.y, sh);
 }
 
 ss_status check_decode_attn(const DecodeAttnArgs &a) {
   if (a.B < 1 || a.B > 32 || a.Hs < 1 || (a.Dh != 64 && a.Dh != 128)) SS_FAIL(SS_EINVAL, "decode attention: bad shape");
   if (a.waves != 4 && a.waves != 16) SS_FAIL(SS_EINVAL, "decode attention: %d waves per block", a.waves);
+  if (a.norm_dim < 0 || a.stat_groups < 0 ||
+      (a.norm_dim > 0 && (a.stat_groups < 1 || !a.stat_in || (!a.rms && !a.wg) || (a.publish && !a.rms && !a.cen))))
+    SS_FAIL(SS_EINVAL, "decode attention: incomplete normalisation arguments for raw q|k|v");
   if (a.rows_per_block < 1 || a.splits < 1 || (size_t)a.splits * a.rows_per_block < (size_t)a.Smax)
     SS_FAIL(SS_EINVAL, "decode attention: %d splits of %d rows do not cover %d rows", a.splits, a.rows_per_block, a.Smax);
   return SS_OK;
@@ -27,8 +30,11 @@ ss_status launch_decode_attn(int dtype, const DecodeAttnArgs &a, hipStream_t st)
   dim3 grid(a.B * a.Hs, a.splits);
 #define SS_LAUNCH(KT, AT, DH)                                                                        \
   do {                                                                                               \
-    if (a.waves == 16) SS_LAUNCH_KERNEL((decode_attn<KT, AT, DH, 16>), grid, dim3(1024), 0, st, a); \
-    else SS_LAUNCH_KERNEL((decode_attn<KT, AT, DH, 4>), grid, dim3(256), 0, st, a);                \
+    if (a.norm_dim > 0) {  /* raw q|k|v: the kernel applies the normalisation */                      \
+      if (a.waves == 16) SS_LAUNCH_KERNEL((decode_attn<KT, AT, DH, 16, true>), grid, dim3(1024), 0, st, a); \
+      else SS_LAUNCH_KERNEL((decode_attn<KT, AT, DH, 4, true>), grid, dim3(256), 0, st, a);          \
+    } else if (a.waves == 16) SS_LAUNCH_KERNEL((decode_attn<KT, AT, DH, 16, false>), grid, dim3(1024), 0, st, a); \
+    else SS_LAUNCH_KERNEL((decode_attn<KT, AT, DH, 4, false>), grid, dim3(256), 0, st, a);           \
   } while (0)
   if (dtype == SS_DTYPE_BF16 && a.kv_dtype == SS_DTYPE_F16) {  // bf16 models: the output operand is halves
     if (a.Dh == 128) SS_LAUNCH(f16_t, f16_t, 128);

@@ -51,10 +51,11 @@ struct AttnShared {
   float sm_m[NWV], sm_l[NWV];
   float sm_acc[NWV][128];
   float sm_red[4];
+  float2 st[NWV];   // raw q|k|v: the waves' shares of the row's (sum, sum of squares)
   int flag;
 };
 
-template <typename T, typename AT, int DH, int NWV>
+template <typename T, typename AT, int DH, int NWV, bool RAW>
 __device__ __forceinline__ void decode_attn_block(const DecodeAttnArgs &a, const int bh, const int sp,
                                                   AttnShared<NWV> &sh) {
   typedef RowGeom<T, DH> Gm;
@@ -135,9 +136,41 @@ __device__ __forceinline__ void decode_attn_block(const DecodeAttnArgs &a, const
     constexpr int STRIDE = NWV * U * G;
     u32x4 kA[U], vA[U], kB[U], vB[U];
     int base = r0 + wave * (U * G);
+    // Raw q|k|v (RAW: a.norm_dim > 0; the GEMM left the normalisation to this kernel; an instance of its own, so that
+    // the other one carries none of this): the row's mean and 1/std from the producer's partial sums, thread t adding
+    // partials t, t + threads, ...; lanes by a butterfly, waves in order: a fixed order.  These requests (one or two
+    // a thread, L2 hits) go out BEFORE the cache rows: loads return in order, and behind the rows they would come back
+    // only when the rows have.  (Hoisting the requests for the partial q|k|v sums as well made the kernel slower.)
+    // (Inside the RAW instance the flag is read from the arguments all the same: with a compile-time flag the compiler
+    // arranged the requests differently and the kernel took 21.4 instead of 20.2 us on the OPT-66B shape.)
+    const bool raw = RAW && a.norm_dim > 0;
+    float mean = 0.f, rstd = 1.f;
+    f32x4 sv = {0.f, 0.f, 0.f, 0.f};
+    if (raw)
+      for (int gi = tid; gi < a.stat_groups; gi += NWV * 64) sv += ((const f32x4 *)a.stat_in)[(size_t)gi * 32 + b];
     // cache rows do not depend on this step's q: request them first, then stage q
     load(kA, vA, base);
     load(kB, vB, base + STRIDE);
+    if (raw && a.stat_groups > 0) {
+      float s1 = sv[0] + sv[2], s2 = sv[1] + sv[3];
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) s1 += __shfl_xor(s1, off), s2 += __shfl_xor(s2, off);
+      if (lane == 0) sh.st[wave] = make_float2(s1, s2);
+      __syncthreads();
+      float u1 = 0.f, u2 = 0.f;
+#pragma unroll
+      for (int w2 = 0; w2 < NWV; ++w2) u1 += sh.st[w2].x, u2 += sh.st[w2].y;
+      const float inv = 1.0f / (float)a.norm_dim;
+      const float ms = u2 * inv;
+      if (a.rms) {
+        rstd = rsqrtf(ms + a.eps);
+      } else {
+        mean = u1 * inv;
+        rstd = rsqrtf(fmaxf(ms - mean * mean, 0.f) + a.eps);
+        // the next producer centres on this norm's mean (one thread per batch row)
+        if (a.publish && a.cen && h == 0 && sp == 0 && tid == 0) a.cen[b] = a.cen[b] + mean;
+      }
+    }
     float kn = 0.f, vraw = 0.f;  // the new token's (rotated) key and value element of thread e
     if (tid < DH) {
       // q | k | v of the new token: the GEMM's partial sums (it may have cut K into slices), all requested at
@@ -154,11 +187,27 @@ __device__ __forceinline__ void decode_attn_block(const DecodeAttnArgs &a, const
           pqo[p] = src[eo], pko[p] = src[HD + eo];  // the rotation partners (unused without a table)
         }
       }
+      // (raw q|k|v: the folded vectors of the five columns, requested with the partial sums)
+      float wgv[5] = {0.f, 0.f, 0.f, 0.f, 0.f}, cbv[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
+      if (raw) {
+        const int cq = h * DH + e, cqo = h * DH + eo;
+        const int col[5] = {cq, HD + cq, 2 * HD + cq, cqo, HD + cqo};
+#pragma unroll
+        for (int i = 0; i < 5; ++i) {
+          if (a.wg) wgv[i] = a.wg[col[i]];
+          if (a.cb) cbv[i] = a.cb[col[i]];
+        }
+      }
       float qe = pq[0], ke = pk[0], qo = pqo[0], ko = pko[0];
       vraw = pv[0];
 #pragma unroll
       for (int p = 1; p < kQkvParts; ++p)
         if (p < qparts) qe += pq[p], ke += pk[p], vraw += pv[p], qo += pqo[p], ko += pko[p];
+      if (raw) {
+        qe = rstd * (qe - mean * wgv[0]) + cbv[0], ke = rstd * (ke - mean * wgv[1]) + cbv[1];
+        vraw = rstd * (vraw - mean * wgv[2]) + cbv[2];
+        qo = rstd * (qo - mean * wgv[3]) + cbv[3], ko = rstd * (ko - mean * wgv[4]) + cbv[4];
+      }
       if (tab) {
         const float2 cs = tab[e < HALF ? e : e - HALF];
         if (e < HALF) qe = qe * cs.x - qo * cs.y, ke = ke * cs.x - ko * cs.y;

@@ -231,14 +231,15 @@ constexpr double kUnitKiBPerUs = 45.0e9 / 1024.0 / 1.0e6;   // what one compute 
 constexpr double kHbmKiBPerUs = 6.8e12 / 1024.0 / 1.0e6;    // a long stream from HBM
 
 // estimated microseconds of streaming (without the few microseconds every launch costs); two_fit: two blocks of the instance fit on a unit
-static double shape_cost(int tu, int units, int k_blocks, double act, double stat_kib, bool two_fit, int n_blocks, int S, double split_cost) {
+static double shape_cost(int tu, int units, int k_blocks, double act, double stat_kib, bool two_fit, int n_blocks, int S, double split_cost,
+                         double unit_rate = 1.0) {
   const int upb = ceil_div(units, n_blocks);                  // units of the largest block
   const double kslice = (double)ceil_div(k_blocks, S);
   const int blocks = n_blocks * S;
   const double largest = ((double)upb * tu + act) * kslice + stat_kib;   // KiB the largest block takes in
   double t_cu;
   if (blocks <= kComputeUnits) {
-    t_cu = largest / kUnitKiBPerUs;
+    t_cu = largest / (kUnitKiBPerUs * unit_rate);
   } else if (act >= 2.0) {
     // More than 16 batch rows (one block a unit at a time, every block bound by the unit's intake): the blocks run in
     // rounds of 256, and a round takes what its largest block takes; a few blocks over a multiple of 256 cost a whole
@@ -247,7 +248,7 @@ static double shape_cost(int tu, int units, int k_blocks, double act, double sta
     const int rounds = ceil_div(blocks, kComputeUnits), big = units % n_blocks == 0 ? blocks : (units % n_blocks) * S;
     const double smaller = ((double)(units / n_blocks) * tu + act) * kslice + stat_kib;
     t_cu = 0.0;
-    for (int r = 0; r < rounds; ++r) t_cu += (r * kComputeUnits < big ? largest : smaller) / kUnitKiBPerUs;
+    for (int r = 0; r < rounds; ++r) t_cu += (r * kComputeUnits < big ? largest : smaller) / (kUnitKiBPerUs * unit_rate);
   } else {
     const double total = ((double)units * tu + (double)n_blocks * act) * k_blocks + (double)blocks * stat_kib;  // KiB all blocks take in
     t_cu = total / (kComputeUnits * kUnitKiBPerUs) * (two_fit ? 1.0 : 1.15) + 0.5 * largest / kUnitKiBPerUs;
@@ -287,11 +288,15 @@ static GemmShape shape_rule(int epi, int row_tiles, int k_blocks, int B, int ks,
     for (int nw : instances) {
       const int upb_max = nw / tu;
       const bool two_fit = B <= 16 ? nw <= 2 : nw <= 1;
+      // the six-tile instance for two batch tiles runs with every register taken: at equal bytes a block of it streams
+      // about a tenth slower than a three-tile block (q|k|v of the OPT-66B shape: 16.5 us in 6-tile blocks x 5 slices,
+      // 15.6 us in 3-tile blocks x 3 slices, 464 and 480 KiB a block)
+      const double unit_rate = (B > 16 && nw == 6) ? 0.89 : 1.0;
       // block counts worth a look: the fewest for every size of the largest block (with a forced instance: its full size only)
       for (int upb = upb_max; upb >= 1; --upb) {
         const int n_blocks = ceil_div(units, upb);
         if (ceil_div(units, n_blocks) != upb) continue;       // the same share-out as a smaller size
-        const double t = shape_cost(tu, units, k_blocks, act, stat_kib, two_fit, n_blocks, S, split_cost);
+        const double t = shape_cost(tu, units, k_blocks, act, stat_kib, two_fit, n_blocks, S, split_cost, unit_rate);
         if (!best.nw || t < best_t) best = {nw, n_blocks, S, t}, best_t = t;
         if (forced_nw) break;
       }
@@ -299,7 +304,7 @@ static GemmShape shape_rule(int epi, int row_tiles, int k_blocks, int B, int ks,
       if (B > 16 && !forced_nw && S == 1) {
         for (int n_blocks = 2 * kComputeUnits; n_blocks <= units; n_blocks += kComputeUnits) {
           if (ceil_div(units, n_blocks) > upb_max) continue;
-          const double t = shape_cost(tu, units, k_blocks, act, stat_kib, two_fit, n_blocks, S, split_cost);
+          const double t = shape_cost(tu, units, k_blocks, act, stat_kib, two_fit, n_blocks, S, split_cost, unit_rate);
           if (!best.nw || t < best_t) best = {nw, n_blocks, S, t}, best_t = t;
         }
       }
@@ -413,6 +418,7 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
   };
   int qkv_parts[8] = {0};     // per shard of the group: partial q|k|v sums its GEMM leaves and their distance (floats)
   size_t qkv_stride[8] = {0};
+  DecodeAttnArgs qkv_norm[8];  // and, where its GEMM leaves raw products, the normalisation the attention kernel applies
   for (int l = 0; l < L0.Ls; ++l) {
     const LayerDev &D0 = g0->layers[l];
     for (int i = 0; i < n_group; ++i) {  // QKV projection of the new token
@@ -428,6 +434,16 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
       a.out_f32 = (float *)(s->dec_at(L.ws_qkvd)), a.ld_out = L.qkv_n;
       a.split_ok = kQkvParts;  // the consumer (decode attention) adds up to that many partial sums,
       a.split_cost_us = m.pos == SS_POS_ROPE ? 2.5f : 1.0f;  // which costs it this much (more where it rotates q and k: measured)
+      // More than 16 batch rows: the GEMM leaves raw products and the attention kernel, which adds the slices up anyway,
+      // applies the normalisation to the elements it stages.  The GEMM's blocks then read no row sums (147 KB each at
+      // d = 9216 and 32 rows) and may be six tiles wide.
+      qkv_norm[i] = DecodeAttnArgs{};
+      if (B > 16) {
+        DecodeAttnArgs &n = qkv_norm[i];
+        n.stat_in = a.stat_in, n.stat_groups = a.stat_groups, n.norm_dim = a.norm_dim, n.rms = a.rms, n.eps = a.eps;
+        n.wg = a.wg, n.cb = a.cb, n.cen = a.cen, n.publish = a.publish;
+        a.stat_in = nullptr, a.stat_groups = 0, a.wg = nullptr, a.cb = nullptr, a.cen = nullptr, a.publish = 0;
+      }
       shape_gemm(a, EPI_F32);
       ph.gx = a.n_blocks * a.k_split, ph.gy = 1;
       qkv_parts[i] = a.k_split, qkv_stride[i] = a.part_stride;
@@ -441,6 +457,11 @@ static void build_decode_plan(Shard *const *group, int n_group, const int32_t *t
       DecodeAttnArgs &a = ph.at;
       a.qkv = (const float *)(s->dec_at(L.ws_qkvd));
       a.qkv_parts = qkv_parts[i], a.qkv_stride = qkv_stride[i];
+      {
+        const DecodeAttnArgs &n = qkv_norm[i];
+        a.stat_in = n.stat_in, a.stat_groups = n.stat_groups, a.norm_dim = n.norm_dim, a.rms = n.rms, a.eps = n.eps;
+        a.wg = n.wg, a.cb = n.cb, a.cen = n.cen, a.publish = n.publish;
+      }
       a.k_cache = s->kv_ptr(l, 0), a.v_cache = s->kv_ptr(l, 1);
       a.row_stride = s->kv_row_stride(), a.head_stride = s->kv_head_stride();
       a.lens = s->d_len, a.rope = m.pos == SS_POS_ROPE ? s->rope : nullptr;

@@ -154,6 +154,16 @@ struct DecodeAttnArgs {
   int kv_dtype;         // cache element type (SS_DTYPE_*)
   int rows_per_block, splits;
   int waves;            // per block: 4, or 16 when one block takes a whole (row, head)
+  // norm_dim > 0: qkv holds RAW products (the q|k|v GEMM left out the deferred normalisation and the bias, so that
+  // its blocks read no row sums), and every block here applies rstd * (sum - (mean - c) * wg[n]) + cb[n] to the
+  // elements it stages, from the producer's partial row sums (as StreamGemmArgs: stat_in, stat_groups, norm_dim,
+  // rms, eps, wg, cb over the q|k|v columns); with publish, the block of head 0 (first split) leaves the new mean in cen
+  const float *stat_in;
+  int stat_groups, norm_dim, rms;
+  float eps;
+  const float *wg, *cb;
+  float *cen;
+  int publish;
 };
 ss_status launch_decode_attn(int dtype, const DecodeAttnArgs &a, hipStream_t st);
 ss_status check_decode_attn(const DecodeAttnArgs &a);

@@ -27,7 +27,9 @@ class GemmArgs(C.Structure):
 class AttnArgs(C.Structure):
     _fields_ = [("qkv", vp), ("qkv_parts", i32), ("qkv_stride", sz), ("k_cache", vp), ("v_cache", vp), ("row_stride", sz), ("head_stride", sz), ("lens", vp),
                 ("rope", vp), ("part", vp), ("counters", vp), ("o_out", vp), ("B", i32), ("Hs", i32), ("Dh", i32),
-                ("Smax", i32), ("kv_dtype", i32), ("rows_per_block", i32), ("splits", i32), ("waves", i32)]
+                ("Smax", i32), ("kv_dtype", i32), ("rows_per_block", i32), ("splits", i32), ("waves", i32),
+                ("stat_in", vp), ("stat_groups", i32), ("norm_dim", i32), ("rms", i32), ("eps", f32), ("wg", vp), ("cb", vp), ("cen", vp),
+                ("publish", i32)]
 
 
 class Phase(C.Structure):
@@ -102,6 +104,19 @@ def check(w):
             rng("vcache", a.v_cache, span, regions)
             assert a.splits * a.rows_per_block >= a.Smax and p.gx == a.B * a.Hs and p.gy == a.splits
             assert a.waves in (4, 16)
+            # more than 16 rows: the q|k|v GEMM leaves raw products and this kernel applies the normalisation it left out
+            q = ph[i - 1].g
+            assert ph[i - 1].kind == QKV
+            if w.batch > 16:
+                assert q.stat_groups == 0 and not q.wg and not q.cb and not q.cen and not q.publish
+                assert a.norm_dim == d and a.stat_groups == qkv_stat_groups and a.publish == 1
+                rng("stat_in", a.stat_in, a.stat_groups * 32 * 16, regions)
+                assert bool(a.wg) == (w.desc["norm"] == "layernorm") == bool(a.cen)
+                if a.wg: rng("wg", a.wg, 3 * a.Hs * a.Dh * 4, regions)
+                if a.cb: rng("cb", a.cb, 3 * a.Hs * a.Dh * 4, regions)
+                rng("cen", a.cen, 32 * 4, regions)
+            else:
+                assert a.norm_dim == 0 and not a.stat_in
         elif p.kind == FFN_ACT:
             g, up = p.g, ph[i - 1].g
             assert ph[i - 1].kind == FFN_UP and ph[i - 1].epi == EPI_F32 and w.batch > 16 and not glu
@@ -146,7 +161,11 @@ def check(w):
             rng("zero_frag", g.zero_frag, 1024, regions)
             if g.wg: rng("wg", g.wg, g.row_tiles * 16 * 4, regions)
             if g.cb: rng("cb", g.cb, g.row_tiles * 16 * 4, regions)
-            if sliced_ffn:      # raw partial products: normalisation and bias are applied by the kernel that adds them up
+            if p.kind == QKV:
+                qkv_stat_groups = stat_groups
+            if p.kind == QKV and w.batch > 16:      # raw products: the attention kernel applies normalisation and bias
+                assert g.stat_groups == 0 and not g.wg and not g.cb and not g.cen and not g.publish and g.k_blocks * fk == d
+            elif sliced_ffn:      # raw partial products: normalisation and bias are applied by the kernel that adds them up
                 assert g.stat_groups == 0 and not g.wg and not g.cb and not g.cen and not g.publish and g.k_blocks * fk == d
             elif p.kind in (QKV, FFN_UP, LM_HEAD):
                 assert g.stat_groups == stat_groups and g.norm_dim == d and g.k_blocks * fk == d
