@@ -393,6 +393,8 @@ def test_prefill_token_blocks_give_the_same_bits(ss, side_stream, name, dtype, b
     ("tiny_gpt", "f32", dict(layers=5, batch=3, s_in=20, steps=4), [0, 2, 3, 5], 1),
     ("gpt20b_m4", "bf16", dict(layers=4, batch=6, s_in=60, steps=4, head_dim=128, n_heads=4, d_model=512), [0, 1, 4], 1),
     ("llama30b_m2", "bf16", dict(layers=4, batch=17, s_in=40, steps=3, head_dim=128, n_heads=4, d_model=512), [0, 3, 4], 2),
+    # more than 16 rows with LayerNorm and biases: attention normalises the raw q|k|v and leaves the new mean, in every stage
+    ("opt66b_m8", "bf16", dict(layers=3, batch=19, s_in=30, steps=3, head_dim=64, n_heads=8, d_model=512, ffn=2048), [0, 1, 3], 2),
 ])
 def test_pipeline_stages(ss, side_stream, name, dtype, kw, cuts, group_m):
     """Shards that hold consecutive layer intervals, chained through hidden states (each stage a
@@ -887,9 +889,10 @@ def test_weights_outside_the_half_range(ss, side_stream):
     sh.destroy()
 
 
-def test_interrupted_step_commits_nothing_and_retry_is_identical(ss, side_stream):
+@pytest.mark.parametrize("batch", [3, 18])
+def test_interrupted_step_commits_nothing_and_retry_is_identical(ss, side_stream, batch):
     import torch
-    w = scaled("tiny_gpt", "bf16", batch=3, s_in=20, steps=2)
+    w = scaled("tiny_gpt", "bf16", batch=batch, s_in=20, steps=2)
     W = make_weights(w.desc, w.slice, w.seed)
     toks = make_tokens(w.seed, w.batch, w.s_in, w.desc["vocab"])
     V = w.desc["vocab"]
