@@ -12,7 +12,8 @@ same process and are reported under `configs`, and the KV re-partition of the
 reparallelize-and-resume configuration (1000 committed tokens, M=2 -> two M'=4 layouts) under
 `repack`.  The initial phase is measured in the same run and reported beside each.
 
-Prints ONE JSON line (see the design doc for the byte counts behind `roofline`).
+Prints ONE JSON line.  `roofline.achieved` = algorithmic bytes of the dominant kernel class (weights once for a GEMM,
+committed cache rows once plus the new row for attention) divided by its launches' own durations.
 """
 import argparse
 import gc
