@@ -252,3 +252,22 @@ def test_forced_k_slices_reach_the_first_ffn_matrix_above_16_rows():
                 assert kinds.count(FFN_ACT) == (2 if want else 0), (name, batch, dtype)
     finally:
         B.force_gemm_shape(0, 0)
+
+
+def test_launch_shapes_chosen_for_the_three_shards():
+    """The cost rule's choices on the full-size shards are the ones that were measured fastest on the GPU: a change to
+    the rule that moves one of them has to be measured again (a term added for more than 16 rows once flipped the
+    GPT-20B shape's q|k|v GEMM to a shape 2 us slower)."""
+    want = {
+        "gpt20b_m4": {QKV: (3, 96, 2), RESID: (2, 192, 1), FFN_UP: (2, 192, 1), LM_HEAD: (2, 1563, 1)},
+        "llama30b_m2": {QKV: (3, 208, 1), RESID: (2, 208, 1), FFN_UP: (6, 187, 1), LM_HEAD: (2, 1000, 1)},
+        "opt66b_m8": {QKV: (3, 72, 3), RESID: (3, 192, 1), FFN_UP: (6, 48, 5), LM_HEAD: (6, 768, 1)},
+    }
+    for name, shapes in want.items():
+        ph, _, _ = plan(workload(name))
+        for p in ph[1:]:                      # (the first q|k|v GEMM follows the embedding: one group of row sums)
+            if p.kind in shapes:
+                g = p.g
+                assert (g.nw, g.n_blocks, max(1, g.k_split)) == shapes[p.kind], (name, p.kind, g.nw, g.n_blocks, g.k_split)
+        kinds = [p.kind for p in ph]
+        assert (FFN_ACT in kinds) == (name == "opt66b_m8")
