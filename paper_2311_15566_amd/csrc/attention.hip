@@ -8,15 +8,16 @@
 
 namespace ss {
 
+// (8-wave blocks are meant to sit two to a compute unit: four waves a SIMD, at most 128 registers)
 template <typename T, typename AT, int DH, int NWV, bool RAW>
-__global__ void __launch_bounds__(NWV * 64) decode_attn(DecodeAttnArgs a) {
+__global__ void __launch_bounds__(NWV * 64, NWV == 8 ? 4 : 1) decode_attn(DecodeAttnArgs a) {
   __shared__ AttnShared<NWV> sh;
   decode_attn_block<T, AT, DH, NWV, RAW>(a, blockIdx.x, blockIdx.y, sh);
 }
 
 ss_status check_decode_attn(const DecodeAttnArgs &a) {
   if (a.B < 1 || a.B > 32 || a.Hs < 1 || (a.Dh != 64 && a.Dh != 128)) SS_FAIL(SS_EINVAL, "decode attention: bad shape");
-  if (a.waves != 4 && a.waves != 16) SS_FAIL(SS_EINVAL, "decode attention: %d waves per block", a.waves);
+  if (a.waves != 4 && a.waves != 8 && a.waves != 16) SS_FAIL(SS_EINVAL, "decode attention: %d waves per block", a.waves);
   if (a.norm_dim < 0 || a.stat_groups < 0 ||
       (a.norm_dim > 0 && (a.stat_groups < 1 || !a.stat_in || (!a.rms && !a.wg) || (a.publish && !a.rms && !a.cen))))
     SS_FAIL(SS_EINVAL, "decode attention: incomplete normalisation arguments for raw q|k|v");
@@ -32,8 +33,10 @@ ss_status launch_decode_attn(int dtype, const DecodeAttnArgs &a, hipStream_t st)
   do {                                                                                               \
     if (a.norm_dim > 0) {  /* raw q|k|v: the kernel applies the normalisation */                      \
       if (a.waves == 16) SS_LAUNCH_KERNEL((decode_attn<KT, AT, DH, 16, true>), grid, dim3(1024), 0, st, a); \
+      else if (a.waves == 8) SS_LAUNCH_KERNEL((decode_attn<KT, AT, DH, 8, true>), grid, dim3(512), 0, st, a); \
       else SS_LAUNCH_KERNEL((decode_attn<KT, AT, DH, 4, true>), grid, dim3(256), 0, st, a);          \
     } else if (a.waves == 16) SS_LAUNCH_KERNEL((decode_attn<KT, AT, DH, 16, false>), grid, dim3(1024), 0, st, a); \
+    else if (a.waves == 8) SS_LAUNCH_KERNEL((decode_attn<KT, AT, DH, 8, false>), grid, dim3(512), 0, st, a); \
     else SS_LAUNCH_KERNEL((decode_attn<KT, AT, DH, 4, false>), grid, dim3(256), 0, st, a);           \
   } while (0)
   if (dtype == SS_DTYPE_BF16 && a.kv_dtype == SS_DTYPE_F16) {  // bf16 models: the output operand is halves

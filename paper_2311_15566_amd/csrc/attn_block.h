@@ -59,7 +59,7 @@ template <typename T, typename AT, int DH, int NWV, bool RAW>
 __device__ __forceinline__ void decode_attn_block(const DecodeAttnArgs &a, const int bh, const int sp,
                                                   AttnShared<NWV> &sh) {
   typedef RowGeom<T, DH> Gm;
-  constexpr int EPL = Gm::EPL, LPR = Gm::LPR, G = Gm::G, U = NWV == 16 ? 2 : 4;
+  constexpr int EPL = Gm::EPL, LPR = Gm::LPR, G = Gm::G, U = NWV >= 8 ? 2 : 4;
   auto &sq = sh.sq;
   auto &sm_m = sh.sm_m;
   auto &sm_l = sh.sm_l;

@@ -103,7 +103,7 @@ def check(w):
             rng("kcache", a.k_cache, span, regions)
             rng("vcache", a.v_cache, span, regions)
             assert a.splits * a.rows_per_block >= a.Smax and p.gx == a.B * a.Hs and p.gy == a.splits
-            assert a.waves in (4, 16)
+            assert a.waves in (4, 8, 16) and (a.waves != 8 or (a.splits == 1 and 256 < a.B * a.Hs <= 512))
             # more than 16 rows: the q|k|v GEMM leaves raw products and this kernel applies the normalisation it left out
             q = ph[i - 1].g
             assert ph[i - 1].kind == QKV
