@@ -94,27 +94,50 @@ __global__ void __launch_bounds__(256, NJ == 8 ? 2 : 3) tile_gemm(TileGemmArgs a
                                        (__attribute__((address_space(3))) void *)(st + (BMT + tile) * 64), 16, 0, 0);
     }
   };
-  issue(0, 0);
-  if (n_stages > 1) issue(1, 1);
-  for (int k = 0; k < n_stages; ++k) {
-    // This wave's share of stage k has landed (loads complete in order; the stage after it may
-    // still be in flight).  The barrier then says that everyone's has, and that everyone has the
-    // operands of stage k - 1 in registers (LDS counter at zero), so that buffer can be refilled.
-    // Not __syncthreads(): its fence would also wait for the loads in flight.
-    if (k + 1 < n_stages) wait_vmcnt<LPS>();
-    else wait_vmcnt<0>();
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    if (k + 2 < n_stages) issue(k + 2, (k + 2) % kTileGemmRing);
-    const u32x4 *st = lds + (k % kTileGemmRing) * STAGE;
-    u32x4 wf[MI], af[NJ];
+  // The operands of a stage are read from LDS one stage ahead of their use: while the matrix cores work on stage
+  // k out of one set of registers, the reads of stage k + 1 into the other set are under way, so a wave's
+  // matrix-core instructions follow each other without waiting for LDS.
+  auto fetch = [&](u32x4(&wf)[MI], u32x4(&af)[NJ], int stage) {
+    const u32x4 *st = lds + (stage % kTileGemmRing) * STAGE;
 #pragma unroll
     for (int i = 0; i < MI; ++i) wf[i] = st[(wr * MI + i) * 64 + lane];
 #pragma unroll
     for (int j = 0; j < NJ; ++j) af[j] = st[(BMT + wc * NJ + j) * 64 + lane];
+  };
+  auto multiply = [&](const u32x4(&wf)[MI], const u32x4(&af)[NJ]) {
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
       for (int j = 0; j < NJ; ++j) acc[i][j] = mma_op<T>(wf[i], af[j], acc[i][j]);
+  };
+  // Before stage s is read: this wave's share of it has landed (loads complete in order; the stages after it may
+  // still be in flight), then the barrier says that everyone's has, and that everyone has the operands of stage
+  // s - 1 in registers (LDS counter at zero), so that buffer can be refilled with stage s + 2.
+  // Not __syncthreads(): its fence would also wait for the loads in flight.
+  auto ready = [&](int s) {
+    if (s + 1 < n_stages) wait_vmcnt<LPS>();
+    else wait_vmcnt<0>();
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    if (s + 2 < n_stages) issue(s + 2, (s + 2) % kTileGemmRing);
+  };
+  u32x4 wf0[MI], af0[NJ], wf1[MI], af1[NJ];
+  issue(0, 0);
+  if (n_stages > 1) issue(1, 1);
+  ready(0);
+  fetch(wf0, af0, 0);
+  for (int k = 0; k < n_stages; k += 2) {
+    if (k + 1 < n_stages) {
+      ready(k + 1);
+      fetch(wf1, af1, k + 1);
+    }
+    multiply(wf0, af0);
+    if (k + 1 < n_stages) {
+      if (k + 2 < n_stages) {
+        ready(k + 2);
+        fetch(wf0, af0, k + 2);
+      }
+      multiply(wf1, af1);
+    }
   }
 
   const int q4 = (lane >> 4) * 4, tl = lane & 15;
