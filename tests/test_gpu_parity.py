@@ -889,6 +889,53 @@ def test_weights_outside_the_half_range(ss, side_stream):
     sh.destroy()
 
 
+def test_replaced_partner_is_not_replayed_from_a_stale_graph(ss, side_stream):
+    """A pair decodes a step (its graph is captured and cached in the first shard), then the second shard is destroyed
+    and a new one with the same slice and cache takes its place, in other device memory (the old memory is handed to a
+    tensor full of junk first): the next step must run on the new shard's memory, i.e. give the bits of a pair that was
+    never touched."""
+    import torch
+    w = scaled("gpt20b_m4", "bf16", batch=5, s_in=30, steps=2, d_model=512, n_heads=8, head_dim=64, ffn=1024, vocab=1201, M=1, m=0)
+    W = make_weights(w.desc, w.slice, w.seed)
+    slices = [tp_slice(w.desc, 0, w.desc["n_layers"], m, 2) for m in range(2)]
+    toks = make_tokens(w.seed, w.batch, w.s_in, w.desc["vocab"])
+    forced = make_tokens(w.seed + 1, w.batch, 2, w.desc["vocab"])
+    V = w.desc["vocab"]
+
+    def fresh_pair():
+        return [ss.Shard(w.desc, sl, W, w.batch, w.s_max) for sl in slices]
+
+    # the pair that is never touched, kernels launched one by one
+    ref = fresh_pair()
+    ref[0].set_graph_launch(False)
+    lr = torch.empty(w.batch, V, dtype=torch.float32, device="cuda")
+    nr = torch.empty(w.batch, dtype=torch.int32, device="cuda")
+    ss.prefill(ref, dev(toks), lr, nr)
+    ss.decode_step(ref, dev(forced[:, 0]), lr, nr)
+    ss.decode_step(ref, dev(forced[:, 1]), lr, nr)
+    torch.cuda.synchronize()
+    want = lr.cpu().numpy().copy()
+    # the pair whose second shard is replaced between the two steps (graph replay)
+    a, b = fresh_pair()
+    logits = torch.empty(w.batch, V, dtype=torch.float32, device="cuda")
+    nxt = torch.empty(w.batch, dtype=torch.int32, device="cuda")
+    t0, t1 = dev(forced[:, 0]), dev(forced[:, 1])
+    ss.prefill([a, b], dev(toks), logits, nxt)
+    ss.decode_step([a, b], t0, logits, nxt)
+    torch.cuda.synchronize()
+    cache, lens, nbytes = ss.kv_export(b), list(ss.committed_len(b)), b.mem.numel()
+    b.destroy()
+    junk = torch.full((nbytes,), 0x7f, dtype=torch.uint8, device="cuda")     # most likely the memory b had
+    b2 = ss.Shard(w.desc, slices[1], W, w.batch, w.s_max)
+    ss.kv_import(b2, cache, lens)
+    ss.decode_step([a, b2], t1, logits, nxt)                                 # same caller buffers, same first shard
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(logits.cpu().numpy()), bits(want))
+    del junk
+    for s_ in ref + [a, b2]:
+        s_.destroy()
+
+
 @pytest.mark.parametrize("batch", [3, 18])
 def test_interrupted_step_commits_nothing_and_retry_is_identical(ss, side_stream, batch):
     import torch
