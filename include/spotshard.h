@@ -159,7 +159,11 @@ ss_status ss_prefill(ss_shard *const *group, int32_t n_group, const int32_t *tok
  * commit, Section 4.1).  Row n[b] is not part of the committed state before that.
  * tokens_in: device int32 [B]; logits: device float32 [B, vocab] or NULL;
  * next_tokens: device int32 [B] or NULL (may alias tokens_in).
- * SS_ESTATE if a row's cache is full or the group's lengths disagree. */
+ * SS_ESTATE if a row's cache is full or the group's lengths disagree.
+ * The step's kernels are captured into a HIP graph the first time a combination of (group, batch size, tokens_in,
+ * logits, next_tokens, stream) is seen, and replayed from then on; the group's first shard keeps up to 16 such graphs
+ * (a caller that hands in other buffers at every step pays the capture every time: keep the buffers).  On the NULL
+ * stream, or on a stream the caller is capturing, the kernels are launched one by one. */
 ss_status ss_decode_step(ss_shard *const *group, int32_t n_group, const int32_t *tokens_in,
                          int32_t B, float *logits, int32_t *next_tokens, void *hip_stream);
 
