@@ -30,10 +30,11 @@ ss_status ss_set_graph_launch(ss_shard *shard, int32_t enabled);
  * sums. */
 ss_status ss_debug_force_gemm_shape(int32_t tiles_per_block, int32_t k_slices);
 
-/* Test aid, process-wide: force the token block of the initial phase's tiled GEMMs (the initial
- * phase over all prompt tokens: the first term of Eq. (1) and Eq. (2)): 128 or 256 tokens per block; 0 = the library's choice,
- * which goes by the size of the output.  Both give the same bits.  SS_EINVAL for any other value. */
-ss_status ss_debug_force_prefill_block(int32_t tokens_per_block);
+/* Test aid, process-wide: force the block of the initial phase's tiled GEMMs (the initial
+ * phase over all prompt tokens: the first term of Eq. (1) and Eq. (2)): 128 weight rows x 128 tokens, 128 x 256 or
+ * 256 x 256; 0 x 0 = the library's choice, which goes by the size of the output (a GEMM whose two-part operand
+ * does not cover whole 256-row blocks keeps 128 rows).  All give the same bits.  SS_EINVAL for any other pair. */
+ss_status ss_debug_force_prefill_block(int32_t rows_per_block, int32_t tokens_per_block);
 
 /* Measurement aid: per-kernel-class timing of decode steps.  While enabled on group[0],
  * ss_decode_step launches kernel by kernel (no graph replay) and every launch records its own

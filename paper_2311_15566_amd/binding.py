@@ -86,7 +86,7 @@ def _load():
     L.ss_shard_model_context_bytes.argtypes = [vp]
     L.ss_shard_model_context_bytes.restype = C.c_size_t
     L.ss_debug_force_gemm_shape.argtypes = [i32, i32]
-    L.ss_debug_force_prefill_block.argtypes = [i32]
+    L.ss_debug_force_prefill_block.argtypes = [i32, i32]
     L.ss_kernel_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), vp]
     return L
 
@@ -292,9 +292,10 @@ def force_gemm_shape(tiles_per_block: int = 0, k_slices: int = 0):
     _check(lib.ss_debug_force_gemm_shape(int(tiles_per_block), int(k_slices)))
 
 
-def force_prefill_block(tokens_per_block: int = 0):
-    """Test aid: force the token block (128 or 256) of the initial phase's GEMMs (0 = library's choice)."""
-    _check(lib.ss_debug_force_prefill_block(int(tokens_per_block)))
+def force_prefill_block(rows_per_block: int = 0, tokens_per_block: int = 0):
+    """Test aid: force the block of the initial phase's GEMMs, rows x tokens: 128 x 128, 128 x 256 or 256 x 256
+    (0 x 0 = library's choice)."""
+    _check(lib.ss_debug_force_prefill_block(int(rows_per_block), int(tokens_per_block)))
 
 
 def device_kv_bytes(shard) -> int:

@@ -9,6 +9,7 @@
 #include <algorithm>
 #include <atomic>
 #include <mutex>
+#include <type_traits>
 
 namespace ss {
 
@@ -26,15 +27,35 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
+// The accumulators of a 128 x 128 wave tile fill all 256 accumulation registers and the operands must stay in the
+// ordinary ones; the register allocator does not find that split by itself (it parks operands in accumulation
+// registers and shuffles accumulators in and out), so the product of that tile is written with the classes spelled out.
+// Written this way the compiler no longer sees a matrix-core instruction: the wait states between the last product and
+// the first read of an accumulator are inserted by hand (drain_mma); between products nothing is needed, every
+// accumulator being used once per 64 products and the operands written by LDS reads only (waited for by counter).
+// FIRST: the product alone (added to the constant 0), which also defines the accumulator
+template <bool FIRST>
+__device__ __forceinline__ void mma_f16_pinned(f32x4 &c, const u32x4 &w, const u32x4 &a) {
+  if constexpr (FIRST) asm("v_mfma_f32_16x16x32_f16 %0, %1, %2, 0" : "=a"(c) : "v"(w), "v"(a));
+  else asm("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(c) : "v"(w), "v"(a));
+}
+__device__ __forceinline__ void drain_mma() {
+  __builtin_amdgcn_sched_barrier(0);
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
+}
+
 // bf16 models: the activation operands and the stored weight fragments are halves; float32 models: floats.
 // Either way a fragment is 64 lanes x 16 bytes, so the loop is the same.
 constexpr int kTileGemmRing = 3;  // LDS stages
+constexpr int kBigBlockRounds = 4;  // 256-row blocks where there are at least this many per compute unit
 
-// NJ: token tiles of a wave, 8 (block of 256 tokens, two blocks per compute unit) or 4 (128 tokens, three)
-template <typename T, int EPI, int NJ>
-__global__ void __launch_bounds__(256, NJ == 8 ? 2 : 3) tile_gemm(TileGemmArgs a) {
+// NJ: token tiles of a wave, 8 (block of 256 tokens) or 4 (128 tokens); MI: weight row tiles of a wave, 4 (block of 128 rows;
+// two blocks per compute unit with 256 tokens, three with 128) or 8 (256 rows x 256 tokens, one block per compute unit and one
+// wave per SIMD with a 128 x 128 tile: 2/3 of the LDS and L2 reads per flop of the 128 x 256 block)
+template <typename T, int EPI, int NJ, int MI>
+__global__ void __launch_bounds__(256, MI == 8 ? 1 : (NJ == 8 ? 2 : 3)) tile_gemm(TileGemmArgs a) {
   typedef typename Operand<T>::type OT;  // element type of the activation operands
-  constexpr int MI = 4;                  // weight row tiles of a wave
   constexpr int BMT = 2 * MI, BTT = 2 * NJ;
   constexpr int STAGE = (BMT + BTT) * 64;  // 16-byte pieces per stage: weight fragments, then activation fragments
   constexpr int LPS = (BMT + BTT) / 4;     // loads a wave issues per stage
@@ -67,10 +88,12 @@ __global__ void __launch_bounds__(256, NJ == 8 ? 2 : 3) tile_gemm(TileGemmArgs a
   const int n_stages = A_lo ? 2 * a.k_blocks : a.k_blocks;
 
   f32x4 acc[MI][NJ];
+  if constexpr (MI != 8) {  // (the 256-row block's first stage defines them)
 #pragma unroll
-  for (int i = 0; i < MI; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int j = 0; j < NJ; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
 
   // Stage k -> buffer buf: every wave brings 2 weight and 4 activation fragments, each as one
   // 1 KiB load that the hardware writes to LDS at (wave-uniform base) + lane * 16.  Row tiles
@@ -120,23 +143,94 @@ __global__ void __launch_bounds__(256, NJ == 8 ? 2 : 3) tile_gemm(TileGemmArgs a
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     if (s + 2 < n_stages) issue(s + 2, (s + 2) % kTileGemmRing);
   };
-  u32x4 wf0[MI], af0[NJ], wf1[MI], af1[NJ];
   issue(0, 0);
   if (n_stages > 1) issue(1, 1);
   ready(0);
-  fetch(wf0, af0, 0);
-  for (int k = 0; k < n_stages; k += 2) {
-    if (k + 1 < n_stages) {
-      ready(k + 1);
-      fetch(wf1, af1, k + 1);
-    }
-    multiply(wf0, af0);
-    if (k + 1 < n_stages) {
-      if (k + 2 < n_stages) {
-        ready(k + 2);
-        fetch(wf0, af0, k + 2);
+  if constexpr (MI == 8) {
+    // 256 accumulator registers leave room for one set of weight operands and two of activation operands: the
+    // products go weight row tile by row tile, and a row tile's register takes the next stage's fragment as soon as its
+    // products are issued; the next stage's activation fragments arrive in the other set during the first rows.
+    static_assert(NJ == 8 && sizeof(T) == 2, "the 256-row block has 256 tokens and half-precision operands");
+    // With one wave per SIMD nothing else fills the matrix cores while this wave does something else, so a stage's
+    // other work is spread between its rows of products.  The barrier that says "stage s + 1 has landed and everyone
+    // has stage s in registers" comes after the second row, when the last LDS read of the previous stage has long
+    // returned; then the reads of stage s + 1 follow the rows that free their registers, and the eight loads of the
+    // stage three ahead go two at a time behind rows 2 to 5.
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const u32x4 *src[LPS];  // this lane's piece of the wave's fragments at k = 0: weight tiles, then activation tiles
+#pragma unroll
+    for (int r = 0; r < BMT / 4; ++r) src[r] = W + (size_t)min(rt0 + wave_u + 4 * r, a.row_tiles - 1) * a.k_blocks * 64 + lane;
+#pragma unroll
+    for (int r = 0; r < BTT / 4; ++r) src[BMT / 4 + r] = A + (size_t)(tt0 + wave_u + 4 * r) * a.k_blocks * 64 + lane;
+    const ptrdiff_t lo_delta = A_lo ? A_lo - A : 0;
+    auto issue_piece = [&](int stage, int r) {  // r: 0 .. LPS - 1
+      const bool second = stage >= a.k_blocks;
+      const int k = second ? stage - a.k_blocks : stage;
+      const ptrdiff_t off = (ptrdiff_t)k * 64 + ((second && r >= BMT / 4) ? lo_delta : 0);
+      u32x4 *dst = lds + (stage % kTileGemmRing) * STAGE + (wave_u + 4 * r) * 64;  // (activation tiles follow the BMT weight tiles)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[r] + off),
+                                       (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
+    };
+    u32x4 wf[MI], af0[NJ], af1[NJ];
+    fetch(wf, af0, 0);
+    // full: stage s + 3 exists (known where the call is written: the steady loop's stages run without a branch, which
+    // also lets the waits for LDS reads count reads instead of waiting for all of them)
+    auto stage = [&](auto first, auto full, int s, const u32x4(&cur)[NJ], u32x4(&nxt)[NJ]) {
+      constexpr bool FULL = decltype(full)::value;
+      const bool more = FULL || s + 1 < n_stages, load = FULL || s + 3 < n_stages;
+      const u32x4 *st = lds + ((s + 1) % kTileGemmRing) * STAGE;
+      auto read_w = [&](int i) { wf[i] = st[(wr * MI + i) * 64 + lane]; };
+      auto read_a = [&](int j) { nxt[j] = st[(BMT + wc * NJ + j) * 64 + lane]; };
+#pragma unroll
+      for (int i = 0; i < MI; ++i) {
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) mma_f16_pinned<decltype(first)::value>(acc[i][j], wf[i], cur[j]);
+        // (the reads are not conditional, so that the waits for them can count: behind the last stage they bring
+        // whatever the ring's next buffer holds, into registers nobody uses again)
+        if (i == 1) {
+          if (more) {
+            if (FULL || s + 2 < n_stages) wait_vmcnt<LPS>();
+            else wait_vmcnt<0>();
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+          }
+          read_a(0), read_a(1), read_w(0), read_w(1);
+        } else if (i >= 2) {
+          if (i <= 4) read_a(2 * i - 2), read_a(2 * i - 1);
+          read_w(i);
+        }
+        if (load && i >= 2 && i < 2 + LPS / 2) issue_piece(s + 3, 2 * i - 4), issue_piece(s + 3, 2 * i - 3);
+        __builtin_amdgcn_sched_barrier(0);
       }
-      multiply(wf1, af1);
+    };
+    const std::true_type yes;
+    const std::false_type no;
+    stage(yes, no, 0, af0, af1);
+    int k = 1;
+    for (; k + 4 < n_stages; k += 2) {
+      stage(no, yes, k, af1, af0);
+      stage(no, yes, k + 1, af0, af1);
+    }
+    for (; k < n_stages; k += 2) {
+      stage(no, no, k, af1, af0);
+      if (k + 1 < n_stages) stage(no, no, k + 1, af0, af1);
+    }
+    drain_mma();
+  } else {
+    u32x4 wf0[MI], af0[NJ], wf1[MI], af1[NJ];
+    fetch(wf0, af0, 0);
+    for (int k = 0; k < n_stages; k += 2) {
+      if (k + 1 < n_stages) {
+        ready(k + 1);
+        fetch(wf1, af1, k + 1);
+      }
+      multiply(wf0, af0);
+      if (k + 1 < n_stages) {
+        if (k + 2 < n_stages) {
+          ready(k + 2);
+          fetch(wf0, af0, k + 2);
+        }
+        multiply(wf1, af1);
+      }
     }
   }
 
@@ -171,10 +265,12 @@ __global__ void __launch_bounds__(256, NJ == 8 ? 2 : 3) tile_gemm(TileGemmArgs a
         }
       }
     } else if (EPI == EPI_RESID) {
-      float s1 = 0.f, s2 = 0.f;
       const float cen = a.g_out ? a.c_in[tok][0] : 0.f;
 #pragma unroll
-      for (int i = 0; i < MI; ++i) {
+      for (int band = 0; band < MI / 4; ++band) {  // 64 features: one partial sum each
+      float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+      for (int i = band * 4; i < band * 4 + 4; ++i) {
         const int rt = rt0 + wr * MI + i;
         const int n0 = rt * 16 + q4;
         if (tok_live && rt < a.row_tiles && n0 < a.N) {
@@ -203,10 +299,12 @@ __global__ void __launch_bounds__(256, NJ == 8 ? 2 : 3) tile_gemm(TileGemmArgs a
           }
         }
       }
-      if (a.g_out) {  // the wave's 64 features of this token
+      if (a.g_out) {  // 64 features of this token
         s1 += __shfl_xor(s1, 16), s2 += __shfl_xor(s2, 16);
         s1 += __shfl_xor(s1, 32), s2 += __shfl_xor(s2, 32);
-        if (lane < 16) a.stat_out[(size_t)(rb * 2 + wr) * a.T + tok] = make_float2(s1, s2);
+        const int g = (rt0 + wr * MI) / 4 + band;  // bands past the last 128-row block have no slot
+        if (lane < 16 && g < 2 * ((a.row_tiles + 7) / 8)) a.stat_out[(size_t)g * a.T + tok] = make_float2(s1, s2);
+      }
       }
     } else {
       const float2 mr = a.mr_in ? make_float2(a.mr_in[tok][2], a.mr_in[tok][1]) : make_float2(0.f, 1.f);
@@ -278,17 +376,18 @@ ss_status launch_row_stats(const float2 *part, int groups, int T, int norm_dim, 
 }
 
 static std::atomic<int> g_forced_tok_tiles{0};  // test aid: 0 = not forced
+static std::atomic<int> g_forced_row_tiles{0};
 
-template <typename T, int EPI, int NJ>
+template <typename T, int EPI, int NJ, int MI>
 static ss_status launch_one(const TileGemmArgs &a, dim3 grid, hipStream_t st) {
-  constexpr size_t lds_bytes = (size_t)kTileGemmRing * (8 + 2 * NJ) * 1024;  // 48 / 72 KiB: above the 64 KiB that need no opt-in
+  constexpr size_t lds_bytes = (size_t)kTileGemmRing * (2 * MI + 2 * NJ) * 1024;  // 48, 72 or 96 KiB: above the 64 KiB that need no opt-in
   static std::once_flag once;
   static hipError_t attr = hipSuccess;
   std::call_once(once, [] {
-    attr = hipFuncSetAttribute((const void *)tile_gemm<T, EPI, NJ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    attr = hipFuncSetAttribute((const void *)tile_gemm<T, EPI, NJ, MI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
   });
   if (attr != hipSuccess) SS_FAIL(SS_EHIP, "prefill GEMM: %zu bytes of LDS refused: %s", lds_bytes, hipGetErrorString(attr));
-  hipLaunchKernelGGL((tile_gemm<T, EPI, NJ>), grid, dim3(256), lds_bytes, st, a);
+  hipLaunchKernelGGL((tile_gemm<T, EPI, NJ, MI>), grid, dim3(256), lds_bytes, st, a);
   return SS_OK;
 }
 
@@ -307,18 +406,28 @@ ss_status launch_tile_gemm(int dtype, int epi, TileGemmArgs a, hipStream_t st) {
     if (!a.norm_out || !a.stat_out || !a.c_in || a.N % fk || a.N != a.row_tiles * 16)
       SS_FAIL(SS_EINVAL, "prefill GEMM: bad next-operand arguments");
   }
-  a.n_row_blocks = ceil_div(a.row_tiles, 8);
   // Token block: measured on every GEMM shape of the GPT-20B, LLaMA-30B and OPT-66B shards, 256-token
   // blocks win by 3-9 % where the output has a few rounds of them (16384 tokens: fewer LDS and L2
   // reads per flop), 128-token blocks by 7-17 % on the 4096-token shapes (more blocks to spread over
   // the compute units) and by 8 % on a short reduction (1152), where a block is mostly epilogue.
-  if (g_forced_tok_tiles.load()) a.tok_tiles = g_forced_tok_tiles.load();
-  if (a.tok_tiles != 4 && a.tok_tiles != 8) a.tok_tiles = ((long)a.n_row_blocks * (a.T / 128) >= 2048 && a.k_blocks >= 64) ? 8 : 4;
+  // Row block: 256 rows x 256 tokens (one wave per SIMD) where the output has several rounds of such blocks too.
+  if (g_forced_tok_tiles.load()) a.tok_tiles = g_forced_tok_tiles.load(), a.wave_row_tiles = g_forced_row_tiles.load();
+  if (a.tok_tiles != 4 && a.tok_tiles != 8) {
+    const long blocks128 = (long)ceil_div(a.row_tiles, 8) * (a.T / 128);
+    a.tok_tiles = (blocks128 >= 2048 && a.k_blocks >= 64) ? 8 : 4;
+    a.wave_row_tiles = (blocks128 >= 4 * kBigBlockRounds * 256 && a.k_blocks >= 64) ? 8 : 4;
+  }
+  if (a.wave_row_tiles != 8 || a.tok_tiles != 8 || dtype != SS_DTYPE_BF16 || (a.act_lo && (a.lo_row_begin % 16 || a.lo_row_end % 16)))
+    a.wave_row_tiles = 4;
+  a.n_row_blocks = ceil_div(a.row_tiles, 2 * a.wave_row_tiles);
   dim3 grid(a.n_row_blocks * (a.T / (a.tok_tiles * 32)));
-#define SS_LAUNCH(TT, EPI)                                                \
-  do {                                                                    \
-    if (a.tok_tiles == 8) SS_TRY((launch_one<TT, EPI, 8>(a, grid, st)));  \
-    else SS_TRY((launch_one<TT, EPI, 4>(a, grid, st)));                   \
+#define SS_LAUNCH(TT, EPI)                                                                                            \
+  do {                                                                                                                \
+    if constexpr (sizeof(TT) == 2) {                                                                                  \
+      if (a.wave_row_tiles == 8) { SS_TRY((launch_one<TT, EPI, 8, 8>(a, grid, st))); break; }                         \
+    }                                                                                                                 \
+    if (a.tok_tiles == 8) SS_TRY((launch_one<TT, EPI, 8, 4>(a, grid, st)));                                           \
+    else SS_TRY((launch_one<TT, EPI, 4, 4>(a, grid, st)));                                                            \
   } while (0)
   if (dtype == SS_DTYPE_BF16) {
     if (epi == EPI_F32) SS_LAUNCH(bf16_t, EPI_F32);
@@ -338,10 +447,13 @@ ss_status launch_tile_gemm(int dtype, int epi, TileGemmArgs a, hipStream_t st) {
 
 }  // namespace ss
 
-extern "C" ss_status ss_debug_force_prefill_block(int32_t tokens_per_block) {
+extern "C" ss_status ss_debug_force_prefill_block(int32_t rows_per_block, int32_t tokens_per_block) {
   using namespace ss;
-  if (tokens_per_block != 0 && tokens_per_block != 128 && tokens_per_block != 256)
-    SS_FAIL(SS_EINVAL, "token block %d (0, 128 or 256)", tokens_per_block);
+  const bool none = rows_per_block == 0 && tokens_per_block == 0;
+  const bool small = rows_per_block == 128 && (tokens_per_block == 128 || tokens_per_block == 256);
+  const bool big = rows_per_block == 256 && tokens_per_block == 256;
+  if (!none && !small && !big) SS_FAIL(SS_EINVAL, "block of %d rows x %d tokens (0 x 0, 128 x 128, 128 x 256 or 256 x 256)", rows_per_block, tokens_per_block);
+  g_forced_row_tiles.store(rows_per_block / 32);
   g_forced_tok_tiles.store(tokens_per_block / 32);
   return SS_OK;
 }

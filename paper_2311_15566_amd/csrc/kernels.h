@@ -125,12 +125,13 @@ struct TileGemmArgs {
   void *norm_out;     // EPI_RESID with g_out: (x - c) * g_out as fragments [T/16][N / FragK]
   void *norm_out_lo;  // or NULL: what rounding norm_out to the operand type lost, as fragments of the same shape
   const f32x4 *c_in;  // EPI_RESID with g_out: [T], .x = the centre c (the token's mean at the previous norm)
-  float2 *stat_out;   // EPI_RESID with g_out: [2 * n_row_blocks][T]
+  float2 *stat_out;   // EPI_RESID with g_out: [2 * ceil(row_tiles / 8)][T], one per 64-feature band
   void *act_out;      // EPI_ACT / EPI_SWIGLU: fragments [T/16][out_k_blocks]
   int out_k_blocks;
   int act_kind;
-  int n_row_blocks;   // set by the launcher: 128-row blocks of the weight matrix
-  int tok_tiles;      // token tiles per wave, 8 or 4: blocks of 256 or 128 tokens (anything else: the launcher chooses)
+  int n_row_blocks;   // set by the launcher: row blocks of the weight matrix
+  int tok_tiles;      // token tiles per wave, 8 or 4: blocks of 256 or 128 tokens (anything else: the launcher chooses both)
+  int wave_row_tiles; // weight row tiles per wave, 4 or 8: blocks of 128 or 256 rows (256 only with 256 tokens)
 };
 ss_status launch_tile_gemm(int dtype, int epi, TileGemmArgs a, hipStream_t st);
 // mr[t] <- (mean, rstd, mean - c, 0) from `groups` partial (sum (x-c), sum (x-c)^2) pairs laid out

@@ -358,10 +358,11 @@ def test_exact_ties_go_to_the_lowest_index(ss, name, dtype, batch):
 
 
 @pytest.mark.parametrize("name,dtype,batch,s_in", [("gpt20b_m4", "bf16", 3, 111), ("llama30b_m2", "bf16", 5, 77), ("tiny_gpt", "f32", 2, 150)])
-def test_prefill_token_blocks_give_the_same_bits(ss, side_stream, name, dtype, batch, s_in):
-    """The initial phase's GEMMs run with 128- or 256-token blocks (chosen by output size): both
-    walk k in the same order, so logits, first tokens and caches must agree bit for bit — here
-    on token counts and feature counts that are multiples of neither block."""
+def test_prefill_blocks_give_the_same_bits(ss, side_stream, name, dtype, batch, s_in):
+    """The initial phase's GEMMs run with blocks of 128 rows x 128 tokens, 128 x 256 or 256 x 256 (chosen by
+    output size): all walk k in the same order and sum the row statistics over the same 64-feature bands, so
+    logits, first tokens and caches must agree bit for bit — here on token counts and feature counts that are
+    multiples of no block."""
     import torch
     if name == "tiny_gpt":
         w = scaled(name, dtype, layers=2, batch=batch, s_in=s_in, steps=1)
@@ -371,8 +372,8 @@ def test_prefill_token_blocks_give_the_same_bits(ss, side_stream, name, dtype, b
     toks = make_tokens(w.seed, w.batch, w.s_in, w.desc["vocab"])
     outs = []
     try:
-        for block in (128, 256, 0):
-            ss.force_prefill_block(block)
+        for block in ((128, 128), (128, 256), (256, 256), (0, 0)):
+            ss.force_prefill_block(*block)
             sh = ss.Shard(w.desc, w.slice, W, w.batch, w.s_max)
             logits = torch.empty(w.batch, w.desc["vocab"], dtype=torch.float32, device="cuda")
             nxt = torch.empty(w.batch, dtype=torch.int32, device="cuda")
@@ -381,9 +382,10 @@ def test_prefill_token_blocks_give_the_same_bits(ss, side_stream, name, dtype, b
             outs.append([logits.cpu().numpy().copy(), nxt.cpu().numpy().copy(), ss.kv_export(sh)])
             sh.destroy()
     finally:
-        ss.force_prefill_block(0)
-    with pytest.raises(Exception):
-        ss.force_prefill_block(64)
+        ss.force_prefill_block(0, 0)
+    for bad in ((128, 64), (256, 128), (0, 256)):
+        with pytest.raises(Exception):
+            ss.force_prefill_block(*bad)
     for other in outs[1:]:
         for a, b in zip(outs[0], other):
             assert np.array_equal(bits(a) if a.dtype != np.int32 else a, bits(b) if b.dtype != np.int32 else b)
