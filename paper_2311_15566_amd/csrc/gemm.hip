@@ -10,6 +10,7 @@
 #include <atomic>
 #include <mutex>
 #include <type_traits>
+#include <utility>
 
 namespace ss {
 
@@ -27,27 +28,57 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
-// The accumulators of a 128 x 128 wave tile fill all 256 accumulation registers and the operands must stay in the
-// ordinary ones; the register allocator does not find that split by itself (it parks operands in accumulation
-// registers and shuffles accumulators in and out), so the product of that tile is written with the classes spelled out.
-// Written this way the compiler no longer sees a matrix-core instruction: the wait states between the last product and
-// the first read of an accumulator are inserted by hand (drain_mma); between products nothing is needed, every
-// accumulator being used once per 64 products and the operands written by LDS reads only (waited for by counter).
-// FIRST: the product alone (added to the constant 0), which also defines the accumulator
-template <bool FIRST>
+// The 256-row block's main loop is scheduled by hand, for two reasons.
+// (1) The accumulators of its 128 x 128 wave tile fill all 256 accumulation registers and the operands must stay in the
+// ordinary ones; the register allocator does not find that split by itself (it parks operands in accumulation registers
+// and shuffles accumulators in and out), so the product is written with the register classes spelled out.
+// (2) With one wave per SIMD nothing else fills the matrix cores while the wave does something else: the LDS reads and
+// the loads of later stages must sit between the products, one at a time, and a product must wait only for the reads it
+// needs, not for all that are under way (which is what the compiler's own wait insertion asks for).
+// So products, LDS reads and their waits are volatile asm statements, which keep their order; the compiler sees neither a
+// matrix-core instruction nor an LDS read in that loop and inserts no wait state or counter wait of its own there:
+//  - an LDS read's destination is valid only after a wait_lds that covers it (reads return in order);
+//  - between products nothing is needed: every accumulator is used once per 64 products;
+//  - drain_mma() ends the loop: all reads returned, and the wait states between the last product and the first read of
+//    an accumulator.
+template <bool FIRST>  // FIRST: the product alone (added to the constant 0), which also defines the accumulator
 __device__ __forceinline__ void mma_f16_pinned(f32x4 &c, const u32x4 &w, const u32x4 &a) {
-  if constexpr (FIRST) asm("v_mfma_f32_16x16x32_f16 %0, %1, %2, 0" : "=a"(c) : "v"(w), "v"(a));
-  else asm("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(c) : "v"(w), "v"(a));
+  if constexpr (FIRST) asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, 0" : "=a"(c) : "v"(w), "v"(a));
+  else asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(c) : "v"(w), "v"(a));
+}
+template <int OFF>  // 16 bytes per lane from LDS byte address addr + OFF
+__device__ __forceinline__ void lds_read_async(u32x4 &dst, uint32_t addr) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
+}
+template <int N>  // until at most N LDS reads are under way
+__device__ __forceinline__ void wait_lds() {
+  asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N));
 }
 __device__ __forceinline__ void drain_mma() {
   __builtin_amdgcn_sched_barrier(0);
-  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
   __builtin_amdgcn_sched_barrier(0);
+}
+template <int... Is, typename F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, Is...>, F &&f) {
+  (f(std::integral_constant<int, Is>()), ...);
+}
+template <int N, typename F>  // f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>)
+__device__ __forceinline__ void static_for(F &&f) {
+  static_for_impl(std::make_integer_sequence<int, N>(), f);
+}
+// s_waitcnt vmcnt(8 * stages), stages 0..3 (wave-uniform)
+__device__ __forceinline__ void wait_stages_in_flight(int stages) {
+  if (stages >= 3) wait_vmcnt<24>();
+  else if (stages == 2) wait_vmcnt<16>();
+  else if (stages == 1) wait_vmcnt<8>();
+  else wait_vmcnt<0>();
 }
 
 // bf16 models: the activation operands and the stored weight fragments are halves; float32 models: floats.
 // Either way a fragment is 64 lanes x 16 bytes, so the loop is the same.
-constexpr int kTileGemmRing = 3;  // LDS stages
+constexpr int kTileGemmRing = 3;  // LDS stages (128-row blocks)
+constexpr int kBigBlockRing = 4;  // LDS stages of the 256-row block
 constexpr int kBigBlockRounds = 4;  // 256-row blocks where there are at least this many per compute unit
 
 // NJ: token tiles of a wave, 8 (block of 256 tokens) or 4 (128 tokens); MI: weight row tiles of a wave, 4 (block of 128 rows;
@@ -59,7 +90,7 @@ __global__ void __launch_bounds__(256, MI == 8 ? 1 : (NJ == 8 ? 2 : 3)) tile_gem
   constexpr int BMT = 2 * MI, BTT = 2 * NJ;
   constexpr int STAGE = (BMT + BTT) * 64;  // 16-byte pieces per stage: weight fragments, then activation fragments
   constexpr int LPS = (BMT + BTT) / 4;     // loads a wave issues per stage
-  extern __shared__ __align__(16) u32x4 lds[];  // kTileGemmRing stages
+  extern __shared__ __align__(16) u32x4 lds[];  // kTileGemmRing or kBigBlockRing stages
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave >> 1, wc = wave & 1;
   // Block -> output tile.  Workgroups go to the 8 XCDs round-robin and each XCD has its own L2, so
@@ -143,19 +174,16 @@ __global__ void __launch_bounds__(256, MI == 8 ? 1 : (NJ == 8 ? 2 : 3)) tile_gem
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     if (s + 2 < n_stages) issue(s + 2, (s + 2) % kTileGemmRing);
   };
-  issue(0, 0);
-  if (n_stages > 1) issue(1, 1);
-  ready(0);
   if constexpr (MI == 8) {
-    // 256 accumulator registers leave room for one set of weight operands and two of activation operands: the
-    // products go weight row tile by row tile, and a row tile's register takes the next stage's fragment as soon as its
-    // products are issued; the next stage's activation fragments arrive in the other set during the first rows.
-    static_assert(NJ == 8 && sizeof(T) == 2, "the 256-row block has 256 tokens and half-precision operands");
-    // With one wave per SIMD nothing else fills the matrix cores while this wave does something else, so a stage's
-    // other work is spread between its rows of products.  The barrier that says "stage s + 1 has landed and everyone
-    // has stage s in registers" comes after the second row, when the last LDS read of the previous stage has long
-    // returned; then the reads of stage s + 1 follow the rows that free their registers, and the eight loads of the
-    // stage three ahead go two at a time behind rows 2 to 5.
+    // One set of weight operands and two of activation operands beside the 256 accumulators.  A stage's 64 products go
+    // weight row tile by row tile; a row tile's register takes the next stage's fragment once its products are issued,
+    // the next stage's activation fragments arrive in the other set.  The barrier that says "stage s + 1 has landed
+    // and everyone has stage s in registers" comes after the second row, when the last LDS read of the previous stage
+    // has long returned; the LDS reads of stage s + 1 and the eight loads of stage s + 4 (into the buffer stage s just
+    // left) follow one by one behind the products of rows 2 to 7.
+    static_assert(NJ == 8 && sizeof(T) == 2 && LPS == 8, "the 256-row block has 256 tokens and half-precision operands");
+    constexpr int R = kBigBlockRing;
+    constexpr uint32_t STAGE_BYTES = STAGE * 16;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const u32x4 *src[LPS];  // this lane's piece of the wave's fragments at k = 0: weight tiles, then activation tiles
 #pragma unroll
@@ -167,46 +195,76 @@ __global__ void __launch_bounds__(256, MI == 8 ? 1 : (NJ == 8 ? 2 : 3)) tile_gem
       const bool second = stage >= a.k_blocks;
       const int k = second ? stage - a.k_blocks : stage;
       const ptrdiff_t off = (ptrdiff_t)k * 64 + ((second && r >= BMT / 4) ? lo_delta : 0);
-      u32x4 *dst = lds + (stage % kTileGemmRing) * STAGE + (wave_u + 4 * r) * 64;  // (activation tiles follow the BMT weight tiles)
+      u32x4 *dst = lds + (stage % R) * STAGE + (wave_u + 4 * r) * 64;  // (activation tiles follow the BMT weight tiles)
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[r] + off),
                                        (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
     };
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)lds;
+    const uint32_t w_at = lds0 + (uint32_t)((wr * MI) * 64 + lane) * 16;         // + 1024 per row tile
+    const uint32_t a_at = lds0 + (uint32_t)((BMT + wc * NJ) * 64 + lane) * 16;   // + 1024 per token tile
     u32x4 wf[MI], af0[NJ], af1[NJ];
-    fetch(wf, af0, 0);
-    // full: stage s + 3 exists (known where the call is written: the steady loop's stages run without a branch, which
-    // also lets the waits for LDS reads count reads instead of waiting for all of them)
-    auto stage = [&](auto first, auto full, int s, const u32x4(&cur)[NJ], u32x4(&nxt)[NJ]) {
-      constexpr bool FULL = decltype(full)::value;
-      const bool more = FULL || s + 1 < n_stages, load = FULL || s + 3 < n_stages;
-      const u32x4 *st = lds + ((s + 1) % kTileGemmRing) * STAGE;
-      auto read_w = [&](int i) { wf[i] = st[(wr * MI + i) * 64 + lane]; };
-      auto read_a = [&](int j) { nxt[j] = st[(BMT + wc * NJ + j) * 64 + lane]; };
+    // the first R stages are requested, stage 0 has landed for everyone, its operands are read
 #pragma unroll
-      for (int i = 0; i < MI; ++i) {
+    for (int s = 0; s < R; ++s)
+      if (s < n_stages) {
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) mma_f16_pinned<decltype(first)::value>(acc[i][j], wf[i], cur[j]);
-        // (the reads are not conditional, so that the waits for them can count: behind the last stage they bring
-        // whatever the ring's next buffer holds, into registers nobody uses again)
-        if (i == 1) {
-          if (more) {
-            if (FULL || s + 2 < n_stages) wait_vmcnt<LPS>();
-            else wait_vmcnt<0>();
-            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-          }
-          read_a(0), read_a(1), read_w(0), read_w(1);
-        } else if (i >= 2) {
-          if (i <= 4) read_a(2 * i - 2), read_a(2 * i - 1);
-          read_w(i);
-        }
-        if (load && i >= 2 && i < 2 + LPS / 2) issue_piece(s + 3, 2 * i - 4), issue_piece(s + 3, 2 * i - 3);
-        __builtin_amdgcn_sched_barrier(0);
+        for (int r = 0; r < LPS; ++r) issue_piece(s, r);
       }
+    wait_stages_in_flight(min(R, n_stages) - 1);
+    asm volatile("s_barrier" ::: "memory");
+    static_for<MI>([&](auto I) { lds_read_async<decltype(I)::value * 1024>(wf[decltype(I)::value], w_at); });
+    static_for<NJ>([&](auto J) { lds_read_async<decltype(J)::value * 1024>(af0[decltype(J)::value], a_at); });
+    wait_lds<0>();
+    // full: stage s + R exists (known where the call is written: the steady loop's stages run without a branch)
+    auto stage = [&](auto first, auto full, int s, const u32x4(&cur)[NJ], u32x4(&nxt)[NJ]) {
+      constexpr bool FIRST = decltype(first)::value, FULL = decltype(full)::value;
+      const bool more = FULL || s + 1 < n_stages, load = FULL || s + R < n_stages;
+      const uint32_t buf = (uint32_t)((s + 1) % R) * STAGE_BYTES;
+      const uint32_t w_rd = w_at + buf, a_rd = a_at + buf;
+      // Order of the reads of stage s + 1: a0 a1 w0 w1 a2 a3 | w2 a4 a5 a6 a7 | w3 | w4 | w5 | w6 | w7 (w_i only after
+      // row i).  Row 0 of the next stage needs w0 and every a_j: all but the last five reads.  (Behind the last
+      // stage the reads bring whatever the ring's next buffer holds, into registers nobody uses again.)
+      wait_lds<5>();
+      static_for<MI * NJ>([&](auto IJ) {
+        constexpr int i = decltype(IJ)::value / NJ, j = decltype(IJ)::value % NJ;
+        mma_f16_pinned<FIRST>(acc[i][j], wf[i], cur[j]);
+        if constexpr (i == 1 && j == NJ - 1) {
+          if (more) {  // block-uniform
+            if constexpr (FULL) wait_vmcnt<(R - 2) * LPS>();
+            else wait_stages_in_flight(min(n_stages - 2 - s, R - 2));
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+          } else {
+            wait_lds<0>();
+          }
+        }
+        if constexpr (i == 2 && j == 0) lds_read_async<0 * 1024>(nxt[0], a_rd);
+        if constexpr (i == 2 && j == 1) lds_read_async<1 * 1024>(nxt[1], a_rd);
+        if constexpr (i == 2 && j == 2) lds_read_async<0 * 1024>(wf[0], w_rd);
+        if constexpr (i == 2 && j == 3) lds_read_async<1 * 1024>(wf[1], w_rd);
+        if constexpr (i == 2 && j == 4) lds_read_async<2 * 1024>(nxt[2], a_rd);
+        if constexpr (i == 2 && j == 5) lds_read_async<3 * 1024>(nxt[3], a_rd);
+        if constexpr (i == 3 && j == 0) lds_read_async<2 * 1024>(wf[2], w_rd);
+        if constexpr (i == 3 && j == 1) lds_read_async<4 * 1024>(nxt[4], a_rd);
+        if constexpr (i == 3 && j == 2) lds_read_async<5 * 1024>(nxt[5], a_rd);
+        if constexpr (i == 3 && j == 3) lds_read_async<6 * 1024>(nxt[6], a_rd);
+        if constexpr (i == 3 && j == 4) lds_read_async<7 * 1024>(nxt[7], a_rd);
+        if constexpr (i >= 4 && j == 0) lds_read_async<(i - 1) * 1024>(wf[i - 1], w_rd);
+        if constexpr (i == MI - 1 && j == NJ - 1) lds_read_async<(MI - 1) * 1024>(wf[MI - 1], w_rd);
+        // the loads of stage s + R: behind (2,6) (2,7) (3,6) (3,7) (4,3) (4,6) (5,3) (5,6)
+        if constexpr ((i == 2 || i == 3) && j >= 6) {
+          if (load) issue_piece(s + R, (i - 2) * 2 + (j - 6));
+        }
+        if constexpr ((i == 4 || i == 5) && (j == 3 || j == 6)) {
+          if (load) issue_piece(s + R, 4 + (i - 4) * 2 + (j == 6));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      });
     };
     const std::true_type yes;
     const std::false_type no;
     stage(yes, no, 0, af0, af1);
     int k = 1;
-    for (; k + 4 < n_stages; k += 2) {
+    for (; k + 1 + R < n_stages; k += 2) {
       stage(no, yes, k, af1, af0);
       stage(no, yes, k + 1, af0, af1);
     }
@@ -216,6 +274,9 @@ __global__ void __launch_bounds__(256, MI == 8 ? 1 : (NJ == 8 ? 2 : 3)) tile_gem
     }
     drain_mma();
   } else {
+    issue(0, 0);
+    if (n_stages > 1) issue(1, 1);
+    ready(0);
     u32x4 wf0[MI], af0[NJ], wf1[MI], af1[NJ];
     fetch(wf0, af0, 0);
     for (int k = 0; k < n_stages; k += 2) {
@@ -234,105 +295,155 @@ __global__ void __launch_bounds__(256, MI == 8 ? 1 : (NJ == 8 ? 2 : 3)) tile_gem
     }
   }
 
+  // The epilogue.  Every global load it needs is issued before the first store, unconditionally and from clamped (valid)
+  // addresses, so that a wave waits for memory a few times and not once per tile: with one wave per SIMD nothing else
+  // covers such a wait.  Only the stores are predicated (tokens past T_live, rows past the matrix).
   const int q4 = (lane >> 4) * 4, tl = lane & 15;
-  const float *cbp = a.mr_in ? a.cb : a.bias;
-  const float *wgp = a.mr_in ? a.wg : nullptr;
-  // the product of weight row n0 + e and this lane's token, with the deferred norm and the bias applied
-  auto finish = [&](const f32x4 &c, const int n0, const float2 mr, float (&v)[4]) {  // mr = (mean - centre, rstd)
-    f32x4 wg = {0.f, 0.f, 0.f, 0.f}, cb = {0.f, 0.f, 0.f, 0.f};
-    if (wgp) wg = *(const f32x4 *)(wgp + n0);
-    if (cbp) cb = *(const f32x4 *)(cbp + n0);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) v[e] = mr.y * (c[e] - mr.x * wg[e]) + cb[e];
+  const int rtw = rt0 + wr * MI;  // the wave's first weight row tile
+  auto tok_of = [&](int j) { return (tt0 + wc * NJ + j) * 16 + tl; };
+  // first of this lane's four weight rows in row tile i, clamped into the per-row vectors (wg, cb, bias, gamma: N entries,
+  // gate/up interleaved: row_tiles * 16)
+  auto row_of = [&](int i) {
+    return EPI == EPI_SWIGLU ? min(rtw + i, a.row_tiles - 1) * 16 + q4 : min((rtw + i) * 16 + q4, a.N - 4);
   };
+  const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+  if constexpr (EPI == EPI_RESID) {
+    constexpr int JB = 1, NB = NJ / JB;  // the tiles of x come JB token tiles at a time, one batch ahead of its use
+    f32x4 bv[MI], gv[MI];
+    float cen[NJ];
 #pragma unroll
-  for (int j = 0; j < NJ; ++j) {
-    const int tok = (tt0 + wc * NJ + j) * 16 + tl;
-    const bool tok_live = tok < a.T_live;
-    if (EPI == EPI_SWIGLU) {
-      const float2 mr = a.mr_in ? make_float2(a.mr_in[tok][2], a.mr_in[tok][1]) : make_float2(0.f, 1.f);
+    for (int i = 0; i < MI; ++i) {
+      bv[i] = a.bias ? *(const f32x4 *)(a.bias + row_of(i)) : zero4;
+      gv[i] = a.g_out ? *(const f32x4 *)(a.g_out + row_of(i)) : zero4;
+    }
 #pragma unroll
-      for (int i = 0; i < MI; i += 2) {
-        const int rt = rt0 + wr * MI + i;  // gate tile; rt + 1 is the matching up tile
-        const int n0 = (rt >> 1) * 16 + q4;
-        if (tok_live && rt + 1 < a.row_tiles && n0 < a.N) {
-          float gt[4], up[4], u[4];
-          finish(acc[i][j], rt * 16 + q4, mr, gt);
-          finish(acc[i + 1][j], (rt + 1) * 16 + q4, mr, up);
+    for (int j = 0; j < NJ; ++j) cen[j] = a.g_out ? a.c_in[tok_of(j)][0] : 0.f;
+    f32x4 xb[2][JB][MI];
+    auto load_x = [&](f32x4(&dst)[JB][MI], int j0) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) u[e] = silu_f(gt[e]) * up[e];
-          store4_frag<OT, false>(a.act_out, tok, n0, a.out_k_blocks, u);
-        }
-      }
-    } else if (EPI == EPI_RESID) {
-      const float cen = a.g_out ? a.c_in[tok][0] : 0.f;
+      for (int jj = 0; jj < JB; ++jj)
 #pragma unroll
-      for (int band = 0; band < MI / 4; ++band) {  // 64 features: one partial sum each
-      float s1 = 0.f, s2 = 0.f;
+        for (int i = 0; i < MI; ++i)
+          dst[jj][i] = *(const f32x4 *)(a.x_resid + (size_t)tok_of(j0 + jj) * a.N + row_of(i));
+    };
+    auto finish_x = [&](const f32x4(&xs)[JB][MI], int j0) {
 #pragma unroll
-      for (int i = band * 4; i < band * 4 + 4; ++i) {
-        const int rt = rt0 + wr * MI + i;
-        const int n0 = rt * 16 + q4;
-        if (tok_live && rt < a.row_tiles && n0 < a.N) {
-          f32x4 *xp = (f32x4 *)(a.x_resid + (size_t)tok * a.N + n0);
-          const f32x4 x = *xp;
-          float v[4];
+      for (int jj = 0; jj < JB; ++jj) {
+        const int j = j0 + jj, tok = tok_of(j);
+        const bool tok_live = tok < a.T_live;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = x[e] + (acc[i][j][e] + (a.bias ? a.bias[n0 + e] : 0.f));
-          *xp = f32x4{v[0], v[1], v[2], v[3]};
-          if (a.g_out) {
-            const f32x4 g = *(const f32x4 *)(a.g_out + n0);
-            float y[4];
+        for (int band = 0; band < MI / 4; ++band) {  // 64 features: one partial sum each
+          float s1 = 0.f, s2 = 0.f;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const float t = v[e] - cen;
-              s1 += t, s2 += t * t;
-              y[e] = t * g[e];
+          for (int i = band * 4; i < band * 4 + 4; ++i) {
+            const int rt = rtw + i, n0 = rt * 16 + q4;
+            if (tok_live && rt < a.row_tiles && n0 < a.N) {
+              float v[4];
+#pragma unroll
+              for (int e = 0; e < 4; ++e) v[e] = xs[jj][i][e] + (acc[i][j][e] + bv[i][e]);
+              *(f32x4 *)(a.x_resid + (size_t)tok * a.N + n0) = f32x4{v[0], v[1], v[2], v[3]};
+              if (a.g_out) {
+                float y[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                  const float t = v[e] - cen[j];
+                  s1 += t, s2 += t * t;
+                  y[e] = t * gv[i][e];
+                }
+                store4_frag<OT, false>(a.norm_out, tok, n0, a.N / Elem<OT>::kFragK, y);
+                if (a.norm_out_lo) {
+                  float lo[4];
+#pragma unroll
+                  for (int e = 0; e < 4; ++e) lo[e] = y[e] - Elem<OT>::to_f32(Elem<OT>::from_f32(y[e]));
+                  store4_frag<OT, false>(a.norm_out_lo, tok, n0, a.N / Elem<OT>::kFragK, lo);
+                }
+              }
             }
-            store4_frag<OT, false>(a.norm_out, tok, n0, a.N / Elem<OT>::kFragK, y);
-            if (a.norm_out_lo) {
-              float lo[4];
-#pragma unroll
-              for (int e = 0; e < 4; ++e) lo[e] = y[e] - Elem<OT>::to_f32(Elem<OT>::from_f32(y[e]));
-              store4_frag<OT, false>(a.norm_out_lo, tok, n0, a.N / Elem<OT>::kFragK, lo);
-            }
+          }
+          if (a.g_out) {  // 64 features of this token
+            s1 += __shfl_xor(s1, 16), s2 += __shfl_xor(s2, 16);
+            s1 += __shfl_xor(s1, 32), s2 += __shfl_xor(s2, 32);
+            const int g = rtw / 4 + band;  // bands past the last 128-row block have no slot
+            if (lane < 16 && g < 2 * ((a.row_tiles + 7) / 8)) a.stat_out[(size_t)g * a.T + tok] = make_float2(s1, s2);
           }
         }
       }
-      if (a.g_out) {  // 64 features of this token
-        s1 += __shfl_xor(s1, 16), s2 += __shfl_xor(s2, 16);
-        s1 += __shfl_xor(s1, 32), s2 += __shfl_xor(s2, 32);
-        const int g = (rt0 + wr * MI) / 4 + band;  // bands past the last 128-row block have no slot
-        if (lane < 16 && g < 2 * ((a.row_tiles + 7) / 8)) a.stat_out[(size_t)g * a.T + tok] = make_float2(s1, s2);
-      }
-      }
-    } else {
-      const float2 mr = a.mr_in ? make_float2(a.mr_in[tok][2], a.mr_in[tok][1]) : make_float2(0.f, 1.f);
+    };
+    constexpr bool AHEAD = !(MI == 4 && NJ == 4);  // (three blocks per compute unit: their registers do not hold a second batch)
+    load_x(xb[0], 0);
 #pragma unroll
-      for (int i = 0; i < MI; ++i) {
-        const int rt = rt0 + wr * MI + i;
-        const int n0 = rt * 16 + q4;
-        if (tok_live && rt < a.row_tiles && n0 < a.N) {
-          float v[4];
-          finish(acc[i][j], n0, mr, v);
-          if (EPI == EPI_F32) {
-            const f32x4 o = {v[0], v[1], v[2], v[3]};
-            const int HD = a.kv_Hs * a.kv_Dh;
-            if (a.k_cache && n0 >= HD) {  // a key or value piece: into the cache row of (sequence, position), not the q|k|v buffer
-              const int is_v = n0 >= 2 * HD, f = n0 - (1 + is_v) * HD, hh = f / a.kv_Dh, dim = f - hh * a.kv_Dh;
-              const int b = tok / a.kv_S, pos = tok - b * a.kv_S;
-              char *row = (is_v ? a.v_cache : a.k_cache) + b * a.kv_row_stride + hh * a.kv_head_stride;
-              const size_t e = (size_t)pos * a.kv_Dh + dim;
-              if (a.kv_dtype == SS_DTYPE_F16) store4_cache<f16_t>((f16_t *)row + e, o);
-              else if (a.kv_dtype == SS_DTYPE_BF16) store4_cache<bf16_t>((bf16_t *)row + e, o);
-              else store4_cache<float>((float *)row + e, o);
-            } else {
-              *(f32x4 *)(a.out_f32 + (size_t)tok * a.ld_out + n0) = o;
+    for (int jb = 0; jb < NB; ++jb) {
+      if (AHEAD && jb + 1 < NB) load_x(xb[(jb + 1) & 1], (jb + 1) * JB);
+      finish_x(xb[AHEAD ? (jb & 1) : 0], jb * JB);
+      if (!AHEAD && jb + 1 < NB) load_x(xb[0], (jb + 1) * JB);
+    }
+  } else {
+    // deferred norm and bias: rstd * (acc - (mean - centre) * wg[n]) + cb[n]
+    const float *cbp = a.mr_in ? a.cb : a.bias;
+    f32x4 wgv[MI], cbv[MI];
+    float2 mrv[NJ];  // (mean - centre, rstd)
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+      wgv[i] = a.mr_in && a.wg ? *(const f32x4 *)(a.wg + row_of(i)) : zero4;
+      cbv[i] = cbp ? *(const f32x4 *)(cbp + row_of(i)) : zero4;
+    }
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      if (a.mr_in) {
+        const f32x4 m = a.mr_in[tok_of(j)];
+        mrv[j] = make_float2(m[2], m[1]);
+      } else {
+        mrv[j] = make_float2(0.f, 1.f);
+      }
+    }
+    auto finish = [&](int i, int j, float(&v)[4]) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = mrv[j].y * (acc[i][j][e] - mrv[j].x * wgv[i][e]) + cbv[i][e];
+    };
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int tok = tok_of(j);
+      const bool tok_live = tok < a.T_live;
+      if constexpr (EPI == EPI_SWIGLU) {
+#pragma unroll
+        for (int i = 0; i < MI; i += 2) {
+          const int rt = rtw + i;  // gate tile; rt + 1 is the matching up tile
+          const int n0 = (rt >> 1) * 16 + q4;
+          if (tok_live && rt + 1 < a.row_tiles && n0 < a.N) {
+            float gt[4], up[4], u[4];
+            finish(i, j, gt);
+            finish(i + 1, j, up);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) u[e] = silu_f(gt[e]) * up[e];
+            store4_frag<OT, false>(a.act_out, tok, n0, a.out_k_blocks, u);
+          }
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+          const int rt = rtw + i, n0 = rt * 16 + q4;
+          if (tok_live && rt < a.row_tiles && n0 < a.N) {
+            float v[4];
+            finish(i, j, v);
+            if constexpr (EPI == EPI_F32) {
+              const f32x4 o = {v[0], v[1], v[2], v[3]};
+              const int HD = a.kv_Hs * a.kv_Dh;
+              if (a.k_cache && n0 >= HD) {  // a key or value piece: into the cache row of (sequence, position), not the q|k|v buffer
+                const int is_v = n0 >= 2 * HD, f = n0 - (1 + is_v) * HD, hh = f / a.kv_Dh, dim = f - hh * a.kv_Dh;
+                const int b = tok / a.kv_S, pos = tok - b * a.kv_S;
+                char *row = (is_v ? a.v_cache : a.k_cache) + b * a.kv_row_stride + hh * a.kv_head_stride;
+                const size_t e = (size_t)pos * a.kv_Dh + dim;
+                if (a.kv_dtype == SS_DTYPE_F16) store4_cache<f16_t>((f16_t *)row + e, o);
+                else if (a.kv_dtype == SS_DTYPE_BF16) store4_cache<bf16_t>((bf16_t *)row + e, o);
+                else store4_cache<float>((float *)row + e, o);
+              } else {
+                *(f32x4 *)(a.out_f32 + (size_t)tok * a.ld_out + n0) = o;
+              }
+            } else {  // EPI_ACT
+              const float w[4] = {act_apply(a.act_kind, v[0]), act_apply(a.act_kind, v[1]), act_apply(a.act_kind, v[2]),
+                                  act_apply(a.act_kind, v[3])};
+              store4_frag<OT, false>(a.act_out, tok, n0, a.out_k_blocks, w);
             }
-          } else {  // EPI_ACT
-            const float w[4] = {act_apply(a.act_kind, v[0]), act_apply(a.act_kind, v[1]), act_apply(a.act_kind, v[2]),
-                                act_apply(a.act_kind, v[3])};
-            store4_frag<OT, false>(a.act_out, tok, n0, a.out_k_blocks, w);
           }
         }
       }
@@ -380,7 +491,7 @@ static std::atomic<int> g_forced_row_tiles{0};
 
 template <typename T, int EPI, int NJ, int MI>
 static ss_status launch_one(const TileGemmArgs &a, dim3 grid, hipStream_t st) {
-  constexpr size_t lds_bytes = (size_t)kTileGemmRing * (2 * MI + 2 * NJ) * 1024;  // 48, 72 or 96 KiB: above the 64 KiB that need no opt-in
+  constexpr size_t lds_bytes = (size_t)(MI == 8 ? kBigBlockRing : kTileGemmRing) * (2 * MI + 2 * NJ) * 1024;  // 48, 72 or 128 KiB: above the 64 KiB that need no opt-in
   static std::once_flag once;
   static hipError_t attr = hipSuccess;
   std::call_once(once, [] {
@@ -393,7 +504,8 @@ static ss_status launch_one(const TileGemmArgs &a, dim3 grid, hipStream_t st) {
 
 ss_status launch_tile_gemm(int dtype, int epi, TileGemmArgs a, hipStream_t st) {
   if (a.T < 256 || a.T % 256) SS_FAIL(SS_EINVAL, "prefill GEMM: token count %d is not a multiple of 256", a.T);
-  if (a.row_tiles < 1 || a.k_blocks < 1 || a.N % 4) SS_FAIL(SS_EINVAL, "prefill GEMM: bad shape");
+  if (a.row_tiles < 1 || a.k_blocks < 1 || a.N < 4 || a.N % 4 || a.N > a.row_tiles * 16) SS_FAIL(SS_EINVAL, "prefill GEMM: bad shape");
+  if (epi == EPI_SWIGLU && 2 * a.N != a.row_tiles * 16) SS_FAIL(SS_EINVAL, "prefill GEMM: gate/up tiles must pair up");
   if ((epi == EPI_F32 && (a.ld_out % 4)) || epi == EPI_LOGITS) SS_FAIL(SS_EINVAL, "prefill GEMM: bad epilogue");
   if (a.k_cache && (epi != EPI_F32 || !a.v_cache || a.kv_S < 1 || a.kv_Dh % 4 || a.N != 3 * a.kv_Hs * a.kv_Dh ||
                     (a.kv_dtype != SS_DTYPE_F16 && a.kv_dtype != SS_DTYPE_BF16 && a.kv_dtype != SS_DTYPE_F32)))
