@@ -67,6 +67,16 @@ template <int N, typename F>  // f(integral_constant<int, 0>) ... f(integral_con
 __device__ __forceinline__ void static_for(F &&f) {
   static_for_impl(std::make_integer_sequence<int, N>(), f);
 }
+// The 256-row block's schedule: what follows product j of row i (slot i * 8 + j) beside an LDS read or the barrier:
+// 0..7 = load r of the stage four ahead, 8..15 = step load r's pointer to the next k, -1 = nothing.  The sixteen of them
+// take the slots from (2, 6) on that hold no LDS read, a load and its step next to each other.
+constexpr int big_block_extra(int slot) {
+  constexpr int at[16] = {2 * 8 + 6, 2 * 8 + 7, 3 * 8 + 5, 3 * 8 + 6, 3 * 8 + 7, 4 * 8 + 1, 4 * 8 + 2, 4 * 8 + 3,
+                          4 * 8 + 4, 4 * 8 + 5, 4 * 8 + 6, 4 * 8 + 7, 5 * 8 + 1, 5 * 8 + 2, 5 * 8 + 3, 5 * 8 + 4};
+  for (int n = 0; n < 16; ++n)
+    if (at[n] == slot) return n % 2 == 0 ? n / 2 : 8 + n / 2;
+  return -1;
+}
 // s_waitcnt vmcnt(8 * stages), stages 0..3 (wave-uniform)
 __device__ __forceinline__ void wait_stages_in_flight(int stages) {
   if (stages >= 3) wait_vmcnt<24>();
@@ -185,19 +195,27 @@ __global__ void __launch_bounds__(256, MI == 8 ? 1 : (NJ == 8 ? 2 : 3)) tile_gem
     constexpr int R = kBigBlockRing;
     constexpr uint32_t STAGE_BYTES = STAGE * 16;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    const u32x4 *src[LPS];  // this lane's piece of the wave's fragments at k = 0: weight tiles, then activation tiles
+    // Running pointers: this lane's piece of the fragment that each of the wave's eight loads brings next (weight tiles,
+    // then activation tiles).  A load and the step of its pointer to the next k sit in different slots of the schedule.
+    const u32x4 *gp[LPS];
 #pragma unroll
-    for (int r = 0; r < BMT / 4; ++r) src[r] = W + (size_t)min(rt0 + wave_u + 4 * r, a.row_tiles - 1) * a.k_blocks * 64 + lane;
+    for (int r = 0; r < BMT / 4; ++r) gp[r] = W + (size_t)min(rt0 + wave_u + 4 * r, a.row_tiles - 1) * a.k_blocks * 64 + lane;
 #pragma unroll
-    for (int r = 0; r < BTT / 4; ++r) src[BMT / 4 + r] = A + (size_t)(tt0 + wave_u + 4 * r) * a.k_blocks * 64 + lane;
-    const ptrdiff_t lo_delta = A_lo ? A_lo - A : 0;
-    auto issue_piece = [&](int stage, int r) {  // r: 0 .. LPS - 1
-      const bool second = stage >= a.k_blocks;
-      const int k = second ? stage - a.k_blocks : stage;
-      const ptrdiff_t off = (ptrdiff_t)k * 64 + ((second && r >= BMT / 4) ? lo_delta : 0);
+    for (int r = 0; r < BTT / 4; ++r) gp[BMT / 4 + r] = A + (size_t)(tt0 + wave_u + 4 * r) * a.k_blocks * 64 + lane;
+    auto issue_piece = [&](int stage, int r) {  // r: 0 .. LPS - 1; stage: the one gp[r] stands at
       u32x4 *dst = lds + (stage % R) * STAGE + (wave_u + 4 * r) * 64;  // (activation tiles follow the BMT weight tiles)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[r] + off),
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gp[r],
                                        (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
+    };
+    const uint64_t k_step = 1024;  // bytes from one k fragment to the next
+    auto step = [&](int r) {  // (asm: the addition stays in its slot of the schedule)
+      asm volatile("v_lshl_add_u64 %0, %0, 0, %1" : "+v"(gp[r]) : "s"(k_step));
+    };
+    // before the loads of stage k_blocks (two-part operand): the weights start over, the activations move to the low parts
+    auto second_pass = [&]() {
+      const ptrdiff_t back = (ptrdiff_t)a.k_blocks * 64;
+#pragma unroll
+      for (int r = 0; r < LPS; ++r) gp[r] += (r < BMT / 4 ? 0 : A_lo - A) - back;
     };
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)lds;
     const uint32_t w_at = lds0 + (uint32_t)((wr * MI) * 64 + lane) * 16;         // + 1024 per row tile
@@ -207,8 +225,9 @@ __global__ void __launch_bounds__(256, MI == 8 ? 1 : (NJ == 8 ? 2 : 3)) tile_gem
 #pragma unroll
     for (int s = 0; s < R; ++s)
       if (s < n_stages) {
+        if (s == a.k_blocks) second_pass();
 #pragma unroll
-        for (int r = 0; r < LPS; ++r) issue_piece(s, r);
+        for (int r = 0; r < LPS; ++r) issue_piece(s, r), step(r);
       }
     wait_stages_in_flight(min(R, n_stages) - 1);
     asm volatile("s_barrier" ::: "memory");
@@ -224,7 +243,11 @@ __global__ void __launch_bounds__(256, MI == 8 ? 1 : (NJ == 8 ? 2 : 3)) tile_gem
       // Order of the reads of stage s + 1: a0 a1 w0 w1 a2 a3 | w2 a4 a5 a6 a7 | w3 | w4 | w5 | w6 | w7 (w_i only after
       // row i).  Row 0 of the next stage needs w0 and every a_j: all but the last five reads.  (Behind the last
       // stage the reads bring whatever the ring's next buffer holds, into registers nobody uses again.)
+      if (load && s + R == a.k_blocks) second_pass();
       wait_lds<5>();
+      // Between two products there is room for about three other instructions (a wave issues one every four cycles,
+      // a product keeps the matrix core busy for sixteen), so everything else is spread thinly: slot (i, j) is what
+      // follows product j of row i.
       static_for<MI * NJ>([&](auto IJ) {
         constexpr int i = decltype(IJ)::value / NJ, j = decltype(IJ)::value % NJ;
         mma_f16_pinned<FIRST>(acc[i][j], wf[i], cur[j]);
@@ -237,6 +260,7 @@ __global__ void __launch_bounds__(256, MI == 8 ? 1 : (NJ == 8 ? 2 : 3)) tile_gem
             wait_lds<0>();
           }
         }
+        // LDS reads of stage s + 1
         if constexpr (i == 2 && j == 0) lds_read_async<0 * 1024>(nxt[0], a_rd);
         if constexpr (i == 2 && j == 1) lds_read_async<1 * 1024>(nxt[1], a_rd);
         if constexpr (i == 2 && j == 2) lds_read_async<0 * 1024>(wf[0], w_rd);
@@ -250,12 +274,13 @@ __global__ void __launch_bounds__(256, MI == 8 ? 1 : (NJ == 8 ? 2 : 3)) tile_gem
         if constexpr (i == 3 && j == 4) lds_read_async<7 * 1024>(nxt[7], a_rd);
         if constexpr (i >= 4 && j == 0) lds_read_async<(i - 1) * 1024>(wf[i - 1], w_rd);
         if constexpr (i == MI - 1 && j == NJ - 1) lds_read_async<(MI - 1) * 1024>(wf[MI - 1], w_rd);
-        // the loads of stage s + R: behind (2,6) (2,7) (3,6) (3,7) (4,3) (4,6) (5,3) (5,6)
-        if constexpr ((i == 2 || i == 3) && j >= 6) {
-          if (load) issue_piece(s + R, (i - 2) * 2 + (j - 6));
-        }
-        if constexpr ((i == 4 || i == 5) && (j == 3 || j == 6)) {
-          if (load) issue_piece(s + R, 4 + (i - 4) * 2 + (j == 6));
+        // the loads of stage s + R, and the steps of their pointers, one per slot
+        constexpr int x = big_block_extra(i * NJ + j);
+        if constexpr (x >= 0) {
+          if (load) {
+            if constexpr (x < LPS) issue_piece(s + R, x);
+            else step(x - LPS);
+          }
         }
         __builtin_amdgcn_sched_barrier(0);
       });
