@@ -344,6 +344,8 @@ __global__ void __launch_bounds__(256, MI == 8 ? 1 : (NJ == 8 ? 2 : 3)) tile_gem
 #pragma unroll
     for (int j = 0; j < NJ; ++j) cen[j] = a.g_out ? a.c_in[tok_of(j)][0] : 0.f;
     f32x4 xb[2][JB][MI];
+    constexpr int SB = MI == 8 ? 1 : 4;  // token tiles whose partial sums are exchanged together (what the registers hold)
+    float s1v[SB][MI / 4], s2v[SB][MI / 4];  // this lane's share of the partial sums: token tile j, band of 64 features
     auto load_x = [&](f32x4(&dst)[JB][MI], int j0) {
 #pragma unroll
       for (int jj = 0; jj < JB; ++jj)
@@ -385,12 +387,7 @@ __global__ void __launch_bounds__(256, MI == 8 ? 1 : (NJ == 8 ? 2 : 3)) tile_gem
               }
             }
           }
-          if (a.g_out) {  // 64 features of this token
-            s1 += __shfl_xor(s1, 16), s2 += __shfl_xor(s2, 16);
-            s1 += __shfl_xor(s1, 32), s2 += __shfl_xor(s2, 32);
-            const int g = rtw / 4 + band;  // bands past the last 128-row block have no slot
-            if (lane < 16 && g < 2 * ((a.row_tiles + 7) / 8)) a.stat_out[(size_t)g * a.T + tok] = make_float2(s1, s2);
-          }
+          s1v[j % SB][band] = s1, s2v[j % SB][band] = s2;
         }
       }
     };
@@ -401,6 +398,19 @@ __global__ void __launch_bounds__(256, MI == 8 ? 1 : (NJ == 8 ? 2 : 3)) tile_gem
       if (AHEAD && jb + 1 < NB) load_x(xb[(jb + 1) & 1], (jb + 1) * JB);
       finish_x(xb[AHEAD ? (jb & 1) : 0], jb * JB);
       if (!AHEAD && jb + 1 < NB) load_x(xb[0], (jb + 1) * JB);
+      static_assert(JB == 1 && NJ % SB == 0, "the exchange below takes token tiles SB at a time");
+      if (a.g_out && jb % SB == SB - 1) {  // the four lanes of a token add up, the exchanges of SB token tiles under way together
+#pragma unroll
+        for (int jj = 0; jj < SB; ++jj)
+#pragma unroll
+          for (int band = 0; band < MI / 4; ++band) {
+            float s1 = s1v[jj][band], s2 = s2v[jj][band];
+            s1 += __shfl_xor(s1, 16), s2 += __shfl_xor(s2, 16);
+            s1 += __shfl_xor(s1, 32), s2 += __shfl_xor(s2, 32);
+            const int g = rtw / 4 + band;  // bands past the last 128-row block have no slot
+            if (lane < 16 && g < 2 * ((a.row_tiles + 7) / 8)) a.stat_out[(size_t)g * a.T + tok_of(jb - (SB - 1) + jj)] = make_float2(s1, s2);
+          }
+      }
     }
   } else {
     // deferred norm and bias: rstd * (acc - (mean - centre) * wg[n]) + cb[n]
@@ -439,7 +449,7 @@ __global__ void __launch_bounds__(256, MI == 8 ? 1 : (NJ == 8 ? 2 : 3)) tile_gem
             finish(i, j, gt);
             finish(i + 1, j, up);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) u[e] = silu_f(gt[e]) * up[e];
+            for (int e = 0; e < 4; ++e) u[e] = silu_rcp(gt[e]) * up[e];
             store4_frag<OT, false>(a.act_out, tok, n0, a.out_k_blocks, u);
           }
         }

@@ -32,6 +32,8 @@ __device__ __forceinline__ float act_apply(int kind, float h) {
   return fmaxf(h, 0.0f);  // SS_ACT_RELU
 }
 __device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)); }
+// the same with the hardware's reciprocal (1 ulp) in place of the division: for epilogues that are bound by instruction count
+__device__ __forceinline__ float silu_rcp(float g) { return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)); }
 
 // Four consecutive activations (k a multiple of 4) into an operand buffer, as whole 32-bit words.
 // DEV: device-scope (write-through) stores, for buffers another block of the same launch reads.
