@@ -89,7 +89,7 @@ __device__ __forceinline__ void wait_stages_in_flight(int stages) {
 // Either way a fragment is 64 lanes x 16 bytes, so the loop is the same.
 constexpr int kTileGemmRing = 3;  // LDS stages (128-row blocks)
 constexpr int kBigBlockRing = 4;  // LDS stages of the 256-row block
-constexpr int kBigBlockRounds = 4;  // 256-row blocks where there are at least this many per compute unit
+constexpr int kBigBlockRounds = 2;  // 256-row blocks where there are at least this many per compute unit
 
 // NJ: token tiles of a wave, 8 (block of 256 tokens) or 4 (128 tokens); MI: weight row tiles of a wave, 4 (block of 128 rows;
 // two blocks per compute unit with 256 tokens, three with 128) or 8 (256 rows x 256 tokens, one block per compute unit and one
