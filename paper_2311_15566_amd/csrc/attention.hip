@@ -78,8 +78,9 @@ __global__ void __launch_bounds__(256) prefill_kv_write(PrefillAttnArgs a) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const float2 cs = tab[i];
-      const float ql = qlo[i] * cs.x - qhi[i] * cs.y, qh = qlo[i] * cs.y + qhi[i] * cs.x;
-      const float kl = klo[i] * cs.x - khi[i] * cs.y, kh = klo[i] * cs.y + khi[i] * cs.x;
+      float ql, qh, kl, kh;
+      rope_rotate(qlo[i], qhi[i], cs, ql, qh);
+      rope_rotate(klo[i], khi[i], cs, kl, kh);
       qlo[i] = ql, qhi[i] = qh, klo[i] = kl, khi[i] = kh;
     }
     *(f32x4 *)(row + e0) = qlo;

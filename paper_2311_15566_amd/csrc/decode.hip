@@ -713,11 +713,15 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, c
       normed(a, s->wg_qkv[l], s->cb_qkv[l]);
       if (abuf_lo) a.act_lo = abuf_lo, a.lo_row_begin = 0, a.lo_row_end = 2 * L.Hs * L.Dh / 16;  // the q and k rows
       a.out_f32 = (float *)(s->ws + L.ws_qkv), a.ld_out = L.qkv_n;
+      // The GEMM's epilogue writes the cache rows itself, rotating q and k first in a model with rotary positions where
+      // its block shape holds whole heads per wave; otherwise a kernel of its own rotates and writes behind it.
       const bool rope_model = m.pos == SS_POS_ROPE;
-      if (!rope_model) {  // nothing to rotate: the GEMM's epilogue writes the cache rows itself
+      const bool gemm_rotates = rope_model && tile_gemm_rotates(dt, a, L.Dh);
+      if (!rope_model || gemm_rotates) {
         a.k_cache = s->kv_ptr(l, 0), a.v_cache = s->kv_ptr(l, 1);
         a.kv_row_stride = s->kv_row_stride(), a.kv_head_stride = s->kv_head_stride();
         a.kv_S = S, a.kv_Hs = L.Hs, a.kv_Dh = L.Dh, a.kv_dtype = s->m.kv_dtype;
+        if (gemm_rotates) a.rope = s->rope;
       }
       SS_TRY(launch_tile_gemm(dt, EPI_F32, a, st));
       PrefillAttnArgs p = {};
@@ -728,7 +732,7 @@ ss_status run_prefill(Shard *const *group, int n_group, const int32_t *tokens, c
       p.o_out = s->ws + L.ws_o;
       p.B = B, p.S = S, p.Hs = L.Hs, p.Dh = L.Dh, p.Smax = L.Smax, p.kv_dtype = s->m.kv_dtype;
       p.vt = s->ws + L.ws_vt, p.s_pad = (int)align_up((size_t)S, 64);
-      if (rope_model) SS_TRY(launch_prefill_kv_write(dt, p, st));  // rotates q and k, writes the cache rows
+      if (rope_model && !gemm_rotates) SS_TRY(launch_prefill_kv_write(dt, p, st));  // rotates q and k, writes the cache rows
       SS_TRY(launch_prefill_attn(dt, p, st));
     }
     stat_groups = 2 * ceil_div(d / 16, 8);  // from here on: one partial per 64-feature band of the residual GEMMs

@@ -435,6 +435,74 @@ __global__ void __launch_bounds__(256, MI == 8 ? 1 : (NJ == 8 ? 2 : 3)) tile_gem
 #pragma unroll
       for (int e = 0; e < 4; ++e) v[e] = mrv[j].y * (acc[i][j][e] - mrv[j].x * wgv[i][e]) + cbv[i][e];
     };
+    if constexpr (EPI == EPI_F32) {
+      if (a.rope) {
+        // q|k|v of a model with rotary positions: the wave holds whole heads, row tile i (low half of a head) and row
+        // tile i + half_tiles (high half) pair up in the same lane.  q is rotated and stored, k rotated and written
+        // to the cache, v written to the cache.  The (cos, sin) of a token tile's pairs are loaded one tile ahead.
+        auto rotary = [&](auto half_tiles) {
+          constexpr int HT2 = decltype(half_tiles)::value;  // row tiles per half head
+          constexpr int NLO = MI / 2;                       // low-half tiles of the wave
+          auto lo_tile = [&](int n) { return (n / HT2) * 2 * HT2 + n % HT2; };
+          const int HD = a.kv_Hs * a.kv_Dh, HALF = a.kv_Dh / 2;
+          f32x4 cs[2][NLO][2];  // [buffer][low tile][first two pairs, last two pairs] as (cos, sin, cos, sin)
+          auto load_cs = [&](f32x4(&dst)[NLO][2], int j) {
+            const int tok = tok_of(j), pos = tok - (tok / a.kv_S) * a.kv_S;
+#pragma unroll
+            for (int n = 0; n < NLO; ++n) {
+              const int n0 = min((rtw + lo_tile(n)) * 16 + q4, a.N - 4), f = n0 % HD, dim = (f % a.kv_Dh) % HALF;
+              const f32x4 *p = (const f32x4 *)(a.rope + (size_t)pos * HALF + dim);
+              dst[n][0] = p[0], dst[n][1] = p[1];
+            }
+          };
+          constexpr bool AHEAD = !(MI == 4 && NJ == 4);  // (three blocks per compute unit: no registers for a second set)
+          load_cs(cs[0], 0);
+#pragma unroll
+          for (int j = 0; j < NJ; ++j) {
+            if (AHEAD && j + 1 < NJ) load_cs(cs[(j + 1) & 1], j + 1);
+            if (!AHEAD && j > 0) load_cs(cs[0], j);
+            const int tok = tok_of(j);
+            const bool tok_live = tok < a.T_live;
+            const int b = tok / a.kv_S, pos = tok - b * a.kv_S;
+#pragma unroll
+            for (int n = 0; n < NLO; ++n) {
+              const int i = lo_tile(n), rt = rtw + i, n0 = rt * 16 + q4;
+              if (tok_live && rt + HT2 < a.row_tiles && n0 + HT2 * 16 < a.N) {
+                float lo[4], hi[4];
+                finish(i, j, lo);
+                finish(i + HT2, j, hi);
+                const int part = n0 / HD, f = n0 - part * HD, hh = f / a.kv_Dh, dim = f - hh * a.kv_Dh;  // part: 0 q, 1 k, 2 v
+                if (part < 2) {
+                  const f32x4 c01 = cs[AHEAD ? (j & 1) : 0][n][0], c23 = cs[AHEAD ? (j & 1) : 0][n][1];
+                  rope_rotate(lo[0], hi[0], make_float2(c01[0], c01[1]), lo[0], hi[0]);
+                  rope_rotate(lo[1], hi[1], make_float2(c01[2], c01[3]), lo[1], hi[1]);
+                  rope_rotate(lo[2], hi[2], make_float2(c23[0], c23[1]), lo[2], hi[2]);
+                  rope_rotate(lo[3], hi[3], make_float2(c23[2], c23[3]), lo[3], hi[3]);
+                }
+                const f32x4 olo = {lo[0], lo[1], lo[2], lo[3]}, ohi = {hi[0], hi[1], hi[2], hi[3]};
+                if (part == 0) {
+                  float *q = a.out_f32 + (size_t)tok * a.ld_out + n0;
+                  *(f32x4 *)q = olo;
+                  *(f32x4 *)(q + HALF) = ohi;
+                } else {
+                  char *row = (part == 2 ? a.v_cache : a.k_cache) + b * a.kv_row_stride + hh * a.kv_head_stride;
+                  const size_t e = (size_t)pos * a.kv_Dh + dim;
+                  if (a.kv_dtype == SS_DTYPE_F16) store4_cache<f16_t>((f16_t *)row + e, olo), store4_cache<f16_t>((f16_t *)row + e + HALF, ohi);
+                  else if (a.kv_dtype == SS_DTYPE_BF16) store4_cache<bf16_t>((bf16_t *)row + e, olo), store4_cache<bf16_t>((bf16_t *)row + e + HALF, ohi);
+                  else store4_cache<float>((float *)row + e, olo), store4_cache<float>((float *)row + e + HALF, ohi);
+                }
+              }
+            }
+          }
+        };
+        if (a.kv_Dh == 128) {
+          if constexpr (MI == 8) rotary(std::integral_constant<int, 4>());
+        } else {
+          rotary(std::integral_constant<int, 2>());
+        }
+        return;
+      }
+    }
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
       const int tok = tok_of(j);
@@ -537,6 +605,31 @@ static ss_status launch_one(const TileGemmArgs &a, dim3 grid, hipStream_t st) {
   return SS_OK;
 }
 
+// Sets a.tok_tiles and a.wave_row_tiles.
+// Token block: measured on every GEMM shape of the GPT-20B, LLaMA-30B and OPT-66B shards, 256-token
+// blocks win by 3-9 % where the output has a few rounds of them (16384 tokens: fewer LDS and L2
+// reads per flop), 128-token blocks by 7-17 % on the 4096-token shapes (more blocks to spread over
+// the compute units) and by 8 % on a short reduction (1152), where a block is mostly epilogue.
+// Row block: 256 rows x 256 tokens (one wave per SIMD) where the output has a few rounds of such blocks too: 12-17 % faster
+// than 128 x 256 on the LLaMA-30B shard's matrices, 10 % on the OPT-66B shard's.
+static void choose_block(int dtype, TileGemmArgs &a) {
+  if (g_forced_tok_tiles.load()) a.tok_tiles = g_forced_tok_tiles.load(), a.wave_row_tiles = g_forced_row_tiles.load();
+  if (a.tok_tiles != 4 && a.tok_tiles != 8) {
+    const long blocks128 = (long)ceil_div(a.row_tiles, 8) * (a.T / 128);
+    a.tok_tiles = (blocks128 >= 2048 && a.k_blocks >= 64) ? 8 : 4;
+    a.wave_row_tiles = (blocks128 >= 4 * kBigBlockRounds * 256 && a.k_blocks >= 64) ? 8 : 4;
+  }
+  if (a.wave_row_tiles != 8 || a.tok_tiles != 8 || dtype != SS_DTYPE_BF16 || (a.act_lo && (a.lo_row_begin % 16 || a.lo_row_end % 16)))
+    a.wave_row_tiles = 4;
+}
+
+bool tile_gemm_rotates(int dtype, const TileGemmArgs &args, int head_dim) {
+  TileGemmArgs a = args;
+  if (a.T < 256 || a.T % 256 || a.row_tiles < 1 || a.k_blocks < 1) return false;
+  choose_block(dtype, a);
+  return (head_dim == 64 || head_dim == 128) && (a.wave_row_tiles * 16) % head_dim == 0;
+}
+
 ss_status launch_tile_gemm(int dtype, int epi, TileGemmArgs a, hipStream_t st) {
   if (a.T < 256 || a.T % 256) SS_FAIL(SS_EINVAL, "prefill GEMM: token count %d is not a multiple of 256", a.T);
   if (a.row_tiles < 1 || a.k_blocks < 1 || a.N < 4 || a.N % 4 || a.N > a.row_tiles * 16) SS_FAIL(SS_EINVAL, "prefill GEMM: bad shape");
@@ -553,19 +646,9 @@ ss_status launch_tile_gemm(int dtype, int epi, TileGemmArgs a, hipStream_t st) {
     if (!a.norm_out || !a.stat_out || !a.c_in || a.N % fk || a.N != a.row_tiles * 16)
       SS_FAIL(SS_EINVAL, "prefill GEMM: bad next-operand arguments");
   }
-  // Token block: measured on every GEMM shape of the GPT-20B, LLaMA-30B and OPT-66B shards, 256-token
-  // blocks win by 3-9 % where the output has a few rounds of them (16384 tokens: fewer LDS and L2
-  // reads per flop), 128-token blocks by 7-17 % on the 4096-token shapes (more blocks to spread over
-  // the compute units) and by 8 % on a short reduction (1152), where a block is mostly epilogue.
-  // Row block: 256 rows x 256 tokens (one wave per SIMD) where the output has several rounds of such blocks too.
-  if (g_forced_tok_tiles.load()) a.tok_tiles = g_forced_tok_tiles.load(), a.wave_row_tiles = g_forced_row_tiles.load();
-  if (a.tok_tiles != 4 && a.tok_tiles != 8) {
-    const long blocks128 = (long)ceil_div(a.row_tiles, 8) * (a.T / 128);
-    a.tok_tiles = (blocks128 >= 2048 && a.k_blocks >= 64) ? 8 : 4;
-    a.wave_row_tiles = (blocks128 >= 4 * kBigBlockRounds * 256 && a.k_blocks >= 64) ? 8 : 4;
-  }
-  if (a.wave_row_tiles != 8 || a.tok_tiles != 8 || dtype != SS_DTYPE_BF16 || (a.act_lo && (a.lo_row_begin % 16 || a.lo_row_end % 16)))
-    a.wave_row_tiles = 4;
+  choose_block(dtype, a);
+  if (a.rope && (!a.k_cache || (a.wave_row_tiles * 16) % a.kv_Dh || (a.kv_Dh != 64 && a.kv_Dh != 128)))
+    SS_FAIL(SS_EINVAL, "prefill GEMM: this block shape cannot rotate heads of %d dimensions", a.kv_Dh);
   a.n_row_blocks = ceil_div(a.row_tiles, 2 * a.wave_row_tiles);
   dim3 grid(a.n_row_blocks * (a.T / (a.tok_tiles * 32)));
 #define SS_LAUNCH(TT, EPI)                                                                                            \

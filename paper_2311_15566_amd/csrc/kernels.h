@@ -115,9 +115,12 @@ struct TileGemmArgs {
   const float *cb;    // [row_tiles * 16] folded beta and bias, or the plain bias, or NULL
   float *out_f32;     // EPI_F32: [T][ld_out]
   int ld_out;
-  // EPI_F32 of a fused q|k|v matrix without rotary positions (k_cache != NULL): the k and v columns go straight
-  // into the cache rows of token t = b * kv_S + pos, rounded as the cache stores them; only q goes to out_f32
+  // EPI_F32 of a fused q|k|v matrix (k_cache != NULL): the k and v columns go straight into the cache rows of token
+  // t = b * kv_S + pos, rounded as the cache stores them; only q goes to out_f32.  With rotary positions (rope != NULL:
+  // [position][kv_Dh / 2] (cos, sin)) q and k are rotated first; that needs both halves of a head in one wave, i.e. a
+  // block shape for which tile_gemm_rotates() says yes: ask before setting rope
   char *k_cache, *v_cache;  // this layer's planes
+  const float2 *rope;
   size_t kv_row_stride, kv_head_stride;  // bytes
   int kv_S, kv_Hs, kv_Dh, kv_dtype;
   float *x_resid;     // EPI_RESID: [T][N]
@@ -134,6 +137,8 @@ struct TileGemmArgs {
   int wave_row_tiles; // weight row tiles per wave, 4 or 8: blocks of 128 or 256 rows (256 only with 256 tokens)
 };
 ss_status launch_tile_gemm(int dtype, int epi, TileGemmArgs a, hipStream_t st);
+// whether the block shape that launch_tile_gemm would take for `a` (without cache arguments) can rotate q and k in its epilogue
+bool tile_gemm_rotates(int dtype, const TileGemmArgs &a, int head_dim);
 // mr[t] <- (mean, rstd, mean - c, 0) from `groups` partial (sum (x-c), sum (x-c)^2) pairs laid out
 // [groups][T], with c = mr[t].x on entry
 ss_status launch_row_stats(const float2 *part, int groups, int T, int norm_dim, int rms, float eps, f32x4 *mr,

@@ -31,6 +31,13 @@ __device__ __forceinline__ float act_apply(int kind, float h) {
   if (kind == SS_ACT_GELU_TANH) return 0.5f * h * (1.0f + tanhf(0.7978845608028654f * (h + 0.044715f * h * h * h)));
   return fmaxf(h, 0.0f);  // SS_ACT_RELU
 }
+// Rotary position embedding of one (low, high) pair of a head's dimensions, cs = (cos, sin) of the position's angle for
+// that pair.  The order of the operations is spelled out: the kernels of the initial phase that rotate (the q|k|v GEMM's
+// epilogue, or prefill_kv_write behind a GEMM that cannot) must agree bit for bit.
+__device__ __forceinline__ void rope_rotate(float lo, float hi, float2 cs, float &out_lo, float &out_hi) {
+  out_lo = __fmaf_rn(lo, cs.x, -__fmul_rn(hi, cs.y));
+  out_hi = __fmaf_rn(lo, cs.y, __fmul_rn(hi, cs.x));
+}
 __device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)); }
 // the same with the hardware's reciprocal (1 ulp) in place of the division: for epilogues that are bound by instruction count
 __device__ __forceinline__ float silu_rcp(float g) { return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)); }

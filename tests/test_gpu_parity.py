@@ -357,17 +357,20 @@ def test_exact_ties_go_to_the_lowest_index(ss, name, dtype, batch):
     sh.destroy()
 
 
-@pytest.mark.parametrize("name,dtype,batch,s_in", [("gpt20b_m4", "bf16", 3, 111), ("llama30b_m2", "bf16", 5, 77), ("tiny_gpt", "f32", 2, 150)])
-def test_prefill_blocks_give_the_same_bits(ss, side_stream, name, dtype, batch, s_in):
+@pytest.mark.parametrize("name,dtype,batch,s_in,head_dim", [("gpt20b_m4", "bf16", 3, 111, 64), ("llama30b_m2", "bf16", 5, 77, 64),
+                                                            ("llama30b_m2", "bf16", 4, 130, 128), ("tiny_gpt", "f32", 2, 150, 64)])
+def test_prefill_blocks_give_the_same_bits(ss, side_stream, name, dtype, batch, s_in, head_dim):
     """The initial phase's GEMMs run with blocks of 128 rows x 128 tokens, 128 x 256 or 256 x 256 (chosen by
     output size): all walk k in the same order and sum the row statistics over the same 64-feature bands, so
     logits, first tokens and caches must agree bit for bit — here on token counts and feature counts that are
-    multiples of no block."""
+    multiples of no block.  In the rotary model the q|k|v GEMM rotates and writes the cache rows itself where a wave of
+    its block holds whole heads (256-row blocks; 128-row blocks with 64-dimensional heads), else a kernel behind it
+    does: the same bits again."""
     import torch
     if name == "tiny_gpt":
         w = scaled(name, dtype, layers=2, batch=batch, s_in=s_in, steps=1)
     else:
-        w = scaled(name, dtype, layers=2, batch=batch, s_in=s_in, steps=1, d_model=448, ffn=1152, head_dim=64, n_heads=4, vocab=1511)
+        w = scaled(name, dtype, layers=2, batch=batch, s_in=s_in, steps=1, d_model=448, ffn=1152, head_dim=head_dim, n_heads=4, vocab=1511)
     W = make_weights(w.desc, w.slice, w.seed)
     toks = make_tokens(w.seed, w.batch, w.s_in, w.desc["vocab"])
     outs = []
