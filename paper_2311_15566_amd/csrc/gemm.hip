@@ -15,11 +15,13 @@
 namespace ss {
 
 // ---------------------------------------------------------------------------
-// tiled prefill GEMM: block = 128 output features x 128 or 256 tokens, 4 waves of 64 x 64 or 64 x 128.
-// One k fragment per stage; the stages go from global memory straight into a ring of three LDS
+// tiled prefill GEMM: block = 4 waves; 128 output features x 128 or 256 tokens (waves of 64 x 64 or 64 x 128, two or
+// three blocks per compute unit), or 256 x 256 (waves of 128 x 128, one block per compute unit) for large outputs.
+// One k fragment per stage; the stages go from global memory straight into a ring of three (256-row block: four) LDS
 // buffers (no registers in between): while stage k is multiplied, stage k + 1 has landed or is
-// landing and stage k + 2 is requested.  Per matrix-core instruction a wave reads 3/8 of a
-// fragment from LDS (1/2 with 64 x 64 wave tiles).
+// landing and the stages behind it are requested.  Per matrix-core instruction a wave reads 1/2 (64 x 64), 3/8
+// (64 x 128) or 1/4 (128 x 128) of a fragment from LDS.  All shapes walk k in the same order and add the row
+// statistics up over the same 64-feature bands: same bits.
 // ---------------------------------------------------------------------------
 // s_waitcnt with only the vector-memory counter set (gfx9 encoding: vmcnt = simm16[3:0] and
 // simm16[15:14]; the export and LDS counters stay at their maxima, i.e. are not waited for)
