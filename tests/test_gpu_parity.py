@@ -357,9 +357,12 @@ def test_exact_ties_go_to_the_lowest_index(ss, name, dtype, batch):
     sh.destroy()
 
 
-@pytest.mark.parametrize("name,dtype,batch,s_in,head_dim", [("gpt20b_m4", "bf16", 3, 111, 64), ("llama30b_m2", "bf16", 5, 77, 64),
-                                                            ("llama30b_m2", "bf16", 4, 130, 128), ("tiny_gpt", "f32", 2, 150, 64)])
-def test_prefill_blocks_give_the_same_bits(ss, side_stream, name, dtype, batch, s_in, head_dim):
+@pytest.mark.parametrize("name,dtype,batch,s_in,head_dim,d_model,ffn", [
+    ("gpt20b_m4", "bf16", 3, 111, 64, 448, 1152), ("llama30b_m2", "bf16", 5, 77, 64, 448, 1152), ("llama30b_m2", "bf16", 4, 130, 128, 448, 1152),
+    # reductions of one to four k fragments: shorter than the ring of stages that the 256-row block keeps in flight
+    ("gpt20b_m4", "bf16", 2, 140, 64, 64, 128), ("llama30b_m2", "bf16", 3, 90, 64, 64, 128), ("opt66b_m8", "bf16", 2, 129, 64, 128, 768),
+    ("tiny_gpt", "f32", 2, 150, 64, 0, 0)])
+def test_prefill_blocks_give_the_same_bits(ss, side_stream, name, dtype, batch, s_in, head_dim, d_model, ffn):
     """The initial phase's GEMMs run with blocks of 128 rows x 128 tokens, 128 x 256 or 256 x 256 (chosen by
     output size): all walk k in the same order and sum the row statistics over the same 64-feature bands, so
     logits, first tokens and caches must agree bit for bit — here on token counts and feature counts that are
@@ -370,7 +373,7 @@ def test_prefill_blocks_give_the_same_bits(ss, side_stream, name, dtype, batch, 
     if name == "tiny_gpt":
         w = scaled(name, dtype, layers=2, batch=batch, s_in=s_in, steps=1)
     else:
-        w = scaled(name, dtype, layers=2, batch=batch, s_in=s_in, steps=1, d_model=448, ffn=1152, head_dim=head_dim, n_heads=4, vocab=1511)
+        w = scaled(name, dtype, layers=2, batch=batch, s_in=s_in, steps=1, d_model=d_model, ffn=ffn, head_dim=head_dim, n_heads=4 if name != "opt66b_m8" else 8, vocab=1511)
     W = make_weights(w.desc, w.slice, w.seed)
     toks = make_tokens(w.seed, w.batch, w.s_in, w.desc["vocab"])
     outs = []
