@@ -234,7 +234,9 @@ template <typename AT, int DH>
 __global__ void __launch_bounds__(256) prefill_attn_mfma(PrefillAttnArgs a) {
   constexpr int TK = 32, KC = DH / 32, DT = DH / 16;
   __shared__ __align__(16) u32x4 lds_k[2][2][KC][64];  // [buffer][16-key subtile][32-dim block][lane]
-  __shared__ __align__(16) uint2 lds_v[2][2][DT][64];  // [buffer][16-key subtile][16-dim tile][lane]
+  // [buffer][16-key subtile][16-dim tile][lane (g, r) at g * 16 + (r ^ 8 * (g >> 1))] + 16 entries between the subtiles: the
+  // staging stores of a wave (16 dims x 4 key pieces) then fall on distinct banks, as the reads (one entry per lane) do anyway
+  __shared__ __align__(16) uint2 lds_v[2][2][DT * 64 + 16];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 15, g = lane >> 4;
   const int bh = blockIdx.x, qt = gridDim.y - 1 - blockIdx.y;  // the longest tiles start first
@@ -280,7 +282,7 @@ __global__ void __launch_bounds__(256) prefill_attn_mfma(PrefillAttnArgs a) {
       const int p = tid + 256 * i;
       lds_k[buf][(p >> 6) / KC][(p >> 6) % KC][p & 63] = kreg[i];  // consecutive lanes, consecutive 16 bytes: no bank conflicts
       const int dim = p >> 2, kp = p & 3;
-      uint2 *dst = &lds_v[buf][kp >> 1][dim >> 4][((kp & 1) * 2) * 16 + (dim & 15)];
+      uint2 *dst = &lds_v[buf][kp >> 1][(dim >> 4) * 64 + ((kp & 1) * 2) * 16 + ((dim & 15) ^ ((kp & 1) * 8))];
       dst[0] = make_uint2(vreg[i][0], vreg[i][1]);    // keys 8*(kp&1) .. + 3 of the subtile
       dst[16] = make_uint2(vreg[i][2], vreg[i][3]);   // the next four: lane group + 1
     }
@@ -324,7 +326,7 @@ __global__ void __launch_bounds__(256) prefill_attn_mfma(PrefillAttnArgs a) {
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
         acc[dt] *= alpha;
-        acc[dt] = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4, lds_v[buf][st][dt][lane]), pf, acc[dt], 0, 0, 0);
+        acc[dt] = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4, lds_v[buf][st][dt * 64 + (lane ^ ((lane >> 5) * 8))]), pf, acc[dt], 0, 0, 0);
       }
     }
     if (more) stash(buf ^ 1);  // last read in the previous iteration, before its barrier
