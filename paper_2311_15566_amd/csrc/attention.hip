@@ -226,8 +226,8 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 //   scores^T = K . Q^T   (16x16x32 products over the head dims): lane (g, r) gets the scores of keys
 //                        4g .. 4g+3 against query r, so a query's softmax state lives in lane r of
 //                        each of the four lane groups;
-//   out^T   += V^T . P^T (16x16x16 products over the keys): those four probabilities are exactly the
-//                        lane's piece of the P operand, nothing is exchanged between lanes.
+//   out^T   += V^T . P^T (one 16x16x32 product over the 32 keys of a tile): the lane's four probabilities of each
+//                        of the tile's two subtiles are exactly its piece of the P operand, nothing is exchanged between lanes.
 // Scores are kept in log2 units (the scale carries log2 e).  q and the probabilities enter the
 // products as halves, keys and values at cache precision.
 template <typename AT, int DH>
@@ -294,39 +294,51 @@ __global__ void __launch_bounds__(256) prefill_attn_mfma(PrefillAttnArgs a) {
     const int buf = t & 1;
     const bool more = t + 1 < n_tiles;
     if (more) fetch(t + 1);
-#pragma unroll
-    for (int st = 0; st < 2; ++st) {
-      const int key0 = t * TK + st * 16;
-      if (key0 > q0 + 15 || key0 >= a.S) continue;  // nothing of this subtile is visible to the wave's queries
-      f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    // The tile's two 16-key subtiles take one softmax step together (one exchange of maxima, one rescaling of the sums),
+    // and their probabilities are the two halves of the P operand of one 16x16x32 product per 16 dims: the product's k
+    // index runs over (subtile 0, keys 4g .. 4g+3), (subtile 1, keys 4g .. 4g+3) in lane group g, for P as for V^T.
+    const int key0 = t * TK;
+    if (!(key0 > q0 + 15 || key0 >= a.S)) {  // else nothing of this tile is visible to the wave's queries
+      const bool vis1 = !(key0 + 16 > q0 + 15 || key0 + 16 >= a.S);
+      f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
 #pragma unroll
       for (int c = 0; c < KC; ++c)
-        s = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, lds_k[buf][st][c][lane]), qf[c], s, 0, 0, 0);
+        s0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, lds_k[buf][0][c][lane]), qf[c], s0, 0, 0, 0);
+      if (vis1) {
+        s1 = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < KC; ++c)
+          s1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, lds_k[buf][1][c][lane]), qf[c], s1, 0, 0, 0);
+      }
       float mx = -INFINITY;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const int key = key0 + g * 4 + i;
-        s[i] = (key <= qi && key < a.S) ? s[i] : -INFINITY;
-        mx = fmaxf(mx, s[i]);
+        const int ka = key0 + g * 4 + i, kb = ka + 16;
+        s0[i] = (ka <= qi && ka < a.S) ? s0[i] : -INFINITY;
+        s1[i] = (kb <= qi && kb < a.S) ? s1[i] : -INFINITY;
+        mx = fmaxf(mx, fmaxf(s0[i], s1[i]));
       }
       mx = fmaxf(mx, __shfl_xor(mx, 16));
       mx = fmaxf(mx, __shfl_xor(mx, 32));
       const float mn = fmaxf(m, mx);
       const float alpha = __builtin_amdgcn_exp2f(m - mn);
-      f16x4 pf;
+      f16x8 pf;
       float ps = 0.f;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float p = __builtin_amdgcn_exp2f(s[i] - mn);
-        ps += p;
-        pf[i] = (f16_t)p;
+        const float p0 = __builtin_amdgcn_exp2f(s0[i] - mn), p1 = __builtin_amdgcn_exp2f(s1[i] - mn);
+        ps += p0 + p1;
+        pf[i] = (f16_t)p0, pf[4 + i] = (f16_t)p1;
       }
       l = l * alpha + ps;
       m = mn;
+      const int vl = lane ^ ((lane >> 5) * 8);
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
         acc[dt] *= alpha;
-        acc[dt] = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4, lds_v[buf][st][dt * 64 + (lane ^ ((lane >> 5) * 8))]), pf, acc[dt], 0, 0, 0);
+        const uint2 va = lds_v[buf][0][dt * 64 + vl], vb = lds_v[buf][1][dt * 64 + vl];
+        const u32x4 v8 = {va.x, va.y, vb.x, vb.y};
+        acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, v8), pf, acc[dt], 0, 0, 0);
       }
     }
     if (more) stash(buf ^ 1);  // last read in the previous iteration, before its barrier
