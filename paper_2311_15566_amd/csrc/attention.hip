@@ -311,12 +311,17 @@ __global__ void __launch_bounds__(256) prefill_attn_mfma(PrefillAttnArgs a) {
           s1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, lds_k[buf][1][c][lane]), qf[c], s1, 0, 0, 0);
       }
       float mx = -INFINITY;
+      if (key0 + 31 <= q0 && key0 + 32 <= a.S) {  // every key of the tile is visible to every query of the wave (wave-uniform)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int ka = key0 + g * 4 + i, kb = ka + 16;
-        s0[i] = (ka <= qi && ka < a.S) ? s0[i] : -INFINITY;
-        s1[i] = (kb <= qi && kb < a.S) ? s1[i] : -INFINITY;
-        mx = fmaxf(mx, fmaxf(s0[i], s1[i]));
+        for (int i = 0; i < 4; ++i) mx = fmaxf(mx, fmaxf(s0[i], s1[i]));
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int ka = key0 + g * 4 + i, kb = ka + 16;
+          s0[i] = (ka <= qi && ka < a.S) ? s0[i] : -INFINITY;
+          s1[i] = (kb <= qi && kb < a.S) ? s1[i] : -INFINITY;
+          mx = fmaxf(mx, fmaxf(s0[i], s1[i]));
+        }
       }
       mx = fmaxf(mx, __shfl_xor(mx, 16));
       mx = fmaxf(mx, __shfl_xor(mx, 32));
