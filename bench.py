@@ -246,6 +246,17 @@ def run_workload(ss, torch, name, K, Wm, eager=False, extras=True, repack5=False
             peak = MFMA_PEAK_TFLOPS[w.desc["dtype"]]       # halves and bf16 share one matrix-core peak
             out["prefill"] = dict(ms=prefill_ms, tokens=w.batch * w.s_in, TFLOPs=fl / (prefill_ms * 1e-3) / 1e12,
                                   peak=peak, frac=fl / (prefill_ms * 1e-3) / 1e12 / peak)
+            if w.desc["dtype"] == "bf16":
+                # what the matrix cores of this chip sustain on random halves with the GEMM's LDS reads and loads beside them
+                # and nothing else (no barrier, no epilogue): the clock under matrix-core load is set by power and power by
+                # the data, so this, not `peak`, is what real operands can reach (see --calibrate-mfma)
+                g = torch.Generator(device="cuda").manual_seed(1)
+                rnd = (torch.randn(4 << 20, generator=g, device="cuda") * 0.5).to(torch.float16)
+                ss.matrix_core_probe(rnd, True, True, 2000)
+                t, c, ghz = ss.matrix_core_probe(rnd, True, True, 40000)
+                out["prefill"]["sustainable_on_random_operands"] = dict(TFLOPs=t, GHz=ghz, cycles_per_64_products=c,
+                                                                         frac=out["prefill"]["TFLOPs"] / t)
+                del rnd
 
             # ---- measured cost model (Section 5; Eq. 1): iteration time over context length, from the timed steps ----
             if K // chunk >= 4:
@@ -345,6 +356,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the kernel-class, prefill, cost-model, repack and re-slice legs")
     ap.add_argument("--eager", action="store_true", help="launch kernel by kernel instead of replaying a graph")
+    ap.add_argument("--calibrate-mfma", action="store_true",
+                    help="only measure what the matrix cores sustain on constant and on random operands (--steps thousand iterations each)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only copy 1 GiB device to device three times (a kernel of known traffic, for scaling "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -366,6 +379,23 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps(dict(copy_bytes=1 << 30, copies=3)), flush=True)
+        return
+    if args.calibrate_mfma:
+        # what the matrix cores sustain with nothing in their way, on constant operands and on random halves (the clock
+        # under matrix-core load is set by power, and power by the data), alone and with the LDS reads and direct-to-LDS
+        # loads of the initial phase's 256-row GEMM block: the ceiling that the `prefill` figure is to be read against
+        g = torch.Generator(device="cuda").manual_seed(1)
+        rnd = (torch.randn(4 << 20, generator=g, device="cuda") * 0.5).to(torch.float16)
+        const = torch.full((4 << 20,), 0.75, dtype=torch.float16, device="cuda")
+        rows = []
+        for name, data in (("constant", const), ("random", rnd)):
+            for lds_reads, loads in ((False, False), (True, False), (False, True), (True, True)):
+                ss.matrix_core_probe(data, lds_reads, loads, 2000)
+                t, c, ghz = ss.matrix_core_probe(data, lds_reads, loads, args.steps * 1000)
+                rows.append(dict(operands=name, lds_reads=lds_reads, loads=loads, TFLOPs=t, cycles_per_64_products=c, GHz=ghz))
+                log(f"[bench] matrix cores, {name} operands, LDS reads {lds_reads}, loads {loads}: {t:.0f} TFLOP/s, "
+                    f"{c:.0f} cycles per 64 products, {ghz:.2f} GHz")
+        print(json.dumps(dict(matrix_core_probe=rows, peak_TFLOPs=MFMA_PEAK_TFLOPS["bf16"])), flush=True)
         return
     K, Wm = args.steps, args.warmup
     extras = not args.no_extras

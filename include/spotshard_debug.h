@@ -36,6 +36,17 @@ ss_status ss_debug_force_gemm_shape(int32_t tiles_per_block, int32_t k_slices);
  * does not cover whole 256-row blocks keeps 128 rows).  All give the same bits.  SS_EINVAL for any other pair. */
 ss_status ss_debug_force_prefill_block(int32_t rows_per_block, int32_t tokens_per_block);
 
+/* Measurement aid for the roofline of the initial phase's GEMM (the first term of Eq. (1); matrix-core bound): what the
+ * matrix cores sustain on the caller's operand data.  One block of four waves per compute unit runs `iters` times 64
+ * half-precision 16x16x32 products per wave on fragments taken from operands_dev (device memory, operand_bytes of it, 1 MiB to
+ * 4 GiB, read only; any bit pattern), optionally with the LDS reads (16 KiB per 64 products and wave) and the direct-to-LDS
+ * loads (8 KiB, from operands_dev) that the GEMM's 256-row block issues per stage.  Returns the rate in TFLOP/s, the
+ * cycles per 64 products and the clock (cycle counter over event time).  The clock under matrix-core load depends on
+ * the operand data: compare constant with random operands.  Allocates and frees a few KiB of device memory and
+ * synchronizes on its own events; SS_EINVAL for bad arguments, SS_EHIP if the runtime fails. */
+ss_status ss_debug_matrix_core_probe(const void *operands_dev, uint64_t operand_bytes, int32_t lds_reads, int32_t loads,
+                                     int32_t iters, double *tflops, double *cycles_per_64, double *ghz, void *hip_stream);
+
 /* Measurement aid: per-kernel-class timing of decode steps.  While enabled on group[0],
  * ss_decode_step launches kernel by kernel (no graph replay) and every launch records its own
  * begin and end on a pair of HIP events of the step's stream (the dispatch's timestamps).

@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     kv_import,
     kv_repack,
     lib,
+    matrix_core_probe,
     prefill,
     stage_decode_step,
     stage_prefill,

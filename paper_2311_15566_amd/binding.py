@@ -87,6 +87,7 @@ def _load():
     L.ss_shard_model_context_bytes.restype = C.c_size_t
     L.ss_debug_force_gemm_shape.argtypes = [i32, i32]
     L.ss_debug_force_prefill_block.argtypes = [i32, i32]
+    L.ss_debug_matrix_core_probe.argtypes = [vp, C.c_uint64, i32, i32, i32, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
     L.ss_kernel_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), vp]
     return L
 
@@ -296,6 +297,15 @@ def force_prefill_block(rows_per_block: int = 0, tokens_per_block: int = 0):
     """Test aid: force the block of the initial phase's GEMMs, rows x tokens: 128 x 128, 128 x 256 or 256 x 256
     (0 x 0 = library's choice)."""
     _check(lib.ss_debug_force_prefill_block(int(rows_per_block), int(tokens_per_block)))
+
+
+def matrix_core_probe(operands, lds_reads: bool, loads: bool, iters: int, stream=None):
+    """Measurement aid: (TFLOP/s, cycles per 64 products, GHz) of the matrix cores on `operands` (a device tensor of 1 MiB or
+    more), optionally with the LDS reads and direct-to-LDS loads of the initial phase's GEMM."""
+    t, c, g = C.c_double(), C.c_double(), C.c_double()
+    _check(lib.ss_debug_matrix_core_probe(operands.data_ptr(), operands.numel() * operands.element_size(), int(lds_reads), int(loads),
+                                          int(iters), C.byref(t), C.byref(c), C.byref(g), _stream(stream)))
+    return t.value, c.value, g.value
 
 
 def device_kv_bytes(shard) -> int:

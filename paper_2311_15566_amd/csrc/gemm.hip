@@ -11,6 +11,7 @@
 #include <mutex>
 #include <type_traits>
 #include <utility>
+#include <vector>
 
 namespace ss {
 
@@ -678,6 +679,109 @@ ss_status launch_tile_gemm(int dtype, int epi, TileGemmArgs a, hipStream_t st) {
 }
 
 }  // namespace ss
+
+// ---------------------------------------------------------------------------
+// Measurement aid: what the matrix cores sustain on given operand data, with and without the data movement of the
+// 256-row block (one wave per SIMD, one block per compute unit, nothing else): per 64 products of 16x16x32 on halves,
+// 16 LDS reads of 1 KiB back into the operand registers and 8 direct-to-LDS loads of 1 KiB.  No barrier, no epilogue.
+// ---------------------------------------------------------------------------
+namespace ss {
+constexpr int kProbeLds = 136 * 1024;
+template <bool LDSR, bool DMA>
+__global__ void __launch_bounds__(256, 1) matrix_core_probe(const u32x4 *src, uint32_t src_pieces, float *out, int iters,
+                                                            unsigned long long *cyc) {
+  extern __shared__ __align__(16) u32x4 lds[];  // pieces 0 .. 4095: operands (read by LDSR), 4096 .. 6143: where the loads land
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  for (int i = threadIdx.x; i < 4096; i += 256) lds[i] = src[(i + blockIdx.x * 977u) % src_pieces];
+  __syncthreads();
+  const uint32_t base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)lds + wave * 16384 + lane * 16;
+  const u32x4 *p = src + ((size_t)blockIdx.x * 4 + wave) * 512 % (src_pieces - 1024) + lane;  // 8 fragments of 64 pieces from here
+  f32x4 acc[64];
+  u32x4 a[8], b[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a[i] = lds[wave * 1024 + i * 64 + lane], b[i] = lds[wave * 1024 + (8 + i) * 64 + lane];
+#pragma unroll
+  for (int i = 0; i < 64; ++i) mma_f16_pinned<true>(acc[i], a[i % 8], b[i / 8]);
+  const unsigned long long t0 = __builtin_readcyclecounter();
+  for (int it = 0; it < iters; ++it) {
+    static_for<64>([&](auto I) {
+      constexpr int i = decltype(I)::value;
+      mma_f16_pinned<false>(acc[i], a[i % 8], b[i / 8]);
+      if constexpr (LDSR && i % 4 == 1) {  // the same values again: the registers stay what they were
+        constexpr int n = i / 4;
+        if constexpr (n < 8) lds_read_async<n * 1024>(a[n], base);
+        else lds_read_async<n * 1024>(b[n - 8], base);
+      }
+      if constexpr (DMA && i % 8 == 3)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(p + (i / 8) * 64),
+                                         (__attribute__((address_space(3))) void *)(lds + 4096 + (wave * 8 + i / 8) * 64), 16, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    wait_lds<0>();
+    if (DMA) wait_vmcnt<8>();
+  }
+  drain_mma();
+  wait_vmcnt<0>();
+  const unsigned long long t1 = __builtin_readcyclecounter();
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 64; ++i) sum += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
+  out[blockIdx.x * 256 + threadIdx.x] = sum;
+  if (threadIdx.x == 0) cyc[blockIdx.x] = t1 - t0;
+}
+}  // namespace ss
+
+extern "C" ss_status ss_debug_matrix_core_probe(const void *operands_dev, uint64_t operand_bytes, int32_t lds_reads, int32_t loads,
+                                                int32_t iters, double *tflops, double *cycles_per_64, double *ghz, void *hip_stream) {
+  using namespace ss;
+  if (!operands_dev || operand_bytes < (1u << 20) || operand_bytes > (1ull << 32) || iters < 1 || !tflops || !cycles_per_64 || !ghz)
+    SS_FAIL(SS_EINVAL, "matrix-core probe: operands of 1 MiB to 4 GiB, at least one iteration, three outputs");
+  hipStream_t st = (hipStream_t)hip_stream;
+  int dev = 0, cus = 0;
+  SS_HIP(hipGetDevice(&dev));
+  SS_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  const void *fn = lds_reads ? (loads ? (const void *)matrix_core_probe<true, true> : (const void *)matrix_core_probe<true, false>)
+                             : (loads ? (const void *)matrix_core_probe<false, true> : (const void *)matrix_core_probe<false, false>);
+  SS_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kProbeLds));
+  float *out = nullptr;
+  unsigned long long *cyc = nullptr;
+  SS_HIP(hipMalloc(&out, (size_t)cus * 256 * sizeof(float)));
+  if (hipMalloc(&cyc, (size_t)cus * sizeof(unsigned long long)) != hipSuccess) {
+    (void)hipFree(out);
+    SS_FAIL(SS_EHIP, "matrix-core probe: out of device memory");
+  }
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  hipError_t e = hipEventCreate(&e0);
+  if (e == hipSuccess) e = hipEventCreate(&e1);
+  float ms = 0.f;
+  std::vector<unsigned long long> h(cus);
+  if (e == hipSuccess) e = hipEventRecord(e0, st);
+  if (e == hipSuccess) {
+    const u32x4 *src = (const u32x4 *)operands_dev;
+    const uint32_t pieces = (uint32_t)(operand_bytes / 16);
+    if (lds_reads && loads) hipLaunchKernelGGL((matrix_core_probe<true, true>), dim3(cus), dim3(256), kProbeLds, st, src, pieces, out, iters, cyc);
+    else if (lds_reads) hipLaunchKernelGGL((matrix_core_probe<true, false>), dim3(cus), dim3(256), kProbeLds, st, src, pieces, out, iters, cyc);
+    else if (loads) hipLaunchKernelGGL((matrix_core_probe<false, true>), dim3(cus), dim3(256), kProbeLds, st, src, pieces, out, iters, cyc);
+    else hipLaunchKernelGGL((matrix_core_probe<false, false>), dim3(cus), dim3(256), kProbeLds, st, src, pieces, out, iters, cyc);
+    e = hipGetLastError();
+  }
+  if (e == hipSuccess) e = hipEventRecord(e1, st);
+  if (e == hipSuccess) e = hipEventSynchronize(e1);
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+  if (e == hipSuccess) e = hipMemcpy(h.data(), cyc, (size_t)cus * sizeof(unsigned long long), hipMemcpyDeviceToHost);
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  (void)hipFree(out);
+  (void)hipFree(cyc);
+  if (e != hipSuccess) SS_FAIL(SS_EHIP, "matrix-core probe: %s", hipGetErrorString(e));
+  double c = 0.0;
+  for (int i = 0; i < cus; ++i) c += (double)h[i];
+  c /= cus;
+  *tflops = 4.0 * iters * 64 * 16384.0 * cus / (ms * 1e-3) / 1e12;  // four waves a block, 64 products of 16 x 16 x 32 an iteration
+  *cycles_per_64 = c / iters;
+  *ghz = c / (ms * 1e-3) / 1e9;
+  return SS_OK;
+}
 
 extern "C" ss_status ss_debug_force_prefill_block(int32_t rows_per_block, int32_t tokens_per_block) {
   using namespace ss;

@@ -994,3 +994,18 @@ def test_argument_errors(ss):
         ss.kv_repack(sh, sh, [0])
     assert e.value.status == 1
     sh.destroy()
+
+
+def test_matrix_core_probe_reports_a_plausible_rate(ss):
+    """The measurement aid behind the initial phase's roofline: 64 products of 16x16x32 take a little over 64 x 16 cycles
+    per wave whatever the data and whatever moves beside them; rate and clock are consistent with that."""
+    import torch
+    data = (torch.randn(1 << 20, device="cuda") * 0.5).to(torch.float16)
+    for lds_reads, loads in ((False, False), (True, True)):
+        tflops, cycles, ghz = ss.matrix_core_probe(data, lds_reads, loads, 3000)
+        assert 1000 <= cycles <= 1400, cycles
+        assert 0.5 <= ghz <= 2.6, ghz
+        cus = torch.cuda.get_device_properties(0).multi_processor_count
+        assert abs(tflops - 4 * 64 * 16384 * cus * ghz * 1e9 / cycles / 1e12) < 0.02 * tflops
+    with pytest.raises(Exception):
+        ss.matrix_core_probe(data[:1000], False, False, 10)
