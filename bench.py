@@ -250,8 +250,8 @@ def run_workload(ss, torch, name, K, Wm, eager=False, extras=True, repack5=False
                 # what the matrix cores of this chip sustain on random halves with the GEMM's LDS reads and loads beside them
                 # and nothing else (no barrier, no epilogue): the clock under matrix-core load is set by power and power by
                 # the data, so this, not `peak`, is what real operands can reach (see --calibrate-mfma)
-                g = torch.Generator(device="cuda").manual_seed(1)
-                rnd = (torch.randn(4 << 20, generator=g, device="cuda") * 0.5).to(torch.float16)
+                gen = torch.Generator(device="cuda").manual_seed(1)
+                rnd = (torch.randn(4 << 20, generator=gen, device="cuda") * 0.5).to(torch.float16)
                 ss.matrix_core_probe(rnd, True, True, 2000)
                 t, c, ghz = ss.matrix_core_probe(rnd, True, True, 40000)
                 out["prefill"]["sustainable_on_random_operands"] = dict(TFLOPs=t, GHz=ghz, cycles_per_64_products=c,
