@@ -612,15 +612,17 @@ static ss_status launch_one(const TileGemmArgs &a, dim3 grid, hipStream_t st) {
 // Token block: measured on every GEMM shape of the GPT-20B, LLaMA-30B and OPT-66B shards, 256-token
 // blocks win by 3-9 % where the output has a few rounds of them (16384 tokens: fewer LDS and L2
 // reads per flop), 128-token blocks by 7-17 % on the 4096-token shapes (more blocks to spread over
-// the compute units) and by 8 % on a short reduction (1152), where a block is mostly epilogue.
+// the compute units).  A short reduction (OPT-66B shard's out-projection, 1152 = 36 k fragments), where a block is mostly
+// epilogue, took the small block by 8 % until the epilogues issued their loads up front; now 630 us (128 x 128),
+// 600 (128 x 256), 585 (256 x 256).
 // Row block: 256 rows x 256 tokens (one wave per SIMD) where the output has a few rounds of such blocks too: 12-17 % faster
 // than 128 x 256 on the LLaMA-30B shard's matrices, 10 % on the OPT-66B shard's.
 static void choose_block(int dtype, TileGemmArgs &a) {
   if (g_forced_tok_tiles.load()) a.tok_tiles = g_forced_tok_tiles.load(), a.wave_row_tiles = g_forced_row_tiles.load();
   if (a.tok_tiles != 4 && a.tok_tiles != 8) {
     const long blocks128 = (long)ceil_div(a.row_tiles, 8) * (a.T / 128);
-    a.tok_tiles = (blocks128 >= 2048 && a.k_blocks >= 64) ? 8 : 4;
-    a.wave_row_tiles = (blocks128 >= 4 * kBigBlockRounds * 256 && a.k_blocks >= 64) ? 8 : 4;
+    a.tok_tiles = (blocks128 >= 2048 && a.k_blocks >= 32) ? 8 : 4;
+    a.wave_row_tiles = (blocks128 >= 4 * kBigBlockRounds * 256 && a.k_blocks >= 32) ? 8 : 4;
   }
   if (a.wave_row_tiles != 8 || a.tok_tiles != 8 || dtype != SS_DTYPE_BF16 || (a.act_lo && (a.lo_row_begin % 16 || a.lo_row_end % 16)))
     a.wave_row_tiles = 4;
